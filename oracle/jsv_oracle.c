@@ -1,0 +1,625 @@
+/*
+ * CPU oracle for the one-tuple-per-task allocation search.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  Nothing in the product path may call it,
+ * link it or fall back to it; it shares no code, header, table or constant
+ * with the HIP sources.
+ *
+ * What it computes, following the paper's MILP (Section 3.2) restricted to one
+ * (variant, partition, batch) tuple per task, replicated as often as needed:
+ *
+ *   - demand at a task:   R(t) = R * m_t                       (Eq. 5, fixed factors)
+ *   - replicas:           smallest M >= 1 with M*H >= R(t)     (Eq. 6)
+ *   - task cost:          M * s_n of the chosen partition      (Eq. 7)
+ *   - total cost:         sum over tasks, <= S_avail           (Eq. 8)
+ *   - latency:            q * max over source-to-sink paths of the summed
+ *                         per-task latencies, <= SLO_l         (Eq. 2, 3; q = 2)
+ *   - path accuracy:      product of the task accuracies       (Eq. 11)
+ *   - system accuracy:    sum_p f_p*A_p / A_max, >= SLO_a      (Eq. 12, 13)
+ *   - result:             among candidates meeting all three constraints the
+ *                         cheapest one; equal costs -> lowest candidate index.
+ *
+ * Paths are enumerated explicitly by depth-first search and every candidate is
+ * scored from the tables on its own: no dynamic programming over the graph, no
+ * sharing between candidates, no blocking.  Integers are exact (64-bit);
+ * accuracy is fp64, multiplied along a path from source to sink and summed
+ * over paths in depth-first order.
+ *
+ * Pins (tests/test_oracle_*.py): a hand-worked two-task chain, an independent
+ * brute force on tiny inputs, closed forms (one task; separable minimum;
+ * multiple-choice knapsack on chains), monotonicity invariants.  The cap-
+ * thinning step of the prune is a heuristic of this build with no outside
+ * definition: it is checked against a second, differently written
+ * implementation and against its stated properties only.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_MAX_TASKS 16
+#define ORC_MAX_PATHS (1 << 20)
+
+enum { ORC_OK = 0, ORC_E_ARG = -1, ORC_E_CYCLE = -2, ORC_E_RANGE = -3, ORC_E_MEM = -4 };
+
+typedef struct {
+    uint64_t index;       /* in the searched space, task 0 = fastest digit */
+    uint64_t full_index;  /* sum_t c_t * C^t, UINT64_MAX if that overflows */
+    uint64_t evaluated;   /* size of the searched space */
+    double accuracy;      /* A_obj of the winner */
+    uint32_t latency_us;  /* q * critical path of the winner */
+    int32_t cost;         /* INT32_MAX when infeasible */
+    uint32_t feasible;
+    uint32_t flags;       /* bit0: cap thinning dropped a choice at this level */
+    uint16_t choice[ORC_MAX_TASKS];
+    uint32_t replicas[ORC_MAX_TASKS];
+} orc_result;
+
+typedef struct {
+    uint32_t T, V, P, B, C, E;
+    uint32_t *units, *batch, *lat, *thr, *mult;
+    double *acc;
+    uint16_t *src, *dst;
+    uint32_t capacity, q;
+    /* graph */
+    int npred[ORC_MAX_TASKS], pred[ORC_MAX_TASKS][ORC_MAX_TASKS];
+    int nsucc[ORC_MAX_TASKS], succ[ORC_MAX_TASKS][ORC_MAX_TASKS];
+    /* explicit paths */
+    int npaths;
+    int *plen;      /* [npaths] */
+    int *pnode;     /* [npaths][T] */
+    double *pf;     /* [npaths] fraction of requests on the path */
+    double amax;
+} orc_model;
+
+/* ---- choice id <-> (variant, partition, batch) ---------------------------- */
+static inline uint32_t variant_of(const orc_model *m, uint32_t c) { return c / (m->P * m->B); }
+static inline uint32_t part_of(const orc_model *m, uint32_t c) { return (c / m->B) % m->P; }
+
+/* ---- path enumeration ------------------------------------------------------ */
+typedef struct { orc_model *m; int stack[ORC_MAX_TASKS]; int depth; int err; int cap; } dfs_t;
+
+static void dfs(dfs_t *d, int node)
+{
+    orc_model *m = d->m;
+    if (d->err) return;
+    d->stack[d->depth++] = node;
+    if (m->nsucc[node] == 0) {
+        if (m->npaths == d->cap) { d->err = ORC_E_RANGE; d->depth--; return; }
+        int k = m->npaths++;
+        m->plen[k] = d->depth;
+        for (int i = 0; i < d->depth; i++) m->pnode[(size_t)k * m->T + i] = d->stack[i];
+    } else {
+        for (int i = 0; i < m->nsucc[node]; i++) dfs(d, m->succ[node][i]);
+    }
+    d->depth--;
+}
+
+/* 0 if acyclic: repeatedly strip nodes without remaining predecessors */
+static int has_cycle(const orc_model *m)
+{
+    int indeg[ORC_MAX_TASKS], gone[ORC_MAX_TASKS] = {0}, left = (int)m->T;
+    for (uint32_t t = 0; t < m->T; t++) indeg[t] = m->npred[t];
+    for (;;) {
+        int found = -1;
+        for (uint32_t t = 0; t < m->T; t++) if (!gone[t] && indeg[t] == 0) { found = (int)t; break; }
+        if (found < 0) break;
+        gone[found] = 1; left--;
+        for (int i = 0; i < m->nsucc[found]; i++) indeg[m->succ[found][i]]--;
+    }
+    return left != 0;
+}
+
+/* system accuracy of one choice of variants, before normalisation (Eq. 11, 12) */
+static double raw_accuracy(const orc_model *m, const uint32_t *variant)
+{
+    double total = 0.0;
+    for (int k = 0; k < m->npaths; k++) {
+        double ap = 1.0;
+        for (int i = 0; i < m->plen[k]; i++) {
+            int t = m->pnode[(size_t)k * m->T + i];
+            ap *= m->acc[(size_t)t * m->V + variant[t]];
+        }
+        total += m->pf[k] * ap;
+    }
+    return total;
+}
+
+void orc_destroy(orc_model *m)
+{
+    if (!m) return;
+    free(m->units); free(m->batch); free(m->lat); free(m->thr); free(m->mult);
+    free(m->acc); free(m->src); free(m->dst); free(m->plen); free(m->pnode); free(m->pf);
+    free(m);
+}
+
+static void *dup_mem(const void *p, size_t n)
+{
+    void *q = malloc(n ? n : 1);
+    if (q && n) memcpy(q, p, n);
+    return q;
+}
+
+/*
+ * Build a model.  thr_mrps may be NULL: throughput is then batch/latency,
+ * floored to whole milli-requests per second.
+ */
+int orc_create(orc_model **out, uint32_t T, uint32_t V, uint32_t P, uint32_t B,
+               const uint32_t *units, const uint32_t *batch, const uint32_t *latency_us,
+               const uint32_t *thr_mrps, const double *accuracy,
+               uint32_t E, const uint16_t *src, const uint16_t *dst,
+               const uint32_t *mult_milli, uint32_t capacity_units, uint32_t queue_factor)
+{
+    if (!out || !units || !batch || !latency_us || !accuracy || !mult_milli) return ORC_E_ARG;
+    if (E && (!src || !dst)) return ORC_E_ARG;
+    if (T == 0 || T > ORC_MAX_TASKS || V == 0 || P == 0 || B == 0 || queue_factor == 0) return ORC_E_ARG;
+    if ((uint64_t)V * P * B > 65535u) return ORC_E_ARG;
+    orc_model *m = (orc_model *)calloc(1, sizeof *m);
+    if (!m) return ORC_E_MEM;
+    m->T = T; m->V = V; m->P = P; m->B = B; m->C = V * P * B; m->E = E;
+    m->capacity = capacity_units; m->q = queue_factor;
+    size_t n = (size_t)T * m->C;
+    m->units = dup_mem(units, P * sizeof *units);
+    m->batch = dup_mem(batch, B * sizeof *batch);
+    m->lat = dup_mem(latency_us, n * sizeof *latency_us);
+    m->mult = dup_mem(mult_milli, T * sizeof *mult_milli);
+    m->acc = dup_mem(accuracy, (size_t)T * V * sizeof *accuracy);
+    m->src = dup_mem(src, E * sizeof *src);
+    m->dst = dup_mem(dst, E * sizeof *dst);
+    m->thr = (uint32_t *)malloc(n * sizeof(uint32_t));
+    if (!m->units || !m->batch || !m->lat || !m->mult || !m->acc || !m->src || !m->dst || !m->thr) {
+        orc_destroy(m); return ORC_E_MEM;
+    }
+    for (size_t i = 0; i < n; i++) {
+        if (m->lat[i] == 0) { orc_destroy(m); return ORC_E_ARG; }
+        if (thr_mrps) m->thr[i] = thr_mrps[i];
+        else {
+            uint64_t h = (uint64_t)m->batch[i % B] * 1000000000ull / m->lat[i];
+            if (h > 0xFFFFFFFFull) { orc_destroy(m); return ORC_E_RANGE; }
+            m->thr[i] = (uint32_t)h;
+        }
+        if (m->thr[i] == 0) { orc_destroy(m); return ORC_E_ARG; }
+    }
+    for (size_t i = 0; i < (size_t)T * V; i++)
+        if (!(m->acc[i] > 0.0 && m->acc[i] <= 1.0)) { orc_destroy(m); return ORC_E_ARG; }
+    for (uint32_t t = 0; t < T; t++) if (m->mult[t] == 0) { orc_destroy(m); return ORC_E_ARG; }
+    for (uint32_t e = 0; e < E; e++) {
+        uint32_t a = src[e], b = dst[e];
+        if (a >= T || b >= T || a == b) { orc_destroy(m); return ORC_E_ARG; }
+        for (int i = 0; i < m->nsucc[a]; i++)
+            if (m->succ[a][i] == (int)b) { orc_destroy(m); return ORC_E_ARG; }
+        m->succ[a][m->nsucc[a]++] = (int)b;
+        m->pred[b][m->npred[b]++] = (int)a;
+    }
+    if (has_cycle(m)) { orc_destroy(m); return ORC_E_CYCLE; }
+
+    /* all source-to-sink paths; an isolated task is a path of length one */
+    m->plen = (int *)malloc(sizeof(int) * ORC_MAX_PATHS);
+    m->pnode = (int *)malloc(sizeof(int) * (size_t)ORC_MAX_PATHS * T);
+    if (!m->plen || !m->pnode) { orc_destroy(m); return ORC_E_MEM; }
+    dfs_t d; memset(&d, 0, sizeof d); d.m = m; d.cap = ORC_MAX_PATHS;
+    for (uint32_t t = 0; t < T; t++) if (m->npred[t] == 0) dfs(&d, (int)t);
+    if (d.err) { orc_destroy(m); return d.err; }
+    m->plen = (int *)realloc(m->plen, sizeof(int) * (size_t)m->npaths);
+    m->pnode = (int *)realloc(m->pnode, sizeof(int) * (size_t)m->npaths * T);
+    m->pf = (double *)malloc(sizeof(double) * (size_t)m->npaths);
+    if (!m->plen || !m->pnode || !m->pf) { orc_destroy(m); return ORC_E_MEM; }
+
+    /*
+     * Fraction of requests on a path (the f_p of Eq. 12), derived from the
+     * per-task multipliers: the share of a sink among all sinks, times, for
+     * every edge of the path, the share of the edge's tail among all
+     * predecessors of its head.
+     */
+    uint64_t sink_total = 0;
+    for (uint32_t t = 0; t < T; t++) if (m->nsucc[t] == 0) sink_total += m->mult[t];
+    for (int k = 0; k < m->npaths; k++) {
+        const int *nodes = m->pnode + (size_t)k * T;
+        int last = nodes[m->plen[k] - 1];
+        double f = (double)m->mult[last] / (double)sink_total;
+        for (int i = 1; i < m->plen[k]; i++) {
+            int head = nodes[i], tail = nodes[i - 1];
+            uint64_t in_total = 0;
+            for (int j = 0; j < m->npred[head]; j++) in_total += m->mult[m->pred[head][j]];
+            f *= (double)m->mult[tail] / (double)in_total;
+        }
+        m->pf[k] = f;
+    }
+    /* A_max: every task on its most accurate variant */
+    uint32_t best[ORC_MAX_TASKS];
+    for (uint32_t t = 0; t < T; t++) {
+        uint32_t bv = 0;
+        for (uint32_t v = 1; v < V; v++)
+            if (m->acc[(size_t)t * V + v] > m->acc[(size_t)t * V + bv]) bv = v;
+        best[t] = bv;
+    }
+    m->amax = raw_accuracy(m, best);
+    *out = m;
+    return ORC_OK;
+}
+
+int orc_num_paths(const orc_model *m) { return m->npaths; }
+double orc_amax(const orc_model *m) { return m->amax; }
+
+/* path k: writes its nodes, returns its length; *f = request fraction */
+int orc_get_path(const orc_model *m, int k, int *nodes, double *f)
+{
+    if (k < 0 || k >= m->npaths) return ORC_E_ARG;
+    for (int i = 0; i < m->plen[k]; i++) nodes[i] = m->pnode[(size_t)k * m->T + i];
+    *f = m->pf[k];
+    return m->plen[k];
+}
+
+/* ---- replicas and cost of every (task, choice) at one demand (Eq. 5-7) ---- */
+int orc_cost_table(const orc_model *m, uint32_t demand_mrps, uint32_t *rep, int32_t *cost)
+{
+    for (uint32_t t = 0; t < m->T; t++) {
+        uint64_t need = (uint64_t)demand_mrps * m->mult[t];          /* micro-requests/s */
+        for (uint32_t c = 0; c < m->C; c++) {
+            uint64_t per = 1000ull * m->thr[(size_t)t * m->C + c];   /* one replica, same unit */
+            uint64_t r = (need + per - 1) / per;
+            if (r < 1) r = 1;
+            uint64_t k = r * m->units[part_of(m, c)];
+            if (r > 0xFFFFFFFFull || k > 0x7FFFFFFFull) return ORC_E_RANGE;
+            rep[(size_t)t * m->C + c] = (uint32_t)r;
+            cost[(size_t)t * m->C + c] = (int32_t)k;
+        }
+    }
+    return ORC_OK;
+}
+
+/* ---- per-task prune --------------------------------------------------------- */
+typedef struct { uint32_t lat; uint32_t c; } lat_c;
+static int cmp_lat_c(const void *a, const void *b)
+{
+    const lat_c *x = (const lat_c *)a, *y = (const lat_c *)b;
+    if (x->lat != y->lat) return x->lat < y->lat ? -1 : 1;
+    return x->c < y->c ? -1 : (x->c > y->c);
+}
+
+/*
+ * Surviving choices of one task, ascending choice id.
+ * cap == 0: everything.  Otherwise: (a) drop what cannot meet the latency SLO
+ * even when every other task runs its fastest choice; (b) drop what another
+ * choice matches or beats on latency, accuracy and cost; (c) if more than cap
+ * remain, thin each variant to floor(cap/V) choices evenly spaced by latency
+ * rank, fastest and slowest always kept.
+ */
+static int prune_task(const orc_model *m, const int32_t *cost, uint32_t slo_latency_us,
+                      uint32_t cap, uint32_t t, uint16_t *ids, uint32_t *K, uint32_t *truncated)
+{
+    const uint32_t C = m->C;
+    *truncated = 0;
+    if (cap == 0) {
+        for (uint32_t c = 0; c < C; c++) ids[c] = (uint16_t)c;
+        *K = C;
+        return ORC_OK;
+    }
+    if (cap < 2 * m->V) return ORC_E_ARG;
+    uint8_t *alive = (uint8_t *)calloc(C, 1);
+    uint8_t *keep = (uint8_t *)calloc(C, 1);
+    lat_c *order = (lat_c *)malloc(sizeof(lat_c) * C);
+    if (!alive || !keep || !order) { free(alive); free(keep); free(order); return ORC_E_MEM; }
+
+    /* (a) longest path through t with every other task at its fastest choice */
+    uint64_t lo[ORC_MAX_TASKS];
+    for (uint32_t u = 0; u < m->T; u++) {
+        uint32_t best = m->lat[(size_t)u * C];
+        for (uint32_t c = 1; c < C; c++) if (m->lat[(size_t)u * C + c] < best) best = m->lat[(size_t)u * C + c];
+        lo[u] = best;
+    }
+    uint64_t through = 0;
+    for (int k = 0; k < m->npaths; k++) {
+        int on = 0; uint64_t s = 0;
+        for (int i = 0; i < m->plen[k]; i++) {
+            uint32_t u = (uint32_t)m->pnode[(size_t)k * m->T + i];
+            if (u == t) on = 1; else s += lo[u];
+        }
+        if (on && s > through) through = s;
+    }
+    for (uint32_t c = 0; c < C; c++)
+        alive[c] = (uint64_t)m->q * ((uint64_t)m->lat[(size_t)t * C + c] + through) <= slo_latency_us;
+
+    /* (b) exact dominance on (latency down, accuracy up, cost down) */
+    for (uint32_t c = 0; c < C; c++) {
+        if (!alive[c]) continue;
+        uint32_t l = m->lat[(size_t)t * C + c];
+        double a = m->acc[(size_t)t * m->V + variant_of(m, c)];
+        int32_t k = cost[(size_t)t * C + c];
+        keep[c] = 1;
+        for (uint32_t o = 0; o < C && keep[c]; o++) {
+            if (o == c || !alive[o]) continue;
+            uint32_t l2 = m->lat[(size_t)t * C + o];
+            double a2 = m->acc[(size_t)t * m->V + variant_of(m, o)];
+            int32_t k2 = cost[(size_t)t * C + o];
+            if (l2 <= l && a2 >= a && k2 <= k) {
+                int strict = (l2 < l) || (a2 > a) || (k2 < k);
+                if (strict || o < c) keep[c] = 0;
+            }
+        }
+    }
+    uint32_t left = 0;
+    for (uint32_t c = 0; c < C; c++) left += keep[c];
+
+    /* (c) cap thinning, variant by variant */
+    if (left > cap) {
+        *truncated = 1;
+        uint32_t quota = cap / m->V;
+        for (uint32_t v = 0; v < m->V; v++) {
+            uint32_t n = 0;
+            for (uint32_t c = 0; c < C; c++)
+                if (keep[c] && variant_of(m, c) == v) { order[n].lat = m->lat[(size_t)t * C + c]; order[n].c = c; n++; }
+            if (n <= quota) continue;
+            qsort(order, n, sizeof(lat_c), cmp_lat_c);
+            for (uint32_t i = 0; i < n; i++) keep[order[i].c] = 0;
+            for (uint32_t j = 0; j < quota; j++) {
+                uint32_t rank = (uint32_t)(((uint64_t)j * (n - 1)) / (quota - 1));
+                keep[order[rank].c] = 1;
+            }
+        }
+    }
+    uint32_t k = 0;
+    for (uint32_t c = 0; c < C; c++) if (keep[c]) ids[k++] = (uint16_t)c;
+    *K = k;
+    free(alive); free(keep); free(order);
+    return ORC_OK;
+}
+
+int orc_pruned(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us, uint32_t cap,
+               uint32_t task, uint16_t *ids, uint32_t *K, uint32_t *truncated)
+{
+    if (task >= m->T) return ORC_E_ARG;
+    size_t n = (size_t)m->T * m->C;
+    uint32_t *rep = (uint32_t *)malloc(n * sizeof *rep);
+    int32_t *cost = (int32_t *)malloc(n * sizeof *cost);
+    if (!rep || !cost) { free(rep); free(cost); return ORC_E_MEM; }
+    int rc = orc_cost_table(m, demand_mrps, rep, cost);
+    if (rc == ORC_OK) rc = prune_task(m, cost, slo_latency_us, cap, task, ids, K, truncated);
+    free(rep); free(cost);
+    return rc;
+}
+
+/* ---- one level: tables + lists --------------------------------------------- */
+typedef struct {
+    const orc_model *m;
+    uint32_t *rep; int32_t *cost;
+    uint16_t *ids;            /* [T][C] surviving choices */
+    uint32_t K[ORC_MAX_TASKS];
+    uint32_t truncated;
+    uint64_t space;           /* prod K_t (0 if some K_t = 0) */
+    uint32_t slo_l; double slo_a;
+} level_t;
+
+static void level_free(level_t *L) { free(L->rep); free(L->cost); free(L->ids); }
+
+static int level_init(level_t *L, const orc_model *m, uint32_t demand, uint32_t slo_l, double slo_a, uint32_t cap)
+{
+    memset(L, 0, sizeof *L);
+    size_t n = (size_t)m->T * m->C;
+    L->m = m; L->slo_l = slo_l; L->slo_a = slo_a;
+    L->rep = (uint32_t *)malloc(n * sizeof(uint32_t));
+    L->cost = (int32_t *)malloc(n * sizeof(int32_t));
+    L->ids = (uint16_t *)malloc(n * sizeof(uint16_t));
+    if (!L->rep || !L->cost || !L->ids) { level_free(L); return ORC_E_MEM; }
+    int rc = orc_cost_table(m, demand, L->rep, L->cost);
+    if (rc) { level_free(L); return rc; }
+    unsigned __int128 space = 1;
+    for (uint32_t t = 0; t < m->T; t++) {
+        uint32_t tr = 0;
+        rc = prune_task(m, L->cost, slo_l, cap, t, L->ids + (size_t)t * m->C, &L->K[t], &tr);
+        if (rc) { level_free(L); return rc; }
+        L->truncated |= tr;
+        space *= L->K[t];
+        if (space >> 63) { level_free(L); return ORC_E_RANGE; }
+    }
+    L->space = (uint64_t)space;
+    return ORC_OK;
+}
+
+typedef struct { uint32_t lat; int32_t cost; double acc; uint8_t mask; } score_t;
+
+/* score candidate i of the searched space; c_out[t] = its choice ids */
+static score_t score(const level_t *L, uint64_t i, uint32_t *c_out)
+{
+    const orc_model *m = L->m;
+    uint32_t c[ORC_MAX_TASKS], v[ORC_MAX_TASKS];
+    for (uint32_t t = 0; t < m->T; t++) {
+        uint32_t d = (uint32_t)(i % L->K[t]);
+        i /= L->K[t];
+        c[t] = L->ids[(size_t)t * m->C + d];
+        v[t] = variant_of(m, c[t]);
+        if (c_out) c_out[t] = c[t];
+    }
+    /* Eq. 3: slowest path, doubled (q) for queueing */
+    uint64_t worst = 0;
+    for (int k = 0; k < m->npaths; k++) {
+        uint64_t s = 0;
+        for (int j = 0; j < m->plen[k]; j++) {
+            int t = m->pnode[(size_t)k * m->T + j];
+            s += m->lat[(size_t)t * m->C + c[t]];
+        }
+        if (s > worst) worst = s;
+    }
+    uint64_t lat = (uint64_t)m->q * worst;
+    /* Eq. 7, 8 */
+    int64_t cost = 0;
+    for (uint32_t t = 0; t < m->T; t++) cost += L->cost[(size_t)t * m->C + c[t]];
+    /* Eq. 11-13 */
+    double a = raw_accuracy(m, v) / m->amax;
+    score_t s;
+    s.lat = lat > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)lat;
+    s.cost = cost > 0x7FFFFFFF ? 0x7FFFFFFF : (int32_t)cost;
+    s.acc = a;
+    s.mask = 0;
+    if (lat <= L->slo_l) s.mask |= 1;
+    if (a >= L->slo_a) s.mask |= 2;
+    if (m->capacity == 0 || cost <= (int64_t)m->capacity) s.mask |= 4;
+    return s;
+}
+
+static void result_clear(orc_result *r, const level_t *L)
+{
+    memset(r, 0, sizeof *r);
+    r->index = UINT64_MAX; r->full_index = UINT64_MAX; r->cost = INT32_MAX;
+    r->evaluated = L ? L->space : 0;
+    r->flags = L ? L->truncated : 0;
+}
+
+static void result_fill(orc_result *r, const level_t *L, uint64_t i)
+{
+    const orc_model *m = L->m;
+    uint32_t c[ORC_MAX_TASKS];
+    score_t s = score(L, i, c);
+    r->index = i; r->feasible = 1;
+    r->accuracy = s.acc; r->latency_us = s.lat; r->cost = s.cost;
+    for (uint32_t t = 0; t < m->T; t++) {
+        r->choice[t] = (uint16_t)c[t];
+        r->replicas[t] = L->rep[(size_t)t * m->C + c[t]];
+    }
+    /* sum_t c_t * C^t by Horner from the last task; it only grows */
+    unsigned __int128 full = 0;
+    int over = 0;
+    for (uint32_t t = m->T; t-- > 0;) {
+        full = full * m->C + c[t];
+        if (full >= (unsigned __int128)UINT64_MAX) { over = 1; break; }
+    }
+    r->full_index = over ? UINT64_MAX : (uint64_t)full;
+}
+
+/* cheapest feasible candidate of [lo, hi), lowest index on equal cost */
+static void argmin_range(const level_t *L, uint64_t lo, uint64_t hi, int threads,
+                         int *found, int32_t *best_cost, uint64_t *best_idx)
+{
+    if (threads < 1) threads = 1;
+    int32_t bc[256]; uint64_t bi[256]; int bf[256];
+    if (threads > 256) threads = 256;
+    for (int k = 0; k < threads; k++) { bf[k] = 0; bc[k] = INT32_MAX; bi[k] = UINT64_MAX; }
+    uint64_t span = hi > lo ? hi - lo : 0;
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(threads) schedule(static, 1)
+#endif
+    for (int k = 0; k < threads; k++) {
+        uint64_t a = lo + (uint64_t)(((unsigned __int128)span * (unsigned)k) / (unsigned)threads);
+        uint64_t b = lo + (uint64_t)(((unsigned __int128)span * (unsigned)(k + 1)) / (unsigned)threads);
+        for (uint64_t i = a; i < b; i++) {
+            score_t s = score(L, i, NULL);
+            if (s.mask == 7 && (!bf[k] || s.cost < bc[k])) { bf[k] = 1; bc[k] = s.cost; bi[k] = i; }
+        }
+    }
+    *found = 0; *best_cost = INT32_MAX; *best_idx = UINT64_MAX;
+    for (int k = 0; k < threads; k++)   /* chunks are in ascending index order */
+        if (bf[k] && (!*found || bc[k] < *best_cost)) { *found = 1; *best_cost = bc[k]; *best_idx = bi[k]; }
+}
+
+/*
+ * Search every demand level.  results[n_levels]; best_level/max_demand: the
+ * feasible level with the largest demand (first position on equal demands),
+ * -1 / 0 when none is feasible.
+ */
+int orc_search(const orc_model *m, const uint32_t *demand_mrps, uint32_t n_levels,
+               uint32_t slo_latency_us, double slo_accuracy, uint32_t cap, int threads,
+               orc_result *results, int32_t *best_level, uint32_t *max_demand)
+{
+    if (!m || !demand_mrps || !results) return ORC_E_ARG;
+    int32_t bl = -1; uint32_t md = 0;
+    for (uint32_t l = 0; l < n_levels; l++) {
+        if (demand_mrps[l] == 0) return ORC_E_ARG;
+        level_t L;
+        int rc = level_init(&L, m, demand_mrps[l], slo_latency_us, slo_accuracy, cap);
+        if (rc) return rc;
+        result_clear(&results[l], &L);
+        int found; int32_t bc; uint64_t bi;
+        argmin_range(&L, 0, L.space, threads, &found, &bc, &bi);
+        if (found) {
+            result_fill(&results[l], &L, bi);
+            if (bl < 0 || demand_mrps[l] > md) { bl = (int32_t)l; md = demand_mrps[l]; }
+        }
+        level_free(&L);
+    }
+    if (best_level) *best_level = bl;
+    if (max_demand) *max_demand = md;
+    return ORC_OK;
+}
+
+/* arg-min restricted to candidate indices [lo, hi) of one level */
+int orc_search_range(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us,
+                     double slo_accuracy, uint32_t cap, uint64_t lo, uint64_t hi, int threads,
+                     orc_result *result)
+{
+    level_t L;
+    int rc = level_init(&L, m, demand_mrps, slo_latency_us, slo_accuracy, cap);
+    if (rc) return rc;
+    if (hi > L.space) hi = L.space;
+    result_clear(result, &L);
+    int found; int32_t bc; uint64_t bi;
+    argmin_range(&L, lo, hi, threads, &found, &bc, &bi);
+    if (found) result_fill(result, &L, bi);
+    level_free(&L);
+    return ORC_OK;
+}
+
+/* K_t of every task and the size of the searched space at one level */
+int orc_space(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us, uint32_t cap,
+              uint32_t *K, uint64_t *space, uint32_t *truncated)
+{
+    level_t L;
+    int rc = level_init(&L, m, demand_mrps, slo_latency_us, 0.0, cap);
+    if (rc) return rc;
+    for (uint32_t t = 0; t < m->T; t++) K[t] = L.K[t];
+    *space = L.space; *truncated = L.truncated;
+    level_free(&L);
+    return ORC_OK;
+}
+
+/* score explicit candidates of one level's searched space */
+int orc_eval(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us, double slo_accuracy,
+             uint32_t cap, const uint64_t *index, uint32_t n,
+             uint32_t *latency_us, uint32_t *replicas, int32_t *cost, double *accuracy, uint8_t *mask)
+{
+    level_t L;
+    int rc = level_init(&L, m, demand_mrps, slo_latency_us, slo_accuracy, cap);
+    if (rc) return rc;
+    for (uint32_t k = 0; k < n; k++) {
+        if (index[k] >= L.space) { level_free(&L); return ORC_E_RANGE; }
+        uint32_t c[ORC_MAX_TASKS];
+        score_t s = score(&L, index[k], c);
+        latency_us[k] = s.lat; cost[k] = s.cost; accuracy[k] = s.acc; mask[k] = s.mask;
+        for (uint32_t t = 0; t < m->T; t++) replicas[(size_t)k * m->T + t] = L.rep[(size_t)t * m->C + c[t]];
+    }
+    level_free(&L);
+    return ORC_OK;
+}
+
+/* normalised accuracy of a choice of variants (used by the input guard band) */
+double orc_accuracy_of_variants(const orc_model *m, const uint32_t *variant)
+{
+    return raw_accuracy(m, variant) / m->amax;
+}
+
+/* smallest |A_obj - slo_accuracy| over all V^T combinations of variants */
+double orc_accuracy_margin(const orc_model *m, double slo_accuracy)
+{
+    uint32_t v[ORC_MAX_TASKS] = {0};
+    double best = 1e300;
+    for (;;) {
+        double d = raw_accuracy(m, v) / m->amax - slo_accuracy;
+        if (d < 0) d = -d;
+        if (d < best) best = d;
+        uint32_t t = 0;
+        while (t < m->T && ++v[t] == m->V) v[t++] = 0;
+        if (t == m->T) break;
+    }
+    return best;
+}
+
+int orc_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,331 @@
+"""Seeded synthetic inputs: profile tables, task graphs, demand sweeps and SLOs.
+
+This module only *draws inputs*.  It holds none of the allocation method's
+arithmetic (no replica counts, no path latency, no accuracy composition, no
+pruning): the HIP library and the CPU oracle both receive the arrays made
+here and each computes everything else on its own.
+
+The shapes follow the compound-inference applications the paper evaluates
+(Section 4.1: task graphs of depth 1-3, a handful of model variants per task;
+Table 2: power-of-two batch sizes; Section 4.4: GPUs of 7 slices), extended
+to an 8-task XR-style pipeline and to a batch of small random task graphs.
+
+Random numbers come from one small counter-based generator (SplitMix64, the
+public-domain mixer by Steele, Lea and Flood) so that the streams do not
+depend on any library version.
+"""
+from __future__ import annotations
+
+import json
+import os
+from dataclasses import dataclass, field
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+_MASK = (1 << 64) - 1
+
+
+class SplitMix64:
+    """SplitMix64 stream keyed by a tuple of small integers."""
+
+    def __init__(self, *key: int):
+        s = 0x243F6A8885A308D3  # fractional bits of pi, an arbitrary start
+        for k in key:
+            s = (s ^ (int(k) & _MASK)) & _MASK
+            s = self._mix((s + 0x9E3779B97F4A7C15) & _MASK)
+        self.state = s
+
+    @staticmethod
+    def _mix(z: int) -> int:
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK
+        return z ^ (z >> 31)
+
+    def next_u64(self) -> int:
+        self.state = (self.state + 0x9E3779B97F4A7C15) & _MASK
+        return self._mix(self.state)
+
+    def uniform(self) -> float:
+        """fp64 in [0, 1) with 53 random bits."""
+        return (self.next_u64() >> 11) * (1.0 / (1 << 53))
+
+    def randint(self, lo: int, hi: int) -> int:
+        """Integer in [lo, hi] inclusive."""
+        return lo + int(self.uniform() * (hi - lo + 1))
+
+
+# Stream identifiers: every quantity has its own stream so that re-drawing one
+# of them (the guard band below) leaves the others untouched.
+_S_BASE, _S_ACC, _S_EDGE, _S_SCALAR, _S_SLOA = 1, 2, 3, 4, 5
+
+
+@dataclass
+class Problem:
+    """Profile tables and task graph of one compound inference system.
+
+    Layouts match the library's C ABI: latency_us and thr_mrps are
+    [T][V][P][B] row-major uint32, accuracy is [T][V] float64.
+    """
+    T: int
+    V: int
+    P: int
+    B: int
+    units: np.ndarray          # uint32[P]  cost of each partition size, in slices
+    batch: np.ndarray          # uint32[B]
+    latency_us: np.ndarray     # uint32[T, V, P, B]
+    thr_mrps: np.ndarray       # uint32[T, V, P, B]  milli-requests per second
+    accuracy: np.ndarray       # float64[T, V]
+    src: np.ndarray            # uint16[E]
+    dst: np.ndarray            # uint16[E]
+    mult_milli: np.ndarray     # uint32[T]  per-task demand multiplier, 1/1000ths
+    capacity_units: int        # total slices available (0 = unlimited)
+    queue_factor: int = 2      # latency is doubled for batch-formation queueing
+
+    @property
+    def C(self) -> int:
+        return self.V * self.P * self.B
+
+    @property
+    def E(self) -> int:
+        return int(self.src.shape[0])
+
+
+@dataclass
+class Search:
+    demand_mrps: np.ndarray    # uint32[n_levels]
+    slo_latency_us: int
+    slo_accuracy: float        # fraction of the best achievable accuracy
+    prune_cap: int             # 0 = exhaustive
+
+
+@dataclass
+class Workload:
+    name: str
+    problems: List[Problem]
+    searches: List[Search]
+    note: str = ""
+    meta: dict = field(default_factory=dict)
+
+
+def _tables(rng_base: SplitMix64, rng_acc: SplitMix64, T: int, V: int,
+            sizes: Sequence[int], total_units: int, batches: Sequence[int]):
+    """Per task: V base latencies (int, U[2000, 20000] us, ascending) and V
+    accuracies (U[0.60, 0.95], ascending); latency grows with batch^0.7 and
+    shrinks with (partition share)^0.8; throughput is the batch size over
+    the latency, floored to whole milli-requests/s."""
+    P, B = len(sizes), len(batches)
+    lat = np.zeros((T, V, P, B), dtype=np.uint32)
+    thr = np.zeros((T, V, P, B), dtype=np.uint32)
+    acc = np.zeros((T, V), dtype=np.float64)
+    for t in range(T):
+        bases = sorted(rng_base.randint(2000, 20000) for _ in range(V))
+        accs = sorted(0.60 + 0.35 * rng_acc.uniform() for _ in range(V))
+        acc[t, :] = accs
+        for v in range(V):
+            for p, size in enumerate(sizes):
+                for b, bs in enumerate(batches):
+                    x = bases[v] * (float(bs) ** 0.7) * ((total_units / float(size)) ** 0.8)
+                    us = int(np.floor(x + 0.5))  # x > 0: round half away from zero
+                    lat[t, v, p, b] = us
+                    thr[t, v, p, b] = (bs * 1_000_000_000) // us
+    return lat, thr, acc
+
+
+def _problem(T, V, sizes, total_units, batches, lat, thr, acc, edges, mult, capacity) -> Problem:
+    src = np.array([e[0] for e in edges], dtype=np.uint16)
+    dst = np.array([e[1] for e in edges], dtype=np.uint16)
+    return Problem(T=T, V=V, P=len(sizes), B=len(batches),
+                   units=np.array(sizes, dtype=np.uint32),
+                   batch=np.array(batches, dtype=np.uint32),
+                   latency_us=lat, thr_mrps=thr, accuracy=acc, src=src, dst=dst,
+                   mult_milli=np.array(mult, dtype=np.uint32),
+                   capacity_units=capacity, queue_factor=2)
+
+
+def _log_sweep(lo_rps: float, ratio: float, n: int) -> np.ndarray:
+    """n log-spaced demand levels from lo_rps to lo_rps*ratio, whole mrps."""
+    out = []
+    for i in range(n):
+        x = lo_rps * (ratio ** (i / (n - 1))) * 1000.0
+        out.append(int(np.floor(x + 0.5)))
+    return np.array(out, dtype=np.uint32)
+
+
+_REDRAW_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "guard_redraws.json")
+
+
+def recorded_redraw(name: str, seed: int, index: int = 0) -> int:
+    """Number of times the accuracy table (or, for the batch workload, the
+    accuracy SLO) was drawn again so that no variant combination lands within
+    1e-9 of the accuracy SLO.  The table is written by a script that checks
+    the band with the CPU oracle; an absent entry means the first draw passed."""
+    try:
+        with open(_REDRAW_FILE) as f:
+            table = json.load(f)
+    except FileNotFoundError:
+        return 0
+    return int(table.get(f"{name}/seed{seed}/{index}", 0))
+
+
+def chain3(seed: int = 0, redraw: int | None = None) -> Workload:
+    """Config 1: A->B->C, V=3, partitions {1,2,4,8} of 8, batches {1,2,4,8};
+    48^3 = 110 592 candidates, exhaustive; 50 rps, 100 ms, 0.5."""
+    name = "chain3"
+    if redraw is None:
+        redraw = recorded_redraw(name, seed)
+    T, V, sizes, U, batches = 3, 3, [1, 2, 4, 8], 8, [1, 2, 4, 8]
+    lat, thr, acc = _tables(SplitMix64(1, seed, _S_BASE), SplitMix64(1, seed, _S_ACC, redraw),
+                            T, V, sizes, U, batches)
+    pb = _problem(T, V, sizes, U, batches, lat, thr, acc, [(0, 1), (1, 2)], [1000] * T, 64)
+    se = Search(np.array([50_000], dtype=np.uint32), 100_000, 0.5, 0)
+    return Workload(name, [pb], [se], "3-task chain, exhaustive 48^3")
+
+
+def diamond5(seed: int = 0, redraw: int | None = None, prune_cap: int = 40) -> Workload:
+    """Config 2: A->{B,C,D}->E with demand multipliers {1,1,.5,.5,1}; V=4,
+    partitions {1..7} of 7, batches {1,2,4,8,16}; 32 log-spaced levels
+    10-1000 rps; pruned to <= prune_cap choices per task."""
+    name = "diamond5"
+    if redraw is None:
+        redraw = recorded_redraw(name, seed)
+    T, V, sizes, U, batches = 5, 4, [1, 2, 3, 4, 5, 6, 7], 7, [1, 2, 4, 8, 16]
+    lat, thr, acc = _tables(SplitMix64(2, seed, _S_BASE), SplitMix64(2, seed, _S_ACC, redraw),
+                            T, V, sizes, U, batches)
+    edges = [(0, 1), (0, 2), (0, 3), (1, 4), (2, 4), (3, 4)]
+    pb = _problem(T, V, sizes, U, batches, lat, thr, acc, edges, [1000, 1000, 500, 500, 1000], 56)
+    se = Search(_log_sweep(10.0, 100.0, 32), 100_000, 0.5, prune_cap)
+    return Workload(name, [pb], [se], "5-task diamond, 32-level sweep, pruned")
+
+
+def chain4(seed: int = 0, redraw: int | None = None) -> Workload:
+    """Config 3: chain of 4, V=4, P=7, B=5, exhaustive 140^4 = 384 160 000
+    candidates; 200 rps, 150 ms, 0.45."""
+    name = "chain4"
+    if redraw is None:
+        redraw = recorded_redraw(name, seed)
+    T, V, sizes, U, batches = 4, 4, [1, 2, 3, 4, 5, 6, 7], 7, [1, 2, 4, 8, 16]
+    lat, thr, acc = _tables(SplitMix64(3, seed, _S_BASE), SplitMix64(3, seed, _S_ACC, redraw),
+                            T, V, sizes, U, batches)
+    pb = _problem(T, V, sizes, U, batches, lat, thr, acc, [(0, 1), (1, 2), (2, 3)], [1000] * T, 56)
+    se = Search(np.array([200_000], dtype=np.uint32), 150_000, 0.45, 0)
+    return Workload(name, [pb], [se], "4-task chain, exhaustive 140^4")
+
+
+XR_TASKS = ["sensor-decode", "detection", "depth", "hand-pose", "fusion", "gaze",
+            "segmentation", "render-prep"]
+XR_SKELETON = [(0, 1), (0, 2), (0, 3), (1, 4), (2, 4), (3, 4), (4, 5), (4, 6), (5, 7), (6, 7)]
+
+
+def xr8(seed: int = 0, redraw: int | None = None, prune_cap: int = 20,
+        n_levels: int = 64) -> Workload:
+    """Config 4: 8-task XR-shaped graph: the fixed skeleton plus every other
+    forward pair with probability 0.3; V=5, partitions {1..8} of 8, batches
+    {1,..,32}; 64 log-spaced levels 10-5000 rps; 250 ms, 0.5; pruned to <= 20."""
+    name = "xr8"
+    if redraw is None:
+        redraw = recorded_redraw(name, seed)
+    T, V, sizes, U, batches = 8, 5, [1, 2, 3, 4, 5, 6, 7, 8], 8, [1, 2, 4, 8, 16, 32]
+    lat, thr, acc = _tables(SplitMix64(4, seed, _S_BASE), SplitMix64(4, seed, _S_ACC, redraw),
+                            T, V, sizes, U, batches)
+    rng_e = SplitMix64(4, seed, _S_EDGE)
+    edges = list(XR_SKELETON)
+    fixed = set(XR_SKELETON)
+    for i in range(T):
+        for j in range(i + 1, T):
+            if (i, j) in fixed:
+                continue
+            if rng_e.uniform() < 0.3:
+                edges.append((i, j))
+    pb = _problem(T, V, sizes, U, batches, lat, thr, acc, edges, [1000] * T, 64)
+    se = Search(_log_sweep(10.0, 500.0, n_levels), 250_000, 0.5, prune_cap)
+    return Workload(name, [pb], [se], "8-task XR graph, 64-level sweep, pruned",
+                    meta={"tasks": XR_TASKS})
+
+
+def dagbatch(seed: int = 0, n: int = 256, prune_cap: int = 30) -> Workload:
+    """Config 5: n independent random task graphs, T uniform in 3..6, a random
+    permutation as topological order and every forward pair with probability
+    0.4; V=4, P=7, B=5; own demand U[20,2000] rps, latency SLO U[50,300] ms,
+    accuracy SLO U[0.3,0.7]; pruned to <= 30 per task."""
+    name = "dagbatch"
+    V, sizes, U, batches = 4, [1, 2, 3, 4, 5, 6, 7], 7, [1, 2, 4, 8, 16]
+    problems, searches = [], []
+    for k in range(n):
+        rs = SplitMix64(5, seed, _S_SCALAR, k)
+        T = rs.randint(3, 6)
+        lat, thr, acc = _tables(SplitMix64(5, seed, _S_BASE, k), SplitMix64(5, seed, _S_ACC, k),
+                                T, V, sizes, U, batches)
+        rng_e = SplitMix64(5, seed, _S_EDGE, k)
+        order = list(range(T))
+        for i in range(T - 1, 0, -1):  # Fisher-Yates
+            j = rng_e.randint(0, i)
+            order[i], order[j] = order[j], order[i]
+        edges = []
+        for i in range(T):
+            for j in range(i + 1, T):
+                if rng_e.uniform() < 0.4:
+                    edges.append((order[i], order[j]))
+        demand = rs.randint(20_000, 2_000_000)
+        slo_l = rs.randint(50_000, 300_000)
+        rs_a = SplitMix64(5, seed, _S_SLOA, k, recorded_redraw(name, seed, k))
+        slo_a = 0.3 + 0.4 * rs_a.uniform()
+        problems.append(_problem(T, V, sizes, U, batches, lat, thr, acc, edges, [1000] * T, 56))
+        searches.append(Search(np.array([demand], dtype=np.uint32), slo_l, slo_a, prune_cap))
+    return Workload(name, problems, searches, f"{n} random task graphs, one launch")
+
+
+def tiny_random(seed: int, T: int | None = None, max_c: int = 8) -> Tuple[Problem, Search]:
+    """Small random instance for exhaustive cross-checks: arbitrary forward
+    edges (so multi-source, multi-sink and isolated tasks all occur), random
+    multipliers, tables drawn directly (not from the smooth latency model) so
+    that ties and dominated choices are frequent."""
+    r = SplitMix64(9, seed)
+    if T is None:
+        T = r.randint(1, 4)
+    while True:
+        V, P, B = r.randint(1, 3), r.randint(1, 3), r.randint(1, 2)
+        if V * P * B <= max_c:
+            break
+    units = sorted(r.randint(1, 4) for _ in range(P))
+    batches = [1 << b for b in range(B)]
+    lat = np.zeros((T, V, P, B), dtype=np.uint32)
+    thr = np.zeros((T, V, P, B), dtype=np.uint32)
+    acc = np.zeros((T, V), dtype=np.float64)
+    for t in range(T):
+        for v in range(V):
+            acc[t, v] = 0.5 + 0.05 * r.randint(0, 9)
+            for p in range(P):
+                for b in range(B):
+                    lat[t, v, p, b] = 1000 * r.randint(1, 12)
+                    thr[t, v, p, b] = 1000 * r.randint(5, 400)
+    edges = []
+    dens = r.uniform()
+    for i in range(T):
+        for j in range(i + 1, T):
+            if r.uniform() < dens:
+                edges.append((i, j))
+    # relabel so that task ids are not already in topological order
+    perm = list(range(T))
+    for i in range(T - 1, 0, -1):
+        j = r.randint(0, i)
+        perm[i], perm[j] = perm[j], perm[i]
+    edges = [(perm[a], perm[b]) for a, b in edges]
+    mult = [250 * r.randint(1, 8) for _ in range(T)]
+    capacity = r.randint(0, 1) * r.randint(4, 40)
+    pb = _problem(T, V, units, max(units), batches, lat, thr, acc, edges, mult, capacity)
+    demand = np.array(sorted({1000 * r.randint(1, 600) for _ in range(r.randint(1, 4))}),
+                      dtype=np.uint32)
+    slo_l = 1000 * r.randint(4, 80)
+    slo_a = [0.0, 0.3, 0.55, 0.7, 0.85, 0.95][r.randint(0, 5)] + 1e-4 * r.uniform()
+    cap = 0 if r.uniform() < 0.5 else r.randint(2 * V, max(2 * V, V * P * B))
+    return pb, Search(demand, slo_l, slo_a, cap)
+
+
+BENCH_WORKLOADS = {
+    "chain3": chain3,
+    "diamond5": diamond5,
+    "chain4": chain4,
+    "xr8": xr8,
+    "dagbatch": dagbatch,
+}

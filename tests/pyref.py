@@ -1,0 +1,153 @@
+"""A second, independent statement of the search in exact Python arithmetic.
+
+Used only to pin the C oracle on tiny inputs: integers are Python ints,
+accuracies are exact rationals (fractions.Fraction of the fp64 inputs), the
+critical path and the accuracy are computed by a dynamic program over a
+topological order (the C oracle enumerates paths instead), and the prune is
+written with sorting and set operations (the C oracle uses flag arrays).
+Follows Section 3.2 of the paper, Eq. 2, 3, 5-8, 11-13, with one
+(variant, partition, batch) tuple per task.
+"""
+from __future__ import annotations
+
+import itertools
+from fractions import Fraction
+from typing import Dict, List, Optional, Tuple
+
+
+class PyRef:
+    def __init__(self, pb):
+        self.pb = pb
+        self.T, self.V, self.P, self.B, self.C = pb.T, pb.V, pb.P, pb.B, pb.C
+        self.lat = pb.latency_us.reshape(pb.T, pb.C).astype(object)
+        self.thr = pb.thr_mrps.reshape(pb.T, pb.C).astype(object)
+        self.m = [int(x) for x in pb.mult_milli]
+        self.q = int(pb.queue_factor)
+        self.preds: List[List[int]] = [[] for _ in range(pb.T)]
+        self.succs: List[List[int]] = [[] for _ in range(pb.T)]
+        for a, b in zip(pb.src.tolist(), pb.dst.tolist()):
+            self.preds[b].append(a)
+            self.succs[a].append(b)
+        # topological order by repeated removal
+        indeg = [len(p) for p in self.preds]
+        order, ready = [], [t for t in range(pb.T) if indeg[t] == 0]
+        while ready:
+            t = ready.pop()
+            order.append(t)
+            for s in self.succs[t]:
+                indeg[s] -= 1
+                if indeg[s] == 0:
+                    ready.append(s)
+        assert len(order) == pb.T, "cycle"
+        self.order = order
+        self.sinks = [t for t in range(pb.T) if not self.succs[t]]
+        self.sink_total = sum(self.m[s] for s in self.sinks)
+        self.accF = [[Fraction(float(pb.accuracy[t, v])) for v in range(pb.V)] for t in range(pb.T)]
+        self.amax = self._acc([max(range(pb.V), key=lambda v: (self.accF[t][v], -v))
+                               for t in range(pb.T)])
+
+    def variant(self, c: int) -> int:
+        return c // (self.P * self.B)
+
+    def part(self, c: int) -> int:
+        return (c // self.B) % self.P
+
+    def _acc(self, variants) -> Fraction:
+        """Sum over paths of (request fraction x product of accuracies), as a
+        node recursion: G(t) = a_t * sum_pred share(pred->t) * G(pred)."""
+        G: Dict[int, Fraction] = {}
+        for t in self.order:
+            a = self.accF[t][variants[t]]
+            if not self.preds[t]:
+                G[t] = a
+            else:
+                tot = sum(self.m[p] for p in self.preds[t])
+                G[t] = a * sum(Fraction(self.m[p], tot) * G[p] for p in self.preds[t])
+        return sum(Fraction(self.m[s], self.sink_total) * G[s] for s in self.sinks)
+
+    def latency(self, choice) -> int:
+        fin: Dict[int, int] = {}
+        for t in self.order:
+            fin[t] = int(self.lat[t][choice[t]]) + max([fin[p] for p in self.preds[t]], default=0)
+        return self.q * max(fin[s] for s in self.sinks)
+
+    def rep_cost(self, D: int, t: int, c: int) -> Tuple[int, int]:
+        need = D * self.m[t]                       # micro-requests per second
+        per = 1000 * int(self.thr[t][c])
+        rep = max(1, -(-need // per))
+        return rep, rep * int(self.pb.units[self.part(c)])
+
+    def lists(self, D: int, slo_l: int, cap: int) -> Tuple[List[List[int]], bool]:
+        if cap == 0:
+            return [list(range(self.C)) for _ in range(self.T)], False
+        # longest path through t with other tasks at their fastest choice:
+        # longest chain ending just before t plus longest chain starting just after it
+        lo = [min(int(x) for x in self.lat[t]) for t in range(self.T)]
+        up = {}
+        for t in self.order:
+            up[t] = max([up[p] + lo[p] for p in self.preds[t]], default=0)
+        down = {}
+        for t in reversed(self.order):
+            down[t] = max([down[s] + lo[s] for s in self.succs[t]], default=0)
+        out, truncated = [], False
+        for t in range(self.T):
+            through = up[t] + down[t]
+            rows = []
+            for c in range(self.C):
+                if self.q * (int(self.lat[t][c]) + through) <= slo_l:
+                    rows.append((int(self.lat[t][c]), self.accF[t][self.variant(c)],
+                                 self.rep_cost(D, t, c)[1], c))
+            front = []
+            for r in rows:
+                beaten = False
+                for o in rows:
+                    if o is r:
+                        continue
+                    if o[0] <= r[0] and o[1] >= r[1] and o[2] <= r[2]:
+                        if (o[0], o[1], o[2]) != (r[0], r[1], r[2]) or o[3] < r[3]:
+                            beaten = True
+                            break
+                if not beaten:
+                    front.append(r)
+            if len(front) > cap:
+                truncated = True
+                quota = cap // self.V
+                kept = []
+                for v in range(self.V):
+                    mine = sorted((r for r in front if self.variant(r[3]) == v),
+                                  key=lambda r: (r[0], r[3]))
+                    n = len(mine)
+                    if n <= quota:
+                        kept += mine
+                    else:
+                        kept += [mine[(j * (n - 1)) // (quota - 1)] for j in range(quota)]
+                front = kept
+            out.append(sorted(r[3] for r in front))
+        return out, truncated
+
+    def search(self, D: int, slo_l: int, slo_a: float, cap: int):
+        """Returns (best index or None, cost, latency, accuracy Fraction, K list,
+        truncated, min |A - slo| seen)."""
+        lists, truncated = self.lists(D, slo_l, cap)
+        K = [len(l) for l in lists]
+        best = None
+        margin = None
+        slo = Fraction(float(slo_a))
+        capu = int(self.pb.capacity_units)
+        if all(K):
+            strides = [1] * self.T
+            for t in range(1, self.T):
+                strides[t] = strides[t - 1] * K[t - 1]
+            for digits in itertools.product(*[range(k) for k in reversed(K)]):
+                digits = digits[::-1]            # digits[t] for task t; task 0 fastest
+                idx = sum(d * s for d, s in zip(digits, strides))
+                choice = [lists[t][digits[t]] for t in range(self.T)]
+                lat = self.latency(choice)
+                cost = sum(self.rep_cost(D, t, choice[t])[1] for t in range(self.T))
+                acc = self._acc([self.variant(c) for c in choice]) / self.amax
+                d = abs(acc - slo)
+                margin = d if margin is None or d < margin else margin
+                ok = lat <= slo_l and acc >= slo and (capu == 0 or cost <= capu)
+                if ok and (best is None or (cost, idx) < (best[1], best[0])):
+                    best = (idx, cost, lat, acc, choice)
+        return best, K, truncated, margin
