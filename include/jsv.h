@@ -1,0 +1,223 @@
+/*
+ * jsv - allocation search for compound inference serving, on one AMD MI355X.
+ *
+ * For every task of a compound-inference task graph the search picks one
+ * (model variant, spatial-partition size, batch size) tuple, replicated as often
+ * as the demand needs, such that the end-to-end latency and accuracy SLOs hold
+ * and the number of GPU partition units is minimal.  This is the optimisation of
+ * Section 3.2 of the paper (Eq. 1-14) restricted to one tuple per task and to
+ * the cost term of the objective, solved by exhaustive enumeration on the GPU.
+ *
+ * Conventions
+ *   choice id      c = (v*P + p)*B + b            (variant slowest, batch fastest)
+ *   candidate      one choice per task; index i = sum_t d_t * prod_{u<t} K_u where
+ *                  d_t is the position of task t's choice in its surviving list
+ *                  (ascending c) and K_t that list's length; task 0 is the fastest
+ *                  digit.  Without pruning K_t = C = V*P*B and d_t = c_t.
+ *   demand         integer milli-requests per second (mrps) at the graph's entry
+ *   latency        integer microseconds
+ *   multipliers    per-task demand multipliers in 1/1000ths (1000 = 1.0)
+ *
+ * All pointers in the signatures below are HOST pointers unless a comment says
+ * "device".  Inputs are copied during the call and stay owned by the caller;
+ * outputs are caller-allocated.  Every function returns JSV_OK (0) or a negative
+ * error code; none throws or aborts.  "No feasible assignment" is not an error.
+ * A context is not thread-safe; distinct contexts are independent.
+ */
+#ifndef JSV_H
+#define JSV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define JSV_API __attribute__((visibility("default")))
+
+#define JSV_MAX_TASKS   16      /* tasks per graph */
+#define JSV_MAX_CHOICES 2048    /* V*P*B per task */
+
+enum {
+    JSV_OK          =  0,
+    JSV_E_NULL      = -1,   /* a required pointer is NULL */
+    JSV_E_BADARG    = -2,   /* value out of range (see each call) */
+    JSV_E_CYCLE     = -3,   /* the task graph has a cycle */
+    JSV_E_OVERFLOW  = -4,   /* latency, cost or search-space size does not fit */
+    JSV_E_STATE     = -5,   /* call order: search before profile/graph, T mismatch */
+    JSV_E_WORKSPACE = -6,   /* caller-supplied workspace too small */
+    JSV_E_DEVICE    = -7    /* a HIP call failed; see jsv_last_hip_error */
+};
+
+typedef struct jsv_ctx jsv_ctx;
+
+/*
+ * Create a context bound to one GPU.  hip_stream is a hipStream_t borrowed from
+ * the caller (NULL = the default stream); all device work of this context is
+ * enqueued on it, in order.  No device call is made before the first search, so
+ * profile and graph validation work on a machine without a GPU.
+ */
+JSV_API int  jsv_create(jsv_ctx** out, int device, void* hip_stream);
+JSV_API void jsv_destroy(jsv_ctx* ctx);
+
+/* HIP error code (hipError_t as int) of the last failed device call, 0 if none. */
+JSV_API int  jsv_last_hip_error(const jsv_ctx* ctx);
+JSV_API const char* jsv_error_string(int code);
+
+/*
+ * Device scratch memory.  By default the library allocates what a search needs
+ * (grow-only, freed by jsv_destroy).  A caller that owns device memory can lend
+ * a buffer instead: jsv_workspace_bytes gives the size a search of n_levels
+ * demand levels (or a batch of n_levels problems) with the loaded profile needs;
+ * jsv_set_workspace lends `bytes` bytes at DEVICE pointer `device_ptr`
+ * (256-byte aligned) until the next set call or jsv_destroy; NULL returns to
+ * library-owned memory.  A lent buffer that is too small makes the search
+ * return JSV_E_WORKSPACE.
+ */
+JSV_API size_t jsv_workspace_bytes(const jsv_ctx* ctx, uint32_t n_levels, uint32_t prune_cap);
+JSV_API int    jsv_set_workspace(jsv_ctx* ctx, void* device_ptr, size_t bytes);
+
+/*
+ * Profile tables (Table 2 of the paper, "profiled information"): the same V, P,
+ * B for every task.
+ *   units[P]               cost s_n of each partition size, in GPU slices (> 0)
+ *   batch[B]               batch sizes (> 0)
+ *   latency_us[T][V][P][B] profiled latency L(t,v,s,b), microseconds, > 0
+ *   thr_mrps[T][V][P][B]   profiled throughput H(t,v,s,b), milli-requests/s, > 0;
+ *                          NULL derives it as floor(batch * 1e9 / latency_us)
+ *   accuracy[T][V]         A(t,v), fp64 in (0, 1]
+ * Errors: JSV_E_NULL; JSV_E_BADARG (T = 0, T > JSV_MAX_TASKS, V*P*B = 0 or
+ * > JSV_MAX_CHOICES, a zero unit/batch/latency/throughput, accuracy outside
+ * (0,1]); JSV_E_OVERFLOW (derived throughput >= 2^32).
+ */
+JSV_API int jsv_load_profile(jsv_ctx* ctx, uint32_t T, uint32_t V, uint32_t P, uint32_t B,
+                     const uint32_t* units, const uint32_t* batch,
+                     const uint32_t* latency_us, const uint32_t* thr_mrps,
+                     const double* accuracy);
+
+/*
+ * Task graph over the same T tasks (Table 2: P, P(t), f_p; Eq. 3, 5, 12).
+ *   src[E], dst[E]         edges by task id, any order
+ *   demand_mult_milli[T]   demand at task t relative to the entry demand, R(t)/R,
+ *                          in 1/1000ths, > 0.  The fraction of requests on a path
+ *                          (f_p of Eq. 12) is derived from these: a sink's share of
+ *                          all sinks times, per edge, the tail's share of the
+ *                          head's predecessors.
+ *   capacity_units         S_avail of Eq. 8; 0 = unlimited
+ *   queue_factor           the factor on latency for batch-formation queueing;
+ *                          Eq. 3 uses 2
+ * Errors: JSV_E_NULL; JSV_E_BADARG (T = 0 or > JSV_MAX_TASKS, endpoint >= T, self
+ * loop, duplicate edge, zero multiplier, queue_factor = 0); JSV_E_CYCLE;
+ * JSV_E_STATE (T differs from the loaded profile).
+ */
+JSV_API int jsv_set_dag(jsv_ctx* ctx, uint32_t T, uint32_t E, const uint16_t* src, const uint16_t* dst,
+                const uint32_t* demand_mult_milli, uint32_t capacity_units, uint32_t queue_factor);
+
+typedef struct {
+    uint64_t index;        /* winner's index in the searched space; UINT64_MAX if infeasible */
+    uint64_t full_index;   /* sum_t c_t * C^t; UINT64_MAX if infeasible or it does not fit */
+    uint64_t evaluated;    /* candidates scored at this level = prod_t K_t */
+    double   accuracy;     /* A_obj of Eq. 12: normalised to the best achievable */
+    uint32_t latency_us;   /* queue_factor * critical path (left side of Eq. 3) */
+    int32_t  cost_units;   /* sum of replicas * units (Eq. 7, 8); INT32_MAX if infeasible */
+    uint32_t feasible;     /* 0 / 1 */
+    uint32_t flags;        /* bit0: the prune cap dropped a non-dominated choice */
+    uint16_t choice[JSV_MAX_TASKS];     /* winner's choice id per task */
+    uint32_t replicas[JSV_MAX_TASKS];   /* M of Eq. 6 per task */
+} jsv_result;
+
+typedef struct {
+    int32_t  best_level;       /* position of the feasible level with the largest demand
+                                  (first one on equal demands); -1 if none */
+    uint32_t max_demand_mrps;  /* its demand: the maximum serviceable demand; 0 if none */
+    double   seconds_device;   /* device time of the whole search, HIP events */
+    double   seconds_enumerate;/* of which the enumeration kernel */
+} jsv_summary;
+
+/*
+ * The search (Eq. 2, 3, 5-8, 11-13).  For every demand level: replicas and cost
+ * of every (task, choice); optional per-task prune; every candidate of the
+ * searched space scored for latency, accuracy and cost and masked against
+ * SLO_l, SLO_a and S_avail; the cheapest feasible candidate, lowest index on
+ * equal cost.  All levels run in one pass on the context's stream; the call
+ * returns after the results are in out[].
+ *   demand_mrps[n_levels]  any order, each > 0
+ *   slo_accuracy           threshold on A_obj, a fraction of the best achievable
+ *   prune_cap              0: exhaustive.  Otherwise >= 2V: each task keeps only
+ *                          choices that can meet SLO_l at all and that no other
+ *                          choice matches or beats on (latency, accuracy, cost);
+ *                          if more than prune_cap remain, each variant is thinned
+ *                          to floor(prune_cap/V) of them evenly spaced by latency
+ *                          rank (fastest and cheapest always kept; sets flags bit0)
+ *   out[n_levels], summary caller-allocated; summary may be NULL
+ * Errors: JSV_E_NULL, JSV_E_STATE, JSV_E_BADARG (n_levels = 0, a zero demand,
+ * prune_cap in (0, 2V)), JSV_E_OVERFLOW (queue_factor * T * max latency >= 2^32;
+ * a cost >= 2^31; searched space and cost do not fit a 64-bit key together),
+ * JSV_E_WORKSPACE, JSV_E_DEVICE.
+ */
+JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_levels,
+               uint32_t slo_latency_us, double slo_accuracy, uint32_t prune_cap,
+               jsv_result* out, jsv_summary* summary);
+
+/*
+ * Parity aid: score n explicit candidates of one level's searched space.
+ * index[n] are candidate indices (< prod K_t).  Outputs, each [n] (replicas
+ * [n][T]): latency_us, cost, accuracy as in jsv_result; mask bit0 latency SLO
+ * met, bit1 accuracy SLO met, bit2 capacity met.  Errors as jsv_search, plus
+ * JSV_E_BADARG for an index outside the space.
+ */
+JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_latency_us,
+                        double slo_accuracy, uint32_t prune_cap,
+                        const uint64_t* index, uint32_t n,
+                        uint32_t* latency_us, uint32_t* replicas, int32_t* cost,
+                        double* accuracy, uint8_t* mask);
+
+/*
+ * Parity aid: the surviving choice ids of one task at one level, ascending.
+ * choice_ids must hold V*P*B entries; *K receives the count, *truncated whether
+ * the cap dropped a non-dominated choice of this task.
+ */
+JSV_API int jsv_get_pruned(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_latency_us,
+                   uint32_t prune_cap, uint32_t task,
+                   uint16_t* choice_ids, uint32_t* K, uint32_t* truncated);
+
+/*
+ * Many independent systems in one pass: each problem has its own tables, graph,
+ * demand, SLOs and prune cap (fields as the arguments of jsv_load_profile,
+ * jsv_set_dag and jsv_search).
+ */
+typedef struct {
+    uint32_t T, V, P, B;
+    const uint32_t* units;
+    const uint32_t* batch;
+    const uint32_t* latency_us;
+    const uint32_t* thr_mrps;        /* may be NULL */
+    const double*   accuracy;
+    uint32_t E;
+    const uint16_t* src;
+    const uint16_t* dst;
+    const uint32_t* demand_mult_milli;
+    uint32_t capacity_units;
+    uint32_t queue_factor;
+    uint32_t demand_mrps;
+    uint32_t slo_latency_us;
+    double   slo_accuracy;
+    uint32_t prune_cap;
+} jsv_problem;
+
+/*
+ * jsv_load_batch validates and stages n problems on the device (replacing any
+ * profile/graph or batch loaded before); jsv_search_loaded_batch searches all of
+ * them in one pass, out[n].  jsv_search_batch does both.  A problem that fails
+ * validation makes the call return its error; *bad (may be NULL) receives its
+ * position.
+ */
+JSV_API int jsv_load_batch(jsv_ctx* ctx, const jsv_problem* problems, uint32_t n, uint32_t* bad);
+JSV_API int jsv_search_loaded_batch(jsv_ctx* ctx, jsv_result* out, jsv_summary* summary);
+JSV_API int jsv_search_batch(jsv_ctx* ctx, const jsv_problem* problems, uint32_t n, jsv_result* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JSV_H */

@@ -1,0 +1,126 @@
+// Device-side data layout shared by the host planner and the HIP kernels.
+//
+// Positions.  Tasks are handled in a topological order fixed by the host
+// (Kahn's algorithm, lowest task id first).  "Position" p means the place of a
+// task in that order: p = 0 is a source.  The kernels evaluate the critical
+// path (Eq. 3) and the accuracy (Eq. 11, 12) by a backward recursion over
+// positions, from the sinks towards the sources:
+//
+//   tail(p) = L(p) + max over successors s of tail(s)            latency to the end
+//   H(p)    = a(p) * ( u(p)                     if p is a sink
+//                      sum_s w(p,s) * H(s)      otherwise )      accuracy mass
+//   latency  = q * max over sources of tail,   A_raw = sum over sources of H
+//
+// with w(p,s) the share of p among the predecessors of s and u(p) the share of
+// sink p among all sinks (both from the per-task demand multipliers).  Summed
+// over sources this is exactly sum_p f_p * prod_{t in p} a_t of Eq. 12.
+#pragma once
+#include <stdint.h>
+
+namespace jsv {
+
+constexpr int MAXT = 16;          // tasks per graph
+constexpr int MAXC = 2048;        // choices per task
+constexpr int TILE_LANES = 256;   // lanes (threads) per enumeration tile
+constexpr uint64_t NO_KEY = ~0ull;
+
+// instance flag bits
+constexpr uint32_t F_TRUNCATED = 1u;        // cap thinning dropped a choice
+constexpr uint32_t F_OVERFLOW  = 1u << 8;   // replicas, cost or key do not fit
+constexpr uint32_t F_EMPTY     = 1u << 9;   // some task has no surviving choice
+
+// One surviving choice of one task at one demand level.
+struct __attribute__((aligned(32))) Entry {
+    uint32_t lat;     // profiled latency, us
+    uint32_t cost;    // replicas * partition units
+    double   acc;     // accuracy of its variant
+    uint64_t key;     // (cost << idx_bits) | digit * stride   (caller's index order)
+    uint32_t rep;     // replicas
+    uint32_t choice;  // original choice id
+};
+static_assert(sizeof(Entry) == 32, "Entry must be 32 bytes");
+
+// Task graph of one problem, by position.
+struct Graph {
+    uint32_t T, V, P, B, C;
+    uint32_t q;               // queue factor
+    uint32_t capacity;        // S_avail, 0 = unlimited
+    uint32_t src_mask;        // bit p: position p has no predecessor
+    uint32_t sink_mask;       // bit p: position p has no successor
+    uint32_t pad0;
+    uint8_t  task_at[MAXT];   // task id at position p
+    uint8_t  pos_of[MAXT];    // position of task id t
+    uint32_t succ[MAXT];      // bit s: position s is a successor of position p (s > p)
+    uint32_t mult[MAXT];      // demand multiplier (1/1000ths), by task id
+    uint32_t through[MAXT];   // longest path through task t with every other task at
+                              // its fastest choice and t itself at zero, by task id
+    double   u[MAXT];         // sink share of position p (0 if not a sink)
+    double   w[MAXT][MAXT];   // w[p][s] share of p among the predecessors of s (0 if no edge)
+    double   amax;            // A_raw with every task on its most accurate variant
+    // tables of this problem, device pointers
+    const uint32_t* lat;      // [T][C]
+    const uint32_t* thr;      // [T][C]  mrps
+    const double*   acc;      // [T][V]
+    const uint32_t* units;    // [P]
+};
+
+// One search instance: a problem at one demand level.
+struct Instance {
+    // inputs (host)
+    uint32_t problem;
+    uint32_t demand;          // mrps
+    uint32_t slo_l;           // us
+    uint32_t cap;             // prune cap, 0 = exhaustive
+    double   slo_a;           // threshold on A_obj
+    double   slo_raw;         // slo_a * amax: threshold on A_raw
+    // written by the prune and plan kernels
+    uint32_t K[MAXT];         // surviving choices per task id
+    uint64_t stride[MAXT];    // prod_{u<t} K_u per task id
+    uint64_t space;           // prod K_t
+    uint64_t s_out;           // outer combinations = prod of K over positions >= n_in
+    uint32_t idx_bits;        // bits of the index part of a key
+    uint32_t flags;
+    uint32_t n_in;            // positions 0..n_in-1 are looped inside a lane
+    uint32_t chunk;           // digits of position n_in-1 per tile
+    uint32_t n_chunks;
+    uint32_t n_groups;        // ceil(s_out / TILE_LANES)
+    uint32_t tiles;           // n_groups * n_chunks
+    uint32_t trunc_mask;      // bit t: cap thinning dropped a choice of task id t
+    uint64_t tile_begin;      // first global tile of this instance (exclusive scan)
+};
+
+// Result record as written by the finalize kernel; same layout as jsv_result.
+struct ResultRec {
+    uint64_t index, full_index, evaluated;
+    double   accuracy;
+    uint32_t latency_us;
+    int32_t  cost_units;
+    uint32_t feasible, flags;
+    uint16_t choice[MAXT];
+    uint32_t replicas[MAXT];
+};
+
+struct SummaryRec {
+    int32_t  best_level;
+    uint32_t max_demand;
+    uint64_t total_tiles;     // written by the scan kernel
+    uint32_t done_count;      // finalize blocks finished
+    uint32_t any_flags;       // OR of all instance flags
+};
+
+// Everything the kernels need to find their data; passed by value.
+struct Plan {
+    const Graph* graphs;      // [n_problems]
+    Instance*    inst;        // [n_inst]
+    Entry*       entries;     // [n_inst][t_max][k_max]   by task id
+    uint32_t*    rep;         // [n_inst][t_max][c_max]   replicas of every choice
+    uint32_t*    cost;        // [n_inst][t_max][c_max]
+    uint64_t*    partial;     // [n_inst][grid]           per-block minima
+    ResultRec*   results;     // [n_inst]
+    SummaryRec*  summary;
+    uint32_t n_inst, t_max, k_max, c_max;
+    uint32_t grid;            // blocks of the enumeration kernel
+    uint32_t lanes_wanted;    // total lanes the planner tries to expose
+};
+
+}  // namespace jsv

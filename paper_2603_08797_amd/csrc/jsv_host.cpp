@@ -1,0 +1,744 @@
+// Host side of the C ABI (include/jsv.h): validation, task-graph staging
+// (topological order, request shares, A_max, per-task latency slack), device
+// memory layout, the launch sequence on the caller's stream, result conversion.
+//
+// The host does no search arithmetic: replicas, cost, prune, scoring and the
+// arg-min all run in the kernels (jsv_kernels.hip).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/jsv.h"
+#include "jsv_device.h"
+#include "jsv_launch.h"
+
+static_assert(JSV_MAX_TASKS == jsv::MAXT, "header and device limits differ");
+static_assert(JSV_MAX_CHOICES == jsv::MAXC, "header and device limits differ");
+static_assert(sizeof(jsv_result) == sizeof(jsv::ResultRec), "result layouts differ");
+
+namespace {
+
+using jsv::Graph;
+using jsv::Instance;
+using jsv::MAXT;
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+// One compound system as staged on the host.
+struct HostProblem {
+    uint32_t T = 0, V = 0, P = 0, B = 0, C = 0;
+    std::vector<uint32_t> units, batch, lat, thr;
+    std::vector<double> acc;
+    bool have_profile = false;
+    // graph inputs
+    uint32_t E = 0;
+    std::vector<uint16_t> src, dst;
+    std::vector<uint32_t> mult;
+    uint32_t capacity = 0, q = 2;
+    bool have_dag = false;
+    // staged
+    Graph graph;
+    bool staged = false;
+};
+
+struct Search {               // per-instance search parameters (batch mode keeps them per problem)
+    uint32_t demand = 0, slo_l = 0, cap = 0;
+    double slo_a = 0.0;
+};
+
+struct Layout {               // offsets into the workspace
+    size_t inst, entries, rep, cost, partial, results, summary, eval, total;
+};
+
+}  // namespace
+
+struct jsv_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    int last_hip = 0;
+    bool device_ready = false;
+    uint32_t grid = 0;
+
+    HostProblem single;
+    std::vector<HostProblem> batch;
+    std::vector<Search> batch_search;
+    bool batch_mode = false;
+    bool dirty = true;                 // host problems changed since the last upload
+
+    void* d_problems = nullptr;        // graphs + tables
+    size_t d_problems_bytes = 0;
+    uint32_t n_problems = 0;
+
+    void* ws_own = nullptr;  size_t ws_own_bytes = 0;
+    void* ws_lent = nullptr; size_t ws_lent_bytes = 0;
+
+    void* pinned = nullptr;  size_t pinned_bytes = 0;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+};
+
+namespace {
+
+#define HIP_TRY(ctx, expr)                                     \
+    do {                                                       \
+        hipError_t e_ = (expr);                                \
+        if (e_ != hipSuccess) { (ctx)->last_hip = (int)e_; return JSV_E_DEVICE; } \
+    } while (0)
+
+int check_profile(uint32_t T, uint32_t V, uint32_t P, uint32_t B, const uint32_t* units,
+                  const uint32_t* batch, const uint32_t* lat, const uint32_t* thr, const double* acc,
+                  HostProblem& hp)
+{
+    if (!units || !batch || !lat || !acc) return JSV_E_NULL;
+    if (T == 0 || T > JSV_MAX_TASKS || V == 0 || P == 0 || B == 0) return JSV_E_BADARG;
+    const uint64_t C64 = (uint64_t)V * P * B;
+    if (C64 > JSV_MAX_CHOICES) return JSV_E_BADARG;
+    const uint32_t C = (uint32_t)C64;
+    for (uint32_t p = 0; p < P; ++p) if (units[p] == 0) return JSV_E_BADARG;
+    for (uint32_t b = 0; b < B; ++b) if (batch[b] == 0) return JSV_E_BADARG;
+    const size_t n = (size_t)T * C;
+    std::vector<uint32_t> h(n);
+    for (size_t k = 0; k < n; ++k) {
+        if (lat[k] == 0) return JSV_E_BADARG;
+        if (thr) {
+            if (thr[k] == 0) return JSV_E_BADARG;
+            h[k] = thr[k];
+        } else {
+            // one batch of batch[b] requests every latency microseconds, in milli-requests/s
+            const uint64_t v = (uint64_t)batch[k % B] * 1000000000ull / lat[k];
+            if (v > 0xFFFFFFFFull) return JSV_E_OVERFLOW;
+            if (v == 0) return JSV_E_BADARG;
+            h[k] = (uint32_t)v;
+        }
+    }
+    for (size_t k = 0; k < (size_t)T * V; ++k)
+        if (!(acc[k] > 0.0 && acc[k] <= 1.0)) return JSV_E_BADARG;
+    hp.T = T; hp.V = V; hp.P = P; hp.B = B; hp.C = C;
+    hp.units.assign(units, units + P);
+    hp.batch.assign(batch, batch + B);
+    hp.lat.assign(lat, lat + n);
+    hp.thr.swap(h);
+    hp.acc.assign(acc, acc + (size_t)T * V);
+    hp.have_profile = true;
+    hp.staged = false;
+    return JSV_OK;
+}
+
+int check_dag(uint32_t T, uint32_t E, const uint16_t* src, const uint16_t* dst, const uint32_t* mult,
+              uint32_t capacity, uint32_t q, HostProblem& hp)
+{
+    if (!mult || (E && (!src || !dst))) return JSV_E_NULL;
+    if (T == 0 || T > JSV_MAX_TASKS || q == 0) return JSV_E_BADARG;
+    bool adj[MAXT][MAXT] = {};
+    for (uint32_t e = 0; e < E; ++e) {
+        const uint32_t a = src[e], b = dst[e];
+        if (a >= T || b >= T || a == b || adj[a][b]) return JSV_E_BADARG;
+        adj[a][b] = true;
+    }
+    for (uint32_t t = 0; t < T; ++t) if (mult[t] == 0) return JSV_E_BADARG;
+    // cycle check (Kahn): strip tasks without remaining predecessors
+    {
+        int indeg[MAXT] = {};
+        bool gone[MAXT] = {};
+        for (uint32_t a = 0; a < T; ++a) for (uint32_t b = 0; b < T; ++b) indeg[b] += adj[a][b];
+        for (uint32_t round = 0; round < T; ++round) {
+            int pick = -1;
+            for (uint32_t t = 0; t < T; ++t) if (!gone[t] && indeg[t] == 0) { pick = (int)t; break; }
+            if (pick < 0) return JSV_E_CYCLE;
+            gone[pick] = true;
+            for (uint32_t b = 0; b < T; ++b) if (adj[pick][b]) --indeg[b];
+        }
+    }
+    hp.E = E;
+    hp.src.assign(src, src + E);
+    hp.dst.assign(dst, dst + E);
+    hp.mult.assign(mult, mult + T);
+    hp.capacity = capacity; hp.q = q;
+    hp.have_dag = true;
+    hp.staged = false;
+    if (!hp.have_profile) hp.T = T;
+    return JSV_OK;
+}
+
+// Topological order, shares, A_max, per-task slack: fills hp.graph (device pointers left null).
+int stage_graph(HostProblem& hp)
+{
+    const uint32_t T = hp.T, C = hp.C, V = hp.V;
+    Graph& g = hp.graph;
+    std::memset(&g, 0, sizeof g);
+    g.T = T; g.V = V; g.P = hp.P; g.B = hp.B; g.C = C; g.q = hp.q; g.capacity = hp.capacity;
+    bool adj[MAXT][MAXT] = {};
+    for (uint32_t e = 0; e < hp.E; ++e) adj[hp.src[e]][hp.dst[e]] = true;
+    // Kahn, lowest task id first
+    {
+        int indeg[MAXT] = {};
+        bool gone[MAXT] = {};
+        for (uint32_t a = 0; a < T; ++a) for (uint32_t b = 0; b < T; ++b) indeg[b] += adj[a][b];
+        for (uint32_t p = 0; p < T; ++p) {
+            int pick = -1;
+            for (uint32_t t = 0; t < T; ++t) if (!gone[t] && indeg[t] == 0) { pick = (int)t; break; }
+            if (pick < 0) return JSV_E_CYCLE;
+            gone[pick] = true;
+            g.task_at[p] = (uint8_t)pick;
+            g.pos_of[pick] = (uint8_t)p;
+            for (uint32_t b = 0; b < T; ++b) if (adj[pick][b]) --indeg[b];
+        }
+    }
+    uint64_t sink_total = 0;
+    for (uint32_t t = 0; t < T; ++t) {
+        bool has_succ = false, has_pred = false;
+        for (uint32_t o = 0; o < T; ++o) { has_succ |= adj[t][o]; has_pred |= adj[o][t]; }
+        const uint32_t p = g.pos_of[t];
+        if (!has_succ) { g.sink_mask |= 1u << p; sink_total += hp.mult[t]; }
+        if (!has_pred) g.src_mask |= 1u << p;
+        g.mult[t] = hp.mult[t];
+    }
+    for (uint32_t s = 0; s < T; ++s) {            // s: head of the edges
+        uint64_t in_total = 0;
+        for (uint32_t a = 0; a < T; ++a) if (adj[a][s]) in_total += hp.mult[a];
+        for (uint32_t a = 0; a < T; ++a) {
+            if (!adj[a][s]) continue;
+            const uint32_t pa = g.pos_of[a], ps = g.pos_of[s];
+            g.succ[pa] |= 1u << ps;
+            g.w[pa][ps] = (double)hp.mult[a] / (double)in_total;
+        }
+        if ((g.sink_mask >> g.pos_of[s]) & 1u) g.u[g.pos_of[s]] = (double)hp.mult[s] / (double)sink_total;
+    }
+    // A_max: the backward recursion with every task on its most accurate variant
+    {
+        double H[MAXT] = {};
+        double raw = 0.0;
+        for (int p = (int)T - 1; p >= 0; --p) {
+            const uint32_t t = g.task_at[p];
+            double a = hp.acc[(size_t)t * V];
+            for (uint32_t v = 1; v < V; ++v) a = std::max(a, hp.acc[(size_t)t * V + v]);
+            double hs = 0.0;
+            for (uint32_t s = p + 1; s < T; ++s) if ((g.succ[p] >> s) & 1u) hs = std::fma(g.w[p][s], H[s], hs);
+            H[p] = a * (((g.sink_mask >> p) & 1u) ? g.u[p] : hs);
+            if ((g.src_mask >> p) & 1u) raw += H[p];
+        }
+        g.amax = raw;
+    }
+    // Latency range and, per task, the longest path through it with every other task at its
+    // fastest choice (used by the prune's latency filter).
+    uint64_t lo[MAXT], hi_sum = 0;
+    for (uint32_t t = 0; t < T; ++t) {
+        uint32_t mn = hp.lat[(size_t)t * C], mx = mn;
+        for (uint32_t c = 1; c < C; ++c) { mn = std::min(mn, hp.lat[(size_t)t * C + c]); mx = std::max(mx, hp.lat[(size_t)t * C + c]); }
+        lo[t] = mn; hi_sum += mx;
+    }
+    if ((uint64_t)hp.q * hi_sum > 0xFFFFFFFFull) return JSV_E_OVERFLOW;
+    uint64_t up[MAXT] = {}, down[MAXT] = {};
+    for (uint32_t p = 0; p < T; ++p)
+        for (uint32_t s = p + 1; s < T; ++s)
+            if ((g.succ[p] >> s) & 1u) up[s] = std::max(up[s], up[p] + lo[g.task_at[p]]);
+    for (int p = (int)T - 1; p >= 0; --p)
+        for (uint32_t s = p + 1; s < T; ++s)
+            if ((g.succ[p] >> s) & 1u) down[p] = std::max(down[p], down[s] + lo[g.task_at[s]]);
+    for (uint32_t p = 0; p < T; ++p) g.through[g.task_at[p]] = (uint32_t)(up[p] + down[p]);
+    hp.staged = true;
+    return JSV_OK;
+}
+
+int ensure_device(jsv_ctx* ctx)
+{
+    if (ctx->device_ready) { HIP_TRY(ctx, hipSetDevice(ctx->device)); return JSV_OK; }
+    HIP_TRY(ctx, hipSetDevice(ctx->device));
+    int cus = 0;
+    HIP_TRY(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device));
+    if (cus <= 0) cus = 256;
+    ctx->grid = (uint32_t)cus * 8u;
+    for (auto& e : ctx->ev) HIP_TRY(ctx, hipEventCreate(&e));
+    ctx->device_ready = true;
+    return JSV_OK;
+}
+
+int ensure_pinned(jsv_ctx* ctx, size_t bytes)
+{
+    if (ctx->pinned_bytes >= bytes) return JSV_OK;
+    if (ctx->pinned) { HIP_TRY(ctx, hipHostFree(ctx->pinned)); ctx->pinned = nullptr; ctx->pinned_bytes = 0; }
+    const size_t want = std::max(bytes, (size_t)1 << 16);
+    HIP_TRY(ctx, hipHostMalloc(&ctx->pinned, want, hipHostMallocDefault));
+    ctx->pinned_bytes = want;
+    return JSV_OK;
+}
+
+// Upload graphs and tables of `n` problems as one blob; graph pointers become device addresses.
+int upload_problems(jsv_ctx* ctx, HostProblem* hps, uint32_t n)
+{
+    size_t off = align_up(sizeof(Graph) * n);
+    std::vector<size_t> o_lat(n), o_thr(n), o_acc(n), o_units(n);
+    for (uint32_t k = 0; k < n; ++k) {
+        const HostProblem& hp = hps[k];
+        o_acc[k] = off;   off = align_up(off + hp.acc.size() * sizeof(double));
+        o_lat[k] = off;   off = align_up(off + hp.lat.size() * sizeof(uint32_t));
+        o_thr[k] = off;   off = align_up(off + hp.thr.size() * sizeof(uint32_t));
+        o_units[k] = off; off = align_up(off + hp.units.size() * sizeof(uint32_t));
+    }
+    if (ctx->d_problems_bytes < off) {
+        if (ctx->d_problems) { HIP_TRY(ctx, hipFree(ctx->d_problems)); ctx->d_problems = nullptr; ctx->d_problems_bytes = 0; }
+        HIP_TRY(ctx, hipMalloc(&ctx->d_problems, off));
+        ctx->d_problems_bytes = off;
+    }
+    std::vector<unsigned char> blob(off, 0);
+    unsigned char* base = (unsigned char*)ctx->d_problems;
+    for (uint32_t k = 0; k < n; ++k) {
+        HostProblem& hp = hps[k];
+        Graph g = hp.graph;
+        g.acc = (const double*)(base + o_acc[k]);
+        g.lat = (const uint32_t*)(base + o_lat[k]);
+        g.thr = (const uint32_t*)(base + o_thr[k]);
+        g.units = (const uint32_t*)(base + o_units[k]);
+        std::memcpy(blob.data() + sizeof(Graph) * k, &g, sizeof g);
+        std::memcpy(blob.data() + o_acc[k], hp.acc.data(), hp.acc.size() * sizeof(double));
+        std::memcpy(blob.data() + o_lat[k], hp.lat.data(), hp.lat.size() * sizeof(uint32_t));
+        std::memcpy(blob.data() + o_thr[k], hp.thr.data(), hp.thr.size() * sizeof(uint32_t));
+        std::memcpy(blob.data() + o_units[k], hp.units.data(), hp.units.size() * sizeof(uint32_t));
+    }
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_problems, blob.data(), off, hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));      // blob is a local buffer
+    ctx->n_problems = n;
+    ctx->dirty = false;
+    return JSV_OK;
+}
+
+Layout make_layout(uint32_t n_inst, uint32_t t_max, uint32_t k_max, uint32_t c_max, uint32_t grid,
+                   uint32_t n_eval)
+{
+    Layout L;
+    size_t off = 0;
+    L.inst = off;    off = align_up(off + sizeof(Instance) * n_inst);
+    L.entries = off; off = align_up(off + sizeof(jsv::Entry) * (size_t)n_inst * t_max * k_max);
+    L.rep = off;     off = align_up(off + sizeof(uint32_t) * (size_t)n_inst * t_max * c_max);
+    L.cost = off;    off = align_up(off + sizeof(uint32_t) * (size_t)n_inst * t_max * c_max);
+    L.partial = off; off = align_up(off + sizeof(uint64_t) * (size_t)n_inst * grid);
+    L.results = off; off = align_up(off + sizeof(jsv::ResultRec) * n_inst);
+    L.summary = off; off = align_up(off + sizeof(jsv::SummaryRec));
+    L.eval = off;    // index u64, latency u32, replicas u32*T, cost i32, accuracy f64, mask u8, bad u32
+    off = align_up(off + (size_t)n_eval * (8 + 4 + 4 * MAXT + 4 + 8 + 1) + 6 * ALIGN);
+    L.total = off;
+    return L;
+}
+
+int get_workspace(jsv_ctx* ctx, size_t bytes, unsigned char** out)
+{
+    if (ctx->ws_lent) {
+        if (ctx->ws_lent_bytes < bytes) return JSV_E_WORKSPACE;
+        *out = (unsigned char*)ctx->ws_lent;
+        return JSV_OK;
+    }
+    if (ctx->ws_own_bytes < bytes) {
+        if (ctx->ws_own) { HIP_TRY(ctx, hipFree(ctx->ws_own)); ctx->ws_own = nullptr; ctx->ws_own_bytes = 0; }
+        HIP_TRY(ctx, hipMalloc(&ctx->ws_own, bytes));
+        ctx->ws_own_bytes = bytes;
+    }
+    *out = (unsigned char*)ctx->ws_own;
+    return JSV_OK;
+}
+
+uint32_t k_max_of(const HostProblem& hp, uint32_t cap) { return cap ? std::min(cap, hp.C) : hp.C; }
+
+int check_search_args(const HostProblem& hp, uint32_t demand, double slo_a, uint32_t cap)
+{
+    if (demand == 0) return JSV_E_BADARG;
+    if (!(slo_a == slo_a)) return JSV_E_BADARG;                  // NaN
+    if (cap != 0 && cap < 2 * hp.V) return JSV_E_BADARG;
+    return JSV_OK;
+}
+
+// The whole device pass for n_inst instances whose parameters are in `inst` (host copies).
+int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32_t k_max, uint32_t c_max,
+               jsv_result* out, jsv_summary* summary)
+{
+    const uint32_t n = (uint32_t)inst.size();
+    if (jsv::enumerate_lds_bytes(t_max, k_max) > 64 * 1024 || jsv::prune_lds_bytes(c_max) > 64 * 1024)
+        return JSV_E_BADARG;
+    const Layout L = make_layout(n, t_max, k_max, c_max, ctx->grid, 0);
+    unsigned char* ws = nullptr;
+    int rc = get_workspace(ctx, L.total, &ws);
+    if (rc) return rc;
+    const size_t in_bytes = sizeof(Instance) * n;
+    const size_t out_bytes = sizeof(jsv::ResultRec) * n + sizeof(jsv::SummaryRec);
+    rc = ensure_pinned(ctx, align_up(in_bytes) + out_bytes);
+    if (rc) return rc;
+    unsigned char* pin_in = (unsigned char*)ctx->pinned;
+    unsigned char* pin_out = pin_in + align_up(in_bytes);
+    std::memcpy(pin_in, inst.data(), in_bytes);
+
+    jsv::Plan pl;
+    pl.graphs = (const Graph*)ctx->d_problems;
+    pl.inst = (Instance*)(ws + L.inst);
+    pl.entries = (jsv::Entry*)(ws + L.entries);
+    pl.rep = (uint32_t*)(ws + L.rep);
+    pl.cost = (uint32_t*)(ws + L.cost);
+    pl.partial = (uint64_t*)(ws + L.partial);
+    pl.results = (jsv::ResultRec*)(ws + L.results);
+    pl.summary = (jsv::SummaryRec*)(ws + L.summary);
+    pl.n_inst = n; pl.t_max = t_max; pl.k_max = k_max; pl.c_max = c_max;
+    pl.grid = ctx->grid;
+    const uint64_t lanes = (uint64_t)ctx->grid * jsv::TILE_LANES * 2 / n;
+    pl.lanes_wanted = (uint32_t)std::max<uint64_t>(64, std::min<uint64_t>(lanes, 0x7FFFFFFF));
+
+    hipStream_t st = ctx->stream;
+    HIP_TRY(ctx, hipMemcpyAsync(pl.inst, pin_in, in_bytes, hipMemcpyHostToDevice, st));
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[0], st));
+    HIP_TRY(ctx, jsv::launch_prune_plan_scan(pl, st));
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[1], st));
+    HIP_TRY(ctx, jsv::launch_enumerate(pl, st));
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[2], st));
+    HIP_TRY(ctx, jsv::launch_finalize(pl, st));
+    HIP_TRY(ctx, hipEventRecord(ctx->ev[3], st));
+    HIP_TRY(ctx, hipMemcpyAsync(pin_out, pl.results, sizeof(jsv::ResultRec) * n, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipMemcpyAsync(pin_out + sizeof(jsv::ResultRec) * n, pl.summary, sizeof(jsv::SummaryRec),
+                                hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+
+    jsv::SummaryRec sr;
+    std::memcpy(&sr, pin_out + sizeof(jsv::ResultRec) * n, sizeof sr);
+    if (sr.any_flags & jsv::F_OVERFLOW) return JSV_E_OVERFLOW;
+    std::memcpy(out, pin_out, sizeof(jsv::ResultRec) * n);
+    for (uint32_t k = 0; k < n; ++k) out[k].flags &= jsv::F_TRUNCATED;
+    if (summary) {
+        float ms_all = 0.f, ms_enum = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&ms_all, ctx->ev[0], ctx->ev[3]));
+        HIP_TRY(ctx, hipEventElapsedTime(&ms_enum, ctx->ev[1], ctx->ev[2]));
+        summary->best_level = sr.best_level;
+        summary->max_demand_mrps = sr.max_demand;
+        summary->seconds_device = ms_all * 1e-3;
+        summary->seconds_enumerate = ms_enum * 1e-3;
+    }
+    return JSV_OK;
+}
+
+Instance make_instance(const HostProblem& hp, uint32_t problem, const Search& s)
+{
+    Instance in;
+    std::memset(&in, 0, sizeof in);
+    in.problem = problem;
+    in.demand = s.demand; in.slo_l = s.slo_l; in.cap = s.cap;
+    in.slo_a = s.slo_a;
+    in.slo_raw = s.slo_a * hp.graph.amax;
+    return in;
+}
+
+int ready_single(jsv_ctx* ctx)
+{
+    if (ctx->batch_mode) return JSV_E_STATE;
+    HostProblem& hp = ctx->single;
+    if (!hp.have_profile || !hp.have_dag) return JSV_E_STATE;
+    if (hp.mult.size() != hp.T) return JSV_E_STATE;
+    if (!hp.staged) {
+        const int rc = stage_graph(hp);
+        if (rc) return rc;
+        ctx->dirty = true;
+    }
+    int rc = ensure_device(ctx);
+    if (rc) return rc;
+    if (ctx->dirty) { rc = upload_problems(ctx, &hp, 1); if (rc) return rc; }
+    return JSV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+JSV_API int jsv_create(jsv_ctx** out, int device, void* hip_stream)
+{
+    if (!out) return JSV_E_NULL;
+    if (device < 0) return JSV_E_BADARG;
+    jsv_ctx* ctx = new (std::nothrow) jsv_ctx();
+    if (!ctx) return JSV_E_DEVICE;
+    ctx->device = device;
+    ctx->stream = (hipStream_t)hip_stream;
+    *out = ctx;
+    return JSV_OK;
+}
+
+JSV_API void jsv_destroy(jsv_ctx* ctx)
+{
+    if (!ctx) return;
+    if (ctx->device_ready) {
+        (void)hipSetDevice(ctx->device);
+        (void)hipStreamSynchronize(ctx->stream);
+        for (auto& e : ctx->ev) if (e) (void)hipEventDestroy(e);
+        if (ctx->d_problems) (void)hipFree(ctx->d_problems);
+        if (ctx->ws_own) (void)hipFree(ctx->ws_own);
+        if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+    }
+    delete ctx;
+}
+
+JSV_API int jsv_last_hip_error(const jsv_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+JSV_API const char* jsv_error_string(int code)
+{
+    switch (code) {
+    case JSV_OK: return "ok";
+    case JSV_E_NULL: return "null pointer";
+    case JSV_E_BADARG: return "argument out of range";
+    case JSV_E_CYCLE: return "task graph has a cycle";
+    case JSV_E_OVERFLOW: return "latency, cost or search space does not fit";
+    case JSV_E_STATE: return "profile/graph missing or inconsistent";
+    case JSV_E_WORKSPACE: return "workspace too small";
+    case JSV_E_DEVICE: return "HIP call failed";
+    default: return "unknown error";
+    }
+}
+
+JSV_API size_t jsv_workspace_bytes(const jsv_ctx* ctx, uint32_t n_levels, uint32_t prune_cap)
+{
+    if (!ctx || n_levels == 0) return 0;
+    uint32_t t_max = 0, k_max = 0, c_max = 0;
+    if (ctx->batch_mode) {
+        for (size_t k = 0; k < ctx->batch.size(); ++k) {
+            t_max = std::max(t_max, ctx->batch[k].T);
+            c_max = std::max(c_max, ctx->batch[k].C);
+            k_max = std::max(k_max, k_max_of(ctx->batch[k], ctx->batch_search[k].cap));
+        }
+        n_levels = (uint32_t)ctx->batch.size();
+    } else {
+        if (!ctx->single.have_profile) return 0;
+        t_max = ctx->single.T; c_max = ctx->single.C; k_max = k_max_of(ctx->single, prune_cap);
+    }
+    const uint32_t grid = ctx->grid ? ctx->grid : 256u * 8u;
+    return make_layout(n_levels, t_max, k_max, c_max, grid, 0).total;
+}
+
+JSV_API int jsv_set_workspace(jsv_ctx* ctx, void* device_ptr, size_t bytes)
+{
+    if (!ctx) return JSV_E_NULL;
+    if (device_ptr && ((uintptr_t)device_ptr % ALIGN) != 0) return JSV_E_BADARG;
+    ctx->ws_lent = device_ptr;
+    ctx->ws_lent_bytes = device_ptr ? bytes : 0;
+    return JSV_OK;
+}
+
+JSV_API int jsv_load_profile(jsv_ctx* ctx, uint32_t T, uint32_t V, uint32_t P, uint32_t B,
+                     const uint32_t* units, const uint32_t* batch,
+                     const uint32_t* latency_us, const uint32_t* thr_mrps, const double* accuracy)
+{
+    if (!ctx) return JSV_E_NULL;
+    HostProblem hp = ctx->batch_mode ? HostProblem() : ctx->single;
+    const int rc = check_profile(T, V, P, B, units, batch, latency_us, thr_mrps, accuracy, hp);
+    if (rc) return rc;
+    if (hp.have_dag && hp.mult.size() != T) { hp.have_dag = false; }   // a graph of another size is dropped
+    ctx->single = std::move(hp);
+    ctx->batch_mode = false;
+    ctx->batch.clear(); ctx->batch_search.clear();
+    ctx->dirty = true;
+    return JSV_OK;
+}
+
+JSV_API int jsv_set_dag(jsv_ctx* ctx, uint32_t T, uint32_t E, const uint16_t* src, const uint16_t* dst,
+                const uint32_t* demand_mult_milli, uint32_t capacity_units, uint32_t queue_factor)
+{
+    if (!ctx) return JSV_E_NULL;
+    if (ctx->batch_mode) { ctx->single = HostProblem(); ctx->batch_mode = false; ctx->batch.clear(); ctx->batch_search.clear(); }
+    HostProblem& hp = ctx->single;
+    if (hp.have_profile && hp.T != T) return JSV_E_STATE;
+    HostProblem tmp = hp;
+    const int rc = check_dag(T, E, src, dst, demand_mult_milli, capacity_units, queue_factor, tmp);
+    if (rc) return rc;
+    if (tmp.have_profile) {                       // stage now so that range errors surface here
+        const int rs = stage_graph(tmp);
+        if (rs) return rs;
+    }
+    hp = std::move(tmp);
+    ctx->dirty = true;
+    return JSV_OK;
+}
+
+JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_levels,
+               uint32_t slo_latency_us, double slo_accuracy, uint32_t prune_cap,
+               jsv_result* out, jsv_summary* summary)
+{
+    if (!ctx || !demand_mrps || !out) return JSV_E_NULL;
+    if (n_levels == 0) return JSV_E_BADARG;
+    if (ctx->batch_mode || !ctx->single.have_profile || !ctx->single.have_dag) return JSV_E_STATE;
+    for (uint32_t l = 0; l < n_levels; ++l) {
+        const int rc = check_search_args(ctx->single, demand_mrps[l], slo_accuracy, prune_cap);
+        if (rc) return rc;
+    }
+    int rc = ready_single(ctx);
+    if (rc) return rc;
+    const HostProblem& hp = ctx->single;
+    std::vector<Instance> inst(n_levels);
+    for (uint32_t l = 0; l < n_levels; ++l)
+        inst[l] = make_instance(hp, 0, Search{demand_mrps[l], slo_latency_us, prune_cap, slo_accuracy});
+    return run_search(ctx, inst, hp.T, k_max_of(hp, prune_cap), hp.C, out, summary);
+}
+
+JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_latency_us,
+                        double slo_accuracy, uint32_t prune_cap,
+                        const uint64_t* index, uint32_t n,
+                        uint32_t* latency_us, uint32_t* replicas, int32_t* cost,
+                        double* accuracy, uint8_t* mask)
+{
+    if (!ctx || !index || !latency_us || !replicas || !cost || !accuracy || !mask) return JSV_E_NULL;
+    if (ctx->batch_mode || !ctx->single.have_profile || !ctx->single.have_dag) return JSV_E_STATE;
+    int rc = check_search_args(ctx->single, demand_mrps, slo_accuracy, prune_cap);
+    if (rc) return rc;
+    if (n == 0) return JSV_OK;
+    rc = ready_single(ctx);
+    if (rc) return rc;
+    const HostProblem& hp = ctx->single;
+    const uint32_t T = hp.T, k_max = k_max_of(hp, prune_cap);
+    if (jsv::prune_lds_bytes(hp.C) > 64 * 1024) return JSV_E_BADARG;
+    const Layout L = make_layout(1, T, k_max, hp.C, ctx->grid, n);
+    unsigned char* ws = nullptr;
+    rc = get_workspace(ctx, L.total, &ws);
+    if (rc) return rc;
+    Instance in = make_instance(hp, 0, Search{demand_mrps, slo_latency_us, prune_cap, slo_accuracy});
+
+    jsv::Plan pl;
+    pl.graphs = (const Graph*)ctx->d_problems;
+    pl.inst = (Instance*)(ws + L.inst);
+    pl.entries = (jsv::Entry*)(ws + L.entries);
+    pl.rep = (uint32_t*)(ws + L.rep);
+    pl.cost = (uint32_t*)(ws + L.cost);
+    pl.partial = (uint64_t*)(ws + L.partial);
+    pl.results = (jsv::ResultRec*)(ws + L.results);
+    pl.summary = (jsv::SummaryRec*)(ws + L.summary);
+    pl.n_inst = 1; pl.t_max = T; pl.k_max = k_max; pl.c_max = hp.C;
+    pl.grid = ctx->grid; pl.lanes_wanted = 64;
+
+    unsigned char* e = ws + L.eval;
+    uint64_t* d_index = (uint64_t*)e;          e += align_up(sizeof(uint64_t) * n);
+    double* d_acc = (double*)e;                e += align_up(sizeof(double) * n);
+    uint32_t* d_lat = (uint32_t*)e;            e += align_up(sizeof(uint32_t) * n);
+    int32_t* d_cost = (int32_t*)e;             e += align_up(sizeof(int32_t) * n);
+    uint32_t* d_rep = (uint32_t*)e;            e += align_up(sizeof(uint32_t) * (size_t)n * T);
+    uint8_t* d_mask = (uint8_t*)e;             e += align_up(n);
+    uint32_t* d_bad = (uint32_t*)e;
+
+    hipStream_t st = ctx->stream;
+    uint32_t bad = 0;
+    HIP_TRY(ctx, hipMemcpyAsync(pl.inst, &in, sizeof in, hipMemcpyHostToDevice, st));
+    HIP_TRY(ctx, hipMemcpyAsync(d_index, index, sizeof(uint64_t) * n, hipMemcpyHostToDevice, st));
+    HIP_TRY(ctx, hipMemcpyAsync(d_bad, &bad, sizeof bad, hipMemcpyHostToDevice, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));      // sources are caller / stack memory
+    HIP_TRY(ctx, jsv::launch_prune_plan_scan(pl, st));
+    HIP_TRY(ctx, jsv::launch_eval(pl, d_index, n, d_lat, d_rep, d_cost, d_acc, d_mask, d_bad, st));
+    Instance back;
+    HIP_TRY(ctx, hipMemcpyAsync(&back, pl.inst, sizeof back, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipMemcpyAsync(&bad, d_bad, sizeof bad, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipMemcpyAsync(latency_us, d_lat, sizeof(uint32_t) * n, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipMemcpyAsync(replicas, d_rep, sizeof(uint32_t) * (size_t)n * T, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipMemcpyAsync(cost, d_cost, sizeof(int32_t) * n, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipMemcpyAsync(accuracy, d_acc, sizeof(double) * n, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipMemcpyAsync(mask, d_mask, n, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    if (back.flags & jsv::F_OVERFLOW) return JSV_E_OVERFLOW;
+    if (bad) return JSV_E_BADARG;
+    return JSV_OK;
+}
+
+JSV_API int jsv_get_pruned(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_latency_us,
+                   uint32_t prune_cap, uint32_t task,
+                   uint16_t* choice_ids, uint32_t* K, uint32_t* truncated)
+{
+    if (!ctx || !choice_ids || !K || !truncated) return JSV_E_NULL;
+    if (ctx->batch_mode || !ctx->single.have_profile || !ctx->single.have_dag) return JSV_E_STATE;
+    if (task >= ctx->single.T) return JSV_E_BADARG;
+    int rc = check_search_args(ctx->single, demand_mrps, 0.0, prune_cap);
+    if (rc) return rc;
+    rc = ready_single(ctx);
+    if (rc) return rc;
+    const HostProblem& hp = ctx->single;
+    const uint32_t T = hp.T, k_max = k_max_of(hp, prune_cap);
+    if (jsv::prune_lds_bytes(hp.C) > 64 * 1024) return JSV_E_BADARG;
+    const Layout L = make_layout(1, T, k_max, hp.C, ctx->grid, 0);
+    unsigned char* ws = nullptr;
+    rc = get_workspace(ctx, L.total, &ws);
+    if (rc) return rc;
+    Instance in = make_instance(hp, 0, Search{demand_mrps, slo_latency_us, prune_cap, 0.0});
+    jsv::Plan pl;
+    pl.graphs = (const Graph*)ctx->d_problems;
+    pl.inst = (Instance*)(ws + L.inst);
+    pl.entries = (jsv::Entry*)(ws + L.entries);
+    pl.rep = (uint32_t*)(ws + L.rep);
+    pl.cost = (uint32_t*)(ws + L.cost);
+    pl.partial = (uint64_t*)(ws + L.partial);
+    pl.results = (jsv::ResultRec*)(ws + L.results);
+    pl.summary = (jsv::SummaryRec*)(ws + L.summary);
+    pl.n_inst = 1; pl.t_max = T; pl.k_max = k_max; pl.c_max = hp.C;
+    pl.grid = ctx->grid; pl.lanes_wanted = 64;
+    hipStream_t st = ctx->stream;
+    HIP_TRY(ctx, hipMemcpyAsync(pl.inst, &in, sizeof in, hipMemcpyHostToDevice, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    HIP_TRY(ctx, jsv::launch_prune_plan_scan(pl, st));
+    Instance back;
+    std::vector<jsv::Entry> ent(k_max);
+    HIP_TRY(ctx, hipMemcpyAsync(&back, pl.inst, sizeof back, hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipMemcpyAsync(ent.data(), pl.entries + (size_t)task * k_max, sizeof(jsv::Entry) * k_max,
+                                hipMemcpyDeviceToHost, st));
+    HIP_TRY(ctx, hipStreamSynchronize(st));
+    const uint32_t k = back.K[task];
+    for (uint32_t d = 0; d < k; ++d) choice_ids[d] = (uint16_t)ent[d].choice;
+    *K = k;
+    *truncated = (back.trunc_mask >> task) & 1u;
+    return JSV_OK;
+}
+
+JSV_API int jsv_load_batch(jsv_ctx* ctx, const jsv_problem* problems, uint32_t n, uint32_t* bad)
+{
+    if (!ctx || !problems) return JSV_E_NULL;
+    if (n == 0) return JSV_E_BADARG;
+    std::vector<HostProblem> hps(n);
+    std::vector<Search> ss(n);
+    for (uint32_t k = 0; k < n; ++k) {
+        const jsv_problem& p = problems[k];
+        if (bad) *bad = k;
+        int rc = check_profile(p.T, p.V, p.P, p.B, p.units, p.batch, p.latency_us, p.thr_mrps, p.accuracy, hps[k]);
+        if (rc) return rc;
+        rc = check_dag(p.T, p.E, p.src, p.dst, p.demand_mult_milli, p.capacity_units, p.queue_factor, hps[k]);
+        if (rc) return rc;
+        rc = stage_graph(hps[k]);
+        if (rc) return rc;
+        rc = check_search_args(hps[k], p.demand_mrps, p.slo_accuracy, p.prune_cap);
+        if (rc) return rc;
+        ss[k] = Search{p.demand_mrps, p.slo_latency_us, p.prune_cap, p.slo_accuracy};
+    }
+    if (bad) *bad = 0;
+    ctx->batch.swap(hps);
+    ctx->batch_search.swap(ss);
+    ctx->batch_mode = true;
+    ctx->single = HostProblem();
+    ctx->dirty = true;
+    int rc = ensure_device(ctx);
+    if (rc) return rc;
+    return upload_problems(ctx, ctx->batch.data(), n);
+}
+
+JSV_API int jsv_search_loaded_batch(jsv_ctx* ctx, jsv_result* out, jsv_summary* summary)
+{
+    if (!ctx || !out) return JSV_E_NULL;
+    if (!ctx->batch_mode || ctx->batch.empty()) return JSV_E_STATE;
+    int rc = ensure_device(ctx);
+    if (rc) return rc;
+    if (ctx->dirty) { rc = upload_problems(ctx, ctx->batch.data(), (uint32_t)ctx->batch.size()); if (rc) return rc; }
+    const uint32_t n = (uint32_t)ctx->batch.size();
+    std::vector<Instance> inst(n);
+    uint32_t t_max = 0, k_max = 0, c_max = 0;
+    for (uint32_t k = 0; k < n; ++k) {
+        inst[k] = make_instance(ctx->batch[k], k, ctx->batch_search[k]);
+        t_max = std::max(t_max, ctx->batch[k].T);
+        c_max = std::max(c_max, ctx->batch[k].C);
+        k_max = std::max(k_max, k_max_of(ctx->batch[k], ctx->batch_search[k].cap));
+    }
+    return run_search(ctx, inst, t_max, k_max, c_max, out, summary);
+}
+
+JSV_API int jsv_search_batch(jsv_ctx* ctx, const jsv_problem* problems, uint32_t n, jsv_result* out)
+{
+    const int rc = jsv_load_batch(ctx, problems, n, nullptr);
+    if (rc) return rc;
+    return jsv_search_loaded_batch(ctx, out, nullptr);
+}
+
+}  // extern "C"

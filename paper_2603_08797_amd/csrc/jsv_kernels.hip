@@ -1,0 +1,688 @@
+// HIP kernels of the allocation search, written for gfx950 (CDNA4, wave64).
+//
+//   prune_kernel      replicas and cost of every (task, choice) at every level
+//                     (Eq. 5-7), then the per-task prune: latency filter, exact
+//                     dominance, cap thinning, compaction.
+//   plan_kernel       index strides, packed keys, tile geometry per instance.
+//   scan_kernel       exclusive scan of the tile counts.
+//   enumerate_kernel  every candidate scored and masked (Eq. 3, 8, 11-13) and
+//                     reduced to the cheapest feasible one per lane / wave / block.
+//   finalize_kernel   grid-level minimum, winner decoded and rescored, summary.
+//   eval_kernel       explicit candidates scored one per thread (parity aid).
+//
+// The enumeration is VALU-bound: per candidate one u32 compare, one fp64 fma and
+// compare, one 64-bit add, one 64-bit compare and a select; there is no dense
+// contraction anywhere, so no MFMA.  Table entries of the tasks looped inside a
+// lane are wave-uniform and are fetched with scalar loads (constant address
+// space) so that they feed the vector ALU as scalar operands; the entries that
+// differ per lane are gathered from a copy of the instance's tables in LDS.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "jsv_device.h"
+#include "jsv_launch.h"
+
+namespace jsv {
+
+#define JSV_CONST __attribute__((address_space(4)))
+
+template <typename T>
+__device__ __forceinline__ const T JSV_CONST* as_uniform(const T* p)
+{
+    return (const T JSV_CONST*)(uintptr_t)p;
+}
+
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
+
+// ---- wave64 / block minimum of a u64 key -----------------------------------------------
+// Rows of 16 lanes are reduced with DPP (two quad permutes, half-row mirror, row
+// mirror), the two 32-lane halves with ds_swizzle, the rest with readlane.
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_min(uint64_t v)
+{
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    uint32_t olo = (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)lo, CTRL, 0xF, 0xF, false);
+    uint32_t ohi = (uint32_t)__builtin_amdgcn_update_dpp((int)hi, (int)hi, CTRL, 0xF, 0xF, false);
+    return umin64(v, ((uint64_t)ohi << 32) | olo);
+}
+
+__device__ __forceinline__ uint64_t wave_min(uint64_t v)
+{
+    v = dpp_min<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_min<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_min<0x141>(v);   // row_half_mirror
+    v = dpp_min<0x140>(v);   // row_mirror: every lane holds its row's minimum
+    {                        // lanes i and i^16 of each 32-lane half
+        uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+        uint32_t olo = (uint32_t)__builtin_amdgcn_ds_swizzle((int)lo, 0x401F);
+        uint32_t ohi = (uint32_t)__builtin_amdgcn_ds_swizzle((int)hi, 0x401F);
+        v = umin64(v, ((uint64_t)ohi << 32) | olo);
+    }
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    uint64_t a = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, 0) << 32) |
+                 (uint32_t)__builtin_amdgcn_readlane((int)lo, 0);
+    uint64_t b = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, 32) << 32) |
+                 (uint32_t)__builtin_amdgcn_readlane((int)lo, 32);
+    return umin64(a, b);
+}
+
+// Minimum over a 256-thread block; the result is valid in thread 0.
+__device__ __forceinline__ uint64_t block_min(uint64_t v, uint64_t* s_red)
+{
+    v = wave_min(v);
+    const uint32_t wave = threadIdx.x >> 6;
+    __syncthreads();                       // s_red may still be read from a previous use
+    if ((threadIdx.x & 63) == 0) s_red[wave] = v;
+    __syncthreads();
+    return umin64(umin64(s_red[0], s_red[1]), umin64(s_red[2], s_red[3]));
+}
+
+// ---- prune ------------------------------------------------------------------------------
+// One block per (instance, task).  Dynamic LDS: per choice lat, cost, rep (u32),
+// acc (f64), two flag bytes.
+__global__ void __launch_bounds__(256) prune_kernel(Plan pl)
+{
+    const uint32_t i = blockIdx.x / pl.t_max;
+    const uint32_t t = blockIdx.x % pl.t_max;
+    Instance* in = pl.inst + i;
+    const Graph* g = pl.graphs + in->problem;
+    if (t >= g->T) return;
+    const uint32_t C = g->C, V = g->V, PB = g->P * g->B, Bn = g->B, Pn = g->P;
+    const uint32_t cap = in->cap;
+    const uint32_t tid = threadIdx.x;
+
+    extern __shared__ unsigned char smem[];
+    double*   s_acc  = (double*)smem;
+    uint32_t* s_lat  = (uint32_t*)(s_acc + C);
+    uint32_t* s_cost = s_lat + C;
+    uint32_t* s_rep  = s_cost + C;
+    uint8_t*  s_a    = (uint8_t*)(s_rep + C);    // alive after the latency filter
+    uint8_t*  s_k    = s_a + C;                  // kept
+    __shared__ uint32_t s_left, s_flags;
+    if (tid == 0) { s_left = 0; s_flags = 0; }
+
+    // Eq. 5-7: demand at the task, replicas (at least one), cost in partition units
+    const uint64_t need = (uint64_t)in->demand * g->mult[t];            // micro-requests / s
+    const uint64_t budget = (uint64_t)in->slo_l;
+    const uint64_t through = g->through[t];
+    uint32_t* g_rep  = pl.rep  + ((size_t)i * pl.t_max + t) * pl.c_max;
+    uint32_t* g_cost = pl.cost + ((size_t)i * pl.t_max + t) * pl.c_max;
+    uint32_t my_flags = 0;
+    for (uint32_t c = tid; c < C; c += blockDim.x) {
+        const uint32_t lat = g->lat[(size_t)t * C + c];
+        const uint64_t per = 1000ull * g->thr[(size_t)t * C + c];
+        uint64_t rep = (need + per - 1) / per;
+        if (rep < 1) rep = 1;
+        uint64_t cost = rep * g->units[(c / Bn) % Pn];
+        if (rep > 0xFFFFFFFFull || cost > 0x7FFFFFFFull) { my_flags |= F_OVERFLOW; rep = 1; cost = 1; }
+        s_lat[c] = lat; s_cost[c] = (uint32_t)cost; s_rep[c] = (uint32_t)rep;
+        s_acc[c] = g->acc[(size_t)t * V + c / PB];
+        g_rep[c] = (uint32_t)rep; g_cost[c] = (uint32_t)cost;
+        // (a) can this choice meet the latency SLO with every other task at its fastest?
+        s_a[c] = cap == 0 ? 1 : ((uint64_t)g->q * ((uint64_t)lat + through) <= budget);
+    }
+    __syncthreads();
+
+    // (b) exact dominance on (latency down, accuracy up, cost down); ties keep the lowest id
+    uint32_t kept_here = 0;
+    for (uint32_t c = tid; c < C; c += blockDim.x) {
+        uint8_t keep = s_a[c];
+        if (keep && cap != 0) {
+            const uint32_t l = s_lat[c], k = s_cost[c];
+            const double a = s_acc[c];
+            for (uint32_t o = 0; o < C; ++o) {
+                if (o == c || !s_a[o]) continue;
+                const uint32_t l2 = s_lat[o], k2 = s_cost[o];
+                const double a2 = s_acc[o];
+                if (l2 <= l && a2 >= a && k2 <= k) {
+                    const bool strict = (l2 < l) || (a2 > a) || (k2 < k);
+                    if (strict || o < c) { keep = 0; break; }
+                }
+            }
+        }
+        s_k[c] = keep;
+        kept_here += keep;
+    }
+    atomicAdd(&s_left, kept_here);
+    __syncthreads();
+
+    // (c) cap thinning: each variant keeps floor(cap/V) choices evenly spaced by latency rank
+    if (cap != 0 && s_left > cap) {
+        my_flags |= F_TRUNCATED;
+        const uint32_t quota = cap / V;
+        for (uint32_t c = tid; c < C; c += blockDim.x) {
+            uint8_t keep = s_k[c];
+            if (keep) {
+                const uint32_t v = c / PB, l = s_lat[c];
+                uint32_t n = 0, rank = 0;
+                for (uint32_t o = v * PB; o < (v + 1) * PB; ++o) {
+                    if (!s_k[o]) continue;
+                    ++n;
+                    if (s_lat[o] < l || (s_lat[o] == l && o < c)) ++rank;
+                }
+                if (n > quota) {
+                    // is rank == floor(j*(n-1)/(quota-1)) for some j < quota ?
+                    const uint32_t j = (rank * (quota - 1) + (n - 2)) / (n - 1);
+                    keep = (j < quota) && ((j * (n - 1)) / (quota - 1) == rank);
+                }
+            }
+            s_a[c] = keep;
+        }
+        __syncthreads();
+        for (uint32_t c = tid; c < C; c += blockDim.x) s_k[c] = s_a[c];
+        __syncthreads();
+    }
+
+    // (d) compaction in ascending choice id
+    Entry* out = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
+    uint32_t total_here = 0;
+    for (uint32_t c = tid; c < C; c += blockDim.x) {
+        if (!s_k[c]) continue;
+        uint32_t pos = 0;
+        for (uint32_t o = 0; o < c; ++o) pos += s_k[o];
+        Entry e;
+        e.lat = s_lat[c]; e.cost = s_cost[c]; e.acc = s_acc[c]; e.key = 0;
+        e.rep = s_rep[c]; e.choice = c;
+        out[pos] = e;
+        ++total_here;
+    }
+    if (tid == 0) s_left = 0;
+    __syncthreads();
+    atomicAdd(&s_left, total_here);
+    if (my_flags) atomicOr(&s_flags, my_flags);
+    __syncthreads();
+    if (tid == 0) {
+        in->K[t] = s_left;
+        uint32_t f = s_flags | (s_left == 0 ? F_EMPTY : 0);
+        if (f) atomicOr(&in->flags, f);
+        if (f & F_TRUNCATED) atomicOr(&in->trunc_mask, 1u << t);
+    }
+}
+
+// ---- plan -------------------------------------------------------------------------------
+// One block per instance: strides of the caller's index order, key packing, choice
+// of how many positions a lane loops over, tile geometry, reset of the partials.
+__global__ void __launch_bounds__(256) plan_kernel(Plan pl)
+{
+    const uint32_t i = blockIdx.x, tid = threadIdx.x;
+    Instance* in = pl.inst + i;
+    const Graph* g = pl.graphs + in->problem;
+    const uint32_t T = g->T;
+    __shared__ uint32_t s_maxcost[MAXT];
+    __shared__ uint32_t s_bits;
+    if (tid < MAXT) s_maxcost[tid] = 0;
+    __syncthreads();
+    for (uint32_t t = 0; t < T; ++t) {
+        const Entry* e = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
+        uint32_t m = 0;
+        for (uint32_t d = tid; d < in->K[t]; d += blockDim.x) m = umax(m, e[d].cost);
+        if (m) atomicMax(&s_maxcost[t], m);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint64_t space = 1, cost_bound = 0;
+        bool over = false;
+        for (uint32_t t = 0; t < T; ++t) {
+            in->stride[t] = space;
+            const uint64_t k = in->K[t];
+            if (k != 0 && __umul64hi(space, k) != 0) over = true;
+            space *= k;
+            cost_bound += s_maxcost[t];
+        }
+        if (space >> 63) over = true;
+        uint32_t idx_bits = 0;
+        while (idx_bits < 63 && (space - 1) >> idx_bits) ++idx_bits;     // bits of space-1
+        if (space <= 1) idx_bits = 0;
+        uint32_t cost_bits = 0;
+        while (cost_bits < 63 && cost_bound >> cost_bits) ++cost_bits;
+        if (cost_bound > 0x7FFFFFFFull || idx_bits + cost_bits > 63) over = true;
+        if (over) { space = 0; atomicOr(&in->flags, F_OVERFLOW); }
+        in->space = space;
+        in->idx_bits = idx_bits;
+
+        // how many leading positions a lane loops over, and the tile geometry
+        uint32_t Kp[MAXT];
+        for (uint32_t p = 0; p < T; ++p) Kp[p] = in->K[g->task_at[p]];
+        uint32_t n_in = 1;
+        uint64_t s_out = 0;
+        const uint32_t n_top = T < 3 ? T : 3;
+        if (space != 0) {
+            for (uint32_t n = n_top; n >= 1; --n) {
+                uint64_t so = 1;
+                for (uint32_t p = n; p < T; ++p) so *= Kp[p];
+                if (n == 1 || (so >= 64 && (so >= pl.lanes_wanted || so * Kp[n - 1] >= pl.lanes_wanted))) { n_in = n; s_out = so; break; }
+            }
+        }
+        uint32_t chunk = 1, n_chunks = 0, n_groups = 0;
+        if (space != 0) {
+            uint64_t inner = 1;
+            for (uint32_t p = 0; p + 1 < n_in; ++p) inner *= Kp[p];
+            const uint32_t Ko = Kp[n_in - 1];
+            uint64_t c = s_out >= pl.lanes_wanted ? Ko : (s_out * Ko) / pl.lanes_wanted;   // digits per tile that still
+            if (c > Ko) c = Ko;                                          // leave lanes_wanted lanes busy
+            const uint64_t c_min = (64 + inner - 1) / inner;             // at least 64 candidates per lane
+            if (c < c_min) c = c_min;
+            if (c > Ko) c = Ko;
+            if (c < 1) c = 1;
+            chunk = (uint32_t)c;
+            n_chunks = (Ko + chunk - 1) / chunk;
+            const uint64_t ng = (s_out + TILE_LANES - 1) / TILE_LANES;
+            if (ng * n_chunks > 0x7FFFFFFFull) { atomicOr(&in->flags, F_OVERFLOW); n_chunks = 0; }
+            else n_groups = (uint32_t)ng;
+        }
+        in->n_in = n_in; in->s_out = s_out; in->chunk = chunk;
+        in->n_chunks = n_chunks; in->n_groups = n_groups;
+        in->tiles = n_groups * n_chunks;
+        s_bits = idx_bits;
+    }
+    __syncthreads();
+    // packed keys: (cost << idx_bits) | digit * stride
+    const uint32_t idx_bits = s_bits;
+    for (uint32_t t = 0; t < T; ++t) {
+        Entry* e = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
+        const uint64_t stride = in->stride[t];
+        for (uint32_t d = tid; d < in->K[t]; d += blockDim.x)
+            e[d].key = ((uint64_t)e[d].cost << idx_bits) | ((uint64_t)d * stride);
+    }
+    for (uint32_t b = tid; b < pl.grid; b += blockDim.x) pl.partial[(size_t)i * pl.grid + b] = NO_KEY;
+}
+
+// Single block: exclusive scan of the tile counts, total, counters reset.
+__global__ void __launch_bounds__(256) scan_kernel(Plan pl)
+{
+    __shared__ uint64_t s_sum[256];
+    const uint32_t tid = threadIdx.x, n = pl.n_inst;
+    const uint32_t per = (n + 255) / 256;
+    const uint32_t lo = tid * per, hi = (lo + per < n) ? lo + per : n;
+    uint64_t sum = 0;
+    for (uint32_t k = lo; k < hi; ++k) sum += pl.inst[k].tiles;
+    s_sum[tid] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        uint64_t run = 0;
+        for (uint32_t k = 0; k < 256; ++k) { const uint64_t v = s_sum[k]; s_sum[k] = run; run += v; }
+        pl.summary->total_tiles = run;
+        pl.summary->done_count = 0;
+        pl.summary->any_flags = 0;
+        pl.summary->best_level = -1;
+        pl.summary->max_demand = 0;
+    }
+    __syncthreads();
+    uint64_t run = s_sum[tid];
+    for (uint32_t k = lo; k < hi; ++k) { pl.inst[k].tile_begin = run; run += pl.inst[k].tiles; }
+}
+
+// ---- enumeration ------------------------------------------------------------------------
+// State a lane carries into the loops over positions 0..NIN-1: for each of those
+// positions the part of its recursion that comes from positions >= NIN, plus what
+// the sources among the outer positions already contribute.
+struct LaneState {
+    uint32_t nxt[3];    // max tail over successors seen so far
+    double   hin[3];    // sum of w * H over successors seen so far
+    uint32_t smax;      // max tail over sources seen so far
+    double   sacc;      // sum of H over sources seen so far
+    uint64_t key;       // sum of keys of the fixed positions
+};
+
+struct Uniforms {       // wave-uniform facts about positions 0..2
+    const Entry JSV_CONST* tab[3];
+    uint32_t K[3];
+    double   u[3];      // sink share
+    bool     sink[3], src[3];
+    bool     e01, e02, e12;   // edge from position a to position b
+    double   w01, w02, w12;
+    uint32_t sloq;      // floor(SLO_l / q)
+    double   slo_raw;   // SLO_a * A_max
+};
+
+// Fix position P (a wave-uniform entry e) and push its contribution down.
+template <int P>
+__device__ __forceinline__ LaneState fix_position(const LaneState& s, const Uniforms& U,
+                                                  uint32_t lat, double acc, uint64_t key)
+{
+    LaneState r = s;
+    const uint32_t tail = lat + s.nxt[P];
+    const double H = acc * (U.sink[P] ? U.u[P] : s.hin[P]);
+    r.key = s.key + key;
+    if (U.src[P]) { r.smax = umax(s.smax, tail); r.sacc = s.sacc + H; }
+    if constexpr (P == 2) {
+        if (U.e12) { r.nxt[1] = umax(s.nxt[1], tail); r.hin[1] = __builtin_fma(U.w12, H, s.hin[1]); }
+        if (U.e02) { r.nxt[0] = umax(s.nxt[0], tail); r.hin[0] = __builtin_fma(U.w02, H, s.hin[0]); }
+    }
+    if constexpr (P == 1) {
+        if (U.e01) { r.nxt[0] = umax(s.nxt[0], tail); r.hin[0] = __builtin_fma(U.w01, H, s.hin[0]); }
+    }
+    return r;
+}
+
+// Innermost loop: position 0 (always a source).  Every candidate gets its latency
+// compare (Eq. 3), its accuracy (Eq. 11-12) and compare (Eq. 13), its key, and
+// the running minimum.  The capacity bound (Eq. 8) is applied to the minimum
+// afterwards: the cheapest candidate meeting Eq. 3 and 13 exceeds S_avail exactly
+// when every such candidate does.
+__device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
+                                       bool live, uint64_t& best)
+{
+    const bool open = live && s.smax <= U.sloq && s.nxt[0] <= U.sloq;
+    const uint32_t thr = open ? U.sloq - s.nxt[0] : 0u;      // latencies are >= 1
+    const double cx = U.sink[0] ? U.u[0] : s.hin[0];
+    const Entry JSV_CONST* tx = U.tab[0];
+    for (uint32_t d = lo; d < hi; ++d) {
+        const uint32_t lat = tx[d].lat;
+        const double acc = tx[d].acc;
+        const uint64_t k = s.key + tx[d].key;
+        const bool ok = (lat <= thr) & (__builtin_fma(acc, cx, s.sacc) >= U.slo_raw);
+        best = (ok && k < best) ? k : best;
+    }
+}
+
+__device__ __forceinline__ void loop_y(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
+                                       bool live, uint64_t& best)
+{
+    const Entry JSV_CONST* ty = U.tab[1];
+    for (uint32_t d = lo; d < hi; ++d) {
+        const LaneState s1 = fix_position<1>(s, U, ty[d].lat, ty[d].acc, ty[d].key);
+        loop_x(s1, U, 0, U.K[0], live, best);
+    }
+}
+
+__device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
+                                       bool live, uint64_t& best)
+{
+    const Entry JSV_CONST* tz = U.tab[2];
+    for (uint32_t d = lo; d < hi; ++d) {
+        const LaneState s2 = fix_position<2>(s, U, tz[d].lat, tz[d].acc, tz[d].key);
+        loop_y(s2, U, 0, U.K[1], live, best);
+    }
+}
+
+// One tile: 256 lanes, each a different combination of the positions >= NIN
+// (decoded from the mixed-radix outer index), all looping over the same digits of
+// positions < NIN.
+template <int NIN>
+__device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instance JSV_CONST* in,
+                                         const Entry JSV_CONST* tab, const Entry* s_tab, uint32_t k_max,
+                                         uint64_t group, uint32_t chunk_id, uint64_t& best)
+{
+    const uint32_t T = g->T;
+    uint64_t o = group * TILE_LANES + threadIdx.x;
+    const bool live = o < in->s_out;
+    if (!live) o = 0;
+
+    // digits of the outer positions, position NIN fastest
+    uint32_t dig[MAXT];
+    if (in->s_out <= 0xFFFFFFFFull) {
+        uint32_t o32 = (uint32_t)o;
+#pragma unroll
+        for (int p = NIN; p < MAXT; ++p)
+            if (p < (int)T) { const uint32_t K = in->K[g->task_at[p]]; dig[p] = o32 % K; o32 /= K; }
+    } else {
+#pragma unroll
+        for (int p = NIN; p < MAXT; ++p)
+            if (p < (int)T) { const uint32_t K = in->K[g->task_at[p]]; dig[p] = (uint32_t)(o % K); o /= K; }
+    }
+
+    // backward recursion over the outer positions, entries gathered from LDS
+    uint32_t tail[MAXT];
+    double H[MAXT];
+    LaneState st;
+    st.smax = 0; st.sacc = 0.0; st.key = 0;
+    const uint32_t src_mask = g->src_mask, sink_mask = g->sink_mask;
+#pragma unroll
+    for (int p = MAXT - 1; p >= NIN; --p) {
+        if (p < (int)T) {
+            const Entry* e = s_tab + (uint32_t)g->task_at[p] * k_max + dig[p];
+            const uint32_t lat = e->lat;
+            const double acc = e->acc;
+            st.key += e->key;
+            uint32_t mx = 0;
+            double hs = 0.0;
+            const uint32_t succ = g->succ[p];
+#pragma unroll
+            for (int s = p + 1; s < MAXT; ++s)
+                if ((succ >> s) & 1u) { mx = umax(mx, tail[s]); hs = __builtin_fma(g->w[p][s], H[s], hs); }
+            tail[p] = lat + mx;
+            H[p] = acc * (((sink_mask >> p) & 1u) ? g->u[p] : hs);
+            if ((src_mask >> p) & 1u) { st.smax = umax(st.smax, tail[p]); st.sacc += H[p]; }
+        }
+    }
+    // what the outer positions contribute to the recursions of positions < NIN
+#pragma unroll
+    for (int p = 0; p < 3; ++p) { st.nxt[p] = 0; st.hin[p] = 0.0; }
+#pragma unroll
+    for (int p = 0; p < NIN; ++p) {
+        const uint32_t succ = g->succ[p];
+#pragma unroll
+        for (int s = NIN; s < MAXT; ++s)
+            if ((succ >> s) & 1u) { st.nxt[p] = umax(st.nxt[p], tail[s]); st.hin[p] = __builtin_fma(g->w[p][s], H[s], st.hin[p]); }
+    }
+
+    Uniforms U;
+#pragma unroll
+    for (int p = 0; p < 3; ++p) {
+        const uint32_t t = g->task_at[p < NIN ? p : 0];
+        U.tab[p] = tab + t * k_max;
+        U.K[p] = in->K[t];
+        U.u[p] = g->u[p];
+        U.sink[p] = (sink_mask >> p) & 1u;
+        U.src[p] = (src_mask >> p) & 1u;
+    }
+    U.e01 = (g->succ[0] >> 1) & 1u; U.e02 = (g->succ[0] >> 2) & 1u; U.e12 = (g->succ[1] >> 2) & 1u;
+    U.w01 = g->w[0][1]; U.w02 = g->w[0][2]; U.w12 = g->w[1][2];
+    U.sloq = in->slo_l / g->q;
+    U.slo_raw = in->slo_raw;
+
+    const uint32_t Ko = U.K[NIN - 1];
+    const uint32_t lo = chunk_id * in->chunk;
+    const uint32_t hi = lo + in->chunk < Ko ? lo + in->chunk : Ko;
+    if constexpr (NIN == 3) loop_z(st, U, lo, hi, live, best);
+    else if constexpr (NIN == 2) loop_y(st, U, lo, hi, live, best);
+    else loop_x(st, U, lo, hi, live, best);
+}
+
+// Persistent grid: block b takes tiles b, b + grid, ...  Tiles are ordered by
+// instance, so a block meets the instances in ascending order; it keeps one
+// running minimum per lane and reduces it (wave, then block) only when the
+// instance changes.  Every block ends when its tile index passes the total.
+__global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
+{
+    extern __shared__ __attribute__((aligned(32))) unsigned char smem_raw[];
+    Entry* s_tab = (Entry*)smem_raw;
+    __shared__ uint64_t s_red[4];
+
+    const Instance JSV_CONST* insts = as_uniform((const Instance*)pl.inst);
+    const Graph JSV_CONST* graphs = as_uniform(pl.graphs);
+    const uint64_t total = as_uniform((const SummaryRec*)pl.summary)->total_tiles;
+    const uint32_t tk = pl.t_max * pl.k_max;
+
+    uint32_t cur = 0xFFFFFFFFu;     // instance whose tables are in LDS
+    uint32_t scan = 0;              // instance search cursor
+    uint64_t best = NO_KEY;
+    for (uint64_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
+        while (scan + 1 < pl.n_inst && insts[scan + 1].tile_begin <= tile) ++scan;
+        // skip instances without tiles that share a tile_begin with their successor
+        if (scan != cur) {
+            if (cur != 0xFFFFFFFFu) {
+                const uint64_t m = block_min(best, s_red);
+                if (threadIdx.x == 0) pl.partial[(size_t)cur * pl.grid + blockIdx.x] = m;
+            }
+            __syncthreads();
+            const Entry* src = pl.entries + (size_t)scan * tk;
+            const uint4* s4 = (const uint4*)src;
+            uint4* d4 = (uint4*)s_tab;
+            for (uint32_t k = threadIdx.x; k < tk * 2; k += blockDim.x) d4[k] = s4[k];
+            __syncthreads();
+            cur = scan;
+            best = NO_KEY;
+        }
+        const Instance JSV_CONST* in = insts + cur;
+        const Graph JSV_CONST* g = graphs + in->problem;
+        const Entry JSV_CONST* tab = as_uniform((const Entry*)pl.entries) + (size_t)cur * tk;
+        const uint64_t local = tile - in->tile_begin;
+        const uint32_t n_chunks = in->n_chunks;
+        const uint32_t chunk_id = (uint32_t)(local % n_chunks);
+        const uint64_t group = local / n_chunks;
+        switch (in->n_in) {
+        case 3: run_tile<3>(g, in, tab, s_tab, pl.k_max, group, chunk_id, best); break;
+        case 2: run_tile<2>(g, in, tab, s_tab, pl.k_max, group, chunk_id, best); break;
+        default: run_tile<1>(g, in, tab, s_tab, pl.k_max, group, chunk_id, best); break;
+        }
+    }
+    if (cur != 0xFFFFFFFFu) {
+        const uint64_t m = block_min(best, s_red);
+        if (threadIdx.x == 0) pl.partial[(size_t)cur * pl.grid + blockIdx.x] = m;
+    }
+}
+
+// ---- scoring of one assignment (finalize and eval) -----------------------------------------
+struct Score { uint32_t latency; uint32_t cost; double accuracy; uint8_t mask; };
+
+// dig[t]: digit of task id t in its surviving list.
+__device__ Score score_digits(const Graph* g, const Instance* in, const Entry* entries, uint32_t k_max,
+                              const uint32_t* dig)
+{
+    uint32_t tail[MAXT];
+    double H[MAXT];
+    const uint32_t T = g->T;
+    uint64_t cost = 0;
+    uint32_t crit = 0;
+    double raw = 0.0;
+    for (int p = (int)T - 1; p >= 0; --p) {
+        const uint32_t t = g->task_at[p];
+        const Entry* e = entries + (size_t)t * k_max + dig[t];
+        uint32_t mx = 0;
+        double hs = 0.0;
+        for (uint32_t s = p + 1; s < T; ++s)
+            if ((g->succ[p] >> s) & 1u) { mx = umax(mx, tail[s]); hs = __builtin_fma(g->w[p][s], H[s], hs); }
+        tail[p] = e->lat + mx;
+        H[p] = e->acc * (((g->sink_mask >> p) & 1u) ? g->u[p] : hs);
+        if ((g->src_mask >> p) & 1u) { crit = umax(crit, tail[p]); raw += H[p]; }
+        cost += e->cost;
+    }
+    Score sc;
+    const uint64_t lat = (uint64_t)g->q * crit;
+    sc.latency = lat > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)lat;
+    sc.cost = cost > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)cost;
+    sc.accuracy = raw / g->amax;
+    sc.mask = 0;
+    if (lat <= in->slo_l) sc.mask |= 1;
+    if (sc.accuracy >= in->slo_a) sc.mask |= 2;
+    if (g->capacity == 0 || cost <= g->capacity) sc.mask |= 4;
+    return sc;
+}
+
+// ---- finalize ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
+{
+    __shared__ uint64_t s_red[4];
+    const uint32_t i = blockIdx.x;
+    const Instance* in = pl.inst + i;
+    const Graph* g = pl.graphs + in->problem;
+    uint64_t m = NO_KEY;
+    for (uint32_t b = threadIdx.x; b < pl.grid; b += blockDim.x)
+        m = umin64(m, pl.partial[(size_t)i * pl.grid + b]);
+    m = block_min(m, s_red);
+    if (threadIdx.x != 0) return;
+
+    ResultRec* r = pl.results + i;
+    r->index = NO_KEY; r->full_index = NO_KEY; r->evaluated = in->space;
+    r->accuracy = 0.0; r->latency_us = 0; r->cost_units = 0x7FFFFFFF; r->feasible = 0;
+    r->flags = in->flags;
+    for (int t = 0; t < MAXT; ++t) { r->choice[t] = 0; r->replicas[t] = 0; }
+    if (m != NO_KEY && !(in->flags & (F_OVERFLOW | F_EMPTY))) {
+        const uint64_t idx = in->idx_bits ? (m & ((1ull << in->idx_bits) - 1)) : 0;
+        uint32_t dig[MAXT];
+        const Entry* ent = pl.entries + (size_t)i * pl.t_max * pl.k_max;
+        for (uint32_t t = 0; t < g->T; ++t) dig[t] = (uint32_t)((idx / in->stride[t]) % in->K[t]);
+        const Score sc = score_digits(g, in, ent, pl.k_max, dig);
+        if (sc.mask == 7) {                 // only the capacity bit can still be missing
+            r->index = idx; r->feasible = 1;
+            r->accuracy = sc.accuracy; r->latency_us = sc.latency; r->cost_units = (int32_t)sc.cost;
+            uint64_t full = 0;
+            bool over = false;
+            for (int t = (int)g->T - 1; t >= 0; --t) {
+                const Entry* e = ent + (size_t)t * pl.k_max + dig[t];
+                r->choice[t] = (uint16_t)e->choice;
+                r->replicas[t] = e->rep;
+                if (__umul64hi(full, g->C) != 0) over = true;
+                const uint64_t f2 = full * g->C + e->choice;
+                if (f2 < full * g->C) over = true;
+                full = f2;
+                if (full == NO_KEY) over = true;
+            }
+            r->full_index = over ? NO_KEY : full;
+        }
+    }
+    // the last block to finish writes the sweep summary
+    __threadfence();
+    const uint32_t ticket = atomicAdd(&pl.summary->done_count, 1u);
+    if (ticket == pl.n_inst - 1) {
+        __threadfence();
+        int32_t bl = -1;
+        uint32_t md = 0, any = 0;
+        for (uint32_t k = 0; k < pl.n_inst; ++k) {
+            const volatile ResultRec* rk = pl.results + k;
+            any |= rk->flags;
+            if (rk->feasible && (bl < 0 || pl.inst[k].demand > md)) { bl = (int32_t)k; md = pl.inst[k].demand; }
+        }
+        pl.summary->best_level = bl;
+        pl.summary->max_demand = md;
+        pl.summary->any_flags = any;
+    }
+}
+
+// ---- eval -------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) eval_kernel(Plan pl, const uint64_t* index, uint32_t n,
+                                                   uint32_t* latency, uint32_t* replicas, int32_t* cost,
+                                                   double* accuracy, uint8_t* mask, uint32_t* bad)
+{
+    const uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n) return;
+    const Instance* in = pl.inst;
+    const Graph* g = pl.graphs + in->problem;
+    const uint64_t idx = index[k];
+    if (idx >= in->space) { atomicOr(bad, 1u); return; }
+    uint32_t dig[MAXT];
+    for (uint32_t t = 0; t < g->T; ++t) dig[t] = (uint32_t)((idx / in->stride[t]) % in->K[t]);
+    const Score sc = score_digits(g, in, pl.entries, pl.k_max, dig);
+    latency[k] = sc.latency; cost[k] = (int32_t)sc.cost; accuracy[k] = sc.accuracy; mask[k] = sc.mask;
+    for (uint32_t t = 0; t < g->T; ++t)
+        replicas[(size_t)k * g->T + t] = pl.entries[(size_t)t * pl.k_max + dig[t]].rep;
+}
+
+// ---- launch wrappers (called from the host planner) -------------------------------------------
+size_t prune_lds_bytes(uint32_t c_max) { return (size_t)c_max * (8 + 4 + 4 + 4 + 1 + 1) + 16; }
+size_t enumerate_lds_bytes(uint32_t t_max, uint32_t k_max) { return (size_t)t_max * k_max * sizeof(Entry); }
+
+hipError_t launch_prune_plan_scan(const Plan& pl, hipStream_t stream)
+{
+    hipLaunchKernelGGL(prune_kernel, dim3(pl.n_inst * pl.t_max), dim3(256), prune_lds_bytes(pl.c_max), stream, pl);
+    hipLaunchKernelGGL(plan_kernel, dim3(pl.n_inst), dim3(256), 0, stream, pl);
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, stream, pl);
+    return hipGetLastError();
+}
+
+hipError_t launch_enumerate(const Plan& pl, hipStream_t stream)
+{
+    hipLaunchKernelGGL(enumerate_kernel, dim3(pl.grid), dim3(TILE_LANES),
+                       enumerate_lds_bytes(pl.t_max, pl.k_max), stream, pl);
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize(const Plan& pl, hipStream_t stream)
+{
+    hipLaunchKernelGGL(finalize_kernel, dim3(pl.n_inst), dim3(256), 0, stream, pl);
+    return hipGetLastError();
+}
+
+hipError_t launch_eval(const Plan& pl, const uint64_t* index, uint32_t n, uint32_t* latency,
+                       uint32_t* replicas, int32_t* cost, double* accuracy, uint8_t* mask,
+                       uint32_t* bad, hipStream_t stream)
+{
+    hipLaunchKernelGGL(eval_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, pl, index, n, latency,
+                       replicas, cost, accuracy, mask, bad);
+    return hipGetLastError();
+}
+
+}  // namespace jsv
