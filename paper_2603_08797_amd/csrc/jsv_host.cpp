@@ -356,7 +356,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
                jsv_result* out, jsv_summary* summary)
 {
     const uint32_t n = (uint32_t)inst.size();
-    if (jsv::enumerate_lds_bytes(t_max, k_max) > 64 * 1024 || jsv::prune_lds_bytes(c_max) > 64 * 1024)
+    if (jsv::enumerate_lds_bytes(t_max, k_max) > 128 * 1024 || jsv::prune_lds_bytes(c_max) > 64 * 1024)
         return JSV_E_BADARG;
     const Layout L = make_layout(n, t_max, k_max, c_max, ctx->grid, 0);
     unsigned char* ws = nullptr;

@@ -665,6 +665,12 @@ hipError_t launch_prune_plan_scan(const Plan& pl, hipStream_t stream)
 
 hipError_t launch_enumerate(const Plan& pl, hipStream_t stream)
 {
+    const size_t lds = enumerate_lds_bytes(pl.t_max, pl.k_max);
+    if (lds > 32 * 1024) {      // beyond the default dynamic limit: ask for it explicitly
+        hipError_t e = hipFuncSetAttribute((const void*)enumerate_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(enumerate_kernel, dim3(pl.grid), dim3(TILE_LANES),
                        enumerate_lds_bytes(pl.t_max, pl.k_max), stream, pl);
     return hipGetLastError();

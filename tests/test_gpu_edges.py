@@ -1,0 +1,162 @@
+"""GPU edge cases: degenerate graphs and spaces, limits, API behaviour."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2603_08797_amd import jsv, workloads as W
+from test_gpu_parity import REL, same, check_search
+
+pytestmark = pytest.mark.gpu
+U32 = 2**32 - 1
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    j = jsv.Jsv(device=0)
+    yield j
+    j.close()
+
+
+def _problem(T, V, P, B, seed, edges, mult=None, capacity=0):
+    r = W.SplitMix64(31, seed)
+    lat = np.zeros((T, V, P, B), dtype=np.uint32)
+    thr = np.zeros((T, V, P, B), dtype=np.uint32)
+    for i in np.ndindex(T, V, P, B):
+        lat[i] = r.randint(500, 30000)
+        thr[i] = r.randint(20_000, 900_000)
+    acc = np.sort(0.55 + 0.44 * np.array([[r.uniform() for _ in range(V)] for _ in range(T)]), axis=1)
+    return W.Problem(T, V, P, B, np.arange(1, P + 1, dtype=np.uint32),
+                     np.array([1 << b for b in range(B)], dtype=np.uint32), lat, thr, acc,
+                     np.array([e[0] for e in edges], dtype=np.uint16),
+                     np.array([e[1] for e in edges], dtype=np.uint16),
+                     np.array(mult if mult else [1000] * T, dtype=np.uint32), capacity, 2)
+
+
+def _search(D, slo_l, slo_a, cap=0):
+    return W.Search(np.array(D, dtype=np.uint32), slo_l, slo_a, cap)
+
+
+def test_single_task(ctx):
+    pb = _problem(1, 3, 4, 3, 1, [])
+    check_search(ctx, pb, _search([5000, 90000, 400000], 40000, 0.9))
+
+
+def test_single_task_maximum_choices(ctx):
+    pb = _problem(1, 8, 16, 16, 2, [])          # C = 2048 = JSV_MAX_CHOICES
+    check_search(ctx, pb, _search([70000], 50000, 0.8))
+    check_search(ctx, pb, _search([70000], 50000, 0.8, cap=64))
+
+
+def test_sixteen_task_chain_and_wide_graph(ctx):
+    T = 16
+    chain = _problem(T, 2, 1, 1, 3, [(i, i + 1) for i in range(T - 1)])
+    check_search(ctx, chain, _search([30000], 2 * 16 * 30000, 0.0))      # 2^16 candidates
+    check_search(ctx, chain, _search([30000], 330000, 0.02))
+    # every task isolated: 16 sources that are also sinks
+    wide = _problem(T, 2, 1, 1, 4, [], mult=[250 * (1 + t % 4) for t in range(T)])
+    check_search(ctx, wide, _search([30000, 900000], 50000, 0.6))
+    # reversed labels: task ids against the topological order
+    rev = _problem(T, 2, 1, 1, 5, [(i + 1, i) for i in range(T - 1)])
+    check_search(ctx, rev, _search([30000], 400000, 0.01))
+
+
+def test_dense_graph_with_uneven_multipliers(ctx):
+    T = 6
+    edges = [(i, j) for i in range(T) for j in range(i + 1, T)]
+    pb = _problem(T, 2, 2, 2, 6, edges, mult=[1000, 300, 2500, 700, 1200, 450], capacity=40)
+    check_search(ctx, pb, _search([20000, 150000, 700000], 150000, 0.35))
+    check_search(ctx, pb, _search([20000, 150000], 150000, 0.35, cap=4))
+
+
+def test_infeasible_is_not_an_error(ctx):
+    pb = _problem(3, 2, 2, 2, 7, [(0, 1), (1, 2)])
+    ctx.load(pb)
+    res, summ = ctx.search([1000], U32, 1.0000001, 0)
+    assert not res[0].feasible and res[0].index == 2**64 - 1 and res[0].cost == 2**31 - 1
+    assert (summ.best_level, summ.max_demand_mrps) == (-1, 0)
+    check_search(ctx, pb, _search([1000], 100, 0.0))               # latency SLO below any path
+    # the prune's latency filter empties every list: nothing is evaluated
+    res, summ = ctx.search([1000], 100, 0.0, 4)
+    ref, _, _ = oracle.Oracle.from_problem(pb).search([1000], 100, 0.0, 4)
+    assert res[0].evaluated == 0 == ref[0].evaluated and not res[0].feasible
+
+
+def test_capacity_bound_is_inclusive_and_binding(ctx):
+    pb = _problem(3, 2, 3, 2, 8, [(0, 1), (0, 2)])
+    ctx.load(pb)
+    free, _ = ctx.search([300000], U32, 0.0, 0)
+    c = free[0].cost
+    for cap_units, want in ((c, True), (c - 1, False)):
+        pb.capacity_units = cap_units
+        ctx.load(pb)
+        res, _ = ctx.search([300000], U32, 0.0, 0)
+        assert res[0].feasible == want
+        check_search(ctx, pb, _search([300000], U32, 0.0))
+
+
+def test_unsorted_and_repeated_demand_levels(ctx):
+    pb = _problem(4, 2, 2, 2, 9, [(0, 1), (1, 2), (1, 3)], capacity=14)
+    D = [500000, 1000, 90000, 90000, 250000, 1000]
+    res, summ = check_search(ctx, pb, _search(D, 120000, 0.3))
+    assert res[2] == res[3] and res[1] == res[5]
+
+
+def test_derived_throughput_equals_explicit_table(ctx):
+    w = W.chain3()
+    pb, se = w.problems[0], w.searches[0]
+    ctx.load(pb)
+    a, _ = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 0)
+    ctx.load(pb, derive_throughput=True)
+    b, _ = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 0)
+    assert a == b
+    o = oracle.Oracle.from_problem(pb, derive_throughput=True)
+    ref, _, _ = o.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 0, threads=4)
+    same(b[0], ref[0])
+
+
+def test_lent_workspace_too_small_is_reported(ctx):
+    pb = W.diamond5().problems[0]
+    ctx.load(pb)
+    import torch
+    t = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    p = (t.data_ptr() + 255) // 256 * 256
+    assert ctx._lib.jsv_set_workspace(ctx._h, p, 1024) == jsv.OK
+    with pytest.raises(jsv.JsvError) as e:
+        ctx.search([1000], 100000, 0.5, 40)
+    assert e.value.code == jsv.E_WORKSPACE
+    ctx._lib.jsv_set_workspace(ctx._h, None, 0)
+    ctx.search([1000], 100000, 0.5, 40)
+
+
+def test_cost_overflow_is_reported(ctx):
+    pb = _problem(2, 1, 1, 1, 10, [(0, 1)])
+    pb.thr_mrps[:] = 1
+    pb.units[:] = 4000
+    ctx.load(pb)
+    with pytest.raises(jsv.JsvError) as e:
+        ctx.search([4_000_000_000], U32, 0.0, 0)       # 4e9 replicas x 4000 units
+    assert e.value.code == jsv.E_OVERFLOW
+
+
+def test_repeated_runs_and_a_second_context_agree(ctx):
+    w = W.diamond5()
+    pb, se = w.problems[0], w.searches[0]
+    ctx.load(pb)
+    a, _ = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap)
+    b, _ = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap)
+    import torch
+    other = jsv.Jsv(device=0, stream=torch.cuda.Stream())
+    other.load(pb)
+    c, _ = other.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap)
+    other.close()
+    assert a == b == c
+
+
+def test_pruned_cost_matches_exhaustive_cost_when_nothing_was_thinned(ctx):
+    w = W.chain3()
+    pb, se = w.problems[0], w.searches[0]
+    ctx.load(pb)
+    full, _ = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 0)
+    pr, _ = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, pb.C)
+    assert pr[0].flags == 0 and pr[0].evaluated < full[0].evaluated
+    assert (pr[0].feasible, pr[0].cost) == (full[0].feasible, full[0].cost)

@@ -1,0 +1,184 @@
+"""GPU parity on the large workloads, in the launch configuration bench.py times.
+
+Where the oracle cannot enumerate the full space in seconds, parity is checked
+(a) in full at a reduced prune cap, (b) element by element on sampled candidates
+of the full-size space, (c) by properties of the full-size winner: the oracle
+rescoring it finds it feasible with the same scores, and no oracle arg-min over
+a sampled index range beats it.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2603_08797_amd import jsv, workloads as W
+from test_gpu_parity import REL, same
+
+pytestmark = pytest.mark.gpu
+THREADS = 16
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    j = jsv.Jsv(device=0)
+    yield j
+    j.close()
+
+
+def eval_equal(ga, gb):
+    for x, y in zip((ga[0], ga[1], ga[2], ga[4]), (gb[0], gb[1], gb[2], gb[4])):
+        assert np.array_equal(x, y)
+    assert np.all(np.abs(ga[3] - gb[3]) <= REL * np.abs(gb[3]))
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_xr8_reduced_cap_full_parity(ctx, seed):
+    w = W.xr8(seed=seed)
+    pb, se = w.problems[0], w.searches[0]
+    levels = se.demand_mrps[::8] if seed == 0 else se.demand_mrps[5::20]
+    ctx.load(pb)
+    res, summ = ctx.search(levels, se.slo_latency_us, se.slo_accuracy, 10)
+    o = oracle.Oracle.from_problem(pb)
+    ref, bl, md = o.search(levels, se.slo_latency_us, se.slo_accuracy, 10, threads=THREADS)
+    for l, (a, b) in enumerate(zip(res, ref)):
+        same(a, b, f"seed {seed} level {l}")
+    assert (summ.best_level, summ.max_demand_mrps) == (bl, md)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_xr8_pruned_lists_all_levels(ctx, seed):
+    w = W.xr8(seed=seed)
+    pb, se = w.problems[0], w.searches[0]
+    ctx.load(pb)
+    o = oracle.Oracle.from_problem(pb)
+    for D in se.demand_mrps[::(1 if seed == 0 else 7)].tolist():
+        for t in range(pb.T):
+            a, ta = ctx.get_pruned(D, se.slo_latency_us, se.prune_cap, t)
+            b, tb = o.pruned(D, se.slo_latency_us, se.prune_cap, t)
+            assert a.tolist() == b.tolist() and ta == tb
+
+
+def test_xr8_one_level_full_parity_at_cap_15(ctx):
+    w = W.xr8(seed=0)
+    pb, se = w.problems[0], w.searches[0]
+    ctx.load(pb)
+    D = se.demand_mrps[20:21]
+    res, _ = ctx.search(D, se.slo_latency_us, se.slo_accuracy, 15)
+    ref, _, _ = oracle.Oracle.from_problem(pb).search(D, se.slo_latency_us, se.slo_accuracy, 15,
+                                                      threads=THREADS)
+    assert ref[0].evaluated == 15 ** 8
+    same(res[0], ref[0])
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_xr8_full_size_sweep_properties(ctx, seed):
+    w = W.xr8(seed=seed)
+    pb, se = w.problems[0], w.searches[0]
+    ctx.load(pb)
+    ctx.lend_workspace(len(se.demand_mrps), se.prune_cap)        # as bench.py does
+    res, summ = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap)
+    ctx._lib.jsv_set_workspace(ctx._h, None, 0)
+    o = oracle.Oracle.from_problem(pb)
+    rng = np.random.default_rng(seed)
+    feas = [r.feasible for r in res]
+    order = np.argsort(se.demand_mrps, kind="stable")
+    # cap thinning depends on the demand, so a thinned sweep need not be monotone:
+    # the prefix and cost-order invariants are asserted only where nothing was thinned
+    exact = all(r.flags == 0 for r in res)
+    if exact:
+        assert [feas[i] for i in order] == sorted(feas, reverse=True)
+    if any(feas):
+        bl = max((i for i in range(len(res)) if feas[i]), key=lambda i: (se.demand_mrps[i], -i))
+        assert (summ.best_level, summ.max_demand_mrps) == (bl, int(se.demand_mrps[bl]))
+    costs = [res[i].cost for i in order if feas[i]]
+    if exact:
+        assert costs == sorted(costs)
+    for l in range(0, len(res), 1 if seed == 0 else 9):
+        r, D = res[l], int(se.demand_mrps[l])
+        K, space, tr = o.space(D, se.slo_latency_us, se.prune_cap)
+        assert r.evaluated == space and r.flags == int(tr)
+        # (b) sampled candidates of the full-size space, element by element
+        idx = rng.integers(0, space, size=20000, dtype=np.uint64)
+        if r.feasible:
+            idx[0] = r.index
+        ga = ctx.eval_candidates(D, se.slo_latency_us, se.slo_accuracy, se.prune_cap, idx)
+        gb = o.eval(D, se.slo_latency_us, se.slo_accuracy, se.prune_cap, idx)
+        eval_equal(ga, gb)
+        ok = gb[4] == 7
+        if r.feasible:
+            # (c) the winner is a real feasible candidate with exactly these scores ...
+            assert gb[4][0] == 7 and gb[2][0] == r.cost and gb[0][0] == r.latency_us
+            assert gb[1][0].tolist() == r.replicas
+            assert abs(gb[3][0] - r.accuracy) <= REL * abs(gb[3][0])
+            # ... and nothing sampled beats it
+            if ok.any():
+                best = min(zip(gb[2][ok].tolist(), idx[ok].tolist()))
+                assert (r.cost, r.index) <= best
+        else:
+            # infeasible: no sampled candidate may meet latency and accuracy within capacity
+            assert not ok.any()
+    # (c') oracle arg-min over index ranges around and away from the winner
+    for l in ([3, 17, 30] if seed == 0 else [11]):
+        r, D = res[l], int(se.demand_mrps[l])
+        if not r.feasible:
+            continue
+        span = 3_000_000
+        for lo in (max(0, r.index - span // 2), int(rng.integers(0, r.evaluated - span))):
+            sub = o.search_range(D, se.slo_latency_us, se.slo_accuracy, se.prune_cap, lo, lo + span,
+                                 threads=THREADS)
+            if sub.feasible:
+                assert (r.cost, r.index) <= (sub.cost, sub.index)
+                if lo <= r.index < lo + span:
+                    assert (sub.cost, sub.index) == (r.cost, r.index)
+
+
+def _batch_case(n, cap_for_six):
+    w = W.dagbatch(n=n)
+    for pb, se in zip(w.problems, w.searches):
+        if pb.T == 6:
+            se.prune_cap = cap_for_six
+    return w
+
+
+def test_dagbatch_full_parity(ctx):
+    """All 256 problems in one launch; 6-task problems at cap 12 so that the
+    oracle finishes in seconds, the others at the benchmark's cap 30."""
+    w = _batch_case(256, 12)
+    res = ctx.search_batch(w.problems, w.searches)
+    for k, (pb, se, a) in enumerate(zip(w.problems, w.searches, res)):
+        o = oracle.Oracle.from_problem(pb)
+        ref, _, _ = o.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap,
+                             threads=THREADS if pb.T >= 5 else 2)
+        same(a, ref[0], f"problem {k}")
+    assert any(r.feasible for r in res) and not all(r.feasible for r in res)
+
+
+def test_dagbatch_bench_configuration_properties(ctx):
+    w = W.dagbatch()
+    ctx.load_batch(w.problems, w.searches)
+    ctx.lend_workspace(len(w.problems), 0)
+    res, summ = ctx.search_loaded_batch()
+    res2, _ = ctx.search_loaded_batch()                           # same answer on a second pass
+    ctx._lib.jsv_set_workspace(ctx._h, None, 0)
+    assert res == res2
+    small = W.dagbatch()
+    one = jsv.Jsv(device=0)
+    rng = np.random.default_rng(5)
+    for k, (pb, se, r) in enumerate(zip(w.problems, w.searches, res)):
+        o = oracle.Oracle.from_problem(pb)
+        D = int(se.demand_mrps[0])
+        K, space, tr = o.space(D, se.slo_latency_us, se.prune_cap)
+        assert r.evaluated == space and r.flags == int(tr)
+        if pb.T <= 4:                                             # small enough: full parity
+            ref, _, _ = o.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap, threads=4)
+            same(r, ref[0], f"problem {k}")
+        elif r.feasible:
+            gb = o.eval(D, se.slo_latency_us, se.slo_accuracy, se.prune_cap, [r.index])
+            assert gb[4][0] == 7 and gb[2][0] == r.cost and gb[0][0] == r.latency_us
+            assert gb[1][0].tolist() == r.replicas
+            if k % 16 == 0 and space > 0:
+                idx = rng.integers(0, space, size=50000, dtype=np.uint64)
+                g2 = o.eval(D, se.slo_latency_us, se.slo_accuracy, se.prune_cap, idx)
+                ok = g2[4] == 7
+                if ok.any():
+                    assert (r.cost, r.index) <= min(zip(g2[2][ok].tolist(), idx[ok].tolist()))
+    one.close()
