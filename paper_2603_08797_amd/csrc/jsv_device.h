@@ -40,6 +40,18 @@ struct __attribute__((aligned(32))) Entry {
 };
 static_assert(sizeof(Entry) == 32, "Entry must be 32 bytes");
 
+// Compact stream of the innermost position's entries for the 32-bit fast path: its
+// surviving choices in ascending choice id, grouped by variant, each group padded to
+// whole quads with entries that can never win (lat = k32 = 0xFFFFFFFF).
+struct XEnt { uint32_t lat; uint32_t k32; };
+struct __attribute__((aligned(16))) Quad {
+    double   acc;       // accuracy of the quad's variant
+    uint32_t newgrp;    // 1 if the accuracy test must be redone here: a new variant starts,
+    uint32_t pad;       //   or a tile's range of quads starts
+    XEnt     e[4];
+};
+static_assert(sizeof(Quad) == 48, "Quad must be 48 bytes");
+
 // Task graph of one problem, by position.
 struct Graph {
     uint32_t T, V, P, B, C;
@@ -87,6 +99,13 @@ struct Instance {
     uint32_t tiles;           // n_groups * n_chunks
     uint32_t trunc_mask;      // bit t: cap thinning dropped a choice of task id t
     uint64_t tile_begin;      // first global tile of this instance (exclusive scan)
+    // 32-bit fast path: inside a lane-tile candidates are compared by
+    // (cost of the in-lane positions << lb) | rank, rank = their order by caller index
+    uint32_t use32;           // 1 if that fits 31 bits
+    uint32_t lb;              // bits of the rank
+    uint32_t nq;              // quads in the innermost position's stream
+    uint32_t ord[3];          // in-lane positions, least significant caller digit first
+    uint32_t pad[2];
 };
 
 // Result record as written by the finalize kernel; same layout as jsv_result.
@@ -115,6 +134,8 @@ struct Plan {
     Entry*       entries;     // [n_inst][t_max][k_max]   by task id
     uint32_t*    rep;         // [n_inst][t_max][c_max]   replicas of every choice
     uint32_t*    cost;        // [n_inst][t_max][c_max]
+    uint32_t*    k32;         // [n_inst][t_max][k_max]   32-bit local keys (in-lane tasks)
+    Quad*        quads;       // [n_inst][k_max]          stream of the innermost position
     uint64_t*    partial;     // [n_inst][grid]           per-block minima
     ResultRec*   results;     // [n_inst]
     SummaryRec*  summary;

@@ -53,7 +53,7 @@ struct Search {               // per-instance search parameters (batch mode keep
 };
 
 struct Layout {               // offsets into the workspace
-    size_t inst, entries, rep, cost, partial, results, summary, eval, total;
+    size_t inst, entries, rep, cost, k32, quads, partial, results, summary, eval, total;
 };
 
 }  // namespace
@@ -316,6 +316,8 @@ Layout make_layout(uint32_t n_inst, uint32_t t_max, uint32_t k_max, uint32_t c_m
     L.entries = off; off = align_up(off + sizeof(jsv::Entry) * (size_t)n_inst * t_max * k_max);
     L.rep = off;     off = align_up(off + sizeof(uint32_t) * (size_t)n_inst * t_max * c_max);
     L.cost = off;    off = align_up(off + sizeof(uint32_t) * (size_t)n_inst * t_max * c_max);
+    L.k32 = off;     off = align_up(off + sizeof(uint32_t) * (size_t)n_inst * t_max * k_max);
+    L.quads = off;   off = align_up(off + sizeof(jsv::Quad) * (size_t)n_inst * k_max);
     L.partial = off; off = align_up(off + sizeof(uint64_t) * (size_t)n_inst * grid);
     L.results = off; off = align_up(off + sizeof(jsv::ResultRec) * n_inst);
     L.summary = off; off = align_up(off + sizeof(jsv::SummaryRec));
@@ -376,6 +378,8 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     pl.entries = (jsv::Entry*)(ws + L.entries);
     pl.rep = (uint32_t*)(ws + L.rep);
     pl.cost = (uint32_t*)(ws + L.cost);
+    pl.k32 = (uint32_t*)(ws + L.k32);
+    pl.quads = (jsv::Quad*)(ws + L.quads);
     pl.partial = (uint64_t*)(ws + L.partial);
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
@@ -601,6 +605,8 @@ JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo
     pl.entries = (jsv::Entry*)(ws + L.entries);
     pl.rep = (uint32_t*)(ws + L.rep);
     pl.cost = (uint32_t*)(ws + L.cost);
+    pl.k32 = (uint32_t*)(ws + L.k32);
+    pl.quads = (jsv::Quad*)(ws + L.quads);
     pl.partial = (uint64_t*)(ws + L.partial);
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
@@ -663,6 +669,8 @@ JSV_API int jsv_get_pruned(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_late
     pl.entries = (jsv::Entry*)(ws + L.entries);
     pl.rep = (uint32_t*)(ws + L.rep);
     pl.cost = (uint32_t*)(ws + L.cost);
+    pl.k32 = (uint32_t*)(ws + L.k32);
+    pl.quads = (jsv::Quad*)(ws + L.quads);
     pl.partial = (uint64_t*)(ws + L.partial);
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);

@@ -210,7 +210,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     const Graph* g = pl.graphs + in->problem;
     const uint32_t T = g->T;
     __shared__ uint32_t s_maxcost[MAXT];
-    __shared__ uint32_t s_bits;
+    __shared__ uint32_t s_bits, s_lb, s_nin, s_ls[3];
     if (tid < MAXT) s_maxcost[tid] = 0;
     __syncthreads();
     for (uint32_t t = 0; t < T; ++t) {
@@ -254,13 +254,55 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
                 if (n == 1 || (so >= 64 && (so >= pl.lanes_wanted || so * Kp[n - 1] >= pl.lanes_wanted))) { n_in = n; s_out = so; break; }
             }
         }
+        // 32-bit fast path: candidates of one lane-tile differ only in the in-lane positions,
+        // so they can be ordered by (cost of those positions << lb) | rank, where rank orders
+        // them as the caller's index does (in-lane task with the lowest id = least significant).
+        uint32_t ord[3] = {0, 1, 2}, ls[3] = {0, 0, 0}, lb = 0, use32 = 0, nq = 0;
+        if (space != 0) {
+            for (uint32_t a = 0; a < n_in; ++a)           // sort in-lane positions by task id
+                for (uint32_t b = a + 1; b < n_in; ++b)
+                    if (g->task_at[ord[b]] < g->task_at[ord[a]]) { const uint32_t x = ord[a]; ord[a] = ord[b]; ord[b] = x; }
+            uint64_t ranks = 1, cost_in = 0;
+            for (uint32_t a = 0; a < n_in; ++a) {
+                ls[ord[a]] = (uint32_t)ranks;
+                ranks *= Kp[ord[a]];
+                cost_in += s_maxcost[g->task_at[ord[a]]];
+            }
+            while (lb < 32 && (ranks - 1) >> lb) ++lb;
+            uint32_t cb = 0;
+            while (cb < 32 && cost_in >> cb) ++cb;
+            use32 = (ranks <= 0x7FFFFFFFull && lb + cb <= 31) ? 1u : 0u;
+        }
+        if (use32) {
+            // stream of position 0: grouped by variant, groups padded to whole quads
+            const uint32_t tx = g->task_at[0], PB = g->P * g->B;
+            const Entry* ex = pl.entries + ((size_t)i * pl.t_max + tx) * pl.k_max;
+            Quad* qd = pl.quads + (size_t)i * pl.k_max;
+            uint32_t slot = 4, prev_var = 0xFFFFFFFFu;
+            for (uint32_t d = 0; d < Kp[0]; ++d) {
+                const uint32_t var = ex[d].choice / PB;
+                if (var != prev_var || slot == 4) {
+                    if (slot < 4) for (; slot < 4; ++slot) { qd[nq - 1].e[slot].lat = 0xFFFFFFFFu; qd[nq - 1].e[slot].k32 = 0xFFFFFFFFu; }
+                    qd[nq].acc = ex[d].acc;
+                    qd[nq].newgrp = (var != prev_var) ? 1u : 0u;
+                    qd[nq].pad = 0;
+                    ++nq; slot = 0; prev_var = var;
+                }
+                qd[nq - 1].e[slot].lat = ex[d].lat;
+                qd[nq - 1].e[slot].k32 = (ex[d].cost << lb) | (d * ls[0]);
+                ++slot;
+            }
+            if (nq) for (; slot < 4; ++slot) { qd[nq - 1].e[slot].lat = 0xFFFFFFFFu; qd[nq - 1].e[slot].k32 = 0xFFFFFFFFu; }
+        }
         uint32_t chunk = 1, n_chunks = 0, n_groups = 0;
         if (space != 0) {
-            uint64_t inner = 1;
+            // extent of the outermost in-lane loop: digits, or quads when it is the stream itself
+            const bool stream = use32 && n_in == 1;
+            uint64_t inner = stream ? 4 : 1;
             for (uint32_t p = 0; p + 1 < n_in; ++p) inner *= Kp[p];
-            const uint32_t Ko = Kp[n_in - 1];
-            uint64_t c = s_out >= pl.lanes_wanted ? Ko : (s_out * Ko) / pl.lanes_wanted;   // digits per tile that still
-            if (c > Ko) c = Ko;                                          // leave lanes_wanted lanes busy
+            const uint32_t Ko = stream ? nq : Kp[n_in - 1];
+            uint64_t c = s_out >= pl.lanes_wanted ? Ko : (s_out * Ko) / pl.lanes_wanted;   // extent per tile that
+            if (c > Ko) c = Ko;                                          // still leaves lanes_wanted lanes busy
             const uint64_t c_min = (64 + inner - 1) / inner;             // at least 64 candidates per lane
             if (c < c_min) c = c_min;
             if (c > Ko) c = Ko;
@@ -271,10 +313,14 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             if (ng * n_chunks > 0x7FFFFFFFull) { atomicOr(&in->flags, F_OVERFLOW); n_chunks = 0; }
             else n_groups = (uint32_t)ng;
         }
+        // every tile's range of quads must start with the accuracy test
+        if (use32 && n_in == 1) for (uint32_t j = 0; j < nq; j += chunk) pl.quads[(size_t)i * pl.k_max + j].newgrp = 1;
         in->n_in = n_in; in->s_out = s_out; in->chunk = chunk;
         in->n_chunks = n_chunks; in->n_groups = n_groups;
         in->tiles = n_groups * n_chunks;
-        s_bits = idx_bits;
+        in->use32 = use32; in->lb = lb; in->nq = nq;
+        for (int a = 0; a < 3; ++a) { in->ord[a] = ord[a]; s_ls[a] = ls[a]; }
+        s_bits = idx_bits; s_lb = lb; s_nin = use32 ? n_in : 0;
     }
     __syncthreads();
     // packed keys: (cost << idx_bits) | digit * stride
@@ -284,6 +330,13 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         const uint64_t stride = in->stride[t];
         for (uint32_t d = tid; d < in->K[t]; d += blockDim.x)
             e[d].key = ((uint64_t)e[d].cost << idx_bits) | ((uint64_t)d * stride);
+    }
+    // 32-bit local keys of the in-lane positions: (cost << lb) | digit * local stride
+    for (uint32_t p = 0; p < s_nin; ++p) {
+        const uint32_t t = g->task_at[p];
+        const Entry* e = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
+        uint32_t* k = pl.k32 + ((size_t)i * pl.t_max + t) * pl.k_max;
+        for (uint32_t d = tid; d < in->K[t]; d += blockDim.x) k[d] = (e[d].cost << s_lb) | (d * s_ls[p]);
     }
     for (uint32_t b = tid; b < pl.grid; b += blockDim.x) pl.partial[(size_t)i * pl.grid + b] = NO_KEY;
 }
@@ -322,11 +375,14 @@ struct LaneState {
     double   hin[3];    // sum of w * H over successors seen so far
     uint32_t smax;      // max tail over sources seen so far
     double   sacc;      // sum of H over sources seen so far
-    uint64_t key;       // sum of keys of the fixed positions
+    uint64_t key;       // sum of the 64-bit keys of the fixed positions
+    uint32_t k32;       // sum of the 32-bit local keys of the fixed in-lane positions
 };
 
 struct Uniforms {       // wave-uniform facts about positions 0..2
     const Entry JSV_CONST* tab[3];
+    const uint32_t JSV_CONST* k32[3];
+    const Quad JSV_CONST* quads;
     uint32_t K[3];
     double   u[3];      // sink share
     bool     sink[3], src[3];
@@ -336,15 +392,16 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     double   slo_raw;   // SLO_a * A_max
 };
 
-// Fix position P (a wave-uniform entry e) and push its contribution down.
+// Fix position P (a wave-uniform entry) and push its contribution down.
 template <int P>
 __device__ __forceinline__ LaneState fix_position(const LaneState& s, const Uniforms& U,
-                                                  uint32_t lat, double acc, uint64_t key)
+                                                  uint32_t lat, double acc, uint64_t key, uint32_t k32)
 {
     LaneState r = s;
     const uint32_t tail = lat + s.nxt[P];
     const double H = acc * (U.sink[P] ? U.u[P] : s.hin[P]);
     r.key = s.key + key;
+    r.k32 = s.k32 + k32;
     if (U.src[P]) { r.smax = umax(s.smax, tail); r.sacc = s.sacc + H; }
     if constexpr (P == 2) {
         if (U.e12) { r.nxt[1] = umax(s.nxt[1], tail); r.hin[1] = __builtin_fma(U.w12, H, s.hin[1]); }
@@ -356,13 +413,16 @@ __device__ __forceinline__ LaneState fix_position(const LaneState& s, const Unif
     return r;
 }
 
-// Innermost loop: position 0 (always a source).  Every candidate gets its latency
-// compare (Eq. 3), its accuracy (Eq. 11-12) and compare (Eq. 13), its key, and
-// the running minimum.  The capacity bound (Eq. 8) is applied to the minimum
-// afterwards: the cheapest candidate meeting Eq. 3 and 13 exceeds S_avail exactly
-// when every such candidate does.
-__device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       bool live, uint64_t& best)
+// Innermost loop: position 0 (always a source, all its successors fixed).  Every
+// candidate gets its latency compare (Eq. 3, against a hoisted threshold), its
+// accuracy (Eq. 11-12) and compare (Eq. 13), its key, and the running minimum.
+// The capacity bound (Eq. 8) is applied to the minimum afterwards: the cheapest
+// candidate meeting Eq. 3 and 13 exceeds S_avail exactly when every such
+// candidate does.
+//
+// 64-bit form: the full (cost, index) key per candidate.
+__device__ __forceinline__ void loop_x64(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
+                                         bool live, uint64_t& best)
 {
     const bool open = live && s.smax <= U.sloq && s.nxt[0] <= U.sloq;
     const uint32_t thr = open ? U.sloq - s.nxt[0] : 0u;      // latencies are >= 1
@@ -377,32 +437,72 @@ __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, ui
     }
 }
 
+// 32-bit form: entries come as quads of one variant, so the accuracy of Eq. 11-13
+// is evaluated once per variant and folded into the latency threshold; per
+// candidate remain one compare, one minimum and one select on 32-bit local keys.
+__device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, uint32_t qlo, uint32_t qhi,
+                                         bool live, uint32_t& best32)
+{
+    const bool open = live && s.smax <= U.sloq && s.nxt[0] <= U.sloq;
+    const uint32_t thr = open ? U.sloq - s.nxt[0] : 0u;
+    const double cx = U.sink[0] ? U.u[0] : s.hin[0];
+    const Quad JSV_CONST* q = U.quads;
+    uint32_t m = 0xFFFFFFFFu, thr_g = 0;
+    for (uint32_t j = qlo; j < qhi; ++j) {
+        if (q[j].newgrp != 0) {
+            const bool ok = __builtin_fma(q[j].acc, cx, s.sacc) >= U.slo_raw;
+            thr_g = ok ? thr : 0u;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t lat = q[j].e[e].lat, k = q[j].e[e].k32;
+            const uint32_t mk = m < k ? m : k;
+            m = (lat <= thr_g) ? mk : m;
+        }
+    }
+    const uint32_t cand = __builtin_elementwise_add_sat(s.k32, m);   // stays 0xFFFFFFFF if none
+    best32 = best32 < cand ? best32 : cand;
+}
+
+template <bool W32>
+__device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
+                                       bool live, uint64_t& best, uint32_t& best32)
+{
+    if constexpr (W32) loop_x32(s, U, lo, hi, live, best32);
+    else loop_x64(s, U, lo, hi, live, best);
+}
+
+template <bool W32>
 __device__ __forceinline__ void loop_y(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       bool live, uint64_t& best)
+                                       uint32_t x_hi, bool live, uint64_t& best, uint32_t& best32)
 {
     const Entry JSV_CONST* ty = U.tab[1];
     for (uint32_t d = lo; d < hi; ++d) {
-        const LaneState s1 = fix_position<1>(s, U, ty[d].lat, ty[d].acc, ty[d].key);
-        loop_x(s1, U, 0, U.K[0], live, best);
+        const LaneState s1 = fix_position<1>(s, U, ty[d].lat, ty[d].acc, W32 ? 0 : ty[d].key,
+                                             W32 ? U.k32[1][d] : 0u);
+        loop_x<W32>(s1, U, 0, x_hi, live, best, best32);
     }
 }
 
+template <bool W32>
 __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       bool live, uint64_t& best)
+                                       uint32_t x_hi, bool live, uint64_t& best, uint32_t& best32)
 {
     const Entry JSV_CONST* tz = U.tab[2];
     for (uint32_t d = lo; d < hi; ++d) {
-        const LaneState s2 = fix_position<2>(s, U, tz[d].lat, tz[d].acc, tz[d].key);
-        loop_y(s2, U, 0, U.K[1], live, best);
+        const LaneState s2 = fix_position<2>(s, U, tz[d].lat, tz[d].acc, W32 ? 0 : tz[d].key,
+                                             W32 ? U.k32[2][d] : 0u);
+        loop_y<W32>(s2, U, 0, U.K[1], x_hi, live, best, best32);
     }
 }
 
 // One tile: 256 lanes, each a different combination of the positions >= NIN
 // (decoded from the mixed-radix outer index), all looping over the same digits of
 // positions < NIN.
-template <int NIN>
+template <int NIN, bool W32>
 __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instance JSV_CONST* in,
-                                         const Entry JSV_CONST* tab, const Entry* s_tab, uint32_t k_max,
+                                         const Entry JSV_CONST* tab, const uint32_t JSV_CONST* k32,
+                                         const Quad JSV_CONST* quads, const Entry* s_tab, uint32_t k_max,
                                          uint64_t group, uint32_t chunk_id, uint64_t& best)
 {
     const uint32_t T = g->T;
@@ -427,7 +527,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     uint32_t tail[MAXT];
     double H[MAXT];
     LaneState st;
-    st.smax = 0; st.sacc = 0.0; st.key = 0;
+    st.smax = 0; st.sacc = 0.0; st.key = 0; st.k32 = 0;
     const uint32_t src_mask = g->src_mask, sink_mask = g->sink_mask;
 #pragma unroll
     for (int p = MAXT - 1; p >= NIN; --p) {
@@ -463,22 +563,44 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     for (int p = 0; p < 3; ++p) {
         const uint32_t t = g->task_at[p < NIN ? p : 0];
         U.tab[p] = tab + t * k_max;
+        U.k32[p] = k32 + t * k_max;
         U.K[p] = in->K[t];
         U.u[p] = g->u[p];
         U.sink[p] = (sink_mask >> p) & 1u;
         U.src[p] = (src_mask >> p) & 1u;
     }
+    U.quads = quads;
     U.e01 = (g->succ[0] >> 1) & 1u; U.e02 = (g->succ[0] >> 2) & 1u; U.e12 = (g->succ[1] >> 2) & 1u;
     U.w01 = g->w[0][1]; U.w02 = g->w[0][2]; U.w12 = g->w[1][2];
     U.sloq = in->slo_l / g->q;
     U.slo_raw = in->slo_raw;
 
-    const uint32_t Ko = U.K[NIN - 1];
+    // extent of the innermost loop (quads of the stream, or digits) and of the chunked loop
+    const uint32_t x_all = W32 ? in->nq : U.K[0];
+    const uint32_t Ko = NIN == 1 ? x_all : U.K[NIN - 1];
     const uint32_t lo = chunk_id * in->chunk;
     const uint32_t hi = lo + in->chunk < Ko ? lo + in->chunk : Ko;
-    if constexpr (NIN == 3) loop_z(st, U, lo, hi, live, best);
-    else if constexpr (NIN == 2) loop_y(st, U, lo, hi, live, best);
-    else loop_x(st, U, lo, hi, live, best);
+    uint32_t best32 = 0xFFFFFFFFu;
+    if constexpr (NIN == 3) loop_z<W32>(st, U, lo, hi, x_all, live, best, best32);
+    else if constexpr (NIN == 2) loop_y<W32>(st, U, lo, hi, x_all, live, best, best32);
+    else loop_x<W32>(st, U, lo, hi, live, best, best32);
+
+    if constexpr (W32) {
+        // the lane's 32-bit winner of this tile -> its full (cost, index) key
+        const bool hit = best32 != 0xFFFFFFFFu;
+        uint32_t r = hit ? (best32 & ((1u << in->lb) - 1u)) : 0u;
+        uint64_t k = st.key;
+#pragma unroll
+        for (int a = 0; a < NIN; ++a) {
+            const uint32_t p = in->ord[a];
+            const uint32_t t = g->task_at[p];
+            const uint32_t K = in->K[t];
+            const uint32_t d = r % K;
+            r /= K;
+            k += s_tab[t * k_max + d].key;
+        }
+        best = (hit && k < best) ? k : best;
+    }
 }
 
 // Persistent grid: block b takes tiles b, b + grid, ...  Tiles are ordered by
@@ -501,7 +623,6 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     uint64_t best = NO_KEY;
     for (uint64_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
         while (scan + 1 < pl.n_inst && insts[scan + 1].tile_begin <= tile) ++scan;
-        // skip instances without tiles that share a tile_begin with their successor
         if (scan != cur) {
             if (cur != 0xFFFFFFFFu) {
                 const uint64_t m = block_min(best, s_red);
@@ -519,14 +640,24 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const Instance JSV_CONST* in = insts + cur;
         const Graph JSV_CONST* g = graphs + in->problem;
         const Entry JSV_CONST* tab = as_uniform((const Entry*)pl.entries) + (size_t)cur * tk;
+        const uint32_t JSV_CONST* k32 = as_uniform((const uint32_t*)pl.k32) + (size_t)cur * tk;
+        const Quad JSV_CONST* quads = as_uniform((const Quad*)pl.quads) + (size_t)cur * pl.k_max;
         const uint64_t local = tile - in->tile_begin;
         const uint32_t n_chunks = in->n_chunks;
         const uint32_t chunk_id = (uint32_t)(local % n_chunks);
         const uint64_t group = local / n_chunks;
-        switch (in->n_in) {
-        case 3: run_tile<3>(g, in, tab, s_tab, pl.k_max, group, chunk_id, best); break;
-        case 2: run_tile<2>(g, in, tab, s_tab, pl.k_max, group, chunk_id, best); break;
-        default: run_tile<1>(g, in, tab, s_tab, pl.k_max, group, chunk_id, best); break;
+        if (in->use32) {
+            switch (in->n_in) {
+            case 3: run_tile<3, true>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            case 2: run_tile<2, true>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            default: run_tile<1, true>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            }
+        } else {
+            switch (in->n_in) {
+            case 3: run_tile<3, false>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            case 2: run_tile<2, false>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            default: run_tile<1, false>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            }
         }
     }
     if (cur != 0xFFFFFFFFu) {
