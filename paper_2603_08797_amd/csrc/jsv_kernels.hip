@@ -384,31 +384,33 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     const uint32_t JSV_CONST* k32[3];
     const Quad JSV_CONST* quads;
     uint32_t K[3];
-    double   u[3];      // sink share
-    bool     sink[3], src[3];
-    bool     e01, e02, e12;   // edge from position a to position b
-    double   w01, w02, w12;
+    bool     src[3];
+    uint32_t m01, m02, m12;   // all ones if position a has an edge to position b, else 0
+    double   w01, w02, w12;   // share of a among the predecessors of b (0 if no edge)
     uint32_t sloq;      // floor(SLO_l / q)
     double   slo_raw;   // SLO_a * A_max
 };
 
-// Fix position P (a wave-uniform entry) and push its contribution down.
+// Fix position P (a wave-uniform entry) and push its contribution down.  hin[P]
+// already holds the sink share u(P) when P is a sink (it then has no successor),
+// and an absent edge has weight 0 and mask 0, so only the "is a source" test is a
+// (wave-uniform) branch.
 template <int P>
 __device__ __forceinline__ LaneState fix_position(const LaneState& s, const Uniforms& U,
                                                   uint32_t lat, double acc, uint64_t key, uint32_t k32)
 {
     LaneState r = s;
     const uint32_t tail = lat + s.nxt[P];
-    const double H = acc * (U.sink[P] ? U.u[P] : s.hin[P]);
+    const double H = acc * s.hin[P];
     r.key = s.key + key;
     r.k32 = s.k32 + k32;
     if (U.src[P]) { r.smax = umax(s.smax, tail); r.sacc = s.sacc + H; }
     if constexpr (P == 2) {
-        if (U.e12) { r.nxt[1] = umax(s.nxt[1], tail); r.hin[1] = __builtin_fma(U.w12, H, s.hin[1]); }
-        if (U.e02) { r.nxt[0] = umax(s.nxt[0], tail); r.hin[0] = __builtin_fma(U.w02, H, s.hin[0]); }
+        r.nxt[1] = umax(s.nxt[1], tail & U.m12); r.hin[1] = __builtin_fma(U.w12, H, s.hin[1]);
+        r.nxt[0] = umax(s.nxt[0], tail & U.m02); r.hin[0] = __builtin_fma(U.w02, H, s.hin[0]);
     }
     if constexpr (P == 1) {
-        if (U.e01) { r.nxt[0] = umax(s.nxt[0], tail); r.hin[0] = __builtin_fma(U.w01, H, s.hin[0]); }
+        r.nxt[0] = umax(s.nxt[0], tail & U.m01); r.hin[0] = __builtin_fma(U.w01, H, s.hin[0]);
     }
     return r;
 }
@@ -422,11 +424,11 @@ __device__ __forceinline__ LaneState fix_position(const LaneState& s, const Unif
 //
 // 64-bit form: the full (cost, index) key per candidate.
 __device__ __forceinline__ void loop_x64(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                         bool live, uint64_t& best)
+                                         uint64_t& best)
 {
-    const bool open = live && s.smax <= U.sloq && s.nxt[0] <= U.sloq;
-    const uint32_t thr = open ? U.sloq - s.nxt[0] : 0u;      // latencies are >= 1
-    const double cx = U.sink[0] ? U.u[0] : s.hin[0];
+    const uint32_t worst = umax(s.smax, s.nxt[0]);           // dead lanes carry smax = 0xFFFFFFFF
+    const uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;   // latencies are >= 1
+    const double cx = s.hin[0];
     const Entry JSV_CONST* tx = U.tab[0];
     for (uint32_t d = lo; d < hi; ++d) {
         const uint32_t lat = tx[d].lat;
@@ -441,11 +443,11 @@ __device__ __forceinline__ void loop_x64(const LaneState& s, const Uniforms& U, 
 // is evaluated once per variant and folded into the latency threshold; per
 // candidate remain one compare, one minimum and one select on 32-bit local keys.
 __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, uint32_t qlo, uint32_t qhi,
-                                         bool live, uint32_t& best32)
+                                         uint32_t& best32)
 {
-    const bool open = live && s.smax <= U.sloq && s.nxt[0] <= U.sloq;
-    const uint32_t thr = open ? U.sloq - s.nxt[0] : 0u;
-    const double cx = U.sink[0] ? U.u[0] : s.hin[0];
+    const uint32_t worst = umax(s.smax, s.nxt[0]);           // dead lanes carry smax = 0xFFFFFFFF
+    const uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;   // latencies are >= 1
+    const double cx = s.hin[0];
     const Quad JSV_CONST* q = U.quads;
     uint32_t m = 0xFFFFFFFFu, thr_g = 0;
     for (uint32_t j = qlo; j < qhi; ++j) {
@@ -466,33 +468,33 @@ __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, 
 
 template <bool W32>
 __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       bool live, uint64_t& best, uint32_t& best32)
+                                       uint64_t& best, uint32_t& best32)
 {
-    if constexpr (W32) loop_x32(s, U, lo, hi, live, best32);
-    else loop_x64(s, U, lo, hi, live, best);
+    if constexpr (W32) loop_x32(s, U, lo, hi, best32);
+    else loop_x64(s, U, lo, hi, best);
 }
 
 template <bool W32>
 __device__ __forceinline__ void loop_y(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       uint32_t x_hi, bool live, uint64_t& best, uint32_t& best32)
+                                       uint32_t x_hi, uint64_t& best, uint32_t& best32)
 {
     const Entry JSV_CONST* ty = U.tab[1];
     for (uint32_t d = lo; d < hi; ++d) {
         const LaneState s1 = fix_position<1>(s, U, ty[d].lat, ty[d].acc, W32 ? 0 : ty[d].key,
                                              W32 ? U.k32[1][d] : 0u);
-        loop_x<W32>(s1, U, 0, x_hi, live, best, best32);
+        loop_x<W32>(s1, U, 0, x_hi, best, best32);
     }
 }
 
 template <bool W32>
 __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       uint32_t x_hi, bool live, uint64_t& best, uint32_t& best32)
+                                       uint32_t x_hi, uint64_t& best, uint32_t& best32)
 {
     const Entry JSV_CONST* tz = U.tab[2];
     for (uint32_t d = lo; d < hi; ++d) {
         const LaneState s2 = fix_position<2>(s, U, tz[d].lat, tz[d].acc, W32 ? 0 : tz[d].key,
                                              W32 ? U.k32[2][d] : 0u);
-        loop_y<W32>(s2, U, 0, U.K[1], x_hi, live, best, best32);
+        loop_y<W32>(s2, U, 0, U.K[1], x_hi, best, best32);
     }
 }
 
@@ -527,7 +529,8 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     uint32_t tail[MAXT];
     double H[MAXT];
     LaneState st;
-    st.smax = 0; st.sacc = 0.0; st.key = 0; st.k32 = 0;
+    st.smax = live ? 0u : 0xFFFFFFFFu;      // a dead lane can never meet the latency SLO
+    st.sacc = 0.0; st.key = 0; st.k32 = 0;
     const uint32_t src_mask = g->src_mask, sink_mask = g->sink_mask;
 #pragma unroll
     for (int p = MAXT - 1; p >= NIN; --p) {
@@ -549,7 +552,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     }
     // what the outer positions contribute to the recursions of positions < NIN
 #pragma unroll
-    for (int p = 0; p < 3; ++p) { st.nxt[p] = 0; st.hin[p] = 0.0; }
+    for (int p = 0; p < 3; ++p) { st.nxt[p] = 0; st.hin[p] = g->u[p]; }     // u(p) = 0 unless p is a sink
 #pragma unroll
     for (int p = 0; p < NIN; ++p) {
         const uint32_t succ = g->succ[p];
@@ -565,12 +568,10 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
         U.tab[p] = tab + t * k_max;
         U.k32[p] = k32 + t * k_max;
         U.K[p] = in->K[t];
-        U.u[p] = g->u[p];
-        U.sink[p] = (sink_mask >> p) & 1u;
         U.src[p] = (src_mask >> p) & 1u;
     }
     U.quads = quads;
-    U.e01 = (g->succ[0] >> 1) & 1u; U.e02 = (g->succ[0] >> 2) & 1u; U.e12 = (g->succ[1] >> 2) & 1u;
+    U.m01 = 0u - ((g->succ[0] >> 1) & 1u); U.m02 = 0u - ((g->succ[0] >> 2) & 1u); U.m12 = 0u - ((g->succ[1] >> 2) & 1u);
     U.w01 = g->w[0][1]; U.w02 = g->w[0][2]; U.w12 = g->w[1][2];
     U.sloq = in->slo_l / g->q;
     U.slo_raw = in->slo_raw;
@@ -581,9 +582,9 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     const uint32_t lo = chunk_id * in->chunk;
     const uint32_t hi = lo + in->chunk < Ko ? lo + in->chunk : Ko;
     uint32_t best32 = 0xFFFFFFFFu;
-    if constexpr (NIN == 3) loop_z<W32>(st, U, lo, hi, x_all, live, best, best32);
-    else if constexpr (NIN == 2) loop_y<W32>(st, U, lo, hi, x_all, live, best, best32);
-    else loop_x<W32>(st, U, lo, hi, live, best, best32);
+    if constexpr (NIN == 3) loop_z<W32>(st, U, lo, hi, x_all, best, best32);
+    else if constexpr (NIN == 2) loop_y<W32>(st, U, lo, hi, x_all, best, best32);
+    else loop_x<W32>(st, U, lo, hi, best, best32);
 
     if constexpr (W32) {
         // the lane's 32-bit winner of this tile -> its full (cost, index) key
