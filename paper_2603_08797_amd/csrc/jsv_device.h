@@ -44,13 +44,14 @@ static_assert(sizeof(Entry) == 32, "Entry must be 32 bytes");
 // surviving choices in ascending choice id, grouped by variant, each group padded to
 // whole quads with entries that can never win (lat = k32 = 0xFFFFFFFF).
 struct XEnt { uint32_t lat; uint32_t k32; };
-struct __attribute__((aligned(16))) Quad {
+struct __attribute__((aligned(64))) Quad {   // one 64-byte scalar load
     double   acc;       // accuracy of the quad's variant
     uint32_t newgrp;    // 1 if the accuracy test must be redone here: a new variant starts,
     uint32_t pad;       //   or a tile's range of quads starts
     XEnt     e[4];
+    uint32_t pad2[4];
 };
-static_assert(sizeof(Quad) == 48, "Quad must be 48 bytes");
+static_assert(sizeof(Quad) == 64, "Quad must be 64 bytes");
 
 // Task graph of one problem, by position.
 struct Graph {
@@ -125,6 +126,7 @@ struct SummaryRec {
     uint64_t total_tiles;     // written by the scan kernel
     uint32_t done_count;      // finalize blocks finished
     uint32_t any_flags;       // OR of all instance flags
+    unsigned long long next_tile;   // work counter of the enumeration kernel
 };
 
 // Everything the kernels need to find their data; passed by value.

@@ -63,7 +63,8 @@ struct jsv_ctx {
     hipStream_t stream = nullptr;
     int last_hip = 0;
     bool device_ready = false;
-    uint32_t grid = 0;
+    uint32_t grid = 0;                 // upper bound on enumeration blocks (sizes the workspace)
+    uint32_t cus = 0;
 
     HostProblem single;
     std::vector<HostProblem> batch;
@@ -252,6 +253,7 @@ int ensure_device(jsv_ctx* ctx)
     int cus = 0;
     HIP_TRY(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device));
     if (cus <= 0) cus = 256;
+    ctx->cus = (uint32_t)cus;
     ctx->grid = (uint32_t)cus * 8u;
     for (auto& e : ctx->ev) HIP_TRY(ctx, hipEventCreate(&e));
     ctx->device_ready = true;
@@ -384,7 +386,10 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
     pl.n_inst = n; pl.t_max = t_max; pl.k_max = k_max; pl.c_max = c_max;
-    pl.grid = ctx->grid;
+    int per_cu = 0;
+    HIP_TRY(ctx, jsv::enumerate_blocks_per_cu(t_max, k_max, &per_cu));
+    if (per_cu < 1) return JSV_E_BADARG;
+    pl.grid = ctx->cus * (uint32_t)std::min(per_cu, 8);     // everything launched is resident
     const uint64_t lanes = (uint64_t)ctx->grid * jsv::TILE_LANES * 2 / n;
     pl.lanes_wanted = (uint32_t)std::max<uint64_t>(64, std::min<uint64_t>(lanes, 0x7FFFFFFF));
 

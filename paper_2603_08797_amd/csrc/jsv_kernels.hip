@@ -357,6 +357,7 @@ __global__ void __launch_bounds__(256) scan_kernel(Plan pl)
         for (uint32_t k = 0; k < 256; ++k) { const uint64_t v = s_sum[k]; s_sum[k] = run; run += v; }
         pl.summary->total_tiles = run;
         pl.summary->done_count = 0;
+        pl.summary->next_tile = 0;
         pl.summary->any_flags = 0;
         pl.summary->best_level = -1;
         pl.summary->max_demand = 0;
@@ -440,27 +441,44 @@ __device__ __forceinline__ void loop_x64(const LaneState& s, const Uniforms& U, 
 }
 
 // 32-bit form: entries come as quads of one variant, so the accuracy of Eq. 11-13
-// is evaluated once per variant and folded into the latency threshold; per
-// candidate remain one compare, one minimum and one select on 32-bit local keys.
+// is evaluated once per variant; its outcome becomes the execution mask under which
+// the quad's candidates run.  Per candidate: v_cmpx_le_u32 narrows the mask to the
+// lanes that also meet the latency threshold, v_min_u32 updates their running
+// minimum of 32-bit local keys, and the mask is set back.  `full` is the execution
+// mask of the surrounding (convergent) code; it is restored before the block ends,
+// and the trailing s_nop keeps a following v_readlane/v_readfirstlane clear of the
+// last VALU write to EXEC.
 __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, uint32_t qlo, uint32_t qhi,
-                                         uint32_t& best32)
+                                         uint64_t full, uint32_t& best32)
 {
     const uint32_t worst = umax(s.smax, s.nxt[0]);           // dead lanes carry smax = 0xFFFFFFFF
     const uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;   // latencies are >= 1
     const double cx = s.hin[0];
     const Quad JSV_CONST* q = U.quads;
-    uint32_t m = 0xFFFFFFFFu, thr_g = 0;
+    uint32_t m = 0xFFFFFFFFu;
+    uint64_t ok = 0;
     for (uint32_t j = qlo; j < qhi; ++j) {
-        if (q[j].newgrp != 0) {
-            const bool ok = __builtin_fma(q[j].acc, cx, s.sacc) >= U.slo_raw;
-            thr_g = ok ? thr : 0u;
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t lat = q[j].e[e].lat, k = q[j].e[e].k32;
-            const uint32_t mk = m < k ? m : k;
-            m = (lat <= thr_g) ? mk : m;
-        }
+        if (q[j].newgrp != 0) ok = __builtin_amdgcn_ballot_w64(__builtin_fma(q[j].acc, cx, s.sacc) >= U.slo_raw);
+        asm volatile(
+            "s_mov_b64 exec, %[ok]\n\t"
+            "v_cmpx_le_u32_e32 vcc, %[l0], %[thr]\n\t"
+            "v_min_u32_e32 %[m], %[k0], %[m]\n\t"
+            "s_mov_b64 exec, %[ok]\n\t"
+            "v_cmpx_le_u32_e32 vcc, %[l1], %[thr]\n\t"
+            "v_min_u32_e32 %[m], %[k1], %[m]\n\t"
+            "s_mov_b64 exec, %[ok]\n\t"
+            "v_cmpx_le_u32_e32 vcc, %[l2], %[thr]\n\t"
+            "v_min_u32_e32 %[m], %[k2], %[m]\n\t"
+            "s_mov_b64 exec, %[ok]\n\t"
+            "v_cmpx_le_u32_e32 vcc, %[l3], %[thr]\n\t"
+            "v_min_u32_e32 %[m], %[k3], %[m]\n\t"
+            "s_mov_b64 exec, %[full]\n\t"
+            "s_nop 1"
+            : [m] "+v"(m)
+            : [ok] "s"(ok), [full] "s"(full), [thr] "v"(thr),
+              [l0] "s"(q[j].e[0].lat), [k0] "s"(q[j].e[0].k32), [l1] "s"(q[j].e[1].lat), [k1] "s"(q[j].e[1].k32),
+              [l2] "s"(q[j].e[2].lat), [k2] "s"(q[j].e[2].k32), [l3] "s"(q[j].e[3].lat), [k3] "s"(q[j].e[3].k32)
+            : "vcc");
     }
     const uint32_t cand = __builtin_elementwise_add_sat(s.k32, m);   // stays 0xFFFFFFFF if none
     best32 = best32 < cand ? best32 : cand;
@@ -468,33 +486,33 @@ __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, 
 
 template <bool W32>
 __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       uint64_t& best, uint32_t& best32)
+                                       uint64_t full, uint64_t& best, uint32_t& best32)
 {
-    if constexpr (W32) loop_x32(s, U, lo, hi, best32);
+    if constexpr (W32) loop_x32(s, U, lo, hi, full, best32);
     else loop_x64(s, U, lo, hi, best);
 }
 
 template <bool W32>
 __device__ __forceinline__ void loop_y(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       uint32_t x_hi, uint64_t& best, uint32_t& best32)
+                                       uint32_t x_hi, uint64_t full, uint64_t& best, uint32_t& best32)
 {
     const Entry JSV_CONST* ty = U.tab[1];
     for (uint32_t d = lo; d < hi; ++d) {
         const LaneState s1 = fix_position<1>(s, U, ty[d].lat, ty[d].acc, W32 ? 0 : ty[d].key,
                                              W32 ? U.k32[1][d] : 0u);
-        loop_x<W32>(s1, U, 0, x_hi, best, best32);
+        loop_x<W32>(s1, U, 0, x_hi, full, best, best32);
     }
 }
 
 template <bool W32>
 __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       uint32_t x_hi, uint64_t& best, uint32_t& best32)
+                                       uint32_t x_hi, uint64_t full, uint64_t& best, uint32_t& best32)
 {
     const Entry JSV_CONST* tz = U.tab[2];
     for (uint32_t d = lo; d < hi; ++d) {
         const LaneState s2 = fix_position<2>(s, U, tz[d].lat, tz[d].acc, W32 ? 0 : tz[d].key,
                                              W32 ? U.k32[2][d] : 0u);
-        loop_y<W32>(s2, U, 0, U.K[1], x_hi, best, best32);
+        loop_y<W32>(s2, U, 0, U.K[1], x_hi, full, best, best32);
     }
 }
 
@@ -582,9 +600,10 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     const uint32_t lo = chunk_id * in->chunk;
     const uint32_t hi = lo + in->chunk < Ko ? lo + in->chunk : Ko;
     uint32_t best32 = 0xFFFFFFFFu;
-    if constexpr (NIN == 3) loop_z<W32>(st, U, lo, hi, x_all, best, best32);
-    else if constexpr (NIN == 2) loop_y<W32>(st, U, lo, hi, x_all, best, best32);
-    else loop_x<W32>(st, U, lo, hi, best, best32);
+    const uint64_t full = __builtin_amdgcn_read_exec();     // the loops below run convergent
+    if constexpr (NIN == 3) loop_z<W32>(st, U, lo, hi, x_all, full, best, best32);
+    else if constexpr (NIN == 2) loop_y<W32>(st, U, lo, hi, x_all, full, best, best32);
+    else loop_x<W32>(st, U, lo, hi, full, best, best32);
 
     if constexpr (W32) {
         // the lane's 32-bit winner of this tile -> its full (cost, index) key
@@ -604,15 +623,18 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     }
 }
 
-// Persistent grid: block b takes tiles b, b + grid, ...  Tiles are ordered by
-// instance, so a block meets the instances in ascending order; it keeps one
-// running minimum per lane and reduces it (wave, then block) only when the
-// instance changes.  Every block ends when its tile index passes the total.
+// Persistent grid sized to what fits on the chip at once; blocks draw tiles from
+// one atomic counter, so no block waits for a second round and uneven tiles even
+// out.  Tiles are ordered by instance and the counter only grows, so a block meets
+// the instances in ascending order; it keeps one running minimum per lane and
+// reduces it (wave, then block) only when the instance changes.  Every block ends
+// with the first ticket at or past the total.
 __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
 {
     extern __shared__ __attribute__((aligned(32))) unsigned char smem_raw[];
     Entry* s_tab = (Entry*)smem_raw;
     __shared__ uint64_t s_red[4];
+    __shared__ unsigned long long s_tile;
 
     const Instance JSV_CONST* insts = as_uniform((const Instance*)pl.inst);
     const Graph JSV_CONST* graphs = as_uniform(pl.graphs);
@@ -622,7 +644,14 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     uint32_t cur = 0xFFFFFFFFu;     // instance whose tables are in LDS
     uint32_t scan = 0;              // instance search cursor
     uint64_t best = NO_KEY;
-    for (uint64_t tile = blockIdx.x; tile < total; tile += gridDim.x) {
+    for (;;) {
+        __syncthreads();                                  // everyone has read the last ticket
+        if (threadIdx.x == 0) s_tile = atomicAdd(&pl.summary->next_tile, 1ull);
+        __syncthreads();
+        const unsigned long long ticket = s_tile;
+        const uint64_t tile = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ticket >> 32)) << 32) |
+                              (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ticket);
+        if (tile >= total) break;
         while (scan + 1 < pl.n_inst && insts[scan + 1].tile_begin <= tile) ++scan;
         if (scan != cur) {
             if (cur != 0xFFFFFFFFu) {
@@ -795,14 +824,20 @@ hipError_t launch_prune_plan_scan(const Plan& pl, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_enumerate(const Plan& pl, hipStream_t stream)
+// Blocks of the enumeration kernel that are resident per CU with this much LDS.
+hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, int* blocks)
 {
-    const size_t lds = enumerate_lds_bytes(pl.t_max, pl.k_max);
+    const size_t lds = enumerate_lds_bytes(t_max, k_max);
     if (lds > 32 * 1024) {      // beyond the default dynamic limit: ask for it explicitly
         hipError_t e = hipFuncSetAttribute((const void*)enumerate_kernel,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, (const void*)enumerate_kernel, TILE_LANES, lds);
+}
+
+hipError_t launch_enumerate(const Plan& pl, hipStream_t stream)
+{
     hipLaunchKernelGGL(enumerate_kernel, dim3(pl.grid), dim3(TILE_LANES),
                        enumerate_lds_bytes(pl.t_max, pl.k_max), stream, pl);
     return hipGetLastError();
