@@ -41,15 +41,17 @@ struct __attribute__((aligned(32))) Entry {
 static_assert(sizeof(Entry) == 32, "Entry must be 32 bytes");
 
 // Compact stream of the innermost position's entries for the 32-bit fast path: its
-// surviving choices in ascending choice id, grouped by variant, each group padded to
-// whole quads with entries that can never win (lat = k32 = 0xFFFFFFFF).
+// surviving choices grouped by variant, inside a variant in ascending latency (ties:
+// ascending digit), each group padded to whole quads with entries that can never
+// win (lat = k32 = 0xFFFFFFFF).  One quad is one 64-byte scalar load; the dword
+// positions below are used by name in the enumeration kernel's inner loop.
 struct XEnt { uint32_t lat; uint32_t k32; };
-struct __attribute__((aligned(64))) Quad {   // one 64-byte scalar load
-    double   acc;       // accuracy of the quad's variant
-    uint32_t newgrp;    // 1 if the accuracy test must be redone here: a new variant starts,
-    uint32_t pad;       //   or a tile's range of quads starts
-    XEnt     e[4];
-    uint32_t pad2[4];
+struct __attribute__((aligned(64))) Quad {
+    XEnt     e[4];      // dwords 0-7
+    double   acc;       // dwords 8-9: accuracy of the quad's variant
+    uint32_t newgrp;    // dword 10: 1 if the accuracy test must be (re)done here: a new
+                        //   variant starts, or a tile's range of quads starts
+    uint32_t pad[5];
 };
 static_assert(sizeof(Quad) == 64, "Quad must be 64 bytes");
 

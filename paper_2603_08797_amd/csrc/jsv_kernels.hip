@@ -211,6 +211,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     const uint32_t T = g->T;
     __shared__ uint32_t s_maxcost[MAXT];
     __shared__ uint32_t s_bits, s_lb, s_nin, s_ls[3];
+    __shared__ uint32_t s_xq0[MAXC];        // first quad of the variant that starts at digit d
     if (tid < MAXT) s_maxcost[tid] = 0;
     __syncthreads();
     for (uint32_t t = 0; t < T; ++t) {
@@ -274,25 +275,19 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             use32 = (ranks <= 0x7FFFFFFFull && lb + cb <= 31) ? 1u : 0u;
         }
         if (use32) {
-            // stream of position 0: grouped by variant, groups padded to whole quads
+            // quads of position 0's stream: every variant's entries rounded up to whole quads
+            // (the stream itself is written by all threads below; s_xq0 = first quad per variant start)
             const uint32_t tx = g->task_at[0], PB = g->P * g->B;
             const Entry* ex = pl.entries + ((size_t)i * pl.t_max + tx) * pl.k_max;
-            Quad* qd = pl.quads + (size_t)i * pl.k_max;
-            uint32_t slot = 4, prev_var = 0xFFFFFFFFu;
-            for (uint32_t d = 0; d < Kp[0]; ++d) {
+            uint32_t d = 0;
+            while (d < Kp[0]) {
                 const uint32_t var = ex[d].choice / PB;
-                if (var != prev_var || slot == 4) {
-                    if (slot < 4) for (; slot < 4; ++slot) { qd[nq - 1].e[slot].lat = 0xFFFFFFFFu; qd[nq - 1].e[slot].k32 = 0xFFFFFFFFu; }
-                    qd[nq].acc = ex[d].acc;
-                    qd[nq].newgrp = (var != prev_var) ? 1u : 0u;
-                    qd[nq].pad = 0;
-                    ++nq; slot = 0; prev_var = var;
-                }
-                qd[nq - 1].e[slot].lat = ex[d].lat;
-                qd[nq - 1].e[slot].k32 = (ex[d].cost << lb) | (d * ls[0]);
-                ++slot;
+                uint32_t d1 = d;
+                while (d1 < Kp[0] && ex[d1].choice / PB == var) ++d1;
+                s_xq0[d] = nq;
+                nq += (d1 - d + 3) / 4;
+                d = d1;
             }
-            if (nq) for (; slot < 4; ++slot) { qd[nq - 1].e[slot].lat = 0xFFFFFFFFu; qd[nq - 1].e[slot].k32 = 0xFFFFFFFFu; }
         }
         uint32_t chunk = 1, n_chunks = 0, n_groups = 0;
         if (space != 0) {
@@ -313,8 +308,6 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             if (ng * n_chunks > 0x7FFFFFFFull) { atomicOr(&in->flags, F_OVERFLOW); n_chunks = 0; }
             else n_groups = (uint32_t)ng;
         }
-        // every tile's range of quads must start with the accuracy test
-        if (use32 && n_in == 1) for (uint32_t j = 0; j < nq; j += chunk) pl.quads[(size_t)i * pl.k_max + j].newgrp = 1;
         in->n_in = n_in; in->s_out = s_out; in->chunk = chunk;
         in->n_chunks = n_chunks; in->n_groups = n_groups;
         in->tiles = n_groups * n_chunks;
@@ -330,6 +323,36 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         const uint64_t stride = in->stride[t];
         for (uint32_t d = tid; d < in->K[t]; d += blockDim.x)
             e[d].key = ((uint64_t)e[d].cost << idx_bits) | ((uint64_t)d * stride);
+    }
+    // stream of position 0: by variant, inside a variant by ascending latency (so that the
+    // lanes still feasible only shrink along a variant), each variant padded to whole quads
+    if (s_nin != 0) {
+        const uint32_t tx = g->task_at[0], PB = g->P * g->B, K = in->K[tx];
+        const Entry* ex = pl.entries + ((size_t)i * pl.t_max + tx) * pl.k_max;
+        Quad* qd = pl.quads + (size_t)i * pl.k_max;
+        for (uint32_t d = tid; d < K; d += blockDim.x) {
+            const uint32_t var = ex[d].choice / PB, lat = ex[d].lat;
+            uint32_t d0 = d, d1 = d + 1, rank = 0;
+            while (d0 > 0 && ex[d0 - 1].choice / PB == var) --d0;
+            while (d1 < K && ex[d1].choice / PB == var) ++d1;
+            for (uint32_t x = d0; x < d1; ++x) rank += (ex[x].lat < lat || (ex[x].lat == lat && x < d)) ? 1u : 0u;
+            const uint32_t q0 = s_xq0[d0], n = d1 - d0, quads = (n + 3) / 4;
+            XEnt me;
+            me.lat = lat;
+            me.k32 = (ex[d].cost << s_lb) | (d * s_ls[0]);
+            qd[q0 + rank / 4].e[rank % 4] = me;
+            if (d == d0) {                                   // the variant's first digit writes headers and padding
+                for (uint32_t j = 0; j < quads; ++j) {
+                    qd[q0 + j].acc = ex[d].acc;
+                    qd[q0 + j].newgrp = j == 0 ? 1u : 0u;
+                    for (int z = 0; z < 5; ++z) qd[q0 + j].pad[z] = 0;
+                }
+                for (uint32_t r = n; r < quads * 4; ++r) { qd[q0 + r / 4].e[r % 4].lat = 0xFFFFFFFFu; qd[q0 + r / 4].e[r % 4].k32 = 0xFFFFFFFFu; }
+            }
+        }
+        // every tile's range of quads must start with the accuracy test
+        __syncthreads();
+        if (in->n_in == 1) for (uint32_t j = tid * in->chunk; j < in->nq; j += blockDim.x * in->chunk) qd[j].newgrp = 1;
     }
     // 32-bit local keys of the in-lane positions: (cost << lb) | digit * local stride
     for (uint32_t p = 0; p < s_nin; ++p) {
@@ -440,46 +463,61 @@ __device__ __forceinline__ void loop_x64(const LaneState& s, const Uniforms& U, 
     }
 }
 
-// 32-bit form: entries come as quads of one variant, so the accuracy of Eq. 11-13
-// is evaluated once per variant; its outcome becomes the execution mask under which
-// the quad's candidates run.  Per candidate: v_cmpx_le_u32 narrows the mask to the
-// lanes that also meet the latency threshold, v_min_u32 updates their running
-// minimum of 32-bit local keys, and the mask is set back.  `full` is the execution
-// mask of the surrounding (convergent) code; it is restored before the block ends,
-// and the trailing s_nop keeps a following v_readlane/v_readfirstlane clear of the
-// last VALU write to EXEC.
+// 32-bit form.  Entries come as quads of one variant, inside a variant in ascending
+// latency.  The accuracy of Eq. 11-13 is evaluated once per variant and its outcome
+// becomes the execution mask (v_cmpx_le_f64); along the variant's candidates
+// v_cmpx_le_u32 narrows the mask to the lanes that also meet the latency threshold
+// of Eq. 3 - a lane that fails one candidate fails all later ones of the variant -
+// and v_min_u32 updates the running minimum of 32-bit local keys of the lanes still
+// in the mask.  Per candidate: two vector instructions and no scalar one.
+//
+// The whole loop is one asm block so that nothing else executes under the narrowed
+// mask: one 64-byte scalar load per quad into s[72:87] (entries in dwords 0-7,
+// accuracy in 8-9, new-variant flag in 10), byte offset in s88.  `full` is the
+// execution mask of the surrounding convergent code; it is put back before the
+// block ends, and the trailing s_nop keeps a following v_readlane /
+// v_readfirstlane clear of the last vector write to EXEC.  The range [qlo, qhi) is
+// never empty and its first quad always carries the new-variant flag.
 __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, uint32_t qlo, uint32_t qhi,
                                          uint64_t full, uint32_t& best32)
 {
     const uint32_t worst = umax(s.smax, s.nxt[0]);           // dead lanes carry smax = 0xFFFFFFFF
     const uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;   // latencies are >= 1
-    const double cx = s.hin[0];
-    const Quad JSV_CONST* q = U.quads;
     uint32_t m = 0xFFFFFFFFu;
-    uint64_t ok = 0;
-    for (uint32_t j = qlo; j < qhi; ++j) {
-        if (q[j].newgrp != 0) ok = __builtin_amdgcn_ballot_w64(__builtin_fma(q[j].acc, cx, s.sacc) >= U.slo_raw);
-        asm volatile(
-            "s_mov_b64 exec, %[ok]\n\t"
-            "v_cmpx_le_u32_e32 vcc, %[l0], %[thr]\n\t"
-            "v_min_u32_e32 %[m], %[k0], %[m]\n\t"
-            "s_mov_b64 exec, %[ok]\n\t"
-            "v_cmpx_le_u32_e32 vcc, %[l1], %[thr]\n\t"
-            "v_min_u32_e32 %[m], %[k1], %[m]\n\t"
-            "s_mov_b64 exec, %[ok]\n\t"
-            "v_cmpx_le_u32_e32 vcc, %[l2], %[thr]\n\t"
-            "v_min_u32_e32 %[m], %[k2], %[m]\n\t"
-            "s_mov_b64 exec, %[ok]\n\t"
-            "v_cmpx_le_u32_e32 vcc, %[l3], %[thr]\n\t"
-            "v_min_u32_e32 %[m], %[k3], %[m]\n\t"
-            "s_mov_b64 exec, %[full]\n\t"
-            "s_nop 1"
-            : [m] "+v"(m)
-            : [ok] "s"(ok), [full] "s"(full), [thr] "v"(thr),
-              [l0] "s"(q[j].e[0].lat), [k0] "s"(q[j].e[0].k32), [l1] "s"(q[j].e[1].lat), [k1] "s"(q[j].e[1].k32),
-              [l2] "s"(q[j].e[2].lat), [k2] "s"(q[j].e[2].k32), [l3] "s"(q[j].e[3].lat), [k3] "s"(q[j].e[3].k32)
-            : "vcc");
-    }
+    double t;
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile(
+        "s_mov_b32 s88, %[begin]\n\t"
+        "1:\n\t"
+        "s_load_dwordx16 s[72:87], %[base], s88\n\t"
+        "s_add_u32 s88, s88, 64\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "s_cmp_eq_u32 s82, 0\n\t"
+        "s_cbranch_scc1 2f\n\t"
+        "s_mov_b64 exec, %[full]\n\t"
+        "v_fma_f64 %[t], s[80:81], %[cx], %[sacc]\n\t"
+        "v_cmpx_le_f64_e32 vcc, %[slo], %[t]\n\t"
+        "2:\n\t"
+        "v_cmpx_le_u32_e32 vcc, s72, %[thr]\n\t"
+        "v_min_u32_e32 %[m], s73, %[m]\n\t"
+        "v_cmpx_le_u32_e32 vcc, s74, %[thr]\n\t"
+        "v_min_u32_e32 %[m], s75, %[m]\n\t"
+        "v_cmpx_le_u32_e32 vcc, s76, %[thr]\n\t"
+        "v_min_u32_e32 %[m], s77, %[m]\n\t"
+        "v_cmpx_le_u32_e32 vcc, s78, %[thr]\n\t"
+        "v_min_u32_e32 %[m], s79, %[m]\n\t"
+        "s_cmp_lt_u32 s88, %[end]\n\t"
+        "s_cbranch_scc1 1b\n\t"
+        "s_mov_b64 exec, %[full]\n\t"
+        "s_nop 1"
+        : [m] "+v"(m), [t] "=&v"(t)
+        : [base] "s"(U.quads), [begin] "s"(qlo * 64u), [end] "s"(qhi * 64u), [full] "s"(full),
+          [thr] "v"(thr), [cx] "v"(s.hin[0]), [sacc] "v"(s.sacc), [slo] "s"(U.slo_raw)
+        : "vcc", "scc", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82",
+          "s83", "s84", "s85", "s86", "s87", "s88");
+#else
+    (void)thr; (void)t; (void)qlo; (void)qhi; (void)full;
+#endif
     const uint32_t cand = __builtin_elementwise_add_sat(s.k32, m);   // stays 0xFFFFFFFF if none
     best32 = best32 < cand ? best32 : cand;
 }
