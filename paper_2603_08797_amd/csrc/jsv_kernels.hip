@@ -428,7 +428,10 @@ __device__ __forceinline__ LaneState fix_position(const LaneState& s, const Unif
     const double H = acc * s.hin[P];
     r.key = s.key + key;
     r.k32 = s.k32 + k32;
-    if (U.src[P]) { r.smax = umax(s.smax, tail); r.sacc = s.sacc + H; }
+    if (U.src[P]) {
+        asm volatile("" ::: "memory");      // rare (a source after position 0): keep it a real, wave-uniform branch
+        r.smax = umax(s.smax, tail); r.sacc = s.sacc + H;
+    }
     if constexpr (P == 2) {
         r.nxt[1] = umax(s.nxt[1], tail & U.m12); r.hin[1] = __builtin_fma(U.w12, H, s.hin[1]);
         r.nxt[0] = umax(s.nxt[0], tail & U.m02); r.hin[0] = __builtin_fma(U.w02, H, s.hin[0]);
@@ -481,8 +484,10 @@ __device__ __forceinline__ void loop_x64(const LaneState& s, const Uniforms& U, 
 __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, uint32_t qlo, uint32_t qhi,
                                          uint64_t full, uint32_t& best32)
 {
-    const uint32_t worst = umax(s.smax, s.nxt[0]);           // dead lanes carry smax = 0xFFFFFFFF
-    const uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;   // latencies are >= 1
+    // lanes whose other sources already break the latency SLO sit out (dead lanes carry
+    // smax = 0xFFFFFFFF); for the rest position 0 may take at most thr (latencies are >= 1)
+    const uint64_t alive = __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
+    const uint32_t thr = __builtin_elementwise_sub_sat(U.sloq, s.nxt[0]);
     uint32_t m = 0xFFFFFFFFu;
     double t;
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -494,7 +499,7 @@ __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, 
         "s_waitcnt lgkmcnt(0)\n\t"
         "s_cmp_eq_u32 s82, 0\n\t"
         "s_cbranch_scc1 2f\n\t"
-        "s_mov_b64 exec, %[full]\n\t"
+        "s_mov_b64 exec, %[alive]\n\t"
         "v_fma_f64 %[t], s[80:81], %[cx], %[sacc]\n\t"
         "v_cmpx_le_f64_e32 vcc, %[slo], %[t]\n\t"
         "2:\n\t"
@@ -512,11 +517,12 @@ __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, 
         "s_nop 1"
         : [m] "+v"(m), [t] "=&v"(t)
         : [base] "s"(U.quads), [begin] "s"(qlo * 64u), [end] "s"(qhi * 64u), [full] "s"(full),
+          [alive] "s"(alive),
           [thr] "v"(thr), [cx] "v"(s.hin[0]), [sacc] "v"(s.sacc), [slo] "s"(U.slo_raw)
         : "vcc", "scc", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82",
           "s83", "s84", "s85", "s86", "s87", "s88");
 #else
-    (void)thr; (void)t; (void)qlo; (void)qhi; (void)full;
+    (void)thr; (void)t; (void)qlo; (void)qhi; (void)full; (void)alive;
 #endif
     const uint32_t cand = __builtin_elementwise_add_sat(s.k32, m);   // stays 0xFFFFFFFF if none
     best32 = best32 < cand ? best32 : cand;
