@@ -122,7 +122,9 @@ typedef struct {
     uint32_t latency_us;   /* queue_factor * critical path (left side of Eq. 3) */
     int32_t  cost_units;   /* sum of replicas * units (Eq. 7, 8); INT32_MAX if infeasible */
     uint32_t feasible;     /* 0 / 1 */
-    uint32_t flags;        /* bit0: the prune cap dropped a non-dominated choice */
+    uint32_t flags;        /* bit0: the prune cap dropped a non-dominated choice;
+                              bit1 (informational): costs were too large for the 32-bit
+                              fast path, 64-bit keys were compared instead */
     uint16_t choice[JSV_MAX_TASKS];     /* winner's choice id per task */
     uint32_t replicas[JSV_MAX_TASKS];   /* M of Eq. 6 per task */
 } jsv_result;

@@ -26,6 +26,7 @@ constexpr uint64_t NO_KEY = ~0ull;
 
 // instance flag bits
 constexpr uint32_t F_TRUNCATED = 1u;        // cap thinning dropped a choice
+constexpr uint32_t F_WIDE      = 2u;        // enumerated with 64-bit keys (32-bit fast path did not fit)
 constexpr uint32_t F_OVERFLOW  = 1u << 8;   // replicas, cost or key do not fit
 constexpr uint32_t F_EMPTY     = 1u << 9;   // some task has no surviving choice
 

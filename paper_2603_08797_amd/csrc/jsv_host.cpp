@@ -411,7 +411,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     std::memcpy(&sr, pin_out + sizeof(jsv::ResultRec) * n, sizeof sr);
     if (sr.any_flags & jsv::F_OVERFLOW) return JSV_E_OVERFLOW;
     std::memcpy(out, pin_out, sizeof(jsv::ResultRec) * n);
-    for (uint32_t k = 0; k < n; ++k) out[k].flags &= jsv::F_TRUNCATED;
+    for (uint32_t k = 0; k < n; ++k) out[k].flags &= (jsv::F_TRUNCATED | jsv::F_WIDE);
     if (summary) {
         float ms_all = 0.f, ms_enum = 0.f;
         HIP_TRY(ctx, hipEventElapsedTime(&ms_all, ctx->ev[0], ctx->ev[3]));

@@ -312,6 +312,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         in->n_chunks = n_chunks; in->n_groups = n_groups;
         in->tiles = n_groups * n_chunks;
         in->use32 = use32; in->lb = lb; in->nq = nq;
+        if (space != 0 && !use32) atomicOr(&in->flags, F_WIDE);
         for (int a = 0; a < 3; ++a) { in->ord[a] = ord[a]; s_ls[a] = ls[a]; }
         s_bits = idx_bits; s_lb = lb; s_nin = use32 ? n_in : 0;
     }

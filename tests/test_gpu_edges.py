@@ -158,5 +158,45 @@ def test_pruned_cost_matches_exhaustive_cost_when_nothing_was_thinned(ctx):
     ctx.load(pb)
     full, _ = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 0)
     pr, _ = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, pb.C)
-    assert pr[0].flags == 0 and pr[0].evaluated < full[0].evaluated
+    assert pr[0].flags & 1 == 0 and pr[0].evaluated < full[0].evaluated
     assert (pr[0].feasible, pr[0].cost) == (full[0].feasible, full[0].cost)
+
+
+def test_large_costs_take_the_64_bit_key_path(ctx):
+    """Costs of ~1e7 units per task do not fit the 32-bit local key (cost bits + rank
+    bits > 31), so the enumeration falls back to comparing full 64-bit keys."""
+    pb = _problem(3, 2, 3, 4, 11, [(0, 1), (1, 2)])
+    pb.thr_mrps[:] = (pb.thr_mrps % 8) + 8              # 8..15 mrps per replica: ~3e8 replicas
+    pb.units[:] = 1
+    res, _ = check_search(ctx, pb, _search([3_000_000_000], 120000, 0.5))
+    assert res[0].flags & 2 and res[0].feasible and res[0].cost > 2**29
+    res, _ = check_search(ctx, pb, _search([3_000_000_000, 1000], 120000, 0.5))
+    assert [r.flags & 2 for r in res] == [2, 0]          # the small level fits the fast path
+    check_search(ctx, pb, _search([3_000_000_000, 2_000_000_000, 1000], 120000, 0.5, cap=8))
+
+
+def test_equal_latencies_inside_a_variant_keep_the_lowest_index(ctx):
+    """All choices of a variant share one latency and one cost: every tie must go to the
+    lowest candidate index although the kernel walks a variant in latency order."""
+    pb = _problem(3, 2, 2, 3, 12, [(0, 1), (0, 2)])
+    pb.latency_us[:, 0] = 7000
+    pb.latency_us[:, 1] = 9000
+    pb.thr_mrps[:] = 500_000
+    pb.units[:] = 2
+    check_search(ctx, pb, _search([100000, 1_400_000], 60000, 0.0))
+    check_search(ctx, pb, _search([100000], 60000, 0.9))
+
+
+def test_many_variants_few_choices_each(ctx):
+    """P = B = 1: every stream group holds one choice and three padding entries."""
+    pb = _problem(3, 12, 1, 1, 13, [(0, 1), (1, 2)])
+    check_search(ctx, pb, _search([40000, 600000], 70000, 0.55))
+    check_search(ctx, pb, _search([40000], 70000, 0.55, cap=24))
+
+
+def test_source_tasks_after_the_first_position(ctx):
+    """Two extra sources feeding one sink: positions 1 and 2 are sources too."""
+    pb = _problem(4, 2, 2, 2, 14, [(0, 3), (1, 3), (2, 3)], mult=[1000, 400, 1600, 1000])
+    check_search(ctx, pb, _search([50000, 300000], 90000, 0.4))
+    wide = _problem(3, 3, 2, 2, 15, [])                  # three isolated tasks
+    check_search(ctx, wide, _search([50000], 50000, 0.7))
