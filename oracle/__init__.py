@@ -34,7 +34,8 @@ class OrcResult(C.Structure):
     _fields_ = [("index", C.c_uint64), ("full_index", C.c_uint64), ("evaluated", C.c_uint64),
                 ("accuracy", C.c_double), ("latency_us", C.c_uint32), ("cost", C.c_int32),
                 ("feasible", C.c_uint32), ("flags", C.c_uint32),
-                ("choice", C.c_uint16 * MAX_TASKS), ("replicas", C.c_uint32 * MAX_TASKS)]
+                ("choice", C.c_uint16 * MAX_TASKS), ("replicas", C.c_uint32 * MAX_TASKS),
+                ("objective", C.c_double)]
 
 
 _lib = None
@@ -78,6 +79,11 @@ def _load():
         lib.orc_accuracy_of_variants.argtypes = [vp, vp]
         lib.orc_accuracy_margin.restype = C.c_double
         lib.orc_accuracy_margin.argtypes = [vp, C.c_double]
+        lib.orc_set_objective.restype = C.c_int
+        lib.orc_set_objective.argtypes = [vp, C.c_int, C.c_double, C.c_double]
+        lib.orc_objective_margin.restype = C.c_int
+        lib.orc_objective_margin.argtypes = [vp, C.c_uint32, C.c_uint32, C.c_double, C.c_uint32,
+                                             C.POINTER(C.c_double)]
         lib.orc_max_threads.restype = C.c_int
         lib.orc_max_threads.argtypes = []
         _lib = lib
@@ -106,12 +112,14 @@ class Result:
     flags: int
     choice: List[int]
     replicas: List[int]
+    objective: float = 0.0
 
 
 def _result(r: OrcResult, T: int) -> Result:
     return Result(int(r.index), int(r.full_index), int(r.evaluated), float(r.accuracy),
                   int(r.latency_us), int(r.cost), bool(r.feasible), int(r.flags),
-                  [int(r.choice[t]) for t in range(T)], [int(r.replicas[t]) for t in range(T)])
+                  [int(r.choice[t]) for t in range(T)], [int(r.replicas[t]) for t in range(T)],
+                  float(r.objective))
 
 
 def max_threads() -> int:
@@ -162,6 +170,21 @@ class Oracle:
             self.close()
         except Exception:
             pass
+
+    def set_objective(self, mode: int, alpha: float = 1.0, beta: float = 0.035):
+        """mode 0: cheapest feasible; mode 1: maximise alpha*A_obj - beta*cost."""
+        rc = self._lib.orc_set_objective(self._h, int(mode), float(alpha), float(beta))
+        if rc != OK:
+            raise OracleError(rc, "orc_set_objective")
+
+    def objective_margin(self, demand_mrps: int, slo_latency_us: int, slo_accuracy: float,
+                         prune_cap: int) -> float:
+        m = C.c_double()
+        rc = self._lib.orc_objective_margin(self._h, int(demand_mrps), int(slo_latency_us),
+                                            float(slo_accuracy), int(prune_cap), C.byref(m))
+        if rc != OK:
+            raise OracleError(rc, "orc_objective_margin")
+        return float(m.value)
 
     # -- graph -----------------------------------------------------------------
     def amax(self) -> float:

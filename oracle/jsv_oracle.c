@@ -19,6 +19,9 @@
  *   - system accuracy:    sum_p f_p*A_p / A_max, >= SLO_a      (Eq. 12, 13)
  *   - result:             among candidates meeting all three constraints the
  *                         cheapest one; equal costs -> lowest candidate index.
+ *                         Optionally instead the paper's objective (Eq. 14): the
+ *                         largest alpha*A_obj - beta*cost; equal objectives ->
+ *                         lower cost -> lowest candidate index.
  *
  * Paths are enumerated explicitly by depth-first search and every candidate is
  * scored from the tables on its own: no dynamic programming over the graph, no
@@ -56,6 +59,7 @@ typedef struct {
     uint32_t flags;       /* bit0: cap thinning dropped a choice at this level */
     uint16_t choice[ORC_MAX_TASKS];
     uint32_t replicas[ORC_MAX_TASKS];
+    double objective;     /* alpha*A_obj - beta*cost of the winner (Eq. 14) */
 } orc_result;
 
 typedef struct {
@@ -64,6 +68,9 @@ typedef struct {
     double *acc;
     uint16_t *src, *dst;
     uint32_t capacity, q;
+    /* what the search optimises: 0 = cheapest feasible, 1 = Eq. 14 */
+    int objective;
+    double alpha, beta;
     /* graph */
     int npred[ORC_MAX_TASKS], pred[ORC_MAX_TASKS][ORC_MAX_TASKS];
     int nsucc[ORC_MAX_TASKS], succ[ORC_MAX_TASKS][ORC_MAX_TASKS];
@@ -161,6 +168,7 @@ int orc_create(orc_model **out, uint32_t T, uint32_t V, uint32_t P, uint32_t B,
     if (!m) return ORC_E_MEM;
     m->T = T; m->V = V; m->P = P; m->B = B; m->C = V * P * B; m->E = E;
     m->capacity = capacity_units; m->q = queue_factor;
+    m->objective = 0; m->alpha = 1.0; m->beta = 0.035;     /* the paper's evaluation parameters */
     size_t n = (size_t)T * m->C;
     m->units = dup_mem(units, P * sizeof *units);
     m->batch = dup_mem(batch, B * sizeof *batch);
@@ -238,6 +246,15 @@ int orc_create(orc_model **out, uint32_t T, uint32_t V, uint32_t P, uint32_t B,
     }
     m->amax = raw_accuracy(m, best);
     *out = m;
+    return ORC_OK;
+}
+
+/* mode 0: cheapest feasible assignment.  mode 1: maximise alpha*A_obj - beta*cost (Eq. 14;
+   the paper's evaluation uses alpha = 1, beta = 0.035). */
+int orc_set_objective(orc_model *m, int mode, double alpha, double beta)
+{
+    if (!m || (mode != 0 && mode != 1) || !(alpha >= 0.0) || !(beta >= 0.0)) return ORC_E_ARG;
+    m->objective = mode; m->alpha = alpha; m->beta = beta;
     return ORC_OK;
 }
 
@@ -475,6 +492,7 @@ static void result_fill(orc_result *r, const level_t *L, uint64_t i)
     score_t s = score(L, i, c);
     r->index = i; r->feasible = 1;
     r->accuracy = s.acc; r->latency_us = s.lat; r->cost = s.cost;
+    r->objective = m->alpha * s.acc - m->beta * (double)s.cost;
     for (uint32_t t = 0; t < m->T; t++) {
         r->choice[t] = (uint16_t)c[t];
         r->replicas[t] = L->rep[(size_t)t * m->C + c[t]];
@@ -489,14 +507,24 @@ static void result_fill(orc_result *r, const level_t *L, uint64_t i)
     r->full_index = over ? UINT64_MAX : (uint64_t)full;
 }
 
-/* cheapest feasible candidate of [lo, hi), lowest index on equal cost */
+/* Is candidate (obj, cost) at a higher index better than the best so far?  Candidates are
+   visited in ascending index, so equality never replaces. */
+static inline int better(const orc_model *m, double obj, int32_t cost, double bobj, int32_t bcost)
+{
+    if (m->objective == 0) return cost < bcost;
+    return obj > bobj || (obj == bobj && cost < bcost);
+}
+
+/* best feasible candidate of [lo, hi): cheapest (mode 0) or largest objective (mode 1);
+   remaining ties go to the lowest index */
 static void argmin_range(const level_t *L, uint64_t lo, uint64_t hi, int threads,
                          int *found, int32_t *best_cost, uint64_t *best_idx)
 {
+    const orc_model *m = L->m;
     if (threads < 1) threads = 1;
-    int32_t bc[256]; uint64_t bi[256]; int bf[256];
+    int32_t bc[256]; uint64_t bi[256]; int bf[256]; double bo[256];
     if (threads > 256) threads = 256;
-    for (int k = 0; k < threads; k++) { bf[k] = 0; bc[k] = INT32_MAX; bi[k] = UINT64_MAX; }
+    for (int k = 0; k < threads; k++) { bf[k] = 0; bc[k] = INT32_MAX; bi[k] = UINT64_MAX; bo[k] = 0.0; }
     uint64_t span = hi > lo ? hi - lo : 0;
 #ifdef _OPENMP
 #pragma omp parallel for num_threads(threads) schedule(static, 1)
@@ -506,12 +534,17 @@ static void argmin_range(const level_t *L, uint64_t lo, uint64_t hi, int threads
         uint64_t b = lo + (uint64_t)(((unsigned __int128)span * (unsigned)(k + 1)) / (unsigned)threads);
         for (uint64_t i = a; i < b; i++) {
             score_t s = score(L, i, NULL);
-            if (s.mask == 7 && (!bf[k] || s.cost < bc[k])) { bf[k] = 1; bc[k] = s.cost; bi[k] = i; }
+            if (s.mask != 7) continue;
+            double obj = m->alpha * s.acc - m->beta * (double)s.cost;
+            if (!bf[k] || better(m, obj, s.cost, bo[k], bc[k])) { bf[k] = 1; bc[k] = s.cost; bi[k] = i; bo[k] = obj; }
         }
     }
     *found = 0; *best_cost = INT32_MAX; *best_idx = UINT64_MAX;
+    double best_obj = 0.0;
     for (int k = 0; k < threads; k++)   /* chunks are in ascending index order */
-        if (bf[k] && (!*found || bc[k] < *best_cost)) { *found = 1; *best_cost = bc[k]; *best_idx = bi[k]; }
+        if (bf[k] && (!*found || better(m, bo[k], bc[k], best_obj, *best_cost))) {
+            *found = 1; *best_cost = bc[k]; *best_idx = bi[k]; best_obj = bo[k];
+        }
 }
 
 /*
@@ -613,6 +646,41 @@ double orc_accuracy_margin(const orc_model *m, double slo_accuracy)
         if (t == m->T) break;
     }
     return best;
+}
+
+/*
+ * Objective mode only: gap between the winner's objective and the best objective of any
+ * feasible candidate that uses a different combination of variants (1e300 if there is
+ * none, -1 if the level is infeasible).  Candidates with the winner's variants have exactly
+ * its accuracy, so their order is decided by integer cost; only this gap is exposed to
+ * floating-point rounding, and tests skip inputs where it is tiny.
+ */
+int orc_objective_margin(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us,
+                         double slo_accuracy, uint32_t cap, double *margin)
+{
+    level_t L;
+    int rc = level_init(&L, m, demand_mrps, slo_latency_us, slo_accuracy, cap);
+    if (rc) return rc;
+    int found; int32_t bc; uint64_t bi;
+    argmin_range(&L, 0, L.space, 1, &found, &bc, &bi);
+    *margin = -1.0;
+    if (found) {
+        uint32_t cw[ORC_MAX_TASKS], c[ORC_MAX_TASKS];
+        score_t w = score(&L, bi, cw);
+        double wobj = m->alpha * w.acc - m->beta * (double)w.cost, other = -1e300;
+        for (uint64_t i = 0; i < L.space; i++) {
+            score_t s = score(&L, i, c);
+            if (s.mask != 7) continue;
+            int same = 1;
+            for (uint32_t t = 0; t < m->T; t++) if (variant_of(m, c[t]) != variant_of(m, cw[t])) same = 0;
+            if (same) continue;
+            double obj = m->alpha * s.acc - m->beta * (double)s.cost;
+            if (obj > other) other = obj;
+        }
+        *margin = other == -1e300 ? 1e300 : wobj - other;
+    }
+    level_free(&L);
+    return ORC_OK;
 }
 
 int orc_max_threads(void)

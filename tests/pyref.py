@@ -125,6 +125,38 @@ class PyRef:
             out.append(sorted(r[3] for r in front))
         return out, truncated
 
+    def search_objective(self, D: int, slo_l: int, slo_a: float, cap: int, alpha: float, beta: float):
+        """Eq. 14 in exact rationals: the feasible candidate with the largest
+        alpha*A_obj - beta*cost; ties -> lower cost -> lower index.  Returns
+        (best (idx, cost, lat, acc, choice, obj) or None, gap to the best candidate
+        with other variants or None)."""
+        lists, _ = self.lists(D, slo_l, cap)
+        K = [len(l) for l in lists]
+        if not all(K):
+            return None, None
+        al, be, slo = Fraction(float(alpha)), Fraction(float(beta)), Fraction(float(slo_a))
+        capu = int(self.pb.capacity_units)
+        strides = [1] * self.T
+        for t in range(1, self.T):
+            strides[t] = strides[t - 1] * K[t - 1]
+        feas = []
+        for digits in itertools.product(*[range(k) for k in reversed(K)]):
+            digits = digits[::-1]
+            idx = sum(d * s for d, s in zip(digits, strides))
+            choice = [lists[t][digits[t]] for t in range(self.T)]
+            lat = self.latency(choice)
+            cost = sum(self.rep_cost(D, t, choice[t])[1] for t in range(self.T))
+            variants = tuple(self.variant(c) for c in choice)
+            acc = self._acc(variants) / self.amax
+            if lat <= slo_l and acc >= slo and (capu == 0 or cost <= capu):
+                feas.append((-(al * acc - be * cost), cost, idx, lat, acc, choice, variants))
+        if not feas:
+            return None, None
+        w = min(feas, key=lambda r: r[:3])
+        others = [-r[0] for r in feas if r[6] != w[6]]
+        gap = (-w[0] - max(others)) if others else None
+        return (w[2], w[1], w[3], w[4], w[5], -w[0]), gap
+
     def search(self, D: int, slo_l: int, slo_a: float, cap: int):
         """Returns (best index or None, cost, latency, accuracy Fraction, K list,
         truncated, min |A - slo| seen)."""
