@@ -114,6 +114,18 @@ JSV_API int jsv_load_profile(jsv_ctx* ctx, uint32_t T, uint32_t V, uint32_t P, u
 JSV_API int jsv_set_dag(jsv_ctx* ctx, uint32_t T, uint32_t E, const uint16_t* src, const uint16_t* dst,
                 const uint32_t* demand_mult_milli, uint32_t capacity_units, uint32_t queue_factor);
 
+/*
+ * What the search optimises (Eq. 14).  mode 0 (default): the cheapest feasible
+ * assignment, lowest index on equal cost - the cost term of Eq. 14 alone.  mode 1:
+ * the feasible assignment with the largest alpha * A_obj - beta * cost; equal
+ * objectives go to the lower cost, then to the lowest index.  The paper's
+ * evaluation uses alpha = 1, beta = 0.035 (Section 4.4), which are the defaults
+ * used for the `objective` field of the results in mode 0.  Applies to all later
+ * searches of the context.  Errors: JSV_E_NULL; JSV_E_BADARG (mode not 0 or 1,
+ * alpha or beta negative or not finite).
+ */
+JSV_API int jsv_set_objective(jsv_ctx* ctx, int mode, double alpha, double beta);
+
 typedef struct {
     uint64_t index;        /* winner's index in the searched space; UINT64_MAX if infeasible */
     uint64_t full_index;   /* sum_t c_t * C^t; UINT64_MAX if infeasible or it does not fit */
@@ -127,6 +139,7 @@ typedef struct {
                               fast path, 64-bit keys were compared instead */
     uint16_t choice[JSV_MAX_TASKS];     /* winner's choice id per task */
     uint32_t replicas[JSV_MAX_TASKS];   /* M of Eq. 6 per task */
+    double   objective;    /* alpha * A_obj - beta * cost_units of the winner (Eq. 14) */
 } jsv_result;
 
 typedef struct {

@@ -110,6 +110,9 @@ struct Instance {
     uint32_t nq;              // quads in the innermost position's stream
     uint32_t ord[3];          // in-lane positions, least significant caller digit first
     uint32_t pad[2];
+    // objective of Eq. 14 (inputs, host): maximise alpha * A_obj - beta * cost
+    double   alpha, beta;
+    double   alpha_n;         // alpha / A_max: factor on A_raw
 };
 
 // Result record as written by the finalize kernel; same layout as jsv_result.
@@ -121,6 +124,7 @@ struct ResultRec {
     uint32_t feasible, flags;
     uint16_t choice[MAXT];
     uint32_t replicas[MAXT];
+    double   objective;
 };
 
 struct SummaryRec {
@@ -141,12 +145,15 @@ struct Plan {
     uint32_t*    cost;        // [n_inst][t_max][c_max]
     uint32_t*    k32;         // [n_inst][t_max][k_max]   32-bit local keys (in-lane tasks)
     Quad*        quads;       // [n_inst][k_max]          stream of the innermost position
-    uint64_t*    partial;     // [n_inst][grid]           per-block minima
+    uint64_t*    partial;     // [n_inst][grid]           per-block minima (keys)
+    double*      partial_obj; // [n_inst][grid]           per-block best objectives (objective mode)
     ResultRec*   results;     // [n_inst]
     SummaryRec*  summary;
     uint32_t n_inst, t_max, k_max, c_max;
     uint32_t grid;            // blocks of the enumeration kernel
     uint32_t lanes_wanted;    // total lanes the planner tries to expose
+    uint32_t objective;       // 0: cheapest feasible; 1: largest alpha*A_obj - beta*cost (Eq. 14)
+    uint32_t pad;
 };
 
 }  // namespace jsv

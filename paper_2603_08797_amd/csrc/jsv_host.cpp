@@ -53,7 +53,7 @@ struct Search {               // per-instance search parameters (batch mode keep
 };
 
 struct Layout {               // offsets into the workspace
-    size_t inst, entries, rep, cost, k32, quads, partial, results, summary, eval, total;
+    size_t inst, entries, rep, cost, k32, quads, partial, partial_obj, results, summary, eval, total;
 };
 
 }  // namespace
@@ -71,6 +71,8 @@ struct jsv_ctx {
     std::vector<Search> batch_search;
     bool batch_mode = false;
     bool dirty = true;                 // host problems changed since the last upload
+    int objective = 0;                 // Eq. 14 mode and weights
+    double alpha = 1.0, beta = 0.035;
 
     void* d_problems = nullptr;        // graphs + tables
     size_t d_problems_bytes = 0;
@@ -321,6 +323,7 @@ Layout make_layout(uint32_t n_inst, uint32_t t_max, uint32_t k_max, uint32_t c_m
     L.k32 = off;     off = align_up(off + sizeof(uint32_t) * (size_t)n_inst * t_max * k_max);
     L.quads = off;   off = align_up(off + sizeof(jsv::Quad) * (size_t)n_inst * k_max);
     L.partial = off; off = align_up(off + sizeof(uint64_t) * (size_t)n_inst * grid);
+    L.partial_obj = off; off = align_up(off + sizeof(double) * (size_t)n_inst * grid);
     L.results = off; off = align_up(off + sizeof(jsv::ResultRec) * n_inst);
     L.summary = off; off = align_up(off + sizeof(jsv::SummaryRec));
     L.eval = off;    // index u64, latency u32, replicas u32*T, cost i32, accuracy f64, mask u8, bad u32
@@ -383,11 +386,13 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     pl.k32 = (uint32_t*)(ws + L.k32);
     pl.quads = (jsv::Quad*)(ws + L.quads);
     pl.partial = (uint64_t*)(ws + L.partial);
+    pl.partial_obj = (double*)(ws + L.partial_obj);
+    pl.objective = (uint32_t)ctx->objective; pl.pad = 0;
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
     pl.n_inst = n; pl.t_max = t_max; pl.k_max = k_max; pl.c_max = c_max;
     int per_cu = 0;
-    HIP_TRY(ctx, jsv::enumerate_blocks_per_cu(t_max, k_max, &per_cu));
+    HIP_TRY(ctx, jsv::enumerate_blocks_per_cu(t_max, k_max, ctx->objective != 0, &per_cu));
     if (per_cu < 1) return JSV_E_BADARG;
     pl.grid = ctx->cus * (uint32_t)std::min(per_cu, 8);     // everything launched is resident
     const uint64_t lanes = (uint64_t)ctx->grid * jsv::TILE_LANES * 2 / n;
@@ -424,10 +429,12 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     return JSV_OK;
 }
 
-Instance make_instance(const HostProblem& hp, uint32_t problem, const Search& s)
+Instance make_instance(const jsv_ctx* ctx, const HostProblem& hp, uint32_t problem, const Search& s)
 {
     Instance in;
     std::memset(&in, 0, sizeof in);
+    in.alpha = ctx->alpha; in.beta = ctx->beta;
+    in.alpha_n = ctx->alpha / hp.graph.amax;
     in.problem = problem;
     in.demand = s.demand; in.slo_l = s.slo_l; in.cap = s.cap;
     in.slo_a = s.slo_a;
@@ -497,6 +504,15 @@ JSV_API const char* jsv_error_string(int code)
     case JSV_E_DEVICE: return "HIP call failed";
     default: return "unknown error";
     }
+}
+
+JSV_API int jsv_set_objective(jsv_ctx* ctx, int mode, double alpha, double beta)
+{
+    if (!ctx) return JSV_E_NULL;
+    if (mode != 0 && mode != 1) return JSV_E_BADARG;
+    if (!(alpha >= 0.0) || !(beta >= 0.0) || std::isinf(alpha) || std::isinf(beta)) return JSV_E_BADARG;
+    ctx->objective = mode; ctx->alpha = alpha; ctx->beta = beta;
+    return JSV_OK;
 }
 
 JSV_API size_t jsv_workspace_bytes(const jsv_ctx* ctx, uint32_t n_levels, uint32_t prune_cap)
@@ -578,7 +594,7 @@ JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_lev
     const HostProblem& hp = ctx->single;
     std::vector<Instance> inst(n_levels);
     for (uint32_t l = 0; l < n_levels; ++l)
-        inst[l] = make_instance(hp, 0, Search{demand_mrps[l], slo_latency_us, prune_cap, slo_accuracy});
+        inst[l] = make_instance(ctx, hp, 0, Search{demand_mrps[l], slo_latency_us, prune_cap, slo_accuracy});
     return run_search(ctx, inst, hp.T, k_max_of(hp, prune_cap), hp.C, out, summary);
 }
 
@@ -602,7 +618,7 @@ JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo
     unsigned char* ws = nullptr;
     rc = get_workspace(ctx, L.total, &ws);
     if (rc) return rc;
-    Instance in = make_instance(hp, 0, Search{demand_mrps, slo_latency_us, prune_cap, slo_accuracy});
+    Instance in = make_instance(ctx, hp, 0, Search{demand_mrps, slo_latency_us, prune_cap, slo_accuracy});
 
     jsv::Plan pl;
     pl.graphs = (const Graph*)ctx->d_problems;
@@ -613,6 +629,8 @@ JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo
     pl.k32 = (uint32_t*)(ws + L.k32);
     pl.quads = (jsv::Quad*)(ws + L.quads);
     pl.partial = (uint64_t*)(ws + L.partial);
+    pl.partial_obj = (double*)(ws + L.partial_obj);
+    pl.objective = (uint32_t)ctx->objective; pl.pad = 0;
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
     pl.n_inst = 1; pl.t_max = T; pl.k_max = k_max; pl.c_max = hp.C;
@@ -667,7 +685,7 @@ JSV_API int jsv_get_pruned(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_late
     unsigned char* ws = nullptr;
     rc = get_workspace(ctx, L.total, &ws);
     if (rc) return rc;
-    Instance in = make_instance(hp, 0, Search{demand_mrps, slo_latency_us, prune_cap, 0.0});
+    Instance in = make_instance(ctx, hp, 0, Search{demand_mrps, slo_latency_us, prune_cap, 0.0});
     jsv::Plan pl;
     pl.graphs = (const Graph*)ctx->d_problems;
     pl.inst = (Instance*)(ws + L.inst);
@@ -677,6 +695,8 @@ JSV_API int jsv_get_pruned(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_late
     pl.k32 = (uint32_t*)(ws + L.k32);
     pl.quads = (jsv::Quad*)(ws + L.quads);
     pl.partial = (uint64_t*)(ws + L.partial);
+    pl.partial_obj = (double*)(ws + L.partial_obj);
+    pl.objective = (uint32_t)ctx->objective; pl.pad = 0;
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
     pl.n_inst = 1; pl.t_max = T; pl.k_max = k_max; pl.c_max = hp.C;
@@ -739,7 +759,7 @@ JSV_API int jsv_search_loaded_batch(jsv_ctx* ctx, jsv_result* out, jsv_summary* 
     std::vector<Instance> inst(n);
     uint32_t t_max = 0, k_max = 0, c_max = 0;
     for (uint32_t k = 0; k < n; ++k) {
-        inst[k] = make_instance(ctx->batch[k], k, ctx->batch_search[k]);
+        inst[k] = make_instance(ctx, ctx->batch[k], k, ctx->batch_search[k]);
         t_max = std::max(t_max, ctx->batch[k].T);
         c_max = std::max(c_max, ctx->batch[k].C);
         k_max = std::max(k_max, k_max_of(ctx->batch[k], ctx->batch_search[k].cap));

@@ -78,6 +78,72 @@ __device__ __forceinline__ uint64_t block_min(uint64_t v, uint64_t* s_red)
     return umin64(umin64(s_red[0], s_red[1]), umin64(s_red[2], s_red[3]));
 }
 
+// Objective mode: a lane's best is the pair (objective, key); larger objective wins,
+// equal objectives go to the smaller key, i.e. lower cost and then lower index.  "No
+// candidate" is (-inf, NO_KEY) and loses against everything.
+struct Best { uint64_t key; double obj; };
+
+__device__ __forceinline__ bool better(double ao, uint64_t ak, double bo, uint64_t bk)
+{
+    return ao > bo || (ao == bo && ak < bk);
+}
+
+__device__ __forceinline__ Best pick(const Best& a, const Best& b) { return better(b.obj, b.key, a.obj, a.key) ? b : a; }
+
+template <int CTRL>
+__device__ __forceinline__ Best dpp_best(const Best& v)
+{
+    const uint64_t ob = __builtin_bit_cast(uint64_t, v.obj);
+    Best o;
+    o.key = ((uint64_t)(uint32_t)__builtin_amdgcn_update_dpp((int)(v.key >> 32), (int)(v.key >> 32), CTRL, 0xF, 0xF, false) << 32) |
+            (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)v.key, (int)(uint32_t)v.key, CTRL, 0xF, 0xF, false);
+    o.obj = __builtin_bit_cast(double,
+            ((uint64_t)(uint32_t)__builtin_amdgcn_update_dpp((int)(ob >> 32), (int)(ob >> 32), CTRL, 0xF, 0xF, false) << 32) |
+            (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)ob, (int)(uint32_t)ob, CTRL, 0xF, 0xF, false));
+    return pick(v, o);
+}
+
+__device__ __forceinline__ uint64_t swz16(uint64_t x)
+{
+    return ((uint64_t)(uint32_t)__builtin_amdgcn_ds_swizzle((int)(x >> 32), 0x401F) << 32) |
+           (uint32_t)__builtin_amdgcn_ds_swizzle((int)(uint32_t)x, 0x401F);
+}
+
+__device__ __forceinline__ uint64_t lane_of(uint64_t x, int lane)
+{
+    return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(x >> 32), lane) << 32) |
+           (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, lane);
+}
+
+__device__ __forceinline__ Best wave_best(Best v)
+{
+    v = dpp_best<0xB1>(v);
+    v = dpp_best<0x4E>(v);
+    v = dpp_best<0x141>(v);
+    v = dpp_best<0x140>(v);
+    Best o;
+    o.key = swz16(v.key);
+    o.obj = __builtin_bit_cast(double, swz16(__builtin_bit_cast(uint64_t, v.obj)));
+    v = pick(v, o);
+    Best a, b;
+    a.key = lane_of(v.key, 0);  a.obj = __builtin_bit_cast(double, lane_of(__builtin_bit_cast(uint64_t, v.obj), 0));
+    b.key = lane_of(v.key, 32); b.obj = __builtin_bit_cast(double, lane_of(__builtin_bit_cast(uint64_t, v.obj), 32));
+    return pick(a, b);
+}
+
+// Best pair over a 256-thread block; valid in thread 0.
+__device__ __forceinline__ Best block_best(Best v, uint64_t* s_key, double* s_obj)
+{
+    v = wave_best(v);
+    const uint32_t wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { s_key[wave] = v.key; s_obj[wave] = v.obj; }
+    __syncthreads();
+    Best r; r.key = s_key[0]; r.obj = s_obj[0];
+    for (int w = 1; w < 4; ++w) { Best o; o.key = s_key[w]; o.obj = s_obj[w]; r = pick(r, o); }
+    return r;
+}
+
 // ---- prune ------------------------------------------------------------------------------
 // One block per (instance, task).  Dynamic LDS: per choice lat, cost, rep (u32),
 // acc (f64), two flag bytes.
@@ -362,7 +428,10 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         uint32_t* k = pl.k32 + ((size_t)i * pl.t_max + t) * pl.k_max;
         for (uint32_t d = tid; d < in->K[t]; d += blockDim.x) k[d] = (e[d].cost << s_lb) | (d * s_ls[p]);
     }
-    for (uint32_t b = tid; b < pl.grid; b += blockDim.x) pl.partial[(size_t)i * pl.grid + b] = NO_KEY;
+    for (uint32_t b = tid; b < pl.grid; b += blockDim.x) {
+        pl.partial[(size_t)i * pl.grid + b] = NO_KEY;
+        pl.partial_obj[(size_t)i * pl.grid + b] = -__builtin_inf();
+    }
 }
 
 // Single block: exclusive scan of the tile counts, total, counters reset.
@@ -402,6 +471,7 @@ struct LaneState {
     double   sacc;      // sum of H over sources seen so far
     uint64_t key;       // sum of the 64-bit keys of the fixed positions
     uint32_t k32;       // sum of the 32-bit local keys of the fixed in-lane positions
+    uint32_t cost_out;  // cost of the positions outside the lane loops (objective mode)
 };
 
 struct Uniforms {       // wave-uniform facts about positions 0..2
@@ -414,6 +484,9 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     double   w01, w02, w12;   // share of a among the predecessors of b (0 if no edge)
     uint32_t sloq;      // floor(SLO_l / q)
     double   slo_raw;   // SLO_a * A_max
+    // objective mode (Eq. 14)
+    uint32_t idx_bits, lb, capacity;
+    double   alpha_n, beta;   // objective = alpha_n * A_raw - beta * cost
 };
 
 // Fix position P (a wave-uniform entry) and push its contribution down.  hin[P]
@@ -529,46 +602,129 @@ __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, 
     best32 = best32 < cand ? best32 : cand;
 }
 
-template <bool W32>
-__device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       uint64_t full, uint64_t& best, uint32_t& best32)
+// Objective mode, 64-bit keys: every candidate gets its objective and the
+// lexicographic (objective, key) maximum.
+__device__ __forceinline__ void loop_x64_obj(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
+                                             Best& best)
 {
-    if constexpr (W32) loop_x32(s, U, lo, hi, full, best32);
-    else loop_x64(s, U, lo, hi, best);
+    const uint32_t worst = umax(s.smax, s.nxt[0]);
+    const uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;
+    const double cx = s.hin[0];
+    const Entry JSV_CONST* tx = U.tab[0];
+    for (uint32_t d = lo; d < hi; ++d) {
+        const uint32_t lat = tx[d].lat;
+        const uint64_t k = s.key + tx[d].key;
+        const double A = __builtin_fma(tx[d].acc, cx, s.sacc);
+        const uint32_t cost = (uint32_t)(k >> U.idx_bits);
+        const bool ok = (lat <= thr) & (A >= U.slo_raw) & (U.capacity == 0 || cost <= U.capacity);   // Eq. 3, 13, 8
+        const double obj = __builtin_fma(-U.beta, (double)cost, U.alpha_n * A);
+        if (ok && better(obj, k, best.obj, best.key)) { best.obj = obj; best.key = k; }
+    }
 }
 
-template <bool W32>
+// Objective mode, 32-bit local keys.  All candidates of one variant of position 0
+// (other digits fixed) share their accuracy, so the one with the best objective is
+// the cheapest feasible one: per variant the same masked minimum as in cost mode,
+// then one objective and one (objective, key) comparison for the variant's winner.
+// A variant whose cheapest candidate exceeds S_avail has no candidate within it.
+struct TileBest { uint32_t k32; double obj; };
+
+__device__ __forceinline__ void fold_variant(const LaneState& s, const Uniforms& U, uint32_t m, double t, TileBest& tb)
+{
+    const uint32_t k = __builtin_elementwise_add_sat(s.k32, m);
+    const uint32_t cost = s.cost_out + (k >> U.lb);
+    const bool hit = (m != 0xFFFFFFFFu) & (U.capacity == 0 || cost <= U.capacity);
+    const double obj = __builtin_fma(-U.beta, (double)cost, U.alpha_n * t);
+    if (hit && (obj > tb.obj || (obj == tb.obj && k < tb.k32))) { tb.obj = obj; tb.k32 = k; }
+}
+
+__device__ __forceinline__ void loop_x32_obj(const LaneState& s, const Uniforms& U, uint32_t qlo, uint32_t qhi,
+                                             uint64_t full, TileBest& tb)
+{
+    const uint64_t alive = __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
+    const uint32_t thr = __builtin_elementwise_sub_sat(U.sloq, s.nxt[0]);
+    const Quad JSV_CONST* q = U.quads;
+    uint32_t m = 0xFFFFFFFFu;
+    double t = 0.0;
+    uint64_t ok = 0;
+    for (uint32_t j = qlo; j < qhi; ++j) {
+        if (q[j].newgrp != 0) {
+            fold_variant(s, U, m, t, tb);
+            t = __builtin_fma(q[j].acc, s.hin[0], s.sacc);
+            ok = alive & __builtin_amdgcn_ballot_w64(t >= U.slo_raw);
+            m = 0xFFFFFFFFu;
+        }
+#if defined(__HIP_DEVICE_COMPILE__)
+        // the quad's candidates in ascending latency under the variant's mask (see loop_x32)
+        asm volatile(
+            "s_mov_b64 exec, %[ok]\n\t"
+            "v_cmpx_le_u32_e32 vcc, %[l0], %[thr]\n\t"
+            "v_min_u32_e32 %[m], %[k0], %[m]\n\t"
+            "v_cmpx_le_u32_e32 vcc, %[l1], %[thr]\n\t"
+            "v_min_u32_e32 %[m], %[k1], %[m]\n\t"
+            "v_cmpx_le_u32_e32 vcc, %[l2], %[thr]\n\t"
+            "v_min_u32_e32 %[m], %[k2], %[m]\n\t"
+            "v_cmpx_le_u32_e32 vcc, %[l3], %[thr]\n\t"
+            "v_min_u32_e32 %[m], %[k3], %[m]\n\t"
+            "s_mov_b64 exec, %[full]\n\t"
+            "s_nop 1"
+            : [m] "+v"(m)
+            : [ok] "s"(ok), [full] "s"(full), [thr] "v"(thr),
+              [l0] "s"(q[j].e[0].lat), [k0] "s"(q[j].e[0].k32), [l1] "s"(q[j].e[1].lat), [k1] "s"(q[j].e[1].k32),
+              [l2] "s"(q[j].e[2].lat), [k2] "s"(q[j].e[2].k32), [l3] "s"(q[j].e[3].lat), [k3] "s"(q[j].e[3].k32)
+            : "vcc");
+#else
+        (void)thr; (void)full; (void)ok;
+#endif
+    }
+    fold_variant(s, U, m, t, tb);
+}
+
+template <bool W32, bool OBJ>
+__device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
+                                       uint64_t full, Best& best, TileBest& tb)
+{
+    if constexpr (OBJ) {
+        if constexpr (W32) loop_x32_obj(s, U, lo, hi, full, tb);
+        else loop_x64_obj(s, U, lo, hi, best);
+    } else {
+        if constexpr (W32) loop_x32(s, U, lo, hi, full, tb.k32);
+        else loop_x64(s, U, lo, hi, best.key);
+    }
+}
+
+template <bool W32, bool OBJ>
 __device__ __forceinline__ void loop_y(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       uint32_t x_hi, uint64_t full, uint64_t& best, uint32_t& best32)
+                                       uint32_t x_hi, uint64_t full, Best& best, TileBest& tb)
 {
     const Entry JSV_CONST* ty = U.tab[1];
     for (uint32_t d = lo; d < hi; ++d) {
         const LaneState s1 = fix_position<1>(s, U, ty[d].lat, ty[d].acc, W32 ? 0 : ty[d].key,
                                              W32 ? U.k32[1][d] : 0u);
-        loop_x<W32>(s1, U, 0, x_hi, full, best, best32);
+        loop_x<W32, OBJ>(s1, U, 0, x_hi, full, best, tb);
     }
 }
 
-template <bool W32>
+template <bool W32, bool OBJ>
 __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                       uint32_t x_hi, uint64_t full, uint64_t& best, uint32_t& best32)
+                                       uint32_t x_hi, uint64_t full, Best& best, TileBest& tb)
 {
     const Entry JSV_CONST* tz = U.tab[2];
     for (uint32_t d = lo; d < hi; ++d) {
         const LaneState s2 = fix_position<2>(s, U, tz[d].lat, tz[d].acc, W32 ? 0 : tz[d].key,
                                              W32 ? U.k32[2][d] : 0u);
-        loop_y<W32>(s2, U, 0, U.K[1], x_hi, full, best, best32);
+        loop_y<W32, OBJ>(s2, U, 0, U.K[1], x_hi, full, best, tb);
     }
 }
 
 // One tile: 256 lanes, each a different combination of the positions >= NIN
 // (decoded from the mixed-radix outer index), all looping over the same digits of
 // positions < NIN.
-template <int NIN, bool W32>
+template <int NIN, bool W32, bool OBJ>
 __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instance JSV_CONST* in,
                                          const Entry JSV_CONST* tab, const uint32_t JSV_CONST* k32,
                                          const Quad JSV_CONST* quads, const Entry* s_tab, uint32_t k_max,
-                                         uint64_t group, uint32_t chunk_id, uint64_t& best)
+                                         uint64_t group, uint32_t chunk_id, Best& best)
 {
     const uint32_t T = g->T;
     uint64_t o = group * TILE_LANES + threadIdx.x;
@@ -638,22 +794,26 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     U.w01 = g->w[0][1]; U.w02 = g->w[0][2]; U.w12 = g->w[1][2];
     U.sloq = in->slo_l / g->q;
     U.slo_raw = in->slo_raw;
+    U.idx_bits = in->idx_bits; U.lb = in->lb; U.capacity = g->capacity;
+    U.alpha_n = in->alpha_n; U.beta = in->beta;
+    st.cost_out = (uint32_t)(st.key >> in->idx_bits);
 
     // extent of the innermost loop (quads of the stream, or digits) and of the chunked loop
     const uint32_t x_all = W32 ? in->nq : U.K[0];
     const uint32_t Ko = NIN == 1 ? x_all : U.K[NIN - 1];
     const uint32_t lo = chunk_id * in->chunk;
     const uint32_t hi = lo + in->chunk < Ko ? lo + in->chunk : Ko;
-    uint32_t best32 = 0xFFFFFFFFu;
+    TileBest tb;
+    tb.k32 = 0xFFFFFFFFu; tb.obj = -__builtin_inf();
     const uint64_t full = __builtin_amdgcn_read_exec();     // the loops below run convergent
-    if constexpr (NIN == 3) loop_z<W32>(st, U, lo, hi, x_all, full, best, best32);
-    else if constexpr (NIN == 2) loop_y<W32>(st, U, lo, hi, x_all, full, best, best32);
-    else loop_x<W32>(st, U, lo, hi, full, best, best32);
+    if constexpr (NIN == 3) loop_z<W32, OBJ>(st, U, lo, hi, x_all, full, best, tb);
+    else if constexpr (NIN == 2) loop_y<W32, OBJ>(st, U, lo, hi, x_all, full, best, tb);
+    else loop_x<W32, OBJ>(st, U, lo, hi, full, best, tb);
 
     if constexpr (W32) {
         // the lane's 32-bit winner of this tile -> its full (cost, index) key
-        const bool hit = best32 != 0xFFFFFFFFu;
-        uint32_t r = hit ? (best32 & ((1u << in->lb) - 1u)) : 0u;
+        const bool hit = tb.k32 != 0xFFFFFFFFu;
+        uint32_t r = hit ? (tb.k32 & ((1u << in->lb) - 1u)) : 0u;
         uint64_t k = st.key;
 #pragma unroll
         for (int a = 0; a < NIN; ++a) {
@@ -664,7 +824,27 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
             r /= K;
             k += s_tab[t * k_max + d].key;
         }
-        best = (hit && k < best) ? k : best;
+        if constexpr (OBJ) {
+            if (hit && better(tb.obj, k, best.obj, best.key)) { best.obj = tb.obj; best.key = k; }
+        } else {
+            best.key = (hit && k < best.key) ? k : best.key;
+        }
+    }
+}
+
+// A block's result for one instance: its lanes' best reduced over the block.
+template <bool OBJ>
+__device__ __forceinline__ void flush_block(const Plan& pl, uint32_t inst, const Best& best, uint64_t* s_key, double* s_obj)
+{
+    if constexpr (OBJ) {
+        const Best b = block_best(best, s_key, s_obj);
+        if (threadIdx.x == 0) {
+            pl.partial[(size_t)inst * pl.grid + blockIdx.x] = b.key;
+            pl.partial_obj[(size_t)inst * pl.grid + blockIdx.x] = b.obj;
+        }
+    } else {
+        const uint64_t m = block_min(best.key, s_key);
+        if (threadIdx.x == 0) pl.partial[(size_t)inst * pl.grid + blockIdx.x] = m;
     }
 }
 
@@ -674,11 +854,13 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
 // the instances in ascending order; it keeps one running minimum per lane and
 // reduces it (wave, then block) only when the instance changes.  Every block ends
 // with the first ticket at or past the total.
+template <bool OBJ>
 __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
 {
     extern __shared__ __attribute__((aligned(32))) unsigned char smem_raw[];
     Entry* s_tab = (Entry*)smem_raw;
     __shared__ uint64_t s_red[4];
+    __shared__ double s_red_obj[4];
     __shared__ unsigned long long s_tile;
 
     const Instance JSV_CONST* insts = as_uniform((const Instance*)pl.inst);
@@ -688,7 +870,8 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
 
     uint32_t cur = 0xFFFFFFFFu;     // instance whose tables are in LDS
     uint32_t scan = 0;              // instance search cursor
-    uint64_t best = NO_KEY;
+    Best best;
+    best.key = NO_KEY; best.obj = -__builtin_inf();
     for (;;) {
         __syncthreads();                                  // everyone has read the last ticket
         if (threadIdx.x == 0) s_tile = atomicAdd(&pl.summary->next_tile, 1ull);
@@ -700,8 +883,7 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         while (scan + 1 < pl.n_inst && insts[scan + 1].tile_begin <= tile) ++scan;
         if (scan != cur) {
             if (cur != 0xFFFFFFFFu) {
-                const uint64_t m = block_min(best, s_red);
-                if (threadIdx.x == 0) pl.partial[(size_t)cur * pl.grid + blockIdx.x] = m;
+                flush_block<OBJ>(pl, cur, best, s_red, s_red_obj);
             }
             __syncthreads();
             const Entry* src = pl.entries + (size_t)scan * tk;
@@ -710,7 +892,7 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
             for (uint32_t k = threadIdx.x; k < tk * 2; k += blockDim.x) d4[k] = s4[k];
             __syncthreads();
             cur = scan;
-            best = NO_KEY;
+            best.key = NO_KEY; best.obj = -__builtin_inf();
         }
         const Instance JSV_CONST* in = insts + cur;
         const Graph JSV_CONST* g = graphs + in->problem;
@@ -723,21 +905,20 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const uint64_t group = local / n_chunks;
         if (in->use32) {
             switch (in->n_in) {
-            case 3: run_tile<3, true>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
-            case 2: run_tile<2, true>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
-            default: run_tile<1, true>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            case 3: run_tile<3, true, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            case 2: run_tile<2, true, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            default: run_tile<1, true, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
             }
         } else {
             switch (in->n_in) {
-            case 3: run_tile<3, false>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
-            case 2: run_tile<2, false>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
-            default: run_tile<1, false>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            case 3: run_tile<3, false, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            case 2: run_tile<2, false, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            default: run_tile<1, false, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
             }
         }
     }
     if (cur != 0xFFFFFFFFu) {
-        const uint64_t m = block_min(best, s_red);
-        if (threadIdx.x == 0) pl.partial[(size_t)cur * pl.grid + blockIdx.x] = m;
+        flush_block<OBJ>(pl, cur, best, s_red, s_red_obj);
     }
 }
 
@@ -782,18 +963,28 @@ __device__ Score score_digits(const Graph* g, const Instance* in, const Entry* e
 __global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
 {
     __shared__ uint64_t s_red[4];
+    __shared__ double s_red_obj[4];
     const uint32_t i = blockIdx.x;
     const Instance* in = pl.inst + i;
     const Graph* g = pl.graphs + in->problem;
     uint64_t m = NO_KEY;
-    for (uint32_t b = threadIdx.x; b < pl.grid; b += blockDim.x)
-        m = umin64(m, pl.partial[(size_t)i * pl.grid + b]);
-    m = block_min(m, s_red);
+    if (pl.objective) {
+        Best v; v.key = NO_KEY; v.obj = -__builtin_inf();
+        for (uint32_t b = threadIdx.x; b < pl.grid; b += blockDim.x) {
+            Best o; o.key = pl.partial[(size_t)i * pl.grid + b]; o.obj = pl.partial_obj[(size_t)i * pl.grid + b];
+            v = pick(v, o);
+        }
+        m = block_best(v, s_red, s_red_obj).key;
+    } else {
+        for (uint32_t b = threadIdx.x; b < pl.grid; b += blockDim.x)
+            m = umin64(m, pl.partial[(size_t)i * pl.grid + b]);
+        m = block_min(m, s_red);
+    }
     if (threadIdx.x != 0) return;
 
     ResultRec* r = pl.results + i;
     r->index = NO_KEY; r->full_index = NO_KEY; r->evaluated = in->space;
-    r->accuracy = 0.0; r->latency_us = 0; r->cost_units = 0x7FFFFFFF; r->feasible = 0;
+    r->accuracy = 0.0; r->latency_us = 0; r->cost_units = 0x7FFFFFFF; r->feasible = 0; r->objective = 0.0;
     r->flags = in->flags;
     for (int t = 0; t < MAXT; ++t) { r->choice[t] = 0; r->replicas[t] = 0; }
     if (m != NO_KEY && !(in->flags & (F_OVERFLOW | F_EMPTY))) {
@@ -805,6 +996,7 @@ __global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
         if (sc.mask == 7) {                 // only the capacity bit can still be missing
             r->index = idx; r->feasible = 1;
             r->accuracy = sc.accuracy; r->latency_us = sc.latency; r->cost_units = (int32_t)sc.cost;
+            r->objective = in->alpha * sc.accuracy - in->beta * (double)sc.cost;
             uint64_t full = 0;
             bool over = false;
             for (int t = (int)g->T - 1; t >= 0; --t) {
@@ -870,21 +1062,28 @@ hipError_t launch_prune_plan_scan(const Plan& pl, hipStream_t stream)
 }
 
 // Blocks of the enumeration kernel that are resident per CU with this much LDS.
-hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, int* blocks)
+hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, bool objective, int* blocks)
 {
     const size_t lds = enumerate_lds_bytes(t_max, k_max);
     if (lds > 32 * 1024) {      // beyond the default dynamic limit: ask for it explicitly
-        hipError_t e = hipFuncSetAttribute((const void*)enumerate_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = objective ? hipFuncSetAttribute((const void*)enumerate_kernel<true>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                                 : hipFuncSetAttribute((const void*)enumerate_kernel<false>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, (const void*)enumerate_kernel, TILE_LANES, lds);
+    return objective ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, (const void*)enumerate_kernel<true>, TILE_LANES, lds)
+                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, (const void*)enumerate_kernel<false>, TILE_LANES, lds);
 }
 
 hipError_t launch_enumerate(const Plan& pl, hipStream_t stream)
 {
-    hipLaunchKernelGGL(enumerate_kernel, dim3(pl.grid), dim3(TILE_LANES),
-                       enumerate_lds_bytes(pl.t_max, pl.k_max), stream, pl);
+    if (pl.objective)
+        hipLaunchKernelGGL(enumerate_kernel<true>, dim3(pl.grid), dim3(TILE_LANES),
+                           enumerate_lds_bytes(pl.t_max, pl.k_max), stream, pl);
+    else
+        hipLaunchKernelGGL(enumerate_kernel<false>, dim3(pl.grid), dim3(TILE_LANES),
+                           enumerate_lds_bytes(pl.t_max, pl.k_max), stream, pl);
     return hipGetLastError();
 }
 

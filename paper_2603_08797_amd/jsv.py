@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libjsv.so")
 MAX_TASKS = 16
 OK, E_NULL, E_BADARG, E_CYCLE, E_OVERFLOW, E_STATE, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6, -7
 
-EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string",
+EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective",
            "jsv_workspace_bytes", "jsv_set_workspace", "jsv_load_profile", "jsv_set_dag",
            "jsv_search", "jsv_eval_candidates", "jsv_get_pruned", "jsv_load_batch",
            "jsv_search_loaded_batch", "jsv_search_batch"]
@@ -30,7 +30,8 @@ class JsvResult(C.Structure):
     _fields_ = [("index", C.c_uint64), ("full_index", C.c_uint64), ("evaluated", C.c_uint64),
                 ("accuracy", C.c_double), ("latency_us", C.c_uint32), ("cost_units", C.c_int32),
                 ("feasible", C.c_uint32), ("flags", C.c_uint32),
-                ("choice", C.c_uint16 * MAX_TASKS), ("replicas", C.c_uint32 * MAX_TASKS)]
+                ("choice", C.c_uint16 * MAX_TASKS), ("replicas", C.c_uint32 * MAX_TASKS),
+                ("objective", C.c_double)]
 
 
 class JsvSummary(C.Structure):
@@ -70,6 +71,8 @@ def load_library():
     lib.jsv_last_hip_error.argtypes = [vp]
     lib.jsv_error_string.restype = C.c_char_p
     lib.jsv_error_string.argtypes = [C.c_int]
+    lib.jsv_set_objective.restype = C.c_int
+    lib.jsv_set_objective.argtypes = [vp, C.c_int, f64, f64]
     lib.jsv_workspace_bytes.restype = C.c_size_t
     lib.jsv_workspace_bytes.argtypes = [vp, u32, u32]
     lib.jsv_set_workspace.restype = C.c_int
@@ -114,6 +117,7 @@ class Result:
     flags: int
     choice: List[int]
     replicas: List[int]
+    objective: float = 0.0
 
 
 @dataclass
@@ -135,7 +139,8 @@ def _ptr(a: Optional[np.ndarray]):
 def _result(r: JsvResult, T: int) -> Result:
     return Result(int(r.index), int(r.full_index), int(r.evaluated), float(r.accuracy),
                   int(r.latency_us), int(r.cost_units), bool(r.feasible), int(r.flags),
-                  [int(r.choice[t]) for t in range(T)], [int(r.replicas[t]) for t in range(T)])
+                  [int(r.choice[t]) for t in range(T)], [int(r.replicas[t]) for t in range(T)],
+                  float(r.objective))
 
 
 class Jsv:
@@ -182,6 +187,11 @@ class Jsv:
     def _check(self, rc: int, where: str):
         if rc != OK:
             raise JsvError(rc, where, self._lib.jsv_last_hip_error(self._h))
+
+    def set_objective(self, mode: int, alpha: float = 1.0, beta: float = 0.035):
+        """mode 0: cheapest feasible; mode 1: maximise alpha*A_obj - beta*cost (Eq. 14)."""
+        self._check(self._lib.jsv_set_objective(self._h, int(mode), float(alpha), float(beta)),
+                    "jsv_set_objective")
 
     # -- inputs ------------------------------------------------------------------
     def load_profile(self, T, V, P, B, units, batch, latency_us, thr_mrps, accuracy):

@@ -22,7 +22,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_sizes_match_the_header():
     import ctypes
-    assert ctypes.sizeof(jsv.JsvResult) == 8 * 4 + 4 * 4 + 2 * 16 + 4 * 16
+    assert ctypes.sizeof(jsv.JsvResult) == 8 * 4 + 4 * 4 + 2 * 16 + 4 * 16 + 8
     assert ctypes.sizeof(jsv.JsvSummary) == 24
 
 
@@ -90,6 +90,15 @@ def test_search_argument_and_state_errors(ctx):
     assert code(ctx.search, [1000], 1000, float("nan"), 0) == jsv.E_BADARG
     assert code(ctx.search, [1000], 1000, 0.5, 2 * pb.V - 1) == jsv.E_BADARG
     assert code(ctx.get_pruned, 1000, 1000, 0, 3) == jsv.E_BADARG           # task out of range
+
+
+def test_objective_arguments(ctx):
+    ctx.set_objective(1, 1.0, 0.035)
+    ctx.set_objective(0)
+    assert code(ctx.set_objective, 2, 1.0, 0.035) == jsv.E_BADARG
+    assert code(ctx.set_objective, 1, -1.0, 0.035) == jsv.E_BADARG
+    assert code(ctx.set_objective, 1, 1.0, float("nan")) == jsv.E_BADARG
+    assert code(ctx.set_objective, 1, float("inf"), 0.0) == jsv.E_BADARG
 
 
 def test_workspace_size_and_alignment(ctx):
