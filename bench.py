@@ -64,11 +64,13 @@ PAPER_CONTEXT = ("paper (other hardware, context only): MILP solve 2-20 s per in
                  "(4x H100 SXM 80GB)")
 
 
-def cpu_baseline(w, seconds_target: float = 12.0):
+def cpu_baseline(w, objective: bool, seconds_target: float = 12.0):
     """The oracle, as it is, on a bounded slice of the first demand level."""
     import oracle
     pb, se = w.problems[0], w.searches[0]
     o = oracle.Oracle.from_problem(pb)
+    if objective:
+        o.set_objective(1, 1.0, 0.035)
     threads = max(1, min(oracle.max_threads(), os.cpu_count() or 1))
     D = int(se.demand_mrps[0])
     K, space, _ = o.space(D, se.slo_latency_us, se.prune_cap)
@@ -94,6 +96,8 @@ def main():
     ap.add_argument("--workload", default="xr8", choices=["chain3", "diamond5", "chain4", "xr8", "dagbatch"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--objective", action="store_true",
+                    help="maximise alpha*A_obj - beta*cost (alpha 1, beta 0.035) instead of minimum cost")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (--gpus 1); sharding is described in DESIGN.md")
@@ -106,6 +110,8 @@ def main():
     w = workloads.BENCH_WORKLOADS[args.workload](seed=args.seed)
     stream = torch.cuda.Stream(device=0)
     j = jsv.Jsv(device=0, stream=stream)
+    if args.objective:
+        j.set_objective(1, 1.0, 0.035)
     batch = len(w.problems) > 1
     if batch:
         j.load_batch(w.problems, w.searches)
@@ -150,6 +156,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32+f64", "data": "synthetic",
         "config": {"workload": f"{w.name} seed {args.seed}: {w.note}", "levels_or_problems": n_levels,
+                   "objective": "alpha*A_obj - beta*cost, alpha 1, beta 0.035" if args.objective else "minimum cost",
                    "candidates_per_step": candidates,
                    "feasible_levels": sum(1 for r in res if r.feasible),
                    "max_serviceable_demand_mrps": summ.max_demand_mrps},
@@ -163,7 +170,7 @@ def main():
         "context": PAPER_CONTEXT,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w, args.objective)
     j.close()
     print(json.dumps(out))
 
