@@ -134,6 +134,8 @@ struct SummaryRec {
     uint32_t done_count;      // finalize blocks finished
     uint32_t any_flags;       // OR of all instance flags
     unsigned long long next_tile;   // work counter of the enumeration kernel
+    uint32_t plan_done;       // plan blocks finished
+    uint32_t pad;
 };
 
 // Everything the kernels need to find their data; passed by value.

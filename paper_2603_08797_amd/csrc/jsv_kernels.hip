@@ -3,8 +3,8 @@
 //   prune_kernel      replicas and cost of every (task, choice) at every level
 //                     (Eq. 5-7), then the per-task prune: latency filter, exact
 //                     dominance, cap thinning, compaction.
-//   plan_kernel       index strides, packed keys, tile geometry per instance.
-//   scan_kernel       exclusive scan of the tile counts.
+//   plan_kernel       index strides, packed keys, local keys and the innermost stream,
+//                     tile geometry per instance; its last block scans the tile counts.
 //   enumerate_kernel  every candidate scored and masked (Eq. 3, 8, 11-13) and
 //                     reduced to the cheapest feasible one per lane / wave / block.
 //   finalize_kernel   grid-level minimum, winner decoded and rescored, summary.
@@ -167,6 +167,7 @@ __global__ void __launch_bounds__(256) prune_kernel(Plan pl)
     uint8_t*  s_k    = s_a + C;                  // kept
     __shared__ uint32_t s_left, s_flags;
     if (tid == 0) { s_left = 0; s_flags = 0; }
+    if (blockIdx.x == 0 && tid == 0) pl.summary->plan_done = 0;     // counted up by the plan kernel
 
     // Eq. 5-7: demand at the task, replicas (at least one), cost in partition units
     const uint64_t need = (uint64_t)in->demand * g->mult[t];            // micro-requests / s
@@ -267,23 +268,62 @@ __global__ void __launch_bounds__(256) prune_kernel(Plan pl)
 }
 
 // ---- plan -------------------------------------------------------------------------------
+// Exclusive scan of the tile counts over the instances, total, counters reset; run by
+// the last plan block to finish.
+__device__ void scan_tiles(const Plan& pl, uint64_t* s_sum)
+{
+    const uint32_t tid = threadIdx.x, n = pl.n_inst;
+    const uint32_t per = (n + 255) / 256;
+    const uint32_t lo = tid * per, hi = (lo + per < n) ? lo + per : n;
+    const volatile Instance* inst = pl.inst;          // written by other blocks
+    uint64_t sum = 0;
+    for (uint32_t k = lo; k < hi; ++k) sum += inst[k].tiles;
+    s_sum[tid] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        uint64_t run = 0;
+        for (uint32_t k = 0; k < 256; ++k) { const uint64_t v = s_sum[k]; s_sum[k] = run; run += v; }
+        pl.summary->total_tiles = run;
+        pl.summary->done_count = 0;
+        pl.summary->next_tile = pl.grid;           // tiles 0..grid-1 go to the blocks by index
+        pl.summary->any_flags = 0;
+        pl.summary->best_level = -1;
+        pl.summary->max_demand = 0;
+    }
+    __syncthreads();
+    uint64_t run = s_sum[tid];
+    for (uint32_t k = lo; k < hi; ++k) { pl.inst[k].tile_begin = run; run += inst[k].tiles; }
+}
+
 // One block per instance: strides of the caller's index order, key packing, choice
-// of how many positions a lane loops over, tile geometry, reset of the partials.
+// of how many positions a lane loops over, tile geometry, local keys and the stream
+// of the innermost position, reset of the partials.  The last block to finish scans
+// the tile counts (plan_done is zeroed by the prune kernel, which runs before).
 __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
 {
     const uint32_t i = blockIdx.x, tid = threadIdx.x;
     Instance* in = pl.inst + i;
     const Graph* g = pl.graphs + in->problem;
     const uint32_t T = g->T;
-    __shared__ uint32_t s_maxcost[MAXT];
-    __shared__ uint32_t s_bits, s_lb, s_nin, s_ls[3];
-    __shared__ uint32_t s_xq0[MAXC];        // first quad of the variant that starts at digit d
-    if (tid < MAXT) s_maxcost[tid] = 0;
+    __shared__ uint32_t s_maxcost[MAXT], s_K[MAXT];
+    __shared__ uint32_t s_bits, s_lb, s_nin, s_ls[3], s_chunk, s_nq, s_last;
+    __shared__ uint64_t s_stride[MAXT];
+    // the innermost position's entries, staged once: variant, latency, cost, and the first
+    // quad of the variant that starts at digit d
+    __shared__ uint16_t s_xvar[MAXC];
+    __shared__ uint32_t s_xlat[MAXC], s_xcost[MAXC], s_xq0[MAXC];
+    __shared__ uint64_t s_sum[256];
+    if (tid < MAXT) { s_maxcost[tid] = 0; s_K[tid] = tid < T ? in->K[tid] : 0; }
     __syncthreads();
+    const uint32_t tx = g->task_at[0], PB = g->P * g->B, KX = s_K[tx];
     for (uint32_t t = 0; t < T; ++t) {
         const Entry* e = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
         uint32_t m = 0;
-        for (uint32_t d = tid; d < in->K[t]; d += blockDim.x) m = umax(m, e[d].cost);
+        for (uint32_t d = tid; d < s_K[t]; d += blockDim.x) {
+            const uint32_t c = e[d].cost;
+            m = umax(m, c);
+            if (t == tx) { s_xcost[d] = c; s_xlat[d] = e[d].lat; s_xvar[d] = (uint16_t)(e[d].choice / PB); }
+        }
         if (m) atomicMax(&s_maxcost[t], m);
     }
     __syncthreads();
@@ -291,8 +331,9 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         uint64_t space = 1, cost_bound = 0;
         bool over = false;
         for (uint32_t t = 0; t < T; ++t) {
+            s_stride[t] = space;
             in->stride[t] = space;
-            const uint64_t k = in->K[t];
+            const uint64_t k = s_K[t];
             if (k != 0 && __umul64hi(space, k) != 0) over = true;
             space *= k;
             cost_bound += s_maxcost[t];
@@ -310,7 +351,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
 
         // how many leading positions a lane loops over, and the tile geometry
         uint32_t Kp[MAXT];
-        for (uint32_t p = 0; p < T; ++p) Kp[p] = in->K[g->task_at[p]];
+        for (uint32_t p = 0; p < T; ++p) Kp[p] = s_K[g->task_at[p]];
         uint32_t n_in = 1;
         uint64_t s_out = 0;
         const uint32_t n_top = T < 3 ? T : 3;
@@ -342,14 +383,11 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         }
         if (use32) {
             // quads of position 0's stream: every variant's entries rounded up to whole quads
-            // (the stream itself is written by all threads below; s_xq0 = first quad per variant start)
-            const uint32_t tx = g->task_at[0], PB = g->P * g->B;
-            const Entry* ex = pl.entries + ((size_t)i * pl.t_max + tx) * pl.k_max;
             uint32_t d = 0;
-            while (d < Kp[0]) {
-                const uint32_t var = ex[d].choice / PB;
+            while (d < KX) {
+                const uint32_t var = s_xvar[d];
                 uint32_t d1 = d;
-                while (d1 < Kp[0] && ex[d1].choice / PB == var) ++d1;
+                while (d1 < KX && s_xvar[d1] == var) ++d1;
                 s_xq0[d] = nq;
                 nq += (d1 - d + 3) / 4;
                 d = d1;
@@ -381,83 +419,62 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         if (space != 0 && !use32) atomicOr(&in->flags, F_WIDE);
         for (int a = 0; a < 3; ++a) { in->ord[a] = ord[a]; s_ls[a] = ls[a]; }
         s_bits = idx_bits; s_lb = lb; s_nin = use32 ? n_in : 0;
+        s_chunk = (use32 && n_in == 1) ? chunk : 0; s_nq = nq;
     }
     __syncthreads();
     // packed keys: (cost << idx_bits) | digit * stride
     const uint32_t idx_bits = s_bits;
     for (uint32_t t = 0; t < T; ++t) {
         Entry* e = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
-        const uint64_t stride = in->stride[t];
-        for (uint32_t d = tid; d < in->K[t]; d += blockDim.x)
+        const uint64_t stride = s_stride[t];
+        for (uint32_t d = tid; d < s_K[t]; d += blockDim.x)
             e[d].key = ((uint64_t)e[d].cost << idx_bits) | ((uint64_t)d * stride);
     }
     // stream of position 0: by variant, inside a variant by ascending latency (so that the
     // lanes still feasible only shrink along a variant), each variant padded to whole quads
     if (s_nin != 0) {
-        const uint32_t tx = g->task_at[0], PB = g->P * g->B, K = in->K[tx];
         const Entry* ex = pl.entries + ((size_t)i * pl.t_max + tx) * pl.k_max;
         Quad* qd = pl.quads + (size_t)i * pl.k_max;
-        for (uint32_t d = tid; d < K; d += blockDim.x) {
-            const uint32_t var = ex[d].choice / PB, lat = ex[d].lat;
+        for (uint32_t d = tid; d < KX; d += blockDim.x) {
+            const uint32_t var = s_xvar[d], lat = s_xlat[d];
             uint32_t d0 = d, d1 = d + 1, rank = 0;
-            while (d0 > 0 && ex[d0 - 1].choice / PB == var) --d0;
-            while (d1 < K && ex[d1].choice / PB == var) ++d1;
-            for (uint32_t x = d0; x < d1; ++x) rank += (ex[x].lat < lat || (ex[x].lat == lat && x < d)) ? 1u : 0u;
+            while (d0 > 0 && s_xvar[d0 - 1] == var) --d0;
+            while (d1 < KX && s_xvar[d1] == var) ++d1;
+            for (uint32_t x = d0; x < d1; ++x) rank += (s_xlat[x] < lat || (s_xlat[x] == lat && x < d)) ? 1u : 0u;
             const uint32_t q0 = s_xq0[d0], n = d1 - d0, quads = (n + 3) / 4;
             XEnt me;
             me.lat = lat;
-            me.k32 = (ex[d].cost << s_lb) | (d * s_ls[0]);
+            me.k32 = (s_xcost[d] << s_lb) | (d * s_ls[0]);
             qd[q0 + rank / 4].e[rank % 4] = me;
             if (d == d0) {                                   // the variant's first digit writes headers and padding
+                const double acc = ex[d].acc;
                 for (uint32_t j = 0; j < quads; ++j) {
-                    qd[q0 + j].acc = ex[d].acc;
-                    qd[q0 + j].newgrp = j == 0 ? 1u : 0u;
+                    qd[q0 + j].acc = acc;
+                    // the accuracy test is (re)done where a variant starts and where a tile's range starts
+                    qd[q0 + j].newgrp = (j == 0 || (s_chunk != 0 && (q0 + j) % s_chunk == 0)) ? 1u : 0u;
                     for (int z = 0; z < 5; ++z) qd[q0 + j].pad[z] = 0;
                 }
                 for (uint32_t r = n; r < quads * 4; ++r) { qd[q0 + r / 4].e[r % 4].lat = 0xFFFFFFFFu; qd[q0 + r / 4].e[r % 4].k32 = 0xFFFFFFFFu; }
             }
         }
-        // every tile's range of quads must start with the accuracy test
-        __syncthreads();
-        if (in->n_in == 1) for (uint32_t j = tid * in->chunk; j < in->nq; j += blockDim.x * in->chunk) qd[j].newgrp = 1;
     }
     // 32-bit local keys of the in-lane positions: (cost << lb) | digit * local stride
     for (uint32_t p = 0; p < s_nin; ++p) {
         const uint32_t t = g->task_at[p];
         const Entry* e = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
         uint32_t* k = pl.k32 + ((size_t)i * pl.t_max + t) * pl.k_max;
-        for (uint32_t d = tid; d < in->K[t]; d += blockDim.x) k[d] = (e[d].cost << s_lb) | (d * s_ls[p]);
+        for (uint32_t d = tid; d < s_K[t]; d += blockDim.x) k[d] = (e[d].cost << s_lb) | (d * s_ls[p]);
     }
     for (uint32_t b = tid; b < pl.grid; b += blockDim.x) {
         pl.partial[(size_t)i * pl.grid + b] = NO_KEY;
         pl.partial_obj[(size_t)i * pl.grid + b] = -__builtin_inf();
     }
-}
-
-// Single block: exclusive scan of the tile counts, total, counters reset.
-__global__ void __launch_bounds__(256) scan_kernel(Plan pl)
-{
-    __shared__ uint64_t s_sum[256];
-    const uint32_t tid = threadIdx.x, n = pl.n_inst;
-    const uint32_t per = (n + 255) / 256;
-    const uint32_t lo = tid * per, hi = (lo + per < n) ? lo + per : n;
-    uint64_t sum = 0;
-    for (uint32_t k = lo; k < hi; ++k) sum += pl.inst[k].tiles;
-    s_sum[tid] = sum;
+    // last block: tile scan
+    __threadfence();
     __syncthreads();
-    if (tid == 0) {
-        uint64_t run = 0;
-        for (uint32_t k = 0; k < 256; ++k) { const uint64_t v = s_sum[k]; s_sum[k] = run; run += v; }
-        pl.summary->total_tiles = run;
-        pl.summary->done_count = 0;
-        pl.summary->next_tile = 0;
-        pl.summary->any_flags = 0;
-        pl.summary->best_level = -1;
-        pl.summary->max_demand = 0;
-    }
+    if (tid == 0) s_last = (atomicAdd(&pl.summary->plan_done, 1u) == pl.n_inst - 1) ? 1u : 0u;
     __syncthreads();
-    uint64_t run = s_sum[tid];
-    for (uint32_t k = lo; k < hi; ++k) { pl.inst[k].tile_begin = run; run += pl.inst[k].tiles; }
+    if (s_last) { __threadfence(); scan_tiles(pl, s_sum); }
 }
 
 // ---- enumeration ------------------------------------------------------------------------
@@ -848,9 +865,9 @@ __device__ __forceinline__ void flush_block(const Plan& pl, uint32_t inst, const
     }
 }
 
-// Persistent grid sized to what fits on the chip at once; blocks draw tiles from
-// one atomic counter, so no block waits for a second round and uneven tiles even
-// out.  Tiles are ordered by instance and the counter only grows, so a block meets
+// Persistent grid sized to what fits on the chip at once; a block starts with the
+// tile of its own index and draws further tiles from one atomic counter, so no block
+// waits for a second round and uneven tiles even out.  Tiles are ordered by instance and the counter only grows, so a block meets
 // the instances in ascending order; it keeps one running minimum per lane and
 // reduces it (wave, then block) only when the instance changes.  Every block ends
 // with the first ticket at or past the total.
@@ -872,13 +889,16 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     uint32_t scan = 0;              // instance search cursor
     Best best;
     best.key = NO_KEY; best.obj = -__builtin_inf();
-    for (;;) {
-        __syncthreads();                                  // everyone has read the last ticket
-        if (threadIdx.x == 0) s_tile = atomicAdd(&pl.summary->next_tile, 1ull);
-        __syncthreads();
-        const unsigned long long ticket = s_tile;
-        const uint64_t tile = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ticket >> 32)) << 32) |
-                              (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ticket);
+    for (bool first = true;; first = false) {
+        uint64_t tile = blockIdx.x;                       // a block's first tile is its own index,
+        if (!first) {                                     // later ones come from the counter
+            __syncthreads();                              // everyone has read the last ticket
+            if (threadIdx.x == 0) s_tile = atomicAdd(&pl.summary->next_tile, 1ull);
+            __syncthreads();
+            const unsigned long long ticket = s_tile;
+            tile = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ticket >> 32)) << 32) |
+                   (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ticket);
+        }
         if (tile >= total) break;
         while (scan + 1 < pl.n_inst && insts[scan + 1].tile_begin <= tile) ++scan;
         if (scan != cur) {
@@ -980,8 +1000,8 @@ __global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
             m = umin64(m, pl.partial[(size_t)i * pl.grid + b]);
         m = block_min(m, s_red);
     }
-    if (threadIdx.x != 0) return;
-
+    __shared__ uint32_t s_last_block;
+    if (threadIdx.x == 0) {
     ResultRec* r = pl.results + i;
     r->index = NO_KEY; r->full_index = NO_KEY; r->evaluated = in->space;
     r->accuracy = 0.0; r->latency_us = 0; r->cost_units = 0x7FFFFFFF; r->feasible = 0; r->objective = 0.0;
@@ -1014,19 +1034,35 @@ __global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
     }
     // the last block to finish writes the sweep summary
     __threadfence();
-    const uint32_t ticket = atomicAdd(&pl.summary->done_count, 1u);
-    if (ticket == pl.n_inst - 1) {
-        __threadfence();
-        int32_t bl = -1;
-        uint32_t md = 0, any = 0;
-        for (uint32_t k = 0; k < pl.n_inst; ++k) {
-            const volatile ResultRec* rk = pl.results + k;
-            any |= rk->flags;
-            if (rk->feasible && (bl < 0 || pl.inst[k].demand > md)) { bl = (int32_t)k; md = pl.inst[k].demand; }
+    s_last_block = (atomicAdd(&pl.summary->done_count, 1u) == pl.n_inst - 1) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!s_last_block) return;
+    __threadfence();
+    // feasible level with the largest demand, first position on equal demands: maximum of
+    // (demand << 32) | (0xFFFFFFFF - position); 0 = none (demands are > 0)
+    uint64_t v = 0;
+    uint32_t any = 0;
+    for (uint32_t k = threadIdx.x; k < pl.n_inst; k += blockDim.x) {
+        const volatile ResultRec* rk = pl.results + k;
+        any |= rk->flags;
+        if (rk->feasible) {
+            const uint64_t cand = ((uint64_t)pl.inst[k].demand << 32) | (0xFFFFFFFFu - k);
+            v = cand > v ? cand : v;
         }
-        pl.summary->best_level = bl;
-        pl.summary->max_demand = md;
-        pl.summary->any_flags = any;
+    }
+    __shared__ uint64_t s_v[256];
+    __shared__ uint32_t s_any;
+    if (threadIdx.x == 0) s_any = 0;
+    s_v[threadIdx.x] = v;
+    __syncthreads();
+    if (any) atomicOr(&s_any, any);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (uint32_t k = 1; k < blockDim.x; ++k) v = s_v[k] > v ? s_v[k] : v;
+        pl.summary->best_level = v ? (int32_t)(0xFFFFFFFFu - (uint32_t)v) : -1;
+        pl.summary->max_demand = (uint32_t)(v >> 32);
+        pl.summary->any_flags = s_any;
     }
 }
 
@@ -1057,7 +1093,6 @@ hipError_t launch_prune_plan_scan(const Plan& pl, hipStream_t stream)
 {
     hipLaunchKernelGGL(prune_kernel, dim3(pl.n_inst * pl.t_max), dim3(256), prune_lds_bytes(pl.c_max), stream, pl);
     hipLaunchKernelGGL(plan_kernel, dim3(pl.n_inst), dim3(256), 0, stream, pl);
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, stream, pl);
     return hipGetLastError();
 }
 
