@@ -21,17 +21,17 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# Algorithmic vector lane-operations of the enumeration, counted for the sharing this
-# design does ("Roofline"): per candidate one latency compare and one
+# Algorithmic vector lane-operations of the enumeration, counted for the sharing the
+# kernel does: per candidate one latency compare and one
 # minimum on its key; per (variant of the innermost task, combination of all other
 # tasks) one fp64 fma and one compare for the accuracy.  Work shared further out
 # (one digit of the second-innermost task and beyond) is left out, so the figure
 # is a lower bound of what the kernel issues.
 OPS_PER_CANDIDATE = 2
 OPS_PER_VARIANT_GROUP = 2
-# The counting rule of the survey (per-candidate cost add, latency add, fma, three
-# compares, two mask ANDs, three for the running minimum) for comparison.
-SURVEY_OPS_PER_CANDIDATE = 11
+# For comparison, a count that charges every candidate its own arithmetic: cost add,
+# latency add, fma, three compares, two mask ANDs, three for the running minimum.
+UNSHARED_OPS_PER_CANDIDATE = 11
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one full-rate VALU lane-op per lane per cycle
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
@@ -100,7 +100,7 @@ def main():
                     help="maximise alpha*A_obj - beta*cost (alpha 1, beta 0.035) instead of minimum cost")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); sharding is described in DESIGN.md")
+        sys.exit("bench.py: the search runs on one GPU only; use --gpus 1")
 
     import torch
     if not torch.cuda.is_available():
@@ -164,8 +164,8 @@ def main():
                      "unit": "Tlane-op/s", "frac": achieved / VALU_PEAK_LANE_OPS, "traffic": None,
                      "kernel": "enumerate_kernel", "kernel_ms": enum_avg * 1e3,
                      "ops_per_candidate": ops / max(candidates, 1),
-                     "survey_rule": {"ops_per_candidate": SURVEY_OPS_PER_CANDIDATE,
-                                     "frac": SURVEY_OPS_PER_CANDIDATE * candidates / enum_avg / VALU_PEAK_LANE_OPS},
+                     "unshared_count": {"ops_per_candidate": UNSHARED_OPS_PER_CANDIDATE,
+                                        "frac": UNSHARED_OPS_PER_CANDIDATE * candidates / enum_avg / VALU_PEAK_LANE_OPS},
                      "device_ms_all_kernels": sum(dev_s) / len(dev_s) * 1e3},
         "context": PAPER_CONTEXT,
     }
