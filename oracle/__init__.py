@@ -84,6 +84,10 @@ def _load():
         lib.orc_objective_margin.restype = C.c_int
         lib.orc_objective_margin.argtypes = [vp, C.c_uint32, C.c_uint32, C.c_double, C.c_uint32,
                                              C.POINTER(C.c_double)]
+        lib.orc_set_search_space.restype = C.c_int
+        lib.orc_set_search_space.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+        lib.orc_budget_margin.restype = C.c_double
+        lib.orc_budget_margin.argtypes = [vp]
         lib.orc_max_threads.restype = C.c_int
         lib.orc_max_threads.argtypes = []
         _lib = lib
@@ -176,6 +180,16 @@ class Oracle:
         rc = self._lib.orc_set_objective(self._h, int(mode), float(alpha), float(beta))
         if rc != OK:
             raise OracleError(rc, "orc_set_objective")
+
+    def set_search_space(self, accuracy_scaling=True, spatial_partitioning=True, graph_informed=True):
+        """Restrictions of the paper's ablations: A (variants), S (partitions), T (global budgets)."""
+        rc = self._lib.orc_set_search_space(self._h, int(accuracy_scaling), int(spatial_partitioning),
+                                            int(graph_informed))
+        if rc != OK:
+            raise OracleError(rc, "orc_set_search_space")
+
+    def budget_margin(self) -> float:
+        return float(self._lib.orc_budget_margin(self._h))
 
     def objective_margin(self, demand_mrps: int, slo_latency_us: int, slo_accuracy: float,
                          prune_cap: int) -> float:

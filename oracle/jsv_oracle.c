@@ -71,6 +71,8 @@ typedef struct {
     /* what the search optimises: 0 = cheapest feasible, 1 = Eq. 14 */
     int objective;
     double alpha, beta;
+    /* search-space restrictions of the paper's ablations (1 = feature on) */
+    int space_a, space_s, space_t;
     /* graph */
     int npred[ORC_MAX_TASKS], pred[ORC_MAX_TASKS][ORC_MAX_TASKS];
     int nsucc[ORC_MAX_TASKS], succ[ORC_MAX_TASKS][ORC_MAX_TASKS];
@@ -169,6 +171,7 @@ int orc_create(orc_model **out, uint32_t T, uint32_t V, uint32_t P, uint32_t B,
     m->T = T; m->V = V; m->P = P; m->B = B; m->C = V * P * B; m->E = E;
     m->capacity = capacity_units; m->q = queue_factor;
     m->objective = 0; m->alpha = 1.0; m->beta = 0.035;     /* the paper's evaluation parameters */
+    m->space_a = m->space_s = m->space_t = 1;
     size_t n = (size_t)T * m->C;
     m->units = dup_mem(units, P * sizeof *units);
     m->batch = dup_mem(batch, B * sizeof *batch);
@@ -298,8 +301,113 @@ static int cmp_lat_c(const void *a, const void *b)
 }
 
 /*
- * Surviving choices of one task, ascending choice id.
- * cap == 0: everything.  Otherwise: (a) drop what cannot meet the latency SLO
+ * Search-space restrictions (Section 4.3 and Appendix B of the paper).
+ *   accuracy scaling off:      only the most accurate variant of every task
+ *   spatial partitioning off:  only the partition with the most units (a whole GPU)
+ *   task-graph-informed off:   static per-task budgets.  Latency: on every path the SLO is
+ *       split in the ratio of the tasks' highest latencies (most accurate variant, any
+ *       allowed partition and batch); a task on several paths gets the smallest share.
+ *       Resources: S_avail is split in the ratio of the expected needs m_t * s / H, with
+ *       (s, H) the allowed tuple of the most accurate variant with the highest throughput;
+ *       the share is floored to whole units.
+ */
+int orc_set_search_space(orc_model *m, int accuracy_scaling, int spatial_partitioning, int graph_informed)
+{
+    if (!m) return ORC_E_ARG;
+    m->space_a = accuracy_scaling != 0; m->space_s = spatial_partitioning != 0; m->space_t = graph_informed != 0;
+    return ORC_OK;
+}
+
+static uint32_t best_variant(const orc_model *m, uint32_t t)
+{
+    uint32_t bv = 0;
+    for (uint32_t v = 1; v < m->V; v++)
+        if (m->acc[(size_t)t * m->V + v] > m->acc[(size_t)t * m->V + bv]) bv = v;
+    return bv;
+}
+
+static uint32_t whole_partition(const orc_model *m)
+{
+    uint32_t bp = 0;
+    for (uint32_t p = 1; p < m->P; p++) if (m->units[p] > m->units[bp]) bp = p;
+    return bp;
+}
+
+/* highest latency and (units, throughput) of the highest-throughput tuple of task u's most
+   accurate variant over the allowed partitions and all batches */
+static void reference_tuple(const orc_model *m, uint32_t u, uint32_t *lat_max, uint32_t *units, uint32_t *thr)
+{
+    const uint32_t v = best_variant(m, u), wp = whole_partition(m);
+    *lat_max = 0; *thr = 0; *units = 0;
+    for (uint32_t p = 0; p < m->P; p++) {
+        if (!m->space_s && p != wp) continue;
+        for (uint32_t b = 0; b < m->B; b++) {
+            const size_t k = (size_t)u * m->C + ((size_t)v * m->P + p) * m->B + b;
+            if (m->lat[k] > *lat_max) *lat_max = m->lat[k];
+            if (m->thr[k] > *thr) { *thr = m->thr[k]; *units = m->units[p]; }
+        }
+    }
+}
+
+/* may task t use choice c at all under the restrictions? */
+static int allowed(const orc_model *m, const int32_t *cost, uint32_t slo_latency_us, uint32_t t, uint32_t c)
+{
+    if (!m->space_a && variant_of(m, c) != best_variant(m, t)) return 0;
+    if (!m->space_s && part_of(m, c) != whole_partition(m)) return 0;
+    if (!m->space_t) {
+        uint32_t lmax[ORC_MAX_TASKS], un[ORC_MAX_TASKS], th[ORC_MAX_TASKS];
+        for (uint32_t u = 0; u < m->T; u++) reference_tuple(m, u, &lmax[u], &un[u], &th[u]);
+        /* latency share on every path through t: q*L <= SLO * lmax_t / sum_path lmax */
+        for (int k = 0; k < m->npaths; k++) {
+            int on = 0; uint64_t sum = 0;
+            for (int i = 0; i < m->plen[k]; i++) {
+                uint32_t u = (uint32_t)m->pnode[(size_t)k * m->T + i];
+                if (u == t) on = 1;
+                sum += lmax[u];
+            }
+            if (!on) continue;
+            unsigned __int128 lhs = (unsigned __int128)m->q * m->lat[(size_t)t * m->C + c] * sum;
+            unsigned __int128 rhs = (unsigned __int128)slo_latency_us * lmax[t];
+            if (lhs > rhs) return 0;
+        }
+        if (m->capacity != 0) {
+            double total = 0.0, mine = 0.0;
+            for (uint32_t u = 0; u < m->T; u++) {
+                double e = ((double)m->mult[u] * (double)un[u]) / (double)th[u];
+                total += e;
+                if (u == t) mine = e;
+            }
+            double share = (double)m->capacity * (mine / total);
+            if ((double)cost[(size_t)t * m->C + c] > __builtin_floor(share)) return 0;
+        }
+    }
+    return 1;
+}
+
+/* distance of the nearest resource share to a whole number (tests keep away from 0) */
+double orc_budget_margin(const orc_model *m)
+{
+    if (m->space_t || m->capacity == 0) return 0.5;
+    uint32_t lmax, un[ORC_MAX_TASKS], th[ORC_MAX_TASKS];
+    double e[ORC_MAX_TASKS], total = 0.0, best = 0.5;
+    for (uint32_t u = 0; u < m->T; u++) {
+        reference_tuple(m, u, &lmax, &un[u], &th[u]);
+        e[u] = ((double)m->mult[u] * (double)un[u]) / (double)th[u];
+        total += e[u];
+    }
+    for (uint32_t u = 0; u < m->T; u++) {
+        double share = (double)m->capacity * (e[u] / total);
+        double d = share - __builtin_floor(share);
+        if (d > 0.5) d = 1.0 - d;
+        if (d < best) best = d;
+    }
+    return best;
+}
+
+/*
+ * Surviving choices of one task, ascending choice id.  Choices the restrictions above
+ * exclude never survive.
+ * cap == 0: everything else.  Otherwise: (a) drop what cannot meet the latency SLO
  * even when every other task runs its fastest choice; (b) drop what another
  * choice matches or beats on latency, accuracy and cost; (c) if more than cap
  * remain, thin each variant to floor(cap/V) choices evenly spaced by latency
@@ -311,8 +419,9 @@ static int prune_task(const orc_model *m, const int32_t *cost, uint32_t slo_late
     const uint32_t C = m->C;
     *truncated = 0;
     if (cap == 0) {
-        for (uint32_t c = 0; c < C; c++) ids[c] = (uint16_t)c;
-        *K = C;
+        uint32_t n = 0;
+        for (uint32_t c = 0; c < C; c++) if (allowed(m, cost, slo_latency_us, t, c)) ids[n++] = (uint16_t)c;
+        *K = n;
         return ORC_OK;
     }
     if (cap < 2 * m->V) return ORC_E_ARG;
@@ -338,7 +447,8 @@ static int prune_task(const orc_model *m, const int32_t *cost, uint32_t slo_late
         if (on && s > through) through = s;
     }
     for (uint32_t c = 0; c < C; c++)
-        alive[c] = (uint64_t)m->q * ((uint64_t)m->lat[(size_t)t * C + c] + through) <= slo_latency_us;
+        alive[c] = allowed(m, cost, slo_latency_us, t, c) &&
+                   (uint64_t)m->q * ((uint64_t)m->lat[(size_t)t * C + c] + through) <= slo_latency_us;
 
     /* (b) exact dominance on (latency down, accuracy up, cost down) */
     for (uint32_t c = 0; c < C; c++) {

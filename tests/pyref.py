@@ -46,6 +46,54 @@ class PyRef:
         self.amax = self._acc([max(range(pb.V), key=lambda v: (self.accF[t][v], -v))
                                for t in range(pb.T)])
 
+    # -- search-space restrictions (Section 4.3, Appendix B) --------------------------
+    space = (True, True, True)          # accuracy scaling, spatial partitioning, graph-informed
+
+    def _reference(self):
+        """Per task, for its most accurate variant over the allowed partitions and all
+        batches: highest latency, and units / throughput of the highest-throughput tuple."""
+        A, S, T = self.space
+        wp = max(range(self.P), key=lambda p: (int(self.pb.units[p]), -p))
+        out = []
+        for t in range(self.T):
+            v = max(range(self.V), key=lambda v: (self.accF[t][v], -v))
+            tuples = [(p, b) for p in range(self.P) if S or p == wp for b in range(self.B)]
+            lmax = max(int(self.lat[t][(v * self.P + p) * self.B + b]) for p, b in tuples)
+            p, b = max(tuples, key=lambda pb_: (int(self.thr[t][(v * self.P + pb_[0]) * self.B + pb_[1]]),
+                                                -pb_[0], -pb_[1]))
+            out.append((v, wp, lmax, int(self.pb.units[p]), int(self.thr[t][(v * self.P + p) * self.B + b])))
+        return out
+
+    def resource_shares(self):
+        """Exact per-task shares of S_avail when budgets are static (None if not)."""
+        if self.space[2] or int(self.pb.capacity_units) == 0:
+            return None
+        ref = self._reference()
+        e = [Fraction(self.m[t] * ref[t][3], ref[t][4]) for t in range(self.T)]
+        return [int(self.pb.capacity_units) * x / sum(e) for x in e]
+
+    def allowed(self, D: int, slo_l: int, t: int, c: int) -> bool:
+        A, S, T = self.space
+        ref = self._reference()
+        if not A and self.variant(c) != ref[t][0]:
+            return False
+        if not S and self.part(c) != ref[t][1]:
+            return False
+        if not T:
+            lmax = [r[2] for r in ref]
+            up, down = {}, {}
+            for u in self.order:
+                up[u] = max([up[p] + lmax[p] for p in self.preds[u]], default=0)
+            for u in reversed(self.order):
+                down[u] = max([down[s] + lmax[s] for s in self.succs[u]], default=0)
+            worst = up[t] + lmax[t] + down[t]          # heaviest path through t
+            if self.q * int(self.lat[t][c]) * worst > slo_l * lmax[t]:
+                return False
+            shares = self.resource_shares()
+            if shares is not None and self.rep_cost(D, t, c)[1] > shares[t].numerator // shares[t].denominator:
+                return False
+        return True
+
     def variant(self, c: int) -> int:
         return c // (self.P * self.B)
 
@@ -79,7 +127,7 @@ class PyRef:
 
     def lists(self, D: int, slo_l: int, cap: int) -> Tuple[List[List[int]], bool]:
         if cap == 0:
-            return [list(range(self.C)) for _ in range(self.T)], False
+            return [[c for c in range(self.C) if self.allowed(D, slo_l, t, c)] for t in range(self.T)], False
         # longest path through t with other tasks at their fastest choice:
         # longest chain ending just before t plus longest chain starting just after it
         lo = [min(int(x) for x in self.lat[t]) for t in range(self.T)]
@@ -94,7 +142,7 @@ class PyRef:
             through = up[t] + down[t]
             rows = []
             for c in range(self.C):
-                if self.q * (int(self.lat[t][c]) + through) <= slo_l:
+                if self.allowed(D, slo_l, t, c) and self.q * (int(self.lat[t][c]) + through) <= slo_l:
                     rows.append((int(self.lat[t][c]), self.accF[t][self.variant(c)],
                                  self.rep_cost(D, t, c)[1], c))
             front = []
