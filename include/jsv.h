@@ -126,6 +126,27 @@ JSV_API int jsv_set_dag(jsv_ctx* ctx, uint32_t T, uint32_t E, const uint16_t* sr
  */
 JSV_API int jsv_set_objective(jsv_ctx* ctx, int mode, double alpha, double beta);
 
+/*
+ * Search-space restrictions used for the paper's ablations (Section 4.3; Appendix B).
+ * All three default to on; switching one off removes choices from every task's list
+ * before any pruning, also when prune_cap is 0:
+ *   accuracy_scaling = 0      only the most accurate variant of each task (lowest id
+ *                             among equally accurate ones)
+ *   spatial_partitioning = 0  only the partition with the most units (lowest index among
+ *                             equals): every replica takes a whole GPU
+ *   graph_informed = 0        static per-task budgets instead of end-to-end ones.  On
+ *                             every path the latency SLO is split in the ratio of the
+ *                             tasks' highest latencies (most accurate variant, any allowed
+ *                             partition and batch); a task keeps its smallest share.
+ *                             S_avail (if not 0) is split in the ratio of the expected
+ *                             needs mult_t * units / throughput of the allowed tuple of the
+ *                             most accurate variant with the highest throughput, floored to
+ *                             whole units.  A choice survives only within both budgets.
+ * Applies to all later searches of the context (single system or batch).
+ */
+JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial_partitioning,
+                                 int graph_informed);
+
 typedef struct {
     uint64_t index;        /* winner's index in the searched space; UINT64_MAX if infeasible */
     uint64_t full_index;   /* sum_t c_t * C^t; UINT64_MAX if infeasible or it does not fit */

@@ -73,6 +73,13 @@ struct Graph {
     double   u[MAXT];         // sink share of position p (0 if not a sink)
     double   w[MAXT][MAXT];   // w[p][s] share of p among the predecessors of s (0 if no edge)
     double   amax;            // A_raw with every task on its most accurate variant
+    // search-space restrictions of the ablations (Section 4.3, Appendix B), by task id
+    uint32_t only_variant[MAXT];   // the only variant allowed, 0xFFFFFFFF = all
+    uint32_t only_part;            // the only partition index allowed, 0xFFFFFFFF = all
+    uint32_t static_budgets;       // 1: per-task latency and resource budgets apply
+    uint32_t lat_ref[MAXT];        // highest latency of the task's reference variant
+    uint64_t lat_path[MAXT];       // heaviest path through the task, tasks weighted by lat_ref
+    uint32_t unit_budget[MAXT];    // resource share in whole units, 0xFFFFFFFF = none
     // tables of this problem, device pointers
     const uint32_t* lat;      // [T][C]
     const uint32_t* thr;      // [T][C]  mrps

@@ -71,6 +71,7 @@ struct jsv_ctx {
     std::vector<Search> batch_search;
     bool batch_mode = false;
     bool dirty = true;                 // host problems changed since the last upload
+    bool space_a = true, space_s = true, space_t = true;   // ablation switches
     int objective = 0;                 // Eq. 14 mode and weights
     double alpha = 1.0, beta = 0.035;
 
@@ -168,8 +169,11 @@ int check_dag(uint32_t T, uint32_t E, const uint16_t* src, const uint16_t* dst, 
     return JSV_OK;
 }
 
-// Topological order, shares, A_max, per-task slack: fills hp.graph (device pointers left null).
-int stage_graph(HostProblem& hp)
+struct SpaceFlags { bool a = true, s = true, t = true; };
+
+// Topological order, shares, A_max, per-task slack, search-space restrictions: fills hp.graph
+// (device pointers left null).
+int stage_graph(HostProblem& hp, const SpaceFlags& sp = SpaceFlags())
 {
     const uint32_t T = hp.T, C = hp.C, V = hp.V;
     Graph& g = hp.graph;
@@ -244,6 +248,51 @@ int stage_graph(HostProblem& hp)
         for (uint32_t s = p + 1; s < T; ++s)
             if ((g.succ[p] >> s) & 1u) down[p] = std::max(down[p], down[s] + lo[g.task_at[s]]);
     for (uint32_t p = 0; p < T; ++p) g.through[g.task_at[p]] = (uint32_t)(up[p] + down[p]);
+
+    // Restrictions of the ablations.  Reference tuple of a task: its most accurate variant
+    // (lowest id among equals) over the allowed partitions and all batches.
+    uint32_t whole = 0;
+    for (uint32_t p = 1; p < hp.P; ++p) if (hp.units[p] > hp.units[whole]) whole = p;
+    g.only_part = sp.s ? 0xFFFFFFFFu : whole;
+    g.static_budgets = sp.t ? 0u : 1u;
+    double need[MAXT], need_total = 0.0;
+    for (uint32_t t = 0; t < T; ++t) {
+        uint32_t bv = 0;
+        for (uint32_t v = 1; v < V; ++v) if (hp.acc[(size_t)t * V + v] > hp.acc[(size_t)t * V + bv]) bv = v;
+        g.only_variant[t] = sp.a ? 0xFFFFFFFFu : bv;
+        uint32_t lmax = 0, best_thr = 0, best_units = 0;
+        for (uint32_t p = 0; p < hp.P; ++p) {
+            if (!sp.s && p != whole) continue;
+            for (uint32_t b = 0; b < hp.B; ++b) {
+                const size_t k = (size_t)t * C + ((size_t)bv * hp.P + p) * hp.B + b;
+                lmax = std::max(lmax, hp.lat[k]);
+                if (hp.thr[k] > best_thr) { best_thr = hp.thr[k]; best_units = hp.units[p]; }
+            }
+        }
+        g.lat_ref[t] = lmax;
+        need[t] = ((double)hp.mult[t] * (double)best_units) / (double)best_thr;
+        need_total += need[t];
+    }
+    {   // heaviest path through each task with the tasks weighted by their reference latency
+        uint64_t upw[MAXT] = {}, downw[MAXT] = {};
+        for (uint32_t p = 0; p < T; ++p)
+            for (uint32_t s = p + 1; s < T; ++s)
+                if ((g.succ[p] >> s) & 1u) upw[s] = std::max(upw[s], upw[p] + g.lat_ref[g.task_at[p]]);
+        for (int p = (int)T - 1; p >= 0; --p)
+            for (uint32_t s = p + 1; s < T; ++s)
+                if ((g.succ[p] >> s) & 1u) downw[p] = std::max(downw[p], downw[s] + g.lat_ref[g.task_at[s]]);
+        for (uint32_t p = 0; p < T; ++p) {
+            const uint32_t t = g.task_at[p];
+            g.lat_path[t] = upw[p] + g.lat_ref[t] + downw[p];
+        }
+    }
+    for (uint32_t t = 0; t < T; ++t) {
+        g.unit_budget[t] = 0xFFFFFFFFu;
+        if (!sp.t && hp.capacity != 0) {
+            const double share = std::floor((double)hp.capacity * (need[t] / need_total));
+            g.unit_budget[t] = share >= 4294967295.0 ? 0xFFFFFFFEu : (uint32_t)share;
+        }
+    }
     hp.staged = true;
     return JSV_OK;
 }
@@ -449,7 +498,7 @@ int ready_single(jsv_ctx* ctx)
     if (!hp.have_profile || !hp.have_dag) return JSV_E_STATE;
     if (hp.mult.size() != hp.T) return JSV_E_STATE;
     if (!hp.staged) {
-        const int rc = stage_graph(hp);
+        const int rc = stage_graph(hp, SpaceFlags{ctx->space_a, ctx->space_s, ctx->space_t});
         if (rc) return rc;
         ctx->dirty = true;
     }
@@ -515,6 +564,22 @@ JSV_API int jsv_set_objective(jsv_ctx* ctx, int mode, double alpha, double beta)
     return JSV_OK;
 }
 
+JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial_partitioning, int graph_informed)
+{
+    if (!ctx) return JSV_E_NULL;
+    ctx->space_a = accuracy_scaling != 0;
+    ctx->space_s = spatial_partitioning != 0;
+    ctx->space_t = graph_informed != 0;
+    // staged graphs carry the restrictions: stage and upload again before the next search
+    ctx->single.staged = false;
+    for (auto& hp : ctx->batch) {
+        const int rc = stage_graph(hp, SpaceFlags{ctx->space_a, ctx->space_s, ctx->space_t});
+        if (rc) return rc;
+    }
+    ctx->dirty = true;
+    return JSV_OK;
+}
+
 JSV_API size_t jsv_workspace_bytes(const jsv_ctx* ctx, uint32_t n_levels, uint32_t prune_cap)
 {
     if (!ctx || n_levels == 0) return 0;
@@ -570,7 +635,7 @@ JSV_API int jsv_set_dag(jsv_ctx* ctx, uint32_t T, uint32_t E, const uint16_t* sr
     const int rc = check_dag(T, E, src, dst, demand_mult_milli, capacity_units, queue_factor, tmp);
     if (rc) return rc;
     if (tmp.have_profile) {                       // stage now so that range errors surface here
-        const int rs = stage_graph(tmp);
+        const int rs = stage_graph(tmp, SpaceFlags{ctx->space_a, ctx->space_s, ctx->space_t});
         if (rs) return rs;
     }
     hp = std::move(tmp);
@@ -731,7 +796,7 @@ JSV_API int jsv_load_batch(jsv_ctx* ctx, const jsv_problem* problems, uint32_t n
         if (rc) return rc;
         rc = check_dag(p.T, p.E, p.src, p.dst, p.demand_mult_milli, p.capacity_units, p.queue_factor, hps[k]);
         if (rc) return rc;
-        rc = stage_graph(hps[k]);
+        rc = stage_graph(hps[k], SpaceFlags{ctx->space_a, ctx->space_s, ctx->space_t});
         if (rc) return rc;
         rc = check_search_args(hps[k], p.demand_mrps, p.slo_accuracy, p.prune_cap);
         if (rc) return rc;

@@ -186,8 +186,17 @@ __global__ void __launch_bounds__(256) prune_kernel(Plan pl)
         s_lat[c] = lat; s_cost[c] = (uint32_t)cost; s_rep[c] = (uint32_t)rep;
         s_acc[c] = g->acc[(size_t)t * V + c / PB];
         g_rep[c] = (uint32_t)rep; g_cost[c] = (uint32_t)cost;
+        // restrictions of the ablations: variant, partition, static per-task budgets
+        bool ok = (g->only_variant[t] == 0xFFFFFFFFu || c / PB == g->only_variant[t]) &&
+                  (g->only_part == 0xFFFFFFFFu || (c / Bn) % Pn == g->only_part);
+        if (ok && g->static_budgets) {
+            // q*L <= SLO * lat_ref / lat_path, exactly: both sides are below 2^96
+            const unsigned __int128 lhs = (unsigned __int128)((uint64_t)g->q * lat) * g->lat_path[t];
+            const unsigned __int128 rhs = (unsigned __int128)budget * g->lat_ref[t];
+            ok = lhs <= rhs && cost <= g->unit_budget[t];
+        }
         // (a) can this choice meet the latency SLO with every other task at its fastest?
-        s_a[c] = cap == 0 ? 1 : ((uint64_t)g->q * ((uint64_t)lat + through) <= budget);
+        s_a[c] = ok && (cap == 0 || ((uint64_t)g->q * ((uint64_t)lat + through) <= budget));
     }
     __syncthreads();
 
