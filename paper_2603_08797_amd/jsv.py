@@ -154,11 +154,14 @@ class Jsv:
     """
 
     def __init__(self, device: int = 0, stream=None, use_torch: bool = True):
-        self._lib = load_library()
         self._torch = None
         handle = None
         if use_torch:
+            # torch first: the library must bind to the HIP runtime torch has loaded, so that
+            # streams and device pointers of both live in one runtime
             import torch
+        self._lib = load_library()
+        if use_torch:
             if torch.cuda.is_available():
                 self._torch = torch
                 s = stream if stream is not None else torch.cuda.current_stream(device)
