@@ -6,16 +6,18 @@
 //   plan_kernel       index strides, packed keys, local keys and the innermost stream,
 //                     tile geometry per instance; its last block scans the tile counts.
 //   enumerate_kernel  every candidate scored and masked (Eq. 3, 8, 11-13) and
-//                     reduced to the cheapest feasible one per lane / wave / block.
-//   finalize_kernel   grid-level minimum, winner decoded and rescored, summary.
+//                     reduced per lane / wave / block to the cheapest feasible one
+//                     (<false>) or to the one with the best objective of Eq. 14 (<true>).
+//   finalize_kernel   grid-level reduction, winner decoded and rescored, sweep summary.
 //   eval_kernel       explicit candidates scored one per thread (parity aid).
 //
-// The enumeration is VALU-bound: per candidate one u32 compare, one fp64 fma and
-// compare, one 64-bit add, one 64-bit compare and a select; there is no dense
-// contraction anywhere, so no MFMA.  Table entries of the tasks looped inside a
-// lane are wave-uniform and are fetched with scalar loads (constant address
-// space) so that they feed the vector ALU as scalar operands; the entries that
-// differ per lane are gathered from a copy of the instance's tables in LDS.
+// The enumeration is bound by vector-ALU issue; there is no dense contraction
+// anywhere, so no MFMA.  Table entries of the tasks looped inside a lane are
+// wave-uniform and are fetched with scalar loads (constant address space) so that
+// they feed the vector ALU as scalar operands; the entries that differ per lane are
+// gathered from a copy of the instance's tables in LDS.  In the common case a
+// candidate costs two vector instructions: a latency compare that narrows the
+// execution mask and a minimum on a 32-bit local key (loop_x32).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
