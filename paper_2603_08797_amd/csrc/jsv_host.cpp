@@ -65,6 +65,8 @@ struct jsv_ctx {
     bool device_ready = false;
     uint32_t grid = 0;                 // upper bound on enumeration blocks (sizes the workspace)
     uint32_t cus = 0;
+    // occupancy of the enumeration kernel, remembered for the last table shape
+    uint32_t occ_t = 0, occ_k = 0; int occ_obj = -1, occ_blocks = 0;
 
     HostProblem single;
     std::vector<HostProblem> batch;
@@ -440,8 +442,12 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
     pl.n_inst = n; pl.t_max = t_max; pl.k_max = k_max; pl.c_max = c_max;
-    int per_cu = 0;
-    HIP_TRY(ctx, jsv::enumerate_blocks_per_cu(t_max, k_max, ctx->objective != 0, &per_cu));
+    if (ctx->occ_t != t_max || ctx->occ_k != k_max || ctx->occ_obj != ctx->objective) {
+        int blocks = 0;
+        HIP_TRY(ctx, jsv::enumerate_blocks_per_cu(t_max, k_max, ctx->objective != 0, &blocks));
+        ctx->occ_t = t_max; ctx->occ_k = k_max; ctx->occ_obj = ctx->objective; ctx->occ_blocks = blocks;
+    }
+    const int per_cu = ctx->occ_blocks;
     if (per_cu < 1) return JSV_E_BADARG;
     pl.grid = ctx->cus * (uint32_t)std::min(per_cu, 8);     // everything launched is resident
     const uint64_t lanes = (uint64_t)ctx->grid * jsv::TILE_LANES * 2 / n;

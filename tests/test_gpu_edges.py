@@ -200,3 +200,39 @@ def test_source_tasks_after_the_first_position(ctx):
     check_search(ctx, pb, _search([50000, 300000], 90000, 0.4))
     wide = _problem(3, 3, 2, 2, 15, [])                  # three isolated tasks
     check_search(ctx, wide, _search([50000], 50000, 0.7))
+
+
+def test_three_in_lane_positions_with_both_key_widths(ctx):
+    """Many levels of a 6-task graph with 12 choices per task: enough lanes for the planner to
+    loop three (resp. two) positions inside a lane; huge demands force the 64-bit keys,
+    small ones run the 32-bit fast path, in one sweep."""
+    edges = [(0, 1), (0, 2), (1, 3), (2, 3), (3, 4), (1, 5)]
+    pb = _problem(6, 2, 3, 2, 16, edges, mult=[1000, 700, 1300, 1000, 1000, 400])
+    pb.thr_mrps[:] = (pb.thr_mrps % 8) + 8
+    pb.units[:] = 1
+    big = [2_000_000_000 + 7_000_000 * k for k in range(40)]
+    small = [1000 + 37 * k for k in range(24)]
+    res, _ = check_search(ctx, pb, _search(big + small, 200000, 0.45))
+    assert all(r.flags & 2 for r in res[:40]) and not any(r.flags & 2 for r in res[40:])
+    assert any(r.feasible for r in res)
+    five = _problem(5, 2, 3, 2, 17, [(0, 1), (1, 2), (2, 3), (3, 4)])
+    five.thr_mrps[:] = (five.thr_mrps % 8) + 8
+    five.units[:] = 1
+    check_search(ctx, five, _search(big + small, 200000, 0.3))
+    ctx.set_objective(1, 1.0, 1e-9)
+    try:
+        ctx.load(pb)
+        got, _ = ctx.search(big[:8] + small[:8], 200000, 0.45, 0)
+    finally:
+        ctx.set_objective(0)
+    o = oracle.Oracle.from_problem(pb)
+    o.set_objective(1, 1.0, 1e-9)
+    ref, _, _ = o.search(big[:8] + small[:8], 200000, 0.45, 0, threads=16)
+    for a, b in zip(got, ref):
+        assert a.feasible == b.feasible
+        if b.feasible:
+            assert abs(a.objective - b.objective) <= 1e-12
+            if a.index != b.index:      # only an objective tie between different variants may differ
+                assert a.objective == pytest.approx(b.objective, abs=1e-12)
+            else:
+                same(a, b)
