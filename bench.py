@@ -32,6 +32,10 @@ OPS_PER_VARIANT_GROUP = 2
 # For comparison, a count that charges every candidate its own arithmetic: cost add,
 # latency add, fma, three compares, two mask ANDs, three for the running minimum.
 UNSHARED_OPS_PER_CANDIDATE = 11
+# HBM bytes per launch of the enumeration kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled
+# against a 1 GiB copy (profiles/enumerate_kernel_xr8_hbm_traffic.md); known only for the
+# default workload in cost mode.
+MEASURED_TRAFFIC_BYTES = {("xr8", 0, False): (3613 + 28080) * 1024}
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one full-rate VALU lane-op per lane per cycle
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
@@ -96,6 +100,9 @@ def main():
     ap.add_argument("--workload", default="xr8", choices=["chain3", "diamond5", "chain4", "xr8", "dagbatch"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device-to-device copy, a kernel of known HBM traffic "
+                         "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     ap.add_argument("--objective", action="store_true",
                     help="maximise alpha*A_obj - beta*cost (alpha 1, beta 0.035) instead of minimum cost")
     args = ap.parse_args()
@@ -141,6 +148,13 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        src.zero_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
     candidates = sum(r.evaluated for r in res)
     ms_per_step = wall / args.steps * 1e3
     enum_avg = sum(enum_s) / len(enum_s)
@@ -161,7 +175,8 @@ def main():
                    "feasible_levels": sum(1 for r in res if r.feasible),
                    "max_serviceable_demand_mrps": summ.max_demand_mrps},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": VALU_PEAK_LANE_OPS / 1e12,
-                     "unit": "Tlane-op/s", "frac": achieved / VALU_PEAK_LANE_OPS, "traffic": None,
+                     "unit": "Tlane-op/s", "frac": achieved / VALU_PEAK_LANE_OPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.seed, args.objective)),
                      "kernel": "enumerate_kernel", "kernel_ms": enum_avg * 1e3,
                      "ops_per_candidate": ops / max(candidates, 1),
                      "unshared_count": {"ops_per_candidate": UNSHARED_OPS_PER_CANDIDATE,
