@@ -278,6 +278,14 @@ __global__ void __launch_bounds__(256) prune_kernel(Plan pl)
     }
 }
 
+// Tiles per ticket of the enumeration kernel's work counter: about 128 tickets per block,
+// so that the counter is touched less often and the tail stays below one percent.
+__device__ __forceinline__ uint32_t tiles_per_ticket(uint64_t total_tiles, uint32_t grid)
+{
+    const uint64_t b = total_tiles / ((uint64_t)grid * 128u);
+    return b < 1 ? 1u : (b > 64 ? 64u : (uint32_t)b);
+}
+
 // ---- plan -------------------------------------------------------------------------------
 // Exclusive scan of the tile counts over the instances, total, counters reset; run by
 // the last plan block to finish.
@@ -296,7 +304,8 @@ __device__ void scan_tiles(const Plan& pl, uint64_t* s_sum)
         for (uint32_t k = 0; k < 256; ++k) { const uint64_t v = s_sum[k]; s_sum[k] = run; run += v; }
         pl.summary->total_tiles = run;
         pl.summary->done_count = 0;
-        pl.summary->next_tile = pl.grid;           // tiles 0..grid-1 go to the blocks by index
+        // the first ticket of every block is its own index: the counter starts behind those
+        pl.summary->next_tile = (unsigned long long)pl.grid * tiles_per_ticket(run, pl.grid);
         pl.summary->any_flags = 0;
         pl.summary->best_level = -1;
         pl.summary->max_demand = 0;
@@ -877,7 +886,7 @@ __device__ __forceinline__ void flush_block(const Plan& pl, uint32_t inst, const
 }
 
 // Persistent grid sized to what fits on the chip at once; a block starts with the
-// tile of its own index and draws further tiles from one atomic counter, so no block
+// run of tiles of its own index and draws further runs from one atomic counter, so no block
 // waits for a second round and uneven tiles even out.  Tiles are ordered by instance and the counter only grows, so a block meets
 // the instances in ascending order; it keeps one running minimum per lane and
 // reduces it (wave, then block) only when the instance changes.  Every block ends
@@ -900,15 +909,18 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     uint32_t scan = 0;              // instance search cursor
     Best best;
     best.key = NO_KEY; best.obj = -__builtin_inf();
-    for (bool first = true;; first = false) {
-        uint64_t tile = blockIdx.x;                       // a block's first tile is its own index,
-        if (!first) {                                     // later ones come from the counter
+    const uint32_t batch = tiles_per_ticket(total, gridDim.x);
+    uint64_t tile = (uint64_t)blockIdx.x * batch;         // a block's first ticket is its own index,
+    uint64_t tile_end = tile + batch;                     // later ones come from the counter
+    for (;; ++tile) {
+        if (tile == tile_end) {
             __syncthreads();                              // everyone has read the last ticket
-            if (threadIdx.x == 0) s_tile = atomicAdd(&pl.summary->next_tile, 1ull);
+            if (threadIdx.x == 0) s_tile = atomicAdd(&pl.summary->next_tile, (unsigned long long)batch);
             __syncthreads();
             const unsigned long long ticket = s_tile;
             tile = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ticket >> 32)) << 32) |
                    (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ticket);
+            tile_end = tile + batch;
         }
         if (tile >= total) break;
         while (scan + 1 < pl.n_inst && insts[scan + 1].tile_begin <= tile) ++scan;
