@@ -103,6 +103,7 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy, a kernel of known HBM traffic "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--graph", action="store_true", help="replay the launch sequence as a HIP graph")
     ap.add_argument("--objective", action="store_true",
                     help="maximise alpha*A_obj - beta*cost (alpha 1, beta 0.035) instead of minimum cost")
     args = ap.parse_args()
@@ -119,6 +120,8 @@ def main():
     j = jsv.Jsv(device=0, stream=stream)
     if args.objective:
         j.set_objective(1, 1.0, 0.035)
+    if args.graph:
+        j.set_graph_mode(True)
     batch = len(w.problems) > 1
     if batch:
         j.load_batch(w.problems, w.searches)
@@ -157,7 +160,7 @@ def main():
 
     candidates = sum(r.evaluated for r in res)
     ms_per_step = wall / args.steps * 1e3
-    enum_avg = sum(enum_s) / len(enum_s)
+    enum_avg = sum(enum_s) / len(enum_s) or sum(dev_s) / len(dev_s)     # graph mode times the whole replay
     ops = algorithmic_ops(jsv, w.problems, w.searches, res)
     achieved = ops / enum_avg
     out = {

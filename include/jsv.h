@@ -127,6 +127,18 @@ JSV_API int jsv_set_dag(jsv_ctx* ctx, uint32_t T, uint32_t E, const uint16_t* sr
 JSV_API int jsv_set_objective(jsv_ctx* ctx, int mode, double alpha, double beta);
 
 /*
+ * Graph mode (off by default): jsv_search and jsv_search_loaded_batch record their
+ * copy - kernels - copy sequence into a HIP graph the first time a shape is seen (number
+ * of levels, table sizes, workspace, objective) and replay it afterwards, which removes
+ * most of the launch overhead of small searches.  New demands and SLOs need no new
+ * recording.  In this mode jsv_summary.seconds_enumerate is 0 (the kernels are not timed
+ * one by one) and the context's stream must not be under capture by the caller.
+ * Needs a context created on a stream of its own: with the default stream (NULL) the call
+ * returns JSV_E_STATE.
+ */
+JSV_API int jsv_set_graph_mode(jsv_ctx* ctx, int on);
+
+/*
  * Search-space restrictions used for the paper's ablations (Section 4.3; Appendix B).
  * All three default to on; switching one off removes choices from every task's list
  * before any pruning, also when prune_cap is 0:

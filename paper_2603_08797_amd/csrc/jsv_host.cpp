@@ -86,6 +86,13 @@ struct jsv_ctx {
 
     void* pinned = nullptr;  size_t pinned_bytes = 0;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+
+    // graph mode: the copy-kernels-copy sequence of a search, captured once per shape
+    bool graph_mode = false;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t graph_exec = nullptr;
+    jsv::Plan graph_plan;              // what the captured sequence was built for
+    const void* graph_pin = nullptr;
 };
 
 namespace {
@@ -313,6 +320,13 @@ int ensure_device(jsv_ctx* ctx)
     return JSV_OK;
 }
 
+void drop_graph(jsv_ctx* ctx)
+{
+    if (ctx->graph_exec) { (void)hipGraphExecDestroy(ctx->graph_exec); ctx->graph_exec = nullptr; }
+    if (ctx->graph) { (void)hipGraphDestroy(ctx->graph); ctx->graph = nullptr; }
+    ctx->graph_pin = nullptr;
+}
+
 int ensure_pinned(jsv_ctx* ctx, size_t bytes)
 {
     if (ctx->pinned_bytes >= bytes) return JSV_OK;
@@ -429,6 +443,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     std::memcpy(pin_in, inst.data(), in_bytes);
 
     jsv::Plan pl;
+    std::memset(&pl, 0, sizeof pl);
     pl.graphs = (const Graph*)ctx->d_problems;
     pl.inst = (Instance*)(ws + L.inst);
     pl.entries = (jsv::Entry*)(ws + L.entries);
@@ -454,17 +469,50 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     pl.lanes_wanted = (uint32_t)std::max<uint64_t>(64, std::min<uint64_t>(lanes, 0x7FFFFFFF));
 
     hipStream_t st = ctx->stream;
-    HIP_TRY(ctx, hipMemcpyAsync(pl.inst, pin_in, in_bytes, hipMemcpyHostToDevice, st));
-    HIP_TRY(ctx, hipEventRecord(ctx->ev[0], st));
-    HIP_TRY(ctx, jsv::launch_prune_plan_scan(pl, st));
-    HIP_TRY(ctx, hipEventRecord(ctx->ev[1], st));
-    HIP_TRY(ctx, jsv::launch_enumerate(pl, st));
-    HIP_TRY(ctx, hipEventRecord(ctx->ev[2], st));
-    HIP_TRY(ctx, jsv::launch_finalize(pl, st));
-    HIP_TRY(ctx, hipEventRecord(ctx->ev[3], st));
-    HIP_TRY(ctx, hipMemcpyAsync(pin_out, pl.results, sizeof(jsv::ResultRec) * n, hipMemcpyDeviceToHost, st));
-    HIP_TRY(ctx, hipMemcpyAsync(pin_out + sizeof(jsv::ResultRec) * n, pl.summary, sizeof(jsv::SummaryRec),
-                                hipMemcpyDeviceToHost, st));
+    bool timed_kernels = true;
+    if (ctx->graph_mode) {
+        // Replay the captured sequence when nothing it was built from has changed: same
+        // buffers, shapes, grid and objective (the instance records travel through the pinned
+        // buffer, so new demands and SLOs need no new capture).
+        if (!ctx->graph_exec || std::memcmp(&ctx->graph_plan, &pl, sizeof pl) != 0 || ctx->graph_pin != pin_in) {
+            drop_graph(ctx);
+            HIP_TRY(ctx, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+            hipError_t e = hipMemcpyAsync(pl.inst, pin_in, in_bytes, hipMemcpyHostToDevice, st);
+            if (e == hipSuccess) e = jsv::launch_prune_plan_scan(pl, st);
+            if (e == hipSuccess) e = jsv::launch_enumerate(pl, st);
+            if (e == hipSuccess) e = jsv::launch_finalize(pl, st);
+            if (e == hipSuccess) e = hipMemcpyAsync(pin_out, pl.results, sizeof(jsv::ResultRec) * n, hipMemcpyDeviceToHost, st);
+            if (e == hipSuccess) e = hipMemcpyAsync(pin_out + sizeof(jsv::ResultRec) * n, pl.summary,
+                                                    sizeof(jsv::SummaryRec), hipMemcpyDeviceToHost, st);
+            hipGraph_t g = nullptr;
+            const hipError_t e2 = hipStreamEndCapture(st, &g);       // always leave capture mode
+            if (e != hipSuccess || e2 != hipSuccess) {
+                if (g) (void)hipGraphDestroy(g);
+                ctx->last_hip = (int)(e != hipSuccess ? e : e2);
+                return JSV_E_DEVICE;
+            }
+            ctx->graph = g;
+            HIP_TRY(ctx, hipGraphInstantiate(&ctx->graph_exec, ctx->graph, nullptr, nullptr, 0));
+            ctx->graph_plan = pl;
+            ctx->graph_pin = pin_in;
+        }
+        HIP_TRY(ctx, hipEventRecord(ctx->ev[0], st));
+        HIP_TRY(ctx, hipGraphLaunch(ctx->graph_exec, st));
+        HIP_TRY(ctx, hipEventRecord(ctx->ev[3], st));
+        timed_kernels = false;
+    } else {
+        HIP_TRY(ctx, hipMemcpyAsync(pl.inst, pin_in, in_bytes, hipMemcpyHostToDevice, st));
+        HIP_TRY(ctx, hipEventRecord(ctx->ev[0], st));
+        HIP_TRY(ctx, jsv::launch_prune_plan_scan(pl, st));
+        HIP_TRY(ctx, hipEventRecord(ctx->ev[1], st));
+        HIP_TRY(ctx, jsv::launch_enumerate(pl, st));
+        HIP_TRY(ctx, hipEventRecord(ctx->ev[2], st));
+        HIP_TRY(ctx, jsv::launch_finalize(pl, st));
+        HIP_TRY(ctx, hipEventRecord(ctx->ev[3], st));
+        HIP_TRY(ctx, hipMemcpyAsync(pin_out, pl.results, sizeof(jsv::ResultRec) * n, hipMemcpyDeviceToHost, st));
+        HIP_TRY(ctx, hipMemcpyAsync(pin_out + sizeof(jsv::ResultRec) * n, pl.summary, sizeof(jsv::SummaryRec),
+                                    hipMemcpyDeviceToHost, st));
+    }
     HIP_TRY(ctx, hipStreamSynchronize(st));
 
     jsv::SummaryRec sr;
@@ -475,7 +523,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     if (summary) {
         float ms_all = 0.f, ms_enum = 0.f;
         HIP_TRY(ctx, hipEventElapsedTime(&ms_all, ctx->ev[0], ctx->ev[3]));
-        HIP_TRY(ctx, hipEventElapsedTime(&ms_enum, ctx->ev[1], ctx->ev[2]));
+        if (timed_kernels) HIP_TRY(ctx, hipEventElapsedTime(&ms_enum, ctx->ev[1], ctx->ev[2]));
         summary->best_level = sr.best_level;
         summary->max_demand_mrps = sr.max_demand;
         summary->seconds_device = ms_all * 1e-3;
@@ -536,6 +584,7 @@ JSV_API void jsv_destroy(jsv_ctx* ctx)
     if (ctx->device_ready) {
         (void)hipSetDevice(ctx->device);
         (void)hipStreamSynchronize(ctx->stream);
+        drop_graph(ctx);
         for (auto& e : ctx->ev) if (e) (void)hipEventDestroy(e);
         if (ctx->d_problems) (void)hipFree(ctx->d_problems);
         if (ctx->ws_own) (void)hipFree(ctx->ws_own);
@@ -583,6 +632,15 @@ JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial
         if (rc) return rc;
     }
     ctx->dirty = true;
+    return JSV_OK;
+}
+
+JSV_API int jsv_set_graph_mode(jsv_ctx* ctx, int on)
+{
+    if (!ctx) return JSV_E_NULL;
+    if (on && ctx->stream == nullptr) return JSV_E_STATE;     // the default stream cannot be captured
+    ctx->graph_mode = on != 0;
+    if (!ctx->graph_mode && ctx->device_ready) { (void)hipSetDevice(ctx->device); drop_graph(ctx); }
     return JSV_OK;
 }
 

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libjsv.so")
 MAX_TASKS = 16
 OK, E_NULL, E_BADARG, E_CYCLE, E_OVERFLOW, E_STATE, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6, -7
 
-EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space",
+EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space", "jsv_set_graph_mode",
            "jsv_workspace_bytes", "jsv_set_workspace", "jsv_load_profile", "jsv_set_dag",
            "jsv_search", "jsv_eval_candidates", "jsv_get_pruned", "jsv_load_batch",
            "jsv_search_loaded_batch", "jsv_search_batch"]
@@ -75,6 +75,8 @@ def load_library():
     lib.jsv_set_objective.argtypes = [vp, C.c_int, f64, f64]
     lib.jsv_set_search_space.restype = C.c_int
     lib.jsv_set_search_space.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+    lib.jsv_set_graph_mode.restype = C.c_int
+    lib.jsv_set_graph_mode.argtypes = [vp, C.c_int]
     lib.jsv_workspace_bytes.restype = C.c_size_t
     lib.jsv_workspace_bytes.argtypes = [vp, u32, u32]
     lib.jsv_set_workspace.restype = C.c_int
@@ -202,6 +204,10 @@ class Jsv:
         """Restrictions of the paper's ablations (A, S, T); all on by default."""
         self._check(self._lib.jsv_set_search_space(self._h, int(accuracy_scaling), int(spatial_partitioning),
                                                    int(graph_informed)), "jsv_set_search_space")
+
+    def set_graph_mode(self, on: bool = True):
+        """Record the launch sequence of a search into a HIP graph and replay it."""
+        self._check(self._lib.jsv_set_graph_mode(self._h, int(on)), "jsv_set_graph_mode")
 
     # -- inputs ------------------------------------------------------------------
     def load_profile(self, T, V, P, B, units, batch, latency_us, thr_mrps, accuracy):
