@@ -35,7 +35,7 @@ UNSHARED_OPS_PER_CANDIDATE = 11
 # HBM bytes per launch of the enumeration kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled
 # against a 1 GiB copy (profiles/enumerate_kernel_xr8_hbm_traffic.md); known only for the
 # default workload in cost mode.
-MEASURED_TRAFFIC_BYTES = {("xr8", 0, False): (3613 + 28080) * 1024}
+MEASURED_TRAFFIC_BYTES = {("xr8", 0, False): (3614 + 11410) * 1024}
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one full-rate VALU lane-op per lane per cycle
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
