@@ -86,6 +86,8 @@ def _load():
                                              C.POINTER(C.c_double)]
         lib.orc_set_search_space.restype = C.c_int
         lib.orc_set_search_space.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+        lib.orc_set_factors.restype = C.c_int
+        lib.orc_set_factors.argtypes = [vp, vp]
         lib.orc_budget_margin.restype = C.c_double
         lib.orc_budget_margin.argtypes = [vp]
         lib.orc_max_threads.restype = C.c_int
@@ -187,6 +189,19 @@ class Oracle:
                                             int(graph_informed))
         if rc != OK:
             raise OracleError(rc, "orc_set_search_space")
+
+    def set_factors(self, factor_milli):
+        """Per-variant multiplicative factors F(t, v, t') of Eq. 4, [E][V] in 1/1000ths in the
+        edge order of the model; None returns to the fixed per-task multipliers."""
+        if factor_milli is None:
+            rc = self._lib.orc_set_factors(self._h, None)
+        else:
+            f = np.ascontiguousarray(factor_milli, dtype=np.uint32)
+            if f.shape != (int(self._keep[5].shape[0]), self.V):
+                raise ValueError("factor_milli must have shape [E][V]")
+            rc = self._lib.orc_set_factors(self._h, _ptr(f))
+        if rc != OK:
+            raise OracleError(rc, "orc_set_factors")
 
     def budget_margin(self) -> float:
         return float(self._lib.orc_budget_margin(self._h))

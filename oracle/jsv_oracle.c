@@ -10,6 +10,9 @@
  * (variant, partition, batch) tuple per task, replicated as often as needed:
  *
  *   - demand at a task:   R(t) = R * m_t                       (Eq. 5, fixed factors)
+ *                         or, with per-variant factors F(t', v, t) given, R(t) = R * m_t at a
+ *                         source and sum over predecessors t' of R(t') * F(t', v_t', t)
+ *                         elsewhere, v_t' the variant chosen for t'  (Eq. 4, 5)
  *   - replicas:           smallest M >= 1 with M*H >= R(t)     (Eq. 6)
  *   - task cost:          M * s_n of the chosen partition      (Eq. 7)
  *   - total cost:         sum over tasks, <= S_avail           (Eq. 8)
@@ -67,6 +70,7 @@ typedef struct {
     uint32_t *units, *batch, *lat, *thr, *mult;
     double *acc;
     uint16_t *src, *dst;
+    uint32_t *fac;  /* [E][V] per-variant factor of an edge's tail, 1/1000ths; NULL = fixed factors */
     uint32_t capacity, q;
     /* what the search optimises: 0 = cheapest feasible, 1 = Eq. 14 */
     int objective;
@@ -141,7 +145,7 @@ void orc_destroy(orc_model *m)
 {
     if (!m) return;
     free(m->units); free(m->batch); free(m->lat); free(m->thr); free(m->mult);
-    free(m->acc); free(m->src); free(m->dst); free(m->plen); free(m->pnode); free(m->pf);
+    free(m->acc); free(m->src); free(m->dst); free(m->fac); free(m->plen); free(m->pnode); free(m->pf);
     free(m);
 }
 
@@ -274,21 +278,90 @@ int orc_get_path(const orc_model *m, int k, int *nodes, double *f)
 }
 
 /* ---- replicas and cost of every (task, choice) at one demand (Eq. 5-7) ---- */
+/* replicas (Eq. 6) and cost (Eq. 7) of choice c of task t under a demand of `need` micro-requests/s */
+static int replicas_and_cost(const orc_model *m, uint64_t need, uint32_t t, uint32_t c, uint32_t *rep, int32_t *cost)
+{
+    uint64_t per = 1000ull * m->thr[(size_t)t * m->C + c];   /* one replica, same unit */
+    uint64_t r = need / per + (need % per != 0);
+    if (r < 1) r = 1;
+    uint64_t k = r * m->units[part_of(m, c)];
+    if (r > 0xFFFFFFFFull || k > 0x7FFFFFFFull) return ORC_E_RANGE;
+    *rep = (uint32_t)r; *cost = (int32_t)k;
+    return ORC_OK;
+}
+
+static int cost_table_of(const orc_model *m, const uint64_t *need, uint32_t *rep, int32_t *cost)
+{
+    for (uint32_t t = 0; t < m->T; t++)
+        for (uint32_t c = 0; c < m->C; c++) {
+            int rc = replicas_and_cost(m, need[t], t, c, &rep[(size_t)t * m->C + c], &cost[(size_t)t * m->C + c]);
+            if (rc) return rc;
+        }
+    return ORC_OK;
+}
+
 int orc_cost_table(const orc_model *m, uint32_t demand_mrps, uint32_t *rep, int32_t *cost)
 {
-    for (uint32_t t = 0; t < m->T; t++) {
-        uint64_t need = (uint64_t)demand_mrps * m->mult[t];          /* micro-requests/s */
-        for (uint32_t c = 0; c < m->C; c++) {
-            uint64_t per = 1000ull * m->thr[(size_t)t * m->C + c];   /* one replica, same unit */
-            uint64_t r = (need + per - 1) / per;
-            if (r < 1) r = 1;
-            uint64_t k = r * m->units[part_of(m, c)];
-            if (r > 0xFFFFFFFFull || k > 0x7FFFFFFFull) return ORC_E_RANGE;
-            rep[(size_t)t * m->C + c] = (uint32_t)r;
-            cost[(size_t)t * m->C + c] = (int32_t)k;
+    uint64_t need[ORC_MAX_TASKS];
+    for (uint32_t t = 0; t < m->T; t++) need[t] = (uint64_t)demand_mrps * m->mult[t];   /* micro-requests/s */
+    return cost_table_of(m, need, rep, cost);
+}
+
+/* ---- per-variant multiplicative factors (Eq. 4, 5) --------------------------- */
+#define ORC_FACTOR_MAX 1000000u             /* a factor of 1000 */
+#define ORC_NEED_MAX ((uint64_t)1 << 44)    /* micro-requests/s */
+
+/* fac[e * V + v]: requests sent along edge e per request served by variant v of the edge's
+   tail, in 1/1000ths; NULL returns to the fixed per-task multipliers */
+int orc_set_factors(orc_model *m, const uint32_t *fac)
+{
+    if (!m) return ORC_E_ARG;
+    free(m->fac); m->fac = NULL;
+    if (!fac) return ORC_OK;
+    if (m->E == 0) return ORC_E_ARG;
+    for (size_t i = 0; i < (size_t)m->E * m->V; i++) if (fac[i] == 0 || fac[i] > ORC_FACTOR_MAX) return ORC_E_ARG;
+    m->fac = dup_mem(fac, (size_t)m->E * m->V * sizeof *fac);
+    return m->fac ? ORC_OK : ORC_E_MEM;
+}
+
+/*
+ * Demand at every task for one choice of variants (Eq. 5).  A source sees R * m_t; any
+ * other task the sum over its incoming edges of the tail's demand times the factor of the
+ * tail's variant, each product rounded down to whole micro-requests/s.
+ */
+static int demand_flow(const orc_model *m, uint32_t demand_mrps, const uint32_t *variant, uint64_t *need)
+{
+    int done[ORC_MAX_TASKS] = {0};
+    for (uint32_t round = 0; round < m->T; round++)
+        for (uint32_t t = 0; t < m->T; t++) {
+            if (done[t]) continue;
+            int ready = 1;
+            for (int i = 0; i < m->npred[t]; i++) if (!done[m->pred[t][i]]) ready = 0;
+            if (!ready) continue;
+            uint64_t r = 0;
+            if (m->npred[t] == 0) r = (uint64_t)demand_mrps * m->mult[t];
+            else
+                for (uint32_t e = 0; e < m->E; e++)
+                    if (m->dst[e] == t) r += need[m->src[e]] * m->fac[(size_t)e * m->V + variant[m->src[e]]] / 1000u;
+            if (r >= ORC_NEED_MAX) return ORC_E_RANGE;
+            need[t] = r; done[t] = 1;
         }
-    }
     return ORC_OK;
+}
+
+/* tasks whose variant changes some downstream demand: an outgoing edge with unequal factors */
+static uint32_t influencers(const orc_model *m, uint32_t *list)
+{
+    uint32_t n = 0;
+    for (uint32_t t = 0; t < m->T; t++) {
+        int varies = 0;
+        for (uint32_t e = 0; e < m->E; e++)
+            if (m->src[e] == t)
+                for (uint32_t v = 1; v < m->V; v++)
+                    if (m->fac[(size_t)e * m->V + v] != m->fac[(size_t)e * m->V]) varies = 1;
+        if (varies) list[n++] = t;
+    }
+    return n;
 }
 
 /* ---- per-task prune --------------------------------------------------------- */
@@ -349,9 +422,12 @@ static void reference_tuple(const orc_model *m, uint32_t u, uint32_t *lat_max, u
     }
 }
 
-/* may task t use choice c at all under the restrictions? */
-static int allowed(const orc_model *m, const int32_t *cost, uint32_t slo_latency_us, uint32_t t, uint32_t c)
+/* may task t use choice c at all under the restrictions?  only[t], if given and not
+   UINT32_MAX, is the one variant task t is held to (per-variant factors, below) */
+static int allowed(const orc_model *m, const int32_t *cost, uint32_t slo_latency_us, uint32_t t, uint32_t c,
+                   const uint32_t *only)
 {
+    if (only && only[t] != UINT32_MAX && variant_of(m, c) != only[t]) return 0;
     if (!m->space_a && variant_of(m, c) != best_variant(m, t)) return 0;
     if (!m->space_s && part_of(m, c) != whole_partition(m)) return 0;
     if (!m->space_t) {
@@ -413,14 +489,14 @@ double orc_budget_margin(const orc_model *m)
  * remain, thin each variant to floor(cap/V) choices evenly spaced by latency
  * rank, fastest and slowest always kept.
  */
-static int prune_task(const orc_model *m, const int32_t *cost, uint32_t slo_latency_us,
-                      uint32_t cap, uint32_t t, uint16_t *ids, uint32_t *K, uint32_t *truncated)
+static int prune_task(const orc_model *m, const int32_t *cost, uint32_t slo_latency_us, uint32_t cap,
+                      const uint32_t *only, uint32_t t, uint16_t *ids, uint32_t *K, uint32_t *truncated)
 {
     const uint32_t C = m->C;
     *truncated = 0;
     if (cap == 0) {
         uint32_t n = 0;
-        for (uint32_t c = 0; c < C; c++) if (allowed(m, cost, slo_latency_us, t, c)) ids[n++] = (uint16_t)c;
+        for (uint32_t c = 0; c < C; c++) if (allowed(m, cost, slo_latency_us, t, c, only)) ids[n++] = (uint16_t)c;
         *K = n;
         return ORC_OK;
     }
@@ -447,7 +523,7 @@ static int prune_task(const orc_model *m, const int32_t *cost, uint32_t slo_late
         if (on && s > through) through = s;
     }
     for (uint32_t c = 0; c < C; c++)
-        alive[c] = allowed(m, cost, slo_latency_us, t, c) &&
+        alive[c] = allowed(m, cost, slo_latency_us, t, c, only) &&
                    (uint64_t)m->q * ((uint64_t)m->lat[(size_t)t * C + c] + through) <= slo_latency_us;
 
     /* (b) exact dominance on (latency down, accuracy up, cost down) */
@@ -498,13 +574,13 @@ static int prune_task(const orc_model *m, const int32_t *cost, uint32_t slo_late
 int orc_pruned(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us, uint32_t cap,
                uint32_t task, uint16_t *ids, uint32_t *K, uint32_t *truncated)
 {
-    if (task >= m->T) return ORC_E_ARG;
+    if (task >= m->T || m->fac) return ORC_E_ARG;
     size_t n = (size_t)m->T * m->C;
     uint32_t *rep = (uint32_t *)malloc(n * sizeof *rep);
     int32_t *cost = (int32_t *)malloc(n * sizeof *cost);
     if (!rep || !cost) { free(rep); free(cost); return ORC_E_MEM; }
     int rc = orc_cost_table(m, demand_mrps, rep, cost);
-    if (rc == ORC_OK) rc = prune_task(m, cost, slo_latency_us, cap, task, ids, K, truncated);
+    if (rc == ORC_OK) rc = prune_task(m, cost, slo_latency_us, cap, NULL, task, ids, K, truncated);
     free(rep); free(cost);
     return rc;
 }
@@ -518,25 +594,36 @@ typedef struct {
     uint32_t truncated;
     uint64_t space;           /* prod K_t (0 if some K_t = 0) */
     uint32_t slo_l; double slo_a;
+    uint32_t demand;
 } level_t;
 
 static void level_free(level_t *L) { free(L->rep); free(L->cost); free(L->ids); }
 
-static int level_init(level_t *L, const orc_model *m, uint32_t demand, uint32_t slo_l, double slo_a, uint32_t cap)
+/* only: NULL, or per task the one variant it is held to (UINT32_MAX = free); the demands
+   then follow the per-variant factors with every held task on its variant */
+static int level_init_held(level_t *L, const orc_model *m, uint32_t demand, uint32_t slo_l, double slo_a,
+                           uint32_t cap, const uint32_t *only)
 {
     memset(L, 0, sizeof *L);
     size_t n = (size_t)m->T * m->C;
-    L->m = m; L->slo_l = slo_l; L->slo_a = slo_a;
+    L->m = m; L->slo_l = slo_l; L->slo_a = slo_a; L->demand = demand;
     L->rep = (uint32_t *)malloc(n * sizeof(uint32_t));
     L->cost = (int32_t *)malloc(n * sizeof(int32_t));
     L->ids = (uint16_t *)malloc(n * sizeof(uint16_t));
     if (!L->rep || !L->cost || !L->ids) { level_free(L); return ORC_E_MEM; }
-    int rc = orc_cost_table(m, demand, L->rep, L->cost);
+    int rc;
+    if (m->fac) {
+        if (!only || !m->space_t) { level_free(L); return ORC_E_ARG; }
+        uint32_t v[ORC_MAX_TASKS]; uint64_t need[ORC_MAX_TASKS];
+        for (uint32_t t = 0; t < m->T; t++) v[t] = only[t] == UINT32_MAX ? 0 : only[t];
+        rc = demand_flow(m, demand, v, need);
+        if (!rc) rc = cost_table_of(m, need, L->rep, L->cost);
+    } else rc = orc_cost_table(m, demand, L->rep, L->cost);
     if (rc) { level_free(L); return rc; }
     unsigned __int128 space = 1;
     for (uint32_t t = 0; t < m->T; t++) {
         uint32_t tr = 0;
-        rc = prune_task(m, L->cost, slo_l, cap, t, L->ids + (size_t)t * m->C, &L->K[t], &tr);
+        rc = prune_task(m, L->cost, slo_l, cap, only, t, L->ids + (size_t)t * m->C, &L->K[t], &tr);
         if (rc) { level_free(L); return rc; }
         L->truncated |= tr;
         space *= L->K[t];
@@ -544,6 +631,12 @@ static int level_init(level_t *L, const orc_model *m, uint32_t demand, uint32_t 
     }
     L->space = (uint64_t)space;
     return ORC_OK;
+}
+
+static int level_init(level_t *L, const orc_model *m, uint32_t demand, uint32_t slo_l, double slo_a, uint32_t cap)
+{
+    if (m->fac) return ORC_E_ARG;     /* with per-variant factors a level is a union of held levels */
+    return level_init_held(L, m, demand, slo_l, slo_a, cap, NULL);
 }
 
 typedef struct { uint32_t lat; int32_t cost; double acc; uint8_t mask; } score_t;
@@ -571,9 +664,19 @@ static score_t score(const level_t *L, uint64_t i, uint32_t *c_out)
         if (s > worst) worst = s;
     }
     uint64_t lat = (uint64_t)m->q * worst;
-    /* Eq. 7, 8 */
+    /* Eq. 7, 8; with per-variant factors the demands are those of this candidate's own variants */
     int64_t cost = 0;
-    for (uint32_t t = 0; t < m->T; t++) cost += L->cost[(size_t)t * m->C + c[t]];
+    if (m->fac) {
+        uint64_t need[ORC_MAX_TASKS];
+        if (demand_flow(m, L->demand, v, need)) cost = 0x7FFFFFFF;
+        else
+            for (uint32_t t = 0; t < m->T; t++) {
+                uint32_t r; int32_t k;
+                if (replicas_and_cost(m, need[t], t, c[t], &r, &k)) k = 0x7FFFFFFF;
+                cost += k;
+            }
+    } else
+        for (uint32_t t = 0; t < m->T; t++) cost += L->cost[(size_t)t * m->C + c[t]];
     /* Eq. 11-13 */
     double a = raw_accuracy(m, v) / m->amax;
     score_t s;
@@ -603,9 +706,16 @@ static void result_fill(orc_result *r, const level_t *L, uint64_t i)
     r->index = i; r->feasible = 1;
     r->accuracy = s.acc; r->latency_us = s.lat; r->cost = s.cost;
     r->objective = m->alpha * s.acc - m->beta * (double)s.cost;
+    uint64_t need[ORC_MAX_TASKS]; uint32_t v[ORC_MAX_TASKS] = {0};
+    for (uint32_t t = 0; t < m->T; t++) v[t] = variant_of(m, c[t]);
+    int flow_ok = m->fac && demand_flow(m, L->demand, v, need) == ORC_OK;
     for (uint32_t t = 0; t < m->T; t++) {
         r->choice[t] = (uint16_t)c[t];
         r->replicas[t] = L->rep[(size_t)t * m->C + c[t]];
+        if (m->fac) {
+            int32_t k;
+            if (!flow_ok || replicas_and_cost(m, need[t], t, c[t], &r->replicas[t], &k)) r->replicas[t] = 0;
+        }
     }
     /* sum_t c_t * C^t by Horner from the last task; it only grows */
     unsigned __int128 full = 0;
@@ -658,6 +768,76 @@ static void argmin_range(const level_t *L, uint64_t lo, uint64_t hi, int threads
 }
 
 /*
+ * One level with per-variant factors.  The tasks whose variant changes a downstream demand
+ * are held to one variant each, in every combination (lowest task id = fastest digit); with
+ * them held, every task's demand is fixed, so its cost table, its pruned list and the search
+ * of the product of the lists are those of the fixed-factor case.  The level's result is the
+ * best over the combinations: cheapest (or largest objective, then cheapest), then lowest
+ * full_index; `index` repeats full_index, `evaluated` and `flags` add up over the combinations.
+ * If other_obj is given it receives the best objective among feasible candidates whose
+ * variants differ from the winner's (-1e300 if none).
+ */
+static int search_held(const orc_model *m, uint32_t demand, uint32_t slo_l, double slo_a, uint32_t cap,
+                       int threads, orc_result *out, double *other_obj)
+{
+    uint32_t inf[ORC_MAX_TASKS], only[ORC_MAX_TASKS], digit[ORC_MAX_TASKS] = {0};
+    const uint32_t n_inf = influencers(m, inf);
+    double combos = 1.0;
+    for (uint32_t i = 0; i < n_inf; i++) combos *= (double)m->V;
+    if (combos > 1048576.0) return ORC_E_RANGE;
+    result_clear(out, NULL);
+    for (int pass = 0; pass < (other_obj ? 2 : 1); pass++) {
+        if (pass == 1) { *other_obj = -1e300; if (!out->feasible) break; }
+        memset(digit, 0, sizeof digit);
+        for (;;) {
+            for (uint32_t t = 0; t < m->T; t++) only[t] = UINT32_MAX;
+            for (uint32_t i = 0; i < n_inf; i++) only[inf[i]] = digit[i];
+            level_t L;
+            int rc = level_init_held(&L, m, demand, slo_l, slo_a, cap, only);
+            if (rc) return rc;
+            if (pass == 0) {
+                out->evaluated += L.space; out->flags |= L.truncated;
+                int found; int32_t bc; uint64_t bi;
+                argmin_range(&L, 0, L.space, threads, &found, &bc, &bi);
+                if (found) {
+                    orc_result r;
+                    result_clear(&r, &L);
+                    result_fill(&r, &L, bi);
+                    if (r.full_index == UINT64_MAX) { level_free(&L); return ORC_E_RANGE; }
+                    int take = !out->feasible;
+                    if (!take) {
+                        if (m->objective && r.objective != out->objective) take = r.objective > out->objective;
+                        else if (r.cost != out->cost) take = r.cost < out->cost;
+                        else take = r.full_index < out->full_index;
+                    }
+                    if (take) {
+                        uint64_t ev = out->evaluated; uint32_t fl = out->flags;
+                        *out = r; out->index = r.full_index; out->evaluated = ev; out->flags = fl;
+                    }
+                }
+            } else {
+                uint32_t c[ORC_MAX_TASKS];
+                for (uint64_t i = 0; i < L.space; i++) {
+                    score_t sc = score(&L, i, c);
+                    if (sc.mask != 7) continue;
+                    int same = 1;
+                    for (uint32_t t = 0; t < m->T; t++)
+                        if (variant_of(m, c[t]) != variant_of(m, out->choice[t])) same = 0;
+                    if (same) continue;
+                    double obj = m->alpha * sc.acc - m->beta * (double)sc.cost;
+                    if (obj > *other_obj) *other_obj = obj;
+                }
+            }
+            level_free(&L);
+            uint32_t i = 0;
+            while (i < n_inf && ++digit[i] == m->V) digit[i++] = 0;
+            if (i == n_inf) break;
+        }
+    }
+    return ORC_OK;
+}
+
+/*
  * Search every demand level.  results[n_levels]; best_level/max_demand: the
  * feasible level with the largest demand (first position on equal demands),
  * -1 / 0 when none is feasible.
@@ -670,6 +850,12 @@ int orc_search(const orc_model *m, const uint32_t *demand_mrps, uint32_t n_level
     int32_t bl = -1; uint32_t md = 0;
     for (uint32_t l = 0; l < n_levels; l++) {
         if (demand_mrps[l] == 0) return ORC_E_ARG;
+        if (m->fac) {
+            int rc = search_held(m, demand_mrps[l], slo_latency_us, slo_accuracy, cap, threads, &results[l], NULL);
+            if (rc) return rc;
+            if (results[l].feasible && (bl < 0 || demand_mrps[l] > md)) { bl = (int32_t)l; md = demand_mrps[l]; }
+            continue;
+        }
         level_t L;
         int rc = level_init(&L, m, demand_mrps[l], slo_latency_us, slo_accuracy, cap);
         if (rc) return rc;
@@ -768,6 +954,13 @@ double orc_accuracy_margin(const orc_model *m, double slo_accuracy)
 int orc_objective_margin(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us,
                          double slo_accuracy, uint32_t cap, double *margin)
 {
+    if (m->fac) {
+        orc_result r; double other;
+        int rc = search_held(m, demand_mrps, slo_latency_us, slo_accuracy, cap, 1, &r, &other);
+        if (rc) return rc;
+        *margin = !r.feasible ? -1.0 : other == -1e300 ? 1e300 : r.objective - other;
+        return ORC_OK;
+    }
     level_t L;
     int rc = level_init(&L, m, demand_mrps, slo_latency_us, slo_accuracy, cap);
     if (rc) return rc;

@@ -57,7 +57,7 @@ class SplitMix64:
 
 # Stream identifiers: every quantity has its own stream so that re-drawing one
 # of them (the guard band below) leaves the others untouched.
-_S_BASE, _S_ACC, _S_EDGE, _S_SCALAR, _S_SLOA = 1, 2, 3, 4, 5
+_S_BASE, _S_ACC, _S_EDGE, _S_SCALAR, _S_SLOA, _S_FACTOR = 1, 2, 3, 4, 5, 6
 
 
 @dataclass
@@ -320,6 +320,44 @@ def tiny_random(seed: int, T: int | None = None, max_c: int = 8) -> Tuple[Proble
     slo_a = [0.0, 0.3, 0.55, 0.7, 0.85, 0.95][r.randint(0, 5)] + 1e-4 * r.uniform()
     cap = 0 if r.uniform() < 0.5 else r.randint(2 * V, max(2 * V, V * P * B))
     return pb, Search(demand, slo_l, slo_a, cap)
+
+
+def random_factors(pb: Problem, seed: int, varying: Sequence[int] | None = None,
+                   lo: int = 500, hi: int = 3000, whole: bool = False) -> np.ndarray:
+    """uint32[E][V] table of per-variant multiplicative factors (the F(t, v, t') of the
+    paper's Eq. 4) in 1/1000ths: how many requests variant v of an edge's tail sends along
+    the edge per request it serves.  Every edge draws a base in [lo, hi]; on edges whose
+    tail is in `varying` (default: every tail) each variant adds its own step, growing with
+    the variant index the way a more accurate detector finds more objects; the other edges
+    keep one value for all variants.  whole = True rounds everything to multiples of 1000."""
+    r = SplitMix64(7, seed, _S_FACTOR)
+    out = np.zeros((pb.E, pb.V), dtype=np.uint32)
+    for e in range(pb.E):
+        base = r.randint(lo, hi)
+        steps = [r.randint(0, 400) for _ in range(pb.V)]
+        vary = varying is None or int(pb.src[e]) in set(varying)
+        for v in range(pb.V):
+            f = base + (sum(steps[:v + 1]) if vary else 0)
+            if whole:
+                f = max(1000, 1000 * ((f + 500) // 1000))
+            out[e, v] = f
+    return out
+
+
+def traffic3(seed: int = 0, n_levels: int = 32) -> Tuple[Workload, np.ndarray]:
+    """Detector feeding two classifiers (the shape of the paper's traffic-analysis
+    application, Section 4.1): T=3, V=5, partitions {1..7} of 7, batches {1,..,64}
+    (245 choices per task), searched exhaustively at n_levels log-spaced demands 5-500 rps;
+    180 ms, 0.6.  Returns the workload and the factor table: what the detector sends on
+    depends on its variant, the classifiers' own factors are unused (they are sinks)."""
+    name = "traffic3"
+    T, V, sizes, U, batches = 3, 5, [1, 2, 3, 4, 5, 6, 7], 7, [1, 2, 4, 8, 16, 32, 64]
+    lat, thr, acc = _tables(SplitMix64(6, seed, _S_BASE), SplitMix64(6, seed, _S_ACC, recorded_redraw(name, seed)),
+                            T, V, sizes, U, batches)
+    pb = _problem(T, V, sizes, U, batches, lat, thr, acc, [(0, 1), (0, 2)], [1000, 1500, 800], 56)
+    se = Search(_log_sweep(5.0, 100.0, n_levels), 180_000, 0.6, 0)
+    fac = random_factors(pb, seed, lo=600, hi=1800)
+    return Workload(name, [pb], [se], "detector -> 2 classifiers, per-variant factors, exhaustive 245^3 per level"), fac
 
 
 BENCH_WORKLOADS = {

@@ -205,6 +205,54 @@ class PyRef:
         gap = (-w[0] - max(others)) if others else None
         return (w[2], w[1], w[3], w[4], w[5], -w[0]), gap
 
+    # -- per-variant multiplicative factors (Eq. 4, 5) ---------------------------------
+    def demands(self, D: int, variants, factor_milli) -> List[int]:
+        """Demand of every task in micro-requests/s for one choice of variants: D*m_t at a
+        source, elsewhere the sum over incoming edges of floor(demand of the tail x factor of
+        the tail's variant / 1000).  factor_milli[e][v] in the edge order of the problem."""
+        edges = list(zip(self.pb.src.tolist(), self.pb.dst.tolist()))
+        need: Dict[int, int] = {}
+        for t in self.order:
+            inc = [(a, e) for e, (a, b) in enumerate(edges) if b == t]
+            if not inc:
+                need[t] = D * self.m[t]
+            else:
+                need[t] = sum(need[a] * int(factor_milli[e][variants[a]]) // 1000 for a, e in inc)
+        return [need[t] for t in range(self.T)]
+
+    def search_factors(self, D: int, slo_l: int, slo_a: float, factor_milli, objective=None):
+        """Brute force over the whole (allowed) space with per-variant factors; every
+        candidate computes its own demands.  objective = None: cheapest feasible, ties to the
+        lowest full index; (alpha, beta): largest alpha*A - beta*cost, then cheaper, then
+        lowest full index.  Returns (full_index, cost, latency, accuracy, choice, replicas,
+        objective or None) or None, and the number of candidates."""
+        lists = [[c for c in range(self.C) if self.allowed(D, slo_l, t, c)] for t in range(self.T)]
+        slo = Fraction(float(slo_a))
+        capu = int(self.pb.capacity_units)
+        best, count = None, 0
+        for choice in itertools.product(*lists):
+            count += 1
+            variants = [self.variant(c) for c in choice]
+            need = self.demands(D, variants, factor_milli)
+            reps = []
+            for t, c in enumerate(choice):
+                per = 1000 * int(self.thr[t][c])
+                reps.append(max(1, -(-need[t] // per)))
+            cost = sum(r * int(self.pb.units[self.part(c)]) for r, c in zip(reps, choice))
+            lat = self.latency(choice)
+            acc = self._acc(variants) / self.amax
+            if not (lat <= slo_l and acc >= slo and (capu == 0 or cost <= capu)):
+                continue
+            full = sum(c * self.C ** t for t, c in enumerate(choice))
+            if objective is None:
+                key, obj = (cost, full), None
+            else:
+                obj = Fraction(float(objective[0])) * acc - Fraction(float(objective[1])) * cost
+                key = (-obj, cost, full)
+            if best is None or key < best[0]:
+                best = (key, (full, cost, lat, acc, list(choice), reps, obj))
+        return (best[1] if best else None), count
+
     def search(self, D: int, slo_l: int, slo_a: float, cap: int):
         """Returns (best index or None, cost, latency, accuracy Fraction, K list,
         truncated, min |A - slo| seen)."""
