@@ -159,6 +159,36 @@ JSV_API int jsv_set_graph_mode(jsv_ctx* ctx, int on);
 JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial_partitioning,
                                  int graph_informed);
 
+/*
+ * Per-variant multiplicative factors F(t, v, t') (Section 3.2, Eq. 4 and 5) for the system
+ * loaded with jsv_load_profile + jsv_set_dag.  factor_milli: host, [E][V] row-major in the
+ * edge order given to jsv_set_dag, copied; entry [e][v] is the number of requests variant v
+ * of the edge's tail sends along the edge per request it serves, in 1/1000ths, 1 ..
+ * JSV_MAX_FACTOR_MILLI.  NULL returns to the fixed per-task multipliers.  A later
+ * jsv_load_profile or jsv_set_dag drops the table.
+ *
+ * With factors set, the demand of a task without predecessors is demand * mult_t as before;
+ * the demand of any other task is the sum over its incoming edges of the tail's demand times
+ * the factor of the tail's chosen variant, floored per edge to whole micro-requests/s; its
+ * mult_t only weighs paths in the accuracy (Eq. 12).  A demand of 2^44 micro-requests/s or more
+ * makes the search return JSV_E_OVERFLOW.
+ *
+ * How a level is searched: every task with an outgoing edge whose factors differ between
+ * variants is held to one variant, in all combinations; inside a combination all demands are
+ * fixed and cost table, prune and search are the ordinary ones (prune_cap applies per
+ * combination).  The level's result is the best over the combinations: cheapest, or in
+ * objective mode largest objective then cheapest, then lowest full_index.  In the result,
+ * index repeats full_index, evaluated and flags add up over the combinations.
+ * levels * combinations may not exceed 65536 (jsv_search: JSV_E_BADARG).
+ *
+ * Returns JSV_E_STATE without a loaded profile and graph or in batch mode, JSV_E_BADARG for
+ * a graph without edges or a factor out of range, JSV_E_OVERFLOW if C^T does not fit 64
+ * bits.  While factors are set, jsv_eval_candidates and jsv_get_pruned return JSV_E_STATE,
+ * and so does jsv_search with graph_informed = 0.
+ */
+#define JSV_MAX_FACTOR_MILLI 1000000u
+JSV_API int jsv_set_factors(jsv_ctx* ctx, const uint32_t* factor_milli);
+
 typedef struct {
     uint64_t index;        /* winner's index in the searched space; UINT64_MAX if infeasible */
     uint64_t full_index;   /* sum_t c_t * C^t; UINT64_MAX if infeasible or it does not fit */

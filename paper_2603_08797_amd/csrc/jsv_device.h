@@ -22,6 +22,9 @@ namespace jsv {
 constexpr int MAXT = 16;          // tasks per graph
 constexpr int MAXC = 2048;        // choices per task
 constexpr int TILE_LANES = 256;   // lanes (threads) per enumeration tile
+constexpr int MAXE = MAXT * (MAXT - 1) / 2;   // edges of a task graph without cycles
+constexpr uint16_t NOT_HELD = 0xFFFF;
+constexpr uint64_t NEED_LIMIT = 1ull << 44;   // micro-requests/s a task may see with per-variant factors
 constexpr uint64_t NO_KEY = ~0ull;
 
 // instance flag bits
@@ -80,6 +83,11 @@ struct Graph {
     uint32_t lat_ref[MAXT];        // highest latency of the task's reference variant
     uint64_t lat_path[MAXT];       // heaviest path through the task, tasks weighted by lat_ref
     uint32_t unit_budget[MAXT];    // resource share in whole units, 0xFFFFFFFF = none
+    // per-variant multiplicative factors (Eq. 4): edges by task id in the caller's order
+    uint32_t n_edges;
+    uint32_t pad1;
+    uint8_t  e_src[MAXE], e_dst[MAXE];
+    const uint32_t* fac;      // [n_edges][V] in 1/1000ths, device pointer; null = fixed multipliers
     // tables of this problem, device pointers
     const uint32_t* lat;      // [T][C]
     const uint32_t* thr;      // [T][C]  mrps
@@ -120,6 +128,10 @@ struct Instance {
     // objective of Eq. 14 (inputs, host): maximise alpha * A_obj - beta * cost
     double   alpha, beta;
     double   alpha_n;         // alpha / A_max: factor on A_raw
+    // per-variant factors (input, host): the one variant task id t is held to in this
+    // instance, NOT_HELD = free.  With every task that changes a downstream demand held, the
+    // demands of all tasks are fixed and the instance is an ordinary search.
+    uint16_t held[MAXT];
 };
 
 // Result record as written by the finalize kernel; same layout as jsv_result.

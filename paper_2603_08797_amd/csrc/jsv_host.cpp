@@ -42,6 +42,7 @@ struct HostProblem {
     std::vector<uint32_t> mult;
     uint32_t capacity = 0, q = 2;
     bool have_dag = false;
+    std::vector<uint32_t> fac;     // [E][V] per-variant factors, empty = fixed multipliers
     // staged
     Graph graph;
     bool staged = false;
@@ -137,6 +138,7 @@ int check_profile(uint32_t T, uint32_t V, uint32_t P, uint32_t B, const uint32_t
     hp.lat.assign(lat, lat + n);
     hp.thr.swap(h);
     hp.acc.assign(acc, acc + (size_t)T * V);
+    hp.fac.clear();
     hp.have_profile = true;
     hp.staged = false;
     return JSV_OK;
@@ -174,6 +176,7 @@ int check_dag(uint32_t T, uint32_t E, const uint16_t* src, const uint16_t* dst, 
     hp.capacity = capacity; hp.q = q;
     hp.have_dag = true;
     hp.staged = false;
+    hp.fac.clear();                // factors belong to the edge list they were given for
     if (!hp.have_profile) hp.T = T;
     return JSV_OK;
 }
@@ -190,6 +193,8 @@ int stage_graph(HostProblem& hp, const SpaceFlags& sp = SpaceFlags())
     g.T = T; g.V = V; g.P = hp.P; g.B = hp.B; g.C = C; g.q = hp.q; g.capacity = hp.capacity;
     bool adj[MAXT][MAXT] = {};
     for (uint32_t e = 0; e < hp.E; ++e) adj[hp.src[e]][hp.dst[e]] = true;
+    g.n_edges = hp.E;              // at most MAXE: no repeated edge, no cycle
+    for (uint32_t e = 0; e < hp.E; ++e) { g.e_src[e] = (uint8_t)hp.src[e]; g.e_dst[e] = (uint8_t)hp.dst[e]; }
     // Kahn, lowest task id first
     {
         int indeg[MAXT] = {};
@@ -341,13 +346,14 @@ int ensure_pinned(jsv_ctx* ctx, size_t bytes)
 int upload_problems(jsv_ctx* ctx, HostProblem* hps, uint32_t n)
 {
     size_t off = align_up(sizeof(Graph) * n);
-    std::vector<size_t> o_lat(n), o_thr(n), o_acc(n), o_units(n);
+    std::vector<size_t> o_lat(n), o_thr(n), o_acc(n), o_units(n), o_fac(n);
     for (uint32_t k = 0; k < n; ++k) {
         const HostProblem& hp = hps[k];
         o_acc[k] = off;   off = align_up(off + hp.acc.size() * sizeof(double));
         o_lat[k] = off;   off = align_up(off + hp.lat.size() * sizeof(uint32_t));
         o_thr[k] = off;   off = align_up(off + hp.thr.size() * sizeof(uint32_t));
         o_units[k] = off; off = align_up(off + hp.units.size() * sizeof(uint32_t));
+        o_fac[k] = off;   off = align_up(off + hp.fac.size() * sizeof(uint32_t));
     }
     if (ctx->d_problems_bytes < off) {
         if (ctx->d_problems) { HIP_TRY(ctx, hipFree(ctx->d_problems)); ctx->d_problems = nullptr; ctx->d_problems_bytes = 0; }
@@ -363,11 +369,13 @@ int upload_problems(jsv_ctx* ctx, HostProblem* hps, uint32_t n)
         g.lat = (const uint32_t*)(base + o_lat[k]);
         g.thr = (const uint32_t*)(base + o_thr[k]);
         g.units = (const uint32_t*)(base + o_units[k]);
+        g.fac = hp.fac.empty() ? nullptr : (const uint32_t*)(base + o_fac[k]);
         std::memcpy(blob.data() + sizeof(Graph) * k, &g, sizeof g);
         std::memcpy(blob.data() + o_acc[k], hp.acc.data(), hp.acc.size() * sizeof(double));
         std::memcpy(blob.data() + o_lat[k], hp.lat.data(), hp.lat.size() * sizeof(uint32_t));
         std::memcpy(blob.data() + o_thr[k], hp.thr.data(), hp.thr.size() * sizeof(uint32_t));
         std::memcpy(blob.data() + o_units[k], hp.units.data(), hp.units.size() * sizeof(uint32_t));
+        if (!hp.fac.empty()) std::memcpy(blob.data() + o_fac[k], hp.fac.data(), hp.fac.size() * sizeof(uint32_t));
     }
     HIP_TRY(ctx, hipMemcpyAsync(ctx->d_problems, blob.data(), off, hipMemcpyHostToDevice, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));      // blob is a local buffer
@@ -542,7 +550,45 @@ Instance make_instance(const jsv_ctx* ctx, const HostProblem& hp, uint32_t probl
     in.demand = s.demand; in.slo_l = s.slo_l; in.cap = s.cap;
     in.slo_a = s.slo_a;
     in.slo_raw = s.slo_a * hp.graph.amax;
+    for (auto& h : in.held) h = jsv::NOT_HELD;
     return in;
+}
+
+// Tasks whose variant changes a downstream demand: an outgoing edge with unequal factors.
+std::vector<uint32_t> influencers(const HostProblem& hp)
+{
+    std::vector<uint32_t> out;
+    for (uint32_t t = 0; t < hp.T; ++t) {
+        bool varies = false;
+        for (uint32_t e = 0; e < hp.E; ++e)
+            if (hp.src[e] == t)
+                for (uint32_t v = 1; v < hp.V; ++v)
+                    varies |= hp.fac[(size_t)e * hp.V + v] != hp.fac[(size_t)e * hp.V];
+        if (varies) out.push_back(t);
+    }
+    return out;
+}
+
+constexpr uint64_t MAX_HELD_INSTANCES = 65536;
+
+// Combinations of held variants per level; 0 if there are too many for one search.
+uint64_t held_combinations(const HostProblem& hp, uint32_t n_levels)
+{
+    uint64_t n = 1;
+    for (size_t k = influencers(hp).size(); k > 0; --k) {
+        n *= hp.V;
+        if (n * n_levels > MAX_HELD_INSTANCES) return 0;
+    }
+    return n;
+}
+
+// Is result a (one combination of held variants) better than the level's best so far, b?
+bool held_better(int objective, const jsv_result& a, const jsv_result& b)
+{
+    if (!b.feasible) return true;
+    if (objective && a.objective != b.objective) return a.objective > b.objective;
+    if (a.cost_units != b.cost_units) return a.cost_units < b.cost_units;
+    return a.full_index < b.full_index;
 }
 
 int ready_single(jsv_ctx* ctx)
@@ -658,6 +704,11 @@ JSV_API size_t jsv_workspace_bytes(const jsv_ctx* ctx, uint32_t n_levels, uint32
     } else {
         if (!ctx->single.have_profile) return 0;
         t_max = ctx->single.T; c_max = ctx->single.C; k_max = k_max_of(ctx->single, prune_cap);
+        if (!ctx->single.fac.empty()) {
+            const uint64_t n_sub = held_combinations(ctx->single, n_levels);
+            if (n_sub == 0) return 0;
+            n_levels = (uint32_t)(n_levels * n_sub);
+        }
     }
     const uint32_t grid = ctx->grid ? ctx->grid : 256u * 8u;
     return make_layout(n_levels, t_max, k_max, c_max, grid, 0).total;
@@ -721,10 +772,75 @@ JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_lev
     int rc = ready_single(ctx);
     if (rc) return rc;
     const HostProblem& hp = ctx->single;
+    if (!hp.fac.empty()) {
+        // Per-variant factors: one instance per (level, combination of held variants), lowest
+        // held task id = fastest digit; the level's result is the best over its combinations.
+        if (!ctx->space_t) return JSV_E_STATE;
+        const std::vector<uint32_t> inf = influencers(hp);
+        const uint64_t n_sub = held_combinations(hp, n_levels);
+        if (n_sub == 0) return JSV_E_BADARG;
+        std::vector<Instance> inst((size_t)n_levels * n_sub);
+        for (uint32_t l = 0; l < n_levels; ++l)
+            for (uint64_t u = 0; u < n_sub; ++u) {
+                Instance in = make_instance(ctx, hp, 0, Search{demand_mrps[l], slo_latency_us, prune_cap, slo_accuracy});
+                uint64_t rest = u;
+                for (uint32_t t : inf) { in.held[t] = (uint16_t)(rest % hp.V); rest /= hp.V; }
+                inst[(size_t)l * n_sub + u] = in;
+            }
+        std::vector<jsv_result> sub(inst.size());
+        rc = run_search(ctx, inst, hp.T, k_max_of(hp, prune_cap), hp.C, sub.data(), summary);
+        if (rc) return rc;
+        int32_t best_level = -1;
+        uint32_t max_demand = 0;
+        for (uint32_t l = 0; l < n_levels; ++l) {
+            jsv_result best;
+            std::memset(&best, 0, sizeof best);
+            best.index = best.full_index = ~0ull;
+            best.cost_units = 0x7FFFFFFF;
+            uint64_t evaluated = 0;
+            uint32_t flags = 0;
+            for (uint64_t u = 0; u < n_sub; ++u) {
+                const jsv_result& r = sub[(size_t)l * n_sub + u];
+                evaluated += r.evaluated;
+                flags |= r.flags;
+                if (!r.feasible) continue;
+                if (r.full_index == ~0ull) return JSV_E_OVERFLOW;
+                if (held_better(ctx->objective, r, best)) best = r;
+            }
+            best.index = best.full_index;
+            best.evaluated = evaluated;
+            best.flags = flags;
+            out[l] = best;
+            if (best.feasible && (best_level < 0 || demand_mrps[l] > max_demand)) { best_level = (int32_t)l; max_demand = demand_mrps[l]; }
+        }
+        if (summary) { summary->best_level = best_level; summary->max_demand_mrps = max_demand; }
+        return JSV_OK;
+    }
     std::vector<Instance> inst(n_levels);
     for (uint32_t l = 0; l < n_levels; ++l)
         inst[l] = make_instance(ctx, hp, 0, Search{demand_mrps[l], slo_latency_us, prune_cap, slo_accuracy});
     return run_search(ctx, inst, hp.T, k_max_of(hp, prune_cap), hp.C, out, summary);
+}
+
+JSV_API int jsv_set_factors(jsv_ctx* ctx, const uint32_t* factor_milli)
+{
+    if (!ctx) return JSV_E_NULL;
+    HostProblem& hp = ctx->single;
+    if (ctx->batch_mode || !hp.have_profile || !hp.have_dag) return JSV_E_STATE;
+    if (!factor_milli) {
+        if (!hp.fac.empty()) { hp.fac.clear(); ctx->dirty = true; }
+        return JSV_OK;
+    }
+    if (hp.E == 0) return JSV_E_BADARG;
+    const size_t n = (size_t)hp.E * hp.V;
+    for (size_t k = 0; k < n; ++k)
+        if (factor_milli[k] == 0 || factor_milli[k] > JSV_MAX_FACTOR_MILLI) return JSV_E_BADARG;
+    // the winner's index is reported in the full space: C^T must fit 64 bits
+    unsigned __int128 full = 1;
+    for (uint32_t t = 0; t < hp.T; ++t) { full *= hp.C; if (full >> 64) return JSV_E_OVERFLOW; }
+    hp.fac.assign(factor_milli, factor_milli + n);
+    ctx->dirty = true;
+    return JSV_OK;
 }
 
 JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_latency_us,
@@ -735,6 +851,7 @@ JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo
 {
     if (!ctx || !index || !latency_us || !replicas || !cost || !accuracy || !mask) return JSV_E_NULL;
     if (ctx->batch_mode || !ctx->single.have_profile || !ctx->single.have_dag) return JSV_E_STATE;
+    if (!ctx->single.fac.empty()) return JSV_E_STATE;      // a level is a union of searches there
     int rc = check_search_args(ctx->single, demand_mrps, slo_accuracy, prune_cap);
     if (rc) return rc;
     if (n == 0) return JSV_OK;
@@ -802,6 +919,7 @@ JSV_API int jsv_get_pruned(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_late
 {
     if (!ctx || !choice_ids || !K || !truncated) return JSV_E_NULL;
     if (ctx->batch_mode || !ctx->single.have_profile || !ctx->single.have_dag) return JSV_E_STATE;
+    if (!ctx->single.fac.empty()) return JSV_E_STATE;      // lists depend on the held variants there
     if (task >= ctx->single.T) return JSV_E_BADARG;
     int rc = check_search_args(ctx->single, demand_mrps, 0.0, prune_cap);
     if (rc) return rc;

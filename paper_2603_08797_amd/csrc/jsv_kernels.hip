@@ -168,11 +168,41 @@ __global__ void __launch_bounds__(256) prune_kernel(Plan pl)
     uint8_t*  s_a    = (uint8_t*)(s_rep + C);    // alive after the latency filter
     uint8_t*  s_k    = s_a + C;                  // kept
     __shared__ uint32_t s_left, s_flags;
-    if (tid == 0) { s_left = 0; s_flags = 0; }
+    __shared__ uint64_t s_need;
+    if (tid == 0) {
+        s_left = 0; s_flags = 0;
+        // Eq. 5: demand at the task in micro-requests/s.  Fixed multipliers: R * m_t.  Per-variant
+        // factors (Eq. 4): R * m_t at a source, elsewhere the sum over incoming edges of the tail's
+        // demand times the factor of the variant the tail is held to, floored per edge; walked in
+        // topological order up to this task.
+        uint64_t need = (uint64_t)in->demand * g->mult[t];
+        if (g->fac != nullptr) {
+            uint64_t nd[MAXT];
+            const uint32_t last = g->pos_of[t];
+            for (uint32_t p = 0; p <= last; ++p) {
+                const uint32_t u = g->task_at[p];
+                uint64_t r = 0;
+                if ((g->src_mask >> p) & 1u) r = (uint64_t)in->demand * g->mult[u];
+                else
+                    for (uint32_t e = 0; e < g->n_edges; ++e)
+                        if (g->e_dst[e] == u) {
+                            const uint32_t a = g->e_src[e];
+                            const uint32_t hv = in->held[a] == NOT_HELD ? 0u : in->held[a];
+                            r += nd[a] * g->fac[(size_t)e * V + hv] / 1000u;     // nd < 2^44, factor < 2^20
+                        }
+                if (r >= NEED_LIMIT) { s_flags = F_OVERFLOW; r = 0; }
+                nd[u] = r;
+            }
+            need = nd[t];
+        }
+        s_need = need;
+    }
     if (blockIdx.x == 0 && tid == 0) pl.summary->plan_done = 0;     // counted up by the plan kernel
+    __syncthreads();
 
-    // Eq. 5-7: demand at the task, replicas (at least one), cost in partition units
-    const uint64_t need = (uint64_t)in->demand * g->mult[t];            // micro-requests / s
+    // Eq. 6, 7: replicas (at least one), cost in partition units
+    const uint64_t need = s_need;
+    const uint32_t held = in->held[t];
     const uint64_t budget = (uint64_t)in->slo_l;
     const uint64_t through = g->through[t];
     uint32_t* g_rep  = pl.rep  + ((size_t)i * pl.t_max + t) * pl.c_max;
@@ -181,7 +211,7 @@ __global__ void __launch_bounds__(256) prune_kernel(Plan pl)
     for (uint32_t c = tid; c < C; c += blockDim.x) {
         const uint32_t lat = g->lat[(size_t)t * C + c];
         const uint64_t per = 1000ull * g->thr[(size_t)t * C + c];
-        uint64_t rep = (need + per - 1) / per;
+        uint64_t rep = need / per + (need % per != 0);
         if (rep < 1) rep = 1;
         uint64_t cost = rep * g->units[(c / Bn) % Pn];
         if (rep > 0xFFFFFFFFull || cost > 0x7FFFFFFFull) { my_flags |= F_OVERFLOW; rep = 1; cost = 1; }
@@ -190,7 +220,8 @@ __global__ void __launch_bounds__(256) prune_kernel(Plan pl)
         g_rep[c] = (uint32_t)rep; g_cost[c] = (uint32_t)cost;
         // restrictions of the ablations: variant, partition, static per-task budgets
         bool ok = (g->only_variant[t] == 0xFFFFFFFFu || c / PB == g->only_variant[t]) &&
-                  (g->only_part == 0xFFFFFFFFu || (c / Bn) % Pn == g->only_part);
+                  (g->only_part == 0xFFFFFFFFu || (c / Bn) % Pn == g->only_part) &&
+                  (held == NOT_HELD || c / PB == held);
         if (ok && g->static_budgets) {
             // q*L <= SLO * lat_ref / lat_path, exactly: both sides are below 2^96
             const unsigned __int128 lhs = (unsigned __int128)((uint64_t)g->q * lat) * g->lat_path[t];

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libjsv.so")
 MAX_TASKS = 16
 OK, E_NULL, E_BADARG, E_CYCLE, E_OVERFLOW, E_STATE, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6, -7
 
-EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space", "jsv_set_graph_mode",
+EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space", "jsv_set_factors", "jsv_set_graph_mode",
            "jsv_workspace_bytes", "jsv_set_workspace", "jsv_load_profile", "jsv_set_dag",
            "jsv_search", "jsv_eval_candidates", "jsv_get_pruned", "jsv_load_batch",
            "jsv_search_loaded_batch", "jsv_search_batch"]
@@ -75,6 +75,8 @@ def load_library():
     lib.jsv_set_objective.argtypes = [vp, C.c_int, f64, f64]
     lib.jsv_set_search_space.restype = C.c_int
     lib.jsv_set_search_space.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+    lib.jsv_set_factors.restype = C.c_int
+    lib.jsv_set_factors.argtypes = [vp, vp]
     lib.jsv_set_graph_mode.restype = C.c_int
     lib.jsv_set_graph_mode.argtypes = [vp, C.c_int]
     lib.jsv_workspace_bytes.restype = C.c_size_t
@@ -205,6 +207,17 @@ class Jsv:
         self._check(self._lib.jsv_set_search_space(self._h, int(accuracy_scaling), int(spatial_partitioning),
                                                    int(graph_informed)), "jsv_set_search_space")
 
+    def set_factors(self, factor_milli):
+        """Per-variant multiplicative factors (Eq. 4, 5), [E][V] in 1/1000ths in the edge order of
+        set_dag; None returns to the fixed multipliers.  Call after load_profile and set_dag."""
+        if factor_milli is None:
+            self._check(self._lib.jsv_set_factors(self._h, None), "jsv_set_factors")
+            return
+        f = _u32(factor_milli)
+        if f.shape != (getattr(self, "E", -1), getattr(self, "V", -1)):
+            raise ValueError("factor_milli must have shape [E][V] of the loaded graph and profile")
+        self._check(self._lib.jsv_set_factors(self._h, f.ctypes.data_as(C.c_void_p)), "jsv_set_factors")
+
     def set_graph_mode(self, on: bool = True):
         """Record the launch sequence of a search into a HIP graph and replay it."""
         self._check(self._lib.jsv_set_graph_mode(self._h, int(on)), "jsv_set_graph_mode")
@@ -216,7 +229,7 @@ class Jsv:
         a = np.ascontiguousarray(accuracy, dtype=np.float64)
         self._check(self._lib.jsv_load_profile(self._h, int(T), int(V), int(P), int(B), _ptr(u),
                                                _ptr(b), _ptr(l), _ptr(h), _ptr(a)), "jsv_load_profile")
-        self.T, self.C = int(T), int(V) * int(P) * int(B)
+        self.T, self.C, self.V = int(T), int(V) * int(P) * int(B), int(V)
 
     def set_dag(self, T, src, dst, demand_mult_milli, capacity_units, queue_factor=2):
         s = np.ascontiguousarray(src, dtype=np.uint16)
@@ -224,6 +237,7 @@ class Jsv:
         m = _u32(demand_mult_milli)
         self._check(self._lib.jsv_set_dag(self._h, int(T), int(s.shape[0]), _ptr(s), _ptr(d), _ptr(m),
                                           int(capacity_units), int(queue_factor)), "jsv_set_dag")
+        self.E = int(s.shape[0])
 
     def load(self, pb, derive_throughput: bool = False):
         """Profile and graph of a workloads.Problem."""

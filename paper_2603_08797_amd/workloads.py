@@ -344,20 +344,23 @@ def random_factors(pb: Problem, seed: int, varying: Sequence[int] | None = None,
     return out
 
 
-def traffic3(seed: int = 0, n_levels: int = 32) -> Tuple[Workload, np.ndarray]:
+def traffic3(seed: int = 0, redraw: int | None = None, n_levels: int = 32) -> Workload:
     """Detector feeding two classifiers (the shape of the paper's traffic-analysis
     application, Section 4.1): T=3, V=5, partitions {1..7} of 7, batches {1,..,64}
     (245 choices per task), searched exhaustively at n_levels log-spaced demands 5-500 rps;
-    180 ms, 0.6.  Returns the workload and the factor table: what the detector sends on
-    depends on its variant, the classifiers' own factors are unused (they are sinks)."""
+    180 ms, 0.6.  meta["factor_milli"] holds the per-variant factor table of the two edges:
+    what the detector sends on depends on its variant."""
     name = "traffic3"
+    if redraw is None:
+        redraw = recorded_redraw(name, seed)
     T, V, sizes, U, batches = 3, 5, [1, 2, 3, 4, 5, 6, 7], 7, [1, 2, 4, 8, 16, 32, 64]
-    lat, thr, acc = _tables(SplitMix64(6, seed, _S_BASE), SplitMix64(6, seed, _S_ACC, recorded_redraw(name, seed)),
+    lat, thr, acc = _tables(SplitMix64(6, seed, _S_BASE), SplitMix64(6, seed, _S_ACC, redraw),
                             T, V, sizes, U, batches)
     pb = _problem(T, V, sizes, U, batches, lat, thr, acc, [(0, 1), (0, 2)], [1000, 1500, 800], 56)
     se = Search(_log_sweep(5.0, 100.0, n_levels), 180_000, 0.6, 0)
     fac = random_factors(pb, seed, lo=600, hi=1800)
-    return Workload(name, [pb], [se], "detector -> 2 classifiers, per-variant factors, exhaustive 245^3 per level"), fac
+    return Workload(name, [pb], [se], "detector -> 2 classifiers, per-variant factors, exhaustive 245^3 per level",
+                    meta={"factor_milli": fac})
 
 
 BENCH_WORKLOADS = {
@@ -366,4 +369,5 @@ BENCH_WORKLOADS = {
     "chain4": chain4,
     "xr8": xr8,
     "dagbatch": dagbatch,
+    "traffic3": traffic3,
 }

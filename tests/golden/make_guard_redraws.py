@@ -20,7 +20,7 @@ import oracle  # noqa: E402
 from paper_2603_08797_amd import workloads as W  # noqa: E402
 
 BAND = 1e-9
-CASES = [("chain3", [0]), ("diamond5", [0]), ("chain4", [0]), ("xr8", [0, 1, 2, 3])]
+CASES = [("chain3", [0]), ("diamond5", [0]), ("chain4", [0]), ("xr8", [0, 1, 2, 3]), ("traffic3", [0])]
 
 
 def margin(pb, se):

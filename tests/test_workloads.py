@@ -33,6 +33,10 @@ def test_generators_are_deterministic_and_shaped():
     assert len(d) == 64 and d[0] == 10_000 and d[-1] == 5_000_000
     assert len(W.dagbatch().problems) == 256
     assert {p.T for p in W.dagbatch().problems} == {3, 4, 5, 6}
+    t3 = W.traffic3()
+    f = t3.meta["factor_milli"]
+    assert f.shape == (2, 5) and f.dtype == np.uint32 and (np.diff(f.astype(np.int64), axis=1) >= 0).all()
+    assert np.array_equal(f, W.traffic3().meta["factor_milli"]) and t3.problems[0].C == 245
 
 
 def test_xr8_keeps_its_skeleton_and_differs_by_seed():
@@ -45,7 +49,7 @@ def test_xr8_keeps_its_skeleton_and_differs_by_seed():
 
 
 @pytest.mark.parametrize("name,seeds", [("chain3", [0]), ("diamond5", [0]), ("chain4", [0]),
-                                        ("xr8", [0, 1, 2, 3]), ("dagbatch", [0])])
+                                        ("xr8", [0, 1, 2, 3]), ("dagbatch", [0]), ("traffic3", [0])])
 def test_no_candidate_within_1e_9_of_the_accuracy_slo(name, seeds):
     for seed in seeds:
         w = W.BENCH_WORKLOADS[name](seed=seed)
