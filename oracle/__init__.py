@@ -25,7 +25,7 @@ OK, E_ARG, E_CYCLE, E_RANGE, E_MEM = 0, -1, -2, -3, -4
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc.  Returns the path of the shared object."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-Wall", "-Wextra", "-fopenmp", "-shared", "-fPIC",
+        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-Wall", "-Wextra", "-fopenmp", "-shared", "-fPIC",
                                "-o", _LIB, _SRC])
     return _LIB
 
@@ -35,7 +35,8 @@ class OrcResult(C.Structure):
                 ("accuracy", C.c_double), ("latency_us", C.c_uint32), ("cost", C.c_int32),
                 ("feasible", C.c_uint32), ("flags", C.c_uint32),
                 ("choice", C.c_uint16 * MAX_TASKS), ("replicas", C.c_uint32 * MAX_TASKS),
-                ("objective", C.c_double)]
+                ("objective", C.c_double),
+                ("choice2", C.c_uint16 * MAX_TASKS), ("replicas2", C.c_uint32 * MAX_TASKS)]
 
 
 _lib = None
@@ -86,6 +87,14 @@ def _load():
                                              C.POINTER(C.c_double)]
         lib.orc_set_search_space.restype = C.c_int
         lib.orc_set_search_space.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+        lib.orc_set_mixtures.restype = C.c_int
+        lib.orc_set_mixtures.argtypes = [vp, C.c_int]
+        lib.orc_options.restype = C.c_int
+        lib.orc_options.argtypes = [vp, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
+                                    vp, vp, vp, vp, vp, vp, vp, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+        lib.orc_mixture_margin.restype = C.c_int
+        lib.orc_mixture_margin.argtypes = [vp, C.c_uint32, C.c_uint32, C.c_double, C.c_uint32,
+                                           C.POINTER(C.c_double)]
         lib.orc_set_factors.restype = C.c_int
         lib.orc_set_factors.argtypes = [vp, vp]
         lib.orc_budget_margin.restype = C.c_double
@@ -119,13 +128,16 @@ class Result:
     choice: List[int]
     replicas: List[int]
     objective: float = 0.0
+    choice2: List[int] = None       # mixtures: second tuple per task (0xFFFF = none)
+    replicas2: List[int] = None
 
 
 def _result(r: OrcResult, T: int) -> Result:
     return Result(int(r.index), int(r.full_index), int(r.evaluated), float(r.accuracy),
                   int(r.latency_us), int(r.cost), bool(r.feasible), int(r.flags),
                   [int(r.choice[t]) for t in range(T)], [int(r.replicas[t]) for t in range(T)],
-                  float(r.objective))
+                  float(r.objective), [int(r.choice2[t]) for t in range(T)],
+                  [int(r.replicas2[t]) for t in range(T)])
 
 
 def max_threads() -> int:
@@ -202,6 +214,39 @@ class Oracle:
             rc = self._lib.orc_set_factors(self._h, _ptr(f))
         if rc != OK:
             raise OracleError(rc, "orc_set_factors")
+
+    def set_mixtures(self, on: bool = True):
+        """Let a task mix two tuples (Eq. 2, 6, 7, 9, 10 with two active instance types)."""
+        rc = self._lib.orc_set_mixtures(self._h, int(on))
+        if rc != OK:
+            raise OracleError(rc, "orc_set_mixtures")
+
+    def options(self, demand_mrps: int, slo_latency_us: int, prune_cap: int, task: int, room: int = 1 << 20):
+        """Mixture mode: surviving options of one task as a list of
+        (c1, c2, m1, m2, latency_us, cost, accuracy) in ascending id, and the thinning flag."""
+        c1 = np.zeros(room, dtype=np.uint16); c2 = np.zeros(room, dtype=np.uint16)
+        m1 = np.zeros(room, dtype=np.uint32); m2 = np.zeros(room, dtype=np.uint32)
+        lat = np.zeros(room, dtype=np.uint32); cost = np.zeros(room, dtype=np.int32)
+        acc = np.zeros(room, dtype=np.float64)
+        n, tr = C.c_uint32(), C.c_uint32()
+        rc = self._lib.orc_options(self._h, int(demand_mrps), int(slo_latency_us), int(prune_cap), int(task),
+                                   room, _ptr(c1), _ptr(c2), _ptr(m1), _ptr(m2), _ptr(lat), _ptr(cost), _ptr(acc),
+                                   C.byref(n), C.byref(tr))
+        if rc != OK:
+            raise OracleError(rc, "orc_options")
+        if n.value > room:
+            raise OracleError(ORC_E_RANGE if "ORC_E_RANGE" in globals() else -3, "orc_options: room")
+        k = n.value
+        return [(int(c1[i]), int(c2[i]), int(m1[i]), int(m2[i]), int(lat[i]), int(cost[i]), float(acc[i]))
+                for i in range(k)], bool(tr.value)
+
+    def mixture_margin(self, demand_mrps: int, slo_latency_us: int, slo_accuracy: float, prune_cap: int) -> float:
+        m = C.c_double()
+        rc = self._lib.orc_mixture_margin(self._h, int(demand_mrps), int(slo_latency_us), float(slo_accuracy),
+                                          int(prune_cap), C.byref(m))
+        if rc != OK:
+            raise OracleError(rc, "orc_mixture_margin")
+        return float(m.value)
 
     def budget_margin(self) -> float:
         return float(self._lib.orc_budget_margin(self._h))

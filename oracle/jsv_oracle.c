@@ -26,6 +26,12 @@
  *                         largest alpha*A_obj - beta*cost; equal objectives ->
  *                         lower cost -> lowest candidate index.
  *
+ *   - optionally, mixtures (Eq. 2, 6, 7, 9, 10 with up to two active tuples per task): besides
+ *                         one tuple replicated M times a task may run M1 >= 1 replicas of one
+ *                         tuple and M2 >= 1 of another, just enough of both to carry R(t);
+ *                         its latency is the slower tuple's, its cost the sum, its accuracy
+ *                         the throughput-weighted mean of the two variants' accuracies.
+ *
  * Paths are enumerated explicitly by depth-first search and every candidate is
  * scored from the tables on its own: no dynamic programming over the graph, no
  * sharing between candidates, no blocking.  Integers are exact (64-bit);
@@ -63,6 +69,8 @@ typedef struct {
     uint16_t choice[ORC_MAX_TASKS];
     uint32_t replicas[ORC_MAX_TASKS];
     double objective;     /* alpha*A_obj - beta*cost of the winner (Eq. 14) */
+    uint16_t choice2[ORC_MAX_TASKS];   /* mixtures: the second tuple, 0xFFFF if the task runs one */
+    uint32_t replicas2[ORC_MAX_TASKS]; /* mixtures: replicas of the second tuple, 0 if none */
 } orc_result;
 
 typedef struct {
@@ -77,6 +85,7 @@ typedef struct {
     double alpha, beta;
     /* search-space restrictions of the paper's ablations (1 = feature on) */
     int space_a, space_s, space_t;
+    int mix;        /* 1: a task may mix two tuples */
     /* graph */
     int npred[ORC_MAX_TASKS], pred[ORC_MAX_TASKS][ORC_MAX_TASKS];
     int nsucc[ORC_MAX_TASKS], succ[ORC_MAX_TASKS][ORC_MAX_TASKS];
@@ -126,19 +135,24 @@ static int has_cycle(const orc_model *m)
     return left != 0;
 }
 
-/* system accuracy of one choice of variants, before normalisation (Eq. 11, 12) */
-static double raw_accuracy(const orc_model *m, const uint32_t *variant)
+/* system accuracy for given per-task accuracies, before normalisation (Eq. 11, 12) */
+static double raw_accuracy_of(const orc_model *m, const double *task_acc)
 {
     double total = 0.0;
     for (int k = 0; k < m->npaths; k++) {
         double ap = 1.0;
-        for (int i = 0; i < m->plen[k]; i++) {
-            int t = m->pnode[(size_t)k * m->T + i];
-            ap *= m->acc[(size_t)t * m->V + variant[t]];
-        }
+        for (int i = 0; i < m->plen[k]; i++) ap *= task_acc[m->pnode[(size_t)k * m->T + i]];
         total += m->pf[k] * ap;
     }
     return total;
+}
+
+/* the same for one choice of variants */
+static double raw_accuracy(const orc_model *m, const uint32_t *variant)
+{
+    double a[ORC_MAX_TASKS];
+    for (uint32_t t = 0; t < m->T; t++) a[t] = m->acc[(size_t)t * m->V + variant[t]];
+    return raw_accuracy_of(m, a);
 }
 
 void orc_destroy(orc_model *m)
@@ -574,7 +588,7 @@ static int prune_task(const orc_model *m, const int32_t *cost, uint32_t slo_late
 int orc_pruned(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us, uint32_t cap,
                uint32_t task, uint16_t *ids, uint32_t *K, uint32_t *truncated)
 {
-    if (task >= m->T || m->fac) return ORC_E_ARG;
+    if (task >= m->T || m->fac || m->mix) return ORC_E_ARG;
     size_t n = (size_t)m->T * m->C;
     uint32_t *rep = (uint32_t *)malloc(n * sizeof *rep);
     int32_t *cost = (int32_t *)malloc(n * sizeof *cost);
@@ -585,11 +599,181 @@ int orc_pruned(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us
     return rc;
 }
 
+/* ---- mixtures of two tuples (Eq. 2, 6, 7, 9, 10) ------------------------------ */
+#define ORC_MIX_MAX_REPLICAS 65535u
+
+/* One way to run a task: m1 replicas of tuple c1 and, if c2 != 0xFFFF, m2 of tuple c2. */
+typedef struct {
+    uint16_t c1, c2;
+    uint32_t m1, m2;
+    uint32_t lat;       /* Eq. 2: the slower of the active tuples */
+    int32_t cost;       /* Eq. 7 */
+    double acc;         /* Eq. 10 */
+    uint64_t id;        /* order of the options: c for a single tuple, C + (c1*C + c2)*65536 + m1 for a mixture */
+} option_t;
+
+int orc_set_mixtures(orc_model *m, int on)
+{
+    if (!m) return ORC_E_ARG;
+    m->mix = on != 0;
+    return ORC_OK;
+}
+
+typedef struct { option_t *v; size_t n, room; } option_list;
+
+static int option_push(option_list *l, const option_t *o)
+{
+    if (l->n == l->room) {
+        size_t room = l->room ? 2 * l->room : 1024;
+        option_t *v = (option_t *)realloc(l->v, room * sizeof *v);
+        if (!v) return ORC_E_MEM;
+        l->v = v; l->room = room;
+    }
+    l->v[l->n++] = *o;
+    return ORC_OK;
+}
+
+/*
+ * Every option of task t under a demand of `need` micro-requests/s, in ascending id.
+ * Single tuples: every allowed choice with its replicas.  Mixtures: allowed c1 < c2 with
+ * m1, m2 >= 1 that carry the demand together while neither (m1-1, m2) nor (m1, m2-1) does.
+ * A mixture that alone costs more than S_avail is left out (it fits no assignment).
+ */
+static int all_options(const orc_model *m, const int32_t *cost, const uint32_t *rep, uint32_t slo_latency_us,
+                       uint64_t need, uint32_t t, option_list *out)
+{
+    const uint32_t C = m->C;
+    for (uint32_t c = 0; c < C; c++) {
+        if (!allowed(m, cost, slo_latency_us, t, c, NULL)) continue;
+        option_t o;
+        o.c1 = (uint16_t)c; o.c2 = 0xFFFF; o.m1 = rep[(size_t)t * C + c]; o.m2 = 0;
+        o.lat = m->lat[(size_t)t * C + c]; o.cost = cost[(size_t)t * C + c];
+        o.acc = m->acc[(size_t)t * m->V + variant_of(m, c)]; o.id = c;
+        int rc = option_push(out, &o);
+        if (rc) return rc;
+    }
+    for (uint32_t c1 = 0; c1 < C; c1++) {
+        if (!allowed(m, cost, slo_latency_us, t, c1, NULL)) continue;
+        const uint64_t h1 = 1000ull * m->thr[(size_t)t * C + c1];
+        const uint64_t alone = need / h1 + (need % h1 != 0);          /* replicas of c1 without help */
+        if (alone < 2) continue;
+        if (alone - 1 > ORC_MIX_MAX_REPLICAS) return ORC_E_RANGE;
+        for (uint32_t c2 = c1 + 1; c2 < C; c2++) {
+            if (!allowed(m, cost, slo_latency_us, t, c2, NULL)) continue;
+            const uint64_t h2 = 1000ull * m->thr[(size_t)t * C + c2];
+            for (uint64_t m1 = 1; m1 < alone; m1++) {
+                const uint64_t rest = need - m1 * h1;                  /* > 0 */
+                const uint64_t m2 = rest / h2 + (rest % h2 != 0);
+                if ((m1 - 1) * h1 + m2 * h2 >= need) continue;         /* one replica of c1 too many */
+                if (m2 > ORC_MIX_MAX_REPLICAS) return ORC_E_RANGE;
+                const uint64_t k = m1 * m->units[part_of(m, c1)] + m2 * m->units[part_of(m, c2)];
+                if (k > 0x7FFFFFFFull) return ORC_E_RANGE;
+                if (m->capacity != 0 && k > m->capacity) continue;
+                option_t o;
+                o.c1 = (uint16_t)c1; o.c2 = (uint16_t)c2; o.m1 = (uint32_t)m1; o.m2 = (uint32_t)m2;
+                const uint32_t l1 = m->lat[(size_t)t * C + c1], l2 = m->lat[(size_t)t * C + c2];
+                o.lat = l1 > l2 ? l1 : l2;
+                o.cost = (int32_t)k;
+                /* Eq. 9, 10: weights are the total throughputs of the two instance types */
+                const double w1 = (double)(m1 * h1), w2 = (double)(m2 * h2);
+                const double a1 = m->acc[(size_t)t * m->V + variant_of(m, c1)];
+                const double a2 = m->acc[(size_t)t * m->V + variant_of(m, c2)];
+                const double p1 = w1 * a1, p2 = w2 * a2;
+                o.acc = (p1 + p2) / (w1 + w2);
+                o.id = C + ((uint64_t)c1 * C + c2) * 65536u + m1;
+                int rc = option_push(out, &o);
+                if (rc) return rc;
+            }
+        }
+    }
+    return ORC_OK;
+}
+
+typedef struct { uint32_t lat; uint64_t id; size_t at; } lat_id;
+static int cmp_lat_id(const void *a, const void *b)
+{
+    const lat_id *x = (const lat_id *)a, *y = (const lat_id *)b;
+    if (x->lat != y->lat) return x->lat < y->lat ? -1 : 1;
+    return x->id < y->id ? -1 : (x->id > y->id);
+}
+
+/*
+ * Surviving options of one task in mixture mode, ascending id.  cap == 0: all of them.
+ * Otherwise the steps of the single-tuple prune on options: (a) latency filter, (b) exact
+ * dominance on (latency, accuracy, cost), equal triples keep the lowest id, (c) if more than
+ * cap remain, the cap options at ranks floor(j*(n-1)/(cap-1)) of the order by (latency, id).
+ */
+static int prune_options(const orc_model *m, uint32_t slo_latency_us, uint32_t cap, uint32_t t,
+                         option_list *all, uint32_t *truncated)
+{
+    *truncated = 0;
+    if (cap == 0) return ORC_OK;
+    if (cap < 2) return ORC_E_ARG;
+    const uint32_t C = m->C;
+    uint64_t lo[ORC_MAX_TASKS];
+    for (uint32_t u = 0; u < m->T; u++) {
+        uint32_t best = m->lat[(size_t)u * C];
+        for (uint32_t c = 1; c < C; c++) if (m->lat[(size_t)u * C + c] < best) best = m->lat[(size_t)u * C + c];
+        lo[u] = best;
+    }
+    uint64_t through = 0;
+    for (int k = 0; k < m->npaths; k++) {
+        int on = 0; uint64_t sum = 0;
+        for (int i = 0; i < m->plen[k]; i++) {
+            uint32_t u = (uint32_t)m->pnode[(size_t)k * m->T + i];
+            if (u == t) on = 1; else sum += lo[u];
+        }
+        if (on && sum > through) through = sum;
+    }
+    size_t n = 0;
+    for (size_t i = 0; i < all->n; i++)                                 /* (a) */
+        if ((uint64_t)m->q * ((uint64_t)all->v[i].lat + through) <= slo_latency_us) all->v[n++] = all->v[i];
+    all->n = n;
+    uint8_t *keep = (uint8_t *)malloc(n ? n : 1);
+    if (!keep) return ORC_E_MEM;
+    for (size_t i = 0; i < n; i++) {                                    /* (b) */
+        const option_t *x = &all->v[i];
+        keep[i] = 1;
+        for (size_t j = 0; j < n && keep[i]; j++) {
+            if (j == i) continue;
+            const option_t *y = &all->v[j];
+            if (y->lat <= x->lat && y->acc >= x->acc && y->cost <= x->cost) {
+                int strict = (y->lat < x->lat) || (y->acc > x->acc) || (y->cost < x->cost);
+                if (strict || y->id < x->id) keep[i] = 0;
+            }
+        }
+    }
+    size_t left = 0;
+    for (size_t i = 0; i < n; i++) if (keep[i]) all->v[left++] = all->v[i];
+    all->n = left;
+    free(keep);
+    if (left > cap) {                                                   /* (c) */
+        *truncated = 1;
+        lat_id *order = (lat_id *)malloc(left * sizeof *order);
+        option_t *kept = (option_t *)malloc(cap * sizeof *kept);
+        if (!order || !kept) { free(order); free(kept); return ORC_E_MEM; }
+        for (size_t i = 0; i < left; i++) { order[i].lat = all->v[i].lat; order[i].id = all->v[i].id; order[i].at = i; }
+        qsort(order, left, sizeof *order, cmp_lat_id);
+        for (uint32_t j = 0; j < cap; j++) kept[j] = all->v[order[((uint64_t)j * (left - 1)) / (cap - 1)].at];
+        /* back to ascending id (insertion sort, cap is small) */
+        for (uint32_t j = 1; j < cap; j++) {
+            option_t x = kept[j]; uint32_t k = j;
+            while (k > 0 && kept[k - 1].id > x.id) { kept[k] = kept[k - 1]; k--; }
+            kept[k] = x;
+        }
+        memcpy(all->v, kept, cap * sizeof *kept);
+        all->n = cap;
+        free(order); free(kept);
+    }
+    return ORC_OK;
+}
+
 /* ---- one level: tables + lists --------------------------------------------- */
 typedef struct {
     const orc_model *m;
     uint32_t *rep; int32_t *cost;
     uint16_t *ids;            /* [T][C] surviving choices */
+    option_t *opt[ORC_MAX_TASKS];   /* mixture mode: surviving options per task instead of ids */
     uint32_t K[ORC_MAX_TASKS];
     uint32_t truncated;
     uint64_t space;           /* prod K_t (0 if some K_t = 0) */
@@ -597,7 +781,11 @@ typedef struct {
     uint32_t demand;
 } level_t;
 
-static void level_free(level_t *L) { free(L->rep); free(L->cost); free(L->ids); }
+static void level_free(level_t *L)
+{
+    free(L->rep); free(L->cost); free(L->ids);
+    for (int t = 0; t < ORC_MAX_TASKS; t++) free(L->opt[t]);
+}
 
 /* only: NULL, or per task the one variant it is held to (UINT32_MAX = free); the demands
    then follow the per-variant factors with every held task on its variant */
@@ -620,9 +808,17 @@ static int level_init_held(level_t *L, const orc_model *m, uint32_t demand, uint
         if (!rc) rc = cost_table_of(m, need, L->rep, L->cost);
     } else rc = orc_cost_table(m, demand, L->rep, L->cost);
     if (rc) { level_free(L); return rc; }
+    if (m->mix && (m->fac || !m->space_t)) { level_free(L); return ORC_E_ARG; }
     unsigned __int128 space = 1;
     for (uint32_t t = 0; t < m->T; t++) {
         uint32_t tr = 0;
+        if (m->mix) {
+            option_list all = {0};
+            rc = all_options(m, L->cost, L->rep, slo_l, (uint64_t)demand * m->mult[t], t, &all);
+            if (!rc) rc = prune_options(m, slo_l, cap, t, &all, &tr);
+            if (!rc && all.n > 0xFFFFFFFFull) rc = ORC_E_RANGE;
+            L->opt[t] = all.v; L->K[t] = (uint32_t)all.n;
+        } else
         rc = prune_task(m, L->cost, slo_l, cap, only, t, L->ids + (size_t)t * m->C, &L->K[t], &tr);
         if (rc) { level_free(L); return rc; }
         L->truncated |= tr;
@@ -641,10 +837,45 @@ static int level_init(level_t *L, const orc_model *m, uint32_t demand, uint32_t 
 
 typedef struct { uint32_t lat; int32_t cost; double acc; uint8_t mask; } score_t;
 
+/* mixture mode: candidate i picks one surviving option per task; c_out[t] = its digits */
+static score_t score_options(const level_t *L, uint64_t i, uint32_t *c_out)
+{
+    const orc_model *m = L->m;
+    const option_t *o[ORC_MAX_TASKS];
+    double a_task[ORC_MAX_TASKS];
+    for (uint32_t t = 0; t < m->T; t++) {
+        uint32_t d = (uint32_t)(i % L->K[t]);
+        i /= L->K[t];
+        o[t] = &L->opt[t][d];
+        a_task[t] = o[t]->acc;
+        if (c_out) c_out[t] = d;
+    }
+    uint64_t worst = 0;                                    /* Eq. 2, 3 */
+    for (int k = 0; k < m->npaths; k++) {
+        uint64_t s = 0;
+        for (int j = 0; j < m->plen[k]; j++) s += o[m->pnode[(size_t)k * m->T + j]]->lat;
+        if (s > worst) worst = s;
+    }
+    uint64_t lat = (uint64_t)m->q * worst;
+    int64_t cost = 0;                                      /* Eq. 7, 8 */
+    for (uint32_t t = 0; t < m->T; t++) cost += o[t]->cost;
+    double a = raw_accuracy_of(m, a_task) / m->amax;       /* Eq. 10-13 */
+    score_t s;
+    s.lat = lat > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)lat;
+    s.cost = cost > 0x7FFFFFFF ? 0x7FFFFFFF : (int32_t)cost;
+    s.acc = a;
+    s.mask = 0;
+    if (lat <= L->slo_l) s.mask |= 1;
+    if (a >= L->slo_a) s.mask |= 2;
+    if (m->capacity == 0 || cost <= (int64_t)m->capacity) s.mask |= 4;
+    return s;
+}
+
 /* score candidate i of the searched space; c_out[t] = its choice ids */
 static score_t score(const level_t *L, uint64_t i, uint32_t *c_out)
 {
     const orc_model *m = L->m;
+    if (m->mix) return score_options(L, i, c_out);
     uint32_t c[ORC_MAX_TASKS], v[ORC_MAX_TASKS];
     for (uint32_t t = 0; t < m->T; t++) {
         uint32_t d = (uint32_t)(i % L->K[t]);
@@ -706,6 +937,16 @@ static void result_fill(orc_result *r, const level_t *L, uint64_t i)
     r->index = i; r->feasible = 1;
     r->accuracy = s.acc; r->latency_us = s.lat; r->cost = s.cost;
     r->objective = m->alpha * s.acc - m->beta * (double)s.cost;
+    if (m->mix) {                                          /* c[] holds digits */
+        for (uint32_t t = 0; t < m->T; t++) {
+            const option_t *o = &L->opt[t][c[t]];
+            r->choice[t] = o->c1; r->choice2[t] = o->c2;
+            r->replicas[t] = o->m1; r->replicas2[t] = o->m2;
+        }
+        r->full_index = UINT64_MAX;                        /* the options have no fixed-size full space */
+        return;
+    }
+    for (uint32_t t = 0; t < m->T; t++) r->choice2[t] = 0xFFFF;
     uint64_t need[ORC_MAX_TASKS]; uint32_t v[ORC_MAX_TASKS] = {0};
     for (uint32_t t = 0; t < m->T; t++) v[t] = variant_of(m, c[t]);
     int flow_ok = m->fac && demand_flow(m, L->demand, v, need) == ORC_OK;
@@ -908,6 +1149,7 @@ int orc_eval(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us, 
              uint32_t cap, const uint64_t *index, uint32_t n,
              uint32_t *latency_us, uint32_t *replicas, int32_t *cost, double *accuracy, uint8_t *mask)
 {
+    if (m->mix) return ORC_E_ARG;
     level_t L;
     int rc = level_init(&L, m, demand_mrps, slo_latency_us, slo_accuracy, cap);
     if (rc) return rc;
@@ -954,6 +1196,7 @@ double orc_accuracy_margin(const orc_model *m, double slo_accuracy)
 int orc_objective_margin(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us,
                          double slo_accuracy, uint32_t cap, double *margin)
 {
+    if (m->mix) return ORC_E_ARG;
     if (m->fac) {
         orc_result r; double other;
         int rc = search_held(m, demand_mrps, slo_latency_us, slo_accuracy, cap, 1, &r, &other);
@@ -982,6 +1225,48 @@ int orc_objective_margin(const orc_model *m, uint32_t demand_mrps, uint32_t slo_
         }
         *margin = other == -1e300 ? 1e300 : wobj - other;
     }
+    level_free(&L);
+    return ORC_OK;
+}
+
+/*
+ * Mixture mode: the surviving options of one task at one level, ascending id; at most room
+ * are written, *n is their number.
+ */
+int orc_options(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us, uint32_t cap, uint32_t task,
+                uint32_t room, uint16_t *c1, uint16_t *c2, uint32_t *m1, uint32_t *m2,
+                uint32_t *latency_us, int32_t *cost, double *accuracy, uint32_t *n, uint32_t *truncated)
+{
+    if (!m->mix || task >= m->T) return ORC_E_ARG;
+    level_t L;
+    int rc = level_init(&L, m, demand_mrps, slo_latency_us, 0.0, cap);
+    if (rc) return rc;
+    *n = L.K[task]; *truncated = L.truncated;
+    for (uint32_t i = 0; i < L.K[task] && i < room; i++) {
+        const option_t *o = &L.opt[task][i];
+        c1[i] = o->c1; c2[i] = o->c2; m1[i] = o->m1; m2[i] = o->m2;
+        latency_us[i] = o->lat; cost[i] = o->cost; accuracy[i] = o->acc;
+    }
+    level_free(&L);
+    return ORC_OK;
+}
+
+/* Mixture mode: smallest |A_obj - slo_accuracy| over the searched space of one level (tests
+   keep away from levels where rounding could flip a candidate's feasibility); 1e300 if empty */
+int orc_mixture_margin(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us, double slo_accuracy,
+                       uint32_t cap, double *margin)
+{
+    if (!m->mix) return ORC_E_ARG;
+    level_t L;
+    int rc = level_init(&L, m, demand_mrps, slo_latency_us, slo_accuracy, cap);
+    if (rc) return rc;
+    double best = 1e300;
+    for (uint64_t i = 0; i < L.space; i++) {
+        double d = score(&L, i, NULL).acc - slo_accuracy;
+        if (d < 0) d = -d;
+        if (d < best) best = d;
+    }
+    *margin = best;
     level_free(&L);
     return ORC_OK;
 }

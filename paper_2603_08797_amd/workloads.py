@@ -322,6 +322,38 @@ def tiny_random(seed: int, T: int | None = None, max_c: int = 8) -> Tuple[Proble
     return pb, Search(demand, slo_l, slo_a, cap)
 
 
+def tiny_mixture(seed: int, T: int | None = None) -> Tuple[Problem, Search]:
+    """Small instance on which mixtures of two tuples matter: demands of a few replicas per
+    task (throughputs 20-120 rps, demand 100-400 rps), a capacity that binds now and then, and
+    accuracy SLOs that fall between the variants' accuracies.  T in 1..3, at most 8 choices."""
+    r = SplitMix64(11, seed)
+    if T is None:
+        T = r.randint(1, 3)
+    V, P = r.randint(2, 3), 2
+    B = 1 if V == 3 else r.randint(1, 2)
+    units = [1, r.randint(2, 3)]
+    batches = [1 << b for b in range(B)]
+    lat = np.zeros((T, V, P, B), dtype=np.uint32)
+    thr = np.zeros((T, V, P, B), dtype=np.uint32)
+    acc = np.zeros((T, V), dtype=np.float64)
+    for t in range(T):
+        accs = sorted(0.55 + 0.4 * r.uniform() for _ in range(V))
+        for v in range(V):
+            acc[t, v] = accs[v]
+            for p in range(P):
+                for b in range(B):
+                    lat[t, v, p, b] = 1000 * r.randint(2, 30)
+                    thr[t, v, p, b] = 1000 * r.randint(20, 120) * units[p]
+    edges = [(i, j) for i in range(T) for j in range(i + 1, T) if r.uniform() < 0.7]
+    mult = [500 * r.randint(1, 4) for _ in range(T)]
+    capacity = r.randint(0, 2) * r.randint(6, 30)
+    pb = _problem(T, V, units, max(units), batches, lat, thr, acc, edges, mult, capacity)
+    demand = np.array(sorted({1000 * r.randint(100, 400) for _ in range(2)}), dtype=np.uint32)
+    slo_l = 1000 * r.randint(40, 200)
+    slo_a = 0.75 + 0.24 * r.uniform()
+    return pb, Search(demand, slo_l, slo_a, 0)
+
+
 def random_factors(pb: Problem, seed: int, varying: Sequence[int] | None = None,
                    lo: int = 500, hi: int = 3000, whole: bool = False) -> np.ndarray:
     """uint32[E][V] table of per-variant multiplicative factors (the F(t, v, t') of the

@@ -113,6 +113,17 @@ class PyRef:
                 G[t] = a * sum(Fraction(self.m[p], tot) * G[p] for p in self.preds[t])
         return sum(Fraction(self.m[s], self.sink_total) * G[s] for s in self.sinks)
 
+    def _acc_values(self, vals) -> Fraction:
+        """The same recursion for given per-task accuracies (exact rationals)."""
+        G: Dict[int, Fraction] = {}
+        for t in self.order:
+            if not self.preds[t]:
+                G[t] = vals[t]
+            else:
+                tot = sum(self.m[p] for p in self.preds[t])
+                G[t] = vals[t] * sum(Fraction(self.m[p], tot) * G[p] for p in self.preds[t])
+        return sum(Fraction(self.m[s], self.sink_total) * G[s] for s in self.sinks)
+
     def latency(self, choice) -> int:
         fin: Dict[int, int] = {}
         for t in self.order:
@@ -252,6 +263,103 @@ class PyRef:
             if best is None or key < best[0]:
                 best = (key, (full, cost, lat, acc, list(choice), reps, obj))
         return (best[1] if best else None), count
+
+    # -- mixtures of two tuples per task (Eq. 2, 6, 7, 9, 10) ---------------------------
+    def mix_options(self, D: int, slo_l: int, t: int) -> List[dict]:
+        """All options of task t, ascending id.  Mixtures are found from the side of the
+        second tuple: for every count m2 of c2 the smallest count m1 of c1 that completes the
+        demand, kept if one replica of c2 less would not do."""
+        need = D * self.m[t]
+        capu = int(self.pb.capacity_units)
+        ok = [c for c in range(self.C) if self.allowed(D, slo_l, t, c)]
+        out = []
+        for c in ok:
+            rep, cost = self.rep_cost(D, t, c)
+            a = self.accF[t][self.variant(c)]
+            out.append(dict(id=c, c1=c, c2=0xFFFF, m1=rep, m2=0, lat=int(self.lat[t][c]), cost=cost,
+                            acc=float(self.pb.accuracy[t, self.variant(c)]), accF=a))
+        for c1, c2 in itertools.combinations(ok, 2):
+            h1, h2 = 1000 * int(self.thr[t][c1]), 1000 * int(self.thr[t][c2])
+            u1, u2 = int(self.pb.units[self.part(c1)]), int(self.pb.units[self.part(c2)])
+            m2 = 1
+            while m2 * h2 < need:
+                m1 = -(-(need - m2 * h2) // h1)
+                if m1 * h1 + (m2 - 1) * h2 < need:
+                    cost = m1 * u1 + m2 * u2
+                    if capu == 0 or cost <= capu:
+                        a1, a2 = self.accF[t][self.variant(c1)], self.accF[t][self.variant(c2)]
+                        w1, w2 = float(m1 * h1), float(m2 * h2)
+                        f1 = float(self.pb.accuracy[t, self.variant(c1)])
+                        f2 = float(self.pb.accuracy[t, self.variant(c2)])
+                        out.append(dict(id=self.C + (c1 * self.C + c2) * 65536 + m1, c1=c1, c2=c2, m1=m1, m2=m2,
+                                        lat=max(int(self.lat[t][c1]), int(self.lat[t][c2])), cost=cost,
+                                        acc=(w1 * f1 + w2 * f2) / (w1 + w2),
+                                        accF=(m1 * h1 * a1 + m2 * h2 * a2) / (m1 * h1 + m2 * h2)))
+                m2 += 1
+        return sorted(out, key=lambda o: o["id"])
+
+    def mix_lists(self, D: int, slo_l: int, cap: int):
+        """Surviving options per task and whether anything was thinned.  Dominance compares the
+        fp64 accuracies (both implementations must take that decision in the same precision)."""
+        lo = [min(int(x) for x in self.lat[t]) for t in range(self.T)]
+        up, down = {}, {}
+        for t in self.order:
+            up[t] = max([up[p] + lo[p] for p in self.preds[t]], default=0)
+        for t in reversed(self.order):
+            down[t] = max([down[s] + lo[s] for s in self.succs[t]], default=0)
+        lists, truncated = [], False
+        for t in range(self.T):
+            opts = self.mix_options(D, slo_l, t)
+            if cap:
+                opts = [o for o in opts if self.q * (o["lat"] + up[t] + down[t]) <= slo_l]
+                # skyline: walk by (cost, latency, -accuracy, id); an option survives if nothing
+                # seen before it is at least as fast and at least as accurate
+                opts.sort(key=lambda o: (o["cost"], o["lat"], -o["acc"], o["id"]))
+                front = []
+                for o in opts:
+                    if not any(f["lat"] <= o["lat"] and f["acc"] >= o["acc"] for f in front):
+                        front.append(o)
+                if len(front) > cap:
+                    truncated = True
+                    front.sort(key=lambda o: (o["lat"], o["id"]))
+                    n = len(front)
+                    front = [front[(j * (n - 1)) // (cap - 1)] for j in range(cap)]
+                opts = sorted(front, key=lambda o: o["id"])
+            lists.append(opts)
+        return lists, truncated
+
+    def search_mix(self, D: int, slo_l: int, slo_a: float, cap: int, max_space: int = 300000):
+        """Returns (best or None, K, truncated, margin); best = (idx, cost, lat, acc, options)."""
+        lists, truncated = self.mix_lists(D, slo_l, cap)
+        K = [len(l) for l in lists]
+        space = 1
+        for k in K:
+            space *= k
+        if space > max_space:
+            raise OverflowError(space)
+        slo = Fraction(float(slo_a))
+        capu = int(self.pb.capacity_units)
+        best, margin = None, None
+        if all(K):
+            strides = [1] * self.T
+            for t in range(1, self.T):
+                strides[t] = strides[t - 1] * K[t - 1]
+            for digits in itertools.product(*[range(k) for k in reversed(K)]):
+                digits = digits[::-1]
+                idx = sum(d * s for d, s in zip(digits, strides))
+                opts = [lists[t][digits[t]] for t in range(self.T)]
+                fin: Dict[int, int] = {}
+                for t in self.order:
+                    fin[t] = opts[t]["lat"] + max([fin[p] for p in self.preds[t]], default=0)
+                lat = self.q * max(fin[s] for s in self.sinks)
+                cost = sum(o["cost"] for o in opts)
+                acc = self._acc_values([o["accF"] for o in opts]) / self.amax
+                d = abs(acc - slo)
+                margin = d if margin is None or d < margin else margin
+                if lat <= slo_l and acc >= slo and (capu == 0 or cost <= capu):
+                    if best is None or (cost, idx) < (best[1], best[0]):
+                        best = (idx, cost, lat, acc, opts)
+        return best, K, truncated, margin
 
     def search(self, D: int, slo_l: int, slo_a: float, cap: int):
         """Returns (best index or None, cost, latency, accuracy Fraction, K list,
