@@ -637,7 +637,7 @@ static int option_push(option_list *l, const option_t *o)
  * Every option of task t under a demand of `need` micro-requests/s, in ascending id.
  * Single tuples: every allowed choice with its replicas.  Mixtures: allowed c1 < c2 with
  * m1, m2 >= 1 that carry the demand together while neither (m1-1, m2) nor (m1, m2-1) does.
- * A mixture that alone costs more than S_avail is left out (it fits no assignment).
+ * An option that alone costs more than S_avail is left out (Eq. 8: it fits no assignment).
  */
 static int all_options(const orc_model *m, const int32_t *cost, const uint32_t *rep, uint32_t slo_latency_us,
                        uint64_t need, uint32_t t, option_list *out)
@@ -645,6 +645,7 @@ static int all_options(const orc_model *m, const int32_t *cost, const uint32_t *
     const uint32_t C = m->C;
     for (uint32_t c = 0; c < C; c++) {
         if (!allowed(m, cost, slo_latency_us, t, c, NULL)) continue;
+        if (m->capacity != 0 && (uint32_t)cost[(size_t)t * C + c] > m->capacity) continue;
         option_t o;
         o.c1 = (uint16_t)c; o.c2 = 0xFFFF; o.m1 = rep[(size_t)t * C + c]; o.m2 = 0;
         o.lat = m->lat[(size_t)t * C + c]; o.cost = cost[(size_t)t * C + c];
@@ -665,10 +666,10 @@ static int all_options(const orc_model *m, const int32_t *cost, const uint32_t *
                 const uint64_t rest = need - m1 * h1;                  /* > 0 */
                 const uint64_t m2 = rest / h2 + (rest % h2 != 0);
                 if ((m1 - 1) * h1 + m2 * h2 >= need) continue;         /* one replica of c1 too many */
-                if (m2 > ORC_MIX_MAX_REPLICAS) return ORC_E_RANGE;
-                const uint64_t k = m1 * m->units[part_of(m, c1)] + m2 * m->units[part_of(m, c2)];
-                if (k > 0x7FFFFFFFull) return ORC_E_RANGE;
+                const unsigned __int128 k = (unsigned __int128)m1 * m->units[part_of(m, c1)] +
+                                            (unsigned __int128)m2 * m->units[part_of(m, c2)];
                 if (m->capacity != 0 && k > m->capacity) continue;
+                if (m2 > ORC_MIX_MAX_REPLICAS || k > 0x7FFFFFFFull) return ORC_E_RANGE;
                 option_t o;
                 o.c1 = (uint16_t)c1; o.c2 = (uint16_t)c2; o.m1 = (uint32_t)m1; o.m2 = (uint32_t)m2;
                 const uint32_t l1 = m->lat[(size_t)t * C + c1], l2 = m->lat[(size_t)t * C + c2];

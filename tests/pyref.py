@@ -275,6 +275,8 @@ class PyRef:
         out = []
         for c in ok:
             rep, cost = self.rep_cost(D, t, c)
+            if capu and cost > capu:
+                continue
             a = self.accF[t][self.variant(c)]
             out.append(dict(id=c, c1=c, c2=0xFFFF, m1=rep, m2=0, lat=int(self.lat[t][c]), cost=cost,
                             acc=float(self.pb.accuracy[t, self.variant(c)]), accF=a))

@@ -142,7 +142,9 @@ def test_invariants(seed):
     if low >= 1:
         for t in range(pb.T):
             opts, _ = mix.options(low, se.slo_latency_us, 0, t)
-            assert all(x[1] == 0xFFFF and x[2] == 1 for x in opts) and len(opts) == pb.C
+            assert all(x[1] == 0xFFFF and x[2] == 1 for x in opts)
+            assert len(opts) == sum(1 for p in range(pb.P) for _ in range(pb.V * pb.B)
+                                    if pb.capacity_units == 0 or pb.units[p] <= pb.capacity_units)
 
 
 def test_mixture_of_equal_variants_keeps_the_accuracy(g):
@@ -154,11 +156,12 @@ def test_mixture_of_equal_variants_keeps_the_accuracy(g):
             assert x[6] == pytest.approx(g["accuracy"][0][x[0] // 4], rel=1e-15)
 
 
-def test_capacity_drops_mixtures_that_cannot_fit(g):
+def test_capacity_drops_options_that_cannot_fit(g):
     o = make(g, capacity=4)
     opts, _ = o.options(260000, 100000, 0, 0)
-    assert all(x[5] <= 4 for x in opts if x[1] != 0xFFFF)
-    assert any(x[5] > 4 for x in opts if x[1] == 0xFFFF)        # single tuples stay (as without mixtures)
+    assert opts and all(x[5] <= 4 for x in opts)
+    free, _ = make(g).options(260000, 100000, 0, 0)
+    assert [x for x in free if x[5] <= 4] == opts
 
 
 def test_argument_errors(g):
