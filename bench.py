@@ -40,10 +40,17 @@ MEASURED_TRAFFIC_BYTES = {("xr8", 0, False): (3614 + 11410) * 1024}
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
 
-def algorithmic_ops(jsv_mod, problems, searches, results, factors=None):
+# Mixture mode: every option has its own accuracy, so each candidate is charged its latency
+# compare, its fma, its accuracy compare and its minimum.
+OPS_PER_CANDIDATE_MIXTURES = 4
+
+
+def algorithmic_ops(jsv_mod, problems, searches, results, factors=None, mixtures=False):
     """Lane-ops per step by the rule above; needs K and the number of surviving
     variants of the innermost task (the lowest-numbered source) at every level."""
     total = 0.0
+    if mixtures:
+        return float(sum(r.evaluated for r in results) * OPS_PER_CANDIDATE_MIXTURES)
     if factors is not None:
         # exhaustive search with per-variant factors: the innermost task is held to one variant
         # per combination if its outgoing factors differ between variants, else it keeps all V
@@ -79,11 +86,13 @@ PAPER_CONTEXT = ("paper (other hardware, context only): MILP solve 2-20 s per in
                  "(4x H100 SXM 80GB)")
 
 
-def cpu_baseline(w, objective: bool, factors=None, seconds_target: float = 12.0):
+def cpu_baseline(w, objective: bool, factors=None, mixtures=False, seconds_target: float = 12.0):
     """The oracle, as it is, on a bounded slice of the first demand level."""
     import oracle
     pb, se = w.problems[0], w.searches[0]
     o = oracle.Oracle.from_problem(pb)
+    if mixtures:
+        o.set_mixtures(True)
     if objective:
         o.set_objective(1, 1.0, 0.035)
     threads = max(1, min(oracle.max_threads(), os.cpu_count() or 1))
@@ -128,6 +137,8 @@ def main():
                     help="also run one 1 GiB device-to-device copy, a kernel of known HBM traffic "
                          "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     ap.add_argument("--graph", action="store_true", help="replay the launch sequence as a HIP graph")
+    ap.add_argument("--mixtures", action="store_true",
+                    help="let a task run two tuples side by side (Eq. 9, 10); needs a pruned single-system workload")
     ap.add_argument("--objective", action="store_true",
                     help="maximise alpha*A_obj - beta*cost (alpha 1, beta 0.035) instead of minimum cost")
     args = ap.parse_args()
@@ -147,6 +158,8 @@ def main():
         j.set_objective(1, 1.0, 0.035)
     if args.graph:
         j.set_graph_mode(True)
+    if args.mixtures:
+        j.set_mixtures(True)
     batch = len(w.problems) > 1
     if batch:
         j.load_batch(w.problems, w.searches)
@@ -188,7 +201,7 @@ def main():
     candidates = sum(r.evaluated for r in res)
     ms_per_step = wall / args.steps * 1e3
     enum_avg = sum(enum_s) / len(enum_s) or sum(dev_s) / len(dev_s)     # graph mode times the whole replay
-    ops = algorithmic_ops(jsv, w.problems, w.searches, res, factors)
+    ops = algorithmic_ops(jsv, w.problems, w.searches, res, factors, args.mixtures)
     achieved = (ops or 0.0) / enum_avg
     out = {
         "metric": "candidate assignments evaluated/sec on 1 MI355X; ms to optimum per demand level",
@@ -201,12 +214,13 @@ def main():
         "dtype": "u32+f64", "data": "synthetic",
         "config": {"workload": f"{w.name} seed {args.seed}: {w.note}", "levels_or_problems": n_levels,
                    "objective": "alpha*A_obj - beta*cost, alpha 1, beta 0.035" if args.objective else "minimum cost",
+                   "mixtures": bool(args.mixtures),
                    "candidates_per_step": candidates,
                    "feasible_levels": sum(1 for r in res if r.feasible),
                    "max_serviceable_demand_mrps": summ.max_demand_mrps},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": VALU_PEAK_LANE_OPS / 1e12,
                      "unit": "Tlane-op/s", "frac": achieved / VALU_PEAK_LANE_OPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.seed, args.objective)),
+                     "traffic": None if args.mixtures else MEASURED_TRAFFIC_BYTES.get((args.workload, args.seed, args.objective)),
                      "kernel": "enumerate_kernel", "kernel_ms": enum_avg * 1e3,
                      "ops_per_candidate": (ops or 0.0) / max(candidates, 1),
                      "unshared_count": {"ops_per_candidate": UNSHARED_OPS_PER_CANDIDATE,
@@ -215,7 +229,7 @@ def main():
         "context": PAPER_CONTEXT,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, args.objective, factors)
+        out["cpu_baseline"] = cpu_baseline(w, args.objective, factors, args.mixtures)
     j.close()
     print(json.dumps(out))
 

@@ -186,6 +186,32 @@ JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial
  * bits.  While factors are set, jsv_eval_candidates and jsv_get_pruned return JSV_E_STATE,
  * and so does jsv_search with graph_informed = 0.
  */
+/*
+ * Mixtures of two tuples per task (Section 3.2: Eq. 2, 6, 7 with two active instance types and
+ * the throughput-weighted task accuracy of Eq. 9, 10).  on != 0: besides replicating one tuple
+ * a task may run m1 >= 1 replicas of tuple c1 and m2 >= 1 of tuple c2 (c1 < c2), where
+ * m1*H1 + m2*H2 covers the task's demand and neither (m1-1, m2) nor (m1, m2-1) does.  Such an
+ * option has the latency of its slower tuple, the cost m1*units1 + m2*units2 and the accuracy
+ * (m1*H1*A1 + m2*H2*A2) / (m1*H1 + m2*H2), evaluated in fp64 as two products, one sum, one
+ * quotient.  Options are ordered by id: c for a single tuple, C + (c1*C + c2)*65536 + m1 for a
+ * mixture; an option that alone costs more than S_avail is left out.  jsv_search then prunes
+ * the options of every task like single choices (latency filter, exact dominance on
+ * (latency, accuracy, cost) with equal triples keeping the lowest id) and, if more than
+ * prune_cap remain (flags bit0), thins them over a grid of latency and accuracy: the n
+ * survivors in the order (latency, id) are cut into bands = floor(sqrt(prune_cap)) runs (rank
+ * r goes to band floor(r*bands/n)), and a band of more than per = floor(prune_cap/bands)
+ * options keeps those at ranks floor(j*(size-1)/(per-1)), j < per, of its order by
+ * (accuracy, id).  The searched space is the product of the surviving
+ * lists, index with task 0 as the fastest digit; full_index is UINT64_MAX; choice2 / replicas2
+ * of the result name the second tuple.
+ *
+ * In mixture mode jsv_search needs 2 <= prune_cap <= JSV_MAX_CHOICES, 1 <= capacity_units <=
+ * 65535 and at most 65536 replicas of any allowed tuple on its own (else JSV_E_BADARG /
+ * JSV_E_OVERFLOW); it returns JSV_E_STATE together with per-variant factors, graph_informed =
+ * 0, objective mode or batch mode, and so do jsv_eval_candidates and jsv_get_pruned.
+ */
+JSV_API int jsv_set_mixtures(jsv_ctx* ctx, int on);
+
 #define JSV_MAX_FACTOR_MILLI 1000000u
 JSV_API int jsv_set_factors(jsv_ctx* ctx, const uint32_t* factor_milli);
 
@@ -203,6 +229,9 @@ typedef struct {
     uint16_t choice[JSV_MAX_TASKS];     /* winner's choice id per task */
     uint32_t replicas[JSV_MAX_TASKS];   /* M of Eq. 6 per task */
     double   objective;    /* alpha * A_obj - beta * cost_units of the winner (Eq. 14) */
+    uint16_t choice2[JSV_MAX_TASKS];    /* mixture mode: the task's second tuple; 0xFFFF if the
+                                           task runs one tuple (always, outside mixture mode) */
+    uint32_t replicas2[JSV_MAX_TASKS];  /* mixture mode: replicas of the second tuple; else 0 */
 } jsv_result;
 
 typedef struct {

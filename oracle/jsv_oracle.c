@@ -690,11 +690,17 @@ static int all_options(const orc_model *m, const int32_t *cost, const uint32_t *
     return ORC_OK;
 }
 
-typedef struct { uint32_t lat; uint64_t id; size_t at; } lat_id;
+typedef struct { uint32_t lat; double acc; uint64_t id; size_t at; } opt_key;
 static int cmp_lat_id(const void *a, const void *b)
 {
-    const lat_id *x = (const lat_id *)a, *y = (const lat_id *)b;
+    const opt_key *x = (const opt_key *)a, *y = (const opt_key *)b;
     if (x->lat != y->lat) return x->lat < y->lat ? -1 : 1;
+    return x->id < y->id ? -1 : (x->id > y->id);
+}
+static int cmp_acc_id(const void *a, const void *b)
+{
+    const opt_key *x = (const opt_key *)a, *y = (const opt_key *)b;
+    if (x->acc != y->acc) return x->acc < y->acc ? -1 : 1;
     return x->id < y->id ? -1 : (x->id > y->id);
 }
 
@@ -702,7 +708,12 @@ static int cmp_lat_id(const void *a, const void *b)
  * Surviving options of one task in mixture mode, ascending id.  cap == 0: all of them.
  * Otherwise the steps of the single-tuple prune on options: (a) latency filter, (b) exact
  * dominance on (latency, accuracy, cost), equal triples keep the lowest id, (c) if more than
- * cap remain, the cap options at ranks floor(j*(n-1)/(cap-1)) of the order by (latency, id).
+ * cap remain, a grid over latency and accuracy: the n survivors, ordered by (latency, id),
+ * are cut into bands = floor(sqrt(cap)) runs (the one at rank r goes to band
+ * floor(r*bands/n)); a band of more than per = floor(cap/bands) options keeps those at ranks
+ * floor(j*(size-1)/(per-1)), j < per, of its order by (accuracy, id): always its least
+ * accurate option, which on a front of non-dominated options is a cheap one, and its most
+ * accurate one.
  */
 static int prune_options(const orc_model *m, uint32_t slo_latency_us, uint32_t cap, uint32_t t,
                          option_list *all, uint32_t *truncated)
@@ -750,20 +761,36 @@ static int prune_options(const orc_model *m, uint32_t slo_latency_us, uint32_t c
     free(keep);
     if (left > cap) {                                                   /* (c) */
         *truncated = 1;
-        lat_id *order = (lat_id *)malloc(left * sizeof *order);
-        option_t *kept = (option_t *)malloc(cap * sizeof *kept);
+        uint32_t bands = 1;
+        while ((uint64_t)(bands + 1) * (bands + 1) <= cap) bands++;
+        const uint32_t per = cap / bands;
+        opt_key *order = (opt_key *)malloc(left * sizeof *order);
+        option_t *kept = (option_t *)malloc((size_t)cap * sizeof *kept);
         if (!order || !kept) { free(order); free(kept); return ORC_E_MEM; }
-        for (size_t i = 0; i < left; i++) { order[i].lat = all->v[i].lat; order[i].id = all->v[i].id; order[i].at = i; }
+        for (size_t i = 0; i < left; i++) {
+            order[i].lat = all->v[i].lat; order[i].acc = all->v[i].acc; order[i].id = all->v[i].id; order[i].at = i;
+        }
         qsort(order, left, sizeof *order, cmp_lat_id);
-        for (uint32_t j = 0; j < cap; j++) kept[j] = all->v[order[((uint64_t)j * (left - 1)) / (cap - 1)].at];
+        size_t nk = 0, lo = 0;
+        for (uint32_t b = 0; b < bands; b++) {
+            size_t hi = lo;                                             /* ranks r with floor(r*bands/left) == b */
+            while (hi < left && (uint64_t)hi * bands / left == b) hi++;
+            const size_t size = hi - lo;
+            qsort(order + lo, size, sizeof *order, cmp_acc_id);
+            if (size <= per)
+                for (size_t r = 0; r < size; r++) kept[nk++] = all->v[order[lo + r].at];
+            else
+                for (uint32_t j = 0; j < per; j++) kept[nk++] = all->v[order[lo + ((uint64_t)j * (size - 1)) / (per - 1)].at];
+            lo = hi;
+        }
         /* back to ascending id (insertion sort, cap is small) */
-        for (uint32_t j = 1; j < cap; j++) {
-            option_t x = kept[j]; uint32_t k = j;
+        for (size_t j = 1; j < nk; j++) {
+            option_t x = kept[j]; size_t k = j;
             while (k > 0 && kept[k - 1].id > x.id) { kept[k] = kept[k - 1]; k--; }
             kept[k] = x;
         }
-        memcpy(all->v, kept, cap * sizeof *kept);
-        all->n = cap;
+        memcpy(all->v, kept, nk * sizeof *kept);
+        all->n = nk;
         free(order); free(kept);
     }
     return ORC_OK;

@@ -39,8 +39,8 @@ struct __attribute__((aligned(32))) Entry {
     uint32_t cost;    // replicas * partition units
     double   acc;     // accuracy of its variant
     uint64_t key;     // (cost << idx_bits) | digit * stride   (caller's index order)
-    uint32_t rep;     // replicas
-    uint32_t choice;  // original choice id
+    uint32_t rep;     // replicas; mixture mode: m1 | m2 << 16
+    uint32_t choice;  // original choice id; mixture mode: c1 | c2 << 16 (c2 = 0xFFFF: one tuple only)
 };
 static_assert(sizeof(Entry) == 32, "Entry must be 32 bytes");
 
@@ -144,6 +144,8 @@ struct ResultRec {
     uint16_t choice[MAXT];
     uint32_t replicas[MAXT];
     double   objective;
+    uint16_t choice2[MAXT];     // mixture mode: second tuple per task, 0xFFFF = none
+    uint32_t replicas2[MAXT];   // mixture mode: its replicas
 };
 
 struct SummaryRec {
@@ -174,7 +176,14 @@ struct Plan {
     uint32_t grid;            // blocks of the enumeration kernel
     uint32_t lanes_wanted;    // total lanes the planner tries to expose
     uint32_t objective;       // 0: cheapest feasible; 1: largest alpha*A_obj - beta*cost (Eq. 14)
-    uint32_t pad;
+    uint32_t mix;             // 1: a task may run two tuples side by side (Eq. 2, 6, 7, 9, 10)
+    // mixture mode: per (instance, task) a grid of cells (cost 0..S_avail) x (latency class),
+    // mix_cells entries each
+    uint64_t* cell_acc;       // best accuracy seen in the cell (bits of a positive double, 0 = empty)
+    uint64_t* cell_id;        // lowest option id among those with that accuracy
+    uint64_t* cell_pm;        // prefix maxima of cell_acc; later reused as a list of kept cells
+    uint32_t* cell_list;      // cells that survive the dominance test
+    uint64_t  mix_cells;
 };
 
 }  // namespace jsv

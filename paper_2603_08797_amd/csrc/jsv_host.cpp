@@ -55,6 +55,7 @@ struct Search {               // per-instance search parameters (batch mode keep
 
 struct Layout {               // offsets into the workspace
     size_t inst, entries, rep, cost, k32, quads, partial, partial_obj, results, summary, eval, total;
+    size_t cell_acc, cell_id, cell_pm, cell_list;     // mixture mode only
 };
 
 }  // namespace
@@ -75,6 +76,7 @@ struct jsv_ctx {
     bool batch_mode = false;
     bool dirty = true;                 // host problems changed since the last upload
     bool space_a = true, space_s = true, space_t = true;   // ablation switches
+    bool mix = false;                  // mixtures of two tuples per task
     int objective = 0;                 // Eq. 14 mode and weights
     double alpha = 1.0, beta = 0.035;
 
@@ -385,7 +387,7 @@ int upload_problems(jsv_ctx* ctx, HostProblem* hps, uint32_t n)
 }
 
 Layout make_layout(uint32_t n_inst, uint32_t t_max, uint32_t k_max, uint32_t c_max, uint32_t grid,
-                   uint32_t n_eval)
+                   uint32_t n_eval, uint64_t mix_cells = 0)
 {
     Layout L;
     size_t off = 0;
@@ -401,6 +403,11 @@ Layout make_layout(uint32_t n_inst, uint32_t t_max, uint32_t k_max, uint32_t c_m
     L.summary = off; off = align_up(off + sizeof(jsv::SummaryRec));
     L.eval = off;    // index u64, latency u32, replicas u32*T, cost i32, accuracy f64, mask u8, bad u32
     off = align_up(off + (size_t)n_eval * (8 + 4 + 4 * MAXT + 4 + 8 + 1) + 6 * ALIGN);
+    const size_t blocks = (size_t)n_inst * t_max;
+    L.cell_acc = off;  off = align_up(off + sizeof(uint64_t) * blocks * mix_cells);
+    L.cell_id = off;   off = align_up(off + sizeof(uint64_t) * blocks * mix_cells);
+    L.cell_pm = off;   off = align_up(off + sizeof(uint64_t) * blocks * mix_cells);
+    L.cell_list = off; off = align_up(off + sizeof(uint32_t) * blocks * mix_cells);
     L.total = off;
     return L;
 }
@@ -433,12 +440,13 @@ int check_search_args(const HostProblem& hp, uint32_t demand, double slo_a, uint
 
 // The whole device pass for n_inst instances whose parameters are in `inst` (host copies).
 int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32_t k_max, uint32_t c_max,
-               jsv_result* out, jsv_summary* summary)
+               jsv_result* out, jsv_summary* summary, uint64_t mix_cells = 0)
 {
     const uint32_t n = (uint32_t)inst.size();
     if (jsv::enumerate_lds_bytes(t_max, k_max) > 128 * 1024 || jsv::prune_lds_bytes(c_max) > 64 * 1024)
         return JSV_E_BADARG;
-    const Layout L = make_layout(n, t_max, k_max, c_max, ctx->grid, 0);
+    if (mix_cells != 0 && jsv::mix_lds_bytes(c_max) > 64 * 1024) return JSV_E_BADARG;
+    const Layout L = make_layout(n, t_max, k_max, c_max, ctx->grid, 0, mix_cells);
     unsigned char* ws = nullptr;
     int rc = get_workspace(ctx, L.total, &ws);
     if (rc) return rc;
@@ -461,7 +469,13 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     pl.quads = (jsv::Quad*)(ws + L.quads);
     pl.partial = (uint64_t*)(ws + L.partial);
     pl.partial_obj = (double*)(ws + L.partial_obj);
-    pl.objective = (uint32_t)ctx->objective; pl.pad = 0;
+    pl.objective = (uint32_t)ctx->objective;
+    pl.mix = mix_cells != 0 ? 1u : 0u;
+    pl.mix_cells = mix_cells;
+    pl.cell_acc = (uint64_t*)(ws + L.cell_acc);
+    pl.cell_id = (uint64_t*)(ws + L.cell_id);
+    pl.cell_pm = (uint64_t*)(ws + L.cell_pm);
+    pl.cell_list = (uint32_t*)(ws + L.cell_list);
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
     pl.n_inst = n; pl.t_max = t_max; pl.k_max = k_max; pl.c_max = c_max;
@@ -711,7 +725,13 @@ JSV_API size_t jsv_workspace_bytes(const jsv_ctx* ctx, uint32_t n_levels, uint32
         }
     }
     const uint32_t grid = ctx->grid ? ctx->grid : 256u * 8u;
-    return make_layout(n_levels, t_max, k_max, c_max, grid, 0).total;
+    uint64_t mix_cells = 0;
+    if (ctx->mix && !ctx->batch_mode) {
+        mix_cells = (uint64_t)(ctx->single.capacity + 1) * c_max;
+        k_max = prune_cap;
+        if (prune_cap < 2 || mix_cells * t_max * n_levels > ((uint64_t)1 << 32)) return 0;
+    }
+    return make_layout(n_levels, t_max, k_max, c_max, grid, 0, mix_cells).total;
 }
 
 JSV_API int jsv_set_workspace(jsv_ctx* ctx, void* device_ptr, size_t bytes)
@@ -766,12 +786,25 @@ JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_lev
     if (n_levels == 0) return JSV_E_BADARG;
     if (ctx->batch_mode || !ctx->single.have_profile || !ctx->single.have_dag) return JSV_E_STATE;
     for (uint32_t l = 0; l < n_levels; ++l) {
-        const int rc = check_search_args(ctx->single, demand_mrps[l], slo_accuracy, prune_cap);
+        // (mixture mode has its own bounds on prune_cap, below)
+        const int rc = check_search_args(ctx->single, demand_mrps[l], slo_accuracy, ctx->mix ? 0 : prune_cap);
         if (rc) return rc;
     }
     int rc = ready_single(ctx);
     if (rc) return rc;
     const HostProblem& hp = ctx->single;
+    if (ctx->mix) {
+        // Mixtures of two tuples: the options of a task live in a grid of (cost 0..S_avail) x
+        // (latency classes <= C) cells per (level, task)
+        if (!hp.fac.empty() || !ctx->space_t || ctx->objective != 0) return JSV_E_STATE;
+        if (prune_cap < 2 || prune_cap > JSV_MAX_CHOICES || hp.capacity == 0 || hp.capacity > 65535) return JSV_E_BADARG;
+        const uint64_t cells = (uint64_t)(hp.capacity + 1) * hp.C;
+        if (cells * hp.T * n_levels > ((uint64_t)1 << 32)) return JSV_E_WORKSPACE;      // 28 B per cell
+        std::vector<Instance> inst(n_levels);
+        for (uint32_t l = 0; l < n_levels; ++l)
+            inst[l] = make_instance(ctx, hp, 0, Search{demand_mrps[l], slo_latency_us, prune_cap, slo_accuracy});
+        return run_search(ctx, inst, hp.T, prune_cap, hp.C, out, summary, cells);
+    }
     if (!hp.fac.empty()) {
         // Per-variant factors: one instance per (level, combination of held variants), lowest
         // held task id = fastest digit; the level's result is the best over its combinations.
@@ -822,6 +855,13 @@ JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_lev
     return run_search(ctx, inst, hp.T, k_max_of(hp, prune_cap), hp.C, out, summary);
 }
 
+JSV_API int jsv_set_mixtures(jsv_ctx* ctx, int on)
+{
+    if (!ctx) return JSV_E_NULL;
+    ctx->mix = on != 0;
+    return JSV_OK;
+}
+
 JSV_API int jsv_set_factors(jsv_ctx* ctx, const uint32_t* factor_milli)
 {
     if (!ctx) return JSV_E_NULL;
@@ -851,7 +891,7 @@ JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo
 {
     if (!ctx || !index || !latency_us || !replicas || !cost || !accuracy || !mask) return JSV_E_NULL;
     if (ctx->batch_mode || !ctx->single.have_profile || !ctx->single.have_dag) return JSV_E_STATE;
-    if (!ctx->single.fac.empty()) return JSV_E_STATE;      // a level is a union of searches there
+    if (!ctx->single.fac.empty() || ctx->mix) return JSV_E_STATE;   // no single list of choice ids there
     int rc = check_search_args(ctx->single, demand_mrps, slo_accuracy, prune_cap);
     if (rc) return rc;
     if (n == 0) return JSV_OK;
@@ -867,6 +907,7 @@ JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo
     Instance in = make_instance(ctx, hp, 0, Search{demand_mrps, slo_latency_us, prune_cap, slo_accuracy});
 
     jsv::Plan pl;
+    std::memset(&pl, 0, sizeof pl);        // every mode switch off unless set below
     pl.graphs = (const Graph*)ctx->d_problems;
     pl.inst = (Instance*)(ws + L.inst);
     pl.entries = (jsv::Entry*)(ws + L.entries);
@@ -876,7 +917,7 @@ JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo
     pl.quads = (jsv::Quad*)(ws + L.quads);
     pl.partial = (uint64_t*)(ws + L.partial);
     pl.partial_obj = (double*)(ws + L.partial_obj);
-    pl.objective = (uint32_t)ctx->objective; pl.pad = 0;
+    pl.objective = (uint32_t)ctx->objective;
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
     pl.n_inst = 1; pl.t_max = T; pl.k_max = k_max; pl.c_max = hp.C;
@@ -919,7 +960,7 @@ JSV_API int jsv_get_pruned(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_late
 {
     if (!ctx || !choice_ids || !K || !truncated) return JSV_E_NULL;
     if (ctx->batch_mode || !ctx->single.have_profile || !ctx->single.have_dag) return JSV_E_STATE;
-    if (!ctx->single.fac.empty()) return JSV_E_STATE;      // lists depend on the held variants there
+    if (!ctx->single.fac.empty() || ctx->mix) return JSV_E_STATE;   // no single list of choice ids there
     if (task >= ctx->single.T) return JSV_E_BADARG;
     int rc = check_search_args(ctx->single, demand_mrps, 0.0, prune_cap);
     if (rc) return rc;
@@ -934,6 +975,7 @@ JSV_API int jsv_get_pruned(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_late
     if (rc) return rc;
     Instance in = make_instance(ctx, hp, 0, Search{demand_mrps, slo_latency_us, prune_cap, 0.0});
     jsv::Plan pl;
+    std::memset(&pl, 0, sizeof pl);        // every mode switch off unless set below
     pl.graphs = (const Graph*)ctx->d_problems;
     pl.inst = (Instance*)(ws + L.inst);
     pl.entries = (jsv::Entry*)(ws + L.entries);
@@ -943,7 +985,7 @@ JSV_API int jsv_get_pruned(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_late
     pl.quads = (jsv::Quad*)(ws + L.quads);
     pl.partial = (uint64_t*)(ws + L.partial);
     pl.partial_obj = (double*)(ws + L.partial_obj);
-    pl.objective = (uint32_t)ctx->objective; pl.pad = 0;
+    pl.objective = (uint32_t)ctx->objective;
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
     pl.n_inst = 1; pl.t_max = T; pl.k_max = k_max; pl.c_max = hp.C;
@@ -998,7 +1040,7 @@ JSV_API int jsv_load_batch(jsv_ctx* ctx, const jsv_problem* problems, uint32_t n
 JSV_API int jsv_search_loaded_batch(jsv_ctx* ctx, jsv_result* out, jsv_summary* summary)
 {
     if (!ctx || !out) return JSV_E_NULL;
-    if (!ctx->batch_mode || ctx->batch.empty()) return JSV_E_STATE;
+    if (!ctx->batch_mode || ctx->batch.empty() || ctx->mix) return JSV_E_STATE;
     int rc = ensure_device(ctx);
     if (rc) return rc;
     if (ctx->dirty) { rc = upload_problems(ctx, ctx->batch.data(), (uint32_t)ctx->batch.size()); if (rc) return rc; }

@@ -309,6 +309,278 @@ __global__ void __launch_bounds__(256) prune_kernel(Plan pl)
     }
 }
 
+// ---- options of mixture mode ------------------------------------------------------------
+// Eq. 9, 10 for two instance types: throughput-weighted mean of the two variants' accuracies.
+// Two products, one sum, one quotient, each rounded on its own (no contraction), so that the
+// dominance test below sees the same bits as any other plain fp64 evaluation of the formula.
+__device__ __forceinline__ double mix_accuracy(uint64_t w1i, double a1, uint64_t w2i, double a2)
+{
+#pragma clang fp contract(off)
+    const double w1 = (double)w1i, w2 = (double)w2i;
+    const double p1 = w1 * a1;
+    const double p2 = w2 * a2;
+    const double num = p1 + p2;
+    const double den = w1 + w2;
+    return num / den;
+}
+
+constexpr uint32_t MIX_MAX_REPLICAS = 65535u;
+
+// Per-tuple facts of one task, in LDS.
+struct MixTuples {
+    const double*   acc;     // accuracy of the tuple's variant
+    const uint64_t* h;       // throughput of one replica, micro-requests/s
+    const uint32_t* lat;
+    const uint32_t* units;
+    const uint32_t* cls;     // latency class: number of distinct smaller latencies of the task
+    const uint32_t* alone;   // replicas the tuple needs on its own (clamped to 65536)
+    const uint8_t*  ok;      // bit0: allowed by the search space and the latency filter
+};
+
+// Calls f(cost, latency class, accuracy, id) for every option of the task this thread is
+// responsible for: single tuples (id = c) and minimal mixtures of c1 < c2
+// (id = C + (c1*C + c2)*65536 + m1).  Options that alone exceed S_avail are skipped.
+template <typename F>
+__device__ __forceinline__ void mix_visit(const MixTuples& m, uint32_t C, uint64_t need, uint32_t S,
+                                          uint32_t tid, uint32_t nthreads, uint32_t& flags, F&& f)
+{
+    for (uint32_t c = tid; c < C; c += nthreads) {
+        if (!(m.ok[c] & 1)) continue;
+        const uint64_t rep = need / m.h[c] + (need % m.h[c] != 0);
+        const uint64_t r1 = rep < 1 ? 1 : rep;
+        if (r1 > S) continue;                               // units >= 1: cost > S_avail
+        const uint64_t cost = r1 * m.units[c];
+        if (cost > S) continue;
+        f((uint32_t)cost, m.cls[c], m.acc[c], (uint64_t)c);
+    }
+    for (uint32_t k = tid; k < C * C; k += nthreads) {
+        const uint32_t c1 = k / C, c2 = k % C;
+        if (c2 <= c1 || !(m.ok[c1] & m.ok[c2] & 1)) continue;
+        const uint32_t u1 = m.units[c1], u2 = m.units[c2];
+        if ((uint64_t)u1 + u2 > S || m.alone[c1] < 2) continue;
+        uint32_t m1max = (S - u2) / u1;
+        if (m1max > m.alone[c1] - 1) m1max = m.alone[c1] - 1;
+        const uint64_t h1 = m.h[c1], h2 = m.h[c2];
+        const uint32_t cls = umax(m.cls[c1], m.cls[c2]);
+        const double a1 = m.acc[c1], a2 = m.acc[c2];
+        for (uint32_t m1 = 1; m1 <= m1max; ++m1) {
+            const uint64_t rest = need - (uint64_t)m1 * h1;            // > 0: m1 < alone
+            const uint64_t m2max = (S - m1 * u1) / u2;                 // >= 1
+            if (__umul64hi(m2max, h2) == 0 && m2max * h2 < rest) continue;   // cannot fit S_avail
+            const uint64_t m2 = rest / h2 + (rest % h2 != 0);
+            if (m2 > m2max) continue;
+            if ((uint64_t)(m1 - 1) * h1 + m2 * h2 >= need) continue;   // one replica of c1 too many
+            if (m2 > MIX_MAX_REPLICAS) { flags |= F_OVERFLOW; continue; }
+            const uint32_t cost = m1 * u1 + (uint32_t)m2 * u2;
+            f(cost, cls, mix_accuracy((uint64_t)m1 * h1, a1, m2 * h2, a2),
+              (uint64_t)C + ((uint64_t)c1 * C + c2) * 65536u + m1);
+        }
+    }
+}
+
+// One block per (instance, task): the task's surviving options as Entry records.
+// Every option lands in the cell (cost, latency class); a cell keeps its most accurate
+// option (lowest id among equals), which dominates the rest of the cell.  A cell survives
+// the exact dominance test iff no other non-empty cell with cost <= and class <= has an
+// accuracy >=, read off a two-dimensional prefix maximum.  More than cap survivors are
+// thinned over a grid of latency bands and accuracy ranks (step (c) below).
+__global__ void __launch_bounds__(256) mix_kernel(Plan pl)
+{
+    const uint32_t i = blockIdx.x / pl.t_max;
+    const uint32_t t = blockIdx.x % pl.t_max;
+    const uint32_t tid = threadIdx.x;
+    Instance* in = pl.inst + i;
+    const Graph* g = pl.graphs + in->problem;
+    if (blockIdx.x == 0 && tid == 0) pl.summary->plan_done = 0;     // counted up by the plan kernel
+    if (t >= g->T) return;
+    const uint32_t C = g->C, V = g->V, PB = g->P * g->B, Bn = g->B, Pn = g->P;
+    const uint32_t cap = in->cap, S = g->capacity;
+
+    extern __shared__ unsigned char smem[];
+    double*   s_acc   = (double*)smem;
+    uint64_t* s_h     = (uint64_t*)(s_acc + C);
+    uint32_t* s_lat   = (uint32_t*)(s_h + C);
+    uint32_t* s_units = s_lat + C;
+    uint32_t* s_cls   = s_units + C;
+    uint32_t* s_alone = s_cls + C;
+    uint8_t*  s_ok    = (uint8_t*)(s_alone + C);
+    __shared__ uint32_t s_flags, s_ncls, s_n, s_kept;
+    if (tid == 0) { s_flags = 0; s_ncls = 0; s_n = 0; s_kept = 0; }
+
+    const uint64_t need = (uint64_t)in->demand * g->mult[t];            // micro-requests / s (Eq. 5)
+    const uint64_t budget = (uint64_t)in->slo_l, through = g->through[t];
+    uint32_t* g_rep  = pl.rep  + ((size_t)i * pl.t_max + t) * pl.c_max;
+    uint32_t* g_cost = pl.cost + ((size_t)i * pl.t_max + t) * pl.c_max;
+    uint32_t my_flags = 0;
+    for (uint32_t c = tid; c < C; c += blockDim.x) {
+        const uint32_t lat = g->lat[(size_t)t * C + c];
+        const uint64_t per = 1000ull * g->thr[(size_t)t * C + c];
+        uint64_t rep = need / per + (need % per != 0);
+        if (rep < 1) rep = 1;
+        const uint32_t units = g->units[(c / Bn) % Pn];
+        uint64_t cost = rep * units;
+        if (rep > 0xFFFFFFFFull || cost > 0x7FFFFFFFull) { my_flags |= F_OVERFLOW; rep = 1; cost = 1; }
+        g_rep[c] = (uint32_t)rep; g_cost[c] = (uint32_t)cost;
+        s_acc[c] = g->acc[(size_t)t * V + c / PB];
+        s_h[c] = per; s_lat[c] = lat; s_units[c] = units;
+        const bool allowed = (g->only_variant[t] == 0xFFFFFFFFu || c / PB == g->only_variant[t]) &&
+                             (g->only_part == 0xFFFFFFFFu || (c / Bn) % Pn == g->only_part);
+        // (a) can this tuple meet the latency SLO with every other task at its fastest?  A
+        // mixture is as slow as its slower tuple, so it passes iff both tuples do.
+        const bool fast = (uint64_t)g->q * ((uint64_t)lat + through) <= budget;
+        s_ok[c] = (allowed && fast) ? 1 : 0;
+        if (allowed && rep >= 2 && rep - 1 > MIX_MAX_REPLICAS) my_flags |= F_OVERFLOW;
+        s_alone[c] = rep > 65536 ? 65536u : (uint32_t)rep;
+    }
+    __syncthreads();
+    // latency classes over all tuples of the task
+    for (uint32_t c = tid; c < C; c += blockDim.x) {
+        bool first = true;
+        for (uint32_t o = 0; o < c; ++o) if (s_lat[o] == s_lat[c]) { first = false; break; }
+        if (first) { s_ok[c] |= 2; atomicAdd(&s_ncls, 1u); }
+    }
+    __syncthreads();
+    for (uint32_t c = tid; c < C; c += blockDim.x) {
+        uint32_t n = 0;
+        for (uint32_t o = 0; o < C; ++o) n += ((s_ok[o] & 2) && s_lat[o] < s_lat[c]) ? 1u : 0u;
+        s_cls[c] = n;
+    }
+    const uint32_t ncls = s_ncls;
+    const uint64_t ncell = (uint64_t)(S + 1) * ncls;        // <= pl.mix_cells (host)
+    const size_t base = ((size_t)i * pl.t_max + t) * pl.mix_cells;
+    uint64_t* c_acc = pl.cell_acc + base;
+    uint64_t* c_id  = pl.cell_id + base;
+    uint64_t* c_pm  = pl.cell_pm + base;
+    uint32_t* c_list = pl.cell_list + base;
+    for (uint64_t x = tid; x < ncell; x += blockDim.x) { c_acc[x] = 0; c_id[x] = NO_KEY; }
+    __syncthreads();
+
+    MixTuples mt{s_acc, s_h, s_lat, s_units, s_cls, s_alone, s_ok};
+    mix_visit(mt, C, need, S, tid, blockDim.x, my_flags,
+              [&](uint32_t cost, uint32_t cls, double acc, uint64_t) {
+                  atomicMax((unsigned long long*)&c_acc[(uint64_t)cost * ncls + cls],
+                            (unsigned long long)__double_as_longlong(acc));
+              });
+    __syncthreads();
+    mix_visit(mt, C, need, S, tid, blockDim.x, my_flags,
+              [&](uint32_t cost, uint32_t cls, double acc, uint64_t id) {
+                  const uint64_t x = (uint64_t)cost * ncls + cls;
+                  if ((uint64_t)__double_as_longlong(acc) == c_acc[x])
+                      atomicMin((unsigned long long*)&c_id[x], (unsigned long long)id);
+              });
+    __syncthreads();
+
+    // (b) exact dominance between cells: inclusive prefix maximum over (cost', class') <= (cost, class)
+    for (uint32_t k = tid; k <= S; k += blockDim.x) {
+        uint64_t run = 0;
+        for (uint32_t l = 0; l < ncls; ++l) { const uint64_t a = c_acc[(uint64_t)k * ncls + l]; run = a > run ? a : run; c_pm[(uint64_t)k * ncls + l] = run; }
+    }
+    __syncthreads();
+    for (uint32_t l = tid; l < ncls; l += blockDim.x) {
+        uint64_t run = 0;
+        for (uint32_t k = 0; k <= S; ++k) { const uint64_t a = c_pm[(uint64_t)k * ncls + l]; run = a > run ? a : run; c_pm[(uint64_t)k * ncls + l] = run; }
+    }
+    __syncthreads();
+    for (uint64_t x = tid; x < ncell; x += blockDim.x) {
+        const uint64_t a = c_acc[x];
+        if (a == 0) continue;
+        const uint32_t k = (uint32_t)(x / ncls), l = (uint32_t)(x % ncls);
+        const uint64_t up = k > 0 ? c_pm[x - ncls] : 0, left = l > 0 ? c_pm[x - 1] : 0;
+        if ((up > left ? up : left) >= a) continue;         // something cheaper-or-equal and faster-or-equal is as accurate
+        c_list[atomicAdd(&s_n, 1u)] = (uint32_t)x;
+    }
+    __syncthreads();
+    const uint32_t n = s_n;
+
+    // latency of the option kept in cell x, from its id
+    auto lat_of = [&](uint64_t id) -> uint32_t {
+        if (id < C) return s_lat[id];
+        const uint64_t pair = (id - C) >> 16;
+        return umax(s_lat[pair / C], s_lat[pair % C]);
+    };
+    // (c) thinning over a grid of latency and accuracy.  The survivors in the order
+    // (latency, id) are cut into `bands` runs; a band of more than `per` options keeps those
+    // at evenly spaced ranks of its order by (accuracy, id).  c_pm is free now: its first
+    // half lists the kept cells, its second half holds the band of every survivor.
+    uint32_t* kept = (uint32_t*)c_pm;
+    uint32_t* band = kept + ncell;
+    uint32_t bands = 1;
+    while ((uint64_t)(bands + 1) * (bands + 1) <= cap) ++bands;
+    const uint32_t per = cap / bands;                       // >= 2
+    if (n > cap) {
+        my_flags |= F_TRUNCATED;
+        for (uint32_t j = tid; j < n; j += blockDim.x) {
+            const uint64_t id = c_id[c_list[j]];
+            const uint32_t l = lat_of(id);
+            uint32_t rank = 0;
+            for (uint32_t o = 0; o < n; ++o) {
+                const uint64_t id2 = c_id[c_list[o]];
+                const uint32_t l2 = lat_of(id2);
+                rank += (l2 < l || (l2 == l && id2 < id)) ? 1u : 0u;
+            }
+            band[j] = (uint32_t)((uint64_t)rank * bands / n);
+        }
+        __syncthreads();
+    }
+    for (uint32_t j = tid; j < n; j += blockDim.x) {
+        const uint32_t x = c_list[j];
+        bool keep = true;
+        if (n > cap) {
+            const uint64_t a = c_acc[x], id = c_id[x];
+            const uint32_t b = band[j];
+            uint32_t rank = 0, size = 0;
+            for (uint32_t o = 0; o < n; ++o) {
+                if (band[o] != b) continue;
+                ++size;
+                const uint32_t y = c_list[o];
+                const uint64_t a2 = c_acc[y];
+                rank += (a2 < a || (a2 == a && c_id[y] < id)) ? 1u : 0u;
+            }
+            if (size > per) {
+                // is rank == floor(j*(size-1)/(per-1)) for some j < per ?
+                const uint64_t jj = ((uint64_t)rank * (per - 1) + (size - 2)) / (size - 1);
+                keep = (jj < per) && ((jj * (size - 1)) / (per - 1) == rank);
+            }
+        }
+        if (keep) kept[atomicAdd(&s_kept, 1u)] = x;
+    }
+    __syncthreads();
+    // (d) ascending id; the entry carries both tuples and both replica counts
+    const uint32_t K = s_kept;
+    Entry* out = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
+    for (uint32_t j = tid; j < K; j += blockDim.x) {
+        const uint32_t x = kept[j];
+        const uint64_t id = c_id[x];
+        uint32_t pos = 0;
+        for (uint32_t o = 0; o < K; ++o) pos += c_id[kept[o]] < id ? 1u : 0u;
+        Entry e;
+        e.cost = (uint32_t)(x / ncls);
+        e.acc = __longlong_as_double((long long)c_acc[x]);
+        e.key = 0;
+        if (id < C) {
+            e.lat = s_lat[id];
+            e.choice = (uint32_t)id | (0xFFFFu << 16);
+            e.rep = e.cost / s_units[id];
+        } else {
+            const uint64_t pair = (id - C) >> 16;
+            const uint32_t c1 = (uint32_t)(pair / C), c2 = (uint32_t)(pair % C), m1 = (uint32_t)((id - C) & 0xFFFFu);
+            const uint32_t m2 = (e.cost - m1 * s_units[c1]) / s_units[c2];
+            e.lat = umax(s_lat[c1], s_lat[c2]);
+            e.choice = c1 | (c2 << 16);
+            e.rep = m1 | (m2 << 16);
+        }
+        out[pos] = e;
+    }
+    if (my_flags) atomicOr(&s_flags, my_flags);
+    __syncthreads();
+    if (tid == 0) {
+        in->K[t] = K;
+        const uint32_t f = s_flags | (K == 0 ? F_EMPTY : 0);
+        if (f) atomicOr(&in->flags, f);
+        if (f & F_TRUNCATED) atomicOr(&in->trunc_mask, 1u << t);
+    }
+}
+
 // Tiles per ticket of the enumeration kernel's work counter: about 128 tickets per block,
 // so that the counter is touched less often and the tail stays below one percent.
 __device__ __forceinline__ uint32_t tiles_per_ticket(uint64_t total_tiles, uint32_t grid)
@@ -430,7 +702,8 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             while (lb < 32 && (ranks - 1) >> lb) ++lb;
             uint32_t cb = 0;
             while (cb < 32 && cost_in >> cb) ++cb;
-            use32 = (ranks <= 0x7FFFFFFFull && lb + cb <= 31) ? 1u : 0u;
+            // (mixture mode: accuracies differ entry by entry, the per-variant stream does not apply)
+            use32 = (!pl.mix && ranks <= 0x7FFFFFFFull && lb + cb <= 31) ? 1u : 0u;
         }
         if (use32) {
             // quads of position 0's stream: every variant's entries rounded up to whole quads
@@ -1060,7 +1333,7 @@ __global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
     r->index = NO_KEY; r->full_index = NO_KEY; r->evaluated = in->space;
     r->accuracy = 0.0; r->latency_us = 0; r->cost_units = 0x7FFFFFFF; r->feasible = 0; r->objective = 0.0;
     r->flags = in->flags;
-    for (int t = 0; t < MAXT; ++t) { r->choice[t] = 0; r->replicas[t] = 0; }
+    for (int t = 0; t < MAXT; ++t) { r->choice[t] = 0; r->replicas[t] = 0; r->choice2[t] = 0; r->replicas2[t] = 0; }
     if (m != NO_KEY && !(in->flags & (F_OVERFLOW | F_EMPTY))) {
         const uint64_t idx = in->idx_bits ? (m & ((1ull << in->idx_bits) - 1)) : 0;
         uint32_t dig[MAXT];
@@ -1077,8 +1350,14 @@ __global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
                 const Entry* e = ent + (size_t)t * pl.k_max + dig[t];
                 r->choice[t] = (uint16_t)e->choice;
                 r->replicas[t] = e->rep;
+                r->choice2[t] = 0xFFFF;
+                if (pl.mix) {
+                    r->choice2[t] = (uint16_t)(e->choice >> 16);
+                    r->replicas[t] = e->rep & 0xFFFFu; r->replicas2[t] = e->rep >> 16;
+                    over = true;                     // no fixed-size full space in mixture mode
+                }
                 if (__umul64hi(full, g->C) != 0) over = true;
-                const uint64_t f2 = full * g->C + e->choice;
+                const uint64_t f2 = full * g->C + (e->choice & 0xFFFFu);
                 if (f2 < full * g->C) over = true;
                 full = f2;
                 if (full == NO_KEY) over = true;
@@ -1141,11 +1420,15 @@ __global__ void __launch_bounds__(256) eval_kernel(Plan pl, const uint64_t* inde
 
 // ---- launch wrappers (called from the host planner) -------------------------------------------
 size_t prune_lds_bytes(uint32_t c_max) { return (size_t)c_max * (8 + 4 + 4 + 4 + 1 + 1) + 16; }
+size_t mix_lds_bytes(uint32_t c_max) { return (size_t)c_max * (8 + 8 + 4 + 4 + 4 + 4 + 1) + 16; }
 size_t enumerate_lds_bytes(uint32_t t_max, uint32_t k_max) { return (size_t)t_max * k_max * sizeof(Entry); }
 
 hipError_t launch_prune_plan_scan(const Plan& pl, hipStream_t stream)
 {
-    hipLaunchKernelGGL(prune_kernel, dim3(pl.n_inst * pl.t_max), dim3(256), prune_lds_bytes(pl.c_max), stream, pl);
+    if (pl.mix)
+        hipLaunchKernelGGL(mix_kernel, dim3(pl.n_inst * pl.t_max), dim3(256), mix_lds_bytes(pl.c_max), stream, pl);
+    else
+        hipLaunchKernelGGL(prune_kernel, dim3(pl.n_inst * pl.t_max), dim3(256), prune_lds_bytes(pl.c_max), stream, pl);
     hipLaunchKernelGGL(plan_kernel, dim3(pl.n_inst), dim3(256), 0, stream, pl);
     return hipGetLastError();
 }

@@ -9,9 +9,11 @@
 namespace jsv {
 
 size_t prune_lds_bytes(uint32_t c_max);
+size_t mix_lds_bytes(uint32_t c_max);
 size_t enumerate_lds_bytes(uint32_t t_max, uint32_t k_max);
 
-// cost table + prune, then plan (with the tile scan): two launches on `stream`
+// cost table + prune (mixture mode: options + prune), then plan (with the tile scan): two
+// launches on `stream`
 hipError_t launch_prune_plan_scan(const Plan& pl, hipStream_t stream);
 hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, bool objective, int* blocks);
 // pl.grid blocks; pl.grid must not exceed what enumerate_blocks_per_cu allows to be resident

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libjsv.so")
 MAX_TASKS = 16
 OK, E_NULL, E_BADARG, E_CYCLE, E_OVERFLOW, E_STATE, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6, -7
 
-EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space", "jsv_set_factors", "jsv_set_graph_mode",
+EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space", "jsv_set_factors", "jsv_set_mixtures", "jsv_set_graph_mode",
            "jsv_workspace_bytes", "jsv_set_workspace", "jsv_load_profile", "jsv_set_dag",
            "jsv_search", "jsv_eval_candidates", "jsv_get_pruned", "jsv_load_batch",
            "jsv_search_loaded_batch", "jsv_search_batch"]
@@ -31,7 +31,8 @@ class JsvResult(C.Structure):
                 ("accuracy", C.c_double), ("latency_us", C.c_uint32), ("cost_units", C.c_int32),
                 ("feasible", C.c_uint32), ("flags", C.c_uint32),
                 ("choice", C.c_uint16 * MAX_TASKS), ("replicas", C.c_uint32 * MAX_TASKS),
-                ("objective", C.c_double)]
+                ("objective", C.c_double),
+                ("choice2", C.c_uint16 * MAX_TASKS), ("replicas2", C.c_uint32 * MAX_TASKS)]
 
 
 class JsvSummary(C.Structure):
@@ -75,6 +76,8 @@ def load_library():
     lib.jsv_set_objective.argtypes = [vp, C.c_int, f64, f64]
     lib.jsv_set_search_space.restype = C.c_int
     lib.jsv_set_search_space.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+    lib.jsv_set_mixtures.restype = C.c_int
+    lib.jsv_set_mixtures.argtypes = [vp, C.c_int]
     lib.jsv_set_factors.restype = C.c_int
     lib.jsv_set_factors.argtypes = [vp, vp]
     lib.jsv_set_graph_mode.restype = C.c_int
@@ -124,6 +127,8 @@ class Result:
     choice: List[int]
     replicas: List[int]
     objective: float = 0.0
+    choice2: List[int] = None       # mixture mode: second tuple per task (0xFFFF = none)
+    replicas2: List[int] = None
 
 
 @dataclass
@@ -146,7 +151,8 @@ def _result(r: JsvResult, T: int) -> Result:
     return Result(int(r.index), int(r.full_index), int(r.evaluated), float(r.accuracy),
                   int(r.latency_us), int(r.cost_units), bool(r.feasible), int(r.flags),
                   [int(r.choice[t]) for t in range(T)], [int(r.replicas[t]) for t in range(T)],
-                  float(r.objective))
+                  float(r.objective), [int(r.choice2[t]) for t in range(T)],
+                  [int(r.replicas2[t]) for t in range(T)])
 
 
 class Jsv:
@@ -217,6 +223,10 @@ class Jsv:
         if f.shape != (getattr(self, "E", -1), getattr(self, "V", -1)):
             raise ValueError("factor_milli must have shape [E][V] of the loaded graph and profile")
         self._check(self._lib.jsv_set_factors(self._h, f.ctypes.data_as(C.c_void_p)), "jsv_set_factors")
+
+    def set_mixtures(self, on: bool = True):
+        """Let a task run two tuples side by side (Eq. 2, 6, 7, 9, 10)."""
+        self._check(self._lib.jsv_set_mixtures(self._h, int(on)), "jsv_set_mixtures")
 
     def set_graph_mode(self, on: bool = True):
         """Record the launch sequence of a search into a HIP graph and replay it."""

@@ -323,9 +323,23 @@ class PyRef:
                         front.append(o)
                 if len(front) > cap:
                     truncated = True
-                    front.sort(key=lambda o: (o["lat"], o["id"]))
+                    # grid over latency and accuracy: isqrt(cap) latency bands of near-equal
+                    # size, each thinned to cap // bands options evenly spaced by accuracy rank
+                    import math
+                    bands = math.isqrt(cap)
+                    per = cap // bands
                     n = len(front)
-                    front = [front[(j * (n - 1)) // (cap - 1)] for j in range(cap)]
+                    front.sort(key=lambda o: (o["lat"], o["id"]))
+                    groups = [[] for _ in range(bands)]
+                    for r, o in enumerate(front):
+                        groups[r * bands // n].append(o)
+                    front = []
+                    for grp in groups:
+                        grp.sort(key=lambda o: (o["acc"], o["id"]))
+                        if len(grp) <= per:
+                            front += grp
+                        else:
+                            front += [grp[(j * (len(grp) - 1)) // (per - 1)] for j in range(per)]
                 opts = sorted(front, key=lambda o: o["id"])
             lists.append(opts)
         return lists, truncated

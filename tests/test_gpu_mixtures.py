@@ -1,0 +1,129 @@
+"""GPU parity of the two-tuple mixtures (Eq. 2, 6, 7, 9, 10) against the oracle."""
+import dataclasses
+import json
+import os
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2603_08797_amd import jsv, workloads
+from test_gpu_parity import same
+
+pytestmark = pytest.mark.gpu
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    j = jsv.Jsv(device=0)
+    j.set_mixtures(True)
+    yield j
+    j.close()
+
+
+def check(ctx, pb, se, cap, levels=None, threads=16, margin=True):
+    D = se.demand_mrps if levels is None else se.demand_mrps[:levels]
+    o = oracle.Oracle.from_problem(pb)
+    o.set_mixtures(True)
+    ctx.load(pb)
+    want, wbl, wmd = o.search(D, se.slo_latency_us, se.slo_accuracy, cap, threads=threads)
+    got, summ = ctx.search(D, se.slo_latency_us, se.slo_accuracy, cap)
+    skipped = 0
+    for l, (w, g) in enumerate(zip(want, got)):
+        if margin and o.mixture_margin(int(D[l]), se.slo_latency_us, se.slo_accuracy, cap) < 1e-9:
+            skipped += 1
+            continue
+        same(g, w, f"level {l}")
+        assert (g.choice2, g.replicas2) == (w.choice2, w.replicas2), f"level {l}"
+        assert g.full_index == 2 ** 64 - 1
+    if not skipped:
+        assert (summ.best_level, summ.max_demand_mrps) == (wbl, wmd)
+    return want
+
+
+def test_hand_worked_chain(ctx):
+    with open(os.path.join(HERE, "golden", "p1_two_task_chain.json")) as f:
+        g = json.load(f)
+    lat = np.array(g["latency_us"], dtype=np.uint32).reshape(g["T"], g["V"], g["P"], g["B"])
+    acc = np.array(g["accuracy"], dtype=np.float64)
+    s = g["mixtures_eq9_10"]["search"]
+    D = g["mixtures_eq9_10"]["demand_mrps"]
+    ctx.load_profile(g["T"], g["V"], g["P"], g["B"], g["units"], g["batch"], lat, None, acc)
+    ctx.set_dag(g["T"], [0], [1], g["mult_milli"], 12, g["queue_factor"])
+    r = ctx.search([D], s["slo_latency_us"], s["slo_accuracy"], 64)[0][0]
+    assert r.feasible and r.cost == s["cost"] and not (r.flags & 1)
+    o = oracle.Oracle(g["T"], g["V"], g["P"], g["B"], g["units"], g["batch"], lat, None, acc, [0], [1],
+                      g["mult_milli"], 12, g["queue_factor"])
+    o.set_mixtures(True)
+    w = o.search([D], s["slo_latency_us"], s["slo_accuracy"], 64)[0][0]
+    same(r, w)
+    assert (r.choice2, r.replicas2) == (w.choice2, w.replicas2)
+
+
+@pytest.mark.parametrize("seed", range(80))
+def test_tiny_mixture(ctx, seed):
+    pb, se = workloads.tiny_mixture(3000 + seed)
+    if pb.capacity_units == 0:
+        pb = dataclasses.replace(pb, capacity_units=30)
+    cap = [2, 4, 7, 12, 40, 400][seed % 6]
+    check(ctx, pb, se, cap)
+
+
+def first(name, seed=0):
+    w = workloads.BENCH_WORKLOADS[name](seed=seed)
+    return w.problems[0], w.searches[0]
+
+
+@pytest.mark.parametrize("cap", [12, 16])
+def test_chain3_sized(ctx, cap):
+    """48 tuples per task: up to 5600 options per task, thinned to cap; mixtures win."""
+    pb, se = first("chain3")
+    se = dataclasses.replace(se, demand_mrps=np.array([100_000, 200_000, 300_000], dtype=np.uint32), slo_accuracy=0.9)
+    want = check(ctx, pb, se, cap)
+    assert any(r.feasible for r in want) and any(r.flags & 1 for r in want)
+    assert any(c != 0xFFFF for r in want if r.feasible for c in r.choice2)
+
+
+def test_diamond5_sized(ctx):
+    """140 tuples per task, 5 tasks, 56 units."""
+    pb, se = first("diamond5")
+    se = dataclasses.replace(se, demand_mrps=se.demand_mrps[[12, 20, 24]], slo_accuracy=0.9)
+    t0 = time.time()
+    want = check(ctx, pb, se, 16)
+    print(f"diamond5 mixtures: {time.time() - t0:.1f} s", flush=True)
+    assert any(r.feasible for r in want)
+
+
+def test_argument_and_state_errors(ctx):
+    pb, se = workloads.tiny_mixture(3000)
+    pb = dataclasses.replace(pb, capacity_units=30)
+    ctx.load(pb)
+    D = se.demand_mrps
+    for cap in (0, 1, 4096):
+        with pytest.raises(jsv.JsvError):
+            ctx.search(D, se.slo_latency_us, se.slo_accuracy, cap)
+    ctx.set_objective(1, 1.0, 0.035)
+    try:
+        with pytest.raises(jsv.JsvError):
+            ctx.search(D, se.slo_latency_us, se.slo_accuracy, 8)
+    finally:
+        ctx.set_objective(0, 1.0, 0.035)
+    with pytest.raises(jsv.JsvError):
+        ctx.get_pruned(int(D[0]), se.slo_latency_us, 8, 0)
+    ctx.load(dataclasses.replace(pb, capacity_units=0))
+    with pytest.raises(jsv.JsvError):
+        ctx.search(D, se.slo_latency_us, se.slo_accuracy, 8)
+    # switching the mode off gives the single-tuple search again
+    ctx.load(pb)
+    ctx.set_mixtures(False)
+    try:
+        o = oracle.Oracle.from_problem(pb)
+        want = o.search(D, se.slo_latency_us, se.slo_accuracy, 0)[0]
+        got = ctx.search(D, se.slo_latency_us, se.slo_accuracy, 0)[0]
+        for w_, g_ in zip(want, got):
+            same(g_, w_)
+            assert g_.choice2 == [0xFFFF] * pb.T and g_.replicas2 == [0] * pb.T
+    finally:
+        ctx.set_mixtures(True)
