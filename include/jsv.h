@@ -187,6 +187,19 @@ JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial
  * and so does jsv_search with graph_informed = 0.
  */
 /*
+ * Bounds in the enumeration (on by default).  A group of candidates that share all digits but
+ * those of the innermost tasks is excluded as a whole when the digits it shares already break
+ * the latency SLO (Eq. 3), when its remaining latency budget is below the fastest choice of
+ * the innermost task, or, with S_avail set, when its shared cost plus the cheapest choices of
+ * the innermost tasks exceeds S_avail (Eq. 8); the kernel skips the tests of such candidates
+ * where a whole 64-lane wave of groups is excluded.  The result is the same with bounds on
+ * or off (every excluded candidate fails a constraint); off makes the kernel issue the tests
+ * of every candidate, which is what throughput measurements of the plain enumeration use.
+ * jsv_summary.candidates_visited tells how many candidates had their tests issued.
+ */
+JSV_API int jsv_set_bounds(jsv_ctx* ctx, int on);
+
+/*
  * Mixtures of two tuples per task (Section 3.2: Eq. 2, 6, 7 with two active instance types and
  * the throughput-weighted task accuracy of Eq. 9, 10).  on != 0: besides replicating one tuple
  * a task may run m1 >= 1 replicas of tuple c1 and m2 >= 1 of tuple c2 (c1 < c2), where
@@ -240,6 +253,10 @@ typedef struct {
     uint32_t max_demand_mrps;  /* its demand: the maximum serviceable demand; 0 if none */
     double   seconds_device;   /* device time of the whole search, HIP events */
     double   seconds_enumerate;/* of which the enumeration kernel */
+    uint64_t candidates_visited;   /* candidates whose tests the enumeration kernel issued, counted
+                                      in whole 64-lane waves; the others were excluded in bulk: by
+                                      a lane's latency or capacity bound holding for a whole wave.
+                                      At most the sum of `evaluated`, rounded up to whole waves */
 } jsv_summary;
 
 /*

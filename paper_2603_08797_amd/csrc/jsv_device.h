@@ -59,6 +59,13 @@ struct __attribute__((aligned(64))) Quad {
 };
 static_assert(sizeof(Quad) == 64, "Quad must be 64 bytes");
 
+// Mixture mode: every entry of the innermost position has its own accuracy, so a quad
+// holds four (latency, local key, accuracy) triples; the whole stream is in ascending
+// latency (ties: ascending digit) and padded with entries that can never win.
+struct XEntM { uint32_t lat; uint32_t k32; double acc; };
+struct __attribute__((aligned(64))) QuadM { XEntM e[4]; };
+static_assert(sizeof(QuadM) == 64, "QuadM must be 64 bytes");
+
 // Task graph of one problem, by position.
 struct Graph {
     uint32_t T, V, P, B, C;
@@ -124,7 +131,9 @@ struct Instance {
     uint32_t lb;              // bits of the rank
     uint32_t nq;              // quads in the innermost position's stream
     uint32_t ord[3];          // in-lane positions, least significant caller digit first
-    uint32_t pad[2];
+    // bounds that let whole lanes and waves sit out (written by the plan kernel)
+    uint32_t min_in_cost;     // sum over the in-lane positions of their cheapest entry
+    uint32_t min_x_lat;       // lowest latency among the innermost position's entries
     // objective of Eq. 14 (inputs, host): maximise alpha * A_obj - beta * cost
     double   alpha, beta;
     double   alpha_n;         // alpha / A_max: factor on A_raw
@@ -157,6 +166,7 @@ struct SummaryRec {
     unsigned long long next_tile;   // work counter of the enumeration kernel
     uint32_t plan_done;       // plan blocks finished
     uint32_t pad;
+    unsigned long long visited;     // entries of the innermost position that waves went through
 };
 
 // Everything the kernels need to find their data; passed by value.
@@ -177,6 +187,8 @@ struct Plan {
     uint32_t lanes_wanted;    // total lanes the planner tries to expose
     uint32_t objective;       // 0: cheapest feasible; 1: largest alpha*A_obj - beta*cost (Eq. 14)
     uint32_t mix;             // 1: a task may run two tuples side by side (Eq. 2, 6, 7, 9, 10)
+    uint32_t bounds;          // 1: skip what latency and capacity bounds exclude; 0: issue every candidate's tests
+    uint32_t pad2;
     // mixture mode: per (instance, task) a grid of cells (cost 0..S_avail) x (latency class),
     // mix_cells entries each
     uint64_t* cell_acc;       // best accuracy seen in the cell (bits of a positive double, 0 = empty)

@@ -68,7 +68,7 @@ struct jsv_ctx {
     uint32_t grid = 0;                 // upper bound on enumeration blocks (sizes the workspace)
     uint32_t cus = 0;
     // occupancy of the enumeration kernel, remembered for the last table shape
-    uint32_t occ_t = 0, occ_k = 0; int occ_obj = -1, occ_blocks = 0;
+    uint32_t occ_t = 0, occ_k = 0; int occ_obj = -1, occ_blocks = 0;      // occ_obj: kernel mode
 
     HostProblem single;
     std::vector<HostProblem> batch;
@@ -77,6 +77,7 @@ struct jsv_ctx {
     bool dirty = true;                 // host problems changed since the last upload
     bool space_a = true, space_s = true, space_t = true;   // ablation switches
     bool mix = false;                  // mixtures of two tuples per task
+    bool bounds = true;                // skip lanes and waves that latency / capacity bounds exclude
     int objective = 0;                 // Eq. 14 mode and weights
     double alpha = 1.0, beta = 0.035;
 
@@ -471,6 +472,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     pl.partial_obj = (double*)(ws + L.partial_obj);
     pl.objective = (uint32_t)ctx->objective;
     pl.mix = mix_cells != 0 ? 1u : 0u;
+    pl.bounds = ctx->bounds ? 1u : 0u;
     pl.mix_cells = mix_cells;
     pl.cell_acc = (uint64_t*)(ws + L.cell_acc);
     pl.cell_id = (uint64_t*)(ws + L.cell_id);
@@ -479,10 +481,11 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
     pl.n_inst = n; pl.t_max = t_max; pl.k_max = k_max; pl.c_max = c_max;
-    if (ctx->occ_t != t_max || ctx->occ_k != k_max || ctx->occ_obj != ctx->objective) {
+    const int mode = jsv::enumerate_mode(ctx->objective != 0, pl.mix != 0) * 2 + (ctx->bounds ? 1 : 0);
+    if (ctx->occ_t != t_max || ctx->occ_k != k_max || ctx->occ_obj != mode) {
         int blocks = 0;
-        HIP_TRY(ctx, jsv::enumerate_blocks_per_cu(t_max, k_max, ctx->objective != 0, &blocks));
-        ctx->occ_t = t_max; ctx->occ_k = k_max; ctx->occ_obj = ctx->objective; ctx->occ_blocks = blocks;
+        HIP_TRY(ctx, jsv::enumerate_blocks_per_cu(t_max, k_max, mode / 2, ctx->bounds, &blocks));
+        ctx->occ_t = t_max; ctx->occ_k = k_max; ctx->occ_obj = mode; ctx->occ_blocks = blocks;
     }
     const int per_cu = ctx->occ_blocks;
     if (per_cu < 1) return JSV_E_BADARG;
@@ -550,6 +553,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
         summary->max_demand_mrps = sr.max_demand;
         summary->seconds_device = ms_all * 1e-3;
         summary->seconds_enumerate = ms_enum * 1e-3;
+        summary->candidates_visited = (uint64_t)sr.visited * 64u;
     }
     return JSV_OK;
 }
@@ -853,6 +857,13 @@ JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_lev
     for (uint32_t l = 0; l < n_levels; ++l)
         inst[l] = make_instance(ctx, hp, 0, Search{demand_mrps[l], slo_latency_us, prune_cap, slo_accuracy});
     return run_search(ctx, inst, hp.T, k_max_of(hp, prune_cap), hp.C, out, summary);
+}
+
+JSV_API int jsv_set_bounds(jsv_ctx* ctx, int on)
+{
+    if (!ctx) return JSV_E_NULL;
+    ctx->bounds = on != 0;
+    return JSV_OK;
 }
 
 JSV_API int jsv_set_mixtures(jsv_ctx* ctx, int on)

@@ -610,6 +610,7 @@ __device__ void scan_tiles(const Plan& pl, uint64_t* s_sum)
         // the first ticket of every block is its own index: the counter starts behind those
         pl.summary->next_tile = (unsigned long long)pl.grid * tiles_per_ticket(run, pl.grid);
         pl.summary->any_flags = 0;
+        pl.summary->visited = 0;
         pl.summary->best_level = -1;
         pl.summary->max_demand = 0;
     }
@@ -628,7 +629,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     Instance* in = pl.inst + i;
     const Graph* g = pl.graphs + in->problem;
     const uint32_t T = g->T;
-    __shared__ uint32_t s_maxcost[MAXT], s_K[MAXT];
+    __shared__ uint32_t s_maxcost[MAXT], s_mincost[MAXT], s_K[MAXT], s_minxlat;
     __shared__ uint32_t s_bits, s_lb, s_nin, s_ls[3], s_chunk, s_nq, s_last;
     __shared__ uint64_t s_stride[MAXT];
     // the innermost position's entries, staged once: variant, latency, cost, and the first
@@ -636,18 +637,25 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     __shared__ uint16_t s_xvar[MAXC];
     __shared__ uint32_t s_xlat[MAXC], s_xcost[MAXC], s_xq0[MAXC];
     __shared__ uint64_t s_sum[256];
-    if (tid < MAXT) { s_maxcost[tid] = 0; s_K[tid] = tid < T ? in->K[tid] : 0; }
+    if (tid < MAXT) { s_maxcost[tid] = 0; s_mincost[tid] = 0xFFFFFFFFu; s_K[tid] = tid < T ? in->K[tid] : 0; }
+    if (tid == 0) s_minxlat = 0xFFFFFFFFu;
     __syncthreads();
     const uint32_t tx = g->task_at[0], PB = g->P * g->B, KX = s_K[tx];
     for (uint32_t t = 0; t < T; ++t) {
         const Entry* e = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
-        uint32_t m = 0;
+        uint32_t m = 0, mn = 0xFFFFFFFFu, ml = 0xFFFFFFFFu;
         for (uint32_t d = tid; d < s_K[t]; d += blockDim.x) {
             const uint32_t c = e[d].cost;
             m = umax(m, c);
-            if (t == tx) { s_xcost[d] = c; s_xlat[d] = e[d].lat; s_xvar[d] = (uint16_t)(e[d].choice / PB); }
+            mn = c < mn ? c : mn;
+            if (t == tx) {
+                s_xcost[d] = c; s_xlat[d] = e[d].lat; s_xvar[d] = (uint16_t)(e[d].choice / PB);
+                ml = e[d].lat < ml ? e[d].lat : ml;
+            }
         }
         if (m) atomicMax(&s_maxcost[t], m);
+        if (mn != 0xFFFFFFFFu) atomicMin(&s_mincost[t], mn);
+        if (ml != 0xFFFFFFFFu) atomicMin(&s_minxlat, ml);
     }
     __syncthreads();
     if (tid == 0) {
@@ -702,10 +710,10 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             while (lb < 32 && (ranks - 1) >> lb) ++lb;
             uint32_t cb = 0;
             while (cb < 32 && cost_in >> cb) ++cb;
-            // (mixture mode: accuracies differ entry by entry, the per-variant stream does not apply)
-            use32 = (!pl.mix && ranks <= 0x7FFFFFFFull && lb + cb <= 31) ? 1u : 0u;
+            use32 = (ranks <= 0x7FFFFFFFull && lb + cb <= 31) ? 1u : 0u;
         }
-        if (use32) {
+        if (use32 && pl.mix) nq = (KX + 3) / 4;             // one stream in latency order
+        else if (use32) {
             // quads of position 0's stream: every variant's entries rounded up to whole quads
             uint32_t d = 0;
             while (d < KX) {
@@ -740,6 +748,10 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         in->n_chunks = n_chunks; in->n_groups = n_groups;
         in->tiles = n_groups * n_chunks;
         in->use32 = use32; in->lb = lb; in->nq = nq;
+        uint64_t min_in = 0;
+        for (uint32_t p = 0; p < n_in; ++p) min_in += s_mincost[g->task_at[p]];
+        in->min_in_cost = (space != 0 && pl.bounds) ? (uint32_t)(min_in > 0xFFFFFFFFull ? 0xFFFFFFFFull : min_in) : 0u;
+        in->min_x_lat = pl.bounds ? s_minxlat : 0u;
         if (space != 0 && !use32) atomicOr(&in->flags, F_WIDE);
         for (int a = 0; a < 3; ++a) { in->ord[a] = ord[a]; s_ls[a] = ls[a]; }
         s_bits = idx_bits; s_lb = lb; s_nin = use32 ? n_in : 0;
@@ -756,7 +768,24 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     }
     // stream of position 0: by variant, inside a variant by ascending latency (so that the
     // lanes still feasible only shrink along a variant), each variant padded to whole quads
-    if (s_nin != 0) {
+    if (s_nin != 0 && pl.mix) {
+        // mixture mode: all entries in ascending latency, each with its own accuracy
+        const Entry* ex = pl.entries + ((size_t)i * pl.t_max + tx) * pl.k_max;
+        QuadM* qm = (QuadM*)(pl.quads + (size_t)i * pl.k_max);
+        for (uint32_t d = tid; d < KX; d += blockDim.x) {
+            const uint32_t lat = s_xlat[d];
+            uint32_t rank = 0;
+            for (uint32_t x = 0; x < KX; ++x) rank += (s_xlat[x] < lat || (s_xlat[x] == lat && x < d)) ? 1u : 0u;
+            XEntM me;
+            me.lat = lat; me.k32 = (s_xcost[d] << s_lb) | (d * s_ls[0]); me.acc = ex[d].acc;
+            qm[rank / 4].e[rank % 4] = me;
+        }
+        for (uint32_t r = KX + tid; r < s_nq * 4; r += blockDim.x) {
+            XEntM pad;
+            pad.lat = 0xFFFFFFFFu; pad.k32 = 0xFFFFFFFFu; pad.acc = 0.0;
+            qm[r / 4].e[r % 4] = pad;
+        }
+    } else if (s_nin != 0) {
         const Entry* ex = pl.entries + ((size_t)i * pl.t_max + tx) * pl.k_max;
         Quad* qd = pl.quads + (size_t)i * pl.k_max;
         for (uint32_t d = tid; d < KX; d += blockDim.x) {
@@ -824,6 +853,7 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     uint32_t m01, m02, m12;   // all ones if position a has an edge to position b, else 0
     double   w01, w02, w12;   // share of a among the predecessors of b (0 if no edge)
     uint32_t sloq;      // floor(SLO_l / q)
+    uint32_t min_x_lat; // lowest latency of position 0's entries: below it a lane has no candidate
     double   slo_raw;   // SLO_a * A_max
     // objective mode (Eq. 14)
     uint32_t idx_bits, lb, capacity;
@@ -865,11 +895,14 @@ __device__ __forceinline__ LaneState fix_position(const LaneState& s, const Unif
 // candidate does.
 //
 // 64-bit form: the full (cost, index) key per candidate.
+template <bool BOUNDS>
 __device__ __forceinline__ void loop_x64(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                         uint64_t& best)
+                                         uint64_t& best, uint32_t& visits)
 {
     const uint32_t worst = umax(s.smax, s.nxt[0]);           // dead lanes carry smax = 0xFFFFFFFF
     const uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;   // latencies are >= 1
+    if (BOUNDS && __builtin_amdgcn_ballot_w64(thr >= U.min_x_lat) == 0) return;   // no lane of the wave has a candidate here
+    visits += hi - lo;
     const double cx = s.hin[0];
     const Entry JSV_CONST* tx = U.tab[0];
     for (uint32_t d = lo; d < hi; ++d) {
@@ -896,46 +929,60 @@ __device__ __forceinline__ void loop_x64(const LaneState& s, const Uniforms& U, 
 // block ends, and the trailing s_nop keeps a following v_readlane /
 // v_readfirstlane clear of the last vector write to EXEC.  The range [qlo, qhi) is
 // never empty and its first quad always carries the new-variant flag.
+template <bool BOUNDS>
 __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, uint32_t qlo, uint32_t qhi,
-                                         uint64_t full, uint32_t& best32)
+                                         uint64_t full, uint32_t& best32, uint32_t& visits)
 {
     // lanes whose other sources already break the latency SLO sit out (dead lanes carry
-    // smax = 0xFFFFFFFF); for the rest position 0 may take at most thr (latencies are >= 1)
-    const uint64_t alive = __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
+    // smax = 0xFFFFFFFF); for the rest position 0 may take at most thr (latencies are >= 1).
+    // A lane whose thr is below every latency of position 0 has no candidate here; if that
+    // holds for the whole wave the loop is skipped.
     const uint32_t thr = __builtin_elementwise_sub_sat(U.sloq, s.nxt[0]);
+    const uint64_t alive = BOUNDS ? __builtin_amdgcn_ballot_w64((s.smax <= U.sloq) & (thr >= U.min_x_lat))
+                                  : __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
+    if (BOUNDS && alive == 0) return;
+    visits += (qhi - qlo) * 4u;
     uint32_t m = 0xFFFFFFFFu;
     double t;
 #if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile(
-        "s_mov_b32 s88, %[begin]\n\t"
-        "1:\n\t"
-        "s_load_dwordx16 s[72:87], %[base], s88\n\t"
-        "s_add_u32 s88, s88, 64\n\t"
-        "s_waitcnt lgkmcnt(0)\n\t"
-        "s_cmp_eq_u32 s82, 0\n\t"
-        "s_cbranch_scc1 2f\n\t"
-        "s_mov_b64 exec, %[alive]\n\t"
-        "v_fma_f64 %[t], s[80:81], %[cx], %[sacc]\n\t"
-        "v_cmpx_le_f64_e32 vcc, %[slo], %[t]\n\t"
-        "2:\n\t"
-        "v_cmpx_le_u32_e32 vcc, s72, %[thr]\n\t"
-        "v_min_u32_e32 %[m], s73, %[m]\n\t"
-        "v_cmpx_le_u32_e32 vcc, s74, %[thr]\n\t"
-        "v_min_u32_e32 %[m], s75, %[m]\n\t"
-        "v_cmpx_le_u32_e32 vcc, s76, %[thr]\n\t"
-        "v_min_u32_e32 %[m], s77, %[m]\n\t"
-        "v_cmpx_le_u32_e32 vcc, s78, %[thr]\n\t"
-        "v_min_u32_e32 %[m], s79, %[m]\n\t"
-        "s_cmp_lt_u32 s88, %[end]\n\t"
-        "s_cbranch_scc1 1b\n\t"
-        "s_mov_b64 exec, %[full]\n\t"
-        "s_nop 1"
-        : [m] "+v"(m), [t] "=&v"(t)
-        : [base] "s"(U.quads), [begin] "s"(qlo * 64u), [end] "s"(qhi * 64u), [full] "s"(full),
-          [alive] "s"(alive),
-          [thr] "v"(thr), [cx] "v"(s.hin[0]), [sacc] "v"(s.sacc), [slo] "s"(U.slo_raw)
-        : "vcc", "scc", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82",
-          "s83", "s84", "s85", "s86", "s87", "s88");
+    // SKIP: with bounds on, a quad whose fastest candidate no lane can take (or whose variant
+    // no lane's accuracy allows) is left at once: the mask is already empty for its rest.
+#define JSV_X32_LOOP(SKIP)                                                                         \
+    asm volatile(                                                                                  \
+        "s_mov_b32 s88, %[begin]\n\t"                                                              \
+        "1:\n\t"                                                                                   \
+        "s_load_dwordx16 s[72:87], %[base], s88\n\t"                                               \
+        "s_add_u32 s88, s88, 64\n\t"                                                               \
+        "s_waitcnt lgkmcnt(0)\n\t"                                                                 \
+        "s_cmp_eq_u32 s82, 0\n\t"                                                                  \
+        "s_cbranch_scc1 2f\n\t"                                                                    \
+        "s_mov_b64 exec, %[alive]\n\t"                                                             \
+        "v_fma_f64 %[t], s[80:81], %[cx], %[sacc]\n\t"                                             \
+        "v_cmpx_le_f64_e32 vcc, %[slo], %[t]\n\t"                                                  \
+        "2:\n\t"                                                                                   \
+        "v_cmpx_le_u32_e32 vcc, s72, %[thr]\n\t"                                                   \
+        SKIP                                                                                       \
+        "v_min_u32_e32 %[m], s73, %[m]\n\t"                                                        \
+        "v_cmpx_le_u32_e32 vcc, s74, %[thr]\n\t"                                                   \
+        "v_min_u32_e32 %[m], s75, %[m]\n\t"                                                        \
+        "v_cmpx_le_u32_e32 vcc, s76, %[thr]\n\t"                                                   \
+        "v_min_u32_e32 %[m], s77, %[m]\n\t"                                                        \
+        "v_cmpx_le_u32_e32 vcc, s78, %[thr]\n\t"                                                   \
+        "v_min_u32_e32 %[m], s79, %[m]\n\t"                                                        \
+        "4:\n\t"                                                                                   \
+        "s_cmp_lt_u32 s88, %[end]\n\t"                                                             \
+        "s_cbranch_scc1 1b\n\t"                                                                    \
+        "s_mov_b64 exec, %[full]\n\t"                                                              \
+        "s_nop 1"                                                                                  \
+        : [m] "+v"(m), [t] "=&v"(t)                                                                \
+        : [base] "s"(U.quads), [begin] "s"(qlo * 64u), [end] "s"(qhi * 64u), [full] "s"(full),     \
+          [alive] "s"(alive),                                                                      \
+          [thr] "v"(thr), [cx] "v"(s.hin[0]), [sacc] "v"(s.sacc), [slo] "s"(U.slo_raw)             \
+        : "vcc", "scc", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", \
+          "s83", "s84", "s85", "s86", "s87", "s88")
+    if constexpr (BOUNDS) { JSV_X32_LOOP("s_cbranch_execz 4f\n\t"); }
+    else { JSV_X32_LOOP(""); }
+#undef JSV_X32_LOOP
 #else
     (void)thr; (void)t; (void)qlo; (void)qhi; (void)full; (void)alive;
 #endif
@@ -943,13 +990,73 @@ __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, 
     best32 = best32 < cand ? best32 : cand;
 }
 
+// Mixture mode, 32-bit form.  Every entry carries its own accuracy; the stream is in ascending
+// latency, so the latency compare narrows the execution mask for good (and ends the loop
+// once no lane is left), while the accuracy compare masks one candidate only: the mask is
+// saved before it and put back after the minimum.  Per candidate four vector instructions
+// (latency compare, fma, accuracy compare, minimum) and two scalar moves.  A quad is one
+// 64-byte scalar load into s[72:87]: per entry latency, local key, accuracy (2 dwords).
+template <bool BOUNDS>
+__device__ __forceinline__ void loop_x32_mix(const LaneState& s, const Uniforms& U, uint32_t qlo, uint32_t qhi,
+                                             uint64_t full, uint32_t& best32, uint32_t& visits)
+{
+    const uint32_t thr = __builtin_elementwise_sub_sat(U.sloq, s.nxt[0]);
+    const uint64_t alive = BOUNDS ? __builtin_amdgcn_ballot_w64((s.smax <= U.sloq) & (thr >= U.min_x_lat))
+                                  : __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
+    if (BOUNDS && alive == 0) return;
+    uint32_t m = 0xFFFFFFFFu, pos = qhi * 64u;
+    double t;
+#if defined(__HIP_DEVICE_COMPILE__)
+#define JSV_MIX_ENTRY(LAT, KEY, ACC)                       \
+        "v_cmpx_le_u32_e32 vcc, " LAT ", %[thr]\n\t"       \
+        "s_mov_b64 s[90:91], exec\n\t"                     \
+        "v_fma_f64 %[t], " ACC ", %[cx], %[sacc]\n\t"      \
+        "v_cmpx_le_f64_e32 vcc, %[slo], %[t]\n\t"          \
+        "v_min_u32_e32 %[m], " KEY ", %[m]\n\t"            \
+        "s_mov_b64 exec, s[90:91]\n\t"
+    asm volatile(
+        "s_mov_b32 s88, %[begin]\n\t"
+        "s_mov_b64 exec, %[alive]\n\t"
+        "1:\n\t"
+        "s_load_dwordx16 s[72:87], %[base], s88\n\t"
+        "s_add_u32 s88, s88, 64\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        JSV_MIX_ENTRY("s72", "s73", "s[74:75]")
+        "s_cbranch_execz 3f\n\t"
+        JSV_MIX_ENTRY("s76", "s77", "s[78:79]")
+        JSV_MIX_ENTRY("s80", "s81", "s[82:83]")
+        JSV_MIX_ENTRY("s84", "s85", "s[86:87]")
+        "s_cmp_lt_u32 s88, %[end]\n\t"
+        "s_cbranch_scc1 1b\n\t"
+        "3:\n\t"
+        "s_mov_b32 %[pos], s88\n\t"
+        "s_mov_b64 exec, %[full]\n\t"
+        "s_nop 1"
+        : [m] "+v"(m), [t] "=&v"(t), [pos] "=&s"(pos)
+        : [base] "s"(U.quads), [begin] "s"(qlo * 64u), [end] "s"(qhi * 64u), [full] "s"(full),
+          [alive] "s"(alive),
+          [thr] "v"(thr), [cx] "v"(s.hin[0]), [sacc] "v"(s.sacc), [slo] "s"(U.slo_raw)
+        : "vcc", "scc", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82",
+          "s83", "s84", "s85", "s86", "s87", "s88", "s90", "s91");
+#undef JSV_MIX_ENTRY
+#else
+    (void)thr; (void)t; (void)qlo; (void)qhi; (void)full; (void)alive;
+#endif
+    visits += (pos - qlo * 64u) / 16u;
+    const uint32_t cand = __builtin_elementwise_add_sat(s.k32, m);   // stays 0xFFFFFFFF if none
+    best32 = best32 < cand ? best32 : cand;
+}
+
 // Objective mode, 64-bit keys: every candidate gets its objective and the
 // lexicographic (objective, key) maximum.
+template <bool BOUNDS>
 __device__ __forceinline__ void loop_x64_obj(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
-                                             Best& best)
+                                             Best& best, uint32_t& visits)
 {
     const uint32_t worst = umax(s.smax, s.nxt[0]);
     const uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;
+    if (BOUNDS && __builtin_amdgcn_ballot_w64(thr >= U.min_x_lat) == 0) return;
+    visits += hi - lo;
     const double cx = s.hin[0];
     const Entry JSV_CONST* tx = U.tab[0];
     for (uint32_t d = lo; d < hi; ++d) {
@@ -968,7 +1075,10 @@ __device__ __forceinline__ void loop_x64_obj(const LaneState& s, const Uniforms&
 // the cheapest feasible one: per variant the same masked minimum as in cost mode,
 // then one objective and one (objective, key) comparison for the variant's winner.
 // A variant whose cheapest candidate exceeds S_avail has no candidate within it.
-struct TileBest { uint32_t k32; double obj; };
+struct TileBest {
+    uint32_t k32; double obj;
+    uint32_t visits;    // wave-uniform: entries of position 0 this wave went through in the tile
+};
 
 __device__ __forceinline__ void fold_variant(const LaneState& s, const Uniforms& U, uint32_t m, double t, TileBest& tb)
 {
@@ -979,11 +1089,15 @@ __device__ __forceinline__ void fold_variant(const LaneState& s, const Uniforms&
     if (hit && (obj > tb.obj || (obj == tb.obj && k < tb.k32))) { tb.obj = obj; tb.k32 = k; }
 }
 
+template <bool BOUNDS>
 __device__ __forceinline__ void loop_x32_obj(const LaneState& s, const Uniforms& U, uint32_t qlo, uint32_t qhi,
                                              uint64_t full, TileBest& tb)
 {
-    const uint64_t alive = __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
     const uint32_t thr = __builtin_elementwise_sub_sat(U.sloq, s.nxt[0]);
+    const uint64_t alive = BOUNDS ? __builtin_amdgcn_ballot_w64((s.smax <= U.sloq) & (thr >= U.min_x_lat))
+                                  : __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
+    if (BOUNDS && alive == 0) return;
+    tb.visits += (qhi - qlo) * 4u;
     const Quad JSV_CONST* q = U.quads;
     uint32_t m = 0xFFFFFFFFu;
     double t = 0.0;
@@ -1021,20 +1135,28 @@ __device__ __forceinline__ void loop_x32_obj(const LaneState& s, const Uniforms&
     fold_variant(s, U, m, t, tb);
 }
 
-template <bool W32, bool OBJ>
+// What the enumeration kernel is instantiated for.
+constexpr int MODE_COST = 0;      // cheapest feasible
+constexpr int MODE_OBJ  = 1;      // largest objective (Eq. 14)
+constexpr int MODE_MIX  = 2;      // cheapest feasible, options with their own accuracies (Eq. 9, 10)
+
+template <bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
                                        uint64_t full, Best& best, TileBest& tb)
 {
-    if constexpr (OBJ) {
-        if constexpr (W32) loop_x32_obj(s, U, lo, hi, full, tb);
-        else loop_x64_obj(s, U, lo, hi, best);
+    if constexpr (MODE == MODE_OBJ) {
+        if constexpr (W32) loop_x32_obj<BOUNDS>(s, U, lo, hi, full, tb);
+        else loop_x64_obj<BOUNDS>(s, U, lo, hi, best, tb.visits);
+    } else if constexpr (MODE == MODE_MIX) {
+        if constexpr (W32) loop_x32_mix<BOUNDS>(s, U, lo, hi, full, tb.k32, tb.visits);
+        else loop_x64<BOUNDS>(s, U, lo, hi, best.key, tb.visits);
     } else {
-        if constexpr (W32) loop_x32(s, U, lo, hi, full, tb.k32);
-        else loop_x64(s, U, lo, hi, best.key);
+        if constexpr (W32) loop_x32<BOUNDS>(s, U, lo, hi, full, tb.k32, tb.visits);
+        else loop_x64<BOUNDS>(s, U, lo, hi, best.key, tb.visits);
     }
 }
 
-template <bool W32, bool OBJ>
+template <bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void loop_y(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
                                        uint32_t x_hi, uint64_t full, Best& best, TileBest& tb)
 {
@@ -1042,11 +1164,11 @@ __device__ __forceinline__ void loop_y(const LaneState& s, const Uniforms& U, ui
     for (uint32_t d = lo; d < hi; ++d) {
         const LaneState s1 = fix_position<1>(s, U, ty[d].lat, ty[d].acc, W32 ? 0 : ty[d].key,
                                              W32 ? U.k32[1][d] : 0u);
-        loop_x<W32, OBJ>(s1, U, 0, x_hi, full, best, tb);
+        loop_x<W32, MODE, BOUNDS>(s1, U, 0, x_hi, full, best, tb);
     }
 }
 
-template <bool W32, bool OBJ>
+template <bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
                                        uint32_t x_hi, uint64_t full, Best& best, TileBest& tb)
 {
@@ -1054,18 +1176,18 @@ __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, ui
     for (uint32_t d = lo; d < hi; ++d) {
         const LaneState s2 = fix_position<2>(s, U, tz[d].lat, tz[d].acc, W32 ? 0 : tz[d].key,
                                              W32 ? U.k32[2][d] : 0u);
-        loop_y<W32, OBJ>(s2, U, 0, U.K[1], x_hi, full, best, tb);
+        loop_y<W32, MODE, BOUNDS>(s2, U, 0, U.K[1], x_hi, full, best, tb);
     }
 }
 
 // One tile: 256 lanes, each a different combination of the positions >= NIN
 // (decoded from the mixed-radix outer index), all looping over the same digits of
 // positions < NIN.
-template <int NIN, bool W32, bool OBJ>
+template <int NIN, bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instance JSV_CONST* in,
                                          const Entry JSV_CONST* tab, const uint32_t JSV_CONST* k32,
                                          const Quad JSV_CONST* quads, const Entry* s_tab, uint32_t k_max,
-                                         uint64_t group, uint32_t chunk_id, Best& best)
+                                         uint64_t group, uint32_t chunk_id, Best& best, uint64_t& visited)
 {
     const uint32_t T = g->T;
     uint64_t o = group * TILE_LANES + threadIdx.x;
@@ -1134,10 +1256,19 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     U.m01 = 0u - ((g->succ[0] >> 1) & 1u); U.m02 = 0u - ((g->succ[0] >> 2) & 1u); U.m12 = 0u - ((g->succ[1] >> 2) & 1u);
     U.w01 = g->w[0][1]; U.w02 = g->w[0][2]; U.w12 = g->w[1][2];
     U.sloq = in->slo_l / g->q;
+    U.min_x_lat = in->min_x_lat;
     U.slo_raw = in->slo_raw;
     U.idx_bits = in->idx_bits; U.lb = in->lb; U.capacity = g->capacity;
     U.alpha_n = in->alpha_n; U.beta = in->beta;
     st.cost_out = (uint32_t)(st.key >> in->idx_bits);
+    // Eq. 8 as a bound: a lane whose fixed positions plus the cheapest entries of the in-lane
+    // positions already exceed S_avail holds no candidate within the capacity; it sits out like
+    // a lane that cannot meet the latency SLO.  The minimum over the remaining candidates is the
+    // reported one whenever that one fits S_avail, and nothing is reported otherwise.
+    if constexpr (BOUNDS) {
+        if (g->capacity != 0 && (uint64_t)st.cost_out + in->min_in_cost > g->capacity) st.smax = 0xFFFFFFFFu;
+        if (__builtin_amdgcn_ballot_w64(st.smax <= U.sloq) == 0) return;     // nothing left for this wave
+    }
 
     // extent of the innermost loop (quads of the stream, or digits) and of the chunked loop
     const uint32_t x_all = W32 ? in->nq : U.K[0];
@@ -1145,11 +1276,12 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     const uint32_t lo = chunk_id * in->chunk;
     const uint32_t hi = lo + in->chunk < Ko ? lo + in->chunk : Ko;
     TileBest tb;
-    tb.k32 = 0xFFFFFFFFu; tb.obj = -__builtin_inf();
+    tb.k32 = 0xFFFFFFFFu; tb.obj = -__builtin_inf(); tb.visits = 0;
     const uint64_t full = __builtin_amdgcn_read_exec();     // the loops below run convergent
-    if constexpr (NIN == 3) loop_z<W32, OBJ>(st, U, lo, hi, x_all, full, best, tb);
-    else if constexpr (NIN == 2) loop_y<W32, OBJ>(st, U, lo, hi, x_all, full, best, tb);
-    else loop_x<W32, OBJ>(st, U, lo, hi, full, best, tb);
+    if constexpr (NIN == 3) loop_z<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
+    else if constexpr (NIN == 2) loop_y<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
+    else loop_x<W32, MODE, BOUNDS>(st, U, lo, hi, full, best, tb);
+    visited += tb.visits;
 
     if constexpr (W32) {
         // the lane's 32-bit winner of this tile -> its full (cost, index) key
@@ -1165,7 +1297,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
             r /= K;
             k += s_tab[t * k_max + d].key;
         }
-        if constexpr (OBJ) {
+        if constexpr (MODE == MODE_OBJ) {
             if (hit && better(tb.obj, k, best.obj, best.key)) { best.obj = tb.obj; best.key = k; }
         } else {
             best.key = (hit && k < best.key) ? k : best.key;
@@ -1195,9 +1327,10 @@ __device__ __forceinline__ void flush_block(const Plan& pl, uint32_t inst, const
 // the instances in ascending order; it keeps one running minimum per lane and
 // reduces it (wave, then block) only when the instance changes.  Every block ends
 // with the first ticket at or past the total.
-template <bool OBJ>
+template <int MODE, bool BOUNDS>
 __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
 {
+    constexpr bool OBJ = MODE == MODE_OBJ;
     extern __shared__ __attribute__((aligned(32))) unsigned char smem_raw[];
     Entry* s_tab = (Entry*)smem_raw;
     __shared__ uint64_t s_red[4];
@@ -1213,6 +1346,7 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     uint32_t scan = 0;              // instance search cursor
     Best best;
     best.key = NO_KEY; best.obj = -__builtin_inf();
+    uint64_t visited = 0;           // wave-uniform
     const uint32_t batch = tiles_per_ticket(total, gridDim.x);
     uint64_t tile = (uint64_t)blockIdx.x * batch;         // a block's first ticket is its own index,
     uint64_t tile_end = tile + batch;                     // later ones come from the counter
@@ -1252,21 +1386,22 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const uint64_t group = local / n_chunks;
         if (in->use32) {
             switch (in->n_in) {
-            case 3: run_tile<3, true, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
-            case 2: run_tile<2, true, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
-            default: run_tile<1, true, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
+            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
+            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
             }
         } else {
             switch (in->n_in) {
-            case 3: run_tile<3, false, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
-            case 2: run_tile<2, false, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
-            default: run_tile<1, false, OBJ>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best); break;
+            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
+            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
+            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
             }
         }
     }
     if (cur != 0xFFFFFFFFu) {
         flush_block<OBJ>(pl, cur, best, s_red, s_red_obj);
     }
+    if ((threadIdx.x & 63u) == 0 && visited != 0) atomicAdd(&pl.summary->visited, (unsigned long long)visited);
 }
 
 // ---- scoring of one assignment (finalize and eval) -----------------------------------------
@@ -1433,29 +1568,36 @@ hipError_t launch_prune_plan_scan(const Plan& pl, hipStream_t stream)
     return hipGetLastError();
 }
 
+// The instantiation a plan runs: objective mode, mixture mode or plain cheapest-feasible, each
+// with or without the bulk exclusion by bounds.
+using EnumerateFn = void (*)(Plan);
+static EnumerateFn enumerate_entry(int mode, bool bounds)
+{
+    switch (mode) {
+    case MODE_OBJ: return bounds ? enumerate_kernel<MODE_OBJ, true> : enumerate_kernel<MODE_OBJ, false>;
+    case MODE_MIX: return bounds ? enumerate_kernel<MODE_MIX, true> : enumerate_kernel<MODE_MIX, false>;
+    default:       return bounds ? enumerate_kernel<MODE_COST, true> : enumerate_kernel<MODE_COST, false>;
+    }
+}
+
+int enumerate_mode(bool objective, bool mixtures) { return objective ? MODE_OBJ : mixtures ? MODE_MIX : MODE_COST; }
+
 // Blocks of the enumeration kernel that are resident per CU with this much LDS.
-hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, bool objective, int* blocks)
+hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, int mode, bool bounds, int* blocks)
 {
     const size_t lds = enumerate_lds_bytes(t_max, k_max);
+    const void* fn = (const void*)enumerate_entry(mode, bounds);
     if (lds > 32 * 1024) {      // beyond the default dynamic limit: ask for it explicitly
-        hipError_t e = objective ? hipFuncSetAttribute((const void*)enumerate_kernel<true>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
-                                 : hipFuncSetAttribute((const void*)enumerate_kernel<false>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    return objective ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, (const void*)enumerate_kernel<true>, TILE_LANES, lds)
-                     : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, (const void*)enumerate_kernel<false>, TILE_LANES, lds);
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, fn, TILE_LANES, lds);
 }
 
 hipError_t launch_enumerate(const Plan& pl, hipStream_t stream)
 {
-    if (pl.objective)
-        hipLaunchKernelGGL(enumerate_kernel<true>, dim3(pl.grid), dim3(TILE_LANES),
-                           enumerate_lds_bytes(pl.t_max, pl.k_max), stream, pl);
-    else
-        hipLaunchKernelGGL(enumerate_kernel<false>, dim3(pl.grid), dim3(TILE_LANES),
-                           enumerate_lds_bytes(pl.t_max, pl.k_max), stream, pl);
+    const EnumerateFn fn = enumerate_entry(enumerate_mode(pl.objective != 0, pl.mix != 0), pl.bounds != 0);
+    hipLaunchKernelGGL(fn, dim3(pl.grid), dim3(TILE_LANES), enumerate_lds_bytes(pl.t_max, pl.k_max), stream, pl);
     return hipGetLastError();
 }
 

@@ -15,7 +15,9 @@ size_t enumerate_lds_bytes(uint32_t t_max, uint32_t k_max);
 // cost table + prune (mixture mode: options + prune), then plan (with the tile scan): two
 // launches on `stream`
 hipError_t launch_prune_plan_scan(const Plan& pl, hipStream_t stream);
-hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, bool objective, int* blocks);
+// which instantiation of the enumeration kernel a search runs
+int enumerate_mode(bool objective, bool mixtures);
+hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, int mode, bool bounds, int* blocks);
 // pl.grid blocks; pl.grid must not exceed what enumerate_blocks_per_cu allows to be resident
 hipError_t launch_enumerate(const Plan& pl, hipStream_t stream);
 hipError_t launch_finalize(const Plan& pl, hipStream_t stream);

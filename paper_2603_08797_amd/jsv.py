@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libjsv.so")
 MAX_TASKS = 16
 OK, E_NULL, E_BADARG, E_CYCLE, E_OVERFLOW, E_STATE, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6, -7
 
-EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space", "jsv_set_factors", "jsv_set_mixtures", "jsv_set_graph_mode",
+EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space", "jsv_set_factors", "jsv_set_mixtures", "jsv_set_bounds", "jsv_set_graph_mode",
            "jsv_workspace_bytes", "jsv_set_workspace", "jsv_load_profile", "jsv_set_dag",
            "jsv_search", "jsv_eval_candidates", "jsv_get_pruned", "jsv_load_batch",
            "jsv_search_loaded_batch", "jsv_search_batch"]
@@ -37,7 +37,8 @@ class JsvResult(C.Structure):
 
 class JsvSummary(C.Structure):
     _fields_ = [("best_level", C.c_int32), ("max_demand_mrps", C.c_uint32),
-                ("seconds_device", C.c_double), ("seconds_enumerate", C.c_double)]
+                ("seconds_device", C.c_double), ("seconds_enumerate", C.c_double),
+                ("candidates_visited", C.c_uint64)]
 
 
 class JsvProblem(C.Structure):
@@ -76,6 +77,8 @@ def load_library():
     lib.jsv_set_objective.argtypes = [vp, C.c_int, f64, f64]
     lib.jsv_set_search_space.restype = C.c_int
     lib.jsv_set_search_space.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+    lib.jsv_set_bounds.restype = C.c_int
+    lib.jsv_set_bounds.argtypes = [vp, C.c_int]
     lib.jsv_set_mixtures.restype = C.c_int
     lib.jsv_set_mixtures.argtypes = [vp, C.c_int]
     lib.jsv_set_factors.restype = C.c_int
@@ -137,6 +140,7 @@ class Summary:
     max_demand_mrps: int
     seconds_device: float
     seconds_enumerate: float
+    candidates_visited: int = 0
 
 
 def _u32(a):
@@ -224,6 +228,11 @@ class Jsv:
             raise ValueError("factor_milli must have shape [E][V] of the loaded graph and profile")
         self._check(self._lib.jsv_set_factors(self._h, f.ctypes.data_as(C.c_void_p)), "jsv_set_factors")
 
+    def set_bounds(self, on: bool = True):
+        """Skip candidates that latency or capacity bounds exclude in bulk (default on); the
+        result does not depend on it."""
+        self._check(self._lib.jsv_set_bounds(self._h, int(on)), "jsv_set_bounds")
+
     def set_mixtures(self, on: bool = True):
         """Let a task run two tuples side by side (Eq. 2, 6, 7, 9, 10)."""
         self._check(self._lib.jsv_set_mixtures(self._h, int(on)), "jsv_set_mixtures")
@@ -280,7 +289,7 @@ class Jsv:
                                          int(prune_cap), res, C.byref(summ)), "jsv_search")
         return ([_result(res[i], self.T) for i in range(n)],
                 Summary(int(summ.best_level), int(summ.max_demand_mrps), float(summ.seconds_device),
-                        float(summ.seconds_enumerate)))
+                        float(summ.seconds_enumerate), int(summ.candidates_visited)))
 
     def eval_candidates(self, demand_mrps: int, slo_latency_us: int, slo_accuracy: float,
                         prune_cap: int, index):
@@ -342,7 +351,7 @@ class Jsv:
         self._check(self._lib.jsv_search_loaded_batch(self._h, res, C.byref(summ)), "jsv_search_loaded_batch")
         return ([_result(res[i], self._batch_T[i]) for i in range(n)],
                 Summary(int(summ.best_level), int(summ.max_demand_mrps), float(summ.seconds_device),
-                        float(summ.seconds_enumerate)))
+                        float(summ.seconds_enumerate), int(summ.candidates_visited)))
 
     def search_batch(self, problems: Sequence, searches: Sequence):
         arr, keep = self._marshal_batch(problems, searches)

@@ -1,0 +1,82 @@
+"""The latency / capacity bounds of the enumeration change what the kernel skips, never the
+result: every search is run with bounds on and off and compared field by field."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from paper_2603_08797_amd import jsv, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    j = jsv.Jsv(device=0)
+    yield j
+    j.set_bounds(True)
+    j.close()
+
+
+def both(ctx, run):
+    ctx.set_bounds(True)
+    a, sa = run()
+    ctx.set_bounds(False)
+    b, sb = run()
+    ctx.set_bounds(True)
+    assert len(a) == len(b)
+    for x, y in zip(a, b):
+        assert dataclasses.asdict(x) == dataclasses.asdict(y)
+    assert (sa.best_level, sa.max_demand_mrps) == (sb.best_level, sb.max_demand_mrps)
+    # off: every candidate's tests are issued (whole waves, padded streams); on: at most as many
+    total = sum(r.evaluated for r in b)
+    assert sb.candidates_visited >= total
+    assert sa.candidates_visited <= sb.candidates_visited
+    return sa.candidates_visited, sb.candidates_visited, total
+
+
+@pytest.mark.parametrize("name", ["chain3", "diamond5", "chain4"])
+def test_bench_workloads(ctx, name):
+    w = workloads.BENCH_WORKLOADS[name]()
+    pb, se = w.problems[0], w.searches[0]
+    ctx.load(pb)
+    both(ctx, lambda: ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap))
+
+
+def test_xr8_small_cap_cuts_most_of_the_sweep(ctx):
+    w = workloads.xr8(prune_cap=10)
+    pb, se = w.problems[0], w.searches[0]
+    ctx.load(pb)
+    on, off, total = both(ctx, lambda: ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 10))
+    assert on < off // 2          # the upper half of the sweep cannot fit S_avail
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_tiny_random(ctx, seed):
+    pb, se = workloads.tiny_random(9000 + seed)
+    ctx.load(pb)
+    both(ctx, lambda: ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap))
+    ctx.set_objective(1, 1.0, 0.035)
+    try:
+        both(ctx, lambda: ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap))
+    finally:
+        ctx.set_objective(0, 1.0, 0.035)
+
+
+def test_batch(ctx):
+    w = workloads.dagbatch(n=48)
+    ctx.load_batch(w.problems, w.searches)
+    both(ctx, ctx.search_loaded_batch)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_mixtures(ctx, seed):
+    pb, se = workloads.tiny_mixture(9100 + seed)
+    if pb.capacity_units == 0:
+        pb = dataclasses.replace(pb, capacity_units=30)
+    ctx.load(pb)
+    ctx.set_mixtures(True)
+    try:
+        both(ctx, lambda: ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 9))
+    finally:
+        ctx.set_mixtures(False)

@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported():
 def test_struct_sizes_match_the_header():
     import ctypes
     assert ctypes.sizeof(jsv.JsvResult) == 8 * 4 + 4 * 4 + 2 * 16 + 4 * 16 + 8 + 2 * 16 + 4 * 16
-    assert ctypes.sizeof(jsv.JsvSummary) == 24
+    assert ctypes.sizeof(jsv.JsvSummary) == 32
 
 
 @pytest.fixture()
