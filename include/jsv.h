@@ -191,9 +191,11 @@ JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial
  * those of the innermost tasks is excluded as a whole when the digits it shares already break
  * the latency SLO (Eq. 3), when its remaining latency budget is below the fastest choice of
  * the innermost task, or, with S_avail set, when its shared cost plus the cheapest choices of
- * the innermost tasks exceeds S_avail (Eq. 8); the kernel skips the tests of such candidates
- * where a whole 64-lane wave of groups is excluded.  The result is the same with bounds on
- * or off (every excluded candidate fails a constraint); off makes the kernel issue the tests
+ * the innermost tasks exceeds S_avail (Eq. 8) or the cost of a candidate already found that
+ * meets both SLOs (objective mode: the cost beyond which alpha - beta * cost falls below an
+ * objective already reached); the kernel skips the tests of such candidates where a whole
+ * 64-lane wave of groups is excluded.  The result is the same with bounds on or off (an
+ * excluded candidate fails a constraint or is worse than one that was found); off makes the kernel issue the tests
  * of every candidate, which is what throughput measurements of the plain enumeration use.
  * jsv_summary.candidates_visited tells how many candidates had their tests issued.
  */

@@ -141,6 +141,8 @@ struct Instance {
     // instance, NOT_HELD = free.  With every task that changes a downstream demand held, the
     // demands of all tasks are fixed and the instance is an ordinary search.
     uint16_t held[MAXT];
+    uint32_t min_x_cost;      // cheapest entry of the innermost position (plan kernel)
+    uint32_t min_xy_cost;     // plus the cheapest entry of the position above it (if looped in-lane)
 };
 
 // Result record as written by the finalize kernel; same layout as jsv_result.
@@ -196,6 +198,9 @@ struct Plan {
     uint64_t* cell_pm;        // prefix maxima of cell_acc; later reused as a list of kept cells
     uint32_t* cell_list;      // cells that survive the dominance test
     uint64_t  mix_cells;
+    // bounds on: per instance the largest total cost still of interest: S_avail at first, then
+    // the cost of the cheapest candidate found so far that meets both SLOs (cost modes only)
+    uint32_t* bound;          // [n_inst]
 };
 
 }  // namespace jsv

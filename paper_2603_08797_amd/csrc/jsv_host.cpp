@@ -56,6 +56,7 @@ struct Search {               // per-instance search parameters (batch mode keep
 struct Layout {               // offsets into the workspace
     size_t inst, entries, rep, cost, k32, quads, partial, partial_obj, results, summary, eval, total;
     size_t cell_acc, cell_id, cell_pm, cell_list;     // mixture mode only
+    size_t bound;
 };
 
 }  // namespace
@@ -402,6 +403,7 @@ Layout make_layout(uint32_t n_inst, uint32_t t_max, uint32_t k_max, uint32_t c_m
     L.partial_obj = off; off = align_up(off + sizeof(double) * (size_t)n_inst * grid);
     L.results = off; off = align_up(off + sizeof(jsv::ResultRec) * n_inst);
     L.summary = off; off = align_up(off + sizeof(jsv::SummaryRec));
+    L.bound = off;   off = align_up(off + sizeof(uint32_t) * n_inst);
     L.eval = off;    // index u64, latency u32, replicas u32*T, cost i32, accuracy f64, mask u8, bad u32
     off = align_up(off + (size_t)n_eval * (8 + 4 + 4 * MAXT + 4 + 8 + 1) + 6 * ALIGN);
     const size_t blocks = (size_t)n_inst * t_max;
@@ -480,6 +482,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     pl.cell_list = (uint32_t*)(ws + L.cell_list);
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
+    pl.bound = (uint32_t*)(ws + L.bound);
     pl.n_inst = n; pl.t_max = t_max; pl.k_max = k_max; pl.c_max = c_max;
     const int mode = jsv::enumerate_mode(ctx->objective != 0, pl.mix != 0) * 2 + (ctx->bounds ? 1 : 0);
     if (ctx->occ_t != t_max || ctx->occ_k != k_max || ctx->occ_obj != mode) {
@@ -931,6 +934,7 @@ JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo
     pl.objective = (uint32_t)ctx->objective;
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
+    pl.bound = (uint32_t*)(ws + L.bound);
     pl.n_inst = 1; pl.t_max = T; pl.k_max = k_max; pl.c_max = hp.C;
     pl.grid = ctx->grid; pl.lanes_wanted = 64;
 
@@ -999,6 +1003,7 @@ JSV_API int jsv_get_pruned(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_late
     pl.objective = (uint32_t)ctx->objective;
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
+    pl.bound = (uint32_t*)(ws + L.bound);
     pl.n_inst = 1; pl.t_max = T; pl.k_max = k_max; pl.c_max = hp.C;
     pl.grid = ctx->grid; pl.lanes_wanted = 64;
     hipStream_t st = ctx->stream;

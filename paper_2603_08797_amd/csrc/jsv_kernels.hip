@@ -752,6 +752,9 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         for (uint32_t p = 0; p < n_in; ++p) min_in += s_mincost[g->task_at[p]];
         in->min_in_cost = (space != 0 && pl.bounds) ? (uint32_t)(min_in > 0xFFFFFFFFull ? 0xFFFFFFFFull : min_in) : 0u;
         in->min_x_lat = pl.bounds ? s_minxlat : 0u;
+        in->min_x_cost = (space != 0 && pl.bounds) ? s_mincost[tx] : 0u;
+        in->min_xy_cost = (space != 0 && pl.bounds && n_in >= 2) ? s_mincost[tx] + s_mincost[g->task_at[1]] : 0u;
+        pl.bound[i] = g->capacity != 0 ? g->capacity : 0xFFFFFFFFu;
         if (space != 0 && !use32) atomicOr(&in->flags, F_WIDE);
         for (int a = 0; a < 3; ++a) { in->ord[a] = ord[a]; s_ls[a] = ls[a]; }
         s_bits = idx_bits; s_lb = lb; s_nin = use32 ? n_in : 0;
@@ -854,6 +857,9 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     double   w01, w02, w12;   // share of a among the predecessors of b (0 if no edge)
     uint32_t sloq;      // floor(SLO_l / q)
     uint32_t min_x_lat; // lowest latency of position 0's entries: below it a lane has no candidate
+    uint32_t min_x_cost; // cheapest entry of position 0
+    uint32_t min_xy_cost; // cheapest entries of positions 0 and 1 together
+    uint32_t bound;     // total cost beyond which a candidate cannot be the answer (as read at the tile's start)
     double   slo_raw;   // SLO_a * A_max
     // objective mode (Eq. 14)
     uint32_t idx_bits, lb, capacity;
@@ -900,8 +906,11 @@ __device__ __forceinline__ void loop_x64(const LaneState& s, const Uniforms& U, 
                                          uint64_t& best, uint32_t& visits)
 {
     const uint32_t worst = umax(s.smax, s.nxt[0]);           // dead lanes carry smax = 0xFFFFFFFF
-    const uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;   // latencies are >= 1
-    if (BOUNDS && __builtin_amdgcn_ballot_w64(thr >= U.min_x_lat) == 0) return;   // no lane of the wave has a candidate here
+    uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;         // latencies are >= 1
+    if constexpr (BOUNDS) {
+        if ((s.key >> U.idx_bits) + U.min_x_cost > U.bound) thr = 0;    // too costly whatever position 0 takes
+        if (__builtin_amdgcn_ballot_w64(thr >= U.min_x_lat) == 0) return;   // no lane of the wave has a candidate here
+    }
     visits += hi - lo;
     const double cx = s.hin[0];
     const Entry JSV_CONST* tx = U.tab[0];
@@ -938,8 +947,12 @@ __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, 
     // A lane whose thr is below every latency of position 0 has no candidate here; if that
     // holds for the whole wave the loop is skipped.
     const uint32_t thr = __builtin_elementwise_sub_sat(U.sloq, s.nxt[0]);
-    const uint64_t alive = BOUNDS ? __builtin_amdgcn_ballot_w64((s.smax <= U.sloq) & (thr >= U.min_x_lat))
-                                  : __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
+    uint64_t alive;
+    if constexpr (BOUNDS) {
+        // also out: lanes whose fixed positions plus the cheapest entry here cost more than the bound
+        const uint32_t fixed = s.cost_out + (s.k32 >> U.lb);
+        alive = __builtin_amdgcn_ballot_w64((s.smax <= U.sloq) & (thr >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
+    } else alive = __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
     if (BOUNDS && alive == 0) return;
     visits += (qhi - qlo) * 4u;
     uint32_t m = 0xFFFFFFFFu;
@@ -1001,8 +1014,12 @@ __device__ __forceinline__ void loop_x32_mix(const LaneState& s, const Uniforms&
                                              uint64_t full, uint32_t& best32, uint32_t& visits)
 {
     const uint32_t thr = __builtin_elementwise_sub_sat(U.sloq, s.nxt[0]);
-    const uint64_t alive = BOUNDS ? __builtin_amdgcn_ballot_w64((s.smax <= U.sloq) & (thr >= U.min_x_lat))
-                                  : __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
+    uint64_t alive;
+    if constexpr (BOUNDS) {
+        // also out: lanes whose fixed positions plus the cheapest entry here cost more than the bound
+        const uint32_t fixed = s.cost_out + (s.k32 >> U.lb);
+        alive = __builtin_amdgcn_ballot_w64((s.smax <= U.sloq) & (thr >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
+    } else alive = __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
     if (BOUNDS && alive == 0) return;
     uint32_t m = 0xFFFFFFFFu, pos = qhi * 64u;
     double t;
@@ -1054,8 +1071,11 @@ __device__ __forceinline__ void loop_x64_obj(const LaneState& s, const Uniforms&
                                              Best& best, uint32_t& visits)
 {
     const uint32_t worst = umax(s.smax, s.nxt[0]);
-    const uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;
-    if (BOUNDS && __builtin_amdgcn_ballot_w64(thr >= U.min_x_lat) == 0) return;
+    uint32_t thr = worst <= U.sloq ? U.sloq - s.nxt[0] : 0u;
+    if constexpr (BOUNDS) {
+        if ((s.key >> U.idx_bits) + U.min_x_cost > U.bound) thr = 0;
+        if (__builtin_amdgcn_ballot_w64(thr >= U.min_x_lat) == 0) return;
+    }
     visits += hi - lo;
     const double cx = s.hin[0];
     const Entry JSV_CONST* tx = U.tab[0];
@@ -1094,8 +1114,12 @@ __device__ __forceinline__ void loop_x32_obj(const LaneState& s, const Uniforms&
                                              uint64_t full, TileBest& tb)
 {
     const uint32_t thr = __builtin_elementwise_sub_sat(U.sloq, s.nxt[0]);
-    const uint64_t alive = BOUNDS ? __builtin_amdgcn_ballot_w64((s.smax <= U.sloq) & (thr >= U.min_x_lat))
-                                  : __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
+    uint64_t alive;
+    if constexpr (BOUNDS) {
+        // also out: lanes whose fixed positions plus the cheapest entry here cost more than the bound
+        const uint32_t fixed = s.cost_out + (s.k32 >> U.lb);
+        alive = __builtin_amdgcn_ballot_w64((s.smax <= U.sloq) & (thr >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
+    } else alive = __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
     if (BOUNDS && alive == 0) return;
     tb.visits += (qhi - qlo) * 4u;
     const Quad JSV_CONST* q = U.quads;
@@ -1176,6 +1200,12 @@ __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, ui
     for (uint32_t d = lo; d < hi; ++d) {
         const LaneState s2 = fix_position<2>(s, U, tz[d].lat, tz[d].acc, W32 ? 0 : tz[d].key,
                                              W32 ? U.k32[2][d] : 0u);
+        if constexpr (BOUNDS) {
+            // with this digit fixed, is any lane left that meets the latency SLO so far and stays
+            // within the cost bound with the cheapest entries of the two positions below?
+            const uint64_t fixed = W32 ? (uint64_t)(s2.cost_out + (s2.k32 >> U.lb)) : (s2.key >> U.idx_bits);
+            if (__builtin_amdgcn_ballot_w64((s2.smax <= U.sloq) & (fixed + U.min_xy_cost <= U.bound)) == 0) continue;
+        }
         loop_y<W32, MODE, BOUNDS>(s2, U, 0, U.K[1], x_hi, full, best, tb);
     }
 }
@@ -1187,7 +1217,7 @@ template <int NIN, bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instance JSV_CONST* in,
                                          const Entry JSV_CONST* tab, const uint32_t JSV_CONST* k32,
                                          const Quad JSV_CONST* quads, const Entry* s_tab, uint32_t k_max,
-                                         uint64_t group, uint32_t chunk_id, Best& best, uint64_t& visited)
+                                         uint64_t group, uint32_t chunk_id, uint32_t bound, Best& best, uint64_t& visited)
 {
     const uint32_t T = g->T;
     uint64_t o = group * TILE_LANES + threadIdx.x;
@@ -1257,16 +1287,20 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     U.w01 = g->w[0][1]; U.w02 = g->w[0][2]; U.w12 = g->w[1][2];
     U.sloq = in->slo_l / g->q;
     U.min_x_lat = in->min_x_lat;
+    U.min_x_cost = in->min_x_cost;
+    U.min_xy_cost = in->min_xy_cost;
+    U.bound = bound;
     U.slo_raw = in->slo_raw;
     U.idx_bits = in->idx_bits; U.lb = in->lb; U.capacity = g->capacity;
     U.alpha_n = in->alpha_n; U.beta = in->beta;
     st.cost_out = (uint32_t)(st.key >> in->idx_bits);
-    // Eq. 8 as a bound: a lane whose fixed positions plus the cheapest entries of the in-lane
-    // positions already exceed S_avail holds no candidate within the capacity; it sits out like
-    // a lane that cannot meet the latency SLO.  The minimum over the remaining candidates is the
-    // reported one whenever that one fits S_avail, and nothing is reported otherwise.
+    // Cost as a bound: `bound` is S_avail (Eq. 8) or, in the cost modes, the cost of a candidate
+    // already found that meets both SLOs, whichever is lower.  A lane whose fixed positions plus
+    // the cheapest entries of the in-lane positions cost more holds neither a candidate within
+    // S_avail nor one cheaper than what is known; it sits out like a lane that cannot meet the
+    // latency SLO.  Candidates as cheap as the bound stay in (the lowest index wins among them).
     if constexpr (BOUNDS) {
-        if (g->capacity != 0 && (uint64_t)st.cost_out + in->min_in_cost > g->capacity) st.smax = 0xFFFFFFFFu;
+        if ((uint64_t)st.cost_out + in->min_in_cost > bound) st.smax = 0xFFFFFFFFu;
         if (__builtin_amdgcn_ballot_w64(st.smax <= U.sloq) == 0) return;     // nothing left for this wave
     }
 
@@ -1384,17 +1418,42 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const uint32_t n_chunks = in->n_chunks;
         const uint32_t chunk_id = (uint32_t)(local % n_chunks);
         const uint64_t group = local / n_chunks;
+        // the instance's cost bound as it stands now; a stale (higher) value only excludes less
+        uint32_t bound = 0xFFFFFFFFu;
+        if constexpr (BOUNDS)
+            bound = (uint32_t)__builtin_amdgcn_readfirstlane(
+                (int)__hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         if (in->use32) {
             switch (in->n_in) {
-            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
-            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
-            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
+            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
+            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
+            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
             }
         } else {
             switch (in->n_in) {
-            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
-            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
-            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, best, visited); break;
+            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
+            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
+            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
+            }
+        }
+        if constexpr (BOUNDS && MODE != MODE_OBJ) {
+            // a candidate that meets both SLOs and costs less than the bound lowers it for every
+            // block working on this instance (cost modes: nothing costlier can be the answer)
+            const uint32_t c = best.key == NO_KEY ? 0xFFFFFFFFu : (uint32_t)(best.key >> in->idx_bits);
+            const uint32_t wc = (uint32_t)wave_min((uint64_t)c);
+            if (wc < bound && (threadIdx.x & 63u) == 0) atomicMin(pl.bound + cur, wc);
+        }
+        if constexpr (BOUNDS && MODE == MODE_OBJ) {
+            // Eq. 14: A_obj <= 1, so a candidate of cost c scores at most alpha - beta*c.  With an
+            // objective o already reached, nothing costlier than (alpha - o)/beta can match it;
+            // one unit of slack keeps the test clear of rounding and of equal objectives.
+            const Best wb = wave_best(best);
+            if (wb.key != NO_KEY && in->beta > 1e-9 * (in->alpha + 1.0)) {     // else rounding could reach a unit of cost
+                const double lim = (in->alpha - wb.obj) / in->beta;
+                if (lim >= 0.0 && lim < 2147483000.0) {
+                    const uint32_t wc = (uint32_t)lim + 1u;
+                    if (wc < bound && (threadIdx.x & 63u) == 0) atomicMin(pl.bound + cur, wc);
+                }
             }
         }
     }
