@@ -40,7 +40,8 @@ UNSHARED_OPS_PER_CANDIDATE = 11
 # against a 1 GiB copy (profiles/enumerate_kernel_xr8_hbm_traffic.md); known only for the
 # default workload in cost mode.
 # key: workload, seed, objective mode, mixture mode, bounds
-MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (3614 + 11410) * 1024}
+MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (3655 + 11633) * 1024,
+                          ("xr8", 0, False, False, True): (15843 + 16139) * 1024}
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one full-rate VALU lane-op per lane per cycle
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 

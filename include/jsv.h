@@ -197,7 +197,9 @@ JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial
  * 64-lane wave of groups is excluded.  The result is the same with bounds on or off (an
  * excluded candidate fails a constraint or is worse than one that was found); off makes the kernel issue the tests
  * of every candidate, which is what throughput measurements of the plain enumeration use.
- * jsv_summary.candidates_visited tells how many candidates had their tests issued.
+ * jsv_summary.candidates_visited tells how many candidates had their tests issued.  A search
+ * with fewer than 32 tiles of 256 lanes per block of the grid runs the plain enumeration even
+ * with bounds on: everything is in flight at once there and no bound would arrive in time.
  */
 JSV_API int jsv_set_bounds(jsv_ctx* ctx, int on);
 
@@ -255,10 +257,10 @@ typedef struct {
     uint32_t max_demand_mrps;  /* its demand: the maximum serviceable demand; 0 if none */
     double   seconds_device;   /* device time of the whole search, HIP events */
     double   seconds_enumerate;/* of which the enumeration kernel */
-    uint64_t candidates_visited;   /* candidates whose tests the enumeration kernel issued, counted
-                                      in whole 64-lane waves; the others were excluded in bulk: by
-                                      a lane's latency or capacity bound holding for a whole wave.
-                                      At most the sum of `evaluated`, rounded up to whole waves */
+    uint64_t candidates_visited;   /* candidates whose tests the enumeration kernel issued.  Bounds
+                                      on: counted in whole 64-lane waves and whole quads of the
+                                      innermost task's stream (padding included), the rest of the
+                                      space was excluded in bulk.  Bounds off: the sum of `evaluated` */
 } jsv_summary;
 
 /*

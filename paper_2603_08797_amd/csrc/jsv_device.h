@@ -32,6 +32,7 @@ constexpr uint32_t F_TRUNCATED = 1u;        // cap thinning dropped a choice
 constexpr uint32_t F_WIDE      = 2u;        // enumerated with 64-bit keys (32-bit fast path did not fit)
 constexpr uint32_t F_OVERFLOW  = 1u << 8;   // replicas, cost or key do not fit
 constexpr uint32_t F_EMPTY     = 1u << 9;   // some task has no surviving choice
+constexpr uint32_t F_CUT       = 1u << 10;  // bounds on: no candidate fits S_avail, nothing was enumerated
 
 // One surviving choice of one task at one demand level.
 struct __attribute__((aligned(32))) Entry {
@@ -167,7 +168,8 @@ struct SummaryRec {
     uint32_t any_flags;       // OR of all instance flags
     unsigned long long next_tile;   // work counter of the enumeration kernel
     uint32_t plan_done;       // plan blocks finished
-    uint32_t pad;
+    uint32_t bounded;         // 1: the enumeration kernel with bounds does the work, 0: the plain one
+                              //    (set by the scan: bounds only pay when a block sees many tiles)
     unsigned long long visited;     // entries of the innermost position that waves went through
 };
 

@@ -547,7 +547,11 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     std::memcpy(&sr, pin_out + sizeof(jsv::ResultRec) * n, sizeof sr);
     if (sr.any_flags & jsv::F_OVERFLOW) return JSV_E_OVERFLOW;
     std::memcpy(out, pin_out, sizeof(jsv::ResultRec) * n);
-    for (uint32_t k = 0; k < n; ++k) out[k].flags &= (jsv::F_TRUNCATED | jsv::F_WIDE);
+    uint64_t enumerated = 0;                        // candidates of the instances that were enumerated at all
+    for (uint32_t k = 0; k < n; ++k) {
+        if (!(out[k].flags & jsv::F_CUT)) enumerated += out[k].evaluated;
+        out[k].flags &= (jsv::F_TRUNCATED | jsv::F_WIDE);
+    }
     if (summary) {
         float ms_all = 0.f, ms_enum = 0.f;
         HIP_TRY(ctx, hipEventElapsedTime(&ms_all, ctx->ev[0], ctx->ev[3]));
@@ -556,7 +560,8 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
         summary->max_demand_mrps = sr.max_demand;
         summary->seconds_device = ms_all * 1e-3;
         summary->seconds_enumerate = ms_enum * 1e-3;
-        summary->candidates_visited = (uint64_t)sr.visited * 64u;
+        if (ctx->bounds && sr.bounded) summary->candidates_visited = (uint64_t)sr.visited * 64u;
+        else summary->candidates_visited = enumerated;     // the plain kernel issues every candidate's tests
     }
     return JSV_OK;
 }

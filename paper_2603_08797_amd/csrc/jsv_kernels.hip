@@ -590,6 +590,8 @@ __device__ __forceinline__ uint32_t tiles_per_ticket(uint64_t total_tiles, uint3
 }
 
 // ---- plan -------------------------------------------------------------------------------
+constexpr uint32_t BOUNDS_MIN_TILES_PER_BLOCK = 32;
+
 // Exclusive scan of the tile counts over the instances, total, counters reset; run by
 // the last plan block to finish.
 __device__ void scan_tiles(const Plan& pl, uint64_t* s_sum)
@@ -611,6 +613,9 @@ __device__ void scan_tiles(const Plan& pl, uint64_t* s_sum)
         pl.summary->next_tile = (unsigned long long)pl.grid * tiles_per_ticket(run, pl.grid);
         pl.summary->any_flags = 0;
         pl.summary->visited = 0;
+        // A cost bound found in one tile helps the tiles that start after it: with only a few
+        // tiles per block everything runs at once and the bookkeeping would be pure overhead.
+        pl.summary->bounded = (pl.bounds && run >= (uint64_t)pl.grid * BOUNDS_MIN_TILES_PER_BLOCK) ? 1u : 0u;
         pl.summary->best_level = -1;
         pl.summary->max_demand = 0;
     }
@@ -679,6 +684,15 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         if (over) { space = 0; atomicOr(&in->flags, F_OVERFLOW); }
         in->space = space;
         in->idx_bits = idx_bits;
+        // Eq. 8 for the whole instance: if even the cheapest entry of every task together exceeds
+        // S_avail, no candidate fits and nothing needs to be enumerated (bounds on only).
+        bool none_fits = false;
+        if (pl.bounds && g->capacity != 0 && space != 0) {
+            uint64_t least = 0;
+            for (uint32_t t = 0; t < T; ++t) least += s_mincost[t];
+            none_fits = least > g->capacity;
+            if (none_fits) atomicOr(&in->flags, F_CUT);
+        }
 
         // how many leading positions a lane loops over, and the tile geometry
         uint32_t Kp[MAXT];
@@ -726,7 +740,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             }
         }
         uint32_t chunk = 1, n_chunks = 0, n_groups = 0;
-        if (space != 0) {
+        if (space != 0 && !none_fits) {
             // extent of the outermost in-lane loop: digits, or quads when it is the stream itself
             const bool stream = use32 && n_in == 1;
             uint64_t inner = stream ? 4 : 1;
@@ -911,7 +925,7 @@ __device__ __forceinline__ void loop_x64(const LaneState& s, const Uniforms& U, 
         if ((s.key >> U.idx_bits) + U.min_x_cost > U.bound) thr = 0;    // too costly whatever position 0 takes
         if (__builtin_amdgcn_ballot_w64(thr >= U.min_x_lat) == 0) return;   // no lane of the wave has a candidate here
     }
-    visits += hi - lo;
+    if constexpr (BOUNDS) visits += hi - lo;
     const double cx = s.hin[0];
     const Entry JSV_CONST* tx = U.tab[0];
     for (uint32_t d = lo; d < hi; ++d) {
@@ -954,7 +968,7 @@ __device__ __forceinline__ void loop_x32(const LaneState& s, const Uniforms& U, 
         alive = __builtin_amdgcn_ballot_w64((s.smax <= U.sloq) & (thr >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
     } else alive = __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
     if (BOUNDS && alive == 0) return;
-    visits += (qhi - qlo) * 4u;
+    if constexpr (BOUNDS) visits += (qhi - qlo) * 4u;
     uint32_t m = 0xFFFFFFFFu;
     double t;
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -1059,7 +1073,7 @@ __device__ __forceinline__ void loop_x32_mix(const LaneState& s, const Uniforms&
 #else
     (void)thr; (void)t; (void)qlo; (void)qhi; (void)full; (void)alive;
 #endif
-    visits += (pos - qlo * 64u) / 16u;
+    if constexpr (BOUNDS) visits += (pos - qlo * 64u) / 16u;
     const uint32_t cand = __builtin_elementwise_add_sat(s.k32, m);   // stays 0xFFFFFFFF if none
     best32 = best32 < cand ? best32 : cand;
 }
@@ -1076,7 +1090,7 @@ __device__ __forceinline__ void loop_x64_obj(const LaneState& s, const Uniforms&
         if ((s.key >> U.idx_bits) + U.min_x_cost > U.bound) thr = 0;
         if (__builtin_amdgcn_ballot_w64(thr >= U.min_x_lat) == 0) return;
     }
-    visits += hi - lo;
+    if constexpr (BOUNDS) visits += hi - lo;
     const double cx = s.hin[0];
     const Entry JSV_CONST* tx = U.tab[0];
     for (uint32_t d = lo; d < hi; ++d) {
@@ -1121,7 +1135,7 @@ __device__ __forceinline__ void loop_x32_obj(const LaneState& s, const Uniforms&
         alive = __builtin_amdgcn_ballot_w64((s.smax <= U.sloq) & (thr >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
     } else alive = __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
     if (BOUNDS && alive == 0) return;
-    tb.visits += (qhi - qlo) * 4u;
+    if constexpr (BOUNDS) tb.visits += (qhi - qlo) * 4u;
     const Quad JSV_CONST* q = U.quads;
     uint32_t m = 0xFFFFFFFFu;
     double t = 0.0;
@@ -1315,7 +1329,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     if constexpr (NIN == 3) loop_z<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
     else if constexpr (NIN == 2) loop_y<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
     else loop_x<W32, MODE, BOUNDS>(st, U, lo, hi, full, best, tb);
-    visited += tb.visits;
+    if constexpr (BOUNDS) visited += tb.visits;
 
     if constexpr (W32) {
         // the lane's 32-bit winner of this tile -> its full (cost, index) key
@@ -1374,6 +1388,8 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     const Instance JSV_CONST* insts = as_uniform((const Instance*)pl.inst);
     const Graph JSV_CONST* graphs = as_uniform(pl.graphs);
     const uint64_t total = as_uniform((const SummaryRec*)pl.summary)->total_tiles;
+    // both variants are launched when bounds are on; the scan has chosen which one works
+    if ((as_uniform((const SummaryRec*)pl.summary)->bounded != 0) != BOUNDS) return;
     const uint32_t tk = pl.t_max * pl.k_max;
 
     uint32_t cur = 0xFFFFFFFFu;     // instance whose tables are in LDS
@@ -1381,6 +1397,7 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     Best best;
     best.key = NO_KEY; best.obj = -__builtin_inf();
     uint64_t visited = 0;           // wave-uniform
+    uint32_t bound_seen = 0xFFFFFFFFu;      // cost bound of instance `cur` as last read or lowered by this wave
     const uint32_t batch = tiles_per_ticket(total, gridDim.x);
     uint64_t tile = (uint64_t)blockIdx.x * batch;         // a block's first ticket is its own index,
     uint64_t tile_end = tile + batch;                     // later ones come from the counter
@@ -1408,6 +1425,9 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
             __syncthreads();
             cur = scan;
             best.key = NO_KEY; best.obj = -__builtin_inf();
+            if constexpr (BOUNDS)
+                bound_seen = (uint32_t)__builtin_amdgcn_readfirstlane(
+                    (int)__hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         }
         const Instance JSV_CONST* in = insts + cur;
         const Graph JSV_CONST* g = graphs + in->problem;
@@ -1418,11 +1438,14 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const uint32_t n_chunks = in->n_chunks;
         const uint32_t chunk_id = (uint32_t)(local % n_chunks);
         const uint64_t group = local / n_chunks;
-        // the instance's cost bound as it stands now; a stale (higher) value only excludes less
-        uint32_t bound = 0xFFFFFFFFu;
-        if constexpr (BOUNDS)
-            bound = (uint32_t)__builtin_amdgcn_readfirstlane(
-                (int)__hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        // The tile works with the instance's cost bound as this wave knows it; a stale (higher)
+        // value only excludes less.  What other blocks have made of it meanwhile is fetched now and
+        // looked at after the tile, so that nobody waits for the load.
+        const uint32_t bound = bound_seen;
+        uint32_t fresh = 0xFFFFFFFFu;
+        if constexpr (BOUNDS) fresh = __hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint64_t key_before = best.key;
+        const double obj_before = best.obj;
         if (in->use32) {
             switch (in->n_in) {
             case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
@@ -1436,23 +1459,31 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
             default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
             }
         }
-        if constexpr (BOUNDS && MODE != MODE_OBJ) {
-            // a candidate that meets both SLOs and costs less than the bound lowers it for every
-            // block working on this instance (cost modes: nothing costlier can be the answer)
-            const uint32_t c = best.key == NO_KEY ? 0xFFFFFFFFu : (uint32_t)(best.key >> in->idx_bits);
-            const uint32_t wc = (uint32_t)wave_min((uint64_t)c);
-            if (wc < bound && (threadIdx.x & 63u) == 0) atomicMin(pl.bound + cur, wc);
-        }
-        if constexpr (BOUNDS && MODE == MODE_OBJ) {
-            // Eq. 14: A_obj <= 1, so a candidate of cost c scores at most alpha - beta*c.  With an
-            // objective o already reached, nothing costlier than (alpha - o)/beta can match it;
-            // one unit of slack keeps the test clear of rounding and of equal objectives.
-            const Best wb = wave_best(best);
-            if (wb.key != NO_KEY && in->beta > 1e-9 * (in->alpha + 1.0)) {     // else rounding could reach a unit of cost
-                const double lim = (in->alpha - wb.obj) / in->beta;
-                if (lim >= 0.0 && lim < 2147483000.0) {
-                    const uint32_t wc = (uint32_t)lim + 1u;
-                    if (wc < bound && (threadIdx.x & 63u) == 0) atomicMin(pl.bound + cur, wc);
+        if constexpr (BOUNDS) {
+            const uint32_t other = (uint32_t)__builtin_amdgcn_readfirstlane((int)fresh);
+            bound_seen = other < bound_seen ? other : bound_seen;
+            // Did a lane of this wave find something better in this tile?  Then the bound may drop
+            // for every block working on the instance.
+            const bool improved = __builtin_amdgcn_ballot_w64((best.key != key_before) | (best.obj != obj_before)) != 0;
+            if (improved) {
+                uint32_t wc = 0xFFFFFFFFu;
+                if constexpr (MODE != MODE_OBJ) {
+                    // cost modes: nothing costlier than a candidate that meets both SLOs can be the answer
+                    const uint32_t c = best.key == NO_KEY ? 0xFFFFFFFFu : (uint32_t)(best.key >> in->idx_bits);
+                    wc = (uint32_t)wave_min((uint64_t)c);
+                } else {
+                    // Eq. 14: A_obj <= 1, so a candidate of cost c scores at most alpha - beta*c.  With an
+                    // objective o already reached, nothing costlier than (alpha - o)/beta can match it;
+                    // one unit of slack keeps the test clear of rounding and of equal objectives.
+                    const Best wb = wave_best(best);
+                    if (wb.key != NO_KEY && in->beta > 1e-9 * (in->alpha + 1.0)) {     // else rounding could reach a unit of cost
+                        const double lim = (in->alpha - wb.obj) / in->beta;
+                        if (lim >= 0.0 && lim < 2147483000.0) wc = (uint32_t)lim + 1u;
+                    }
+                }
+                if (wc < bound_seen) {
+                    bound_seen = wc;
+                    if ((threadIdx.x & 63u) == 0) atomicMin(pl.bound + cur, wc);
                 }
             }
         }
@@ -1460,7 +1491,8 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     if (cur != 0xFFFFFFFFu) {
         flush_block<OBJ>(pl, cur, best, s_red, s_red_obj);
     }
-    if ((threadIdx.x & 63u) == 0 && visited != 0) atomicAdd(&pl.summary->visited, (unsigned long long)visited);
+    if constexpr (BOUNDS)       // (the plain enumeration visits everything: the host reports the space)
+        if ((threadIdx.x & 63u) == 0 && visited != 0) atomicAdd(&pl.summary->visited, (unsigned long long)visited);
 }
 
 // ---- scoring of one assignment (finalize and eval) -----------------------------------------
@@ -1641,22 +1673,36 @@ static EnumerateFn enumerate_entry(int mode, bool bounds)
 
 int enumerate_mode(bool objective, bool mixtures) { return objective ? MODE_OBJ : mixtures ? MODE_MIX : MODE_COST; }
 
-// Blocks of the enumeration kernel that are resident per CU with this much LDS.
+// Blocks of the enumeration kernel that are resident per CU with this much LDS; with bounds
+// on, the smaller figure of the two variants that launch_enumerate sends out.
 hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, int mode, bool bounds, int* blocks)
 {
     const size_t lds = enumerate_lds_bytes(t_max, k_max);
-    const void* fn = (const void*)enumerate_entry(mode, bounds);
-    if (lds > 32 * 1024) {      // beyond the default dynamic limit: ask for it explicitly
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    int least = 0;
+    for (int b = 0; b <= (bounds ? 1 : 0); ++b) {
+        const void* fn = (const void*)enumerate_entry(mode, b != 0);
+        if (lds > 32 * 1024) {      // beyond the default dynamic limit: ask for it explicitly
+            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        int n = 0;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, TILE_LANES, lds);
         if (e != hipSuccess) return e;
+        least = (b == 0 || n < least) ? n : least;
     }
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, fn, TILE_LANES, lds);
+    *blocks = least;
+    return hipSuccess;
 }
 
 hipError_t launch_enumerate(const Plan& pl, hipStream_t stream)
 {
-    const EnumerateFn fn = enumerate_entry(enumerate_mode(pl.objective != 0, pl.mix != 0), pl.bounds != 0);
-    hipLaunchKernelGGL(fn, dim3(pl.grid), dim3(TILE_LANES), enumerate_lds_bytes(pl.t_max, pl.k_max), stream, pl);
+    // With bounds on, both variants go out and the one the scan did not choose returns at once
+    // (the choice depends on the tile count, which only the device knows at this point).
+    const int mode = enumerate_mode(pl.objective != 0, pl.mix != 0);
+    const size_t lds = enumerate_lds_bytes(pl.t_max, pl.k_max);
+    hipLaunchKernelGGL(enumerate_entry(mode, false), dim3(pl.grid), dim3(TILE_LANES), lds, stream, pl);
+    if (pl.bounds)
+        hipLaunchKernelGGL(enumerate_entry(mode, true), dim3(pl.grid), dim3(TILE_LANES), lds, stream, pl);
     return hipGetLastError();
 }
 

@@ -118,3 +118,42 @@ def test_batch_validation_reports_the_offending_problem(ctx):
     with pytest.raises(jsv.JsvError) as e:
         ctx.load_batch(w.problems, w.searches)
     assert e.value.code == jsv.E_CYCLE and "problem 4" in str(e.value)
+
+
+def test_factor_arguments_and_state(ctx):
+    pb, _ = W.tiny_random(1, T=3)
+    assert code(ctx.set_factors, None) == jsv.E_STATE                        # nothing loaded
+    ctx.load_profile(pb.T, pb.V, pb.P, pb.B, pb.units, pb.batch, pb.latency_us, pb.thr_mrps, pb.accuracy)
+    ctx.set_dag(3, [], [], [1000] * 3, 0, 2)
+    ctx.E = 0
+    with pytest.raises(ValueError):
+        ctx.set_factors(np.ones((1, pb.V)))                                  # shape must be [E][V]
+    lib = jsv.load_library()
+    one = np.full((1, pb.V), 1000, dtype=np.uint32)
+    assert lib.jsv_set_factors(ctx._h, one.ctypes.data) == jsv.E_BADARG      # a graph without edges
+    ctx.set_dag(3, [0, 1], [1, 2], [1000] * 3, 0, 2)
+    f = np.full((2, pb.V), 1500, dtype=np.uint32)
+    ctx.set_factors(f)
+    for bad in (0, 1_000_001):
+        g = f.copy(); g[1, 0] = bad
+        assert code(ctx.set_factors, g) == jsv.E_BADARG
+    ctx.set_factors(None)
+    # the full index must fit 64 bits
+    big = W.xr8().problems[0]                                                # 240^8 < 2^64: accepted
+    ctx.load(big)
+    ctx.set_factors(np.full((big.E, big.V), 1000, dtype=np.uint32))
+    wide = np.ones((16, 2, 32, 32), dtype=np.uint32)                         # 2048^16 candidates
+    ctx.load_profile(16, 2, 32, 32, np.ones(32), np.ones(32), wide * 1000, wide * 1000, np.full((16, 2), 0.9))
+    ctx.set_dag(16, [0], [1], [1000] * 16, 0, 2)
+    assert code(ctx.set_factors, np.full((1, 2), 1000, dtype=np.uint32)) == jsv.E_OVERFLOW
+
+
+def test_mode_switches_need_no_device(ctx):
+    ctx.set_bounds(False)
+    ctx.set_bounds(True)
+    ctx.set_mixtures(True)
+    pb, se = W.tiny_mixture(3)
+    ctx.load(pb)
+    # mixture mode checks its own bounds on the prune cap before anything touches the GPU
+    assert code(ctx.search, se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 1) in (jsv.E_BADARG, jsv.E_DEVICE)
+    ctx.set_mixtures(False)
