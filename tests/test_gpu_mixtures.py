@@ -127,3 +127,50 @@ def test_argument_and_state_errors(ctx):
             assert g_.choice2 == [0xFFFF] * pb.T and g_.replicas2 == [0] * pb.T
     finally:
         ctx.set_mixtures(True)
+
+
+def test_xr8_full_size_winner_properties(ctx):
+    """8 tasks, 240 tuples each, cap 20 (20^8 candidates per level): too large for the oracle's
+    search, so the winners are checked for what must hold at any size: every task's option is a
+    valid minimal mixture, and cost, latency and accuracy recomputed from the tables (exact
+    rationals, tests/pyref.py) are the reported ones and meet the SLOs and S_avail."""
+    from fractions import Fraction
+    from pyref import PyRef
+    w = workloads.xr8()
+    pb, se = w.problems[0], w.searches[0]
+    ref = PyRef(pb)
+    levels = se.demand_mrps[[0, 9, 18, 27, 31, 40]]
+    ctx.load(pb)
+    res, summ = ctx.search(levels, se.slo_latency_us, se.slo_accuracy, 20)
+    assert any(r.feasible for r in res) and not res[-1].feasible
+    mixed = 0
+    for D, r in zip(levels.tolist(), res):
+        if not r.feasible:
+            continue
+        lat_t, acc_t, cost = [], [], 0
+        for t in range(pb.T):
+            need = D * int(pb.mult_milli[t])
+            c1, c2, m1, m2 = r.choice[t], r.choice2[t], r.replicas[t], r.replicas2[t]
+            h1 = 1000 * int(ref.thr[t][c1])
+            a1 = ref.accF[t][ref.variant(c1)]
+            u1 = int(pb.units[ref.part(c1)])
+            if c2 == 0xFFFF:
+                assert m2 == 0 and m1 == max(1, -(-need // h1))
+                lat_t.append(int(ref.lat[t][c1])); acc_t.append(a1); cost += m1 * u1
+            else:
+                mixed += 1
+                h2 = 1000 * int(ref.thr[t][c2])
+                assert c1 < c2 and m1 >= 1 and m2 >= 1
+                assert m1 * h1 + m2 * h2 >= need > max((m1 - 1) * h1 + m2 * h2, m1 * h1 + (m2 - 1) * h2)
+                lat_t.append(max(int(ref.lat[t][c1]), int(ref.lat[t][c2])))
+                acc_t.append((m1 * h1 * a1 + m2 * h2 * ref.accF[t][ref.variant(c2)]) / (m1 * h1 + m2 * h2))
+                cost += m1 * u1 + m2 * int(pb.units[ref.part(c2)])
+        fin = {}
+        for t in ref.order:
+            fin[t] = lat_t[t] + max([fin[p] for p in ref.preds[t]], default=0)
+        latency = ref.q * max(fin[s] for s in ref.sinks)
+        acc = ref._acc_values(acc_t) / ref.amax
+        assert (r.cost, r.latency_us) == (cost, latency)
+        assert abs(r.accuracy - float(acc)) <= 1e-12 * float(acc)
+        assert latency <= se.slo_latency_us and acc >= Fraction(float(se.slo_accuracy)) and cost <= pb.capacity_units
+    assert mixed > 0
