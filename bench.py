@@ -40,8 +40,8 @@ UNSHARED_OPS_PER_CANDIDATE = 11
 # against a 1 GiB copy (profiles/enumerate_kernel_xr8_hbm_traffic.md); known only for the
 # default workload in cost mode.
 # key: workload, seed, objective mode, mixture mode, bounds
-MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (3655 + 11633) * 1024,
-                          ("xr8", 0, False, False, True): (15843 + 16139) * 1024}
+MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (3641 + 11411) * 1024,
+                          ("xr8", 0, False, False, True): (15069 + 14636) * 1024}
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one full-rate VALU lane-op per lane per cycle
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
@@ -148,6 +148,8 @@ def main():
                          "exclude in bulk, as the headline.  Without this flag the headline is the plain "
                          "enumeration (the tests of every candidate are issued) and the bounded search is "
                          "timed as a second leg, reported under with_bounds; results are the same")
+    ap.add_argument("--plain-only", action="store_true",
+                    help="skip the second, bounded leg (for profiles of the plain enumeration alone)")
     ap.add_argument("--mixtures", action="store_true",
                     help="let a task run two tuples side by side (Eq. 9, 10); needs a pruned single-system workload")
     ap.add_argument("--objective", action="store_true",
@@ -212,7 +214,7 @@ def main():
         torch.cuda.synchronize()
 
     with_bounds = None
-    if not args.bounds:
+    if not args.bounds and not args.plain_only:
         # second leg: the same steps with the bounds on (what a caller gets by default)
         j.set_bounds(True)
         for _ in range(args.warmup):
