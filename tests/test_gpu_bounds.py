@@ -51,6 +51,17 @@ def test_xr8_small_cap_cuts_most_of_the_sweep(ctx):
     assert on < off // 2          # the upper half of the sweep cannot fit S_avail, the lower half has cheap answers
 
 
+def test_xr8_at_the_benchmark_size(ctx):
+    """cap 20 (20^8 candidates per level), the configuration bench.py times: a few levels from
+    both sides of the feasibility edge, plain enumeration against the bounded search."""
+    w = workloads.xr8()
+    pb, se = w.problems[0], w.searches[0]
+    levels = se.demand_mrps[[0, 13, 26, 31, 32, 45, 63]]
+    ctx.load(pb)
+    on, off, total = both(ctx, lambda: ctx.search(levels, se.slo_latency_us, se.slo_accuracy, se.prune_cap))
+    assert total == 7 * 20 ** 8 and on < off // 4
+
+
 @pytest.mark.parametrize("seed", range(40))
 def test_tiny_random(ctx, seed):
     pb, se = workloads.tiny_random(9000 + seed)
