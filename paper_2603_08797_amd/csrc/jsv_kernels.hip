@@ -1142,7 +1142,7 @@ __device__ __forceinline__ void loop_x32_obj(const LaneState& s, const Uniforms&
     uint64_t ok = 0;
     for (uint32_t j = qlo; j < qhi; ++j) {
         if (q[j].newgrp != 0) {
-            fold_variant(s, U, m, t, tb);
+            if (__builtin_amdgcn_ballot_w64(m != 0xFFFFFFFFu) != 0) fold_variant(s, U, m, t, tb);   // some lane has a candidate
             t = __builtin_fma(q[j].acc, s.hin[0], s.sacc);
             ok = alive & __builtin_amdgcn_ballot_w64(t >= U.slo_raw);
             m = 0xFFFFFFFFu;
@@ -1170,7 +1170,7 @@ __device__ __forceinline__ void loop_x32_obj(const LaneState& s, const Uniforms&
         (void)thr; (void)full; (void)ok;
 #endif
     }
-    fold_variant(s, U, m, t, tb);
+    if (__builtin_amdgcn_ballot_w64(m != 0xFFFFFFFFu) != 0) fold_variant(s, U, m, t, tb);
 }
 
 // What the enumeration kernel is instantiated for.
