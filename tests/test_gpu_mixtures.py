@@ -174,3 +174,61 @@ def test_xr8_full_size_winner_properties(ctx):
         assert abs(r.accuracy - float(acc)) <= 1e-12 * float(acc)
         assert latency <= se.slo_latency_us and acc >= Fraction(float(se.slo_accuracy)) and cost <= pb.capacity_units
     assert mixed > 0
+
+
+def crafted(T=2, V=2, P=2, B=1, units=(1, 2), thr=50_000, lat=5000, capacity=20, mult=1000, edges=((0, 1),)):
+    """Small problem with regular tables: every tuple serves thr mrps per unit, latencies grow with the tuple id."""
+    C = V * P * B
+    la = np.zeros((T, V, P, B), dtype=np.uint32)
+    th = np.zeros((T, V, P, B), dtype=np.uint32)
+    for t in range(T):
+        for v in range(V):
+            for p in range(P):
+                for b in range(B):
+                    c = (v * P + p) * B + b
+                    la[t, v, p, b] = lat * (1 + c)
+                    th[t, v, p, b] = thr * units[p] * (1 + v)
+    acc = np.array([[0.6 + 0.3 * v / max(V - 1, 1) for v in range(V)] for _ in range(T)], dtype=np.float64)
+    src = np.array([e[0] for e in edges if e[1] < T], dtype=np.uint16)
+    dst = np.array([e[1] for e in edges if e[1] < T], dtype=np.uint16)
+    return workloads.Problem(T=T, V=V, P=P, B=B, units=np.array(units[:P], dtype=np.uint32),
+                             batch=np.array([1 << b for b in range(B)], dtype=np.uint32), latency_us=la, thr_mrps=th,
+                             accuracy=acc, src=src, dst=dst, mult_milli=np.array([mult] * T, dtype=np.uint32),
+                             capacity_units=capacity, queue_factor=2)
+
+
+@pytest.mark.parametrize("case", ["one_tuple", "capacity_one", "one_replica", "nothing_fast_enough", "nothing_fits",
+                                  "many_replicas"])
+def test_edge_cases(ctx, case):
+    slo_l, slo_a, D, cap = 400_000, 0.7, [300_000], 16
+    if case == "one_tuple":                       # no pair to mix
+        pb = crafted(V=1, P=1, units=(1,))
+    elif case == "capacity_one":                  # only single replicas of 1-unit tuples fit, and none carries the demand
+        pb = crafted(capacity=1)
+    elif case == "one_replica":                   # every tuple carries the demand alone: no mixture exists
+        pb, D = crafted(), [20_000]
+    elif case == "nothing_fast_enough":
+        pb, slo_l = crafted(), 1000
+    elif case == "nothing_fits":
+        pb, D = crafted(capacity=3), [2_000_000]
+    else:                                         # hundreds of replicas per tuple, thousands of splits per pair
+        pb, D, cap = crafted(thr=1000, capacity=2000, T=1, edges=()), [700_000], 40
+    se = workloads.Search(np.array(D, dtype=np.uint32), slo_l, slo_a, cap)
+    want = check(ctx, pb, se, cap)
+    if case in ("nothing_fast_enough", "nothing_fits", "capacity_one"):
+        assert not want[0].feasible
+    if case == "one_replica":
+        assert want[0].feasible and want[0].choice2 == [0xFFFF] * pb.T
+
+
+def test_too_many_replicas_is_an_overflow_on_both_sides(ctx):
+    pb = crafted(thr=1, capacity=60000, T=1, edges=())           # 1 mrps per unit: 70000 replicas of a tuple alone
+    o = oracle.Oracle.from_problem(pb)
+    o.set_mixtures(True)
+    with pytest.raises(oracle.OracleError) as e:
+        o.search([70_000], 400_000, 0.0, 8)
+    assert e.value.code == -3
+    ctx.load(pb)
+    with pytest.raises(jsv.JsvError) as e:
+        ctx.search([70_000], 400_000, 0.0, 8)
+    assert e.value.code == jsv.E_OVERFLOW
