@@ -140,3 +140,26 @@ def test_state_and_argument_errors(ctx):
     got = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 0)[0]
     for w_, g_ in zip(want, got):
         same(g_, w_)
+
+
+def test_demand_beyond_the_flow_range_is_an_overflow_on_both_sides(ctx):
+    with open(os.path.join(HERE, "golden", "p1_two_task_chain.json")) as f:
+        g = json.load(f)
+    lat = np.array(g["latency_us"], dtype=np.uint32).reshape(g["T"], g["V"], g["P"], g["B"])
+    acc = np.array(g["accuracy"], dtype=np.float64)
+    o = oracle.Oracle(g["T"], g["V"], g["P"], g["B"], g["units"], g["batch"], lat, None, acc, [0], [1],
+                      g["mult_milli"], 0, g["queue_factor"])
+    o.set_factors([[1_000_000, 1_000_000]])
+    with pytest.raises(oracle.OracleError) as e:
+        o.search([4_000_000_000], 100000, 0.0, 0)
+    assert e.value.code == -3
+    ctx.load_profile(g["T"], g["V"], g["P"], g["B"], g["units"], g["batch"], lat, None, acc)
+    ctx.set_dag(g["T"], [0], [1], g["mult_milli"], 0, g["queue_factor"])
+    ctx.set_factors([[1_000_000, 1_000_000]])
+    with pytest.raises(jsv.JsvError) as e:
+        ctx.search([4_000_000_000], 100000, 0.0, 0)
+    assert e.value.code == jsv.E_OVERFLOW
+    # a demand just inside the range is searched on both sides
+    want = o.search([17_000], 100000, 0.0, 0)[0][0]
+    got = ctx.search([17_000], 100000, 0.0, 0)[0][0]
+    same(got, want)
