@@ -7,6 +7,10 @@
  * and the number of GPU partition units is minimal.  This is the optimisation of
  * Section 3.2 of the paper (Eq. 1-14) restricted to one tuple per task and to
  * the cost term of the objective, solved by exhaustive enumeration on the GPU.
+ * Switches widen it: the paper's full objective (jsv_set_objective), per-variant
+ * multiplicative factors (jsv_set_factors), two tuples per task (jsv_set_mixtures),
+ * the search spaces of the paper's ablations (jsv_set_search_space); jsv_set_bounds
+ * and jsv_set_graph_mode change how the search runs, not what it returns.
  *
  * Conventions
  *   choice id      c = (v*P + p)*B + b            (variant slowest, batch fastest)
@@ -73,7 +77,8 @@ JSV_API const char* jsv_error_string(int code);
  * jsv_set_workspace lends `bytes` bytes at DEVICE pointer `device_ptr`
  * (256-byte aligned) until the next set call or jsv_destroy; NULL returns to
  * library-owned memory.  A lent buffer that is too small makes the search
- * return JSV_E_WORKSPACE.
+ * return JSV_E_WORKSPACE.  The size depends on the modes in force (factors,
+ * mixtures): ask after setting them; 0 means the request cannot be served.
  */
 JSV_API size_t jsv_workspace_bytes(const jsv_ctx* ctx, uint32_t n_levels, uint32_t prune_cap);
 JSV_API int    jsv_set_workspace(jsv_ctx* ctx, void* device_ptr, size_t bytes);
