@@ -148,6 +148,8 @@ def main():
                          "exclude in bulk, as the headline.  Without this flag the headline is the plain "
                          "enumeration (the tests of every candidate are issued) and the bounded search is "
                          "timed as a second leg, reported under with_bounds; results are the same")
+    ap.add_argument("--prune-cap", type=int, default=None,
+                    help="override the workload's per-task prune cap (single-system workloads)")
     ap.add_argument("--plain-only", action="store_true",
                     help="skip the second, bounded leg (for profiles of the plain enumeration alone)")
     ap.add_argument("--mixtures", action="store_true",
@@ -164,6 +166,10 @@ def main():
     from paper_2603_08797_amd import jsv, workloads
 
     w = workloads.BENCH_WORKLOADS[args.workload](seed=args.seed)
+    if args.prune_cap is not None:
+        for se_ in w.searches:
+            se_.prune_cap = args.prune_cap
+        w.note += f", prune cap {args.prune_cap}"
     factors = w.meta.get("factor_milli")
     stream = torch.cuda.Stream(device=0)
     j = jsv.Jsv(device=0, stream=stream)
