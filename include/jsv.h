@@ -230,7 +230,9 @@ JSV_API int jsv_set_bounds(jsv_ctx* ctx, int on);
  * In mixture mode jsv_search needs 2 <= prune_cap <= JSV_MAX_CHOICES, 1 <= capacity_units <=
  * 65535 and at most 65536 replicas of any allowed tuple on its own (else JSV_E_BADARG /
  * JSV_E_OVERFLOW); it returns JSV_E_STATE together with per-variant factors, graph_informed =
- * 0, objective mode or batch mode, and so do jsv_eval_candidates and jsv_get_pruned.
+ * 0 or batch mode, and so do jsv_eval_candidates and jsv_get_pruned.  Objective mode works over
+ * the options too (every option has its own accuracy, so every candidate gets its own
+ * objective: the general, slower loop of the enumeration).
  */
 JSV_API int jsv_set_mixtures(jsv_ctx* ctx, int on);
 

@@ -1216,15 +1216,14 @@ double orc_accuracy_margin(const orc_model *m, double slo_accuracy)
 
 /*
  * Objective mode only: gap between the winner's objective and the best objective of any
- * feasible candidate that uses a different combination of variants (1e300 if there is
- * none, -1 if the level is infeasible).  Candidates with the winner's variants have exactly
+ * feasible candidate that uses a different combination of variants (mixture mode: of per-task
+ * accuracies; 1e300 if there is none, -1 if the level is infeasible).  Candidates with the winner's variants have exactly
  * its accuracy, so their order is decided by integer cost; only this gap is exposed to
  * floating-point rounding, and tests skip inputs where it is tiny.
  */
 int orc_objective_margin(const orc_model *m, uint32_t demand_mrps, uint32_t slo_latency_us,
                          double slo_accuracy, uint32_t cap, double *margin)
 {
-    if (m->mix) return ORC_E_ARG;
     if (m->fac) {
         orc_result r; double other;
         int rc = search_held(m, demand_mrps, slo_latency_us, slo_accuracy, cap, 1, &r, &other);
@@ -1246,7 +1245,11 @@ int orc_objective_margin(const orc_model *m, uint32_t demand_mrps, uint32_t slo_
             score_t s = score(&L, i, c);
             if (s.mask != 7) continue;
             int same = 1;
-            for (uint32_t t = 0; t < m->T; t++) if (variant_of(m, c[t]) != variant_of(m, cw[t])) same = 0;
+            for (uint32_t t = 0; t < m->T; t++) {
+                if (m->mix) {       /* c[] are digits: the same per-task accuracies give exactly the same A_obj */
+                    if (L.opt[t][c[t]].acc != L.opt[t][cw[t]].acc) same = 0;
+                } else if (variant_of(m, c[t]) != variant_of(m, cw[t])) same = 0;
+            }
             if (same) continue;
             double obj = m->alpha * s.acc - m->beta * (double)s.cost;
             if (obj > other) other = obj;

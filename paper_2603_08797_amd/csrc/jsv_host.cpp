@@ -808,7 +808,7 @@ JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_lev
     if (ctx->mix) {
         // Mixtures of two tuples: the options of a task live in a grid of (cost 0..S_avail) x
         // (latency classes <= C) cells per (level, task)
-        if (!hp.fac.empty() || !ctx->space_t || ctx->objective != 0) return JSV_E_STATE;
+        if (!hp.fac.empty() || !ctx->space_t) return JSV_E_STATE;
         if (prune_cap < 2 || prune_cap > JSV_MAX_CHOICES || hp.capacity == 0 || hp.capacity > 65535) return JSV_E_BADARG;
         const uint64_t cells = (uint64_t)(hp.capacity + 1) * hp.C;
         if (cells * hp.T * n_levels > ((uint64_t)1 << 32)) return JSV_E_WORKSPACE;      // 28 B per cell

@@ -724,7 +724,9 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             while (lb < 32 && (ranks - 1) >> lb) ++lb;
             uint32_t cb = 0;
             while (cb < 32 && cost_in >> cb) ++cb;
-            use32 = (ranks <= 0x7FFFFFFFull && lb + cb <= 31) ? 1u : 0u;
+            // (objective mode over mixtures: every entry has its own accuracy and so its own
+            // objective; only the general per-candidate loop handles that)
+            use32 = (ranks <= 0x7FFFFFFFull && lb + cb <= 31 && !(pl.mix && pl.objective)) ? 1u : 0u;
         }
         if (use32 && pl.mix) nq = (KX + 3) / 4;             // one stream in latency order
         else if (use32) {

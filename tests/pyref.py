@@ -344,8 +344,10 @@ class PyRef:
             lists.append(opts)
         return lists, truncated
 
-    def search_mix(self, D: int, slo_l: int, slo_a: float, cap: int, max_space: int = 300000):
-        """Returns (best or None, K, truncated, margin); best = (idx, cost, lat, acc, options)."""
+    def search_mix(self, D: int, slo_l: int, slo_a: float, cap: int, max_space: int = 300000, objective=None):
+        """Returns (best or None, K, truncated, margin); best = (idx, cost, lat, acc, options).
+        objective = (alpha, beta): the largest alpha*A_obj - beta*cost wins instead of the lowest
+        cost (then lower cost, then lower index), and a sixth field holds its exact value."""
         lists, truncated = self.mix_lists(D, slo_l, cap)
         K = [len(l) for l in lists]
         space = 1
@@ -373,8 +375,13 @@ class PyRef:
                 d = abs(acc - slo)
                 margin = d if margin is None or d < margin else margin
                 if lat <= slo_l and acc >= slo and (capu == 0 or cost <= capu):
-                    if best is None or (cost, idx) < (best[1], best[0]):
-                        best = (idx, cost, lat, acc, opts)
+                    if objective is None:
+                        if best is None or (cost, idx) < (best[1], best[0]):
+                            best = (idx, cost, lat, acc, opts)
+                    else:
+                        obj = Fraction(float(objective[0])) * acc - Fraction(float(objective[1])) * cost
+                        if best is None or (-obj, cost, idx) < (-best[5], best[1], best[0]):
+                            best = (idx, cost, lat, acc, opts, obj)
         return best, K, truncated, margin
 
     def search(self, D: int, slo_l: int, slo_a: float, cap: int):

@@ -23,16 +23,25 @@ def ctx():
     j.close()
 
 
-def check(ctx, pb, se, cap, levels=None, threads=16, margin=True):
+def check(ctx, pb, se, cap, levels=None, threads=16, margin=True, objective=None):
     D = se.demand_mrps if levels is None else se.demand_mrps[:levels]
     o = oracle.Oracle.from_problem(pb)
     o.set_mixtures(True)
     ctx.load(pb)
-    want, wbl, wmd = o.search(D, se.slo_latency_us, se.slo_accuracy, cap, threads=threads)
-    got, summ = ctx.search(D, se.slo_latency_us, se.slo_accuracy, cap)
+    if objective:
+        o.set_objective(1, *objective)
+        ctx.set_objective(1, *objective)
+    try:
+        want, wbl, wmd = o.search(D, se.slo_latency_us, se.slo_accuracy, cap, threads=threads)
+        got, summ = ctx.search(D, se.slo_latency_us, se.slo_accuracy, cap)
+    finally:
+        ctx.set_objective(0, 1.0, 0.035)
     skipped = 0
     for l, (w, g) in enumerate(zip(want, got)):
         if margin and o.mixture_margin(int(D[l]), se.slo_latency_us, se.slo_accuracy, cap) < 1e-9:
+            skipped += 1
+            continue
+        if objective and w.feasible and o.objective_margin(int(D[l]), se.slo_latency_us, se.slo_accuracy, cap) < 1e-9:
             skipped += 1
             continue
         same(g, w, f"level {l}")
@@ -71,6 +80,14 @@ def test_tiny_mixture(ctx, seed):
     check(ctx, pb, se, cap)
 
 
+@pytest.mark.parametrize("seed", range(40))
+def test_objective_over_mixtures(ctx, seed):
+    pb, se = workloads.tiny_mixture(3500 + seed)
+    if pb.capacity_units == 0:
+        pb = dataclasses.replace(pb, capacity_units=30)
+    check(ctx, pb, se, [4, 7, 12, 40][seed % 4], objective=(1.0, 0.035))
+
+
 def first(name, seed=0):
     w = workloads.BENCH_WORKLOADS[name](seed=seed)
     return w.problems[0], w.searches[0]
@@ -104,12 +121,6 @@ def test_argument_and_state_errors(ctx):
     for cap in (0, 1, 4096):
         with pytest.raises(jsv.JsvError):
             ctx.search(D, se.slo_latency_us, se.slo_accuracy, cap)
-    ctx.set_objective(1, 1.0, 0.035)
-    try:
-        with pytest.raises(jsv.JsvError):
-            ctx.search(D, se.slo_latency_us, se.slo_accuracy, 8)
-    finally:
-        ctx.set_objective(0, 1.0, 0.035)
     with pytest.raises(jsv.JsvError):
         ctx.get_pruned(int(D[0]), se.slo_latency_us, 8, 0)
     ctx.load(dataclasses.replace(pb, capacity_units=0))

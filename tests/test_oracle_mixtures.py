@@ -68,6 +68,26 @@ def small(seed, T=None):
     return pb, se, PyRef(pb)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_objective_with_mixtures_matches_brute_force(seed):
+    """Eq. 14 over options with their own accuracies (the paper's objective on the widened space)."""
+    pb, se, ref = small(400 + seed)
+    o = oracle.Oracle.from_problem(pb)
+    o.set_mixtures(True)
+    o.set_objective(1, 1.0, 0.035)
+    cap = [4, 6, 9, 12][seed % 4] if pb.T == 3 else [6, 12, 24, 40][seed % 4]
+    for D in se.demand_mrps.tolist():
+        want, K, tr, margin = ref.search_mix(D, se.slo_latency_us, se.slo_accuracy, cap, objective=(1.0, 0.035))
+        r = o.search([D], se.slo_latency_us, se.slo_accuracy, cap)[0][0]
+        assert bool(r.feasible) == (want is not None)
+        if want is None or (margin is not None and margin < 1e-9):
+            continue
+        if o.objective_margin(D, se.slo_latency_us, se.slo_accuracy, cap) < 1e-9:
+            continue
+        compare(r, want[:5], K, tr)
+        assert r.objective == pytest.approx(float(want[5]), rel=1e-12, abs=1e-12)
+
+
 def compare(r, want, K, truncated):
     ev = 1
     for k in K:
