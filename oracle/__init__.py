@@ -45,8 +45,11 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = C.CDLL(_LIB)
+        # JSV_ORACLE_LIBRARY: a differently built copy of the same source (the sanitizer test's)
+        alt = os.environ.get("JSV_ORACLE_LIBRARY")
+        if not alt:
+            build()
+        lib = C.CDLL(alt or _LIB)
         vp = C.c_void_p
         lib.orc_create.restype = C.c_int
         lib.orc_create.argtypes = [C.POINTER(vp), C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,

@@ -15,10 +15,11 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libjsv.so")
+# JSV_LIBRARY: a differently built copy of the same sources (the host-sanitizer test's build)
+LIB_PATH = os.environ.get("JSV_LIBRARY") or os.path.join(_HERE, "libjsv.so")
 
 MAX_TASKS = 16
-OK, E_NULL, E_BADARG, E_CYCLE, E_OVERFLOW, E_STATE, E_WORKSPACE, E_DEVICE = 0, -1, -2, -3, -4, -5, -6, -7
+OK, E_NULL, E_BADARG, E_CYCLE, E_OVERFLOW, E_STATE, E_WORKSPACE, E_DEVICE, E_INTERNAL = 0, -1, -2, -3, -4, -5, -6, -7, -8
 
 EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space", "jsv_set_factors", "jsv_set_mixtures", "jsv_set_bounds", "jsv_set_graph_mode",
            "jsv_workspace_bytes", "jsv_set_workspace", "jsv_load_profile", "jsv_set_dag",
