@@ -51,7 +51,9 @@ enum {
     JSV_E_OVERFLOW  = -4,   /* latency, cost or search-space size does not fit */
     JSV_E_STATE     = -5,   /* call order: search before profile/graph, T mismatch */
     JSV_E_WORKSPACE = -6,   /* caller-supplied workspace too small */
-    JSV_E_DEVICE    = -7    /* a HIP call failed; see jsv_last_hip_error */
+    JSV_E_DEVICE    = -7,   /* a HIP call failed; see jsv_last_hip_error */
+    JSV_E_INTERNAL  = -8    /* the enumeration's winner failed the rescoring of its latency or
+                               accuracy test: an inconsistency inside the library, never expected */
 };
 
 typedef struct jsv_ctx jsv_ctx;
@@ -78,7 +80,10 @@ JSV_API const char* jsv_error_string(int code);
  * (256-byte aligned) until the next set call or jsv_destroy; NULL returns to
  * library-owned memory.  A lent buffer that is too small makes the search
  * return JSV_E_WORKSPACE.  The size depends on the modes in force (factors,
- * mixtures): ask after setting them; 0 means the request cannot be served.
+ * mixtures): ask after setting them; 0 means the request cannot be served.  The size also
+ * depends on the number of compute units of the GPU (per-block partial results): before the
+ * context's first device call it is computed for 256 compute units, the MI355X figure, and for
+ * the device's own count afterwards.
  */
 JSV_API size_t jsv_workspace_bytes(const jsv_ctx* ctx, uint32_t n_levels, uint32_t prune_cap);
 JSV_API int    jsv_set_workspace(jsv_ctx* ctx, void* device_ptr, size_t bytes);
@@ -165,33 +170,6 @@ JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial
                                  int graph_informed);
 
 /*
- * Per-variant multiplicative factors F(t, v, t') (Section 3.2, Eq. 4 and 5) for the system
- * loaded with jsv_load_profile + jsv_set_dag.  factor_milli: host, [E][V] row-major in the
- * edge order given to jsv_set_dag, copied; entry [e][v] is the number of requests variant v
- * of the edge's tail sends along the edge per request it serves, in 1/1000ths, 1 ..
- * JSV_MAX_FACTOR_MILLI.  NULL returns to the fixed per-task multipliers.  A later
- * jsv_load_profile or jsv_set_dag drops the table.
- *
- * With factors set, the demand of a task without predecessors is demand * mult_t as before;
- * the demand of any other task is the sum over its incoming edges of the tail's demand times
- * the factor of the tail's chosen variant, floored per edge to whole micro-requests/s; its
- * mult_t only weighs paths in the accuracy (Eq. 12).  A demand of 2^44 micro-requests/s or more
- * makes the search return JSV_E_OVERFLOW.
- *
- * How a level is searched: every task with an outgoing edge whose factors differ between
- * variants is held to one variant, in all combinations; inside a combination all demands are
- * fixed and cost table, prune and search are the ordinary ones (prune_cap applies per
- * combination).  The level's result is the best over the combinations: cheapest, or in
- * objective mode largest objective then cheapest, then lowest full_index.  In the result,
- * index repeats full_index, evaluated and flags add up over the combinations.
- * levels * combinations may not exceed 65536 (jsv_search: JSV_E_BADARG).
- *
- * Returns JSV_E_STATE without a loaded profile and graph or in batch mode, JSV_E_BADARG for
- * a graph without edges or a factor out of range, JSV_E_OVERFLOW if C^T does not fit 64
- * bits.  While factors are set, jsv_eval_candidates and jsv_get_pruned return JSV_E_STATE,
- * and so does jsv_search with graph_informed = 0.
- */
-/*
  * Bounds in the enumeration (on by default).  A group of candidates that share all digits but
  * those of the innermost tasks is excluded as a whole when the digits it shares already break
  * the latency SLO (Eq. 3), when its remaining latency budget is below the fastest choice of
@@ -227,6 +205,12 @@ JSV_API int jsv_set_bounds(jsv_ctx* ctx, int on);
  * lists, index with task 0 as the fastest digit; full_index is UINT64_MAX; choice2 / replicas2
  * of the result name the second tuple.
  *
+ * This narrows the paper's space: Eq. 6 holds with slack too, and Eq. 10 weights accuracy by the
+ * provisioned throughput M*H, so a surplus replica of the more accurate tuple can be the
+ * cheapest way to meet Eq. 13 (or score higher under Eq. 14).  Splits with surplus replicas and
+ * mixtures of more than two tuples are not searched; the result is an upper bound on the cost
+ * of the best mixture.
+ *
  * In mixture mode jsv_search needs 2 <= prune_cap <= JSV_MAX_CHOICES, 1 <= capacity_units <=
  * 65535 and at most 65536 replicas of any allowed tuple on its own (else JSV_E_BADARG /
  * JSV_E_OVERFLOW); it returns JSV_E_STATE together with per-variant factors, graph_informed =
@@ -236,6 +220,33 @@ JSV_API int jsv_set_bounds(jsv_ctx* ctx, int on);
  */
 JSV_API int jsv_set_mixtures(jsv_ctx* ctx, int on);
 
+/*
+ * Per-variant multiplicative factors F(t, v, t') (Section 3.2, Eq. 4 and 5) for the system
+ * loaded with jsv_load_profile + jsv_set_dag.  factor_milli: host, [E][V] row-major in the
+ * edge order given to jsv_set_dag, copied; entry [e][v] is the number of requests variant v
+ * of the edge's tail sends along the edge per request it serves, in 1/1000ths, 1 ..
+ * JSV_MAX_FACTOR_MILLI.  NULL returns to the fixed per-task multipliers.  A later
+ * jsv_load_profile or jsv_set_dag drops the table.
+ *
+ * With factors set, the demand of a task without predecessors is demand * mult_t as before;
+ * the demand of any other task is the sum over its incoming edges of the tail's demand times
+ * the factor of the tail's chosen variant, floored per edge to whole micro-requests/s; its
+ * mult_t only weighs paths in the accuracy (Eq. 12).  A demand of 2^44 micro-requests/s or more
+ * makes the search return JSV_E_OVERFLOW.
+ *
+ * How a level is searched: every task with an outgoing edge whose factors differ between
+ * variants is held to one variant, in all combinations; inside a combination all demands are
+ * fixed and cost table, prune and search are the ordinary ones (prune_cap applies per
+ * combination).  The level's result is the best over the combinations: cheapest, or in
+ * objective mode largest objective then cheapest, then lowest full_index.  In the result,
+ * index repeats full_index, evaluated and flags add up over the combinations.
+ * levels * combinations may not exceed 65536 (jsv_search: JSV_E_BADARG).
+ *
+ * Returns JSV_E_STATE without a loaded profile and graph or in batch mode, JSV_E_BADARG for
+ * a graph without edges or a factor out of range, JSV_E_OVERFLOW if C^T does not fit 64
+ * bits.  While factors are set, jsv_eval_candidates and jsv_get_pruned return JSV_E_STATE,
+ * and so does jsv_search with graph_informed = 0.
+ */
 #define JSV_MAX_FACTOR_MILLI 1000000u
 JSV_API int jsv_set_factors(jsv_ctx* ctx, const uint32_t* factor_milli);
 
@@ -278,7 +289,12 @@ typedef struct {
  * equal cost.  All levels run in one pass on the context's stream; the call
  * returns after the results are in out[].
  *   demand_mrps[n_levels]  any order, each > 0
- *   slo_accuracy           threshold on A_obj, a fraction of the best achievable
+ *   slo_accuracy           threshold on A_obj, a fraction of the best achievable.  Eq. 13 is
+ *                          tested in fp64 as A_raw >= slo_accuracy * A_max with one fixed
+ *                          order of operations for A_raw and A_max, so 1.0 accepts exactly
+ *                          the assignments as accurate as the best one.  An assignment
+ *                          whose exact A_obj lies within a few ulp of the threshold may
+ *                          fall on either side of it
  *   prune_cap              0: exhaustive.  Otherwise >= 2V: each task keeps only
  *                          choices that can meet SLO_l at all and that no other
  *                          choice matches or beats on (latency, accuracy, cost);
@@ -286,10 +302,16 @@ typedef struct {
  *                          to floor(prune_cap/V) of them evenly spaced by latency
  *                          rank (fastest and cheapest always kept; sets flags bit0)
  *   out[n_levels], summary caller-allocated; summary may be NULL
- * Errors: JSV_E_NULL, JSV_E_STATE, JSV_E_BADARG (n_levels = 0, a zero demand,
- * prune_cap in (0, 2V)), JSV_E_OVERFLOW (queue_factor * T * max latency >= 2^32;
- * a cost >= 2^31; searched space and cost do not fit a 64-bit key together),
- * JSV_E_WORKSPACE, JSV_E_DEVICE.
+ * Errors: JSV_E_NULL; JSV_E_STATE (no profile or graph, batch loaded; per-variant
+ * factors or mixtures together with graph_informed = 0, mixtures together with
+ * factors); JSV_E_BADARG (n_levels = 0, a zero demand, NaN threshold, prune_cap in
+ * (0, 2V); with factors: levels * combinations > 65536; with mixtures: prune_cap
+ * outside [2, JSV_MAX_CHOICES], capacity_units outside [1, 65535]); JSV_E_OVERFLOW
+ * (queue_factor * sum of the tasks' largest latencies >= 2^32; a cost >= 2^31;
+ * searched space and cost do not fit a 64-bit key together; with factors a demand
+ * >= 2^44 micro-requests/s or a winner whose full_index does not fit; with mixtures
+ * more than 65535 replicas of one tuple); JSV_E_WORKSPACE (lent buffer too small;
+ * with mixtures also a cell grid beyond 2^32 cells); JSV_E_DEVICE; JSV_E_INTERNAL.
  */
 JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_levels,
                uint32_t slo_latency_us, double slo_accuracy, uint32_t prune_cap,

@@ -14,6 +14,19 @@
 // with w(p,s) the share of p among the predecessors of s and u(p) the share of
 // sink p among all sinks (both from the per-task demand multipliers).  Summed
 // over sources this is exactly sum_p f_p * prod_{t in p} a_t of Eq. 12.
+//
+// One order of fp64 operations, used wherever A_raw is formed (host: A_max; device: the
+// enumeration, the rescoring of the winner, jsv_eval_candidates), so that the same assignment
+// always yields the same bits and the accuracy test of Eq. 13 has one outcome:
+//   positions are visited from T-1 down to 0;
+//   sum_s w(p,s)*H(s) starts at +0.0 and takes the successors in DESCENDING position, one fma
+//     each:  hs = fma(w(p,s), H(s), hs);
+//   H(p) = a(p) * (u(p) or hs), one rounded product;
+//   A_raw starts at +0.0 and takes the sources in descending position, one rounded add each,
+//     except position 0 (always a source, always last), which joins as  fma(a(0), hs(0), A_raw);
+//   Eq. 13 is tested as  A_raw >= SLO_a * A_max  (the product rounded once, on the host).
+// Descending successor order is what lets a lane hoist the part of hs that comes from the
+// positions it holds fixed and add the looped positions (2, then 1) afterwards.
 #pragma once
 #include <stdint.h>
 
@@ -33,6 +46,7 @@ constexpr uint32_t F_WIDE      = 2u;        // enumerated with 64-bit keys (32-b
 constexpr uint32_t F_OVERFLOW  = 1u << 8;   // replicas, cost or key do not fit
 constexpr uint32_t F_EMPTY     = 1u << 9;   // some task has no surviving choice
 constexpr uint32_t F_CUT       = 1u << 10;  // bounds on: no candidate fits S_avail, nothing was enumerated
+constexpr uint32_t F_MISMATCH  = 1u << 11;  // the enumeration's winner failed the rescoring (internal error)
 
 // One surviving choice of one task at one demand level.
 struct __attribute__((aligned(32))) Entry {
@@ -173,36 +187,38 @@ struct SummaryRec {
     unsigned long long visited;     // entries of the innermost position that waves went through
 };
 
-// Everything the kernels need to find their data; passed by value.
+// Everything the kernels need to find their data; passed by value.  Every member has a
+// default (null / 0 / off), so a Plan that a call site forgets to fill in completely never
+// carries a stale mode switch or pointer into a kernel.
 struct Plan {
-    const Graph* graphs;      // [n_problems]
-    Instance*    inst;        // [n_inst]
-    Entry*       entries;     // [n_inst][t_max][k_max]   by task id
-    uint32_t*    rep;         // [n_inst][t_max][c_max]   replicas of every choice
-    uint32_t*    cost;        // [n_inst][t_max][c_max]
-    uint32_t*    k32;         // [n_inst][t_max][k_max]   32-bit local keys (in-lane tasks)
-    Quad*        quads;       // [n_inst][k_max]          stream of the innermost position
-    uint64_t*    partial;     // [n_inst][grid]           per-block minima (keys)
-    double*      partial_obj; // [n_inst][grid]           per-block best objectives (objective mode)
-    ResultRec*   results;     // [n_inst]
-    SummaryRec*  summary;
-    uint32_t n_inst, t_max, k_max, c_max;
-    uint32_t grid;            // blocks of the enumeration kernel
-    uint32_t lanes_wanted;    // total lanes the planner tries to expose
-    uint32_t objective;       // 0: cheapest feasible; 1: largest alpha*A_obj - beta*cost (Eq. 14)
-    uint32_t mix;             // 1: a task may run two tuples side by side (Eq. 2, 6, 7, 9, 10)
-    uint32_t bounds;          // 1: skip what latency and capacity bounds exclude; 0: issue every candidate's tests
-    uint32_t pad2;
+    const Graph* graphs = nullptr;      // [n_problems]
+    Instance*    inst = nullptr;        // [n_inst]
+    Entry*       entries = nullptr;     // [n_inst][t_max][k_max]   by task id
+    uint32_t*    rep = nullptr;         // [n_inst][t_max][c_max]   replicas of every choice
+    uint32_t*    cost = nullptr;        // [n_inst][t_max][c_max]
+    uint32_t*    k32 = nullptr;         // [n_inst][t_max][k_max]   32-bit local keys (in-lane tasks)
+    Quad*        quads = nullptr;       // [n_inst][k_max]          stream of the innermost position
+    uint64_t*    partial = nullptr;     // [n_inst][grid]           per-block minima (keys)
+    double*      partial_obj = nullptr; // [n_inst][grid]           per-block best objectives (objective mode)
+    ResultRec*   results = nullptr;     // [n_inst]
+    SummaryRec*  summary = nullptr;
+    uint32_t n_inst = 0, t_max = 0, k_max = 0, c_max = 0;
+    uint32_t grid = 0;            // blocks of the enumeration kernel
+    uint32_t lanes_wanted = 0;    // total lanes the planner tries to expose
+    uint32_t objective = 0;       // 0: cheapest feasible; 1: largest alpha*A_obj - beta*cost (Eq. 14)
+    uint32_t mix = 0;             // 1: a task may run two tuples side by side (Eq. 2, 6, 7, 9, 10)
+    uint32_t bounds = 0;          // 1: skip what latency and capacity bounds exclude; 0: issue every candidate's tests
+    uint32_t pad2 = 0;
     // mixture mode: per (instance, task) a grid of cells (cost 0..S_avail) x (latency class),
     // mix_cells entries each
-    uint64_t* cell_acc;       // best accuracy seen in the cell (bits of a positive double, 0 = empty)
-    uint64_t* cell_id;        // lowest option id among those with that accuracy
-    uint64_t* cell_pm;        // prefix maxima of cell_acc; later reused as a list of kept cells
-    uint32_t* cell_list;      // cells that survive the dominance test
-    uint64_t  mix_cells;
+    uint64_t* cell_acc = nullptr;  // best accuracy seen in the cell (bits of a positive double, 0 = empty)
+    uint64_t* cell_id = nullptr;   // lowest option id among those with that accuracy
+    uint64_t* cell_pm = nullptr;   // prefix maxima of cell_acc; later reused as a list of kept cells
+    uint32_t* cell_list = nullptr; // cells that survive the dominance test
+    uint64_t  mix_cells = 0;
     // bounds on: per instance the largest total cost still of interest: S_avail at first, then
     // the cost of the cheapest candidate found so far that meets both SLOs (cost modes only)
-    uint32_t* bound;          // [n_inst]
+    uint32_t* bound = nullptr;     // [n_inst]
 };
 
 }  // namespace jsv

@@ -234,8 +234,13 @@ int stage_graph(HostProblem& hp, const SpaceFlags& sp = SpaceFlags())
         }
         if ((g.sink_mask >> g.pos_of[s]) & 1u) g.u[g.pos_of[s]] = (double)hp.mult[s] / (double)sink_total;
     }
-    // A_max: the backward recursion with every task on its most accurate variant
+    // A_max: the backward recursion with every task on its most accurate variant, in the one
+    // order of operations that the kernels use for every candidate (see jsv_device.h): successors
+    // added by fma in descending position, sources added in descending position, position 0 joined
+    // by one fma.  The all-best assignment then reproduces A_max bit for bit on the device, so a
+    // threshold of exactly 1.0 accepts it.
     {
+#pragma clang fp contract(off)
         double H[MAXT] = {};
         double raw = 0.0;
         for (int p = (int)T - 1; p >= 0; --p) {
@@ -243,9 +248,12 @@ int stage_graph(HostProblem& hp, const SpaceFlags& sp = SpaceFlags())
             double a = hp.acc[(size_t)t * V];
             for (uint32_t v = 1; v < V; ++v) a = std::max(a, hp.acc[(size_t)t * V + v]);
             double hs = 0.0;
-            for (uint32_t s = p + 1; s < T; ++s) if ((g.succ[p] >> s) & 1u) hs = std::fma(g.w[p][s], H[s], hs);
-            H[p] = a * (((g.sink_mask >> p) & 1u) ? g.u[p] : hs);
-            if ((g.src_mask >> p) & 1u) raw += H[p];
+            for (int s = (int)T - 1; s > p; --s) if ((g.succ[p] >> s) & 1u) hs = std::fma(g.w[p][s], H[s], hs);
+            const double inner = ((g.sink_mask >> p) & 1u) ? g.u[p] : hs;
+            if (p == 0) { raw = std::fma(a, inner, raw); break; }      // position 0 is always a source
+            const double prod = a * inner;
+            H[p] = prod;
+            if ((g.src_mask >> p) & 1u) { const double sum = raw + prod; raw = sum; }
         }
         g.amax = raw;
     }
@@ -324,8 +332,13 @@ int ensure_device(jsv_ctx* ctx)
     if (cus <= 0) cus = 256;
     ctx->cus = (uint32_t)cus;
     ctx->grid = (uint32_t)cus * 8u;
-    for (auto& e : ctx->ev) HIP_TRY(ctx, hipEventCreate(&e));
     ctx->device_ready = true;
+    return JSV_OK;
+}
+
+int ensure_events(jsv_ctx* ctx)
+{
+    for (auto& e : ctx->ev) if (!e) HIP_TRY(ctx, hipEventCreate(&e));
     return JSV_OK;
 }
 
@@ -346,8 +359,9 @@ int ensure_pinned(jsv_ctx* ctx, size_t bytes)
     return JSV_OK;
 }
 
-// Upload graphs and tables of `n` problems as one blob; graph pointers become device addresses.
-int upload_problems(jsv_ctx* ctx, HostProblem* hps, uint32_t n)
+// Graphs and tables of `n` problems as one blob that will live at device address `base`
+// (graph pointers are device addresses inside it).  base = nullptr only sizes the blob.
+size_t build_blob(const HostProblem* hps, uint32_t n, const unsigned char* base, std::vector<unsigned char>* blob)
 {
     size_t off = align_up(sizeof(Graph) * n);
     std::vector<size_t> o_lat(n), o_thr(n), o_acc(n), o_units(n), o_fac(n);
@@ -359,29 +373,38 @@ int upload_problems(jsv_ctx* ctx, HostProblem* hps, uint32_t n)
         o_units[k] = off; off = align_up(off + hp.units.size() * sizeof(uint32_t));
         o_fac[k] = off;   off = align_up(off + hp.fac.size() * sizeof(uint32_t));
     }
-    if (ctx->d_problems_bytes < off) {
-        if (ctx->d_problems) { HIP_TRY(ctx, hipFree(ctx->d_problems)); ctx->d_problems = nullptr; ctx->d_problems_bytes = 0; }
-        HIP_TRY(ctx, hipMalloc(&ctx->d_problems, off));
-        ctx->d_problems_bytes = off;
-    }
-    std::vector<unsigned char> blob(off, 0);
-    unsigned char* base = (unsigned char*)ctx->d_problems;
+    if (!blob) return off;
+    blob->assign(off, 0);
     for (uint32_t k = 0; k < n; ++k) {
-        HostProblem& hp = hps[k];
+        const HostProblem& hp = hps[k];
         Graph g = hp.graph;
         g.acc = (const double*)(base + o_acc[k]);
         g.lat = (const uint32_t*)(base + o_lat[k]);
         g.thr = (const uint32_t*)(base + o_thr[k]);
         g.units = (const uint32_t*)(base + o_units[k]);
         g.fac = hp.fac.empty() ? nullptr : (const uint32_t*)(base + o_fac[k]);
-        std::memcpy(blob.data() + sizeof(Graph) * k, &g, sizeof g);
-        std::memcpy(blob.data() + o_acc[k], hp.acc.data(), hp.acc.size() * sizeof(double));
-        std::memcpy(blob.data() + o_lat[k], hp.lat.data(), hp.lat.size() * sizeof(uint32_t));
-        std::memcpy(blob.data() + o_thr[k], hp.thr.data(), hp.thr.size() * sizeof(uint32_t));
-        std::memcpy(blob.data() + o_units[k], hp.units.data(), hp.units.size() * sizeof(uint32_t));
-        if (!hp.fac.empty()) std::memcpy(blob.data() + o_fac[k], hp.fac.data(), hp.fac.size() * sizeof(uint32_t));
+        std::memcpy(blob->data() + sizeof(Graph) * k, &g, sizeof g);
+        std::memcpy(blob->data() + o_acc[k], hp.acc.data(), hp.acc.size() * sizeof(double));
+        std::memcpy(blob->data() + o_lat[k], hp.lat.data(), hp.lat.size() * sizeof(uint32_t));
+        std::memcpy(blob->data() + o_thr[k], hp.thr.data(), hp.thr.size() * sizeof(uint32_t));
+        std::memcpy(blob->data() + o_units[k], hp.units.data(), hp.units.size() * sizeof(uint32_t));
+        if (!hp.fac.empty()) std::memcpy(blob->data() + o_fac[k], hp.fac.data(), hp.fac.size() * sizeof(uint32_t));
     }
-    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_problems, blob.data(), off, hipMemcpyHostToDevice, ctx->stream));
+    return off;
+}
+
+// Upload the blob of `n` problems into library-owned device memory (grow-only).
+int upload_problems(jsv_ctx* ctx, HostProblem* hps, uint32_t n)
+{
+    const size_t bytes = build_blob(hps, n, nullptr, nullptr);
+    if (ctx->d_problems_bytes < bytes) {
+        if (ctx->d_problems) { HIP_TRY(ctx, hipFree(ctx->d_problems)); ctx->d_problems = nullptr; ctx->d_problems_bytes = 0; }
+        HIP_TRY(ctx, hipMalloc(&ctx->d_problems, bytes));
+        ctx->d_problems_bytes = bytes;
+    }
+    std::vector<unsigned char> blob;
+    build_blob(hps, n, (const unsigned char*)ctx->d_problems, &blob);
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->d_problems, blob.data(), bytes, hipMemcpyHostToDevice, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));      // blob is a local buffer
     ctx->n_problems = n;
     ctx->dirty = false;
@@ -433,6 +456,39 @@ int get_workspace(jsv_ctx* ctx, size_t bytes, unsigned char** out)
 
 uint32_t k_max_of(const HostProblem& hp, uint32_t cap) { return cap ? std::min(cap, hp.C) : hp.C; }
 
+// The one place a Plan is built: all bytes zero (padding too: graph mode compares plans with
+// memcmp), every buffer pointer from the layout, every mode switch off unless the context has it
+// on.  Callers set what is theirs alone afterwards (grid, lanes_wanted).
+jsv::Plan make_plan(const jsv_ctx* ctx, const void* graphs, const Layout& L, unsigned char* ws, uint32_t n_inst,
+                    uint32_t t_max, uint32_t k_max, uint32_t c_max, uint64_t mix_cells)
+{
+    jsv::Plan pl;
+    std::memset((void*)&pl, 0, sizeof pl);
+    pl.graphs = (const Graph*)graphs;
+    pl.inst = (Instance*)(ws + L.inst);
+    pl.entries = (jsv::Entry*)(ws + L.entries);
+    pl.rep = (uint32_t*)(ws + L.rep);
+    pl.cost = (uint32_t*)(ws + L.cost);
+    pl.k32 = (uint32_t*)(ws + L.k32);
+    pl.quads = (jsv::Quad*)(ws + L.quads);
+    pl.partial = (uint64_t*)(ws + L.partial);
+    pl.partial_obj = (double*)(ws + L.partial_obj);
+    pl.results = (jsv::ResultRec*)(ws + L.results);
+    pl.summary = (jsv::SummaryRec*)(ws + L.summary);
+    pl.bound = (uint32_t*)(ws + L.bound);
+    pl.n_inst = n_inst; pl.t_max = t_max; pl.k_max = k_max; pl.c_max = c_max;
+    pl.objective = (uint32_t)ctx->objective;
+    if (mix_cells != 0) {
+        pl.mix = 1u;
+        pl.mix_cells = mix_cells;
+        pl.cell_acc = (uint64_t*)(ws + L.cell_acc);
+        pl.cell_id = (uint64_t*)(ws + L.cell_id);
+        pl.cell_pm = (uint64_t*)(ws + L.cell_pm);
+        pl.cell_list = (uint32_t*)(ws + L.cell_list);
+    }
+    return pl;
+}
+
 int check_search_args(const HostProblem& hp, uint32_t demand, double slo_a, uint32_t cap)
 {
     if (demand == 0) return JSV_E_BADARG;
@@ -451,39 +507,21 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     if (mix_cells != 0 && jsv::mix_lds_bytes(c_max) > 64 * 1024) return JSV_E_BADARG;
     const Layout L = make_layout(n, t_max, k_max, c_max, ctx->grid, 0, mix_cells);
     unsigned char* ws = nullptr;
-    int rc = get_workspace(ctx, L.total, &ws);
-    if (rc) return rc;
+    const void* graphs = ctx->d_problems;
     const size_t in_bytes = sizeof(Instance) * n;
     const size_t out_bytes = sizeof(jsv::ResultRec) * n + sizeof(jsv::SummaryRec);
+    int rc = get_workspace(ctx, L.total, &ws);
+    if (rc) return rc;
     rc = ensure_pinned(ctx, align_up(in_bytes) + out_bytes);
+    if (rc) return rc;
+    rc = ensure_events(ctx);
     if (rc) return rc;
     unsigned char* pin_in = (unsigned char*)ctx->pinned;
     unsigned char* pin_out = pin_in + align_up(in_bytes);
     std::memcpy(pin_in, inst.data(), in_bytes);
 
-    jsv::Plan pl;
-    std::memset(&pl, 0, sizeof pl);
-    pl.graphs = (const Graph*)ctx->d_problems;
-    pl.inst = (Instance*)(ws + L.inst);
-    pl.entries = (jsv::Entry*)(ws + L.entries);
-    pl.rep = (uint32_t*)(ws + L.rep);
-    pl.cost = (uint32_t*)(ws + L.cost);
-    pl.k32 = (uint32_t*)(ws + L.k32);
-    pl.quads = (jsv::Quad*)(ws + L.quads);
-    pl.partial = (uint64_t*)(ws + L.partial);
-    pl.partial_obj = (double*)(ws + L.partial_obj);
-    pl.objective = (uint32_t)ctx->objective;
-    pl.mix = mix_cells != 0 ? 1u : 0u;
+    jsv::Plan pl = make_plan(ctx, graphs, L, ws, n, t_max, k_max, c_max, mix_cells);
     pl.bounds = ctx->bounds ? 1u : 0u;
-    pl.mix_cells = mix_cells;
-    pl.cell_acc = (uint64_t*)(ws + L.cell_acc);
-    pl.cell_id = (uint64_t*)(ws + L.cell_id);
-    pl.cell_pm = (uint64_t*)(ws + L.cell_pm);
-    pl.cell_list = (uint32_t*)(ws + L.cell_list);
-    pl.results = (jsv::ResultRec*)(ws + L.results);
-    pl.summary = (jsv::SummaryRec*)(ws + L.summary);
-    pl.bound = (uint32_t*)(ws + L.bound);
-    pl.n_inst = n; pl.t_max = t_max; pl.k_max = k_max; pl.c_max = c_max;
     const int mode = jsv::enumerate_mode(ctx->objective != 0, pl.mix != 0) * 2 + (ctx->bounds ? 1 : 0);
     if (ctx->occ_t != t_max || ctx->occ_k != k_max || ctx->occ_obj != mode) {
         int blocks = 0;
@@ -498,6 +536,8 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
 
     hipStream_t st = ctx->stream;
     bool timed_kernels = true;
+    jsv::SummaryRec sr;
+    std::memset(&sr, 0, sizeof sr);
     if (ctx->graph_mode) {
         // Replay the captured sequence when nothing it was built from has changed: same
         // buffers, shapes, grid and objective (the instance records travel through the pinned
@@ -521,7 +561,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
             }
             ctx->graph = g;
             HIP_TRY(ctx, hipGraphInstantiate(&ctx->graph_exec, ctx->graph, nullptr, nullptr, 0));
-            ctx->graph_plan = pl;
+            std::memcpy((void*)&ctx->graph_plan, &pl, sizeof pl);
             ctx->graph_pin = pin_in;
         }
         HIP_TRY(ctx, hipEventRecord(ctx->ev[0], st));
@@ -543,9 +583,9 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     }
     HIP_TRY(ctx, hipStreamSynchronize(st));
 
-    jsv::SummaryRec sr;
     std::memcpy(&sr, pin_out + sizeof(jsv::ResultRec) * n, sizeof sr);
     if (sr.any_flags & jsv::F_OVERFLOW) return JSV_E_OVERFLOW;
+    if (sr.any_flags & jsv::F_MISMATCH) return JSV_E_INTERNAL;
     std::memcpy(out, pin_out, sizeof(jsv::ResultRec) * n);
     uint64_t enumerated = 0;                        // candidates of the instances that were enumerated at all
     for (uint32_t k = 0; k < n; ++k) {
@@ -678,6 +718,7 @@ JSV_API const char* jsv_error_string(int code)
     case JSV_E_STATE: return "profile/graph missing or inconsistent";
     case JSV_E_WORKSPACE: return "workspace too small";
     case JSV_E_DEVICE: return "HIP call failed";
+    case JSV_E_INTERNAL: return "enumeration and rescoring disagree";
     default: return "unknown error";
     }
 }
@@ -925,22 +966,7 @@ JSV_API int jsv_eval_candidates(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo
     if (rc) return rc;
     Instance in = make_instance(ctx, hp, 0, Search{demand_mrps, slo_latency_us, prune_cap, slo_accuracy});
 
-    jsv::Plan pl;
-    std::memset(&pl, 0, sizeof pl);        // every mode switch off unless set below
-    pl.graphs = (const Graph*)ctx->d_problems;
-    pl.inst = (Instance*)(ws + L.inst);
-    pl.entries = (jsv::Entry*)(ws + L.entries);
-    pl.rep = (uint32_t*)(ws + L.rep);
-    pl.cost = (uint32_t*)(ws + L.cost);
-    pl.k32 = (uint32_t*)(ws + L.k32);
-    pl.quads = (jsv::Quad*)(ws + L.quads);
-    pl.partial = (uint64_t*)(ws + L.partial);
-    pl.partial_obj = (double*)(ws + L.partial_obj);
-    pl.objective = (uint32_t)ctx->objective;
-    pl.results = (jsv::ResultRec*)(ws + L.results);
-    pl.summary = (jsv::SummaryRec*)(ws + L.summary);
-    pl.bound = (uint32_t*)(ws + L.bound);
-    pl.n_inst = 1; pl.t_max = T; pl.k_max = k_max; pl.c_max = hp.C;
+    jsv::Plan pl = make_plan(ctx, ctx->d_problems, L, ws, 1, T, k_max, hp.C, 0);
     pl.grid = ctx->grid; pl.lanes_wanted = 64;
 
     unsigned char* e = ws + L.eval;
@@ -994,22 +1020,7 @@ JSV_API int jsv_get_pruned(jsv_ctx* ctx, uint32_t demand_mrps, uint32_t slo_late
     rc = get_workspace(ctx, L.total, &ws);
     if (rc) return rc;
     Instance in = make_instance(ctx, hp, 0, Search{demand_mrps, slo_latency_us, prune_cap, 0.0});
-    jsv::Plan pl;
-    std::memset(&pl, 0, sizeof pl);        // every mode switch off unless set below
-    pl.graphs = (const Graph*)ctx->d_problems;
-    pl.inst = (Instance*)(ws + L.inst);
-    pl.entries = (jsv::Entry*)(ws + L.entries);
-    pl.rep = (uint32_t*)(ws + L.rep);
-    pl.cost = (uint32_t*)(ws + L.cost);
-    pl.k32 = (uint32_t*)(ws + L.k32);
-    pl.quads = (jsv::Quad*)(ws + L.quads);
-    pl.partial = (uint64_t*)(ws + L.partial);
-    pl.partial_obj = (double*)(ws + L.partial_obj);
-    pl.objective = (uint32_t)ctx->objective;
-    pl.results = (jsv::ResultRec*)(ws + L.results);
-    pl.summary = (jsv::SummaryRec*)(ws + L.summary);
-    pl.bound = (uint32_t*)(ws + L.bound);
-    pl.n_inst = 1; pl.t_max = T; pl.k_max = k_max; pl.c_max = hp.C;
+    jsv::Plan pl = make_plan(ctx, ctx->d_problems, L, ws, 1, T, k_max, hp.C, 0);
     pl.grid = ctx->grid; pl.lanes_wanted = 64;
     hipStream_t st = ctx->stream;
     HIP_TRY(ctx, hipMemcpyAsync(pl.inst, &in, sizeof in, hipMemcpyHostToDevice, st));

@@ -890,6 +890,7 @@ template <int P>
 __device__ __forceinline__ LaneState fix_position(const LaneState& s, const Uniforms& U,
                                                   uint32_t lat, double acc, uint64_t key, uint32_t k32)
 {
+#pragma clang fp contract(off)      // the product below is rounded on its own (see jsv_device.h)
     LaneState r = s;
     const uint32_t tail = lat + s.nxt[P];
     const double H = acc * s.hin[P];
@@ -1235,6 +1236,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
                                          const Quad JSV_CONST* quads, const Entry* s_tab, uint32_t k_max,
                                          uint64_t group, uint32_t chunk_id, uint32_t bound, Best& best, uint64_t& visited)
 {
+#pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
     const uint32_t T = g->T;
     uint64_t o = group * TILE_LANES + threadIdx.x;
     const bool live = o < in->s_out;
@@ -1271,11 +1273,11 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
             double hs = 0.0;
             const uint32_t succ = g->succ[p];
 #pragma unroll
-            for (int s = p + 1; s < MAXT; ++s)
+            for (int s = MAXT - 1; s > p; --s)
                 if ((succ >> s) & 1u) { mx = umax(mx, tail[s]); hs = __builtin_fma(g->w[p][s], H[s], hs); }
             tail[p] = lat + mx;
             H[p] = acc * (((sink_mask >> p) & 1u) ? g->u[p] : hs);
-            if ((src_mask >> p) & 1u) { st.smax = umax(st.smax, tail[p]); st.sacc += H[p]; }
+            if ((src_mask >> p) & 1u) { st.smax = umax(st.smax, tail[p]); st.sacc = st.sacc + H[p]; }
         }
     }
     // what the outer positions contribute to the recursions of positions < NIN
@@ -1285,7 +1287,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     for (int p = 0; p < NIN; ++p) {
         const uint32_t succ = g->succ[p];
 #pragma unroll
-        for (int s = NIN; s < MAXT; ++s)
+        for (int s = MAXT - 1; s >= NIN; --s)
             if ((succ >> s) & 1u) { st.nxt[p] = umax(st.nxt[p], tail[s]); st.hin[p] = __builtin_fma(g->w[p][s], H[s], st.hin[p]); }
     }
 
@@ -1504,6 +1506,7 @@ struct Score { uint32_t latency; uint32_t cost; double accuracy; uint8_t mask; }
 __device__ Score score_digits(const Graph* g, const Instance* in, const Entry* entries, uint32_t k_max,
                               const uint32_t* dig)
 {
+#pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
     uint32_t tail[MAXT];
     double H[MAXT];
     const uint32_t T = g->T;
@@ -1515,12 +1518,18 @@ __device__ Score score_digits(const Graph* g, const Instance* in, const Entry* e
         const Entry* e = entries + (size_t)t * k_max + dig[t];
         uint32_t mx = 0;
         double hs = 0.0;
-        for (uint32_t s = p + 1; s < T; ++s)
+        for (int s = (int)T - 1; s > p; --s)
             if ((g->succ[p] >> s) & 1u) { mx = umax(mx, tail[s]); hs = __builtin_fma(g->w[p][s], H[s], hs); }
         tail[p] = e->lat + mx;
-        H[p] = e->acc * (((g->sink_mask >> p) & 1u) ? g->u[p] : hs);
-        if ((g->src_mask >> p) & 1u) { crit = umax(crit, tail[p]); raw += H[p]; }
+        const double inner = ((g->sink_mask >> p) & 1u) ? g->u[p] : hs;
         cost += e->cost;
+        if (p == 0) {                       // always a source; joins the sum by one fma
+            crit = umax(crit, tail[0]);
+            raw = __builtin_fma(e->acc, inner, raw);
+        } else {
+            H[p] = e->acc * inner;
+            if ((g->src_mask >> p) & 1u) { crit = umax(crit, tail[p]); raw = raw + H[p]; }
+        }
     }
     Score sc;
     const uint64_t lat = (uint64_t)g->q * crit;
@@ -1529,7 +1538,7 @@ __device__ Score score_digits(const Graph* g, const Instance* in, const Entry* e
     sc.accuracy = raw / g->amax;
     sc.mask = 0;
     if (lat <= in->slo_l) sc.mask |= 1;
-    if (sc.accuracy >= in->slo_a) sc.mask |= 2;
+    if (raw >= in->slo_raw) sc.mask |= 2;               // Eq. 13, the test the enumeration applies
     if (g->capacity == 0 || cost <= g->capacity) sc.mask |= 4;
     return sc;
 }
@@ -1568,7 +1577,12 @@ __global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
         const Entry* ent = pl.entries + (size_t)i * pl.t_max * pl.k_max;
         for (uint32_t t = 0; t < g->T; ++t) dig[t] = (uint32_t)((idx / in->stride[t]) % in->K[t]);
         const Score sc = score_digits(g, in, ent, pl.k_max, dig);
-        if (sc.mask == 7) {                 // only the capacity bit can still be missing
+        // The rescoring repeats the enumeration's latency and accuracy tests operation by
+        // operation, so only the capacity bit (Eq. 8, applied to the minimum) can be missing.  A
+        // winner that fails one of the other two would mean the two disagree: reported as an
+        // error, never as "infeasible".
+        if ((sc.mask & 3) != 3) r->flags |= F_MISMATCH;
+        if (sc.mask == 7) {
             r->index = idx; r->feasible = 1;
             r->accuracy = sc.accuracy; r->latency_us = sc.latency; r->cost_units = (int32_t)sc.cost;
             r->objective = in->alpha * sc.accuracy - in->beta * (double)sc.cost;

@@ -236,3 +236,48 @@ def test_three_in_lane_positions_with_both_key_widths(ctx):
                 assert a.objective == pytest.approx(b.objective, abs=1e-12)
             else:
                 same(a, b)
+
+
+@pytest.mark.parametrize("name", ["diamond5", "xr8", "chain3"])
+def test_threshold_of_exactly_one_accepts_the_most_accurate_assignment(ctx, name):
+    """SLO_a = 1.0 (no accuracy loss allowed): A_max and every candidate's A_raw are formed by
+    one order of operations, so the all-best-variant candidates pass Eq. 13 on the device as
+    they do in the oracle; on graphs whose source has several successors a different
+    summation order would land one ulp below A_max and reject them."""
+    w = W.BENCH_WORKLOADS[name](seed=0)
+    pb, se = w.problems[0], w.searches[0]
+    o = oracle.Oracle.from_problem(pb)
+    dem = se.demand_mrps[:6:2] if len(se.demand_mrps) > 1 else se.demand_mrps
+    cap = 10 if name == "xr8" else se.prune_cap
+    slo_l = se.slo_latency_us * (2 if name == "chain3" else 1)   # the best variants are the slowest
+    ctx.load(pb)
+    res, summ = ctx.search(dem, slo_l, 1.0, cap)
+    ref, bl, md = o.search(dem, slo_l, 1.0, cap, threads=16)
+    assert any(b.feasible for b in ref)
+    for l, (a, b) in enumerate(zip(res, ref)):
+        same(a, b, f"{name} level {l}")
+        if b.feasible:
+            assert a.accuracy == 1.0
+            assert all(c // (pb.P * pb.B) == int(np.argmax(pb.accuracy[t])) for t, c in enumerate(a.choice))
+    assert (summ.best_level, summ.max_demand_mrps) == (bl, md)
+    # all candidates of the first level that the oracle accepts, the device accepts, and vice versa
+    D = int(dem[0])
+    K, space, _ = o.space(D, slo_l, cap)
+    idx = np.random.default_rng(3).integers(0, space, size=200_000, dtype=np.uint64)
+    idx[0] = ref[0].index if ref[0].feasible else 0
+    ga = ctx.eval_candidates(D, slo_l, 1.0, cap, idx)
+    gb = o.eval(D, slo_l, 1.0, cap, idx)
+    assert np.array_equal(ga[4], gb[4]) and (gb[4] & 2).any()
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_threshold_of_exactly_one_on_random_graphs(ctx, seed):
+    """Random multi-branch graphs with uneven multipliers: shares like 1/3 and 3/7 make the
+    weighted sums inexact, which is where summation order shows."""
+    r = W.SplitMix64(77, seed)
+    T = 4 + seed % 4
+    edges = [(a, b) for a in range(T) for b in range(a + 1, T) if r.uniform() < 0.55]
+    mult = [int(r.randint(300, 1700)) for _ in range(T)]
+    pb = _problem(T, 3, 2, 2, 100 + seed, edges, mult=mult)
+    check_search(ctx, pb, _search([20000, 250000], 400000, 1.0))
+    check_search(ctx, pb, _search([20000], 400000, 1.0, cap=6))

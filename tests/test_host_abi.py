@@ -26,6 +26,17 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(jsv.JsvSummary) == 32
 
 
+def test_a_fresh_plan_has_every_mode_switch_off(tmp_path):
+    """The kernels' argument block (jsv::Plan): default-constructed over memory full of ones,
+    every switch reads 0 and every pointer null."""
+    import subprocess
+    exe = str(tmp_path / "plan_defaults")
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-Wall", os.path.join(ROOT, "tests", "c_abi", "plan_defaults.cpp"),
+                           "-o", exe])
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0 and "plan defaults ok" in out.stdout, out.stdout + out.stderr
+
+
 @pytest.fixture()
 def ctx():
     j = jsv.Jsv(use_torch=False)
