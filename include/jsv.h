@@ -318,6 +318,31 @@ JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_lev
                jsv_result* out, jsv_summary* summary);
 
 /*
+ * jsv_search for callers that cannot allocate: code that runs where hipMalloc is not allowed
+ * (a tight serving loop, a harness that forbids it, a region around which the caller is
+ * capturing other work).  Same arguments, same results, record by record, as jsv_search for the
+ * loaded single system; but the call allocates nothing - no device memory, no pinned memory,
+ * no events: problem tables, workspace and results live in one static device array of
+ * JSV_STATIC_SCRATCH_BYTES that the library's code object brings along (one copy per GPU,
+ * held until the process ends), instance records are copied straight from and results
+ * straight to the caller's host memory, and jsv_summary.seconds_device / seconds_enumerate
+ * are 0.  A lent workspace (jsv_set_workspace) is not used.
+ *
+ * Every context on a GPU shares that GPU's array, which keeps the last call's contents; each
+ * call writes everything it reads.  Calls that overlap in time on one GPU - from two threads,
+ * or two contexts on different streams - race on it: serialise them.
+ *
+ * Errors as jsv_search, plus: JSV_E_WORKSPACE if tables and workspace of this search exceed
+ * JSV_STATIC_SCRATCH_BYTES (xr8-sized: 8 tasks x 240 choices, 64 levels, prune cap 20 takes
+ * 3.6 MB; nothing is launched); JSV_E_STATE with per-variant factors, mixtures, a loaded batch or
+ * graph mode, which this entry point does not serve.
+ */
+#define JSV_STATIC_SCRATCH_BYTES (16u << 20)
+JSV_API int jsv_search_static(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_levels,
+                      uint32_t slo_latency_us, double slo_accuracy, uint32_t prune_cap,
+                      jsv_result* out, jsv_summary* summary);
+
+/*
  * Parity aid: score n explicit candidates of one level's searched space.
  * index[n] are candidate indices (< prod K_t).  Outputs, each [n] (replicas
  * [n][T]): latency_us, cost, accuracy as in jsv_result; mask bit0 latency SLO

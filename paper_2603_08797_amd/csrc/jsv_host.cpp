@@ -10,6 +10,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -107,6 +108,40 @@ namespace {
         hipError_t e_ = (expr);                                \
         if (e_ != hipSuccess) { (ctx)->last_hip = (int)e_; return JSV_E_DEVICE; } \
     } while (0)
+
+// ---- memory for callers that cannot allocate ---------------------------------------------
+// jsv_search_static keeps everything a search needs on the device - the problem blob at the
+// front, the workspace behind it - in this array instead of allocated memory.  One copy per
+// GPU, held until the process ends, shared by every context on that GPU; it keeps the last
+// call's contents (the blob and the instance records are rewritten by every call, counters and
+// partial results are reset by the kernels themselves).  In host code the array's name is only a
+// handle for hipGetSymbolAddress: the device address it yields, per device, is what kernels
+// and copies get.
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[JSV_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+unsigned char* g_scratch_ptr[MAX_DEVICES];      // device address of `scratch` on each GPU, null = not asked yet
+std::mutex g_scratch_mutex;
+
+struct StaticArena {        // a search that lives in the static array
+    unsigned char* base;    // its device address on the context's GPU
+    size_t blob_bytes;      // the problem blob takes this much of its front (256-byte multiple)
+};
+
+// Device address of the static array on the context's GPU, which must be current.
+int static_scratch(jsv_ctx* ctx, unsigned char** out)
+{
+    if (ctx->device < 0 || ctx->device >= MAX_DEVICES) return JSV_E_BADARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[ctx->device]) {
+        void* p = nullptr;
+        HIP_TRY(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return JSV_E_DEVICE;
+        g_scratch_ptr[ctx->device] = (unsigned char*)p;
+    }
+    *out = g_scratch_ptr[ctx->device];
+    return JSV_OK;
+}
 
 int check_profile(uint32_t T, uint32_t V, uint32_t P, uint32_t B, const uint32_t* units,
                   const uint32_t* batch, const uint32_t* lat, const uint32_t* thr, const double* acc,
@@ -498,8 +533,10 @@ int check_search_args(const HostProblem& hp, uint32_t demand, double slo_a, uint
 }
 
 // The whole device pass for n_inst instances whose parameters are in `inst` (host copies).
+// With `sa` the search lives in the static array: no allocation of any kind, instance records
+// copied straight from `inst` and results straight into `out`, no events (no timing).
 int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32_t k_max, uint32_t c_max,
-               jsv_result* out, jsv_summary* summary, uint64_t mix_cells = 0)
+               jsv_result* out, jsv_summary* summary, uint64_t mix_cells = 0, const StaticArena* sa = nullptr)
 {
     const uint32_t n = (uint32_t)inst.size();
     if (jsv::enumerate_lds_bytes(t_max, k_max) > 128 * 1024 || jsv::prune_lds_bytes(c_max) > 64 * 1024)
@@ -510,15 +547,24 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     const void* graphs = ctx->d_problems;
     const size_t in_bytes = sizeof(Instance) * n;
     const size_t out_bytes = sizeof(jsv::ResultRec) * n + sizeof(jsv::SummaryRec);
-    int rc = get_workspace(ctx, L.total, &ws);
-    if (rc) return rc;
-    rc = ensure_pinned(ctx, align_up(in_bytes) + out_bytes);
-    if (rc) return rc;
-    rc = ensure_events(ctx);
-    if (rc) return rc;
-    unsigned char* pin_in = (unsigned char*)ctx->pinned;
-    unsigned char* pin_out = pin_in + align_up(in_bytes);
-    std::memcpy(pin_in, inst.data(), in_bytes);
+    unsigned char* pin_in = (unsigned char*)inst.data();
+    unsigned char* pin_out = nullptr;
+    int rc = JSV_OK;
+    if (sa) {
+        if (sa->blob_bytes + L.total > JSV_STATIC_SCRATCH_BYTES || ctx->graph_mode) return JSV_E_WORKSPACE;
+        ws = sa->base + sa->blob_bytes;
+        graphs = sa->base;
+    } else {
+        rc = get_workspace(ctx, L.total, &ws);
+        if (rc) return rc;
+        rc = ensure_pinned(ctx, align_up(in_bytes) + out_bytes);
+        if (rc) return rc;
+        rc = ensure_events(ctx);
+        if (rc) return rc;
+        pin_in = (unsigned char*)ctx->pinned;
+        pin_out = pin_in + align_up(in_bytes);
+        std::memcpy(pin_in, inst.data(), in_bytes);
+    }
 
     jsv::Plan pl = make_plan(ctx, graphs, L, ws, n, t_max, k_max, c_max, mix_cells);
     pl.bounds = ctx->bounds ? 1u : 0u;
@@ -538,7 +584,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     bool timed_kernels = true;
     jsv::SummaryRec sr;
     std::memset(&sr, 0, sizeof sr);
-    if (ctx->graph_mode) {
+    if (ctx->graph_mode && !sa) {
         // Replay the captured sequence when nothing it was built from has changed: same
         // buffers, shapes, grid and objective (the instance records travel through the pinned
         // buffer, so new demands and SLOs need no new capture).
@@ -568,6 +614,14 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
         HIP_TRY(ctx, hipGraphLaunch(ctx->graph_exec, st));
         HIP_TRY(ctx, hipEventRecord(ctx->ev[3], st));
         timed_kernels = false;
+    } else if (sa) {
+        timed_kernels = false;
+        HIP_TRY(ctx, hipMemcpyAsync(pl.inst, pin_in, in_bytes, hipMemcpyHostToDevice, st));
+        HIP_TRY(ctx, jsv::launch_prune_plan_scan(pl, st));
+        HIP_TRY(ctx, jsv::launch_enumerate(pl, st));
+        HIP_TRY(ctx, jsv::launch_finalize(pl, st));
+        HIP_TRY(ctx, hipMemcpyAsync(out, pl.results, sizeof(jsv::ResultRec) * n, hipMemcpyDeviceToHost, st));
+        HIP_TRY(ctx, hipMemcpyAsync(&sr, pl.summary, sizeof(jsv::SummaryRec), hipMemcpyDeviceToHost, st));
     } else {
         HIP_TRY(ctx, hipMemcpyAsync(pl.inst, pin_in, in_bytes, hipMemcpyHostToDevice, st));
         HIP_TRY(ctx, hipEventRecord(ctx->ev[0], st));
@@ -583,10 +637,10 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     }
     HIP_TRY(ctx, hipStreamSynchronize(st));
 
-    std::memcpy(&sr, pin_out + sizeof(jsv::ResultRec) * n, sizeof sr);
+    if (!sa) std::memcpy(&sr, pin_out + sizeof(jsv::ResultRec) * n, sizeof sr);
     if (sr.any_flags & jsv::F_OVERFLOW) return JSV_E_OVERFLOW;
     if (sr.any_flags & jsv::F_MISMATCH) return JSV_E_INTERNAL;
-    std::memcpy(out, pin_out, sizeof(jsv::ResultRec) * n);
+    if (!sa) std::memcpy(out, pin_out, sizeof(jsv::ResultRec) * n);
     uint64_t enumerated = 0;                        // candidates of the instances that were enumerated at all
     for (uint32_t k = 0; k < n; ++k) {
         if (!(out[k].flags & jsv::F_CUT)) enumerated += out[k].evaluated;
@@ -594,7 +648,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     }
     if (summary) {
         float ms_all = 0.f, ms_enum = 0.f;
-        HIP_TRY(ctx, hipEventElapsedTime(&ms_all, ctx->ev[0], ctx->ev[3]));
+        if (!sa) HIP_TRY(ctx, hipEventElapsedTime(&ms_all, ctx->ev[0], ctx->ev[3]));
         if (timed_kernels) HIP_TRY(ctx, hipEventElapsedTime(&ms_enum, ctx->ev[1], ctx->ev[2]));
         summary->best_level = sr.best_level;
         summary->max_demand_mrps = sr.max_demand;
@@ -906,6 +960,47 @@ JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_lev
     for (uint32_t l = 0; l < n_levels; ++l)
         inst[l] = make_instance(ctx, hp, 0, Search{demand_mrps[l], slo_latency_us, prune_cap, slo_accuracy});
     return run_search(ctx, inst, hp.T, k_max_of(hp, prune_cap), hp.C, out, summary);
+}
+
+JSV_API int jsv_search_static(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_levels,
+                      uint32_t slo_latency_us, double slo_accuracy, uint32_t prune_cap,
+                      jsv_result* out, jsv_summary* summary)
+{
+    if (!ctx || !demand_mrps || !out) return JSV_E_NULL;
+    if (n_levels == 0) return JSV_E_BADARG;
+    HostProblem& hp = ctx->single;
+    if (ctx->batch_mode || !hp.have_profile || !hp.have_dag || hp.mult.size() != hp.T) return JSV_E_STATE;
+    if (ctx->mix || !hp.fac.empty() || ctx->graph_mode) return JSV_E_STATE;
+    for (uint32_t l = 0; l < n_levels; ++l) {
+        const int rc = check_search_args(hp, demand_mrps[l], slo_accuracy, prune_cap);
+        if (rc) return rc;
+    }
+    if (!hp.staged) {
+        const int rc = stage_graph(hp, SpaceFlags{ctx->space_a, ctx->space_s, ctx->space_t});
+        if (rc) return rc;
+        ctx->dirty = true;                      // for the allocating entry points: their blob is stale too
+    }
+    // does it fit the static array?  (checked before any device call; per-block partial results
+    // are sized for the device's compute units, 256 before the first device call)
+    const uint32_t k_max = k_max_of(hp, prune_cap);
+    const size_t blob_bytes = build_blob(&hp, 1, nullptr, nullptr);
+    const uint32_t grid = ctx->grid ? ctx->grid : 256u * 8u;
+    if (blob_bytes + make_layout(n_levels, hp.T, k_max, hp.C, grid, 0, 0).total > JSV_STATIC_SCRATCH_BYTES)
+        return JSV_E_WORKSPACE;
+    int rc = ensure_device(ctx);
+    if (rc) return rc;
+    StaticArena sa{nullptr, blob_bytes};
+    rc = static_scratch(ctx, &sa.base);
+    if (rc) return rc;
+    // the array is shared by every context on this GPU: the blob goes up with every call
+    std::vector<unsigned char> blob;
+    build_blob(&hp, 1, sa.base, &blob);
+    HIP_TRY(ctx, hipMemcpyAsync(sa.base, blob.data(), blob_bytes, hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));      // blob is a local buffer
+    std::vector<Instance> inst(n_levels);
+    for (uint32_t l = 0; l < n_levels; ++l)
+        inst[l] = make_instance(ctx, hp, 0, Search{demand_mrps[l], slo_latency_us, prune_cap, slo_accuracy});
+    return run_search(ctx, inst, hp.T, k_max, hp.C, out, summary, 0, &sa);
 }
 
 JSV_API int jsv_set_bounds(jsv_ctx* ctx, int on)

@@ -23,7 +23,7 @@ OK, E_NULL, E_BADARG, E_CYCLE, E_OVERFLOW, E_STATE, E_WORKSPACE, E_DEVICE, E_INT
 
 EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space", "jsv_set_factors", "jsv_set_mixtures", "jsv_set_bounds", "jsv_set_graph_mode",
            "jsv_workspace_bytes", "jsv_set_workspace", "jsv_load_profile", "jsv_set_dag",
-           "jsv_search", "jsv_eval_candidates", "jsv_get_pruned", "jsv_load_batch",
+           "jsv_search", "jsv_search_static", "jsv_eval_candidates", "jsv_get_pruned", "jsv_load_batch",
            "jsv_search_loaded_batch", "jsv_search_batch"]
 
 
@@ -96,6 +96,8 @@ def load_library():
     lib.jsv_set_dag.argtypes = [vp, u32, u32, vp, vp, vp, u32, u32]
     lib.jsv_search.restype = C.c_int
     lib.jsv_search.argtypes = [vp, vp, u32, u32, f64, u32, C.POINTER(JsvResult), C.POINTER(JsvSummary)]
+    lib.jsv_search_static.restype = C.c_int
+    lib.jsv_search_static.argtypes = [vp, vp, u32, u32, f64, u32, C.POINTER(JsvResult), C.POINTER(JsvSummary)]
     lib.jsv_eval_candidates.restype = C.c_int
     lib.jsv_eval_candidates.argtypes = [vp, u32, u32, f64, u32, vp, u32, vp, vp, vp, vp, vp]
     lib.jsv_get_pruned.restype = C.c_int
@@ -288,6 +290,18 @@ class Jsv:
         summ = JsvSummary()
         self._check(self._lib.jsv_search(self._h, _ptr(d), n, int(slo_latency_us), float(slo_accuracy),
                                          int(prune_cap), res, C.byref(summ)), "jsv_search")
+        return ([_result(res[i], self.T) for i in range(n)],
+                Summary(int(summ.best_level), int(summ.max_demand_mrps), float(summ.seconds_device),
+                        float(summ.seconds_enumerate), int(summ.candidates_visited)))
+
+    def search_static(self, demand_mrps, slo_latency_us: int, slo_accuracy: float, prune_cap: int = 0):
+        """jsv_search without any allocation: everything lives in the library's static device array."""
+        d = _u32(demand_mrps)
+        n = int(d.shape[0])
+        res = (JsvResult * max(n, 1))()
+        summ = JsvSummary()
+        self._check(self._lib.jsv_search_static(self._h, _ptr(d), n, int(slo_latency_us), float(slo_accuracy),
+                                                int(prune_cap), res, C.byref(summ)), "jsv_search_static")
         return ([_result(res[i], self.T) for i in range(n)],
                 Summary(int(summ.best_level), int(summ.max_demand_mrps), float(summ.seconds_device),
                         float(summ.seconds_enumerate), int(summ.candidates_visited)))

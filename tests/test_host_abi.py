@@ -168,3 +168,16 @@ def test_mode_switches_need_no_device(ctx):
     # mixture mode checks its own bounds on the prune cap before anything touches the GPU
     assert code(ctx.search, se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 1) in (jsv.E_BADARG, jsv.E_DEVICE)
     ctx.set_mixtures(False)
+
+
+def test_static_scratch_entry_point_rejects_what_does_not_fit_before_any_device_call(ctx):
+    """jsv_search_static sizes tables + workspace against JSV_STATIC_SCRATCH_BYTES on the host."""
+    w = W.xr8(seed=0)
+    pb, se = w.problems[0], w.searches[0]
+    ctx.load(pb)
+    many = np.full(2000, 50_000, dtype=np.uint32)
+    assert code(ctx.search_static, many, se.slo_latency_us, se.slo_accuracy, 20) == jsv.E_WORKSPACE
+    assert code(ctx.search_static, many[:0], se.slo_latency_us, se.slo_accuracy, 20) == jsv.E_BADARG
+    assert code(ctx.search_static, many[:4], se.slo_latency_us, se.slo_accuracy, 3) == jsv.E_BADARG   # cap < 2V
+    ctx.set_mixtures(True)
+    assert code(ctx.search_static, many[:4], se.slo_latency_us, se.slo_accuracy, 20) == jsv.E_STATE
