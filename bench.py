@@ -42,8 +42,36 @@ UNSHARED_OPS_PER_CANDIDATE = 11
 # key: workload, seed, objective mode, mixture mode, bounds
 MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (3641 + 11411) * 1024,
                           ("xr8", 0, False, False, True): (15069 + 14636) * 1024}
+# SQ counters of the same launch (profiles/enumerate_kernel_xr8_counters.md): vector instructions
+# issued per candidate (wave instructions x 64 lanes / candidates) and VALU issue utilisation
+# (busy cycles of the vector ALUs / elapsed cycles); same key as above
+MEASURED_COUNTERS = {("xr8", 0, False, False, False): {"valu_lane_ops_per_candidate": 3.17, "issue_utilisation": 0.982,
+                                                       "source": "profiles/enumerate_kernel_xr8_counters.md"}}
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one full-rate VALU lane-op per lane per cycle
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+
+
+def peak_probe():
+    """Sustained lane-operations/s of dependent-free v_add_u32 and v_fma_f64 streams on this GPU
+    (paper_2603_08797_amd/csrc/peak_probe.hip, a library of its own): what the vector ALUs deliver
+    at the clock they hold under load, beside the 2.4 GHz paper figure."""
+    import ctypes as C
+    path = os.path.join(ROOT, "paper_2603_08797_amd", "libjsv_probe.so")
+    if not os.path.exists(path):
+        return None
+    lib = C.CDLL(path)
+    lib.jsv_probe_valu.restype = C.c_int
+    lib.jsv_probe_valu.argtypes = [C.c_int, C.c_uint32, C.c_uint32, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    out = {"unit": "Tlane-op/s", "paper_peak": VALU_PEAK_LANE_OPS / 1e12}
+    for kind, name in ((0, "v_add_u32"), (1, "v_fma_f64")):
+        sec, ops = C.c_double(), C.c_double()
+        rc = lib.jsv_probe_valu(kind, 256 * 8, 6000, 5, C.byref(sec), C.byref(ops))
+        if rc != 0 or sec.value <= 0:
+            out[name] = None
+            continue
+        out[name] = ops.value / sec.value / 1e12
+        out[name + "_ms"] = sec.value * 1e3
+    return out
 
 
 # Mixture mode: every option has its own accuracy, so each candidate is charged its latency
@@ -117,18 +145,58 @@ def cpu_baseline(w, objective: bool, factors=None, mixtures=False, seconds_targe
                 "sample": f"the first {n_lv} demand levels of the same workload ({done} candidates), {dt:.1f} s"}
     D = int(se.demand_mrps[0])
     K, space, _ = o.space(D, se.slo_latency_us, se.prune_cap)
-    n = min(space, 2_000_000 * threads)            # probe
-    t0 = time.perf_counter()
-    o.search_range(D, se.slo_latency_us, se.slo_accuracy, se.prune_cap, 0, n, threads=threads)
-    dt = time.perf_counter() - t0
-    rate = n / max(dt, 1e-9)
-    n2 = int(min(space, rate * seconds_target))
-    t0 = time.perf_counter()
-    o.search_range(D, se.slo_latency_us, se.slo_accuracy, se.prune_cap, 0, n2, threads=threads)
-    dt = time.perf_counter() - t0
+
+    def timed(nthreads, seconds):
+        n = min(space, 1_000_000 * nthreads)       # probe for the rate, then a slice of the wanted length
+        t0 = time.perf_counter()
+        o.search_range(D, se.slo_latency_us, se.slo_accuracy, se.prune_cap, 0, n, threads=nthreads)
+        rate = n / max(time.perf_counter() - t0, 1e-9)
+        n2 = int(min(space, max(n, rate * seconds)))
+        t0 = time.perf_counter()
+        o.search_range(D, se.slo_latency_us, se.slo_accuracy, se.prune_cap, 0, n2, threads=nthreads)
+        dt = time.perf_counter() - t0
+        return n2, dt
+
+    n1, dt1 = timed(1, seconds_target / 3)
+    n2, dt = timed(threads, seconds_target)
     return {"value": n2 / dt, "unit": "candidates/s", "cores": threads, "kind": "oracle",
             "sample": f"first {n2} candidates of demand level 0 ({D} mrps) of the same workload, "
-                      f"{dt:.1f} s"}
+                      f"{dt:.1f} s",
+            "all_threads": {"value": n2 / dt, "cores": threads},
+            "single_thread": {"value": n1 / dt1, "cores": 1,
+                              "sample": f"first {n1} candidates of the same level, {dt1:.1f} s"}}
+
+
+def thinning_loss(jsv_mod, w, mixtures: bool):
+    """What the prune cap costs (the thinning is a lossy rule of this library, not the paper's):
+    the same sweep with the workload's cap and with a cap that never thins (single tuples: C; the
+    exact front is then searched) - for mixtures, where no cap holds every option, cap 16 against
+    cap 36 - and the per-level cost gap."""
+    pb, se = w.problems[0], w.searches[0]
+    j = jsv_mod.Jsv(device=0)
+    if mixtures:
+        j.set_mixtures(True)
+    j.load(pb)
+    lo_cap, hi_cap = (16, 36) if mixtures else (se.prune_cap, pb.C)
+    a, sa = j.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, lo_cap)
+    b, sb = j.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, hi_cap)
+    j.close()
+    gaps = []
+    for l, (x, y) in enumerate(zip(a, b)):
+        gaps.append({"level": l, "demand_mrps": int(se.demand_mrps[l]),
+                     "cost_capped": x.cost if x.feasible else None, "cost_reference": y.cost if y.feasible else None,
+                     "thinned": bool(x.flags & 1), "reference_thinned": bool(y.flags & 1)})
+    both = [(g["cost_capped"], g["cost_reference"]) for g in gaps if g["cost_capped"] is not None and g["cost_reference"] is not None]
+    return {"cap": lo_cap, "reference_cap": hi_cap, "reference_is_exact_front": not any(g["reference_thinned"] for g in gaps),
+            "levels_feasible_capped": sum(g["cost_capped"] is not None for g in gaps),
+            "levels_feasible_reference": sum(g["cost_reference"] is not None for g in gaps),
+            "levels_costlier_when_capped": sum(x > y for x, y in both),
+            "levels_cheaper_when_capped": sum(x < y for x, y in both),
+            "max_relative_cost_gap": max([(x - y) / y for x, y in both], default=0.0),
+            "candidates_capped": sum(r.evaluated for r in a), "candidates_reference": sum(r.evaluated for r in b),
+            "ms_capped": sa.seconds_device * 1e3, "ms_reference": sb.seconds_device * 1e3,
+            "max_demand_capped": sa.max_demand_mrps, "max_demand_reference": sb.max_demand_mrps,
+            "per_level": gaps}
 
 
 def main():
@@ -154,6 +222,14 @@ def main():
                     help="skip the second, bounded leg (for profiles of the plain enumeration alone)")
     ap.add_argument("--mixtures", action="store_true",
                     help="let a task run two tuples side by side (Eq. 9, 10); needs a pruned single-system workload")
+    ap.add_argument("--no-peak-probe", action="store_true",
+                    help="skip the microbenchmark of the vector ALUs' sustained issue rate")
+    ap.add_argument("--peak-probe", action="store_true", help="(default) run that microbenchmark")
+    ap.add_argument("--no-other-seeds", action="store_true",
+                    help="default workload only: skip the one timed step each for seeds 1-3")
+    ap.add_argument("--exact-front", action="store_true",
+                    help="also report what the prune cap costs: the sweep at the workload's cap against a cap that "
+                         "never thins (with --mixtures: cap 16 against cap 36), per-level cost gap")
     ap.add_argument("--objective", action="store_true",
                     help="maximise alpha*A_obj - beta*cost (alpha 1, beta 0.035) instead of minimum cost")
     args = ap.parse_args()
@@ -239,6 +315,31 @@ def main():
                        "candidates_scored_per_step": min(summ_b.candidates_visited, sum(r.evaluated for r in res_b)),
                        "same_results_as_plain_enumeration": same}
 
+    other_seeds = None
+    if (args.workload == "xr8" and not args.no_other_seeds and not batch and factors is None
+            and not args.mixtures and not args.objective and not args.bounds and not args.graph):
+        # the same configuration on the other seeds of the workload: one warm-up, one timed step each
+        other_seeds = {}
+        for sd in (1, 2, 3):
+            if sd == args.seed:
+                continue
+            w2 = workloads.BENCH_WORKLOADS[args.workload](seed=sd)
+            pb2, se2 = w2.problems[0], w2.searches[0]
+            cap2 = args.prune_cap if args.prune_cap is not None else se2.prune_cap
+            j.set_bounds(False)
+            j.load(pb2)
+            j.search(se2.demand_mrps, se2.slo_latency_us, se2.slo_accuracy, cap2)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            r2, s2 = j.search(se2.demand_mrps, se2.slo_latency_us, se2.slo_accuracy, cap2)
+            torch.cuda.synchronize()
+            dt2 = time.perf_counter() - t2
+            n2 = sum(r.evaluated for r in r2)
+            other_seeds[str(sd)] = {"candidates_per_step": n2, "ms_per_step": dt2 * 1e3, "candidates_per_s": n2 / dt2,
+                                    "enumerate_kernel_ms": s2.seconds_enumerate * 1e3,
+                                    "feasible_levels": sum(1 for r in r2 if r.feasible),
+                                    "max_serviceable_demand_mrps": s2.max_demand_mrps}
+
     candidates = sum(r.evaluated for r in res)
     ms_per_step = wall / args.steps * 1e3
     enum_avg = sum(enum_s) / len(enum_s) or sum(dev_s) / len(dev_s)     # graph mode times the whole replay
@@ -277,8 +378,20 @@ def main():
                      "device_ms_all_kernels": sum(dev_s) / len(dev_s) * 1e3},
         "context": PAPER_CONTEXT,
     }
+    key = (args.workload, args.seed, args.objective, args.mixtures, bool(args.bounds))
+    if key in MEASURED_COUNTERS and args.prune_cap is None:
+        out["roofline"]["counters"] = MEASURED_COUNTERS[key]
+    if not args.no_peak_probe:
+        probe = peak_probe()
+        out["roofline"]["peak_measured"] = probe
+        if probe and probe.get("v_add_u32"):
+            out["roofline"]["frac_of_measured_peak"] = achieved / (probe["v_add_u32"] * 1e12)
+    if other_seeds is not None:
+        out["config"]["other_seeds"] = other_seeds
     if with_bounds is not None:
         out["with_bounds"] = with_bounds
+    if args.exact_front and not batch and factors is None:
+        out["thinning_loss"] = thinning_loss(jsv, w, args.mixtures)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.objective, factors, args.mixtures)
     j.close()

@@ -187,6 +187,17 @@ JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial
 JSV_API int jsv_set_bounds(jsv_ctx* ctx, int on);
 
 /*
+ * Launch geometry of the enumeration, for tuning and for tests that the result does not depend
+ * on it (the arg-min is a minimum over a total order, so it must not).  blocks_per_cu: resident
+ * 256-lane blocks per compute unit, 1..8, capped by what the kernel's registers and LDS allow;
+ * 0 = as many as fit (up to 8).  lanes_percent: scales the number of lanes the planner tries to
+ * keep busy per demand level, which decides how many leading tasks a lane loops over and how
+ * the outermost of those loops is cut into tiles; 1..1600, 0 or 100 = the default.
+ * Errors: JSV_E_NULL; JSV_E_BADARG (out of range).
+ */
+JSV_API int jsv_set_geometry(jsv_ctx* ctx, int blocks_per_cu, int lanes_percent);
+
+/*
  * Mixtures of two tuples per task (Section 3.2: Eq. 2, 6, 7 with two active instance types and
  * the throughput-weighted task accuracy of Eq. 9, 10).  on != 0: besides replicating one tuple
  * a task may run m1 >= 1 replicas of tuple c1 and m2 >= 1 of tuple c2 (c1 < c2), where

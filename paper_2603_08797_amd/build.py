@@ -14,6 +14,19 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall"]
 
 
+PROBE_LIB = os.path.join(HERE, "libjsv_probe.so")
+PROBE_SRC = os.path.join(CSRC, "peak_probe.hip")
+
+
+def build_probe(force: bool = True) -> str:
+    """The VALU peak microbenchmark of bench.py --peak-probe: a library of its own."""
+    if not force and os.path.exists(PROBE_LIB) and os.path.getmtime(PROBE_LIB) >= os.path.getmtime(PROBE_SRC):
+        return PROBE_LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    subprocess.check_call([hipcc] + FLAGS + ["-x", "hip", PROBE_SRC, "-shared", "-o", PROBE_LIB])
+    return PROBE_LIB
+
+
 def build(force: bool = True) -> str:
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
     deps = srcs + [os.path.join(CSRC, h) for h in HEADERS]
@@ -27,3 +40,4 @@ def build(force: bool = True) -> str:
 
 if __name__ == "__main__":
     print(build())
+    print(build_probe())

@@ -158,6 +158,11 @@ struct Instance {
     uint16_t held[MAXT];
     uint32_t min_x_cost;      // cheapest entry of the innermost position (plan kernel)
     uint32_t min_xy_cost;     // plus the cheapest entry of the position above it (if looped in-lane)
+    // for the rebalancing of tile sizes once all instances are planned
+    uint32_t ko;              // extent of the chunked loop: digits of position n_in-1, or quads of the stream
+    uint32_t unit_cost;       // candidates per lane and unit of that loop (clamped)
+    uint32_t tile_cost;       // candidates per lane and tile = chunk * unit_cost (clamped)
+    uint32_t splittable;      // 1: chunk may still be lowered (not when the stream itself is chunked)
 };
 
 // Result record as written by the finalize kernel; same layout as jsv_result.
@@ -180,11 +185,15 @@ struct SummaryRec {
     uint64_t total_tiles;     // written by the scan kernel
     uint32_t done_count;      // finalize blocks finished
     uint32_t any_flags;       // OR of all instance flags
-    unsigned long long next_tile;   // work counter of the enumeration kernel
+    unsigned long long next_tile;   // work counter of the enumeration kernel: first tile not handed out yet
     uint32_t plan_done;       // plan blocks finished
     uint32_t bounded;         // 1: the enumeration kernel with bounds does the work, 0: the plain one
                               //    (set by the scan: bounds only pay when a block sees many tiles)
     unsigned long long visited;     // entries of the innermost position that waves went through
+    uint32_t own_tiles;       // tiles of one run that a block of the enumeration takes by its index
+    uint32_t own_rounds;      // rounds of such runs: round r, block b starts at (r * blocks + b) * own_tiles
+    uint32_t batch_tiles;     // tiles per ticket of the work counter afterwards; 0: no tickets at all
+    uint32_t pad3;
 };
 
 // Everything the kernels need to find their data; passed by value.  Every member has a
@@ -208,7 +217,7 @@ struct Plan {
     uint32_t objective = 0;       // 0: cheapest feasible; 1: largest alpha*A_obj - beta*cost (Eq. 14)
     uint32_t mix = 0;             // 1: a task may run two tuples side by side (Eq. 2, 6, 7, 9, 10)
     uint32_t bounds = 0;          // 1: skip what latency and capacity bounds exclude; 0: issue every candidate's tests
-    uint32_t pad2 = 0;
+    uint32_t cut = 0;             // 1: an instance whose cheapest entries together exceed S_avail gets no tiles
     // mixture mode: per (instance, task) a grid of cells (cost 0..S_avail) x (latency class),
     // mix_cells entries each
     uint64_t* cell_acc = nullptr;  // best accuracy seen in the cell (bits of a positive double, 0 = empty)
@@ -219,6 +228,7 @@ struct Plan {
     // bounds on: per instance the largest total cost still of interest: S_avail at first, then
     // the cost of the cheapest candidate found so far that meets both SLOs (cost modes only)
     uint32_t* bound = nullptr;     // [n_inst]
+    uint64_t* tile_begin = nullptr; // [n_inst] first global tile of every instance, for the search by tile
 };
 
 }  // namespace jsv

@@ -57,7 +57,7 @@ struct Search {               // per-instance search parameters (batch mode keep
 struct Layout {               // offsets into the workspace
     size_t inst, entries, rep, cost, k32, quads, partial, partial_obj, results, summary, eval, total;
     size_t cell_acc, cell_id, cell_pm, cell_list;     // mixture mode only
-    size_t bound;
+    size_t bound, tile_begin;
 };
 
 }  // namespace
@@ -80,6 +80,8 @@ struct jsv_ctx {
     bool space_a = true, space_s = true, space_t = true;   // ablation switches
     bool mix = false;                  // mixtures of two tuples per task
     bool bounds = true;                // skip lanes and waves that latency / capacity bounds exclude
+    int geo_blocks = 0;                // launch geometry overrides (jsv_set_geometry), 0 = automatic
+    int geo_lanes_percent = 0;
     int objective = 0;                 // Eq. 14 mode and weights
     double alpha = 1.0, beta = 0.035;
 
@@ -462,6 +464,7 @@ Layout make_layout(uint32_t n_inst, uint32_t t_max, uint32_t k_max, uint32_t c_m
     L.results = off; off = align_up(off + sizeof(jsv::ResultRec) * n_inst);
     L.summary = off; off = align_up(off + sizeof(jsv::SummaryRec));
     L.bound = off;   off = align_up(off + sizeof(uint32_t) * n_inst);
+    L.tile_begin = off; off = align_up(off + sizeof(uint64_t) * n_inst);
     L.eval = off;    // index u64, latency u32, replicas u32*T, cost i32, accuracy f64, mask u8, bad u32
     off = align_up(off + (size_t)n_eval * (8 + 4 + 4 * MAXT + 4 + 8 + 1) + 6 * ALIGN);
     const size_t blocks = (size_t)n_inst * t_max;
@@ -511,6 +514,7 @@ jsv::Plan make_plan(const jsv_ctx* ctx, const void* graphs, const Layout& L, uns
     pl.results = (jsv::ResultRec*)(ws + L.results);
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
     pl.bound = (uint32_t*)(ws + L.bound);
+    pl.tile_begin = (uint64_t*)(ws + L.tile_begin);
     pl.n_inst = n_inst; pl.t_max = t_max; pl.k_max = k_max; pl.c_max = c_max;
     pl.objective = (uint32_t)ctx->objective;
     if (mix_cells != 0) {
@@ -546,7 +550,9 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     unsigned char* ws = nullptr;
     const void* graphs = ctx->d_problems;
     const size_t in_bytes = sizeof(Instance) * n;
-    const size_t out_bytes = sizeof(jsv::ResultRec) * n + sizeof(jsv::SummaryRec);
+    // result records and the summary are neighbours in the workspace: one copy brings both
+    const size_t res_bytes = L.summary - L.results;             // the records, padded to the summary's offset
+    const size_t out_bytes = res_bytes + sizeof(jsv::SummaryRec);
     unsigned char* pin_in = (unsigned char*)inst.data();
     unsigned char* pin_out = nullptr;
     int rc = JSV_OK;
@@ -567,17 +573,36 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
     }
 
     jsv::Plan pl = make_plan(ctx, graphs, L, ws, n, t_max, k_max, c_max, mix_cells);
-    pl.bounds = ctx->bounds ? 1u : 0u;
-    const int mode = jsv::enumerate_mode(ctx->objective != 0, pl.mix != 0) * 2 + (ctx->bounds ? 1 : 0);
+    // Bounds pay only when a block sees many tiles (the device decides that from the real tile
+    // count).  Where even an upper estimate of the tiles - every list full, 64 candidates per
+    // lane and tile - stays below that, the variant with bounds is not launched at all.  Instances
+    // that no candidate can fit are still dropped at plan time (cut).
+    bool with_bounds = ctx->bounds;
+    if (with_bounds) {
+        double most = 0.0;
+        for (uint32_t k = 0; k < n; ++k) {
+            const HostProblem& hp = ctx->batch_mode ? ctx->batch[inst[k].problem] : ctx->single;
+            const double kk = mix_cells ? (double)k_max : (double)k_max_of(hp, inst[k].cap);
+            most += std::pow(kk, (double)hp.T) / (64.0 * jsv::TILE_LANES) + 1.0;
+        }
+        if (most < (double)ctx->grid * 32.0) with_bounds = false;
+    }
+    pl.bounds = with_bounds ? 1u : 0u;
+    pl.cut = ctx->bounds ? 1u : 0u;
+    const int mode = jsv::enumerate_mode(ctx->objective != 0, pl.mix != 0) * 2 + (with_bounds ? 1 : 0);
     if (ctx->occ_t != t_max || ctx->occ_k != k_max || ctx->occ_obj != mode) {
         int blocks = 0;
-        HIP_TRY(ctx, jsv::enumerate_blocks_per_cu(t_max, k_max, mode / 2, ctx->bounds, &blocks));
+        HIP_TRY(ctx, jsv::enumerate_blocks_per_cu(t_max, k_max, mode / 2, with_bounds, &blocks));
         ctx->occ_t = t_max; ctx->occ_k = k_max; ctx->occ_obj = mode; ctx->occ_blocks = blocks;
     }
     const int per_cu = ctx->occ_blocks;
     if (per_cu < 1) return JSV_E_BADARG;
-    pl.grid = ctx->cus * (uint32_t)std::min(per_cu, 8);     // everything launched is resident
-    const uint64_t lanes = (uint64_t)ctx->grid * jsv::TILE_LANES * 2 / n;
+    int blocks = std::min(per_cu, 8);                        // everything launched is resident
+    if (ctx->geo_blocks > 0) blocks = std::min(blocks, ctx->geo_blocks);
+    pl.grid = ctx->cus * (uint32_t)blocks;
+    // lanes the planner tries to keep busy per instance: all that can be resident, shared evenly
+    uint64_t lanes = (uint64_t)ctx->grid * jsv::TILE_LANES / n;
+    if (ctx->geo_lanes_percent > 0) lanes = lanes * (uint64_t)ctx->geo_lanes_percent / 100u;
     pl.lanes_wanted = (uint32_t)std::max<uint64_t>(64, std::min<uint64_t>(lanes, 0x7FFFFFFF));
 
     hipStream_t st = ctx->stream;
@@ -595,9 +620,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
             if (e == hipSuccess) e = jsv::launch_prune_plan_scan(pl, st);
             if (e == hipSuccess) e = jsv::launch_enumerate(pl, st);
             if (e == hipSuccess) e = jsv::launch_finalize(pl, st);
-            if (e == hipSuccess) e = hipMemcpyAsync(pin_out, pl.results, sizeof(jsv::ResultRec) * n, hipMemcpyDeviceToHost, st);
-            if (e == hipSuccess) e = hipMemcpyAsync(pin_out + sizeof(jsv::ResultRec) * n, pl.summary,
-                                                    sizeof(jsv::SummaryRec), hipMemcpyDeviceToHost, st);
+            if (e == hipSuccess) e = hipMemcpyAsync(pin_out, pl.results, out_bytes, hipMemcpyDeviceToHost, st);
             hipGraph_t g = nullptr;
             const hipError_t e2 = hipStreamEndCapture(st, &g);       // always leave capture mode
             if (e != hipSuccess || e2 != hipSuccess) {
@@ -631,13 +654,11 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
         HIP_TRY(ctx, hipEventRecord(ctx->ev[2], st));
         HIP_TRY(ctx, jsv::launch_finalize(pl, st));
         HIP_TRY(ctx, hipEventRecord(ctx->ev[3], st));
-        HIP_TRY(ctx, hipMemcpyAsync(pin_out, pl.results, sizeof(jsv::ResultRec) * n, hipMemcpyDeviceToHost, st));
-        HIP_TRY(ctx, hipMemcpyAsync(pin_out + sizeof(jsv::ResultRec) * n, pl.summary, sizeof(jsv::SummaryRec),
-                                    hipMemcpyDeviceToHost, st));
+        HIP_TRY(ctx, hipMemcpyAsync(pin_out, pl.results, out_bytes, hipMemcpyDeviceToHost, st));
     }
     HIP_TRY(ctx, hipStreamSynchronize(st));
 
-    if (!sa) std::memcpy(&sr, pin_out + sizeof(jsv::ResultRec) * n, sizeof sr);
+    if (!sa) std::memcpy(&sr, pin_out + res_bytes, sizeof sr);
     if (sr.any_flags & jsv::F_OVERFLOW) return JSV_E_OVERFLOW;
     if (sr.any_flags & jsv::F_MISMATCH) return JSV_E_INTERNAL;
     if (!sa) std::memcpy(out, pin_out, sizeof(jsv::ResultRec) * n);
@@ -654,7 +675,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
         summary->max_demand_mrps = sr.max_demand;
         summary->seconds_device = ms_all * 1e-3;
         summary->seconds_enumerate = ms_enum * 1e-3;
-        if (ctx->bounds && sr.bounded) summary->candidates_visited = (uint64_t)sr.visited * 64u;
+        if (with_bounds && sr.bounded) summary->candidates_visited = (uint64_t)sr.visited * 64u;
         else summary->candidates_visited = enumerated;     // the plain kernel issues every candidate's tests
     }
     return JSV_OK;
@@ -1007,6 +1028,15 @@ JSV_API int jsv_set_bounds(jsv_ctx* ctx, int on)
 {
     if (!ctx) return JSV_E_NULL;
     ctx->bounds = on != 0;
+    return JSV_OK;
+}
+
+JSV_API int jsv_set_geometry(jsv_ctx* ctx, int blocks_per_cu, int lanes_percent)
+{
+    if (!ctx) return JSV_E_NULL;
+    if (blocks_per_cu < 0 || blocks_per_cu > 8 || lanes_percent < 0 || lanes_percent > 1600) return JSV_E_BADARG;
+    ctx->geo_blocks = blocks_per_cu;
+    ctx->geo_lanes_percent = lanes_percent;
     return JSV_OK;
 }
 

@@ -581,60 +581,173 @@ __global__ void __launch_bounds__(256) mix_kernel(Plan pl)
     }
 }
 
-// Tiles per ticket of the enumeration kernel's work counter: about 128 tickets per block,
-// so that the counter is touched less often and the tail stays below one percent.
-__device__ __forceinline__ uint32_t tiles_per_ticket(uint64_t total_tiles, uint32_t grid)
-{
-    const uint64_t b = total_tiles / ((uint64_t)grid * 128u);
-    return b < 1 ? 1u : (b > 64 ? 64u : (uint32_t)b);
-}
+// How the enumeration's blocks share the tiles.  Tiles can go out by index, without any
+// atomic, in rounds - in round r block b takes the run of OWN tiles that starts at
+// (r * blocks + b) * OWN, so that all blocks move through the tile order together - or through
+// one global counter, in batches.  Measured on the 20^8 sweep and on the batch of graphs:
+//  * Atomics on one address go through one at a time, about 10 ns each.  A search with few
+//    tiles per block spends longer waiting for tickets than working: it is shared out by
+//    index alone.
+//  * When every candidate is scored, tiles of one instance cost the same, but equal shares by
+//    index still end unevenly: with 7 waves on a SIMD the vector ALU is saturated by about 5
+//    and the waves launched last get what is left, so they finish their equal share late and
+//    alone (34 ms with the counter against 47 ms by index on a quarter of the sweep).  There
+//    the counter hands out everything, in 128 batches per block.
+//  * With bounds, most tiles are excluded at once and the counter itself is the limit (tens
+//    of tickets per microsecond): a quarter goes out by index and the rest in 8 batches per
+//    block (9.1 ms against 16.6 ms for the sweep).
+// Giving every block one long contiguous run was tried too and is slower still: seven blocks of
+// a compute unit then stream seven instances' tables through one scalar cache.
+constexpr uint32_t STATIC_ONLY_TILES_PER_BLOCK = 8;   // up to here: no counter at all
+constexpr uint32_t ROUNDS_WANTED = 64;                // with bounds: rounds the part shared out by index is cut into
+constexpr uint32_t BATCHES_PER_BLOCK_PLAIN = 128;     // batches per block from the counter, every candidate scored
+constexpr uint32_t BATCHES_PER_BLOCK_BOUNDED = 8;     // ... and with bounds
 
 // ---- plan -------------------------------------------------------------------------------
 constexpr uint32_t BOUNDS_MIN_TILES_PER_BLOCK = 32;
+// Balancing of the tile sizes (scan_tiles): the enumeration's blocks should each see about this
+// many tiles, but no tile is cut below MIN_TILE_COST candidates per lane, where the per-tile
+// set-up would start to show.
+constexpr uint32_t TILES_PER_BLOCK_WANTED = 16;
+constexpr uint32_t MIN_TILE_COST = 2048;
 
-// Exclusive scan of the tile counts over the instances, total, counters reset; run by
-// the last plan block to finish.
+__device__ __forceinline__ uint32_t bits_of(uint64_t x) { return x ? 64u - (uint32_t)__builtin_clzll(x) : 0u; }
+
+// Exclusive prefix sum of a[0..n) (n <= 256 * 8) in place, by all 256 threads of the block;
+// returns the total.  s_part: 256 words of scratch.
+__device__ uint32_t block_exclusive_scan(uint32_t* a, uint32_t n, uint32_t* s_part)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint32_t per = (n + 255) / 256;
+    const uint32_t lo = tid * per, hi = lo + per < n ? lo + per : n;
+    uint32_t sum = 0;
+    for (uint32_t k = lo; k < hi; ++k) sum += a[k];
+    s_part[tid] = sum;
+    __syncthreads();
+    for (uint32_t off = 1; off < 256; off <<= 1) {      // inclusive scan of the 256 partial sums
+        const uint32_t v = tid >= off ? s_part[tid - off] : 0u;
+        __syncthreads();
+        s_part[tid] += v;
+        __syncthreads();
+    }
+    uint32_t run = s_part[tid] - sum;
+    const uint32_t total = s_part[255];
+    for (uint32_t k = lo; k < hi; ++k) { const uint32_t v = a[k]; a[k] = run; run += v; }
+    __syncthreads();
+    return total;
+}
+
+// Exclusive prefix of v over the 256 threads of the block, and the total.  s: 256 words of scratch.
+__device__ uint64_t block_scan_u64(uint64_t v, uint64_t* s, uint64_t* total)
+{
+    const uint32_t tid = threadIdx.x;
+    s[tid] = v;
+    __syncthreads();
+    for (uint32_t off = 1; off < 256; off <<= 1) {
+        const uint64_t x = tid >= off ? s[tid - off] : 0;
+        __syncthreads();
+        s[tid] += x;
+        __syncthreads();
+    }
+    const uint64_t incl = s[tid];
+    *total = s[255];
+    __syncthreads();
+    return incl - v;
+}
+
+// Run by the last plan block to finish: the global view.  Tiles that are much larger than the
+// average share of a block are cut into smaller ones (fewer digits of the outermost in-lane
+// loop per tile), so that blocks end together also when a few instances hold most of the work;
+// then the exclusive scan of the tile counts, the total, and the counters' reset.
 __device__ void scan_tiles(const Plan& pl, uint64_t* s_sum)
 {
     const uint32_t tid = threadIdx.x, n = pl.n_inst;
     const uint32_t per = (n + 255) / 256;
     const uint32_t lo = tid * per, hi = (lo + per < n) ? lo + per : n;
     const volatile Instance* inst = pl.inst;          // written by other blocks
+    uint64_t work = 0;
+    for (uint32_t k = lo; k < hi; ++k) {
+        const uint32_t tiles = inst[k].tiles, cost = inst[k].tile_cost;      // independent loads, one round trip
+        work += (uint64_t)tiles * cost;
+    }
+    uint64_t total_work;
+    (void)block_scan_u64(work, s_sum, &total_work);
+    uint64_t target = total_work / ((uint64_t)pl.grid * TILES_PER_BLOCK_WANTED);
+    if (target < MIN_TILE_COST) target = MIN_TILE_COST;
     uint64_t sum = 0;
-    for (uint32_t k = lo; k < hi; ++k) sum += inst[k].tiles;
-    s_sum[tid] = sum;
-    __syncthreads();
+    for (uint32_t k = lo; k < hi; ++k) {
+        Instance* in = pl.inst + k;
+        uint32_t tiles = inst[k].tiles, cost = inst[k].tile_cost;
+        const uint32_t chunk = inst[k].chunk, unit = inst[k].unit_cost;
+        if (tiles != 0 && inst[k].splittable && cost > target && chunk > 1) {
+            uint64_t c = target / (unit ? unit : 1u);           // digits per tile that stay within the target
+            if (c < 1) c = 1;
+            if (c < chunk) {
+                const uint32_t ko = inst[k].ko, n_chunks = (ko + (uint32_t)c - 1) / (uint32_t)c;
+                if ((uint64_t)inst[k].n_groups * n_chunks <= 0x7FFFFFFFull) {
+                    const uint64_t tc = c * unit;
+                    cost = tc > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)tc;
+                    tiles = inst[k].n_groups * n_chunks;
+                    in->chunk = (uint32_t)c; in->n_chunks = n_chunks;
+                    in->tiles = tiles; in->tile_cost = cost;
+                }
+            }
+        }
+        sum += tiles;
+    }
+    uint64_t total_tiles;
+    uint64_t run = block_scan_u64(sum, s_sum, &total_tiles);
+    for (uint32_t k = lo; k < hi; ++k) { pl.inst[k].tile_begin = run; pl.tile_begin[k] = run; run += inst[k].tiles; }
     if (tid == 0) {
-        uint64_t run = 0;
-        for (uint32_t k = 0; k < 256; ++k) { const uint64_t v = s_sum[k]; s_sum[k] = run; run += v; }
-        pl.summary->total_tiles = run;
+        pl.summary->total_tiles = total_tiles;
         pl.summary->done_count = 0;
-        // the first ticket of every block is its own index: the counter starts behind those
-        pl.summary->next_tile = (unsigned long long)pl.grid * tiles_per_ticket(run, pl.grid);
         pl.summary->any_flags = 0;
         pl.summary->visited = 0;
         // A cost bound found in one tile helps the tiles that start after it: with only a few
         // tiles per block everything runs at once and the bookkeeping would be pure overhead.
-        pl.summary->bounded = (pl.bounds && run >= (uint64_t)pl.grid * BOUNDS_MIN_TILES_PER_BLOCK) ? 1u : 0u;
+        const bool bounded = pl.bounds && total_tiles >= (uint64_t)pl.grid * BOUNDS_MIN_TILES_PER_BLOCK;
+        pl.summary->bounded = bounded ? 1u : 0u;
+        // Rounds of own runs, then batches of the rest from the counter (see above).
+        const uint64_t G = pl.grid;
+        uint64_t own = 1, rounds = 0, batch;
+        if (total_tiles <= G * STATIC_ONLY_TILES_PER_BLOCK) { rounds = (total_tiles + G - 1) / G; batch = 0; }
+        else {
+            if (bounded) {
+                own = total_tiles / (4 * G * ROUNDS_WANTED);
+                if (own < 1) own = 1;
+                if (own > 0x40000000ull) own = 0x40000000ull;
+                rounds = total_tiles / 4 / (G * own);
+            }
+            batch = (total_tiles - rounds * G * own) / (G * (bounded ? BATCHES_PER_BLOCK_BOUNDED : BATCHES_PER_BLOCK_PLAIN));
+            if (batch < 1) batch = 1;
+            if (batch > 0x40000000ull) batch = 0x40000000ull;
+        }
+        pl.summary->own_tiles = (uint32_t)own;
+        pl.summary->own_rounds = (uint32_t)rounds;               // (at most 8 or about 64)
+        pl.summary->batch_tiles = (uint32_t)batch;
+        const uint64_t first = rounds * G * own;                 // the counter starts behind the rounds
+        pl.summary->next_tile = (unsigned long long)(first < total_tiles ? first : total_tiles);
         pl.summary->best_level = -1;
         pl.summary->max_demand = 0;
     }
-    __syncthreads();
-    uint64_t run = s_sum[tid];
-    for (uint32_t k = lo; k < hi; ++k) { pl.inst[k].tile_begin = run; run += inst[k].tiles; }
 }
 
 // One block per instance: strides of the caller's index order, key packing, choice
 // of how many positions a lane loops over, tile geometry, local keys and the stream
 // of the innermost position, reset of the partials.  The last block to finish scans
 // the tile counts (plan_done is zeroed by the prune kernel, which runs before).
+//
+// Written for latency (one small instance is often all there is): every pass over the
+// entries covers all tasks at once (one round trip to memory instead of one per task), the
+// quads of the innermost stream are laid out by a parallel scan, and what only one thread
+// can decide is kept short.
 __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
 {
     const uint32_t i = blockIdx.x, tid = threadIdx.x;
     Instance* in = pl.inst + i;
     const Graph* g = pl.graphs + in->problem;
     const uint32_t T = g->T;
-    __shared__ uint32_t s_maxcost[MAXT], s_mincost[MAXT], s_K[MAXT], s_minxlat;
+    __shared__ uint32_t s_maxcost[MAXT], s_mincost[MAXT], s_K[MAXT], s_off[MAXT + 1], s_lsT[MAXT], s_minxlat;
     __shared__ uint32_t s_bits, s_lb, s_nin, s_ls[3], s_chunk, s_nq, s_last;
     __shared__ uint64_t s_stride[MAXT];
     // the innermost position's entries, staged once: variant, latency, cost, and the first
@@ -642,27 +755,51 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     __shared__ uint16_t s_xvar[MAXC];
     __shared__ uint32_t s_xlat[MAXC], s_xcost[MAXC], s_xq0[MAXC];
     __shared__ uint64_t s_sum[256];
-    if (tid < MAXT) { s_maxcost[tid] = 0; s_mincost[tid] = 0xFFFFFFFFu; s_K[tid] = tid < T ? in->K[tid] : 0; }
+    __shared__ uint32_t s_part[256];
+    // graph facts the single-thread section below needs, fetched by many threads at once
+    __shared__ uint32_t s_task_at[MAXT], s_capacity, s_PB;
+    if (tid < MAXT) {
+        s_maxcost[tid] = 0; s_mincost[tid] = 0xFFFFFFFFu; s_K[tid] = tid < T ? in->K[tid] : 0; s_lsT[tid] = 0xFFFFFFFFu;
+        s_task_at[tid] = g->task_at[tid];
+    }
+    if (tid == 32) s_capacity = g->capacity;
+    if (tid == 33) s_PB = g->P * g->B;
     if (tid == 0) s_minxlat = 0xFFFFFFFFu;
     __syncthreads();
-    const uint32_t tx = g->task_at[0], PB = g->P * g->B, KX = s_K[tx];
-    for (uint32_t t = 0; t < T; ++t) {
-        const Entry* e = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
-        uint32_t m = 0, mn = 0xFFFFFFFFu, ml = 0xFFFFFFFFu;
-        for (uint32_t d = tid; d < s_K[t]; d += blockDim.x) {
-            const uint32_t c = e[d].cost;
-            m = umax(m, c);
-            mn = c < mn ? c : mn;
-            if (t == tx) {
-                s_xcost[d] = c; s_xlat[d] = e[d].lat; s_xvar[d] = (uint16_t)(e[d].choice / PB);
-                ml = e[d].lat < ml ? e[d].lat : ml;
-            }
+    if (tid == 0) { uint32_t run = 0; for (uint32_t t = 0; t < T; ++t) { s_off[t] = run; run += s_K[t]; } s_off[T] = run; }
+    __syncthreads();
+    const uint32_t tx = s_task_at[0], PB = s_PB, KX = s_K[tx], n_all = s_off[T];
+    const Entry* ent = pl.entries + (size_t)i * pl.t_max * pl.k_max;
+    // pass 1, all tasks at once: cost range per task; the innermost position's entries staged
+    for (uint32_t f = tid; f < n_all; f += blockDim.x) {
+        uint32_t t = 0;
+        while (t + 1 < T && s_off[t + 1] <= f) ++t;
+        const uint32_t d = f - s_off[t];
+        const Entry* e = ent + (size_t)t * pl.k_max + d;
+        const uint32_t c = e->cost;
+        atomicMax(&s_maxcost[t], c);
+        atomicMin(&s_mincost[t], c);
+        if (t == tx) {
+            const uint32_t lat = e->lat;
+            s_xcost[d] = c; s_xlat[d] = lat; s_xvar[d] = (uint16_t)(e->choice / PB);
+            atomicMin(&s_minxlat, lat);
         }
-        if (m) atomicMax(&s_maxcost[t], m);
-        if (mn != 0xFFFFFFFFu) atomicMin(&s_mincost[t], mn);
-        if (ml != 0xFFFFFFFFu) atomicMin(&s_minxlat, ml);
     }
     __syncthreads();
+    // quads of position 0's stream (single tuples): every variant's entries rounded up to whole
+    // quads.  The first digit of a variant counts its entries; an exclusive scan places it.
+    for (uint32_t d = tid; d < KX; d += blockDim.x) {
+        uint32_t q = 0;
+        if (d == 0 || s_xvar[d - 1] != s_xvar[d]) {
+            const uint32_t var = s_xvar[d];
+            uint32_t d1 = d + 1;
+            while (d1 < KX && s_xvar[d1] == var) ++d1;
+            q = (d1 - d + 3) / 4;
+        }
+        s_xq0[d] = q;
+    }
+    __syncthreads();
+    const uint32_t nq_groups = block_exclusive_scan(s_xq0, KX, s_part);
     if (tid == 0) {
         uint64_t space = 1, cost_bound = 0;
         bool over = false;
@@ -675,11 +812,8 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             cost_bound += s_maxcost[t];
         }
         if (space >> 63) over = true;
-        uint32_t idx_bits = 0;
-        while (idx_bits < 63 && (space - 1) >> idx_bits) ++idx_bits;     // bits of space-1
-        if (space <= 1) idx_bits = 0;
-        uint32_t cost_bits = 0;
-        while (cost_bits < 63 && cost_bound >> cost_bits) ++cost_bits;
+        const uint32_t idx_bits = space <= 1 ? 0u : bits_of(space - 1);
+        const uint32_t cost_bits = bits_of(cost_bound);
         if (cost_bound > 0x7FFFFFFFull || idx_bits + cost_bits > 63) over = true;
         if (over) { space = 0; atomicOr(&in->flags, F_OVERFLOW); }
         in->space = space;
@@ -687,16 +821,16 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         // Eq. 8 for the whole instance: if even the cheapest entry of every task together exceeds
         // S_avail, no candidate fits and nothing needs to be enumerated (bounds on only).
         bool none_fits = false;
-        if (pl.bounds && g->capacity != 0 && space != 0) {
+        if (pl.cut && s_capacity != 0 && space != 0) {
             uint64_t least = 0;
             for (uint32_t t = 0; t < T; ++t) least += s_mincost[t];
-            none_fits = least > g->capacity;
+            none_fits = least > s_capacity;
             if (none_fits) atomicOr(&in->flags, F_CUT);
         }
 
         // how many leading positions a lane loops over, and the tile geometry
         uint32_t Kp[MAXT];
-        for (uint32_t p = 0; p < T; ++p) Kp[p] = s_K[g->task_at[p]];
+        for (uint32_t p = 0; p < T; ++p) Kp[p] = s_K[s_task_at[p]];
         uint32_t n_in = 1;
         uint64_t s_out = 0;
         const uint32_t n_top = T < 3 ? T : 3;
@@ -714,38 +848,26 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         if (space != 0) {
             for (uint32_t a = 0; a < n_in; ++a)           // sort in-lane positions by task id
                 for (uint32_t b = a + 1; b < n_in; ++b)
-                    if (g->task_at[ord[b]] < g->task_at[ord[a]]) { const uint32_t x = ord[a]; ord[a] = ord[b]; ord[b] = x; }
+                    if (s_task_at[ord[b]] < s_task_at[ord[a]]) { const uint32_t x = ord[a]; ord[a] = ord[b]; ord[b] = x; }
             uint64_t ranks = 1, cost_in = 0;
             for (uint32_t a = 0; a < n_in; ++a) {
                 ls[ord[a]] = (uint32_t)ranks;
                 ranks *= Kp[ord[a]];
-                cost_in += s_maxcost[g->task_at[ord[a]]];
+                cost_in += s_maxcost[s_task_at[ord[a]]];
             }
-            while (lb < 32 && (ranks - 1) >> lb) ++lb;
-            uint32_t cb = 0;
-            while (cb < 32 && cost_in >> cb) ++cb;
+            lb = bits_of(ranks - 1);
+            const uint32_t cb = bits_of(cost_in);
             // (objective mode over mixtures: every entry has its own accuracy and so its own
             // objective; only the general per-candidate loop handles that)
             use32 = (ranks <= 0x7FFFFFFFull && lb + cb <= 31 && !(pl.mix && pl.objective)) ? 1u : 0u;
         }
-        if (use32 && pl.mix) nq = (KX + 3) / 4;             // one stream in latency order
-        else if (use32) {
-            // quads of position 0's stream: every variant's entries rounded up to whole quads
-            uint32_t d = 0;
-            while (d < KX) {
-                const uint32_t var = s_xvar[d];
-                uint32_t d1 = d;
-                while (d1 < KX && s_xvar[d1] == var) ++d1;
-                s_xq0[d] = nq;
-                nq += (d1 - d + 3) / 4;
-                d = d1;
-            }
-        }
-        uint32_t chunk = 1, n_chunks = 0, n_groups = 0;
+        if (use32) nq = pl.mix ? (KX + 3) / 4 : nq_groups;      // mixtures: one stream in latency order
+        uint32_t chunk = 1, n_chunks = 0, n_groups = 0, ko = 0;
+        uint64_t inner = 1;
+        const bool stream = use32 && n_in == 1;
         if (space != 0 && !none_fits) {
             // extent of the outermost in-lane loop: digits, or quads when it is the stream itself
-            const bool stream = use32 && n_in == 1;
-            uint64_t inner = stream ? 4 : 1;
+            inner = stream ? 4 : 1;
             for (uint32_t p = 0; p + 1 < n_in; ++p) inner *= Kp[p];
             const uint32_t Ko = stream ? nq : Kp[n_in - 1];
             uint64_t c = s_out >= pl.lanes_wanted ? Ko : (s_out * Ko) / pl.lanes_wanted;   // extent per tile that
@@ -755,6 +877,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             if (c > Ko) c = Ko;
             if (c < 1) c = 1;
             chunk = (uint32_t)c;
+            ko = Ko;
             n_chunks = (Ko + chunk - 1) / chunk;
             const uint64_t ng = (s_out + TILE_LANES - 1) / TILE_LANES;
             if (ng * n_chunks > 0x7FFFFFFFull) { atomicOr(&in->flags, F_OVERFLOW); n_chunks = 0; }
@@ -763,33 +886,50 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         in->n_in = n_in; in->s_out = s_out; in->chunk = chunk;
         in->n_chunks = n_chunks; in->n_groups = n_groups;
         in->tiles = n_groups * n_chunks;
+        // what scan_tiles needs to rebalance: candidates per lane of one tile and of one digit of
+        // its chunked loop (clamped), that loop's extent, and whether its cut may change (the
+        // stream's quads carry flags that depend on the cut)
+        const uint64_t tc = inner * chunk;
+        in->unit_cost = inner > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)inner;
+        in->tile_cost = tc > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)tc;
+        in->ko = ko;
+        in->splittable = stream ? 0u : 1u;
         in->use32 = use32; in->lb = lb; in->nq = nq;
         uint64_t min_in = 0;
-        for (uint32_t p = 0; p < n_in; ++p) min_in += s_mincost[g->task_at[p]];
+        for (uint32_t p = 0; p < n_in; ++p) min_in += s_mincost[s_task_at[p]];
         in->min_in_cost = (space != 0 && pl.bounds) ? (uint32_t)(min_in > 0xFFFFFFFFull ? 0xFFFFFFFFull : min_in) : 0u;
         in->min_x_lat = pl.bounds ? s_minxlat : 0u;
         in->min_x_cost = (space != 0 && pl.bounds) ? s_mincost[tx] : 0u;
-        in->min_xy_cost = (space != 0 && pl.bounds && n_in >= 2) ? s_mincost[tx] + s_mincost[g->task_at[1]] : 0u;
-        pl.bound[i] = g->capacity != 0 ? g->capacity : 0xFFFFFFFFu;
+        in->min_xy_cost = (space != 0 && pl.bounds && n_in >= 2) ? s_mincost[tx] + s_mincost[s_task_at[1]] : 0u;
+        pl.bound[i] = s_capacity != 0 ? s_capacity : 0xFFFFFFFFu;
         if (space != 0 && !use32) atomicOr(&in->flags, F_WIDE);
         for (int a = 0; a < 3; ++a) { in->ord[a] = ord[a]; s_ls[a] = ls[a]; }
+        if (use32) for (uint32_t p = 0; p < n_in; ++p) s_lsT[s_task_at[p]] = ls[p];
         s_bits = idx_bits; s_lb = lb; s_nin = use32 ? n_in : 0;
-        s_chunk = (use32 && n_in == 1) ? chunk : 0; s_nq = nq;
+        s_chunk = stream ? chunk : 0; s_nq = nq;
     }
     __syncthreads();
-    // packed keys: (cost << idx_bits) | digit * stride
-    const uint32_t idx_bits = s_bits;
-    for (uint32_t t = 0; t < T; ++t) {
-        Entry* e = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
-        const uint64_t stride = s_stride[t];
-        for (uint32_t d = tid; d < s_K[t]; d += blockDim.x)
-            e[d].key = ((uint64_t)e[d].cost << idx_bits) | ((uint64_t)d * stride);
+    // pass 2, all tasks at once: packed keys (cost << idx_bits) | digit * stride, and for the
+    // in-lane positions the 32-bit local keys (cost << lb) | digit * local stride
+    {
+        const uint32_t idx_bits = s_bits, lb = s_lb;
+        Entry* entw = pl.entries + (size_t)i * pl.t_max * pl.k_max;
+        uint32_t* k32 = pl.k32 + (size_t)i * pl.t_max * pl.k_max;
+        for (uint32_t f = tid; f < n_all; f += blockDim.x) {
+            uint32_t t = 0;
+            while (t + 1 < T && s_off[t + 1] <= f) ++t;
+            const uint32_t d = f - s_off[t];
+            Entry* e = entw + (size_t)t * pl.k_max + d;
+            const uint32_t c = e->cost;
+            e->key = ((uint64_t)c << idx_bits) | ((uint64_t)d * s_stride[t]);
+            if (s_lsT[t] != 0xFFFFFFFFu) k32[(size_t)t * pl.k_max + d] = (c << lb) | (d * s_lsT[t]);
+        }
     }
     // stream of position 0: by variant, inside a variant by ascending latency (so that the
     // lanes still feasible only shrink along a variant), each variant padded to whole quads
     if (s_nin != 0 && pl.mix) {
         // mixture mode: all entries in ascending latency, each with its own accuracy
-        const Entry* ex = pl.entries + ((size_t)i * pl.t_max + tx) * pl.k_max;
+        const Entry* ex = ent + (size_t)tx * pl.k_max;
         QuadM* qm = (QuadM*)(pl.quads + (size_t)i * pl.k_max);
         for (uint32_t d = tid; d < KX; d += blockDim.x) {
             const uint32_t lat = s_xlat[d];
@@ -805,7 +945,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             qm[r / 4].e[r % 4] = pad;
         }
     } else if (s_nin != 0) {
-        const Entry* ex = pl.entries + ((size_t)i * pl.t_max + tx) * pl.k_max;
+        const Entry* ex = ent + (size_t)tx * pl.k_max;
         Quad* qd = pl.quads + (size_t)i * pl.k_max;
         for (uint32_t d = tid; d < KX; d += blockDim.x) {
             const uint32_t var = s_xvar[d], lat = s_xlat[d];
@@ -829,13 +969,6 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
                 for (uint32_t r = n; r < quads * 4; ++r) { qd[q0 + r / 4].e[r % 4].lat = 0xFFFFFFFFu; qd[q0 + r / 4].e[r % 4].k32 = 0xFFFFFFFFu; }
             }
         }
-    }
-    // 32-bit local keys of the in-lane positions: (cost << lb) | digit * local stride
-    for (uint32_t p = 0; p < s_nin; ++p) {
-        const uint32_t t = g->task_at[p];
-        const Entry* e = pl.entries + ((size_t)i * pl.t_max + t) * pl.k_max;
-        uint32_t* k = pl.k32 + ((size_t)i * pl.t_max + t) * pl.k_max;
-        for (uint32_t d = tid; d < s_K[t]; d += blockDim.x) k[d] = (e[d].cost << s_lb) | (d * s_ls[p]);
     }
     for (uint32_t b = tid; b < pl.grid; b += blockDim.x) {
         pl.partial[(size_t)i * pl.grid + b] = NO_KEY;
@@ -1373,12 +1506,14 @@ __device__ __forceinline__ void flush_block(const Plan& pl, uint32_t inst, const
     }
 }
 
-// Persistent grid sized to what fits on the chip at once; a block starts with the
-// run of tiles of its own index and draws further runs from one atomic counter, so no block
-// waits for a second round and uneven tiles even out.  Tiles are ordered by instance and the counter only grows, so a block meets
-// the instances in ascending order; it keeps one running minimum per lane and
-// reduces it (wave, then block) only when the instance changes.  Every block ends
-// with the first ticket at or past the total.
+// Persistent grid sized to what fits on the chip at once; a block starts with the run of
+// tiles that is its own by its index and then draws batches from one atomic counter (see
+// STATIC_ONLY_TILES_PER_BLOCK above), so uneven tiles even out without the counter being
+// asked tile by tile.  Tiles are ordered by instance, a block's own run lies before everything
+// the counter hands out, and the counter only grows: a block meets the instances in
+// ascending order; it keeps one running minimum per lane and reduces it (wave, then block)
+// only when the instance changes.  Every block ends when its own run is done and no batches
+// are handed out, or with the first ticket at or past the total.
 template <int MODE, bool BOUNDS>
 __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
 {
@@ -1397,26 +1532,49 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     const uint32_t tk = pl.t_max * pl.k_max;
 
     uint32_t cur = 0xFFFFFFFFu;     // instance whose tables are in LDS
-    uint32_t scan = 0;              // instance search cursor
+    uint32_t scan = 0;              // instance of the current tile
+    uint64_t scan_end = 0;          // first tile behind that instance
     Best best;
     best.key = NO_KEY; best.obj = -__builtin_inf();
     uint64_t visited = 0;           // wave-uniform
     uint32_t bound_seen = 0xFFFFFFFFu;      // cost bound of instance `cur` as last read or lowered by this wave
-    const uint32_t batch = tiles_per_ticket(total, gridDim.x);
-    uint64_t tile = (uint64_t)blockIdx.x * batch;         // a block's first ticket is its own index,
-    uint64_t tile_end = tile + batch;                     // later ones come from the counter
+    const uint32_t own = as_uniform((const SummaryRec*)pl.summary)->own_tiles;
+    const uint32_t rounds = as_uniform((const SummaryRec*)pl.summary)->own_rounds;
+    const uint32_t batch = as_uniform((const SummaryRec*)pl.summary)->batch_tiles;
+    const uint64_t* begins = pl.tile_begin;
+    // rounds of own runs first (round r: the run that starts at (r * blocks + block) * own),
+    // then batches from the counter
+    uint32_t round = 0;
+    uint64_t tile = (uint64_t)blockIdx.x * own;
+    uint64_t tile_end = rounds != 0 ? tile + own : tile;
     for (;; ++tile) {
-        if (tile == tile_end) {
-            __syncthreads();                              // everyone has read the last ticket
-            if (threadIdx.x == 0) s_tile = atomicAdd(&pl.summary->next_tile, (unsigned long long)batch);
-            __syncthreads();
-            const unsigned long long ticket = s_tile;
-            tile = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ticket >> 32)) << 32) |
-                   (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ticket);
-            tile_end = tile + batch;
+        if (tile >= tile_end) {
+            ++round;
+            if (round < rounds) {
+                tile = ((uint64_t)round * gridDim.x + blockIdx.x) * own;
+                tile_end = tile + own;
+            } else {
+                if (batch == 0) break;                    // everything was shared out by index
+                __syncthreads();                          // everyone has read the last ticket
+                if (threadIdx.x == 0) s_tile = atomicAdd(&pl.summary->next_tile, (unsigned long long)batch);
+                __syncthreads();
+                const unsigned long long ticket = s_tile;
+                tile = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ticket >> 32)) << 32) |
+                       (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ticket);
+                tile_end = tile + batch;
+            }
         }
         if (tile >= total) break;
-        while (scan + 1 < pl.n_inst && insts[scan + 1].tile_begin <= tile) ++scan;
+        if (tile >= scan_end) {
+            // the instance that holds this tile: the last one that begins at or before it
+            uint32_t lo = 0, hi = pl.n_inst;
+            while (hi - lo > 1) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (as_uniform(begins)[mid] <= tile) lo = mid; else hi = mid;
+            }
+            scan = lo;
+            scan_end = insts[scan].tile_begin + insts[scan].tiles;
+        }
         if (scan != cur) {
             if (cur != 0xFFFFFFFFu) {
                 flush_block<OBJ>(pl, cur, best, s_red, s_red_obj);
@@ -1548,9 +1706,18 @@ __global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
 {
     __shared__ uint64_t s_red[4];
     __shared__ double s_red_obj[4];
+    // instance record, graph and the winner's entries are staged in LDS by all threads, so that
+    // the one thread that rescores the winner does not wait for memory load by load
+    __shared__ __attribute__((aligned(16))) Instance s_in;
+    __shared__ __attribute__((aligned(16))) Graph s_g;
+    __shared__ __attribute__((aligned(16))) Entry s_ent[MAXT];
+    static_assert(sizeof(Instance) % 8 == 0 && sizeof(Graph) % 8 == 0, "staged by 8-byte words");
     const uint32_t i = blockIdx.x;
-    const Instance* in = pl.inst + i;
-    const Graph* g = pl.graphs + in->problem;
+    {
+        const uint64_t* src = (const uint64_t*)(pl.inst + i);
+        uint64_t* dst = (uint64_t*)&s_in;
+        for (uint32_t k = threadIdx.x; k < sizeof(Instance) / 8; k += blockDim.x) dst[k] = src[k];
+    }
     uint64_t m = NO_KEY;
     if (pl.objective) {
         Best v; v.key = NO_KEY; v.obj = -__builtin_inf();
@@ -1564,19 +1731,40 @@ __global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
             m = umin64(m, pl.partial[(size_t)i * pl.grid + b]);
         m = block_min(m, s_red);
     }
+    const Instance* in = &s_in;          // complete: block_min / block_best synchronise
+    {
+        const uint64_t* src = (const uint64_t*)(pl.graphs + in->problem);
+        uint64_t* dst = (uint64_t*)&s_g;
+        for (uint32_t k = threadIdx.x; k < sizeof(Graph) / 8; k += blockDim.x) dst[k] = src[k];
+    }
+    const Graph* g = &s_g;
     __shared__ uint32_t s_last_block;
+    // the winner's digits: one 64-bit divide per task, by one thread per task
+    __shared__ uint64_t s_win;
+    __shared__ uint32_t s_dig[MAXT];
+    if (threadIdx.x == 0) s_win = m;
+    __syncthreads();
+    m = s_win;
+    const bool have = m != NO_KEY && !(in->flags & (F_OVERFLOW | F_EMPTY));
+    const uint64_t idx = in->idx_bits ? (m & ((1ull << in->idx_bits) - 1)) : 0;
+    if (have && threadIdx.x < g->T) {
+        const uint32_t t = threadIdx.x;
+        const uint32_t d = (uint32_t)((idx / in->stride[t]) % in->K[t]);
+        s_dig[t] = d;
+        s_ent[t] = pl.entries[((size_t)i * pl.t_max + t) * pl.k_max + d];
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
     ResultRec* r = pl.results + i;
     r->index = NO_KEY; r->full_index = NO_KEY; r->evaluated = in->space;
     r->accuracy = 0.0; r->latency_us = 0; r->cost_units = 0x7FFFFFFF; r->feasible = 0; r->objective = 0.0;
     r->flags = in->flags;
     for (int t = 0; t < MAXT; ++t) { r->choice[t] = 0; r->replicas[t] = 0; r->choice2[t] = 0; r->replicas2[t] = 0; }
-    if (m != NO_KEY && !(in->flags & (F_OVERFLOW | F_EMPTY))) {
-        const uint64_t idx = in->idx_bits ? (m & ((1ull << in->idx_bits) - 1)) : 0;
-        uint32_t dig[MAXT];
-        const Entry* ent = pl.entries + (size_t)i * pl.t_max * pl.k_max;
-        for (uint32_t t = 0; t < g->T; ++t) dig[t] = (uint32_t)((idx / in->stride[t]) % in->K[t]);
-        const Score sc = score_digits(g, in, ent, pl.k_max, dig);
+    if (have) {
+        // (the staged entries stand in for the table: one entry per task, digit 0)
+        uint32_t zero[MAXT];
+        for (int t = 0; t < MAXT; ++t) zero[t] = 0;
+        const Score sc = score_digits(g, in, s_ent, 1, zero);
         // The rescoring repeats the enumeration's latency and accuracy tests operation by
         // operation, so only the capacity bit (Eq. 8, applied to the minimum) can be missing.  A
         // winner that fails one of the other two would mean the two disagree: reported as an
@@ -1589,7 +1777,7 @@ __global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
             uint64_t full = 0;
             bool over = false;
             for (int t = (int)g->T - 1; t >= 0; --t) {
-                const Entry* e = ent + (size_t)t * pl.k_max + dig[t];
+                const Entry* e = s_ent + t;
                 r->choice[t] = (uint16_t)e->choice;
                 r->replicas[t] = e->rep;
                 r->choice2[t] = 0xFFFF;
@@ -1626,15 +1814,12 @@ __global__ void __launch_bounds__(256) finalize_kernel(Plan pl)
             v = cand > v ? cand : v;
         }
     }
-    __shared__ uint64_t s_v[256];
     __shared__ uint32_t s_any;
     if (threadIdx.x == 0) s_any = 0;
-    s_v[threadIdx.x] = v;
     __syncthreads();
     if (any) atomicOr(&s_any, any);
-    __syncthreads();
+    v = ~block_min(~v, s_red);           // maximum over the block, valid in thread 0
     if (threadIdx.x == 0) {
-        for (uint32_t k = 1; k < blockDim.x; ++k) v = s_v[k] > v ? s_v[k] : v;
         pl.summary->best_level = v ? (int32_t)(0xFFFFFFFFu - (uint32_t)v) : -1;
         pl.summary->max_demand = (uint32_t)(v >> 32);
         pl.summary->any_flags = s_any;

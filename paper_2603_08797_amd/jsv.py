@@ -21,7 +21,7 @@ LIB_PATH = os.environ.get("JSV_LIBRARY") or os.path.join(_HERE, "libjsv.so")
 MAX_TASKS = 16
 OK, E_NULL, E_BADARG, E_CYCLE, E_OVERFLOW, E_STATE, E_WORKSPACE, E_DEVICE, E_INTERNAL = 0, -1, -2, -3, -4, -5, -6, -7, -8
 
-EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space", "jsv_set_factors", "jsv_set_mixtures", "jsv_set_bounds", "jsv_set_graph_mode",
+EXPORTS = ["jsv_create", "jsv_destroy", "jsv_last_hip_error", "jsv_error_string", "jsv_set_objective", "jsv_set_search_space", "jsv_set_factors", "jsv_set_mixtures", "jsv_set_bounds", "jsv_set_geometry", "jsv_set_graph_mode",
            "jsv_workspace_bytes", "jsv_set_workspace", "jsv_load_profile", "jsv_set_dag",
            "jsv_search", "jsv_search_static", "jsv_eval_candidates", "jsv_get_pruned", "jsv_load_batch",
            "jsv_search_loaded_batch", "jsv_search_batch"]
@@ -80,6 +80,8 @@ def load_library():
     lib.jsv_set_search_space.argtypes = [vp, C.c_int, C.c_int, C.c_int]
     lib.jsv_set_bounds.restype = C.c_int
     lib.jsv_set_bounds.argtypes = [vp, C.c_int]
+    lib.jsv_set_geometry.restype = C.c_int
+    lib.jsv_set_geometry.argtypes = [vp, C.c_int, C.c_int]
     lib.jsv_set_mixtures.restype = C.c_int
     lib.jsv_set_mixtures.argtypes = [vp, C.c_int]
     lib.jsv_set_factors.restype = C.c_int
@@ -154,12 +156,23 @@ def _ptr(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
 
 
-def _result(r: JsvResult, T: int) -> Result:
-    return Result(int(r.index), int(r.full_index), int(r.evaluated), float(r.accuracy),
-                  int(r.latency_us), int(r.cost_units), bool(r.feasible), int(r.flags),
-                  [int(r.choice[t]) for t in range(T)], [int(r.replicas[t]) for t in range(T)],
-                  float(r.objective), [int(r.choice2[t]) for t in range(T)],
-                  [int(r.replicas2[t]) for t in range(T)])
+# the same record as a numpy dtype: whole result arrays convert in one call
+_RESULT_DTYPE = np.dtype([("index", "<u8"), ("full_index", "<u8"), ("evaluated", "<u8"), ("accuracy", "<f8"),
+                          ("latency_us", "<u4"), ("cost_units", "<i4"), ("feasible", "<u4"), ("flags", "<u4"),
+                          ("choice", "<u2", (MAX_TASKS,)), ("replicas", "<u4", (MAX_TASKS,)), ("objective", "<f8"),
+                          ("choice2", "<u2", (MAX_TASKS,)), ("replicas2", "<u4", (MAX_TASKS,))])
+assert _RESULT_DTYPE.itemsize == C.sizeof(JsvResult)
+
+
+def _results(res, n: int, Ts) -> List[Result]:
+    """n records of a JsvResult array as Result objects; Ts: tasks per record (int or list)."""
+    rows = np.frombuffer(res, dtype=_RESULT_DTYPE, count=n).tolist()
+    out = []
+    for k, (index, full, ev, acc, lat, cost, feas, flags, ch, rep, obj, ch2, rep2) in enumerate(rows):
+        T = Ts if isinstance(Ts, int) else Ts[k]
+        out.append(Result(index, full, ev, acc, lat, cost, bool(feas), flags, ch[:T].tolist(), rep[:T].tolist(), obj,
+                          ch2[:T].tolist(), rep2[:T].tolist()))
+    return out
 
 
 class Jsv:
@@ -236,6 +249,10 @@ class Jsv:
         result does not depend on it."""
         self._check(self._lib.jsv_set_bounds(self._h, int(on)), "jsv_set_bounds")
 
+    def set_geometry(self, blocks_per_cu: int = 0, lanes_percent: int = 0):
+        """Launch geometry of the enumeration (0 = automatic); the result does not depend on it."""
+        self._check(self._lib.jsv_set_geometry(self._h, int(blocks_per_cu), int(lanes_percent)), "jsv_set_geometry")
+
     def set_mixtures(self, on: bool = True):
         """Let a task run two tuples side by side (Eq. 2, 6, 7, 9, 10)."""
         self._check(self._lib.jsv_set_mixtures(self._h, int(on)), "jsv_set_mixtures")
@@ -290,7 +307,7 @@ class Jsv:
         summ = JsvSummary()
         self._check(self._lib.jsv_search(self._h, _ptr(d), n, int(slo_latency_us), float(slo_accuracy),
                                          int(prune_cap), res, C.byref(summ)), "jsv_search")
-        return ([_result(res[i], self.T) for i in range(n)],
+        return (_results(res, n, self.T),
                 Summary(int(summ.best_level), int(summ.max_demand_mrps), float(summ.seconds_device),
                         float(summ.seconds_enumerate), int(summ.candidates_visited)))
 
@@ -302,7 +319,7 @@ class Jsv:
         summ = JsvSummary()
         self._check(self._lib.jsv_search_static(self._h, _ptr(d), n, int(slo_latency_us), float(slo_accuracy),
                                                 int(prune_cap), res, C.byref(summ)), "jsv_search_static")
-        return ([_result(res[i], self.T) for i in range(n)],
+        return (_results(res, n, self.T),
                 Summary(int(summ.best_level), int(summ.max_demand_mrps), float(summ.seconds_device),
                         float(summ.seconds_enumerate), int(summ.candidates_visited)))
 
@@ -364,7 +381,7 @@ class Jsv:
         res = (JsvResult * max(n, 1))()
         summ = JsvSummary()
         self._check(self._lib.jsv_search_loaded_batch(self._h, res, C.byref(summ)), "jsv_search_loaded_batch")
-        return ([_result(res[i], self._batch_T[i]) for i in range(n)],
+        return (_results(res, n, self._batch_T),
                 Summary(int(summ.best_level), int(summ.max_demand_mrps), float(summ.seconds_device),
                         float(summ.seconds_enumerate), int(summ.candidates_visited)))
 
@@ -374,4 +391,4 @@ class Jsv:
         res = (JsvResult * max(n, 1))()
         self._check(self._lib.jsv_search_batch(self._h, arr, n, res), "jsv_search_batch")
         self._batch_T = [pb.T for pb in problems]
-        return [_result(res[i], problems[i].T) for i in range(n)]
+        return _results(res, n, self._batch_T)

@@ -281,3 +281,34 @@ def test_threshold_of_exactly_one_on_random_graphs(ctx, seed):
     pb = _problem(T, 3, 2, 2, 100 + seed, edges, mult=mult)
     check_search(ctx, pb, _search([20000, 250000], 400000, 1.0))
     check_search(ctx, pb, _search([20000], 400000, 1.0, cap=6))
+
+
+@pytest.mark.parametrize("name,cap", [("diamond5", 40), ("xr8", 10), ("chain4", 0)])
+def test_results_do_not_depend_on_the_launch_geometry(ctx, name, cap):
+    """1, 3 and 8 blocks per compute unit; half, double and eight times the lanes the planner
+    aims for (which changes how many tasks a lane loops over and the tile cut); bounds on and
+    off; both objective modes: every field of every record is the same."""
+    w = W.BENCH_WORKLOADS[name](seed=0)
+    pb, se = w.problems[0], w.searches[0]
+    dem = se.demand_mrps[::7] if len(se.demand_mrps) > 1 else se.demand_mrps
+    ctx.load(pb)
+    try:
+        for objective in (0, 1):
+            ctx.set_objective(objective, 1.0, 0.035)
+            ctx.set_geometry(0, 0)
+            ctx.set_bounds(True)
+            want, wsum = ctx.search(dem, se.slo_latency_us, se.slo_accuracy, cap)
+            for bounds in (False, True):
+                ctx.set_bounds(bounds)
+                for blocks, lanes in ((1, 100), (3, 100), (8, 100), (0, 50), (0, 200), (2, 800), (0, 12)):
+                    ctx.set_geometry(blocks, lanes)
+                    got, gsum = ctx.search(dem, se.slo_latency_us, se.slo_accuracy, cap)
+                    assert got == want, (name, objective, bounds, blocks, lanes)
+                    assert (gsum.best_level, gsum.max_demand_mrps) == (wsum.best_level, wsum.max_demand_mrps)
+    finally:
+        ctx.set_geometry(0, 0)
+        ctx.set_bounds(True)
+        ctx.set_objective(0)
+    with pytest.raises(jsv.JsvError) as e:
+        ctx.set_geometry(9, 0)
+    assert e.value.code == jsv.E_BADARG
