@@ -152,6 +152,7 @@ struct Instance {
     // objective of Eq. 14 (inputs, host): maximise alpha * A_obj - beta * cost
     double   alpha, beta;
     double   alpha_n;         // alpha / A_max: factor on A_raw
+    double   inv_beta;        // 1 / beta, or 0 when beta is too small for a cost limit to be derived from an objective
     // per-variant factors (input, host): the one variant task id t is held to in this
     // instance, NOT_HELD = free.  With every task that changes a downstream demand held, the
     // demands of all tasks are fixed and the instance is an ordinary search.

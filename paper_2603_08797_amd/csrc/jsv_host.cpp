@@ -687,6 +687,7 @@ Instance make_instance(const jsv_ctx* ctx, const HostProblem& hp, uint32_t probl
     std::memset(&in, 0, sizeof in);
     in.alpha = ctx->alpha; in.beta = ctx->beta;
     in.alpha_n = ctx->alpha / hp.graph.amax;
+    in.inv_beta = ctx->beta > 1e-9 * (ctx->alpha + 1.0) ? 1.0 / ctx->beta : 0.0;    // (else rounding could reach a unit of cost)
     in.problem = problem;
     in.demand = s.demand; in.slo_l = s.slo_l; in.cap = s.cap;
     in.slo_a = s.slo_a;

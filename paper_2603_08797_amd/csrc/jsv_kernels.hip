@@ -857,9 +857,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             }
             lb = bits_of(ranks - 1);
             const uint32_t cb = bits_of(cost_in);
-            // (objective mode over mixtures: every entry has its own accuracy and so its own
-            // objective; only the general per-candidate loop handles that)
-            use32 = (ranks <= 0x7FFFFFFFull && lb + cb <= 31 && !(pl.mix && pl.objective)) ? 1u : 0u;
+            use32 = (ranks <= 0x7FFFFFFFull && lb + cb <= 31) ? 1u : 0u;
         }
         if (use32) nq = pl.mix ? (KX + 3) / 4 : nq_groups;      // mixtures: one stream in latency order
         uint32_t chunk = 1, n_chunks = 0, n_groups = 0, ko = 0;
@@ -1013,6 +1011,8 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     // objective mode (Eq. 14)
     uint32_t idx_bits, lb, capacity;
     double   alpha_n, beta;   // objective = alpha_n * A_raw - beta * cost
+    double   alpha, inv_beta; // for the cost beyond which an objective already reached is out of reach; inv_beta 0: no such limit
+    bool     mix;             // entries carry their own accuracies (mixtures)
 };
 
 // Fix position P (a wave-uniform entry) and push its contribution down.  hin[P]
@@ -1240,23 +1240,69 @@ __device__ __forceinline__ void loop_x64_obj(const LaneState& s, const Uniforms&
     }
 }
 
+// One quad of the innermost stream as sixteen dwords: a single 64-byte scalar load.
+typedef uint32_t QuadWords __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ QuadWords load_quad(const Quad JSV_CONST* q, uint32_t j)
+{
+    return *(const QuadWords JSV_CONST*)(q + j);
+}
+__device__ __forceinline__ double words_f64(uint32_t lo, uint32_t hi)
+{
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
 // Objective mode, 32-bit local keys.  All candidates of one variant of position 0
 // (other digits fixed) share their accuracy, so the one with the best objective is
 // the cheapest feasible one: per variant the same masked minimum as in cost mode,
 // then one objective and one (objective, key) comparison for the variant's winner.
 // A variant whose cheapest candidate exceeds S_avail has no candidate within it.
+//
+// The objective itself (a conversion, two fp64 operations, three compares, three selects) is
+// evaluated only where it can matter.  A_obj <= 1, so a candidate of cost c scores at most
+// alpha - beta*c: once a lane holds a candidate of objective o, nothing costlier than
+// (alpha - o)/beta can replace it.  That limit, S_avail, and the cost of the lane's fixed
+// positions give one threshold on the 32-bit local key (klim); a variant whose winner lies
+// above it in every lane of the wave is skipped with one compare.  Every candidate's latency
+// test and minimum, and every variant's accuracy test, are still issued.
 struct TileBest {
     uint32_t k32; double obj;
     uint32_t visits;    // wave-uniform: entries of position 0 this wave went through in the tile
+    uint32_t klim;      // objective mode: local keys above it (fixed in-lane positions included) cannot matter
 };
 
-__device__ __forceinline__ void fold_variant(const LaneState& s, const Uniforms& U, uint32_t m, double t, TileBest& tb)
+// Largest local key that can still matter for a lane whose positions outside the lane loops cost
+// `cost_out` and that already holds a candidate of objective `have` (-inf: none).  0: none can
+// (real keys are at least 1 << lb: every task costs at least one unit).
+__device__ __forceinline__ uint32_t key_limit(const Uniforms& U, uint32_t cost_out, double have)
 {
-    const uint32_t k = __builtin_elementwise_add_sat(s.k32, m);
+    // Eq. 8, and what any block has made of the instance's shared limit so far (at most S_avail)
+    uint32_t cost_lim = U.bound;
+    if (U.inv_beta > 0.0 && have > -__builtin_inf()) {
+        const double lim = (U.alpha - have) * U.inv_beta;
+        // one unit of slack keeps rounding and equal objectives out of the decision
+        if (lim < 4294967000.0) { const uint32_t l = (lim > 0.0 ? (uint32_t)lim : 0u) + 1u; cost_lim = l < cost_lim ? l : cost_lim; }
+    }
+    if (cost_lim < cost_out) return 0u;
+    const uint64_t k = (((uint64_t)(cost_lim - cost_out) + 1u) << U.lb) - 1u;
+    return k > 0xFFFFFFFEull ? 0xFFFFFFFEu : (uint32_t)k;
+}
+
+// m: the variant's cheapest local key among the candidates that pass Eq. 3 (0xFFFFFFFF: none),
+// t: its A_raw, mlim: klim less the fixed in-lane positions' key.
+__device__ __forceinline__ void fold_variant(const LaneState& s, const Uniforms& U, uint32_t m, double t, TileBest& tb,
+                                             uint32_t& mlim)
+{
+    const bool hit = m <= mlim;                                  // (mlim < 0xFFFFFFFF)
+    const uint32_t k = s.k32 + m;
     const uint32_t cost = s.cost_out + (k >> U.lb);
-    const bool hit = (m != 0xFFFFFFFFu) & (U.capacity == 0 || cost <= U.capacity);
     const double obj = __builtin_fma(-U.beta, (double)cost, U.alpha_n * t);
-    if (hit && (obj > tb.obj || (obj == tb.obj && k < tb.k32))) { tb.obj = obj; tb.k32 = k; }
+    const bool improved = hit && (obj > tb.obj || (obj == tb.obj && k < tb.k32));
+    if (improved) { tb.obj = obj; tb.k32 = k; }
+    if (__builtin_amdgcn_ballot_w64(improved) != 0) {            // rare once a lane holds something good
+        const uint32_t kl = key_limit(U, s.cost_out, tb.obj);
+        tb.klim = kl < tb.klim ? kl : tb.klim;
+        mlim = __builtin_elementwise_sub_sat(tb.klim, s.k32);
+    }
 }
 
 template <bool BOUNDS>
@@ -1274,12 +1320,17 @@ __device__ __forceinline__ void loop_x32_obj(const LaneState& s, const Uniforms&
     if constexpr (BOUNDS) tb.visits += (qhi - qlo) * 4u;
     const Quad JSV_CONST* q = U.quads;
     uint32_t m = 0xFFFFFFFFu;
+    uint32_t mlim = __builtin_elementwise_sub_sat(tb.klim, s.k32);
     double t = 0.0;
     uint64_t ok = 0;
+    // every quad comes in through one 64-byte scalar load, issued one quad ahead of its use
+    QuadWords w = load_quad(q, qlo);
     for (uint32_t j = qlo; j < qhi; ++j) {
-        if (q[j].newgrp != 0) {
-            if (__builtin_amdgcn_ballot_w64(m != 0xFFFFFFFFu) != 0) fold_variant(s, U, m, t, tb);   // some lane has a candidate
-            t = __builtin_fma(q[j].acc, s.hin[0], s.sacc);
+        const QuadWords cur = w;
+        w = load_quad(q, j + 1 < qhi ? j + 1 : j);
+        if (cur[10] != 0) {                                     // a new variant (or the tile's range) starts
+            if (__builtin_amdgcn_ballot_w64(m <= mlim) != 0) fold_variant(s, U, m, t, tb, mlim);   // some lane's winner can matter
+            t = __builtin_fma(words_f64(cur[8], cur[9]), s.hin[0], s.sacc);
             ok = alive & __builtin_amdgcn_ballot_w64(t >= U.slo_raw);
             m = 0xFFFFFFFFu;
         }
@@ -1299,14 +1350,63 @@ __device__ __forceinline__ void loop_x32_obj(const LaneState& s, const Uniforms&
             "s_nop 1"
             : [m] "+v"(m)
             : [ok] "s"(ok), [full] "s"(full), [thr] "v"(thr),
-              [l0] "s"(q[j].e[0].lat), [k0] "s"(q[j].e[0].k32), [l1] "s"(q[j].e[1].lat), [k1] "s"(q[j].e[1].k32),
-              [l2] "s"(q[j].e[2].lat), [k2] "s"(q[j].e[2].k32), [l3] "s"(q[j].e[3].lat), [k3] "s"(q[j].e[3].k32)
+              [l0] "s"(cur[0]), [k0] "s"(cur[1]), [l1] "s"(cur[2]), [k1] "s"(cur[3]),
+              [l2] "s"(cur[4]), [k2] "s"(cur[5]), [l3] "s"(cur[6]), [k3] "s"(cur[7])
             : "vcc");
 #else
         (void)thr; (void)full; (void)ok;
 #endif
     }
-    if (__builtin_amdgcn_ballot_w64(m != 0xFFFFFFFFu) != 0) fold_variant(s, U, m, t, tb);
+    if (__builtin_amdgcn_ballot_w64(m <= mlim) != 0) fold_variant(s, U, m, t, tb, mlim);
+}
+
+// Objective mode over mixtures, 32-bit local keys.  Every entry has its own accuracy and so
+// its own objective; the stream is in ascending latency (QuadM).  Per candidate: the latency
+// compare (once no lane of the wave passes it, nothing later can: the loop ends), the
+// accuracy fma and compare, and one compare of the entry's key against the lane's limit
+// (see key_limit); the objective is evaluated only where all three pass in some lane.
+template <bool BOUNDS>
+__device__ __forceinline__ void loop_x32_mixobj(const LaneState& s, const Uniforms& U, uint32_t qlo, uint32_t qhi, TileBest& tb)
+{
+    const uint32_t thr = __builtin_elementwise_sub_sat(U.sloq, s.nxt[0]);
+    bool lane_ok = s.smax <= U.sloq;
+    if constexpr (BOUNDS) {
+        const uint32_t fixed = s.cost_out + (s.k32 >> U.lb);
+        lane_ok = lane_ok & (thr >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound);
+        if (__builtin_amdgcn_ballot_w64(lane_ok) == 0) return;
+    }
+    uint32_t mlim = __builtin_elementwise_sub_sat(tb.klim, s.k32);
+    const Quad JSV_CONST* q = U.quads;                       // (QuadM records: four entries of lat, key, accuracy)
+    uint32_t seen = 0;
+    QuadWords w = load_quad(q, qlo);
+    for (uint32_t j = qlo; j < qhi; ++j) {
+        const QuadWords cur = w;                                // one 64-byte scalar load per quad, one quad ahead
+        w = load_quad(q, j + 1 < qhi ? j + 1 : j);
+        bool done = false;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t lat = cur[4 * e], key = cur[4 * e + 1];
+            const bool fast = lane_ok & (lat <= thr);                             // Eq. 3
+            if (__builtin_amdgcn_ballot_w64(fast) == 0) { done = true; break; }   // (padding entries end here too)
+            ++seen;
+            const double t = __builtin_fma(words_f64(cur[4 * e + 2], cur[4 * e + 3]), s.hin[0], s.sacc);
+            const bool cand = fast & (t >= U.slo_raw) & (key <= mlim);            // Eq. 13; can it matter?
+            if (__builtin_amdgcn_ballot_w64(cand) != 0) {
+                const uint32_t k = s.k32 + key;
+                const uint32_t cost = s.cost_out + (k >> U.lb);
+                const double obj = __builtin_fma(-U.beta, (double)cost, U.alpha_n * t);
+                const bool improved = cand && (obj > tb.obj || (obj == tb.obj && k < tb.k32));
+                if (improved) { tb.obj = obj; tb.k32 = k; }
+                if (__builtin_amdgcn_ballot_w64(improved) != 0) {
+                    const uint32_t kl = key_limit(U, s.cost_out, tb.obj);
+                    tb.klim = kl < tb.klim ? kl : tb.klim;
+                    mlim = __builtin_elementwise_sub_sat(tb.klim, s.k32);
+                }
+            }
+        }
+        if (done) break;
+    }
+    if constexpr (BOUNDS) tb.visits += seen;
 }
 
 // What the enumeration kernel is instantiated for.
@@ -1319,8 +1419,24 @@ __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, ui
                                        uint64_t full, Best& best, TileBest& tb)
 {
     if constexpr (MODE == MODE_OBJ) {
-        if constexpr (W32) loop_x32_obj<BOUNDS>(s, U, lo, hi, full, tb);
-        else loop_x64_obj<BOUNDS>(s, U, lo, hi, best, tb.visits);
+        if constexpr (W32) {
+            // Two passes.  The first is the cost modes' loop: the cheapest candidate of this pass
+            // that meets Eq. 3 and 13, over all variants, at two vector instructions per candidate.
+            // Only if that one lies within the lane's key limit in some lane of the wave can the
+            // pass hold a new best objective (see key_limit); then the second pass goes through it
+            // again variant by variant (mixtures: entry by entry) and evaluates objectives.
+            uint32_t cheapest = 0xFFFFFFFFu, unused = 0;
+            if (U.mix) loop_x32_mix<BOUNDS>(s, U, lo, hi, full, cheapest, tb.visits);
+            else loop_x32<BOUNDS>(s, U, lo, hi, full, cheapest, tb.visits);
+            if (__builtin_amdgcn_ballot_w64(cheapest <= tb.klim) != 0) {
+                TileBest again = tb;
+                again.visits = 0;
+                if (U.mix) loop_x32_mixobj<BOUNDS>(s, U, lo, hi, again);
+                else loop_x32_obj<BOUNDS>(s, U, lo, hi, full, again);
+                tb.k32 = again.k32; tb.obj = again.obj; tb.klim = again.klim;
+            }
+            (void)unused;
+        } else loop_x64_obj<BOUNDS>(s, U, lo, hi, best, tb.visits);
     } else if constexpr (MODE == MODE_MIX) {
         if constexpr (W32) loop_x32_mix<BOUNDS>(s, U, lo, hi, full, tb.k32, tb.visits);
         else loop_x64<BOUNDS>(s, U, lo, hi, best.key, tb.visits);
@@ -1366,7 +1482,7 @@ __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, ui
 template <int NIN, bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instance JSV_CONST* in,
                                          const Entry JSV_CONST* tab, const uint32_t JSV_CONST* k32,
-                                         const Quad JSV_CONST* quads, const Entry* s_tab, uint32_t k_max,
+                                         const Quad JSV_CONST* quads, const Entry* s_tab, uint32_t k_max, bool mix,
                                          uint64_t group, uint32_t chunk_id, uint32_t bound, Best& best, uint64_t& visited)
 {
 #pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
@@ -1444,6 +1560,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     U.slo_raw = in->slo_raw;
     U.idx_bits = in->idx_bits; U.lb = in->lb; U.capacity = g->capacity;
     U.alpha_n = in->alpha_n; U.beta = in->beta;
+    U.alpha = in->alpha; U.inv_beta = in->inv_beta; U.mix = mix;
     st.cost_out = (uint32_t)(st.key >> in->idx_bits);
     // Cost as a bound: `bound` is S_avail (Eq. 8) or, in the cost modes, the cost of a candidate
     // already found that meets both SLOs, whichever is lower.  A lane whose fixed positions plus
@@ -1462,6 +1579,8 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     const uint32_t hi = lo + in->chunk < Ko ? lo + in->chunk : Ko;
     TileBest tb;
     tb.k32 = 0xFFFFFFFFu; tb.obj = -__builtin_inf(); tb.visits = 0;
+    tb.klim = 0xFFFFFFFEu;
+    if constexpr (MODE == MODE_OBJ && W32) tb.klim = key_limit(U, st.cost_out, best.obj);
     const uint64_t full = __builtin_amdgcn_read_exec();     // the loops below run convergent
     if constexpr (NIN == 3) loop_z<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
     else if constexpr (NIN == 2) loop_y<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
@@ -1518,6 +1637,9 @@ template <int MODE, bool BOUNDS>
 __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
 {
     constexpr bool OBJ = MODE == MODE_OBJ;
+    // the per-instance cost limit is read and lowered with bounds on, and in objective mode also
+    // without them: there it only decides where the objective itself needs evaluating
+    constexpr bool SHARE = BOUNDS || OBJ;
     extern __shared__ __attribute__((aligned(32))) unsigned char smem_raw[];
     Entry* s_tab = (Entry*)smem_raw;
     __shared__ uint64_t s_red[4];
@@ -1587,7 +1709,7 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
             __syncthreads();
             cur = scan;
             best.key = NO_KEY; best.obj = -__builtin_inf();
-            if constexpr (BOUNDS)
+            if constexpr (SHARE)
                 bound_seen = (uint32_t)__builtin_amdgcn_readfirstlane(
                     (int)__hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         }
@@ -1605,23 +1727,23 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         // looked at after the tile, so that nobody waits for the load.
         const uint32_t bound = bound_seen;
         uint32_t fresh = 0xFFFFFFFFu;
-        if constexpr (BOUNDS) fresh = __hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if constexpr (SHARE) fresh = __hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const uint64_t key_before = best.key;
         const double obj_before = best.obj;
         if (in->use32) {
             switch (in->n_in) {
-            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
-            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
-            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
+            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
             }
         } else {
             switch (in->n_in) {
-            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
-            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
-            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, group, chunk_id, bound, best, visited); break;
+            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
             }
         }
-        if constexpr (BOUNDS) {
+        if constexpr (SHARE) {
             const uint32_t other = (uint32_t)__builtin_amdgcn_readfirstlane((int)fresh);
             bound_seen = other < bound_seen ? other : bound_seen;
             // Did a lane of this wave find something better in this tile?  Then the bound may drop
