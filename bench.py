@@ -26,12 +26,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 # Algorithmic vector lane-operations of the enumeration, counted for the sharing the
-# kernel does: per candidate one latency compare and one
-# minimum on its key; per (variant of the innermost task, combination of all other
-# tasks) one fp64 fma and one compare for the accuracy.  Work shared further out
-# (one digit of the second-innermost task and beyond) is left out, so the figure
-# is a lower bound of what the kernel issues.
+# kernel does: per candidate one latency compare and one minimum on its key.  The
+# accuracy test is shared by all candidates of one pair of variants of the two innermost
+# tasks (and one combination of the others) and is left out, like everything shared further
+# out, so the figure is a lower bound of what the kernel issues.
 OPS_PER_CANDIDATE = 2
+# The rule of the previous kernel, which tested the accuracy once per (variant of the innermost
+# task, combination of all other tasks): two more lane-operations per such group.  Reported
+# beside the headline fraction so that the two kernels can be compared under one rule.
 OPS_PER_VARIANT_GROUP = 2
 # For comparison, a count that charges every candidate its own arithmetic: cost add,
 # latency add, fma, three compares, two mask ANDs, three for the running minimum.
@@ -52,9 +54,11 @@ VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
 
 def peak_probe():
-    """Sustained lane-operations/s of dependent-free v_add_u32 and v_fma_f64 streams on this GPU
+    """Sustained lane-operations/s of dependent-free instruction streams on this GPU
     (paper_2603_08797_amd/csrc/peak_probe.hip, a library of its own): what the vector ALUs deliver
-    at the clock they hold under load, beside the 2.4 GHz paper figure."""
+    at the clock they hold under load, beside the 2.4 GHz paper figure.  v_min_u32 and
+    v_cmp_le_u32 are the two instructions the enumeration spends per candidate; v_add_u32 issues
+    at a higher rate that those two do not reach."""
     import ctypes as C
     path = os.path.join(ROOT, "paper_2603_08797_amd", "libjsv_probe.so")
     if not os.path.exists(path):
@@ -63,7 +67,7 @@ def peak_probe():
     lib.jsv_probe_valu.restype = C.c_int
     lib.jsv_probe_valu.argtypes = [C.c_int, C.c_uint32, C.c_uint32, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     out = {"unit": "Tlane-op/s", "paper_peak": VALU_PEAK_LANE_OPS / 1e12}
-    for kind, name in ((0, "v_add_u32"), (1, "v_fma_f64")):
+    for kind, name in ((0, "v_add_u32"), (2, "v_min_u32"), (3, "v_cmp_le_u32"), (1, "v_fma_f64")):
         sec, ops = C.c_double(), C.c_double()
         rc = lib.jsv_probe_valu(kind, 256 * 8, 6000, 5, C.byref(sec), C.byref(ops))
         if rc != 0 or sec.value <= 0:
@@ -79,8 +83,13 @@ def peak_probe():
 OPS_PER_CANDIDATE_MIXTURES = 4
 
 
-def algorithmic_ops(jsv_mod, problems, searches, results, factors=None, mixtures=False):
-    """Lane-ops per step by the rule above; needs K and the number of surviving
+def algorithmic_ops(results, mixtures=False):
+    """Lane-ops per step by the rule above."""
+    return float(sum(r.evaluated for r in results) * (OPS_PER_CANDIDATE_MIXTURES if mixtures else OPS_PER_CANDIDATE))
+
+
+def previous_rule_ops(jsv_mod, problems, searches, results, factors=None, mixtures=False):
+    """Lane-ops per step by the previous kernel's rule; needs K and the number of surviving
     variants of the innermost task (the lowest-numbered source) at every level."""
     total = 0.0
     if mixtures:
@@ -346,10 +355,11 @@ def main():
     # The roofline counts the candidates whose tests the kernel issued; with bounds on, the rest
     # of the searched space was excluded in bulk and costs (almost) nothing.
     scored = min(visited, candidates)
-    ops = algorithmic_ops(jsv, w.problems, w.searches, res, factors, args.mixtures)
-    if ops is not None:
-        ops *= scored / max(candidates, 1)
-    achieved = (ops or 0.0) / enum_avg
+    ops = algorithmic_ops(res, args.mixtures) * scored / max(candidates, 1)
+    achieved = ops / enum_avg
+    ops_prev = previous_rule_ops(jsv, w.problems, w.searches, res, factors, args.mixtures)
+    if ops_prev is not None:
+        ops_prev *= scored / max(candidates, 1)
     out = {
         "metric": "candidate assignments evaluated/sec on 1 MI355X; ms to optimum per demand level",
         "value": candidates / (wall / args.steps),
@@ -373,6 +383,9 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.seed, args.objective, args.mixtures, bool(args.bounds))),
                      "kernel": "enumerate_kernel", "kernel_ms": enum_avg * 1e3,
                      "ops_per_candidate": (ops or 0.0) / max(scored, 1),
+                     "previous_rule": None if ops_prev is None else {
+                         "ops_per_candidate": ops_prev / max(scored, 1),
+                         "frac": ops_prev / enum_avg / VALU_PEAK_LANE_OPS},
                      "unshared_count": {"ops_per_candidate": UNSHARED_OPS_PER_CANDIDATE,
                                         "frac": UNSHARED_OPS_PER_CANDIDATE * scored / enum_avg / VALU_PEAK_LANE_OPS},
                      "device_ms_all_kernels": sum(dev_s) / len(dev_s) * 1e3},
@@ -384,8 +397,9 @@ def main():
     if not args.no_peak_probe:
         probe = peak_probe()
         out["roofline"]["peak_measured"] = probe
-        if probe and probe.get("v_add_u32"):
-            out["roofline"]["frac_of_measured_peak"] = achieved / (probe["v_add_u32"] * 1e12)
+        if probe and probe.get("v_min_u32"):
+            # against the issue rate of the loop's own instructions (compare and minimum)
+            out["roofline"]["frac_of_measured_peak"] = achieved / (probe["v_min_u32"] * 1e12)
     if other_seeds is not None:
         out["config"]["other_seeds"] = other_seeds
     if with_bounds is not None:

@@ -289,7 +289,10 @@ typedef struct {
     uint64_t candidates_visited;   /* candidates whose tests the enumeration kernel issued.  Bounds
                                       on: counted in whole 64-lane waves and whole quads of the
                                       innermost task's stream (padding included), the rest of the
-                                      space was excluded in bulk.  Bounds off: the sum of `evaluated` */
+                                      space was excluded in bulk.  Bounds off: the sum of `evaluated`;
+                                      in mixture mode, whose stream of options is sorted by latency
+                                      and left once no lane can take a later one, counted as with
+                                      bounds on */
 } jsv_summary;
 
 /*

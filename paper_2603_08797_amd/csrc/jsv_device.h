@@ -80,6 +80,24 @@ static_assert(sizeof(Quad) == 64, "Quad must be 64 bytes");
 struct XEntM { uint32_t lat; uint32_t k32; double acc; };
 struct __attribute__((aligned(64))) QuadM { XEntM e[4]; };
 static_assert(sizeof(QuadM) == 64, "QuadM must be 64 bytes");
+// Single tuples, second copy of the same stream without the headers: four (lat, k32) pairs
+// per 32-byte record, read two records deep by the loop that keeps the accuracy outcome per
+// variant in scalar registers (it needs neither the accuracy nor the flag).  One record past
+// the stream's end is read ahead and never used.
+struct __attribute__((aligned(32))) QuadC { XEnt e[4]; };
+static_assert(sizeof(QuadC) == 32, "QuadC must be 32 bytes");
+// What that loop needs of one digit of the position above the innermost one (position 1), one
+// 16-byte scalar load: its latency, its 32-bit local key, and the first later digit whose
+// variant has another accuracy (digits in between share the accuracy outcome of every variant
+// of position 0).
+struct __attribute__((aligned(16))) YRec { uint32_t lat; uint32_t k32; uint32_t run_end; uint32_t pad; };
+static_assert(sizeof(YRec) == 16, "YRec must be 16 bytes");
+// Records of 64 bytes per instance in the stream buffer: k_max Quad (or QuadM), then
+// k_max + 1 QuadC, then k_max + 3 YRec (four are read at a time, from any digit).
+constexpr uint32_t quad_stride(uint32_t k_max) { return k_max + (k_max + 2) / 2 + (k_max + 6) / 4; }
+constexpr uint32_t quadc_offset(uint32_t k_max) { return k_max; }                          // in Quad units
+constexpr uint32_t yrec_offset(uint32_t k_max) { return k_max + (k_max + 2) / 2; }
+
 
 // Task graph of one problem, by position.
 struct Graph {
@@ -118,6 +136,9 @@ struct Graph {
 };
 
 // One search instance: a problem at one demand level.
+// Variants of the innermost position whose accuracy masks a wave keeps in scalar registers.
+constexpr int MAX_XVAR = 8;
+
 struct Instance {
     // inputs (host)
     uint32_t problem;
@@ -164,6 +185,12 @@ struct Instance {
     uint32_t unit_cost;       // candidates per lane and unit of that loop (clamped)
     uint32_t tile_cost;       // candidates per lane and tile = chunk * unit_cost (clamped)
     uint32_t splittable;      // 1: chunk may still be lowered (not when the stream itself is chunked)
+    // the variants of the innermost position in the order of its stream (single tuples): how
+    // many, and the accuracy of the first MAX_XVAR of them (plan kernel)
+    uint32_t nvx;
+    uint32_t pad_nvx;
+    double   xacc[MAX_XVAR];
+    uint32_t xqe[MAX_XVAR];   // byte offset in the QuadC copy at which each of them ends (past nvx: the stream's end)
 };
 
 // Result record as written by the finalize kernel; same layout as jsv_result.
@@ -207,7 +234,7 @@ struct Plan {
     uint32_t*    rep = nullptr;         // [n_inst][t_max][c_max]   replicas of every choice
     uint32_t*    cost = nullptr;        // [n_inst][t_max][c_max]
     uint32_t*    k32 = nullptr;         // [n_inst][t_max][k_max]   32-bit local keys (in-lane tasks)
-    Quad*        quads = nullptr;       // [n_inst][k_max]          stream of the innermost position
+    Quad*        quads = nullptr;       // [n_inst][quad_stride(k_max)]  stream of the innermost position
     uint64_t*    partial = nullptr;     // [n_inst][grid]           per-block minima (keys)
     double*      partial_obj = nullptr; // [n_inst][grid]           per-block best objectives (objective mode)
     ResultRec*   results = nullptr;     // [n_inst]

@@ -458,7 +458,7 @@ Layout make_layout(uint32_t n_inst, uint32_t t_max, uint32_t k_max, uint32_t c_m
     L.rep = off;     off = align_up(off + sizeof(uint32_t) * (size_t)n_inst * t_max * c_max);
     L.cost = off;    off = align_up(off + sizeof(uint32_t) * (size_t)n_inst * t_max * c_max);
     L.k32 = off;     off = align_up(off + sizeof(uint32_t) * (size_t)n_inst * t_max * k_max);
-    L.quads = off;   off = align_up(off + sizeof(jsv::Quad) * (size_t)n_inst * k_max);
+    L.quads = off;   off = align_up(off + sizeof(jsv::Quad) * (size_t)n_inst * jsv::quad_stride(k_max));
     L.partial = off; off = align_up(off + sizeof(uint64_t) * (size_t)n_inst * grid);
     L.partial_obj = off; off = align_up(off + sizeof(double) * (size_t)n_inst * grid);
     L.results = off; off = align_up(off + sizeof(jsv::ResultRec) * n_inst);
@@ -675,7 +675,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
         summary->max_demand_mrps = sr.max_demand;
         summary->seconds_device = ms_all * 1e-3;
         summary->seconds_enumerate = ms_enum * 1e-3;
-        if (with_bounds && sr.bounded) summary->candidates_visited = (uint64_t)sr.visited * 64u;
+        if ((with_bounds && sr.bounded) || ctx->mix) summary->candidates_visited = (uint64_t)sr.visited * 64u;
         else summary->candidates_visited = enumerated;     // the plain kernel issues every candidate's tests
     }
     return JSV_OK;

@@ -893,6 +893,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         in->ko = ko;
         in->splittable = stream ? 0u : 1u;
         in->use32 = use32; in->lb = lb; in->nq = nq;
+        in->nvx = 0;                      // set with the stream of single tuples, if there is one
         uint64_t min_in = 0;
         for (uint32_t p = 0; p < n_in; ++p) min_in += s_mincost[s_task_at[p]];
         in->min_in_cost = (space != 0 && pl.bounds) ? (uint32_t)(min_in > 0xFFFFFFFFull ? 0xFFFFFFFFull : min_in) : 0u;
@@ -928,7 +929,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     if (s_nin != 0 && pl.mix) {
         // mixture mode: all entries in ascending latency, each with its own accuracy
         const Entry* ex = ent + (size_t)tx * pl.k_max;
-        QuadM* qm = (QuadM*)(pl.quads + (size_t)i * pl.k_max);
+        QuadM* qm = (QuadM*)(pl.quads + (size_t)i * quad_stride(pl.k_max));
         for (uint32_t d = tid; d < KX; d += blockDim.x) {
             const uint32_t lat = s_xlat[d];
             uint32_t rank = 0;
@@ -944,7 +945,8 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         }
     } else if (s_nin != 0) {
         const Entry* ex = ent + (size_t)tx * pl.k_max;
-        Quad* qd = pl.quads + (size_t)i * pl.k_max;
+        Quad* qd = pl.quads + (size_t)i * quad_stride(pl.k_max);
+        QuadC* qc = (QuadC*)(qd + quadc_offset(pl.k_max));
         for (uint32_t d = tid; d < KX; d += blockDim.x) {
             const uint32_t var = s_xvar[d], lat = s_xlat[d];
             uint32_t d0 = d, d1 = d + 1, rank = 0;
@@ -956,6 +958,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             me.lat = lat;
             me.k32 = (s_xcost[d] << s_lb) | (d * s_ls[0]);
             qd[q0 + rank / 4].e[rank % 4] = me;
+            qc[q0 + rank / 4].e[rank % 4] = me;
             if (d == d0) {                                   // the variant's first digit writes headers and padding
                 const double acc = ex[d].acc;
                 for (uint32_t j = 0; j < quads; ++j) {
@@ -964,8 +967,36 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
                     qd[q0 + j].newgrp = (j == 0 || (s_chunk != 0 && (q0 + j) % s_chunk == 0)) ? 1u : 0u;
                     for (int z = 0; z < 5; ++z) qd[q0 + j].pad[z] = 0;
                 }
-                for (uint32_t r = n; r < quads * 4; ++r) { qd[q0 + r / 4].e[r % 4].lat = 0xFFFFFFFFu; qd[q0 + r / 4].e[r % 4].k32 = 0xFFFFFFFFu; }
+                for (uint32_t r = n; r < quads * 4; ++r) {
+                    XEnt pad;
+                    pad.lat = 0xFFFFFFFFu; pad.k32 = 0xFFFFFFFFu;
+                    qd[q0 + r / 4].e[r % 4] = pad;
+                    qc[q0 + r / 4].e[r % 4] = pad;
+                }
+                // the variant's place in the stream, and its accuracy for the waves that keep
+                // one accuracy mask per variant
+                uint32_t ordinal = 0;
+                for (uint32_t x = 1; x <= d0; ++x) ordinal += s_xvar[x - 1] != s_xvar[x] ? 1u : 0u;
+                if (ordinal < (uint32_t)MAX_XVAR) { in->xacc[ordinal] = acc; in->xqe[ordinal] = (q0 + quads) * (uint32_t)sizeof(QuadC); }
+                if (d1 == KX) {
+                    in->nvx = ordinal + 1;
+                    for (uint32_t v = ordinal + 1; v < (uint32_t)MAX_XVAR; ++v) in->xqe[v] = (q0 + quads) * (uint32_t)sizeof(QuadC);
+                }
             }
+        }
+    }
+    // position 1's digits for the loop that batches them (single tuples, two or more in-lane positions)
+    if (s_nin >= 2 && !pl.mix) {
+        const uint32_t ty = s_task_at[1], KY = s_K[ty];
+        const Entry* ey = ent + (size_t)ty * pl.k_max;
+        YRec* yr = (YRec*)(pl.quads + (size_t)i * quad_stride(pl.k_max) + yrec_offset(pl.k_max));
+        for (uint32_t d = tid; d < KY; d += blockDim.x) {
+            const uint64_t bits = __builtin_bit_cast(uint64_t, ey[d].acc);
+            uint32_t e = d + 1;
+            while (e < KY && __builtin_bit_cast(uint64_t, ey[e].acc) == bits) ++e;
+            YRec r;
+            r.lat = ey[d].lat; r.k32 = (ey[d].cost << s_lb) | (d * s_lsT[ty]); r.run_end = e; r.pad = 0;
+            yr[d] = r;
         }
     }
     for (uint32_t b = tid; b < pl.grid; b += blockDim.x) {
@@ -1013,6 +1044,12 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     double   alpha_n, beta;   // objective = alpha_n * A_raw - beta * cost
     double   alpha, inv_beta; // for the cost beyond which an objective already reached is out of reach; inv_beta 0: no such limit
     bool     mix;             // entries carry their own accuracies (mixtures)
+    // single tuples: variants in position 0's stream and their accuracies (see loop_y_masked)
+    uint32_t nvx;
+    const double JSV_CONST* xacc;
+    const uint32_t JSV_CONST* xqe;     // where each variant ends in the QuadC copy of the stream (bytes)
+    const QuadC JSV_CONST* xq;         // that copy
+    const YRec JSV_CONST* yrec;        // position 1's digits
 };
 
 // Fix position P (a wave-uniform entry) and push its contribution down.  hin[P]
@@ -1061,7 +1098,7 @@ __device__ __forceinline__ void loop_x64(const LaneState& s, const Uniforms& U, 
         if ((s.key >> U.idx_bits) + U.min_x_cost > U.bound) thr = 0;    // too costly whatever position 0 takes
         if (__builtin_amdgcn_ballot_w64(thr >= U.min_x_lat) == 0) return;   // no lane of the wave has a candidate here
     }
-    if constexpr (BOUNDS) visits += hi - lo;
+    if (BOUNDS || U.mix) visits += hi - lo;
     const double cx = s.hin[0];
     const Entry JSV_CONST* tx = U.tab[0];
     for (uint32_t d = lo; d < hi; ++d) {
@@ -1209,7 +1246,7 @@ __device__ __forceinline__ void loop_x32_mix(const LaneState& s, const Uniforms&
 #else
     (void)thr; (void)t; (void)qlo; (void)qhi; (void)full; (void)alive;
 #endif
-    if constexpr (BOUNDS) visits += (pos - qlo * 64u) / 16u;
+    visits += (pos - qlo * 64u) / 16u;      // the stream ends early: counted with and without bounds
     const uint32_t cand = __builtin_elementwise_add_sat(s.k32, m);   // stays 0xFFFFFFFF if none
     best32 = best32 < cand ? best32 : cand;
 }
@@ -1226,7 +1263,7 @@ __device__ __forceinline__ void loop_x64_obj(const LaneState& s, const Uniforms&
         if ((s.key >> U.idx_bits) + U.min_x_cost > U.bound) thr = 0;
         if (__builtin_amdgcn_ballot_w64(thr >= U.min_x_lat) == 0) return;
     }
-    if constexpr (BOUNDS) visits += hi - lo;
+    if (BOUNDS || U.mix) visits += hi - lo;
     const double cx = s.hin[0];
     const Entry JSV_CONST* tx = U.tab[0];
     for (uint32_t d = lo; d < hi; ++d) {
@@ -1413,12 +1450,15 @@ __device__ __forceinline__ void loop_x32_mixobj(const LaneState& s, const Unifor
 constexpr int MODE_COST = 0;      // cheapest feasible
 constexpr int MODE_OBJ  = 1;      // largest objective (Eq. 14)
 constexpr int MODE_MIX  = 2;      // cheapest feasible, options with their own accuracies (Eq. 9, 10)
+constexpr int MODE_MIXOBJ = 3;    // largest objective over such options
+constexpr bool is_obj(int mode) { return mode == MODE_OBJ || mode == MODE_MIXOBJ; }
+constexpr bool is_mix(int mode) { return mode == MODE_MIX || mode == MODE_MIXOBJ; }
 
 template <bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
                                        uint64_t full, Best& best, TileBest& tb)
 {
-    if constexpr (MODE == MODE_OBJ) {
+    if constexpr (is_obj(MODE)) {
         if constexpr (W32) {
             // Two passes.  The first is the cost modes' loop: the cheapest candidate of this pass
             // that meets Eq. 3 and 13, over all variants, at two vector instructions per candidate.
@@ -1426,12 +1466,12 @@ __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, ui
             // pass hold a new best objective (see key_limit); then the second pass goes through it
             // again variant by variant (mixtures: entry by entry) and evaluates objectives.
             uint32_t cheapest = 0xFFFFFFFFu, unused = 0;
-            if (U.mix) loop_x32_mix<BOUNDS>(s, U, lo, hi, full, cheapest, tb.visits);
+            if constexpr (is_mix(MODE)) loop_x32_mix<BOUNDS>(s, U, lo, hi, full, cheapest, tb.visits);
             else loop_x32<BOUNDS>(s, U, lo, hi, full, cheapest, tb.visits);
             if (__builtin_amdgcn_ballot_w64(cheapest <= tb.klim) != 0) {
                 TileBest again = tb;
                 again.visits = 0;
-                if (U.mix) loop_x32_mixobj<BOUNDS>(s, U, lo, hi, again);
+                if constexpr (is_mix(MODE)) loop_x32_mixobj<BOUNDS>(s, U, lo, hi, again);
                 else loop_x32_obj<BOUNDS>(s, U, lo, hi, full, again);
                 tb.k32 = again.k32; tb.obj = again.obj; tb.klim = again.klim;
             }
@@ -1446,10 +1486,289 @@ __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, ui
     }
 }
 
+// Positions 1 and 0 together, single tuples, 32-bit keys, at most MAX_XVAR variants in position
+// 0's stream.  The accuracy of a candidate (Eq. 11-13) depends on the variants only, so while
+// position 1 stays with one accuracy the outcome of Eq. 13 for each variant of position 0 is
+// the same: it is evaluated once per variant pair - the same fma and compare as in loop_x32 -
+// and kept as one execution mask per variant of position 0 in scalar registers.  Along the
+// digits of position 1 only latencies and keys change, and G of them (slots) go through
+// position 0's stream together: every record that is loaded serves G digits, each with its own
+// latency threshold, set of live lanes and running minimum.
+//
+// The stream is walked in its QuadC copy, variant by variant, in code written out per place of
+// the variant in the stream: per slot and record one scalar AND puts the variant's mask and
+// the slot's live lanes into EXEC, then per candidate the two vector instructions of loop_x32
+// follow (a lane that fails one candidate's latency test sits out the rest of the record).
+// Records alternate between two register sets (A: s[72:79], B: s[80:87]); the next record's
+// load is issued before the current one's vector instructions and waited for after them.  s88
+// is the byte offset of the next record to load, so the record in flight lies 32 bytes before
+// it: it still belongs to variant v while s88 <= xqe[v], and the stream is done once s88 > its
+// length (the record then in flight is the spare one behind the stream).  A variant may end in
+// either register set, hence two ways into every block: labels 10(v+1)+1 and +3 (start of
+// variant v with the current record in A, in B), +2 and +4 (the loop itself), 99 the end.
+//
+// SKIP (with bounds on): a slot none of whose lanes can take the record's fastest candidate
+// leaves the record at once.
+#define JSV_SLOT(L0, K0, L1, K1, L2, K2, L3, K3, MASK, ALIVE, THR, M, SKIP)                        \
+        "s_and_b64 exec, " MASK ", " ALIVE "\n\t"                                                  \
+        "v_cmpx_le_u32_e32 vcc, " L0 ", " THR "\n\t"                                               \
+        SKIP                                                                                       \
+        "v_min_u32_e32 " M ", " K0 ", " M "\n\t"                                                   \
+        "v_cmpx_le_u32_e32 vcc, " L1 ", " THR "\n\t"                                               \
+        "v_min_u32_e32 " M ", " K1 ", " M "\n\t"                                                   \
+        "v_cmpx_le_u32_e32 vcc, " L2 ", " THR "\n\t"                                               \
+        "v_min_u32_e32 " M ", " K2 ", " M "\n\t"                                                   \
+        "v_cmpx_le_u32_e32 vcc, " L3 ", " THR "\n\t"                                               \
+        "v_min_u32_e32 " M ", " K3 ", " M "\n\t"                                                   \
+        "5:\n\t"
+#define JSV_SLOTS_A1(MASK, SKIP) JSV_SLOT("s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", MASK, "%[a0]", "%[t0]", "%[r0]", SKIP)
+#define JSV_SLOTS_B1(MASK, SKIP) JSV_SLOT("s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", MASK, "%[a0]", "%[t0]", "%[r0]", SKIP)
+#define JSV_SLOTS_A2(MASK, SKIP) JSV_SLOTS_A1(MASK, SKIP) JSV_SLOT("s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", MASK, "%[a1]", "%[t1]", "%[r1]", SKIP)
+#define JSV_SLOTS_B2(MASK, SKIP) JSV_SLOTS_B1(MASK, SKIP) JSV_SLOT("s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", MASK, "%[a1]", "%[t1]", "%[r1]", SKIP)
+#define JSV_SLOTS_A4(MASK, SKIP) JSV_SLOTS_A2(MASK, SKIP)                                          \
+        JSV_SLOT("s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", MASK, "%[a2]", "%[t2]", "%[r2]", SKIP) \
+        JSV_SLOT("s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", MASK, "%[a3]", "%[t3]", "%[r3]", SKIP)
+#define JSV_SLOTS_B4(MASK, SKIP) JSV_SLOTS_B2(MASK, SKIP)                                          \
+        JSV_SLOT("s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", MASK, "%[a2]", "%[t2]", "%[r2]", SKIP) \
+        JSV_SLOT("s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", MASK, "%[a3]", "%[t3]", "%[r3]", SKIP)
+#define JSV_XV_HALF(START, LOOP, SLOTS, NEXTREGS, STAY, LEAVE, QE)                                 \
+        START ":\n\t"                                                                              \
+        "s_cmp_gt_u32 s88, %[endb]\n\t"                                                            \
+        "s_cbranch_scc1 99f\n\t"                                                                   \
+        LOOP ":\n\t"                                                                               \
+        "s_load_dwordx8 " NEXTREGS ", %[base], s88\n\t"                                            \
+        "s_add_u32 s88, s88, 32\n\t"                                                               \
+        SLOTS                                                                                      \
+        "s_waitcnt lgkmcnt(0)\n\t"                                                                 \
+        "s_cmp_le_u32 s88, " QE "\n\t"                                                             \
+        "s_cbranch_scc1 " STAY "\n\t"                                                              \
+        "s_branch " LEAVE "\n\t"
+// variant block N (labels N1..N4), ways out to the next block: XA (current record in A), XB (in B)
+#define JSV_XV(G, N, XA, XB, MASK, QE, SKIP)                                                       \
+        JSV_XV_HALF(N "1", N "2", JSV_SLOTS_A##G(MASK, SKIP), "s[80:87]", N "4f", XB, QE)          \
+        JSV_XV_HALF(N "3", N "4", JSV_SLOTS_B##G(MASK, SKIP), "s[72:79]", N "2b", XA, QE)
+#define JSV_XV_ALL(G, SKIP)                                                                        \
+        "s_mov_b32 s88, 0\n\t"                                                                     \
+        "s_load_dwordx8 s[72:79], %[base], s88\n\t"                                                \
+        "s_mov_b32 s88, 32\n\t"                                                                    \
+        "s_waitcnt lgkmcnt(0)\n\t"                                                                 \
+        JSV_XV(G, "1", "21f", "23f", "%[m0]", "%[q0]", SKIP) JSV_XV(G, "2", "31f", "33f", "%[m1]", "%[q1]", SKIP) \
+        JSV_XV(G, "3", "41f", "43f", "%[m2]", "%[q2]", SKIP) JSV_XV(G, "4", "51f", "53f", "%[m3]", "%[q3]", SKIP) \
+        JSV_XV(G, "5", "61f", "63f", "%[m4]", "%[q4]", SKIP) JSV_XV(G, "6", "71f", "73f", "%[m5]", "%[q5]", SKIP) \
+        JSV_XV(G, "7", "81f", "83f", "%[m6]", "%[q6]", SKIP) JSV_XV(G, "8", "99f", "99f", "%[m7]", "%[q7]", SKIP) \
+        "99:\n\t"                                                                                  \
+        "s_mov_b64 exec, %[full]\n\t"                                                              \
+        "s_nop 1"
+#define JSV_XV_COMMON_IN                                                                           \
+          [base] "s"(U.xq), [endb] "s"(endb), [full] "s"(full),                                    \
+          [m0] "s"(mk[0]), [m1] "s"(mk[1]), [m2] "s"(mk[2]), [m3] "s"(mk[3]),                      \
+          [m4] "s"(mk[4]), [m5] "s"(mk[5]), [m6] "s"(mk[6]), [m7] "s"(mk[7]),                      \
+          [q0] "s"(qe[0]), [q1] "s"(qe[1]), [q2] "s"(qe[2]), [q3] "s"(qe[3]),                      \
+          [q4] "s"(qe[4]), [q5] "s"(qe[5]), [q6] "s"(qe[6]), [q7] "s"(qe[7])
+#define JSV_XV_CLOBBER                                                                             \
+          "vcc", "scc", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", \
+          "s83", "s84", "s85", "s86", "s87", "s88"
+
+// G = 4, 2 or 1 slots: thresholds thr[g], live lanes go[g], running minima m[g] (in and out).
+template <int G, bool BOUNDS>
+__device__ __forceinline__ void loop_x32_masked(const Uniforms& U, const uint32_t (&thr)[4], const uint64_t (&go)[4],
+                                                const uint64_t (&mk)[MAX_XVAR], const uint32_t (&qe)[MAX_XVAR],
+                                                uint32_t endb, uint64_t full, uint32_t (&m)[4])
+{
+    static_assert(MAX_XVAR == 8, "the blocks above are written out for eight variants");
+    static_assert(G == 1 || G == 2 || G == 4, "slots");
+#if defined(__HIP_DEVICE_COMPILE__)
+    if constexpr (G == 4) {
+        if constexpr (BOUNDS)
+            asm volatile(JSV_XV_ALL(4, "s_cbranch_execz 5f\n\t")
+                : [r0] "+v"(m[0]), [r1] "+v"(m[1]), [r2] "+v"(m[2]), [r3] "+v"(m[3])
+                : JSV_XV_COMMON_IN, [t0] "v"(thr[0]), [t1] "v"(thr[1]), [t2] "v"(thr[2]), [t3] "v"(thr[3]),
+                  [a0] "s"(go[0]), [a1] "s"(go[1]), [a2] "s"(go[2]), [a3] "s"(go[3])
+                : JSV_XV_CLOBBER);
+        else
+            asm volatile(JSV_XV_ALL(4, "")
+                : [r0] "+v"(m[0]), [r1] "+v"(m[1]), [r2] "+v"(m[2]), [r3] "+v"(m[3])
+                : JSV_XV_COMMON_IN, [t0] "v"(thr[0]), [t1] "v"(thr[1]), [t2] "v"(thr[2]), [t3] "v"(thr[3]),
+                  [a0] "s"(go[0]), [a1] "s"(go[1]), [a2] "s"(go[2]), [a3] "s"(go[3])
+                : JSV_XV_CLOBBER);
+    } else if constexpr (G == 2) {
+        if constexpr (BOUNDS)
+            asm volatile(JSV_XV_ALL(2, "s_cbranch_execz 5f\n\t")
+                : [r0] "+v"(m[0]), [r1] "+v"(m[1])
+                : JSV_XV_COMMON_IN, [t0] "v"(thr[0]), [t1] "v"(thr[1]), [a0] "s"(go[0]), [a1] "s"(go[1])
+                : JSV_XV_CLOBBER);
+        else
+            asm volatile(JSV_XV_ALL(2, "")
+                : [r0] "+v"(m[0]), [r1] "+v"(m[1])
+                : JSV_XV_COMMON_IN, [t0] "v"(thr[0]), [t1] "v"(thr[1]), [a0] "s"(go[0]), [a1] "s"(go[1])
+                : JSV_XV_CLOBBER);
+    } else {
+        if constexpr (BOUNDS)
+            asm volatile(JSV_XV_ALL(1, "s_cbranch_execz 5f\n\t")
+                : [r0] "+v"(m[0]) : JSV_XV_COMMON_IN, [t0] "v"(thr[0]), [a0] "s"(go[0]) : JSV_XV_CLOBBER);
+        else
+            asm volatile(JSV_XV_ALL(1, "")
+                : [r0] "+v"(m[0]) : JSV_XV_COMMON_IN, [t0] "v"(thr[0]), [a0] "s"(go[0]) : JSV_XV_CLOBBER);
+    }
+#else
+    (void)U; (void)thr; (void)go; (void)mk; (void)qe; (void)endb; (void)full; (void)m;
+#endif
+}
+#undef JSV_XV_CLOBBER
+#undef JSV_XV_COMMON_IN
+#undef JSV_XV_ALL
+#undef JSV_XV
+#undef JSV_XV_HALF
+#undef JSV_SLOTS_B4
+#undef JSV_SLOTS_A4
+#undef JSV_SLOTS_B2
+#undef JSV_SLOTS_A2
+#undef JSV_SLOTS_B1
+#undef JSV_SLOTS_A1
+#undef JSV_SLOT
+
+// Eq. 13 for every variant of position 0, given what the other positions contribute to A_raw:
+// mk[v] = lanes with fma(xacc[v], hin0, sacc) >= slo_raw, v < nvx; the others 0.  One
+// 64-byte scalar load brings all MAX_XVAR accuracies.
+__device__ __forceinline__ void variant_masks(const Uniforms& U, uint32_t nvx, double hin0, double sacc,
+                                              uint64_t (&mk)[MAX_XVAR])
+{
+    static_assert(MAX_XVAR == 8, "written out for eight variants");
+#if defined(__HIP_DEVICE_COMPILE__)
+    double t;
+#define JSV_VM(N, REGS, OUT)                                                                       \
+        "s_cmp_lt_u32 %[nvx], " N "\n\t"                                                           \
+        "s_cbranch_scc1 1f\n\t"                                                                    \
+        "v_fma_f64 %[t], " REGS ", %[hin0], %[sacc]\n\t"                                           \
+        "v_cmp_le_f64_e64 " OUT ", %[slo], %[t]\n\t"
+    asm volatile(
+        "s_load_dwordx16 s[72:87], %[xacc], 0x0\n\t"
+        "s_mov_b64 %[m1], 0\n\t"
+        "s_mov_b64 %[m2], 0\n\t"
+        "s_mov_b64 %[m3], 0\n\t"
+        "s_mov_b64 %[m4], 0\n\t"
+        "s_mov_b64 %[m5], 0\n\t"
+        "s_mov_b64 %[m6], 0\n\t"
+        "s_mov_b64 %[m7], 0\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "v_fma_f64 %[t], s[72:73], %[hin0], %[sacc]\n\t"
+        "v_cmp_le_f64_e64 %[m0], %[slo], %[t]\n\t"
+        JSV_VM("2", "s[74:75]", "%[m1]") JSV_VM("3", "s[76:77]", "%[m2]") JSV_VM("4", "s[78:79]", "%[m3]")
+        JSV_VM("5", "s[80:81]", "%[m4]") JSV_VM("6", "s[82:83]", "%[m5]") JSV_VM("7", "s[84:85]", "%[m6]")
+        JSV_VM("8", "s[86:87]", "%[m7]")
+        "1:"
+        : [m0] "=&s"(mk[0]), [m1] "=&s"(mk[1]), [m2] "=&s"(mk[2]), [m3] "=&s"(mk[3]),
+          [m4] "=&s"(mk[4]), [m5] "=&s"(mk[5]), [m6] "=&s"(mk[6]), [m7] "=&s"(mk[7]), [t] "=&v"(t)
+        : [xacc] "s"(U.xacc), [nvx] "s"(nvx), [hin0] "v"(hin0), [sacc] "v"(sacc), [slo] "s"(U.slo_raw)
+        : "scc", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82",
+          "s83", "s84", "s85", "s86", "s87");
+#undef JSV_VM
+#else
+    (void)U; (void)nvx; (void)hin0; (void)sacc; (void)mk;
+#endif
+}
+
+typedef uint32_t YWords __attribute__((ext_vector_type(16), aligned(16)));      // four YRec
+
+template <int MODE, bool BOUNDS>
+__device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
+                                              uint32_t x_hi, uint64_t full, TileBest& tb)
+{
+#pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
+    const Entry JSV_CONST* ty = U.tab[1];
+    // Position 1 is either a successor of position 0 (its only possible predecessor) or a source:
+    // in the first case its tail changes position 0's latency threshold, in the second the
+    // lanes that still meet the latency SLO.  Wave-uniform, as scalars.
+    const uint32_t e01 = __builtin_amdgcn_readfirstlane(U.m01);
+    const uint32_t src1 = __builtin_amdgcn_readfirstlane(U.src[1] ? 1u : 0u);
+    const uint32_t nvx = __builtin_amdgcn_readfirstlane(U.nvx);
+    uint32_t qe[MAX_XVAR];
+#pragma unroll
+    for (int v = 0; v < MAX_XVAR; ++v) qe[v] = U.xqe[v];
+    const uint32_t endb = x_hi * (uint32_t)sizeof(QuadC);
+    const uint64_t alive0 = __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
+    const uint32_t thr0 = __builtin_elementwise_sub_sat(U.sloq, s.nxt[0]);
+    uint32_t d = lo;
+    while (d < hi) {
+        // a run of digits of position 1 that share their accuracy: what fix_position<1> does to the
+        // accuracy state, then Eq. 13 for every variant of position 0
+        const uint32_t run_end = U.yrec[d].run_end;
+        const uint32_t re = run_end < hi ? run_end : hi;
+        const double H = ty[d].acc * s.hin[1];
+        const double sacc = src1 != 0 ? s.sacc + H : s.sacc;
+        const double hin0 = __builtin_fma(U.w01, H, s.hin[0]);
+        uint64_t mk[MAX_XVAR];
+        variant_masks(U, nvx, hin0, sacc, mk);
+        uint32_t best_rel = 0xFFFFFFFFu;        // cost modes: the run's minimum of position 1's key plus position 0's
+        for (; d < re; d += 4) {
+            // four digits at a time, one 64-byte scalar load (slots past the run stay without lanes)
+            const YWords w = *(const YWords JSV_CONST*)(U.yrec + d);
+            const uint32_t n = re - d;
+            uint32_t thr[4], m[4];
+            uint64_t go[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const uint32_t tail = w[4 * g] + s.nxt[1];
+                uint32_t smax = s.smax;
+                thr[g] = thr0; go[g] = alive0; m[g] = 0xFFFFFFFFu;
+                if (e01 != 0) thr[g] = __builtin_elementwise_sub_sat(U.sloq, umax(s.nxt[0], tail));
+                if (src1 != 0) { smax = umax(s.smax, tail); go[g] = __builtin_amdgcn_ballot_w64(smax <= U.sloq); }
+                if constexpr (BOUNDS) {
+                    // also out: lanes whose fixed positions plus the cheapest entry of position 0 cost more than the bound
+                    const uint32_t fixed = s.cost_out + ((s.k32 + w[4 * g + 1]) >> U.lb);
+                    go[g] = __builtin_amdgcn_ballot_w64((smax <= U.sloq) & (thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
+                }
+                if ((uint32_t)g >= n) go[g] = 0;
+                if constexpr (BOUNDS) { if (go[g] != 0) tb.visits += x_hi * 4u; }
+            }
+            if constexpr (BOUNDS) { if ((go[0] | go[1] | go[2] | go[3]) == 0) continue; }
+            if (n >= 4) loop_x32_masked<4, BOUNDS>(U, thr, go, mk, qe, endb, full, m);
+            else {
+                // three digits: two and one (a slot without lanes would still cost its vector instructions)
+                if (n >= 2) loop_x32_masked<2, BOUNDS>(U, thr, go, mk, qe, endb, full, m);
+                if (n != 2) {
+                    const int g = n == 3 ? 2 : 0;
+                    uint32_t thr1[4] = {g == 2 ? thr[2] : thr[0], 0, 0, 0}, m1[4] = {0xFFFFFFFFu, 0, 0, 0};
+                    uint64_t go1[4] = {g == 2 ? go[2] : go[0], 0, 0, 0};
+                    loop_x32_masked<1, BOUNDS>(U, thr1, go1, mk, qe, endb, full, m1);
+                    if (g == 2) m[2] = m1[0]; else m[0] = m1[0];
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const uint32_t rel = __builtin_elementwise_add_sat(m[g], w[4 * g + 1]);    // stays 0xFFFFFFFF if none
+                if constexpr (MODE == MODE_OBJ) {
+                    // first of the two passes of objective mode (see loop_x); the second, rare, takes the
+                    // general path with the lane state of this digit
+                    const uint32_t cand = __builtin_elementwise_add_sat(rel, s.k32);
+                    if ((uint32_t)g < n && __builtin_amdgcn_ballot_w64(cand <= tb.klim) != 0) {
+                        const LaneState s1 = fix_position<1>(s, U, ty[d + g].lat, ty[d + g].acc, 0, U.k32[1][d + g]);
+                        TileBest again = tb;
+                        again.visits = 0;
+                        loop_x32_obj<BOUNDS>(s1, U, 0, x_hi, full, again);
+                        tb.k32 = again.k32; tb.obj = again.obj; tb.klim = again.klim;
+                    }
+                } else {
+                    best_rel = best_rel < rel ? best_rel : rel;        // (a slot without lanes kept m = 0xFFFFFFFF)
+                }
+            }
+        }
+        d = re;
+        if constexpr (MODE != MODE_OBJ) {
+            const uint32_t cand = __builtin_elementwise_add_sat(best_rel, s.k32);
+            tb.k32 = tb.k32 < cand ? tb.k32 : cand;
+        }
+    }
+}
+
 template <bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void loop_y(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
                                        uint32_t x_hi, uint64_t full, Best& best, TileBest& tb)
 {
+    if constexpr (W32 && !is_mix(MODE)) {
+        // single tuples with few variants in position 0 (nvx is 0 for a stream of mixtures)
+        if (U.nvx - 1u < (uint32_t)MAX_XVAR) { loop_y_masked<MODE, BOUNDS>(s, U, lo, hi, x_hi, full, tb); return; }
+    }
     const Entry JSV_CONST* ty = U.tab[1];
     for (uint32_t d = lo; d < hi; ++d) {
         const LaneState s1 = fix_position<1>(s, U, ty[d].lat, ty[d].acc, W32 ? 0 : ty[d].key,
@@ -1561,6 +1880,8 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     U.idx_bits = in->idx_bits; U.lb = in->lb; U.capacity = g->capacity;
     U.alpha_n = in->alpha_n; U.beta = in->beta;
     U.alpha = in->alpha; U.inv_beta = in->inv_beta; U.mix = mix;
+    U.nvx = in->nvx; U.xacc = in->xacc; U.xqe = in->xqe; U.xq = (const QuadC JSV_CONST*)(quads + quadc_offset(k_max));
+    U.yrec = (const YRec JSV_CONST*)(quads + yrec_offset(k_max));
     st.cost_out = (uint32_t)(st.key >> in->idx_bits);
     // Cost as a bound: `bound` is S_avail (Eq. 8) or, in the cost modes, the cost of a candidate
     // already found that meets both SLOs, whichever is lower.  A lane whose fixed positions plus
@@ -1580,12 +1901,12 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     TileBest tb;
     tb.k32 = 0xFFFFFFFFu; tb.obj = -__builtin_inf(); tb.visits = 0;
     tb.klim = 0xFFFFFFFEu;
-    if constexpr (MODE == MODE_OBJ && W32) tb.klim = key_limit(U, st.cost_out, best.obj);
+    if constexpr (is_obj(MODE) && W32) tb.klim = key_limit(U, st.cost_out, best.obj);
     const uint64_t full = __builtin_amdgcn_read_exec();     // the loops below run convergent
     if constexpr (NIN == 3) loop_z<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
     else if constexpr (NIN == 2) loop_y<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
     else loop_x<W32, MODE, BOUNDS>(st, U, lo, hi, full, best, tb);
-    if constexpr (BOUNDS) visited += tb.visits;
+    if (BOUNDS || U.mix) visited += tb.visits;
 
     if constexpr (W32) {
         // the lane's 32-bit winner of this tile -> its full (cost, index) key
@@ -1601,7 +1922,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
             r /= K;
             k += s_tab[t * k_max + d].key;
         }
-        if constexpr (MODE == MODE_OBJ) {
+        if constexpr (is_obj(MODE)) {
             if (hit && better(tb.obj, k, best.obj, best.key)) { best.obj = tb.obj; best.key = k; }
         } else {
             best.key = (hit && k < best.key) ? k : best.key;
@@ -1636,7 +1957,7 @@ __device__ __forceinline__ void flush_block(const Plan& pl, uint32_t inst, const
 template <int MODE, bool BOUNDS>
 __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
 {
-    constexpr bool OBJ = MODE == MODE_OBJ;
+    constexpr bool OBJ = is_obj(MODE);
     // the per-instance cost limit is read and lowered with bounds on, and in objective mode also
     // without them: there it only decides where the objective itself needs evaluating
     constexpr bool SHARE = BOUNDS || OBJ;
@@ -1717,7 +2038,7 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const Graph JSV_CONST* g = graphs + in->problem;
         const Entry JSV_CONST* tab = as_uniform((const Entry*)pl.entries) + (size_t)cur * tk;
         const uint32_t JSV_CONST* k32 = as_uniform((const uint32_t*)pl.k32) + (size_t)cur * tk;
-        const Quad JSV_CONST* quads = as_uniform((const Quad*)pl.quads) + (size_t)cur * pl.k_max;
+        const Quad JSV_CONST* quads = as_uniform((const Quad*)pl.quads) + (size_t)cur * quad_stride(pl.k_max);
         const uint64_t local = tile - in->tile_begin;
         const uint32_t n_chunks = in->n_chunks;
         const uint32_t chunk_id = (uint32_t)(local % n_chunks);
@@ -1751,7 +2072,7 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
             const bool improved = __builtin_amdgcn_ballot_w64((best.key != key_before) | (best.obj != obj_before)) != 0;
             if (improved) {
                 uint32_t wc = 0xFFFFFFFFu;
-                if constexpr (MODE != MODE_OBJ) {
+                if constexpr (!is_obj(MODE)) {
                     // cost modes: nothing costlier than a candidate that meets both SLOs can be the answer
                     const uint32_t c = best.key == NO_KEY ? 0xFFFFFFFFu : (uint32_t)(best.key >> in->idx_bits);
                     wc = (uint32_t)wave_min((uint64_t)c);
@@ -1775,7 +2096,9 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     if (cur != 0xFFFFFFFFu) {
         flush_block<OBJ>(pl, cur, best, s_red, s_red_obj);
     }
-    if constexpr (BOUNDS)       // (the plain enumeration visits everything: the host reports the space)
+    // (the plain enumeration of single tuples visits everything: the host reports the space;
+    // the latency-sorted stream of mixture mode ends early, so its entries are counted)
+    if (BOUNDS || pl.mix != 0)
         if ((threadIdx.x & 63u) == 0 && visited != 0) atomicAdd(&pl.summary->visited, (unsigned long long)visited);
 }
 
@@ -1990,11 +2313,15 @@ static EnumerateFn enumerate_entry(int mode, bool bounds)
     switch (mode) {
     case MODE_OBJ: return bounds ? enumerate_kernel<MODE_OBJ, true> : enumerate_kernel<MODE_OBJ, false>;
     case MODE_MIX: return bounds ? enumerate_kernel<MODE_MIX, true> : enumerate_kernel<MODE_MIX, false>;
+    case MODE_MIXOBJ: return bounds ? enumerate_kernel<MODE_MIXOBJ, true> : enumerate_kernel<MODE_MIXOBJ, false>;
     default:       return bounds ? enumerate_kernel<MODE_COST, true> : enumerate_kernel<MODE_COST, false>;
     }
 }
 
-int enumerate_mode(bool objective, bool mixtures) { return objective ? MODE_OBJ : mixtures ? MODE_MIX : MODE_COST; }
+int enumerate_mode(bool objective, bool mixtures)
+{
+    return objective ? (mixtures ? MODE_MIXOBJ : MODE_OBJ) : mixtures ? MODE_MIX : MODE_COST;
+}
 
 // Blocks of the enumeration kernel that are resident per CU with this much LDS; with bounds
 // on, the smaller figure of the two variants that launch_enumerate sends out.
