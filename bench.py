@@ -42,13 +42,18 @@ UNSHARED_OPS_PER_CANDIDATE = 11
 # against a 1 GiB copy (profiles/enumerate_kernel_xr8_hbm_traffic.md); known only for the
 # default workload in cost mode.
 # key: workload, seed, objective mode, mixture mode, bounds
-MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (3641 + 11411) * 1024,
-                          ("xr8", 0, False, False, True): (15069 + 14636) * 1024}
+MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (5411 + 11125) * 1024,
+                          ("xr8", 0, False, False, True): (16277 + 3211) * 1024}
 # SQ counters of the same launch (profiles/enumerate_kernel_xr8_counters.md): vector instructions
 # issued per candidate (wave instructions x 64 lanes / candidates) and VALU issue utilisation
-# (busy cycles of the vector ALUs / elapsed cycles); same key as above
-MEASURED_COUNTERS = {("xr8", 0, False, False, False): {"valu_lane_ops_per_candidate": 3.17, "issue_utilisation": 0.982,
-                                                       "source": "profiles/enumerate_kernel_xr8_counters.md"}}
+# (wave instructions x 4 cycles / (SIMDs x elapsed cycles)); same key as above
+MEASURED_COUNTERS = {("xr8", 0, False, False, False): {"valu_lane_ops_per_candidate": 2.82, "issue_utilisation": 1.01,
+                                                       "scalar_instructions_per_cu_cycle": 0.48,
+                                                       "source": "profiles/enumerate_kernel_xr8_counters.md"},
+                     ("xr8", 0, False, False, True): {"valu_lane_ops_per_scored_candidate": 10.1, "issue_utilisation": 0.73,
+                                                      "source": "profiles/enumerate_kernel_xr8_counters.md"},
+                     ("xr8", 0, True, False, False): {"valu_lane_ops_per_candidate": 3.82, "issue_utilisation": 1.00,
+                                                      "source": "profiles/enumerate_kernel_xr8_counters.md"}}
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one full-rate VALU lane-op per lane per cycle
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
@@ -188,7 +193,13 @@ def thinning_loss(jsv_mod, w, mixtures: bool):
     j.load(pb)
     lo_cap, hi_cap = (16, 36) if mixtures else (se.prune_cap, pb.C)
     a, sa = j.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, lo_cap)
-    b, sb = j.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, hi_cap)
+    try:
+        b, sb = j.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, hi_cap)
+    except jsv_mod.JsvError:
+        # the exact fronts of some level span more than a 63-bit key holds: twice the cap instead
+        # (exact wherever no list is thinned at that cap; "reference_thinned" says where not)
+        hi_cap = 2 * lo_cap
+        b, sb = j.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, hi_cap)
     j.close()
     gaps = []
     for l, (x, y) in enumerate(zip(a, b)):
@@ -197,6 +208,7 @@ def thinning_loss(jsv_mod, w, mixtures: bool):
                      "thinned": bool(x.flags & 1), "reference_thinned": bool(y.flags & 1)})
     both = [(g["cost_capped"], g["cost_reference"]) for g in gaps if g["cost_capped"] is not None and g["cost_reference"] is not None]
     return {"cap": lo_cap, "reference_cap": hi_cap, "reference_is_exact_front": not any(g["reference_thinned"] for g in gaps),
+            "levels_with_exact_reference": sum(not g["reference_thinned"] for g in gaps),
             "levels_feasible_capped": sum(g["cost_capped"] is not None for g in gaps),
             "levels_feasible_reference": sum(g["cost_reference"] is not None for g in gaps),
             "levels_costlier_when_capped": sum(x > y for x, y in both),
