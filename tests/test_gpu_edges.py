@@ -312,3 +312,77 @@ def test_results_do_not_depend_on_the_launch_geometry(ctx, name, cap):
     with pytest.raises(jsv.JsvError) as e:
         ctx.set_geometry(9, 0)
     assert e.value.code == jsv.E_BADARG
+
+
+# ---- the loop that keeps one accuracy mask per variant of the innermost position ---------------
+# It runs where a lane loops over two or three positions.  Small graphs get there when the planner
+# is asked for few lanes (one block per compute unit, 1 % of the usual lane count); every case
+# also runs with the automatic geometry.
+GEOMETRIES = [(0, 0), (1, 1), (2, 4)]
+
+
+def _check_under_geometries(ctx, pb, se, bounds=(True, False)):
+    try:
+        for blocks, lanes in GEOMETRIES:
+            ctx.set_geometry(blocks, lanes)
+            for b in bounds:
+                ctx.set_bounds(b)
+                check_search(ctx, pb, se)
+    finally:
+        ctx.set_geometry(0, 0)
+        ctx.set_bounds(True)
+
+
+@pytest.mark.parametrize("V", [1, 2, 7, 8, 9])
+def test_variant_counts_around_the_limit_of_the_masked_loop(ctx, V):
+    """Up to eight variants in the innermost position's stream take the loop with one mask per
+    variant; nine take the general loop.  Same answers either way (oracle), with and without
+    bounds and in objective mode."""
+    T = 7 if V == 1 else 5               # (few choices per task need more tasks for a lane to loop over two)
+    edges = [(0, 1), (0, 2), (1, 3), (2, 3), (3, 4)] + ([(2, 5), (4, 6)] if V == 1 else [])
+    pb = _problem(T, V, 2, 2, 40 + V, edges, capacity=60)
+    se = _search([30000, 150000, 700000], 160000 if V > 1 else 260000, 0.6)
+    _check_under_geometries(ctx, pb, se)
+    o = oracle.Oracle.from_problem(pb)
+    o.set_objective(1, 1.0, 0.02)
+    ref, _, _ = o.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 0, threads=16)
+    margins = [o.objective_margin(int(D), se.slo_latency_us, se.slo_accuracy, 0) if V <= 2 else None
+               for D in se.demand_mrps]
+    ctx.set_objective(1, 1.0, 0.02)
+    try:
+        ctx.load(pb)
+        for blocks, lanes in GEOMETRIES:
+            ctx.set_geometry(blocks, lanes)
+            got, _ = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 0)
+            for l, (a, b) in enumerate(zip(got, ref)):
+                assert a.feasible == b.feasible
+                if not b.feasible:
+                    continue
+                assert abs(a.objective - b.objective) <= 1e-12 * max(1.0, abs(b.objective))
+                if a.index == b.index or (margins[l] is not None and margins[l] > 1e-9):
+                    same(a, b, f"level {l}")
+    finally:
+        ctx.set_objective(0)
+        ctx.set_geometry(0, 0)
+
+
+@pytest.mark.parametrize("PB", [(1, 1), (1, 2), (1, 3), (1, 5), (2, 3), (1, 7), (3, 3)])
+def test_every_length_of_a_run_of_equal_accuracy(ctx, PB):
+    """The second in-lane position goes through the stream four digits at a time, then two, then
+    one: runs of 1, 2, 3, 5, 6, 7 and 9 digits per variant cover every remainder."""
+    P, B = PB
+    K = 3 * P * B
+    T = 10 if K <= 3 else 6 if K <= 9 else 5
+    edges = [(0, 1), (1, 2), (0, 3), (3, 4)] + ([(2, 5)] if T >= 6 else []) + ([(4, 6), (5, 7), (6, 8), (7, 9)] if T == 10 else [])
+    pb = _problem(T, 3, P, B, 60 + 10 * P + B, edges, capacity=0)
+    for slo_a in (0.0, 0.62, 0.8):
+        _check_under_geometries(ctx, pb, _search([20000, 400000], 250000 if K > 3 else 1200000, slo_a))
+
+
+def test_variants_of_equal_accuracy_share_their_run(ctx):
+    """Two variants of a task with bit-identical accuracy: in the second position they form one
+    run, in the innermost they keep their own masks, which are then equal."""
+    pb = _problem(5, 4, 2, 2, 77, [(0, 1), (1, 2), (2, 3), (0, 4)])
+    pb.accuracy[:, 1] = pb.accuracy[:, 2]
+    for slo_a in (0.55, 0.7, 0.85):
+        _check_under_geometries(ctx, pb, _search([50000, 900000], 210000, slo_a))
