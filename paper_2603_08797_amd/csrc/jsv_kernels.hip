@@ -1670,17 +1670,17 @@ __device__ __forceinline__ void variant_masks(const Uniforms& U, uint32_t nvx, d
 
 typedef uint32_t YWords __attribute__((ext_vector_type(16), aligned(16)));      // four YRec
 
-template <int MODE, bool BOUNDS>
+template <int MODE, bool BOUNDS, bool E01>
 __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
                                               uint32_t x_hi, uint64_t full, TileBest& tb)
 {
 #pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
     const Entry JSV_CONST* ty = U.tab[1];
-    // Position 1 is either a successor of position 0 (its only possible predecessor) or a source:
-    // in the first case its tail changes position 0's latency threshold, in the second the
-    // lanes that still meet the latency SLO.  Wave-uniform, as scalars.
-    const uint32_t e01 = __builtin_amdgcn_readfirstlane(U.m01);
-    const uint32_t src1 = __builtin_amdgcn_readfirstlane(U.src[1] ? 1u : 0u);
+    // Position 1 is either a successor of position 0 (its only possible predecessor; E01) or a
+    // source: in the first case its tail changes position 0's latency threshold, in the second
+    // the lanes that still meet the latency SLO.
+    constexpr uint32_t e01 = E01 ? 1u : 0u;
+    constexpr uint32_t src1 = E01 ? 0u : 1u;
     const uint32_t nvx = __builtin_amdgcn_readfirstlane(U.nvx);
     uint32_t qe[MAX_XVAR];
 #pragma unroll
@@ -1767,7 +1767,12 @@ __device__ __forceinline__ void loop_y(const LaneState& s, const Uniforms& U, ui
 {
     if constexpr (W32 && !is_mix(MODE)) {
         // single tuples with few variants in position 0 (nvx is 0 for a stream of mixtures)
-        if (U.nvx - 1u < (uint32_t)MAX_XVAR) { loop_y_masked<MODE, BOUNDS>(s, U, lo, hi, x_hi, full, tb); return; }
+        // (position 1 is a source exactly when position 0, its only possible predecessor, does not feed it)
+        if (U.nvx - 1u < (uint32_t)MAX_XVAR && U.src[1] == (U.m01 == 0)) {
+            if (U.m01 != 0) loop_y_masked<MODE, BOUNDS, true>(s, U, lo, hi, x_hi, full, tb);
+            else loop_y_masked<MODE, BOUNDS, false>(s, U, lo, hi, x_hi, full, tb);
+            return;
+        }
     }
     const Entry JSV_CONST* ty = U.tab[1];
     for (uint32_t d = lo; d < hi; ++d) {
