@@ -35,6 +35,7 @@ __device__ __forceinline__ const T JSV_CONST* as_uniform(const T* p)
 }
 
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 __device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
 
 // ---- wave64 / block minimum of a u64 key -----------------------------------------------
@@ -1688,6 +1689,7 @@ __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms
     const uint32_t endb = x_hi * (uint32_t)sizeof(QuadC);
     const uint64_t alive0 = __builtin_amdgcn_ballot_w64(s.smax <= U.sloq);
     const uint32_t thr0 = __builtin_elementwise_sub_sat(U.sloq, s.nxt[0]);
+    const uint32_t room1 = __builtin_elementwise_sub_sat(U.sloq, s.nxt[1]);
     uint32_t d = lo;
     while (d < hi) {
         // a run of digits of position 1 that share their accuracy: what fix_position<1> does to the
@@ -1708,15 +1710,18 @@ __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms
             uint64_t go[4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const uint32_t tail = w[4 * g] + s.nxt[1];
-                uint32_t smax = s.smax;
+                // With tail = lat + nxt[1] (the digit's latency to the sinks) and room1 = sloq -sat nxt[1]:
+                // sloq -sat max(nxt[0], tail) = min(thr0, room1 -sat lat), and
+                // max(smax, tail) <= sloq  <=>  smax <= sloq and lat <= room1 (latencies are >= 1).
+                const uint32_t lat = w[4 * g];
+                bool meets = s.smax <= U.sloq;
                 thr[g] = thr0; go[g] = alive0; m[g] = 0xFFFFFFFFu;
-                if (e01 != 0) thr[g] = __builtin_elementwise_sub_sat(U.sloq, umax(s.nxt[0], tail));
-                if (src1 != 0) { smax = umax(s.smax, tail); go[g] = __builtin_amdgcn_ballot_w64(smax <= U.sloq); }
+                if (e01 != 0) thr[g] = umin(thr0, __builtin_elementwise_sub_sat(room1, lat));
+                if (src1 != 0) { meets = meets & (lat <= room1); go[g] = __builtin_amdgcn_ballot_w64(meets); }
                 if constexpr (BOUNDS) {
                     // also out: lanes whose fixed positions plus the cheapest entry of position 0 cost more than the bound
                     const uint32_t fixed = s.cost_out + ((s.k32 + w[4 * g + 1]) >> U.lb);
-                    go[g] = __builtin_amdgcn_ballot_w64((smax <= U.sloq) & (thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
+                    go[g] = __builtin_amdgcn_ballot_w64(meets & (thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
                 }
                 if ((uint32_t)g >= n) go[g] = 0;
                 if constexpr (BOUNDS) { if (go[g] != 0) tb.visits += x_hi * 4u; }

@@ -386,3 +386,11 @@ def test_variants_of_equal_accuracy_share_their_run(ctx):
     pb.accuracy[:, 1] = pb.accuracy[:, 2]
     for slo_a in (0.55, 0.7, 0.85):
         _check_under_geometries(ctx, pb, _search([50000, 900000], 210000, slo_a))
+
+
+def test_long_streams_and_long_runs_in_the_masked_loop(ctx):
+    """512 choices per task in 8 variants: 128 records in the innermost stream, runs of 64 digits in
+    the second position."""
+    pb = _problem(3, 8, 8, 8, 91, [(0, 1), (0, 2)], capacity=0)
+    _check_under_geometries(ctx, pb, _search([60000, 2_000_000], 140000, 0.7), bounds=(True,))
+    _check_under_geometries(ctx, pb, _search([60000], 140000, 0.7, cap=96), bounds=(False,))
