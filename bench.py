@@ -336,6 +336,29 @@ def main():
                        "candidates_scored_per_step": min(summ_b.candidates_visited, sum(r.evaluated for r in res_b)),
                        "same_results_as_plain_enumeration": same}
 
+    single_level = None
+    if not batch and factors is None and n_levels > 1 and not args.graph and not args.plain_only:
+        # latency of one search over one demand level: the feasible level with the largest demand,
+        # as a caller would ask for it (bounds on) and as the plain enumeration; 3 warm-up + 10 timed
+        feas = [l for l, r in enumerate(res) if r.feasible]
+        if feas:
+            l1 = max(feas, key=lambda l: int(se.demand_mrps[l]))
+            one = se.demand_mrps[l1:l1 + 1]
+            single_level = {"level": l1, "demand_mrps": int(one[0]), "candidates": res[l1].evaluated}
+            for name, on in (("with_bounds_ms", True), ("plain_ms", False)):
+                j.set_bounds(on)
+                for _ in range(3):
+                    j.search(one, se.slo_latency_us, se.slo_accuracy, se.prune_cap)
+                torch.cuda.synchronize()
+                t3 = time.perf_counter()
+                for _ in range(10):
+                    r1, _ = j.search(one, se.slo_latency_us, se.slo_accuracy, se.prune_cap)
+                torch.cuda.synchronize()
+                single_level[name] = (time.perf_counter() - t3) / 10 * 1e3
+                single_level["same_answer"] = single_level.get("same_answer", True) and \
+                    (r1[0].feasible, r1[0].index, r1[0].cost) == (res[l1].feasible, res[l1].index, res[l1].cost)
+            j.set_bounds(args.bounds)
+
     other_seeds = None
     if (args.workload == "xr8" and not args.no_other_seeds and not batch and factors is None
             and not args.mixtures and not args.objective and not args.bounds and not args.graph):
@@ -412,6 +435,8 @@ def main():
         if probe and probe.get("v_min_u32"):
             # against the issue rate of the loop's own instructions (compare and minimum)
             out["roofline"]["frac_of_measured_peak"] = achieved / (probe["v_min_u32"] * 1e12)
+    if single_level is not None:
+        out["single_level"] = single_level
     if other_seeds is not None:
         out["config"]["other_seeds"] = other_seeds
     if with_bounds is not None:

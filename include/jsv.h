@@ -181,7 +181,7 @@ JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial
  * excluded candidate fails a constraint or is worse than one that was found); off makes the kernel issue the tests
  * of every candidate, which is what throughput measurements of the plain enumeration use.
  * jsv_summary.candidates_visited tells how many candidates had their tests issued.  A search
- * with fewer than 32 tiles of 256 lanes per block of the grid runs the plain enumeration even
+ * with fewer than 8 tiles of 256 lanes per block of the grid runs the plain enumeration even
  * with bounds on: everything is in flight at once there and no bound would arrive in time.
  */
 JSV_API int jsv_set_bounds(jsv_ctx* ctx, int on);

@@ -35,6 +35,7 @@ namespace jsv {
 constexpr int MAXT = 16;          // tasks per graph
 constexpr int MAXC = 2048;        // choices per task
 constexpr int TILE_LANES = 256;   // lanes (threads) per enumeration tile
+constexpr uint32_t BOUNDS_MIN_TILES_PER_BLOCK = 8;   // fewer tiles per block of the grid: the search runs without bounds
 constexpr int MAXE = MAXT * (MAXT - 1) / 2;   // edges of a task graph without cycles
 constexpr uint16_t NOT_HELD = 0xFFFF;
 constexpr uint64_t NEED_LIMIT = 1ull << 44;   // micro-requests/s a task may see with per-variant factors

@@ -585,7 +585,7 @@ int run_search(jsv_ctx* ctx, std::vector<Instance>& inst, uint32_t t_max, uint32
             const double kk = mix_cells ? (double)k_max : (double)k_max_of(hp, inst[k].cap);
             most += std::pow(kk, (double)hp.T) / (64.0 * jsv::TILE_LANES) + 1.0;
         }
-        if (most < (double)ctx->grid * 32.0) with_bounds = false;
+        if (most < (double)ctx->grid * (double)jsv::BOUNDS_MIN_TILES_PER_BLOCK) with_bounds = false;
     }
     pl.bounds = with_bounds ? 1u : 0u;
     pl.cut = ctx->bounds ? 1u : 0u;

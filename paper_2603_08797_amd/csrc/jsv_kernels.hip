@@ -3,11 +3,16 @@
 //   prune_kernel      replicas and cost of every (task, choice) at every level
 //                     (Eq. 5-7), then the per-task prune: latency filter, exact
 //                     dominance, cap thinning, compaction.
+//   mix_kernel        mixture mode: the options of every task (Eq. 2, 6, 7, 9, 10) in place
+//                     of prune_kernel.
 //   plan_kernel       index strides, packed keys, local keys and the innermost stream,
-//                     tile geometry per instance; its last block scans the tile counts.
+//                     tile geometry per instance; its last block evens out the tiles,
+//                     scans their counts and fixes how they are handed to the blocks.
 //   enumerate_kernel  every candidate scored and masked (Eq. 3, 8, 11-13) and
-//                     reduced per lane / wave / block to the cheapest feasible one
-//                     (<false>) or to the one with the best objective of Eq. 14 (<true>).
+//                     reduced per lane / wave / block to the cheapest feasible one or to
+//                     the one with the best objective of Eq. 14; <MODE, BOUNDS>: single
+//                     tuples or mixtures, either objective, with or without the bulk
+//                     exclusion by bounds.
 //   finalize_kernel   grid-level reduction, winner decoded and rescored, sweep summary.
 //   eval_kernel       explicit candidates scored one per thread (parity aid).
 //
@@ -17,7 +22,7 @@
 // they feed the vector ALU as scalar operands; the entries that differ per lane are
 // gathered from a copy of the instance's tables in LDS.  In the common case a
 // candidate costs two vector instructions: a latency compare that narrows the
-// execution mask and a minimum on a 32-bit local key (loop_x32).
+// execution mask and a minimum on a 32-bit local key (loop_x32_masked, loop_x32).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -600,12 +605,13 @@ __global__ void __launch_bounds__(256) mix_kernel(Plan pl)
 // Giving every block one long contiguous run was tried too and is slower still: seven blocks of
 // a compute unit then stream seven instances' tables through one scalar cache.
 constexpr uint32_t STATIC_ONLY_TILES_PER_BLOCK = 8;   // up to here: no counter at all
+constexpr uint32_t BOUNDED_COUNTER_TILES_PER_BLOCK = 64;   // with bounds: below this no counter either (one level of a
+                                                      // large search: 0.51-0.72 ms by index, 0.59-0.85 ms with tickets)
 constexpr uint32_t ROUNDS_WANTED = 64;                // with bounds: rounds the part shared out by index is cut into
 constexpr uint32_t BATCHES_PER_BLOCK_PLAIN = 128;     // batches per block from the counter, every candidate scored
 constexpr uint32_t BATCHES_PER_BLOCK_BOUNDED = 8;     // ... and with bounds
 
 // ---- plan -------------------------------------------------------------------------------
-constexpr uint32_t BOUNDS_MIN_TILES_PER_BLOCK = 32;
 // Balancing of the tile sizes (scan_tiles): the enumeration's blocks should each see about this
 // many tiles, but no tile is cut below MIN_TILE_COST candidates per lane, where the per-tile
 // set-up would start to show.
@@ -706,12 +712,15 @@ __device__ void scan_tiles(const Plan& pl, uint64_t* s_sum)
         pl.summary->visited = 0;
         // A cost bound found in one tile helps the tiles that start after it: with only a few
         // tiles per block everything runs at once and the bookkeeping would be pure overhead.
+        // (From 8 tiles per block it pays: one 20^8-candidate level takes 0.6-0.8 ms instead of 2.0.)
         const bool bounded = pl.bounds && total_tiles >= (uint64_t)pl.grid * BOUNDS_MIN_TILES_PER_BLOCK;
         pl.summary->bounded = bounded ? 1u : 0u;
         // Rounds of own runs, then batches of the rest from the counter (see above).
         const uint64_t G = pl.grid;
         uint64_t own = 1, rounds = 0, batch;
-        if (total_tiles <= G * STATIC_ONLY_TILES_PER_BLOCK) { rounds = (total_tiles + G - 1) / G; batch = 0; }
+        if (total_tiles <= G * STATIC_ONLY_TILES_PER_BLOCK || (bounded && total_tiles < G * BOUNDED_COUNTER_TILES_PER_BLOCK)) {
+            rounds = (total_tiles + G - 1) / G; batch = 0;
+        }
         else {
             if (bounded) {
                 own = total_tiles / (4 * G * ROUNDS_WANTED);
