@@ -42,17 +42,17 @@ UNSHARED_OPS_PER_CANDIDATE = 11
 # against a 1 GiB copy (profiles/enumerate_kernel_xr8_hbm_traffic.md); known only for the
 # default workload in cost mode.
 # key: workload, seed, objective mode, mixture mode, bounds
-MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (5411 + 11125) * 1024,
-                          ("xr8", 0, False, False, True): (16277 + 3211) * 1024}
+MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (5985 + 11087) * 1024,
+                          ("xr8", 0, False, False, True): (16048 + 3296) * 1024}
 # SQ counters of the same launch (profiles/enumerate_kernel_xr8_counters.md): vector instructions
 # issued per candidate (wave instructions x 64 lanes / candidates) and VALU issue utilisation
 # (wave instructions x 4 cycles / (SIMDs x elapsed cycles)); same key as above
-MEASURED_COUNTERS = {("xr8", 0, False, False, False): {"valu_lane_ops_per_candidate": 2.82, "issue_utilisation": 1.01,
-                                                       "scalar_instructions_per_cu_cycle": 0.48,
+MEASURED_COUNTERS = {("xr8", 0, False, False, False): {"valu_lane_ops_per_candidate": 2.66, "issue_utilisation": 1.01,
+                                                       "scalar_instructions_per_cu_cycle": 0.43,
                                                        "source": "profiles/enumerate_kernel_xr8_counters.md"},
-                     ("xr8", 0, False, False, True): {"valu_lane_ops_per_scored_candidate": 10.1, "issue_utilisation": 0.73,
+                     ("xr8", 0, False, False, True): {"valu_lane_ops_per_scored_candidate": 8.6, "issue_utilisation": 0.69,
                                                       "source": "profiles/enumerate_kernel_xr8_counters.md"},
-                     ("xr8", 0, True, False, False): {"valu_lane_ops_per_candidate": 3.82, "issue_utilisation": 1.00,
+                     ("xr8", 0, True, False, False): {"valu_lane_ops_per_candidate": 3.67, "issue_utilisation": 0.99,
                                                       "source": "profiles/enumerate_kernel_xr8_counters.md"}}
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one full-rate VALU lane-op per lane per cycle
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
@@ -337,7 +337,7 @@ def main():
                        "same_results_as_plain_enumeration": same}
 
     single_level = None
-    if not batch and factors is None and n_levels > 1 and not args.graph and not args.plain_only:
+    if not batch and factors is None and n_levels > 1 and not args.graph and not args.plain_only and not args.bounds:
         # latency of one search over one demand level: the feasible level with the largest demand,
         # as a caller would ask for it (bounds on) and as the plain enumeration; 3 warm-up + 10 timed
         feas = [l for l, r in enumerate(res) if r.feasible]
