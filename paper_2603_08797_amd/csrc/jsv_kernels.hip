@@ -764,6 +764,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     // quad of the variant that starts at digit d
     __shared__ uint16_t s_xvar[MAXC];
     __shared__ uint32_t s_xlat[MAXC], s_xcost[MAXC], s_xq0[MAXC];
+    __shared__ uint64_t s_yacc[MAXC];       // position 1's accuracies as bit patterns (runs of equal accuracy)
     __shared__ uint64_t s_sum[256];
     __shared__ uint32_t s_part[256];
     // graph facts the single-thread section below needs, fetched by many threads at once
@@ -794,6 +795,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             s_xcost[d] = c; s_xlat[d] = lat; s_xvar[d] = (uint16_t)(e->choice / PB);
             atomicMin(&s_minxlat, lat);
         }
+        if (T >= 2 && t == s_task_at[1]) s_yacc[d] = __builtin_bit_cast(uint64_t, e->acc);
     }
     __syncthreads();
     // quads of position 0's stream (single tuples): every variant's entries rounded up to whole
@@ -1001,9 +1003,9 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         const Entry* ey = ent + (size_t)ty * pl.k_max;
         YRec* yr = (YRec*)(pl.quads + (size_t)i * quad_stride(pl.k_max) + yrec_offset(pl.k_max));
         for (uint32_t d = tid; d < KY; d += blockDim.x) {
-            const uint64_t bits = __builtin_bit_cast(uint64_t, ey[d].acc);
+            const uint64_t bits = s_yacc[d];
             uint32_t e = d + 1;
-            while (e < KY && __builtin_bit_cast(uint64_t, ey[e].acc) == bits) ++e;
+            while (e < KY && s_yacc[e] == bits) ++e;
             YRec r;
             r.lat = ey[d].lat; r.k32 = (ey[d].cost << s_lb) | (d * s_lsT[ty]); r.run_end = e; r.pad = 0;
             yr[d] = r;
