@@ -87,14 +87,14 @@ static_assert(sizeof(QuadM) == 64, "QuadM must be 64 bytes");
 // the stream's end is read ahead and never used.
 struct __attribute__((aligned(32))) QuadC { XEnt e[4]; };
 static_assert(sizeof(QuadC) == 32, "QuadC must be 32 bytes");
-// What that loop needs of one digit of the position above the innermost one (position 1), one
-// 16-byte scalar load: its latency, its 32-bit local key, and the first later digit whose
-// variant has another accuracy (digits in between share the accuracy outcome of every variant
-// of position 0).
-struct __attribute__((aligned(16))) YRec { uint32_t lat; uint32_t k32; uint32_t run_end; uint32_t pad; };
-static_assert(sizeof(YRec) == 16, "YRec must be 16 bytes");
+// What that loop needs of the digits of the position above the innermost one (position 1): three
+// arrays of k_max + 3 words each, one after the other - latencies, 32-bit local keys (four of
+// each are read at a time, from any digit), and per digit the first later digit whose variant
+// has another accuracy (digits in between share the accuracy outcome of every variant of
+// position 0).
+constexpr uint32_t ydigit_words(uint32_t k_max) { return k_max + 3; }
 // Records of 64 bytes per instance in the stream buffer: k_max Quad (or QuadM), then
-// k_max + 1 QuadC, then k_max + 3 YRec (four are read at a time, from any digit).
+// k_max + 1 QuadC, then the three arrays of position 1's digits (3 x ydigit_words(k_max) words).
 constexpr uint32_t quad_stride(uint32_t k_max) { return k_max + (k_max + 2) / 2 + (k_max + 6) / 4; }
 constexpr uint32_t quadc_offset(uint32_t k_max) { return k_max; }                          // in Quad units
 constexpr uint32_t yrec_offset(uint32_t k_max) { return k_max + (k_max + 2) / 2; }

@@ -1001,14 +1001,14 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     if (s_nin >= 2 && !pl.mix) {
         const uint32_t ty = s_task_at[1], KY = s_K[ty];
         const Entry* ey = ent + (size_t)ty * pl.k_max;
-        YRec* yr = (YRec*)(pl.quads + (size_t)i * quad_stride(pl.k_max) + yrec_offset(pl.k_max));
+        uint32_t* ylat = (uint32_t*)(pl.quads + (size_t)i * quad_stride(pl.k_max) + yrec_offset(pl.k_max));
+        uint32_t* yk32 = ylat + ydigit_words(pl.k_max);
+        uint32_t* yrun = yk32 + ydigit_words(pl.k_max);
         for (uint32_t d = tid; d < KY; d += blockDim.x) {
             const uint64_t bits = s_yacc[d];
             uint32_t e = d + 1;
             while (e < KY && s_yacc[e] == bits) ++e;
-            YRec r;
-            r.lat = ey[d].lat; r.k32 = (ey[d].cost << s_lb) | (d * s_lsT[ty]); r.run_end = e; r.pad = 0;
-            yr[d] = r;
+            ylat[d] = ey[d].lat; yk32[d] = (ey[d].cost << s_lb) | (d * s_lsT[ty]); yrun[d] = e;
         }
     }
     for (uint32_t b = tid; b < pl.grid; b += blockDim.x) {
@@ -1061,7 +1061,9 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     const double JSV_CONST* xacc;
     const uint32_t JSV_CONST* xqe;     // where each variant ends in the QuadC copy of the stream (bytes)
     const QuadC JSV_CONST* xq;         // that copy
-    const YRec JSV_CONST* yrec;        // position 1's digits
+    const uint32_t JSV_CONST* ylat;    // position 1's digits: latencies,
+    const uint32_t JSV_CONST* yk32;    // local keys,
+    const uint32_t JSV_CONST* yrun;    // ends of their runs of equal accuracy
 };
 
 // Fix position P (a wave-uniform entry) and push its contribution down.  hin[P]
@@ -1680,7 +1682,7 @@ __device__ __forceinline__ void variant_masks(const Uniforms& U, uint32_t nvx, d
 #endif
 }
 
-typedef uint32_t YWords __attribute__((ext_vector_type(16), aligned(16)));      // four YRec
+typedef uint32_t YWords __attribute__((ext_vector_type(4), aligned(4)));       // four digits' latencies or keys
 
 template <int MODE, bool BOUNDS, bool E01>
 __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
@@ -1705,7 +1707,7 @@ __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms
     while (d < hi) {
         // a run of digits of position 1 that share their accuracy: what fix_position<1> does to the
         // accuracy state, then Eq. 13 for every variant of position 0
-        const uint32_t run_end = U.yrec[d].run_end;
+        const uint32_t run_end = U.yrun[d];
         const uint32_t re = run_end < hi ? run_end : hi;
         const double H = ty[d].acc * s.hin[1];
         const double sacc = src1 != 0 ? s.sacc + H : s.sacc;
@@ -1714,8 +1716,9 @@ __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms
         variant_masks(U, nvx, hin0, sacc, mk);
         uint32_t best_rel = 0xFFFFFFFFu;        // cost modes: the run's minimum of position 1's key plus position 0's
         for (; d < re; d += 4) {
-            // four digits at a time, one 64-byte scalar load (slots past the run stay without lanes)
-            const YWords w = *(const YWords JSV_CONST*)(U.yrec + d);
+            // four digits at a time, two 16-byte scalar loads
+            const YWords lat4 = *(const YWords JSV_CONST*)(U.ylat + d);
+            const YWords key4 = *(const YWords JSV_CONST*)(U.yk32 + d);
             const uint32_t n = re - d;
             uint32_t thr[4], m[4];
             uint64_t go[4];
@@ -1724,18 +1727,22 @@ __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms
                 // With tail = lat + nxt[1] (the digit's latency to the sinks) and room1 = sloq -sat nxt[1]:
                 // sloq -sat max(nxt[0], tail) = min(thr0, room1 -sat lat), and
                 // max(smax, tail) <= sloq  <=>  smax <= sloq and lat <= room1 (latencies are >= 1).
-                const uint32_t lat = w[4 * g];
+                const uint32_t lat = lat4[g];
                 bool meets = s.smax <= U.sloq;
                 thr[g] = thr0; go[g] = alive0; m[g] = 0xFFFFFFFFu;
                 if (e01 != 0) thr[g] = umin(thr0, __builtin_elementwise_sub_sat(room1, lat));
                 if (src1 != 0) { meets = meets & (lat <= room1); go[g] = __builtin_amdgcn_ballot_w64(meets); }
                 if constexpr (BOUNDS) {
                     // also out: lanes whose fixed positions plus the cheapest entry of position 0 cost more than the bound
-                    const uint32_t fixed = s.cost_out + ((s.k32 + w[4 * g + 1]) >> U.lb);
+                    const uint32_t fixed = s.cost_out + ((s.k32 + key4[g]) >> U.lb);
                     go[g] = __builtin_amdgcn_ballot_w64(meets & (thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
                 }
-                if ((uint32_t)g >= n) go[g] = 0;
-                if constexpr (BOUNDS) { if (go[g] != 0) tb.visits += x_hi * 4u; }
+                // (without bounds a slot past the run keeps whatever lanes: only the first n slots are
+                // passed on below, and in the usual case all four share one set of live lanes)
+                if constexpr (BOUNDS) {
+                    if ((uint32_t)g >= n) go[g] = 0;
+                    if (go[g] != 0) tb.visits += x_hi * 4u;
+                }
             }
             if constexpr (BOUNDS) { if ((go[0] | go[1] | go[2] | go[3]) == 0) continue; }
             if (n >= 4) loop_x32_masked<4, BOUNDS>(U, thr, go, mk, qe, endb, full, m);
@@ -1752,7 +1759,7 @@ __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms
             }
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const uint32_t rel = __builtin_elementwise_add_sat(m[g], w[4 * g + 1]);    // stays 0xFFFFFFFF if none
+                const uint32_t rel = __builtin_elementwise_add_sat(m[g], key4[g]);    // stays 0xFFFFFFFF if none
                 if constexpr (MODE == MODE_OBJ) {
                     // first of the two passes of objective mode (see loop_x); the second, rare, takes the
                     // general path with the lane state of this digit
@@ -1902,7 +1909,9 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     U.alpha_n = in->alpha_n; U.beta = in->beta;
     U.alpha = in->alpha; U.inv_beta = in->inv_beta; U.mix = mix;
     U.nvx = in->nvx; U.xacc = in->xacc; U.xqe = in->xqe; U.xq = (const QuadC JSV_CONST*)(quads + quadc_offset(k_max));
-    U.yrec = (const YRec JSV_CONST*)(quads + yrec_offset(k_max));
+    U.ylat = (const uint32_t JSV_CONST*)(quads + yrec_offset(k_max));
+    U.yk32 = U.ylat + ydigit_words(k_max);
+    U.yrun = U.yk32 + ydigit_words(k_max);
     st.cost_out = (uint32_t)(st.key >> in->idx_bits);
     // Cost as a bound: `bound` is S_avail (Eq. 8) or, in the cost modes, the cost of a candidate
     // already found that meets both SLOs, whichever is lower.  A lane whose fixed positions plus
