@@ -42,17 +42,17 @@ UNSHARED_OPS_PER_CANDIDATE = 11
 # against a 1 GiB copy (profiles/enumerate_kernel_xr8_hbm_traffic.md); known only for the
 # default workload in cost mode.
 # key: workload, seed, objective mode, mixture mode, bounds
-MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (5985 + 11087) * 1024,
-                          ("xr8", 0, False, False, True): (16048 + 3296) * 1024}
+MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (5253 + 11092) * 1024,
+                          ("xr8", 0, False, False, True): (14619 + 3302) * 1024}
 # SQ counters of the same launch (profiles/enumerate_kernel_xr8_counters.md): vector instructions
 # issued per candidate (wave instructions x 64 lanes / candidates) and VALU issue utilisation
 # (wave instructions x 4 cycles / (SIMDs x elapsed cycles)); same key as above
-MEASURED_COUNTERS = {("xr8", 0, False, False, False): {"valu_lane_ops_per_candidate": 2.66, "issue_utilisation": 1.01,
-                                                       "scalar_instructions_per_cu_cycle": 0.43,
+MEASURED_COUNTERS = {("xr8", 0, False, False, False): {"valu_lane_ops_per_candidate": 2.63, "issue_utilisation": 1.01,
+                                                       "scalar_instructions_per_cu_cycle": 0.45,
                                                        "source": "profiles/enumerate_kernel_xr8_counters.md"},
-                     ("xr8", 0, False, False, True): {"valu_lane_ops_per_scored_candidate": 8.6, "issue_utilisation": 0.69,
+                     ("xr8", 0, False, False, True): {"valu_lane_ops_per_scored_candidate": 8.7, "issue_utilisation": 0.68,
                                                       "source": "profiles/enumerate_kernel_xr8_counters.md"},
-                     ("xr8", 0, True, False, False): {"valu_lane_ops_per_candidate": 3.67, "issue_utilisation": 0.99,
+                     ("xr8", 0, True, False, False): {"valu_lane_ops_per_candidate": 3.58, "issue_utilisation": 0.99,
                                                       "source": "profiles/enumerate_kernel_xr8_counters.md"}}
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one full-rate VALU lane-op per lane per cycle
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
