@@ -91,10 +91,11 @@ static_assert(sizeof(QuadC) == 32, "QuadC must be 32 bytes");
 // arrays of k_max + 3 words each, one after the other - latencies, 32-bit local keys (four of
 // each are read at a time, from any digit), and per digit the first later digit whose variant
 // has another accuracy (digits in between share the accuracy outcome of every variant of
-// position 0).
+// position 0).  A fourth array of the same size holds, per digit of position 2, the first later
+// digit of another variant.
 constexpr uint32_t ydigit_words(uint32_t k_max) { return k_max + 3; }
 // Records of 64 bytes per instance in the stream buffer: k_max Quad (or QuadM), then
-// k_max + 1 QuadC, then the three arrays of position 1's digits (3 x ydigit_words(k_max) words).
+// k_max + 1 QuadC, then the four arrays of the digits of positions 1 and 2 (4 x ydigit_words(k_max) words).
 constexpr uint32_t quad_stride(uint32_t k_max) { return k_max + (k_max + 2) / 2 + (k_max + 6) / 4; }
 constexpr uint32_t quadc_offset(uint32_t k_max) { return k_max; }                          // in Quad units
 constexpr uint32_t yrec_offset(uint32_t k_max) { return k_max + (k_max + 2) / 2; }

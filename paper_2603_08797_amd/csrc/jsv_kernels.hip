@@ -765,6 +765,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     __shared__ uint16_t s_xvar[MAXC];
     __shared__ uint32_t s_xlat[MAXC], s_xcost[MAXC], s_xq0[MAXC];
     __shared__ uint64_t s_yacc[MAXC];       // position 1's accuracies as bit patterns (runs of equal accuracy)
+    __shared__ uint16_t s_zvar[MAXC];       // position 2's variants (runs of one variant)
     __shared__ uint64_t s_sum[256];
     __shared__ uint32_t s_part[256];
     // graph facts the single-thread section below needs, fetched by many threads at once
@@ -796,6 +797,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             atomicMin(&s_minxlat, lat);
         }
         if (T >= 2 && t == s_task_at[1]) s_yacc[d] = __builtin_bit_cast(uint64_t, e->acc);
+        if (T >= 3 && t == s_task_at[2]) s_zvar[d] = (uint16_t)(e->choice / PB);
     }
     __syncthreads();
     // quads of position 0's stream (single tuples): every variant's entries rounded up to whole
@@ -1010,6 +1012,17 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             while (e < KY && s_yacc[e] == bits) ++e;
             ylat[d] = ey[d].lat; yk32[d] = (ey[d].cost << s_lb) | (d * s_lsT[ty]); yrun[d] = e;
         }
+        if (s_nin >= 3) {
+            // position 2: per digit the end of its run of one variant
+            uint32_t* zrun = yrun + ydigit_words(pl.k_max);
+            const uint32_t KZ = s_K[s_task_at[2]];
+            for (uint32_t d = tid; d < KZ; d += blockDim.x) {
+                const uint16_t var = s_zvar[d];
+                uint32_t e = d + 1;
+                while (e < KZ && s_zvar[e] == var) ++e;
+                zrun[d] = e;
+            }
+        }
     }
     for (uint32_t b = tid; b < pl.grid; b += blockDim.x) {
         pl.partial[(size_t)i * pl.grid + b] = NO_KEY;
@@ -1064,6 +1077,7 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     const uint32_t JSV_CONST* ylat;    // position 1's digits: latencies,
     const uint32_t JSV_CONST* yk32;    // local keys,
     const uint32_t JSV_CONST* yrun;    // ends of their runs of equal accuracy
+    const uint32_t JSV_CONST* zrun;    // position 2's digits: ends of their runs of one variant
 };
 
 // Fix position P (a wave-uniform entry) and push its contribution down.  hin[P]
@@ -1684,17 +1698,97 @@ __device__ __forceinline__ void variant_masks(const Uniforms& U, uint32_t nvx, d
 
 typedef uint32_t YWords __attribute__((ext_vector_type(4), aligned(4)));       // four digits' latencies or keys
 
+// The digits [d, re) of one run of position 1, four at a time, against position 0's stream.
+// What the positions fixed so far give: smax (latest source so far), thr0 = sloq -sat nxt[0],
+// room1 = sloq -sat nxt[1], alive0 = lanes with smax <= sloq, k32 and cost_out.  mk: the
+// accuracy outcome per variant of position 0 for this run.  make_s1(digit): the full lane
+// state with that digit of position 1 fixed (objective mode's second pass only).
+template <int MODE, bool BOUNDS, bool E01, typename MakeS1>
+__device__ __forceinline__ void y_batches(const Uniforms& U, uint32_t smax, uint32_t thr0, uint32_t room1, uint64_t alive0,
+                                          uint32_t k32, uint32_t cost_out, uint32_t d, uint32_t re,
+                                          const uint64_t (&mk)[MAX_XVAR], const uint32_t (&qe)[MAX_XVAR], uint32_t endb,
+                                          uint32_t x_hi, uint64_t full, TileBest& tb, MakeS1 make_s1)
+{
+    // Position 1 is either a successor of position 0 (its only possible predecessor; E01) or a
+    // source: in the first case its tail changes position 0's latency threshold, in the second
+    // the lanes that still meet the latency SLO.
+    constexpr uint32_t e01 = E01 ? 1u : 0u;
+    constexpr uint32_t src1 = E01 ? 0u : 1u;
+    uint32_t best_rel = 0xFFFFFFFFu;        // cost modes: the run's minimum of position 1's key plus position 0's
+    for (; d < re; d += 4) {
+        // four digits at a time, two 16-byte scalar loads
+        const YWords lat4 = *(const YWords JSV_CONST*)(U.ylat + d);
+        const YWords key4 = *(const YWords JSV_CONST*)(U.yk32 + d);
+        const uint32_t n = re - d;
+        uint32_t thr[4], m[4];
+        uint64_t go[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            // With tail = lat + nxt[1] (the digit's latency to the sinks) and room1 = sloq -sat nxt[1]:
+            // sloq -sat max(nxt[0], tail) = min(thr0, room1 -sat lat), and
+            // max(smax, tail) <= sloq  <=>  smax <= sloq and lat <= room1 (latencies are >= 1).
+            const uint32_t lat = lat4[g];
+            bool meets = smax <= U.sloq;
+            thr[g] = thr0; go[g] = alive0; m[g] = 0xFFFFFFFFu;
+            if (e01 != 0) thr[g] = umin(thr0, __builtin_elementwise_sub_sat(room1, lat));
+            if (src1 != 0) { meets = meets & (lat <= room1); go[g] = __builtin_amdgcn_ballot_w64(meets); }
+            if constexpr (BOUNDS) {
+                // also out: lanes whose fixed positions plus the cheapest entry of position 0 cost more than the bound
+                const uint32_t fixed = cost_out + ((k32 + key4[g]) >> U.lb);
+                go[g] = __builtin_amdgcn_ballot_w64(meets & (thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
+            }
+            // (without bounds a slot past the run keeps whatever lanes: only the first n slots are
+            // passed on below, and in the usual case all four share one set of live lanes)
+            if constexpr (BOUNDS) {
+                if ((uint32_t)g >= n) go[g] = 0;
+                if (go[g] != 0) tb.visits += x_hi * 4u;
+            }
+        }
+        if constexpr (BOUNDS) { if ((go[0] | go[1] | go[2] | go[3]) == 0) continue; }
+        if (n >= 4) loop_x32_masked<4, BOUNDS>(U, thr, go, mk, qe, endb, full, m);
+        else {
+            // three digits: two and one (a slot without lanes would still cost its vector instructions)
+            if (n >= 2) loop_x32_masked<2, BOUNDS>(U, thr, go, mk, qe, endb, full, m);
+            if (n != 2) {
+                const int g = n == 3 ? 2 : 0;
+                uint32_t thr1[4] = {g == 2 ? thr[2] : thr[0], 0, 0, 0}, m1[4] = {0xFFFFFFFFu, 0, 0, 0};
+                uint64_t go1[4] = {g == 2 ? go[2] : go[0], 0, 0, 0};
+                loop_x32_masked<1, BOUNDS>(U, thr1, go1, mk, qe, endb, full, m1);
+                if (g == 2) m[2] = m1[0]; else m[0] = m1[0];
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint32_t rel = __builtin_elementwise_add_sat(m[g], key4[g]);    // stays 0xFFFFFFFF if none
+            if constexpr (MODE == MODE_OBJ) {
+                // first of the two passes of objective mode (see loop_x); the second, rare, takes the
+                // general path with the lane state of this digit
+                const uint32_t cand = __builtin_elementwise_add_sat(rel, k32);
+                if ((uint32_t)g < n && __builtin_amdgcn_ballot_w64(cand <= tb.klim) != 0) {
+                    const LaneState s1 = make_s1(d + g);
+                    TileBest again = tb;
+                    again.visits = 0;
+                    loop_x32_obj<BOUNDS>(s1, U, 0, x_hi, full, again);
+                    tb.k32 = again.k32; tb.obj = again.obj; tb.klim = again.klim;
+                }
+            } else {
+                best_rel = best_rel < rel ? best_rel : rel;        // (a slot without lanes kept m = 0xFFFFFFFF)
+            }
+        }
+    }
+    if constexpr (MODE != MODE_OBJ) {
+        const uint32_t cand = __builtin_elementwise_add_sat(best_rel, k32);
+        tb.k32 = tb.k32 < cand ? tb.k32 : cand;
+    }
+}
+
+// Two in-lane positions: runs of position 1, each with its masks, then its digits.
 template <int MODE, bool BOUNDS, bool E01>
 __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
                                               uint32_t x_hi, uint64_t full, TileBest& tb)
 {
 #pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
     const Entry JSV_CONST* ty = U.tab[1];
-    // Position 1 is either a successor of position 0 (its only possible predecessor; E01) or a
-    // source: in the first case its tail changes position 0's latency threshold, in the second
-    // the lanes that still meet the latency SLO.
-    constexpr uint32_t e01 = E01 ? 1u : 0u;
-    constexpr uint32_t src1 = E01 ? 0u : 1u;
     const uint32_t nvx = __builtin_amdgcn_readfirstlane(U.nvx);
     uint32_t qe[MAX_XVAR];
 #pragma unroll
@@ -1710,77 +1804,78 @@ __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms
         const uint32_t run_end = U.yrun[d];
         const uint32_t re = run_end < hi ? run_end : hi;
         const double H = ty[d].acc * s.hin[1];
-        const double sacc = src1 != 0 ? s.sacc + H : s.sacc;
+        const double sacc = E01 ? s.sacc : s.sacc + H;
         const double hin0 = __builtin_fma(U.w01, H, s.hin[0]);
         uint64_t mk[MAX_XVAR];
         variant_masks(U, nvx, hin0, sacc, mk);
-        uint32_t best_rel = 0xFFFFFFFFu;        // cost modes: the run's minimum of position 1's key plus position 0's
-        for (; d < re; d += 4) {
-            // four digits at a time, two 16-byte scalar loads
-            const YWords lat4 = *(const YWords JSV_CONST*)(U.ylat + d);
-            const YWords key4 = *(const YWords JSV_CONST*)(U.yk32 + d);
-            const uint32_t n = re - d;
-            uint32_t thr[4], m[4];
-            uint64_t go[4];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                // With tail = lat + nxt[1] (the digit's latency to the sinks) and room1 = sloq -sat nxt[1]:
-                // sloq -sat max(nxt[0], tail) = min(thr0, room1 -sat lat), and
-                // max(smax, tail) <= sloq  <=>  smax <= sloq and lat <= room1 (latencies are >= 1).
-                const uint32_t lat = lat4[g];
-                bool meets = s.smax <= U.sloq;
-                thr[g] = thr0; go[g] = alive0; m[g] = 0xFFFFFFFFu;
-                if (e01 != 0) thr[g] = umin(thr0, __builtin_elementwise_sub_sat(room1, lat));
-                if (src1 != 0) { meets = meets & (lat <= room1); go[g] = __builtin_amdgcn_ballot_w64(meets); }
-                if constexpr (BOUNDS) {
-                    // also out: lanes whose fixed positions plus the cheapest entry of position 0 cost more than the bound
-                    const uint32_t fixed = s.cost_out + ((s.k32 + key4[g]) >> U.lb);
-                    go[g] = __builtin_amdgcn_ballot_w64(meets & (thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
-                }
-                // (without bounds a slot past the run keeps whatever lanes: only the first n slots are
-                // passed on below, and in the usual case all four share one set of live lanes)
-                if constexpr (BOUNDS) {
-                    if ((uint32_t)g >= n) go[g] = 0;
-                    if (go[g] != 0) tb.visits += x_hi * 4u;
-                }
-            }
-            if constexpr (BOUNDS) { if ((go[0] | go[1] | go[2] | go[3]) == 0) continue; }
-            if (n >= 4) loop_x32_masked<4, BOUNDS>(U, thr, go, mk, qe, endb, full, m);
-            else {
-                // three digits: two and one (a slot without lanes would still cost its vector instructions)
-                if (n >= 2) loop_x32_masked<2, BOUNDS>(U, thr, go, mk, qe, endb, full, m);
-                if (n != 2) {
-                    const int g = n == 3 ? 2 : 0;
-                    uint32_t thr1[4] = {g == 2 ? thr[2] : thr[0], 0, 0, 0}, m1[4] = {0xFFFFFFFFu, 0, 0, 0};
-                    uint64_t go1[4] = {g == 2 ? go[2] : go[0], 0, 0, 0};
-                    loop_x32_masked<1, BOUNDS>(U, thr1, go1, mk, qe, endb, full, m1);
-                    if (g == 2) m[2] = m1[0]; else m[0] = m1[0];
-                }
-            }
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const uint32_t rel = __builtin_elementwise_add_sat(m[g], key4[g]);    // stays 0xFFFFFFFF if none
-                if constexpr (MODE == MODE_OBJ) {
-                    // first of the two passes of objective mode (see loop_x); the second, rare, takes the
-                    // general path with the lane state of this digit
-                    const uint32_t cand = __builtin_elementwise_add_sat(rel, s.k32);
-                    if ((uint32_t)g < n && __builtin_amdgcn_ballot_w64(cand <= tb.klim) != 0) {
-                        const LaneState s1 = fix_position<1>(s, U, ty[d + g].lat, ty[d + g].acc, 0, U.k32[1][d + g]);
-                        TileBest again = tb;
-                        again.visits = 0;
-                        loop_x32_obj<BOUNDS>(s1, U, 0, x_hi, full, again);
-                        tb.k32 = again.k32; tb.obj = again.obj; tb.klim = again.klim;
-                    }
-                } else {
-                    best_rel = best_rel < rel ? best_rel : rel;        // (a slot without lanes kept m = 0xFFFFFFFF)
-                }
-            }
-        }
+        y_batches<MODE, BOUNDS, E01>(U, s.smax, thr0, room1, alive0, s.k32, s.cost_out, d, re, mk, qe, endb, x_hi, full, tb,
+            [&](uint32_t yd) { return fix_position<1>(s, U, ty[yd].lat, ty[yd].acc, 0, U.k32[1][yd]); });
         d = re;
-        if constexpr (MODE != MODE_OBJ) {
-            const uint32_t cand = __builtin_elementwise_add_sat(best_rel, s.k32);
-            tb.k32 = tb.k32 < cand ? tb.k32 : cand;
+    }
+}
+
+// Three in-lane positions.  The accuracy outcome depends on the variants only, so the loops
+// run by runs: for a run of position 2 (digits of one variant) and a run of position 1 the
+// masks are made once and serve every pair of their digits; per digit of position 2 only its
+// latency state (what fix_position<2> does to tails and keys) is formed again.  Same
+// operations on the same operands as digit by digit, in another order of the candidates.
+template <int MODE, bool BOUNDS, bool E01>
+__device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
+                                               uint32_t x_hi, uint64_t full, TileBest& tb)
+{
+#pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
+    const Entry JSV_CONST* ty = U.tab[1];
+    const Entry JSV_CONST* tz = U.tab[2];
+    const uint32_t nvx = __builtin_amdgcn_readfirstlane(U.nvx);
+    const uint32_t src2 = __builtin_amdgcn_readfirstlane(U.src[2] ? 1u : 0u);
+    uint32_t qe[MAX_XVAR];
+#pragma unroll
+    for (int v = 0; v < MAX_XVAR; ++v) qe[v] = U.xqe[v];
+    const uint32_t endb = x_hi * (uint32_t)sizeof(QuadC);
+    const uint32_t KY = U.K[1];
+    uint32_t z = lo;
+    while (z < hi) {
+        const uint32_t zrun_end = U.zrun[z];
+        const uint32_t zre = zrun_end < hi ? zrun_end : hi;
+        // accuracy state with position 2 fixed to this variant (fix_position<2>)
+        const double Hz = tz[z].acc * s.hin[2];
+        const double sacc2 = src2 != 0 ? s.sacc + Hz : s.sacc;
+        const double hin1 = __builtin_fma(U.w12, Hz, s.hin[1]);
+        const double hin0z = __builtin_fma(U.w02, Hz, s.hin[0]);
+        uint32_t y = 0;
+        while (y < KY) {
+            const uint32_t yre = U.yrun[y];
+            // ... and position 1 to this one (fix_position<1>), then Eq. 13 per variant of position 0
+            const double H = ty[y].acc * hin1;
+            const double sacc = E01 ? sacc2 : sacc2 + H;
+            const double hin0 = __builtin_fma(U.w01, H, hin0z);
+            uint64_t mk[MAX_XVAR];
+            variant_masks(U, nvx, hin0, sacc, mk);
+            for (uint32_t zd = z; zd < zre; ++zd) {
+                // latency state and key with this digit of position 2 fixed
+                const uint32_t tail = tz[zd].lat + s.nxt[2];
+                const uint32_t smax = src2 != 0 ? umax(s.smax, tail) : s.smax;
+                const uint32_t nxt1 = umax(s.nxt[1], tail & U.m12);
+                const uint32_t nxt0 = umax(s.nxt[0], tail & U.m02);
+                const uint32_t k32 = s.k32 + U.k32[2][zd];
+                if constexpr (BOUNDS) {
+                    // is any lane left that meets the latency SLO so far and stays within the cost
+                    // bound with the cheapest entries of the two positions below?
+                    const uint32_t fixed = s.cost_out + (k32 >> U.lb);
+                    if (__builtin_amdgcn_ballot_w64((smax <= U.sloq) & (fixed + U.min_xy_cost <= U.bound)) == 0) continue;
+                }
+                const uint64_t alive0 = __builtin_amdgcn_ballot_w64(smax <= U.sloq);
+                const uint32_t thr0 = __builtin_elementwise_sub_sat(U.sloq, nxt0);
+                const uint32_t room1 = __builtin_elementwise_sub_sat(U.sloq, nxt1);
+                y_batches<MODE, BOUNDS, E01>(U, smax, thr0, room1, alive0, k32, s.cost_out, y, yre, mk, qe, endb, x_hi, full, tb,
+                    [&](uint32_t yd) {
+                        const LaneState s2 = fix_position<2>(s, U, tz[zd].lat, tz[zd].acc, 0, U.k32[2][zd]);
+                        return fix_position<1>(s2, U, ty[yd].lat, ty[yd].acc, 0, U.k32[1][yd]);
+                    });
+            }
+            y = yre;
         }
+        z = zre;
     }
 }
 
@@ -1809,6 +1904,14 @@ template <bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
                                        uint32_t x_hi, uint64_t full, Best& best, TileBest& tb)
 {
+    if constexpr (W32 && !is_mix(MODE)) {
+        // single tuples with few variants in position 0: by runs of positions 2 and 1 (see loop_y for the tests)
+        if (U.nvx - 1u < (uint32_t)MAX_XVAR && U.src[1] == (U.m01 == 0)) {
+            if (U.m01 != 0) loop_zy_masked<MODE, BOUNDS, true>(s, U, lo, hi, x_hi, full, tb);
+            else loop_zy_masked<MODE, BOUNDS, false>(s, U, lo, hi, x_hi, full, tb);
+            return;
+        }
+    }
     const Entry JSV_CONST* tz = U.tab[2];
     for (uint32_t d = lo; d < hi; ++d) {
         const LaneState s2 = fix_position<2>(s, U, tz[d].lat, tz[d].acc, W32 ? 0 : tz[d].key,
@@ -1912,6 +2015,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     U.ylat = (const uint32_t JSV_CONST*)(quads + yrec_offset(k_max));
     U.yk32 = U.ylat + ydigit_words(k_max);
     U.yrun = U.yk32 + ydigit_words(k_max);
+    U.zrun = U.yrun + ydigit_words(k_max);
     st.cost_out = (uint32_t)(st.key >> in->idx_bits);
     // Cost as a bound: `bound` is S_avail (Eq. 8) or, in the cost modes, the cost of a candidate
     // already found that meets both SLOs, whichever is lower.  A lane whose fixed positions plus
