@@ -11,7 +11,10 @@ SOURCES = ["jsv_kernels.hip", "jsv_host.cpp"]
 HEADERS = ["jsv_device.h", "jsv_launch.h", os.path.join("..", "..", "include", "jsv.h")]
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
+         # the hot loops name scalar registers in inline asm: a build in which the compiler has
+         # reserved one of them for itself (it then warns) must not come out
+         "-Werror=inline-asm"]
 
 
 PROBE_LIB = os.path.join(HERE, "libjsv_probe.so")

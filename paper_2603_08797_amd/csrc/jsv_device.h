@@ -99,6 +99,21 @@ constexpr uint32_t ydigit_words(uint32_t k_max) { return k_max + 3; }
 constexpr uint32_t quad_stride(uint32_t k_max) { return k_max + (k_max + 2) / 2 + (k_max + 6) / 4; }
 constexpr uint32_t quadc_offset(uint32_t k_max) { return k_max; }                          // in Quad units
 constexpr uint32_t yrec_offset(uint32_t k_max) { return k_max + (k_max + 2) / 2; }
+// Pair stream (single tuples, three in-lane positions): for every digit of position 1 a copy of
+// position 0's QuadC records with that digit's local key already added to every key, so that a
+// lane's running minimum can stay in one register across all digits of position 1.  Records of
+// 32 bytes per instance that are set aside for it (an instance whose stream does not fit runs
+// without it), plus one spare record that is read ahead and never used.  Small for many
+// instances: all of them together stay below PAIR_BUDGET_BYTES.
+constexpr uint32_t PAIR_CAP = 8192;
+constexpr uint64_t PAIR_BUDGET_BYTES = 256ull << 20;
+constexpr uint32_t pair_records(uint32_t k_max, uint32_t n_inst)
+{
+    const uint64_t want = (uint64_t)k_max * ((k_max + 3) / 4 + 8);      // every variant pads to whole quads
+    const uint64_t share = PAIR_BUDGET_BYTES / 32u / (n_inst ? n_inst : 1u);
+    const uint64_t r = want < share ? want : share;
+    return r < PAIR_CAP ? (uint32_t)r : PAIR_CAP;
+}
 
 
 // Task graph of one problem, by position.
@@ -190,7 +205,7 @@ struct Instance {
     // the variants of the innermost position in the order of its stream (single tuples): how
     // many, and the accuracy of the first MAX_XVAR of them (plan kernel)
     uint32_t nvx;
-    uint32_t pad_nvx;
+    uint32_t pair_nq;         // records per digit of position 1 in the pair stream; 0: no pair stream
     double   xacc[MAX_XVAR];
     uint32_t xqe[MAX_XVAR];   // byte offset in the QuadC copy at which each of them ends (past nvx: the stream's end)
 };
@@ -237,6 +252,8 @@ struct Plan {
     uint32_t*    cost = nullptr;        // [n_inst][t_max][c_max]
     uint32_t*    k32 = nullptr;         // [n_inst][t_max][k_max]   32-bit local keys (in-lane tasks)
     Quad*        quads = nullptr;       // [n_inst][quad_stride(k_max)]  stream of the innermost position
+    QuadC*       pairs = nullptr;       // [n_inst][pair_cap + 1]   pair stream of positions 1 and 0
+    uint32_t     pair_cap = 0;          // records of it per instance (0: none)
     uint64_t*    partial = nullptr;     // [n_inst][grid]           per-block minima (keys)
     double*      partial_obj = nullptr; // [n_inst][grid]           per-block best objectives (objective mode)
     ResultRec*   results = nullptr;     // [n_inst]

@@ -55,7 +55,7 @@ struct Search {               // per-instance search parameters (batch mode keep
 };
 
 struct Layout {               // offsets into the workspace
-    size_t inst, entries, rep, cost, k32, quads, partial, partial_obj, results, summary, eval, total;
+    size_t inst, entries, rep, cost, k32, quads, pairs, partial, partial_obj, results, summary, eval, total;
     size_t cell_acc, cell_id, cell_pm, cell_list;     // mixture mode only
     size_t bound, tile_begin;
 };
@@ -459,6 +459,7 @@ Layout make_layout(uint32_t n_inst, uint32_t t_max, uint32_t k_max, uint32_t c_m
     L.cost = off;    off = align_up(off + sizeof(uint32_t) * (size_t)n_inst * t_max * c_max);
     L.k32 = off;     off = align_up(off + sizeof(uint32_t) * (size_t)n_inst * t_max * k_max);
     L.quads = off;   off = align_up(off + sizeof(jsv::Quad) * (size_t)n_inst * jsv::quad_stride(k_max));
+    L.pairs = off;   off = align_up(off + sizeof(jsv::QuadC) * (size_t)n_inst * (jsv::pair_records(k_max, n_inst) + 1));
     L.partial = off; off = align_up(off + sizeof(uint64_t) * (size_t)n_inst * grid);
     L.partial_obj = off; off = align_up(off + sizeof(double) * (size_t)n_inst * grid);
     L.results = off; off = align_up(off + sizeof(jsv::ResultRec) * n_inst);
@@ -509,6 +510,8 @@ jsv::Plan make_plan(const jsv_ctx* ctx, const void* graphs, const Layout& L, uns
     pl.cost = (uint32_t*)(ws + L.cost);
     pl.k32 = (uint32_t*)(ws + L.k32);
     pl.quads = (jsv::Quad*)(ws + L.quads);
+    pl.pairs = (jsv::QuadC*)(ws + L.pairs);
+    pl.pair_cap = jsv::pair_records(k_max, n_inst);
     pl.partial = (uint64_t*)(ws + L.partial);
     pl.partial_obj = (double*)(ws + L.partial_obj);
     pl.results = (jsv::ResultRec*)(ws + L.results);

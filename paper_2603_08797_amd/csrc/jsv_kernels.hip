@@ -758,7 +758,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     const Graph* g = pl.graphs + in->problem;
     const uint32_t T = g->T;
     __shared__ uint32_t s_maxcost[MAXT], s_mincost[MAXT], s_K[MAXT], s_off[MAXT + 1], s_lsT[MAXT], s_minxlat;
-    __shared__ uint32_t s_bits, s_lb, s_nin, s_ls[3], s_chunk, s_nq, s_last;
+    __shared__ uint32_t s_bits, s_lb, s_nin, s_ls[3], s_chunk, s_nq, s_last, s_nvx;
     __shared__ uint64_t s_stride[MAXT];
     // the innermost position's entries, staged once: variant, latency, cost, and the first
     // quad of the variant that starts at digit d
@@ -908,6 +908,8 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         in->splittable = stream ? 0u : 1u;
         in->use32 = use32; in->lb = lb; in->nq = nq;
         in->nvx = 0;                      // set with the stream of single tuples, if there is one
+        in->pair_nq = 0;                  // set with the pair stream, if there is one
+        s_nvx = 0;
         uint64_t min_in = 0;
         for (uint32_t p = 0; p < n_in; ++p) min_in += s_mincost[s_task_at[p]];
         in->min_in_cost = (space != 0 && pl.bounds) ? (uint32_t)(min_in > 0xFFFFFFFFull ? 0xFFFFFFFFull : min_in) : 0u;
@@ -994,6 +996,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
                 if (ordinal < (uint32_t)MAX_XVAR) { in->xacc[ordinal] = acc; in->xqe[ordinal] = (q0 + quads) * (uint32_t)sizeof(QuadC); }
                 if (d1 == KX) {
                     in->nvx = ordinal + 1;
+                    s_nvx = ordinal + 1;
                     for (uint32_t v = ordinal + 1; v < (uint32_t)MAX_XVAR; ++v) in->xqe[v] = (q0 + quads) * (uint32_t)sizeof(QuadC);
                 }
             }
@@ -1022,6 +1025,32 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
                 while (e < KZ && s_zvar[e] == var) ++e;
                 zrun[d] = e;
             }
+        }
+    }
+    // pair stream (three in-lane positions, single tuples, few variants in position 0): per digit
+    // of position 1 the records of position 0's stream with that digit's local key added to
+    // every key.  Built from what this block has just written (read back past the L1).
+    if (s_nin >= 3 && !pl.mix) {
+        __syncthreads();
+        const uint32_t nq = s_nq, KY = s_K[s_task_at[1]];
+        const bool fits = pl.pair_cap != 0 && s_nvx >= 1 && s_nvx <= (uint32_t)MAX_XVAR && (uint64_t)nq * KY <= pl.pair_cap;
+        if (fits) {
+            const uint32_t* xw = (const uint32_t*)(pl.quads + (size_t)i * quad_stride(pl.k_max) + quadc_offset(pl.k_max));
+            const uint32_t* yk = (const uint32_t*)(pl.quads + (size_t)i * quad_stride(pl.k_max) + yrec_offset(pl.k_max)) +
+                                 ydigit_words(pl.k_max);
+            XEnt* pr = (XEnt*)(pl.pairs + (size_t)i * (pl.pair_cap + 1));
+            const uint32_t per = nq * 4;
+            for (uint32_t f = tid; f < KY * per; f += blockDim.x) {
+                const uint32_t dy = f / per, e = f % per;
+                XEnt me;
+                me.lat = __hip_atomic_load(xw + 2 * e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const uint32_t kx = __hip_atomic_load(xw + 2 * e + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const uint32_t ky = __hip_atomic_load(yk + dy, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                me.k32 = kx == 0xFFFFFFFFu ? kx : kx + ky;          // padding stays padding
+                pr[f] = me;
+            }
+            if (tid < 4) { XEnt pad; pad.lat = 0xFFFFFFFFu; pad.k32 = 0xFFFFFFFFu; pr[KY * per + tid] = pad; }
+            if (tid == 0) in->pair_nq = nq;
         }
     }
     for (uint32_t b = tid; b < pl.grid; b += blockDim.x) {
@@ -1078,6 +1107,8 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     const uint32_t JSV_CONST* yk32;    // local keys,
     const uint32_t JSV_CONST* yrun;    // ends of their runs of equal accuracy
     const uint32_t JSV_CONST* zrun;    // position 2's digits: ends of their runs of one variant
+    const QuadC JSV_CONST* pairs;      // pair stream: per digit of position 1, position 0's records with that digit's key added
+    uint32_t pair_nq;                  // records per digit in it; 0: none
 };
 
 // Fix position P (a wave-uniform entry) and push its contribution down.  hin[P]
@@ -1553,11 +1584,13 @@ __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, ui
 #define JSV_SLOTS_B1(MASK, SKIP) JSV_SLOT("s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", MASK, "%[a0]", "%[t0]", "%[r0]", SKIP)
 #define JSV_SLOTS_A2(MASK, SKIP) JSV_SLOTS_A1(MASK, SKIP) JSV_SLOT("s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", MASK, "%[a1]", "%[t1]", "%[r1]", SKIP)
 #define JSV_SLOTS_B2(MASK, SKIP) JSV_SLOTS_B1(MASK, SKIP) JSV_SLOT("s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", MASK, "%[a1]", "%[t1]", "%[r1]", SKIP)
-#define JSV_SLOTS_A4(MASK, SKIP) JSV_SLOTS_A2(MASK, SKIP)                                          \
-        JSV_SLOT("s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", MASK, "%[a2]", "%[t2]", "%[r2]", SKIP) \
+#define JSV_SLOTS_A3(MASK, SKIP) JSV_SLOTS_A2(MASK, SKIP)                                          \
+        JSV_SLOT("s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", MASK, "%[a2]", "%[t2]", "%[r2]", SKIP)
+#define JSV_SLOTS_B3(MASK, SKIP) JSV_SLOTS_B2(MASK, SKIP)                                          \
+        JSV_SLOT("s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", MASK, "%[a2]", "%[t2]", "%[r2]", SKIP)
+#define JSV_SLOTS_A4(MASK, SKIP) JSV_SLOTS_A3(MASK, SKIP)                                          \
         JSV_SLOT("s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", MASK, "%[a3]", "%[t3]", "%[r3]", SKIP)
-#define JSV_SLOTS_B4(MASK, SKIP) JSV_SLOTS_B2(MASK, SKIP)                                          \
-        JSV_SLOT("s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", MASK, "%[a2]", "%[t2]", "%[r2]", SKIP) \
+#define JSV_SLOTS_B4(MASK, SKIP) JSV_SLOTS_B3(MASK, SKIP)                                          \
         JSV_SLOT("s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", MASK, "%[a3]", "%[t3]", "%[r3]", SKIP)
 #define JSV_XV_HALF(START, LOOP, SLOTS, NEXTREGS, STAY, LEAVE, QE)                                 \
         START ":\n\t"                                                                              \
@@ -1588,7 +1621,7 @@ __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, ui
         "s_mov_b64 exec, %[full]\n\t"                                                              \
         "s_nop 1"
 #define JSV_XV_COMMON_IN                                                                           \
-          [base] "s"(U.xq), [endb] "s"(endb), [full] "s"(full),                                    \
+          [base] "s"(base), [endb] "s"(endb), [full] "s"(full),                                    \
           [m0] "s"(mk[0]), [m1] "s"(mk[1]), [m2] "s"(mk[2]), [m3] "s"(mk[3]),                      \
           [m4] "s"(mk[4]), [m5] "s"(mk[5]), [m6] "s"(mk[6]), [m7] "s"(mk[7]),                      \
           [q0] "s"(qe[0]), [q1] "s"(qe[1]), [q2] "s"(qe[2]), [q3] "s"(qe[3]),                      \
@@ -1597,14 +1630,15 @@ __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, ui
           "vcc", "scc", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", \
           "s83", "s84", "s85", "s86", "s87", "s88"
 
-// G = 4, 2 or 1 slots: thresholds thr[g], live lanes go[g], running minima m[g] (in and out).
+// G = 4, 3, 2 or 1 slots: thresholds thr[g], live lanes go[g], running minima m[g] (in and out).
+// base: the stream's records (position 0's QuadC copy, or one digit's block of the pair stream).
 template <int G, bool BOUNDS>
-__device__ __forceinline__ void loop_x32_masked(const Uniforms& U, const uint32_t (&thr)[4], const uint64_t (&go)[4],
+__device__ __forceinline__ void loop_x32_masked(const QuadC JSV_CONST* base, const uint32_t (&thr)[4], const uint64_t (&go)[4],
                                                 const uint64_t (&mk)[MAX_XVAR], const uint32_t (&qe)[MAX_XVAR],
                                                 uint32_t endb, uint64_t full, uint32_t (&m)[4])
 {
     static_assert(MAX_XVAR == 8, "the blocks above are written out for eight variants");
-    static_assert(G == 1 || G == 2 || G == 4, "slots");
+    static_assert(G >= 1 && G <= 4, "slots");
 #if defined(__HIP_DEVICE_COMPILE__)
     if constexpr (G == 4) {
         if constexpr (BOUNDS)
@@ -1618,6 +1652,19 @@ __device__ __forceinline__ void loop_x32_masked(const Uniforms& U, const uint32_
                 : [r0] "+v"(m[0]), [r1] "+v"(m[1]), [r2] "+v"(m[2]), [r3] "+v"(m[3])
                 : JSV_XV_COMMON_IN, [t0] "v"(thr[0]), [t1] "v"(thr[1]), [t2] "v"(thr[2]), [t3] "v"(thr[3]),
                   [a0] "s"(go[0]), [a1] "s"(go[1]), [a2] "s"(go[2]), [a3] "s"(go[3])
+                : JSV_XV_CLOBBER);
+    } else if constexpr (G == 3) {
+        if constexpr (BOUNDS)
+            asm volatile(JSV_XV_ALL(3, "s_cbranch_execz 5f\n\t")
+                : [r0] "+v"(m[0]), [r1] "+v"(m[1]), [r2] "+v"(m[2])
+                : JSV_XV_COMMON_IN, [t0] "v"(thr[0]), [t1] "v"(thr[1]), [t2] "v"(thr[2]),
+                  [a0] "s"(go[0]), [a1] "s"(go[1]), [a2] "s"(go[2])
+                : JSV_XV_CLOBBER);
+        else
+            asm volatile(JSV_XV_ALL(3, "")
+                : [r0] "+v"(m[0]), [r1] "+v"(m[1]), [r2] "+v"(m[2])
+                : JSV_XV_COMMON_IN, [t0] "v"(thr[0]), [t1] "v"(thr[1]), [t2] "v"(thr[2]),
+                  [a0] "s"(go[0]), [a1] "s"(go[1]), [a2] "s"(go[2])
                 : JSV_XV_CLOBBER);
     } else if constexpr (G == 2) {
         if constexpr (BOUNDS)
@@ -1639,7 +1686,7 @@ __device__ __forceinline__ void loop_x32_masked(const Uniforms& U, const uint32_
                 : [r0] "+v"(m[0]) : JSV_XV_COMMON_IN, [t0] "v"(thr[0]), [a0] "s"(go[0]) : JSV_XV_CLOBBER);
     }
 #else
-    (void)U; (void)thr; (void)go; (void)mk; (void)qe; (void)endb; (void)full; (void)m;
+    (void)base; (void)thr; (void)go; (void)mk; (void)qe; (void)endb; (void)full; (void)m;
 #endif
 }
 #undef JSV_XV_CLOBBER
@@ -1649,6 +1696,8 @@ __device__ __forceinline__ void loop_x32_masked(const Uniforms& U, const uint32_
 #undef JSV_XV_HALF
 #undef JSV_SLOTS_B4
 #undef JSV_SLOTS_A4
+#undef JSV_SLOTS_B3
+#undef JSV_SLOTS_A3
 #undef JSV_SLOTS_B2
 #undef JSV_SLOTS_A2
 #undef JSV_SLOTS_B1
@@ -1745,15 +1794,15 @@ __device__ __forceinline__ void y_batches(const Uniforms& U, uint32_t smax, uint
             }
         }
         if constexpr (BOUNDS) { if ((go[0] | go[1] | go[2] | go[3]) == 0) continue; }
-        if (n >= 4) loop_x32_masked<4, BOUNDS>(U, thr, go, mk, qe, endb, full, m);
+        if (n >= 4) loop_x32_masked<4, BOUNDS>(U.xq, thr, go, mk, qe, endb, full, m);
         else {
             // three digits: two and one (a slot without lanes would still cost its vector instructions)
-            if (n >= 2) loop_x32_masked<2, BOUNDS>(U, thr, go, mk, qe, endb, full, m);
+            if (n >= 2) loop_x32_masked<2, BOUNDS>(U.xq, thr, go, mk, qe, endb, full, m);
             if (n != 2) {
                 const int g = n == 3 ? 2 : 0;
                 uint32_t thr1[4] = {g == 2 ? thr[2] : thr[0], 0, 0, 0}, m1[4] = {0xFFFFFFFFu, 0, 0, 0};
                 uint64_t go1[4] = {g == 2 ? go[2] : go[0], 0, 0, 0};
-                loop_x32_masked<1, BOUNDS>(U, thr1, go1, mk, qe, endb, full, m1);
+                loop_x32_masked<1, BOUNDS>(U.xq, thr1, go1, mk, qe, endb, full, m1);
                 if (g == 2) m[2] = m1[0]; else m[0] = m1[0];
             }
         }
@@ -1879,6 +1928,110 @@ __device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniform
     }
 }
 
+// Three in-lane positions with the pair stream (cost modes, single tuples).  The slots that go
+// through a record together are up to four digits of position 2 (one run: one variant, so one
+// set of masks per run of position 1 serves them all), and the records are those of the pair
+// stream: for the digit of position 1 at hand, position 0's candidates with that digit's key
+// already in theirs.  A slot's running minimum therefore covers positions 1 and 0 together and
+// stays in its register across all digits of position 1; per (digit of position 2, digit of
+// position 1) only the latency threshold is formed (two vector instructions), per candidate
+// the same two as everywhere.  Same tests on the same operands as digit by digit.
+template <bool BOUNDS, bool E01>
+__device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
+                                               uint32_t x_hi, uint64_t full, TileBest& tb)
+{
+#pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
+    const Entry JSV_CONST* ty = U.tab[1];
+    const Entry JSV_CONST* tz = U.tab[2];
+    const uint32_t nvx = __builtin_amdgcn_readfirstlane(U.nvx);
+    const uint32_t src2 = __builtin_amdgcn_readfirstlane(U.src[2] ? 1u : 0u);
+    uint32_t qe[MAX_XVAR];
+#pragma unroll
+    for (int v = 0; v < MAX_XVAR; ++v) qe[v] = U.xqe[v];
+    const uint32_t endb = x_hi * (uint32_t)sizeof(QuadC);
+    const uint32_t KY = U.K[1];
+    uint32_t z = lo;
+    while (z < hi) {
+        const uint32_t zrun_end = U.zrun[z];
+        const uint32_t zre = zrun_end < hi ? zrun_end : hi;
+        // accuracy state with position 2 fixed to this variant (fix_position<2>)
+        const double Hz = tz[z].acc * s.hin[2];
+        const double sacc2 = src2 != 0 ? s.sacc + Hz : s.sacc;
+        const double hin1 = __builtin_fma(U.w12, Hz, s.hin[1]);
+        const double hin0z = __builtin_fma(U.w02, Hz, s.hin[0]);
+        for (uint32_t zb = z; zb < zre; zb += 4) {
+            const uint32_t n = zre - zb < 4u ? zre - zb : 4u;
+            // latency state and key of each slot's digit of position 2 (a slot past the run repeats the last digit and is never passed on)
+            uint32_t thr0[4], room1[4], k32z[4], m[4];
+            uint64_t alive[4];
+            uint64_t any = 0;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const uint32_t zd = zb + ((uint32_t)g < n ? (uint32_t)g : n - 1u);
+                const uint32_t tail = tz[zd].lat + s.nxt[2];
+                const uint32_t smax = src2 != 0 ? umax(s.smax, tail) : s.smax;
+                const uint32_t nxt1 = umax(s.nxt[1], tail & U.m12);
+                const uint32_t nxt0 = umax(s.nxt[0], tail & U.m02);
+                k32z[g] = s.k32 + U.k32[2][zd];
+                thr0[g] = __builtin_elementwise_sub_sat(U.sloq, nxt0);
+                room1[g] = __builtin_elementwise_sub_sat(U.sloq, nxt1);
+                m[g] = 0xFFFFFFFFu;
+                bool meets = smax <= U.sloq;
+                if constexpr (BOUNDS) {
+                    // ... and stays within the cost bound with the cheapest entries of the two positions below
+                    const uint32_t fixed = s.cost_out + (k32z[g] >> U.lb);
+                    meets = meets & (fixed + U.min_xy_cost <= U.bound);
+                }
+                alive[g] = (uint32_t)g < n ? __builtin_amdgcn_ballot_w64(meets) : 0ull;
+                any |= alive[g];
+            }
+            if constexpr (BOUNDS) { if (any == 0) continue; }
+            uint32_t y = 0;
+            while (y < KY) {
+                const uint32_t yre = U.yrun[y];
+                // position 1 fixed to this run's accuracy (fix_position<1>), then Eq. 13 per variant of position 0
+                const double H = ty[y].acc * hin1;
+                const double sacc = E01 ? sacc2 : sacc2 + H;
+                const double hin0 = __builtin_fma(U.w01, H, hin0z);
+                uint64_t mk[MAX_XVAR];
+                variant_masks(U, nvx, hin0, sacc, mk);
+                for (uint32_t dy = y; dy < yre; ++dy) {
+                    const uint32_t lat = U.ylat[dy];
+                    uint32_t thr[4];
+                    uint64_t go[4];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        // as in y_batches: position 1 either feeds position 0's threshold or is a source
+                        thr[g] = thr0[g]; go[g] = alive[g];
+                        if constexpr (E01) thr[g] = umin(thr0[g], __builtin_elementwise_sub_sat(room1[g], lat));
+                        else go[g] = alive[g] & __builtin_amdgcn_ballot_w64(lat <= room1[g]);
+                        if constexpr (BOUNDS) {
+                            const uint32_t fixed = s.cost_out + ((k32z[g] + U.yk32[dy]) >> U.lb);
+                            go[g] &= __builtin_amdgcn_ballot_w64((thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
+                            if (go[g] != 0) tb.visits += x_hi * 4u;
+                        }
+                    }
+                    if constexpr (BOUNDS) { if ((go[0] | go[1] | go[2] | go[3]) == 0) continue; }
+                    const QuadC JSV_CONST* base = U.pairs + (size_t)dy * U.pair_nq;
+                    switch (n) {
+                    case 4: loop_x32_masked<4, BOUNDS>(base, thr, go, mk, qe, endb, full, m); break;
+                    case 3: loop_x32_masked<3, BOUNDS>(base, thr, go, mk, qe, endb, full, m); break;
+                    case 2: loop_x32_masked<2, BOUNDS>(base, thr, go, mk, qe, endb, full, m); break;
+                    default: loop_x32_masked<1, BOUNDS>(base, thr, go, mk, qe, endb, full, m); break;
+                    }
+                }
+                y = yre;
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const uint32_t cand = __builtin_elementwise_add_sat(m[g], k32z[g]);    // stays 0xFFFFFFFF if none (unused slots kept it)
+                tb.k32 = tb.k32 < cand ? tb.k32 : cand;
+            }
+        }
+        z = zre;
+    }
+}
+
 template <bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void loop_y(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
                                        uint32_t x_hi, uint64_t full, Best& best, TileBest& tb)
@@ -1907,6 +2060,14 @@ __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, ui
     if constexpr (W32 && !is_mix(MODE)) {
         // single tuples with few variants in position 0: by runs of positions 2 and 1 (see loop_y for the tests)
         if (U.nvx - 1u < (uint32_t)MAX_XVAR && U.src[1] == (U.m01 == 0)) {
+            if constexpr (MODE == MODE_COST) {
+                // (worth it from four digits of position 2 per tile: they are the slots that share a record)
+                if (U.pair_nq != 0 && hi - lo >= 4u) {
+                    if (U.m01 != 0) loop_zyx_pairs<BOUNDS, true>(s, U, lo, hi, x_hi, full, tb);
+                    else loop_zyx_pairs<BOUNDS, false>(s, U, lo, hi, x_hi, full, tb);
+                    return;
+                }
+            }
             if (U.m01 != 0) loop_zy_masked<MODE, BOUNDS, true>(s, U, lo, hi, x_hi, full, tb);
             else loop_zy_masked<MODE, BOUNDS, false>(s, U, lo, hi, x_hi, full, tb);
             return;
@@ -1932,7 +2093,7 @@ __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, ui
 template <int NIN, bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instance JSV_CONST* in,
                                          const Entry JSV_CONST* tab, const uint32_t JSV_CONST* k32,
-                                         const Quad JSV_CONST* quads, const Entry* s_tab, uint32_t k_max, bool mix,
+                                         const Quad JSV_CONST* quads, const QuadC JSV_CONST* pairs, const Entry* s_tab, uint32_t k_max, bool mix,
                                          uint64_t group, uint32_t chunk_id, uint32_t bound, Best& best, uint64_t& visited)
 {
 #pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
@@ -2016,6 +2177,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     U.yk32 = U.ylat + ydigit_words(k_max);
     U.yrun = U.yk32 + ydigit_words(k_max);
     U.zrun = U.yrun + ydigit_words(k_max);
+    U.pairs = pairs; U.pair_nq = in->pair_nq;
     st.cost_out = (uint32_t)(st.key >> in->idx_bits);
     // Cost as a bound: `bound` is S_avail (Eq. 8) or, in the cost modes, the cost of a candidate
     // already found that meets both SLOs, whichever is lower.  A lane whose fixed positions plus
@@ -2173,6 +2335,7 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const Entry JSV_CONST* tab = as_uniform((const Entry*)pl.entries) + (size_t)cur * tk;
         const uint32_t JSV_CONST* k32 = as_uniform((const uint32_t*)pl.k32) + (size_t)cur * tk;
         const Quad JSV_CONST* quads = as_uniform((const Quad*)pl.quads) + (size_t)cur * quad_stride(pl.k_max);
+        const QuadC JSV_CONST* pairs = as_uniform((const QuadC*)pl.pairs) + (size_t)cur * (pl.pair_cap + 1);
         const uint64_t local = tile - in->tile_begin;
         const uint32_t n_chunks = in->n_chunks;
         const uint32_t chunk_id = (uint32_t)(local % n_chunks);
@@ -2187,15 +2350,15 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const double obj_before = best.obj;
         if (in->use32) {
             switch (in->n_in) {
-            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
-            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
-            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
             }
         } else {
             switch (in->n_in) {
-            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
-            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
-            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
             }
         }
         if constexpr (SHARE) {
