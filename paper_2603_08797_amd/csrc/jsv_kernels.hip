@@ -1936,12 +1936,88 @@ __device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniform
 // stays in its register across all digits of position 1; per (digit of position 2, digit of
 // position 1) only the latency threshold is formed (two vector instructions), per candidate
 // the same two as everywhere.  Same tests on the same operands as digit by digit.
+//
+// One batch of G digits of position 2, starting at zb, against all digits of position 1 (the
+// slot count is a template parameter so that the minima keep their registers over the loops).
+// sacc2, hin1, hin0z: the accuracy state with position 2 fixed to the run's variant.
+template <int G, bool BOUNDS, bool E01>
+__device__ __forceinline__ void z_batch_pairs(const LaneState& s, const Uniforms& U, uint32_t zb, uint32_t nvx, uint32_t src2,
+                                              double sacc2, double hin1, double hin0z, const uint32_t (&qe)[MAX_XVAR],
+                                              uint32_t endb, uint32_t x_hi, uint64_t full, TileBest& tb)
+{
+#pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
+    const Entry JSV_CONST* ty = U.tab[1];
+    const Entry JSV_CONST* tz = U.tab[2];
+    const uint32_t KY = U.K[1];
+    // latency state and key of each slot's digit of position 2
+    uint32_t thr0[4], room1[4], k32z[4], m[4];
+    uint64_t alive[4];
+    uint64_t any = 0;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const uint32_t zd = zb + (uint32_t)g;
+        const uint32_t tail = tz[zd].lat + s.nxt[2];
+        const uint32_t smax = src2 != 0 ? umax(s.smax, tail) : s.smax;
+        const uint32_t nxt1 = umax(s.nxt[1], tail & U.m12);
+        const uint32_t nxt0 = umax(s.nxt[0], tail & U.m02);
+        k32z[g] = s.k32 + U.k32[2][zd];
+        thr0[g] = __builtin_elementwise_sub_sat(U.sloq, nxt0);
+        room1[g] = __builtin_elementwise_sub_sat(U.sloq, nxt1);
+        m[g] = 0xFFFFFFFFu;
+        bool meets = smax <= U.sloq;
+        if constexpr (BOUNDS) {
+            // ... and stays within the cost bound with the cheapest entries of the two positions below
+            const uint32_t fixed = s.cost_out + (k32z[g] >> U.lb);
+            meets = meets & (fixed + U.min_xy_cost <= U.bound);
+        }
+        alive[g] = __builtin_amdgcn_ballot_w64(meets);
+        any |= alive[g];
+    }
+#pragma unroll
+    for (int g = G; g < 4; ++g) { thr0[g] = 0; room1[g] = 0; k32z[g] = 0; m[g] = 0xFFFFFFFFu; alive[g] = 0; }
+    if constexpr (BOUNDS) { if (any == 0) return; }
+    uint32_t y = 0;
+    while (y < KY) {
+        const uint32_t yre = U.yrun[y];
+        // position 1 fixed to this run's accuracy (fix_position<1>), then Eq. 13 per variant of position 0
+        const double H = ty[y].acc * hin1;
+        const double sacc = E01 ? sacc2 : sacc2 + H;
+        const double hin0 = __builtin_fma(U.w01, H, hin0z);
+        uint64_t mk[MAX_XVAR];
+        variant_masks(U, nvx, hin0, sacc, mk);
+        for (uint32_t dy = y; dy < yre; ++dy) {
+            const uint32_t lat = U.ylat[dy];
+            uint32_t thr[4] = {0, 0, 0, 0};
+            uint64_t go[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                // as in y_batches: position 1 either feeds position 0's threshold or is a source
+                thr[g] = thr0[g]; go[g] = alive[g];
+                if constexpr (E01) thr[g] = umin(thr0[g], __builtin_elementwise_sub_sat(room1[g], lat));
+                else go[g] = alive[g] & __builtin_amdgcn_ballot_w64(lat <= room1[g]);
+                if constexpr (BOUNDS) {
+                    const uint32_t fixed = s.cost_out + ((k32z[g] + U.yk32[dy]) >> U.lb);
+                    go[g] &= __builtin_amdgcn_ballot_w64((thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
+                    if (go[g] != 0) tb.visits += x_hi * 4u;
+                }
+            }
+            if constexpr (BOUNDS) { if ((go[0] | go[1] | go[2] | go[3]) == 0) continue; }
+            loop_x32_masked<G, BOUNDS>(U.pairs + (size_t)dy * U.pair_nq, thr, go, mk, qe, endb, full, m);
+        }
+        y = yre;
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const uint32_t cand = __builtin_elementwise_add_sat(m[g], k32z[g]);    // stays 0xFFFFFFFF if none
+        tb.k32 = tb.k32 < cand ? tb.k32 : cand;
+    }
+}
+
 template <bool BOUNDS, bool E01>
 __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
                                                uint32_t x_hi, uint64_t full, TileBest& tb)
 {
 #pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
-    const Entry JSV_CONST* ty = U.tab[1];
     const Entry JSV_CONST* tz = U.tab[2];
     const uint32_t nvx = __builtin_amdgcn_readfirstlane(U.nvx);
     const uint32_t src2 = __builtin_amdgcn_readfirstlane(U.src[2] ? 1u : 0u);
@@ -1949,7 +2025,6 @@ __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniform
 #pragma unroll
     for (int v = 0; v < MAX_XVAR; ++v) qe[v] = U.xqe[v];
     const uint32_t endb = x_hi * (uint32_t)sizeof(QuadC);
-    const uint32_t KY = U.K[1];
     uint32_t z = lo;
     while (z < hi) {
         const uint32_t zrun_end = U.zrun[z];
@@ -1959,74 +2034,13 @@ __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniform
         const double sacc2 = src2 != 0 ? s.sacc + Hz : s.sacc;
         const double hin1 = __builtin_fma(U.w12, Hz, s.hin[1]);
         const double hin0z = __builtin_fma(U.w02, Hz, s.hin[0]);
-        for (uint32_t zb = z; zb < zre; zb += 4) {
-            const uint32_t n = zre - zb < 4u ? zre - zb : 4u;
-            // latency state and key of each slot's digit of position 2 (a slot past the run repeats the last digit and is never passed on)
-            uint32_t thr0[4], room1[4], k32z[4], m[4];
-            uint64_t alive[4];
-            uint64_t any = 0;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const uint32_t zd = zb + ((uint32_t)g < n ? (uint32_t)g : n - 1u);
-                const uint32_t tail = tz[zd].lat + s.nxt[2];
-                const uint32_t smax = src2 != 0 ? umax(s.smax, tail) : s.smax;
-                const uint32_t nxt1 = umax(s.nxt[1], tail & U.m12);
-                const uint32_t nxt0 = umax(s.nxt[0], tail & U.m02);
-                k32z[g] = s.k32 + U.k32[2][zd];
-                thr0[g] = __builtin_elementwise_sub_sat(U.sloq, nxt0);
-                room1[g] = __builtin_elementwise_sub_sat(U.sloq, nxt1);
-                m[g] = 0xFFFFFFFFu;
-                bool meets = smax <= U.sloq;
-                if constexpr (BOUNDS) {
-                    // ... and stays within the cost bound with the cheapest entries of the two positions below
-                    const uint32_t fixed = s.cost_out + (k32z[g] >> U.lb);
-                    meets = meets & (fixed + U.min_xy_cost <= U.bound);
-                }
-                alive[g] = (uint32_t)g < n ? __builtin_amdgcn_ballot_w64(meets) : 0ull;
-                any |= alive[g];
-            }
-            if constexpr (BOUNDS) { if (any == 0) continue; }
-            uint32_t y = 0;
-            while (y < KY) {
-                const uint32_t yre = U.yrun[y];
-                // position 1 fixed to this run's accuracy (fix_position<1>), then Eq. 13 per variant of position 0
-                const double H = ty[y].acc * hin1;
-                const double sacc = E01 ? sacc2 : sacc2 + H;
-                const double hin0 = __builtin_fma(U.w01, H, hin0z);
-                uint64_t mk[MAX_XVAR];
-                variant_masks(U, nvx, hin0, sacc, mk);
-                for (uint32_t dy = y; dy < yre; ++dy) {
-                    const uint32_t lat = U.ylat[dy];
-                    uint32_t thr[4];
-                    uint64_t go[4];
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        // as in y_batches: position 1 either feeds position 0's threshold or is a source
-                        thr[g] = thr0[g]; go[g] = alive[g];
-                        if constexpr (E01) thr[g] = umin(thr0[g], __builtin_elementwise_sub_sat(room1[g], lat));
-                        else go[g] = alive[g] & __builtin_amdgcn_ballot_w64(lat <= room1[g]);
-                        if constexpr (BOUNDS) {
-                            const uint32_t fixed = s.cost_out + ((k32z[g] + U.yk32[dy]) >> U.lb);
-                            go[g] &= __builtin_amdgcn_ballot_w64((thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
-                            if (go[g] != 0) tb.visits += x_hi * 4u;
-                        }
-                    }
-                    if constexpr (BOUNDS) { if ((go[0] | go[1] | go[2] | go[3]) == 0) continue; }
-                    const QuadC JSV_CONST* base = U.pairs + (size_t)dy * U.pair_nq;
-                    switch (n) {
-                    case 4: loop_x32_masked<4, BOUNDS>(base, thr, go, mk, qe, endb, full, m); break;
-                    case 3: loop_x32_masked<3, BOUNDS>(base, thr, go, mk, qe, endb, full, m); break;
-                    case 2: loop_x32_masked<2, BOUNDS>(base, thr, go, mk, qe, endb, full, m); break;
-                    default: loop_x32_masked<1, BOUNDS>(base, thr, go, mk, qe, endb, full, m); break;
-                    }
-                }
-                y = yre;
-            }
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const uint32_t cand = __builtin_elementwise_add_sat(m[g], k32z[g]);    // stays 0xFFFFFFFF if none (unused slots kept it)
-                tb.k32 = tb.k32 < cand ? tb.k32 : cand;
-            }
+        uint32_t zb = z;
+        for (; zb + 4 <= zre; zb += 4) z_batch_pairs<4, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
+        switch (zre - zb) {
+        case 3: z_batch_pairs<3, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        case 2: z_batch_pairs<2, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        case 1: z_batch_pairs<1, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        default: break;
         }
         z = zre;
     }
