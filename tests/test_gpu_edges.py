@@ -394,3 +394,55 @@ def test_long_streams_and_long_runs_in_the_masked_loop(ctx):
     pb = _problem(3, 8, 8, 8, 91, [(0, 1), (0, 2)], capacity=0)
     _check_under_geometries(ctx, pb, _search([60000, 2_000_000], 140000, 0.7), bounds=(True,))
     _check_under_geometries(ctx, pb, _search([60000], 140000, 0.7, cap=96), bounds=(False,))
+
+
+# ---- three in-lane positions with the pair stream -----------------------------------------------
+# Cost modes, single tuples, at most eight variants in the innermost position, four or more digits
+# of the third position per tile: the digits of the third position are the slots, the stream holds
+# (second position, innermost position) pairs.  Few lanes asked of the planner bring small graphs there.
+PAIR_SHAPES = {
+    # position 1 a successor of position 0 (chain), a source (two sources), position 2 a source, both
+    "chain": [(0, 1), (1, 2), (2, 3), (3, 4)],
+    "source_at_1": [(0, 2), (1, 2), (2, 3), (3, 4)],
+    "source_at_2": [(0, 1), (2, 3), (1, 4), (3, 4)],
+    "sources_at_1_and_2": [(0, 3), (1, 3), (2, 4), (3, 4)],
+    "fan": [(0, 1), (0, 2), (1, 3), (2, 3), (0, 4)],
+}
+
+
+@pytest.mark.parametrize("shape", sorted(PAIR_SHAPES))
+@pytest.mark.parametrize("PB", [(1, 5), (2, 3), (1, 7), (3, 3)])
+def test_pair_stream_with_every_remainder_of_a_run(ctx, shape, PB):
+    """Runs of 5, 6, 7 and 9 digits per variant of the third position: batches of four slots and
+    every remainder (1, 2, 3), cut further by the tiles' chunks; the second position a successor
+    of the innermost one or a source; with and without bounds; thresholds that no, some and
+    most variant combinations meet."""
+    P, B = PB
+    pb = _problem(5, 3, P, B, 300 + 10 * P + B, PAIR_SHAPES[shape], mult=[1000, 800, 1200, 1000, 900], capacity=0)
+    try:
+        for blocks, lanes in ((1, 1), (1, 3), (0, 0)):
+            ctx.set_geometry(blocks, lanes)
+            for b in (False, True):
+                ctx.set_bounds(b)
+                for slo_a in (0.0, 0.66, 0.8):
+                    check_search(ctx, pb, _search([20000, 600000], 240000, slo_a))
+    finally:
+        ctx.set_geometry(0, 0)
+        ctx.set_bounds(True)
+
+
+def test_pair_stream_with_capacity_and_thinned_lists(ctx):
+    """A capacity that binds (the cost bound of the bounded search moves) and a prune cap that thins
+    the lists to uneven runs, on a six-task graph under the small-lane geometries."""
+    edges = [(0, 1), (0, 2), (1, 3), (2, 3), (3, 4), (1, 5)]
+    pb = _problem(6, 4, 3, 3, 411, edges, mult=[1000, 700, 1300, 1000, 1000, 400], capacity=90)
+    try:
+        for blocks, lanes in ((1, 1), (2, 2), (0, 0)):
+            ctx.set_geometry(blocks, lanes)
+            for b in (False, True):
+                ctx.set_bounds(b)
+                check_search(ctx, pb, _search([15000, 120000, 900000], 300000, 0.6, cap=14))
+                check_search(ctx, pb, _search([15000, 120000], 300000, 0.7, cap=22))
+    finally:
+        ctx.set_geometry(0, 0)
+        ctx.set_bounds(True)
