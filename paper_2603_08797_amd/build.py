@@ -36,8 +36,24 @@ def build(force: bool = True) -> str:
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + ["-x", "hip"] + srcs + ["-shared", "-o", LIB]
-    subprocess.check_call(cmd)
+    cmd = [hipcc] + FLAGS + ["-Rpass-analysis=kernel-resource-usage", "-x", "hip"] + srcs + ["-shared", "-o", LIB]
+    done = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    remarks = [l for l in done.stderr.splitlines() if "-Rpass-analysis=kernel-resource-usage" in l]
+    if done.returncode != 0 or " warning: " in done.stderr:
+        print("\n".join(l for l in done.stderr.splitlines() if l not in remarks and "packed-fp32-ops" not in l))
+    if done.returncode != 0:
+        raise subprocess.CalledProcessError(done.returncode, cmd)
+    # The enumeration kernels may not spill vector registers to scratch memory: the inline asm of
+    # their hot loops names scalar registers by number, and in a build with scratch in it the
+    # compiler keeps state of its own in registers that it then reserves.
+    name = ""
+    for l in remarks:
+        if "Function Name:" in l:
+            name = l.split("Function Name:")[1].split()[0]
+        elif ("enumerate_kernel" in name and "ScratchSize [bytes/lane]:" in l
+              and int(l.split("ScratchSize [bytes/lane]:")[1].split()[0]) != 0):
+            os.remove(LIB)
+            raise RuntimeError(f"kernel {name} uses scratch memory; lower its register pressure")
     return LIB
 
 

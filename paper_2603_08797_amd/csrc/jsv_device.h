@@ -276,6 +276,9 @@ struct Plan {
     // the cost of the cheapest candidate found so far that meets both SLOs (cost modes only)
     uint32_t* bound = nullptr;     // [n_inst]
     uint64_t* tile_begin = nullptr; // [n_inst] first global tile of every instance, for the search by tile
+    // objective mode: per instance the best objective any wave has reached so far, as a 64-bit
+    // pattern whose unsigned order is the order of the doubles (so that atomicMax keeps the best)
+    unsigned long long* best_obj = nullptr;  // [n_inst]
 };
 
 }  // namespace jsv

@@ -57,7 +57,7 @@ struct Search {               // per-instance search parameters (batch mode keep
 struct Layout {               // offsets into the workspace
     size_t inst, entries, rep, cost, k32, quads, pairs, partial, partial_obj, results, summary, eval, total;
     size_t cell_acc, cell_id, cell_pm, cell_list;     // mixture mode only
-    size_t bound, tile_begin;
+    size_t bound, tile_begin, best_obj;
 };
 
 }  // namespace
@@ -466,6 +466,7 @@ Layout make_layout(uint32_t n_inst, uint32_t t_max, uint32_t k_max, uint32_t c_m
     L.summary = off; off = align_up(off + sizeof(jsv::SummaryRec));
     L.bound = off;   off = align_up(off + sizeof(uint32_t) * n_inst);
     L.tile_begin = off; off = align_up(off + sizeof(uint64_t) * n_inst);
+    L.best_obj = off; off = align_up(off + sizeof(uint64_t) * n_inst);
     L.eval = off;    // index u64, latency u32, replicas u32*T, cost i32, accuracy f64, mask u8, bad u32
     off = align_up(off + (size_t)n_eval * (8 + 4 + 4 * MAXT + 4 + 8 + 1) + 6 * ALIGN);
     const size_t blocks = (size_t)n_inst * t_max;
@@ -518,6 +519,7 @@ jsv::Plan make_plan(const jsv_ctx* ctx, const void* graphs, const Layout& L, uns
     pl.summary = (jsv::SummaryRec*)(ws + L.summary);
     pl.bound = (uint32_t*)(ws + L.bound);
     pl.tile_begin = (uint64_t*)(ws + L.tile_begin);
+    pl.best_obj = (unsigned long long*)(ws + L.best_obj);
     pl.n_inst = n_inst; pl.t_max = t_max; pl.k_max = k_max; pl.c_max = c_max;
     pl.objective = (uint32_t)ctx->objective;
     if (mix_cells != 0) {

@@ -139,6 +139,18 @@ __device__ __forceinline__ Best wave_best(Best v)
     return pick(a, b);
 }
 
+// A double as a 64-bit pattern whose unsigned order is the doubles' order (no NaN here), and back.
+__device__ __forceinline__ unsigned long long ordered_bits(double x)
+{
+    const uint64_t b = __builtin_bit_cast(uint64_t, x);
+    return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+__device__ __forceinline__ double from_ordered_bits(unsigned long long o)
+{
+    const uint64_t b = (o >> 63) ? (o & 0x7FFFFFFFFFFFFFFFull) : ~o;
+    return __builtin_bit_cast(double, b);
+}
+
 // Best pair over a 256-thread block; valid in thread 0.
 __device__ __forceinline__ Best block_best(Best v, uint64_t* s_key, double* s_obj)
 {
@@ -917,6 +929,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         in->min_x_cost = (space != 0 && pl.bounds) ? s_mincost[tx] : 0u;
         in->min_xy_cost = (space != 0 && pl.bounds && n_in >= 2) ? s_mincost[tx] + s_mincost[s_task_at[1]] : 0u;
         pl.bound[i] = s_capacity != 0 ? s_capacity : 0xFFFFFFFFu;
+        pl.best_obj[i] = ordered_bits(-__builtin_inf());
         if (space != 0 && !use32) atomicOr(&in->flags, F_WIDE);
         for (int a = 0; a < 3; ++a) { in->ord[a] = ord[a]; s_ls[a] = ls[a]; }
         if (use32) for (uint32_t p = 0; p < n_in; ++p) s_lsT[s_task_at[p]] = ls[p];
@@ -1092,6 +1105,7 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     uint32_t min_x_cost; // cheapest entry of position 0
     uint32_t min_xy_cost; // cheapest entries of positions 0 and 1 together
     uint32_t bound;     // total cost beyond which a candidate cannot be the answer (as read at the tile's start)
+    double   obj_seen;  // objective mode: an objective some wave has already reached for this instance (-inf: none known)
     double   slo_raw;   // SLO_a * A_max
     // objective mode (Eq. 14)
     uint32_t idx_bits, lb, capacity;
@@ -1369,12 +1383,15 @@ struct TileBest {
 // Largest local key that can still matter for a lane whose positions outside the lane loops cost
 // `cost_out` and that already holds a candidate of objective `have` (-inf: none).  0: none can
 // (real keys are at least 1 << lb: every task costs at least one unit).
-__device__ __forceinline__ uint32_t key_limit(const Uniforms& U, uint32_t cost_out, double have)
+// `top`: what alpha * A_obj can be at most among the candidates in question - alpha itself
+// (A_obj <= 1), or less where their accuracy is known to stay below some value.
+__device__ __forceinline__ uint32_t key_limit(const Uniforms& U, uint32_t cost_out, double have, double top)
 {
     // Eq. 8, and what any block has made of the instance's shared limit so far (at most S_avail)
     uint32_t cost_lim = U.bound;
+    have = have > U.obj_seen ? have : U.obj_seen;           // (-inf where no objective is shared)
     if (U.inv_beta > 0.0 && have > -__builtin_inf()) {
-        const double lim = (U.alpha - have) * U.inv_beta;
+        const double lim = (top - have) * U.inv_beta;
         // one unit of slack keeps rounding and equal objectives out of the decision
         if (lim < 4294967000.0) { const uint32_t l = (lim > 0.0 ? (uint32_t)lim : 0u) + 1u; cost_lim = l < cost_lim ? l : cost_lim; }
     }
@@ -1395,7 +1412,7 @@ __device__ __forceinline__ void fold_variant(const LaneState& s, const Uniforms&
     const bool improved = hit && (obj > tb.obj || (obj == tb.obj && k < tb.k32));
     if (improved) { tb.obj = obj; tb.k32 = k; }
     if (__builtin_amdgcn_ballot_w64(improved) != 0) {            // rare once a lane holds something good
-        const uint32_t kl = key_limit(U, s.cost_out, tb.obj);
+        const uint32_t kl = key_limit(U, s.cost_out, tb.obj, U.alpha);
         tb.klim = kl < tb.klim ? kl : tb.klim;
         mlim = __builtin_elementwise_sub_sat(tb.klim, s.k32);
     }
@@ -1494,7 +1511,7 @@ __device__ __forceinline__ void loop_x32_mixobj(const LaneState& s, const Unifor
                 const bool improved = cand && (obj > tb.obj || (obj == tb.obj && k < tb.k32));
                 if (improved) { tb.obj = obj; tb.k32 = k; }
                 if (__builtin_amdgcn_ballot_w64(improved) != 0) {
-                    const uint32_t kl = key_limit(U, s.cost_out, tb.obj);
+                    const uint32_t kl = key_limit(U, s.cost_out, tb.obj, U.alpha);
                     tb.klim = kl < tb.klim ? kl : tb.klim;
                     mlim = __builtin_elementwise_sub_sat(tb.klim, s.k32);
                 }
@@ -1745,6 +1762,62 @@ __device__ __forceinline__ void variant_masks(const Uniforms& U, uint32_t nvx, d
 #endif
 }
 
+// The same, and the largest A_raw among the variants of position 0 (objective mode: no candidate
+// of this combination of variants of the other positions can be more accurate).
+__device__ __forceinline__ void variant_masks_tmax(const Uniforms& U, uint32_t nvx, double hin0, double sacc,
+                                                   uint64_t (&mk)[MAX_XVAR], double& tmax)
+{
+    static_assert(MAX_XVAR == 8, "written out for eight variants");
+#if defined(__HIP_DEVICE_COMPILE__)
+    double t, tm;
+#define JSV_VM(N, REGS, OUT)                                                                       \
+        "s_cmp_lt_u32 %[nvx], " N "\n\t"                                                           \
+        "s_cbranch_scc1 1f\n\t"                                                                    \
+        "v_fma_f64 %[t], " REGS ", %[hin0], %[sacc]\n\t"                                           \
+        "v_cmp_le_f64_e64 " OUT ", %[slo], %[t]\n\t"                                               \
+        "v_max_f64 %[tm], %[tm], %[t]\n\t"
+    asm volatile(
+        "s_load_dwordx16 s[72:87], %[xacc], 0x0\n\t"
+        "s_mov_b64 %[m1], 0\n\t"
+        "s_mov_b64 %[m2], 0\n\t"
+        "s_mov_b64 %[m3], 0\n\t"
+        "s_mov_b64 %[m4], 0\n\t"
+        "s_mov_b64 %[m5], 0\n\t"
+        "s_mov_b64 %[m6], 0\n\t"
+        "s_mov_b64 %[m7], 0\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "v_fma_f64 %[tm], s[72:73], %[hin0], %[sacc]\n\t"
+        "v_cmp_le_f64_e64 %[m0], %[slo], %[tm]\n\t"
+        JSV_VM("2", "s[74:75]", "%[m1]") JSV_VM("3", "s[76:77]", "%[m2]") JSV_VM("4", "s[78:79]", "%[m3]")
+        JSV_VM("5", "s[80:81]", "%[m4]") JSV_VM("6", "s[82:83]", "%[m5]") JSV_VM("7", "s[84:85]", "%[m6]")
+        JSV_VM("8", "s[86:87]", "%[m7]")
+        "1:"
+        : [m0] "=&s"(mk[0]), [m1] "=&s"(mk[1]), [m2] "=&s"(mk[2]), [m3] "=&s"(mk[3]),
+          [m4] "=&s"(mk[4]), [m5] "=&s"(mk[5]), [m6] "=&s"(mk[6]), [m7] "=&s"(mk[7]), [t] "=&v"(t), [tm] "=&v"(tm)
+        : [xacc] "s"(U.xacc), [nvx] "s"(nvx), [hin0] "v"(hin0), [sacc] "v"(sacc), [slo] "s"(U.slo_raw)
+        : "scc", "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82",
+          "s83", "s84", "s85", "s86", "s87");
+#undef JSV_VM
+    tmax = tm;
+#else
+    (void)U; (void)nvx; (void)hin0; (void)sacc; (void)mk; tmax = 0.0;
+#endif
+}
+
+// Objective mode: what can still matter among the candidates whose A_raw is at most tmax (one
+// combination of variants of positions 1 and 2, any variant of position 0): the key limit with
+// alpha_n * tmax in place of alpha, never above tb.klim, and the same as a total cost.
+__device__ __forceinline__ void combination_limits(const Uniforms& U, const TileBest& tb, uint32_t cost_out, double an_tmax,
+                                                   uint32_t& klim_blk, uint32_t& clim_abs)
+{
+    const uint32_t k = key_limit(U, cost_out, tb.obj, an_tmax);
+    klim_blk = k < tb.klim ? k : tb.klim;
+    // ((c - cost_out + 1) << lb) - 1 back to c; a limit too large for a key stands for "none"
+    clim_abs = klim_blk == 0u ? 0u
+             : klim_blk == 0xFFFFFFFEu ? 0xFFFFFFFFu
+             : __builtin_elementwise_add_sat(((klim_blk + 1u) >> U.lb) - 1u, cost_out);
+}
+
 typedef uint32_t YWords __attribute__((ext_vector_type(4), aligned(4)));       // four digits' latencies or keys
 
 // The digits [d, re) of one run of position 1, four at a time, against position 0's stream.
@@ -1756,7 +1829,8 @@ template <int MODE, bool BOUNDS, bool E01, typename MakeS1>
 __device__ __forceinline__ void y_batches(const Uniforms& U, uint32_t smax, uint32_t thr0, uint32_t room1, uint64_t alive0,
                                           uint32_t k32, uint32_t cost_out, uint32_t d, uint32_t re,
                                           const uint64_t (&mk)[MAX_XVAR], const uint32_t (&qe)[MAX_XVAR], uint32_t endb,
-                                          uint32_t x_hi, uint64_t full, TileBest& tb, MakeS1 make_s1)
+                                          uint32_t x_hi, uint64_t full, TileBest& tb, MakeS1 make_s1,
+                                          uint32_t klim_blk = 0xFFFFFFFEu, uint32_t clim_abs = 0xFFFFFFFFu, double an_tmax = 0.0)
 {
     // Position 1 is either a successor of position 0 (its only possible predecessor; E01) or a
     // source: in the first case its tail changes position 0's latency threshold, in the second
@@ -1784,7 +1858,9 @@ __device__ __forceinline__ void y_batches(const Uniforms& U, uint32_t smax, uint
             if constexpr (BOUNDS) {
                 // also out: lanes whose fixed positions plus the cheapest entry of position 0 cost more than the bound
                 const uint32_t fixed = cost_out + ((k32 + key4[g]) >> U.lb);
-                go[g] = __builtin_amdgcn_ballot_w64(meets & (thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
+                // (objective mode: the bound of this combination of variants, see combination_limits)
+                const uint32_t within = MODE == MODE_OBJ ? umin(clim_abs, U.bound) : U.bound;
+                go[g] = __builtin_amdgcn_ballot_w64(meets & (thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= within));
             }
             // (without bounds a slot past the run keeps whatever lanes: only the first n slots are
             // passed on below, and in the usual case all four share one set of live lanes)
@@ -1794,17 +1870,19 @@ __device__ __forceinline__ void y_batches(const Uniforms& U, uint32_t smax, uint
             }
         }
         if constexpr (BOUNDS) { if ((go[0] | go[1] | go[2] | go[3]) == 0) continue; }
+        // (fewer than four digits left in the run: only those slots go through the stream - a slot
+        // without lanes would still cost its vector instructions)
         if (n >= 4) loop_x32_masked<4, BOUNDS>(U.xq, thr, go, mk, qe, endb, full, m);
-        else {
-            // three digits: two and one (a slot without lanes would still cost its vector instructions)
-            if (n >= 2) loop_x32_masked<2, BOUNDS>(U.xq, thr, go, mk, qe, endb, full, m);
-            if (n != 2) {
-                const int g = n == 3 ? 2 : 0;
-                uint32_t thr1[4] = {g == 2 ? thr[2] : thr[0], 0, 0, 0}, m1[4] = {0xFFFFFFFFu, 0, 0, 0};
-                uint64_t go1[4] = {g == 2 ? go[2] : go[0], 0, 0, 0};
-                loop_x32_masked<1, BOUNDS>(U.xq, thr1, go1, mk, qe, endb, full, m1);
-                if (g == 2) m[2] = m1[0]; else m[0] = m1[0];
-            }
+        else if (n == 3) loop_x32_masked<3, BOUNDS>(U.xq, thr, go, mk, qe, endb, full, m);
+        else if (n == 2) loop_x32_masked<2, BOUNDS>(U.xq, thr, go, mk, qe, endb, full, m);
+        else loop_x32_masked<1, BOUNDS>(U.xq, thr, go, mk, qe, endb, full, m);
+        if constexpr (MODE == MODE_OBJ) {
+            // the four digits' cheapest candidate first: mostly none of them lies within the limit
+            // (a slot past the run, or without lanes, kept m = 0xFFFFFFFF)
+            const uint32_t r01 = umin(__builtin_elementwise_add_sat(m[0], key4[0]), __builtin_elementwise_add_sat(m[1], key4[1]));
+            const uint32_t r23 = umin(__builtin_elementwise_add_sat(m[2], key4[2]), __builtin_elementwise_add_sat(m[3], key4[3]));
+            const uint32_t cand4 = __builtin_elementwise_add_sat(umin(r01, r23), k32);
+            if (__builtin_amdgcn_ballot_w64(cand4 <= umin(tb.klim, klim_blk)) == 0) continue;
         }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -1813,7 +1891,16 @@ __device__ __forceinline__ void y_batches(const Uniforms& U, uint32_t smax, uint
                 // first of the two passes of objective mode (see loop_x); the second, rare, takes the
                 // general path with the lane state of this digit
                 const uint32_t cand = __builtin_elementwise_add_sat(rel, k32);
-                if ((uint32_t)g < n && __builtin_amdgcn_ballot_w64(cand <= tb.klim) != 0) {
+                bool want = cand <= umin(tb.klim, klim_blk);
+                if ((uint32_t)g < n && __builtin_amdgcn_ballot_w64(want) != 0) {
+                    // Exactly: every candidate of this pair of digits costs at least what the cheapest one
+                    // does and is at most as accurate as the combination's best variant, so none scores
+                    // more than this (same operations as the objective itself, which are monotone).
+                    const uint32_t cost = cost_out + (cand >> U.lb);
+                    const double most = __builtin_fma(-U.beta, (double)cost, an_tmax);
+                    want = want & (most >= tb.obj) & (most >= U.obj_seen);
+                }
+                if ((uint32_t)g < n && __builtin_amdgcn_ballot_w64(want) != 0) {
                     const LaneState s1 = make_s1(d + g);
                     TileBest again = tb;
                     again.visits = 0;
@@ -1856,9 +1943,16 @@ __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms
         const double sacc = E01 ? s.sacc : s.sacc + H;
         const double hin0 = __builtin_fma(U.w01, H, s.hin[0]);
         uint64_t mk[MAX_XVAR];
-        variant_masks(U, nvx, hin0, sacc, mk);
+        uint32_t klim_blk = 0xFFFFFFFEu, clim_abs = 0xFFFFFFFFu;
+        double an_tmax = 0.0;
+        if constexpr (MODE == MODE_OBJ) {
+            double tmax;
+            variant_masks_tmax(U, nvx, hin0, sacc, mk, tmax);
+            an_tmax = U.alpha_n * tmax;
+            combination_limits(U, tb, s.cost_out, an_tmax, klim_blk, clim_abs);
+        } else variant_masks(U, nvx, hin0, sacc, mk);
         y_batches<MODE, BOUNDS, E01>(U, s.smax, thr0, room1, alive0, s.k32, s.cost_out, d, re, mk, qe, endb, x_hi, full, tb,
-            [&](uint32_t yd) { return fix_position<1>(s, U, ty[yd].lat, ty[yd].acc, 0, U.k32[1][yd]); });
+            [&](uint32_t yd) { return fix_position<1>(s, U, ty[yd].lat, ty[yd].acc, 0, U.k32[1][yd]); }, klim_blk, clim_abs, an_tmax);
         d = re;
     }
 }
@@ -1899,7 +1993,14 @@ __device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniform
             const double sacc = E01 ? sacc2 : sacc2 + H;
             const double hin0 = __builtin_fma(U.w01, H, hin0z);
             uint64_t mk[MAX_XVAR];
-            variant_masks(U, nvx, hin0, sacc, mk);
+            uint32_t klim_blk = 0xFFFFFFFEu, clim_abs = 0xFFFFFFFFu;
+            double an_tmax = 0.0;
+            if constexpr (MODE == MODE_OBJ) {
+                double tmax;
+                variant_masks_tmax(U, nvx, hin0, sacc, mk, tmax);
+                an_tmax = U.alpha_n * tmax;
+                combination_limits(U, tb, s.cost_out, an_tmax, klim_blk, clim_abs);
+            } else variant_masks(U, nvx, hin0, sacc, mk);
             for (uint32_t zd = z; zd < zre; ++zd) {
                 // latency state and key with this digit of position 2 fixed
                 const uint32_t tail = tz[zd].lat + s.nxt[2];
@@ -1911,7 +2012,8 @@ __device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniform
                     // is any lane left that meets the latency SLO so far and stays within the cost
                     // bound with the cheapest entries of the two positions below?
                     const uint32_t fixed = s.cost_out + (k32 >> U.lb);
-                    if (__builtin_amdgcn_ballot_w64((smax <= U.sloq) & (fixed + U.min_xy_cost <= U.bound)) == 0) continue;
+                    const uint32_t within = MODE == MODE_OBJ ? umin(clim_abs, U.bound) : U.bound;
+                    if (__builtin_amdgcn_ballot_w64((smax <= U.sloq) & (fixed + U.min_xy_cost <= within)) == 0) continue;
                 }
                 const uint64_t alive0 = __builtin_amdgcn_ballot_w64(smax <= U.sloq);
                 const uint32_t thr0 = __builtin_elementwise_sub_sat(U.sloq, nxt0);
@@ -1920,7 +2022,7 @@ __device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniform
                     [&](uint32_t yd) {
                         const LaneState s2 = fix_position<2>(s, U, tz[zd].lat, tz[zd].acc, 0, U.k32[2][zd]);
                         return fix_position<1>(s2, U, ty[yd].lat, ty[yd].acc, 0, U.k32[1][yd]);
-                    });
+                    }, klim_blk, clim_abs, an_tmax);
             }
             y = yre;
         }
@@ -2108,7 +2210,7 @@ template <int NIN, bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instance JSV_CONST* in,
                                          const Entry JSV_CONST* tab, const uint32_t JSV_CONST* k32,
                                          const Quad JSV_CONST* quads, const QuadC JSV_CONST* pairs, const Entry* s_tab, uint32_t k_max, bool mix,
-                                         uint64_t group, uint32_t chunk_id, uint32_t bound, Best& best, uint64_t& visited)
+                                         uint64_t group, uint32_t chunk_id, uint32_t bound, double obj_seen, Best& best, uint64_t& visited)
 {
 #pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
     const uint32_t T = g->T;
@@ -2182,6 +2284,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     U.min_x_cost = in->min_x_cost;
     U.min_xy_cost = in->min_xy_cost;
     U.bound = bound;
+    U.obj_seen = MODE == MODE_OBJ ? obj_seen : -__builtin_inf();
     U.slo_raw = in->slo_raw;
     U.idx_bits = in->idx_bits; U.lb = in->lb; U.capacity = g->capacity;
     U.alpha_n = in->alpha_n; U.beta = in->beta;
@@ -2209,9 +2312,12 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     const uint32_t lo = chunk_id * in->chunk;
     const uint32_t hi = lo + in->chunk < Ko ? lo + in->chunk : Ko;
     TileBest tb;
-    tb.k32 = 0xFFFFFFFFu; tb.obj = -__builtin_inf(); tb.visits = 0;
+    // (objective mode over single tuples, 32-bit keys: the tile's best starts at the objective the lane already holds, with
+    // no key - a candidate must reach that objective to be noted, and ties are settled on the full
+    // keys after the tile)
+    tb.k32 = 0xFFFFFFFFu; tb.obj = (MODE == MODE_OBJ && W32) ? best.obj : -__builtin_inf(); tb.visits = 0;
     tb.klim = 0xFFFFFFFEu;
-    if constexpr (is_obj(MODE) && W32) tb.klim = key_limit(U, st.cost_out, best.obj);
+    if constexpr (is_obj(MODE) && W32) tb.klim = key_limit(U, st.cost_out, best.obj, U.alpha);
     const uint64_t full = __builtin_amdgcn_read_exec();     // the loops below run convergent
     if constexpr (NIN == 3) loop_z<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
     else if constexpr (NIN == 2) loop_y<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
@@ -2291,6 +2397,7 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     best.key = NO_KEY; best.obj = -__builtin_inf();
     uint64_t visited = 0;           // wave-uniform
     uint32_t bound_seen = 0xFFFFFFFFu;      // cost bound of instance `cur` as last read or lowered by this wave
+    double obj_seen = -__builtin_inf();     // objective mode: best objective of instance `cur` that this wave knows of
     const uint32_t own = as_uniform((const SummaryRec*)pl.summary)->own_tiles;
     const uint32_t rounds = as_uniform((const SummaryRec*)pl.summary)->own_rounds;
     const uint32_t batch = as_uniform((const SummaryRec*)pl.summary)->batch_tiles;
@@ -2343,6 +2450,11 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
             if constexpr (SHARE)
                 bound_seen = (uint32_t)__builtin_amdgcn_readfirstlane(
                     (int)__hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            if constexpr (MODE == MODE_OBJ) {
+                const unsigned long long ob = __hip_atomic_load(pl.best_obj + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                obj_seen = from_ordered_bits(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ob >> 32)) << 32) |
+                                             (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ob));
+            }
         }
         const Instance JSV_CONST* in = insts + cur;
         const Graph JSV_CONST* g = graphs + in->problem;
@@ -2360,24 +2472,31 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const uint32_t bound = bound_seen;
         uint32_t fresh = 0xFFFFFFFFu;
         if constexpr (SHARE) fresh = __hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned long long fresh_obj = 0;
+        if constexpr (MODE == MODE_OBJ) fresh_obj = __hip_atomic_load(pl.best_obj + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const uint64_t key_before = best.key;
         const double obj_before = best.obj;
         if (in->use32) {
             switch (in->n_in) {
-            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
-            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
-            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
+            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
+            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
             }
         } else {
             switch (in->n_in) {
-            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
-            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
-            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, best, visited); break;
+            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
+            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
+            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
             }
         }
         if constexpr (SHARE) {
             const uint32_t other = (uint32_t)__builtin_amdgcn_readfirstlane((int)fresh);
             bound_seen = other < bound_seen ? other : bound_seen;
+            if constexpr (MODE == MODE_OBJ) {
+                const double oo = from_ordered_bits(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(fresh_obj >> 32)) << 32) |
+                                                    (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)fresh_obj));
+                obj_seen = oo > obj_seen ? oo : obj_seen;
+            }
             // Did a lane of this wave find something better in this tile?  Then the bound may drop
             // for every block working on the instance.
             const bool improved = __builtin_amdgcn_ballot_w64((best.key != key_before) | (best.obj != obj_before)) != 0;
@@ -2392,6 +2511,12 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
                     // objective o already reached, nothing costlier than (alpha - o)/beta can match it;
                     // one unit of slack keeps the test clear of rounding and of equal objectives.
                     const Best wb = wave_best(best);
+                    if constexpr (MODE == MODE_OBJ) {
+                        if (wb.key != NO_KEY && wb.obj > obj_seen) {
+                            obj_seen = wb.obj;
+                            if ((threadIdx.x & 63u) == 0) atomicMax(pl.best_obj + cur, ordered_bits(wb.obj));
+                        }
+                    }
                     if (wb.key != NO_KEY && in->beta > 1e-9 * (in->alpha + 1.0)) {     // else rounding could reach a unit of cost
                         const double lim = (in->alpha - wb.obj) / in->beta;
                         if (lim >= 0.0 && lim < 2147483000.0) wc = (uint32_t)lim + 1u;
