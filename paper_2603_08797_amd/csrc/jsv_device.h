@@ -254,6 +254,7 @@ struct Plan {
     Quad*        quads = nullptr;       // [n_inst][quad_stride(k_max)]  stream of the innermost position
     QuadC*       pairs = nullptr;       // [n_inst][pair_cap + 1]   pair stream of positions 1 and 0
     uint32_t     pair_cap = 0;          // records of it per instance (0: none)
+    uint32_t     pair_pad = 0;          // (explicit, so that the struct has no unnamed padding)
     uint64_t*    partial = nullptr;     // [n_inst][grid]           per-block minima (keys)
     double*      partial_obj = nullptr; // [n_inst][grid]           per-block best objectives (objective mode)
     ResultRec*   results = nullptr;     // [n_inst]
