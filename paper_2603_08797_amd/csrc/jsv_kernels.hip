@@ -771,6 +771,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     const uint32_t T = g->T;
     __shared__ uint32_t s_maxcost[MAXT], s_mincost[MAXT], s_K[MAXT], s_off[MAXT + 1], s_lsT[MAXT], s_minxlat;
     __shared__ uint32_t s_bits, s_lb, s_nin, s_ls[3], s_chunk, s_nq, s_last, s_nvx;
+    __shared__ unsigned long long s_xtop;
     __shared__ uint64_t s_stride[MAXT];
     // the innermost position's entries, staged once: variant, latency, cost, and the first
     // quad of the variant that starts at digit d
@@ -922,6 +923,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         in->nvx = 0;                      // set with the stream of single tuples, if there is one
         in->pair_nq = 0;                  // set with the pair stream, if there is one
         s_nvx = 0;
+        s_xtop = 0;
         uint64_t min_in = 0;
         for (uint32_t p = 0; p < n_in; ++p) min_in += s_mincost[s_task_at[p]];
         in->min_in_cost = (space != 0 && pl.bounds) ? (uint32_t)(min_in > 0xFFFFFFFFull ? 0xFFFFFFFFull : min_in) : 0u;
@@ -967,11 +969,22 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             me.lat = lat; me.k32 = (s_xcost[d] << s_lb) | (d * s_ls[0]); me.acc = ex[d].acc;
             qm[rank / 4].e[rank % 4] = me;
         }
+        // the most accurate option of position 0: a ceiling for objective mode (positive doubles order as their bits)
+        {
+            unsigned long long top = 0;
+            for (uint32_t d = tid; d < KX; d += blockDim.x) {
+                const unsigned long long b = __builtin_bit_cast(unsigned long long, ex[d].acc);
+                top = b > top ? b : top;
+            }
+            if (top != 0) atomicMax(&s_xtop, top);
+        }
         for (uint32_t r = KX + tid; r < s_nq * 4; r += blockDim.x) {
             XEntM pad;
             pad.lat = 0xFFFFFFFFu; pad.k32 = 0xFFFFFFFFu; pad.acc = 0.0;
             qm[r / 4].e[r % 4] = pad;
         }
+        __syncthreads();
+        if (tid == 0) in->xacc[0] = __builtin_bit_cast(double, s_xtop);
     } else if (s_nin != 0) {
         const Entry* ex = ent + (size_t)tx * pl.k_max;
         Quad* qd = pl.quads + (size_t)i * quad_stride(pl.k_max);
@@ -1544,7 +1557,18 @@ __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, ui
             uint32_t cheapest = 0xFFFFFFFFu, unused = 0;
             if constexpr (is_mix(MODE)) loop_x32_mix<BOUNDS>(s, U, lo, hi, full, cheapest, tb.visits);
             else loop_x32<BOUNDS>(s, U, lo, hi, full, cheapest, tb.visits);
-            if (__builtin_amdgcn_ballot_w64(cheapest <= tb.klim) != 0) {
+            bool want = cheapest <= tb.klim;
+            if constexpr (is_mix(MODE)) {
+                if (__builtin_amdgcn_ballot_w64(want) != 0) {
+                    // Exactly: no option of position 0 is more accurate than its most accurate one and
+                    // none that passes costs less than the cheapest, so nothing in this pass scores more
+                    // than this (same operations as the objective itself, which are monotone).
+                    const double top = U.alpha_n * __builtin_fma(U.xacc[0], s.hin[0], s.sacc);
+                    const uint32_t cost = s.cost_out + (cheapest >> U.lb);
+                    want = want & (__builtin_fma(-U.beta, (double)cost, top) >= tb.obj);
+                }
+            }
+            if (__builtin_amdgcn_ballot_w64(want) != 0) {
                 TileBest again = tb;
                 again.visits = 0;
                 if constexpr (is_mix(MODE)) loop_x32_mixobj<BOUNDS>(s, U, lo, hi, again);
@@ -2312,10 +2336,10 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     const uint32_t lo = chunk_id * in->chunk;
     const uint32_t hi = lo + in->chunk < Ko ? lo + in->chunk : Ko;
     TileBest tb;
-    // (objective mode over single tuples, 32-bit keys: the tile's best starts at the objective the lane already holds, with
+    // (objective mode, 32-bit keys: the tile's best starts at the objective the lane already holds, with
     // no key - a candidate must reach that objective to be noted, and ties are settled on the full
     // keys after the tile)
-    tb.k32 = 0xFFFFFFFFu; tb.obj = (MODE == MODE_OBJ && W32) ? best.obj : -__builtin_inf(); tb.visits = 0;
+    tb.k32 = 0xFFFFFFFFu; tb.obj = (is_obj(MODE) && W32) ? best.obj : -__builtin_inf(); tb.visits = 0;
     tb.klim = 0xFFFFFFFEu;
     if constexpr (is_obj(MODE) && W32) tb.klim = key_limit(U, st.cost_out, best.obj, U.alpha);
     const uint64_t full = __builtin_amdgcn_read_exec();     // the loops below run convergent
