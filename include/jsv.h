@@ -348,7 +348,7 @@ JSV_API int jsv_search(jsv_ctx* ctx, const uint32_t* demand_mrps, uint32_t n_lev
  *
  * Errors as jsv_search, plus: JSV_E_WORKSPACE if tables and workspace of this search exceed
  * JSV_STATIC_SCRATCH_BYTES (xr8-sized: 8 tasks x 240 choices, 64 levels, prune cap 20 takes
- * 3.6 MB; nothing is launched); JSV_E_STATE with per-variant factors, mixtures, a loaded batch or
+ * 4.2 MB; nothing is launched); JSV_E_STATE with per-variant factors, mixtures, a loaded batch or
  * graph mode, which this entry point does not serve.
  */
 #define JSV_STATIC_SCRATCH_BYTES (16u << 20)
