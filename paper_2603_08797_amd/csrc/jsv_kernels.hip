@@ -2066,7 +2066,7 @@ __device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniform
 // One batch of G digits of position 2, starting at zb, against all digits of position 1 (the
 // slot count is a template parameter so that the minima keep their registers over the loops).
 // sacc2, hin1, hin0z: the accuracy state with position 2 fixed to the run's variant.
-template <int G, bool BOUNDS, bool E01>
+template <int MODE, int G, bool BOUNDS, bool E01>
 __device__ __forceinline__ void z_batch_pairs(const LaneState& s, const Uniforms& U, uint32_t zb, uint32_t nvx, uint32_t src2,
                                               double sacc2, double hin1, double hin0z, const uint32_t (&qe)[MAX_XVAR],
                                               uint32_t endb, uint32_t x_hi, uint64_t full, TileBest& tb)
@@ -2110,7 +2110,18 @@ __device__ __forceinline__ void z_batch_pairs(const LaneState& s, const Uniforms
         const double sacc = E01 ? sacc2 : sacc2 + H;
         const double hin0 = __builtin_fma(U.w01, H, hin0z);
         uint64_t mk[MAX_XVAR];
-        variant_masks(U, nvx, hin0, sacc, mk);
+        uint32_t klim_blk = 0xFFFFFFFEu, clim_abs = 0xFFFFFFFFu;
+        double an_tmax = 0.0;
+        if constexpr (MODE == MODE_OBJ) {
+            // objective mode: the limits of this combination of variants (see combination_limits); the
+            // slots' minima start afresh, so that a minimum within the limit belongs to this run
+            double tmax;
+            variant_masks_tmax(U, nvx, hin0, sacc, mk, tmax);
+            an_tmax = U.alpha_n * tmax;
+            combination_limits(U, tb, s.cost_out, an_tmax, klim_blk, clim_abs);
+#pragma unroll
+            for (int g = 0; g < G; ++g) m[g] = 0xFFFFFFFFu;
+        } else variant_masks(U, nvx, hin0, sacc, mk);
         for (uint32_t dy = y; dy < yre; ++dy) {
             const uint32_t lat = U.ylat[dy];
             uint32_t thr[4] = {0, 0, 0, 0};
@@ -2123,23 +2134,56 @@ __device__ __forceinline__ void z_batch_pairs(const LaneState& s, const Uniforms
                 else go[g] = alive[g] & __builtin_amdgcn_ballot_w64(lat <= room1[g]);
                 if constexpr (BOUNDS) {
                     const uint32_t fixed = s.cost_out + ((k32z[g] + U.yk32[dy]) >> U.lb);
-                    go[g] &= __builtin_amdgcn_ballot_w64((thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound));
+                    const uint32_t within = MODE == MODE_OBJ ? umin(clim_abs, U.bound) : U.bound;
+                    go[g] &= __builtin_amdgcn_ballot_w64((thr[g] >= U.min_x_lat) & (fixed + U.min_x_cost <= within));
                     if (go[g] != 0) tb.visits += x_hi * 4u;
                 }
             }
             if constexpr (BOUNDS) { if ((go[0] | go[1] | go[2] | go[3]) == 0) continue; }
             loop_x32_masked<G, BOUNDS>(U.pairs + (size_t)dy * U.pair_nq, thr, go, mk, qe, endb, full, m);
+            if constexpr (MODE == MODE_OBJ) {
+                // First of the two passes of objective mode (see loop_x).  A slot's minimum runs over the
+                // digits of position 1 since it was last reset; while it lies above the limit nothing so
+                // far can matter, and once it lies within, this digit gets its second pass (its own
+                // cheapest candidate is at least that minimum) and the minimum starts afresh.
+                uint32_t c[4] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+#pragma unroll
+                for (int g = 0; g < G; ++g) c[g] = __builtin_elementwise_add_sat(m[g], k32z[g]);
+                const uint32_t cmin = umin(umin(c[0], c[1]), umin(c[2], c[3]));
+                if (__builtin_amdgcn_ballot_w64(cmin <= umin(tb.klim, klim_blk)) == 0) continue;
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    bool want = c[g] <= umin(tb.klim, klim_blk);
+                    if (__builtin_amdgcn_ballot_w64(want) == 0) continue;
+                    m[g] = 0xFFFFFFFFu;
+                    // exactly: nothing of this pair of digits scores more than its cheapest candidate would
+                    // with the combination's best accuracy (see y_batches)
+                    const uint32_t cost = s.cost_out + (c[g] >> U.lb);
+                    const double most = __builtin_fma(-U.beta, (double)cost, an_tmax);
+                    want = want & (most >= tb.obj) & (most >= U.obj_seen);
+                    if (__builtin_amdgcn_ballot_w64(want) == 0) continue;
+                    const uint32_t zd = zb + (uint32_t)g;
+                    const LaneState s2 = fix_position<2>(s, U, tz[zd].lat, tz[zd].acc, 0, U.k32[2][zd]);
+                    const LaneState s1 = fix_position<1>(s2, U, ty[dy].lat, ty[dy].acc, 0, U.k32[1][dy]);
+                    TileBest again = tb;
+                    again.visits = 0;
+                    loop_x32_obj<BOUNDS>(s1, U, 0, x_hi, full, again);
+                    tb.k32 = again.k32; tb.obj = again.obj; tb.klim = again.klim;
+                }
+            }
         }
         y = yre;
     }
+    if constexpr (MODE != MODE_OBJ) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const uint32_t cand = __builtin_elementwise_add_sat(m[g], k32z[g]);    // stays 0xFFFFFFFF if none
-        tb.k32 = tb.k32 < cand ? tb.k32 : cand;
+        for (int g = 0; g < G; ++g) {
+            const uint32_t cand = __builtin_elementwise_add_sat(m[g], k32z[g]);    // stays 0xFFFFFFFF if none
+            tb.k32 = tb.k32 < cand ? tb.k32 : cand;
+        }
     }
 }
 
-template <bool BOUNDS, bool E01>
+template <int MODE, bool BOUNDS, bool E01>
 __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
                                                uint32_t x_hi, uint64_t full, TileBest& tb)
 {
@@ -2161,11 +2205,11 @@ __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniform
         const double hin1 = __builtin_fma(U.w12, Hz, s.hin[1]);
         const double hin0z = __builtin_fma(U.w02, Hz, s.hin[0]);
         uint32_t zb = z;
-        for (; zb + 4 <= zre; zb += 4) z_batch_pairs<4, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
+        for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
         switch (zre - zb) {
-        case 3: z_batch_pairs<3, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
-        case 2: z_batch_pairs<2, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
-        case 1: z_batch_pairs<1, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        case 3: z_batch_pairs<MODE, 3, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        case 2: z_batch_pairs<MODE, 2, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        case 1: z_batch_pairs<MODE, 1, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
         default: break;
         }
         z = zre;
@@ -2200,11 +2244,13 @@ __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, ui
     if constexpr (W32 && !is_mix(MODE)) {
         // single tuples with few variants in position 0: by runs of positions 2 and 1 (see loop_y for the tests)
         if (U.nvx - 1u < (uint32_t)MAX_XVAR && U.src[1] == (U.m01 == 0)) {
-            if constexpr (MODE == MODE_COST) {
-                // (worth it from four digits of position 2 per tile: they are the slots that share a record)
+            // (worth it from four digits of position 2 per tile: they are the slots that share a record;
+            // objective mode with bounds stays with the loops below: there the pair loop's larger
+            // register set costs more in resident waves than it saves in instructions)
+            if constexpr (MODE == MODE_COST || !BOUNDS) {
                 if (U.pair_nq != 0 && hi - lo >= 4u) {
-                    if (U.m01 != 0) loop_zyx_pairs<BOUNDS, true>(s, U, lo, hi, x_hi, full, tb);
-                    else loop_zyx_pairs<BOUNDS, false>(s, U, lo, hi, x_hi, full, tb);
+                    if (U.m01 != 0) loop_zyx_pairs<MODE, BOUNDS, true>(s, U, lo, hi, x_hi, full, tb);
+                    else loop_zyx_pairs<MODE, BOUNDS, false>(s, U, lo, hi, x_hi, full, tb);
                     return;
                 }
             }
@@ -2783,12 +2829,15 @@ int enumerate_mode(bool objective, bool mixtures)
     return objective ? (mixtures ? MODE_MIXOBJ : MODE_OBJ) : mixtures ? MODE_MIX : MODE_COST;
 }
 
-// Blocks of the enumeration kernel that are resident per CU with this much LDS; with bounds
-// on, the smaller figure of the two variants that launch_enumerate sends out.
+// Blocks of the enumeration kernel that are resident per CU with this much LDS.  With bounds on
+// both variants are launched with one grid (launch_enumerate) and the figure is that of the
+// variant with bounds, which does the work in every search large enough for the grid to matter;
+// where the device picks the plain variant after all, blocks beyond what is resident simply
+// start later (no block ever waits for another).
 hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, int mode, bool bounds, int* blocks)
 {
     const size_t lds = enumerate_lds_bytes(t_max, k_max);
-    int least = 0;
+    int wanted = 0;
     for (int b = 0; b <= (bounds ? 1 : 0); ++b) {
         const void* fn = (const void*)enumerate_entry(mode, b != 0);
         if (lds > 32 * 1024) {      // beyond the default dynamic limit: ask for it explicitly
@@ -2798,9 +2847,10 @@ hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, int mode, boo
         int n = 0;
         hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, TILE_LANES, lds);
         if (e != hipSuccess) return e;
-        least = (b == 0 || n < least) ? n : least;
+        if (n < 1) { *blocks = 0; return hipSuccess; }      // (a variant that does not fit at all)
+        wanted = n;                                         // the last one asked: with bounds, that variant
     }
-    *blocks = least;
+    *blocks = wanted;
     return hipSuccess;
 }
 

@@ -18,7 +18,7 @@ hipError_t launch_prune_plan_scan(const Plan& pl, hipStream_t stream);
 // which instantiation of the enumeration kernel a search runs
 int enumerate_mode(bool objective, bool mixtures);
 hipError_t enumerate_blocks_per_cu(uint32_t t_max, uint32_t k_max, int mode, bool bounds, int* blocks);
-// pl.grid blocks; pl.grid must not exceed what enumerate_blocks_per_cu allows to be resident
+// pl.grid blocks, as many as enumerate_blocks_per_cu says are resident at once (more would only start later)
 hipError_t launch_enumerate(const Plan& pl, hipStream_t stream);
 hipError_t launch_finalize(const Plan& pl, hipStream_t stream);
 // all pointers are device pointers; pl.inst / pl.entries address ONE instance
