@@ -92,11 +92,17 @@ static_assert(sizeof(QuadC) == 32, "QuadC must be 32 bytes");
 // each are read at a time, from any digit), and per digit the first later digit whose variant
 // has another accuracy (digits in between share the accuracy outcome of every variant of
 // position 0).  A fourth array of the same size holds, per digit of position 2, the first later
-// digit of another variant.
+// digit of another variant; a fifth and a sixth, per digit of position 1, the smallest local key
+// and the lowest latency from that digit to the end of its run (bounds: a run none of whose digits
+// can stay within the cost bound or meet the latency SLO is left out as a whole).
 constexpr uint32_t ydigit_words(uint32_t k_max) { return k_max + 3; }
+constexpr uint32_t YDIGIT_ARRAYS = 6;
 // Records of 64 bytes per instance in the stream buffer: k_max Quad (or QuadM), then
-// k_max + 1 QuadC, then the four arrays of the digits of positions 1 and 2 (4 x ydigit_words(k_max) words).
-constexpr uint32_t quad_stride(uint32_t k_max) { return k_max + (k_max + 2) / 2 + (k_max + 6) / 4; }
+// k_max + 1 QuadC, then the arrays of the digits of positions 1 and 2 (YDIGIT_ARRAYS x ydigit_words(k_max) words).
+constexpr uint32_t quad_stride(uint32_t k_max)
+{
+    return k_max + (k_max + 2) / 2 + (YDIGIT_ARRAYS * ydigit_words(k_max) + 15) / 16;
+}
 constexpr uint32_t quadc_offset(uint32_t k_max) { return k_max; }                          // in Quad units
 constexpr uint32_t yrec_offset(uint32_t k_max) { return k_max + (k_max + 2) / 2; }
 // Pair stream (single tuples, three in-lane positions): for every digit of position 1 a copy of

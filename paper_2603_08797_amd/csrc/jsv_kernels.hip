@@ -1041,6 +1041,20 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             while (e < KY && s_yacc[e] == bits) ++e;
             ylat[d] = ey[d].lat; yk32[d] = (ey[d].cost << s_lb) | (d * s_lsT[ty]); yrun[d] = e;
         }
+        if (pl.bounds) {
+            // for the bounds: the smallest key and the lowest latency from each digit to the end of its run
+            uint32_t* yrk = yrun + 2 * ydigit_words(pl.k_max);
+            uint32_t* yrl = yrk + ydigit_words(pl.k_max);
+            for (uint32_t d = tid; d < KY; d += blockDim.x) {
+                const uint64_t bits = s_yacc[d];
+                uint32_t mk = 0xFFFFFFFFu, ml = 0xFFFFFFFFu;
+                for (uint32_t x = d; x < KY && s_yacc[x] == bits; ++x) {
+                    mk = umin(mk, (ey[x].cost << s_lb) | (x * s_lsT[ty]));
+                    ml = umin(ml, ey[x].lat);
+                }
+                yrk[d] = mk; yrl[d] = ml;
+            }
+        }
         if (s_nin >= 3) {
             // position 2: per digit the end of its run of one variant
             uint32_t* zrun = yrun + ydigit_words(pl.k_max);
@@ -1134,6 +1148,8 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     const uint32_t JSV_CONST* yk32;    // local keys,
     const uint32_t JSV_CONST* yrun;    // ends of their runs of equal accuracy
     const uint32_t JSV_CONST* zrun;    // position 2's digits: ends of their runs of one variant
+    const uint32_t JSV_CONST* yrk;     // position 1's digits: smallest local key and
+    const uint32_t JSV_CONST* yrl;     // lowest latency from the digit to the end of its run (with bounds only)
     const QuadC JSV_CONST* pairs;      // pair stream: per digit of position 1, position 0's records with that digit's key added
     uint32_t pair_nq;                  // records per digit in it; 0: none
 };
@@ -2105,6 +2121,22 @@ __device__ __forceinline__ void z_batch_pairs(const LaneState& s, const Uniforms
     uint32_t y = 0;
     while (y < KY) {
         const uint32_t yre = U.yrun[y];
+        if constexpr (BOUNDS) {
+            // The run as a whole first: with its cheapest digit and its fastest one, can any lane of any
+            // slot stay within the cost bound and leave position 0 a candidate?  Mostly none can, and
+            // the run is left out before its masks are made and its digits are tested one by one.
+            const uint32_t rk = U.yrk[y], rl = U.yrl[y];
+            uint64_t some = 0;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const uint32_t most = E01 ? umin(thr0[g], __builtin_elementwise_sub_sat(room1[g], rl)) : thr0[g];
+                const uint32_t fixed = s.cost_out + ((k32z[g] + rk) >> U.lb);
+                bool can = (most >= U.min_x_lat) & (fixed + U.min_x_cost <= U.bound);
+                if constexpr (!E01) can = can & (rl <= room1[g]);
+                some |= alive[g] & __builtin_amdgcn_ballot_w64(can);
+            }
+            if (some == 0) { y = yre; continue; }
+        }
         // position 1 fixed to this run's accuracy (fix_position<1>), then Eq. 13 per variant of position 0
         const double H = ty[y].acc * hin1;
         const double sacc = E01 ? sacc2 : sacc2 + H;
@@ -2364,6 +2396,8 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     U.yk32 = U.ylat + ydigit_words(k_max);
     U.yrun = U.yk32 + ydigit_words(k_max);
     U.zrun = U.yrun + ydigit_words(k_max);
+    U.yrk = U.zrun + ydigit_words(k_max);
+    U.yrl = U.yrk + ydigit_words(k_max);
     U.pairs = pairs; U.pair_nq = in->pair_nq;
     st.cost_out = (uint32_t)(st.key >> in->idx_bits);
     // Cost as a bound: `bound` is S_avail (Eq. 8) or, in the cost modes, the cost of a candidate
