@@ -1877,6 +1877,17 @@ __device__ __forceinline__ void y_batches(const Uniforms& U, uint32_t smax, uint
     // the lanes that still meet the latency SLO.
     constexpr uint32_t e01 = E01 ? 1u : 0u;
     constexpr uint32_t src1 = E01 ? 0u : 1u;
+    if constexpr (BOUNDS) {
+        // The digits from d to the end of their run as a whole first: with the cheapest and the fastest
+        // of them, can any lane stay within the cost bound and leave position 0 a candidate?
+        const uint32_t rk = U.yrk[d], rl = U.yrl[d];
+        const uint32_t most = E01 ? umin(thr0, __builtin_elementwise_sub_sat(room1, rl)) : thr0;
+        const uint32_t fixed = cost_out + ((k32 + rk) >> U.lb);
+        const uint32_t within = MODE == MODE_OBJ ? umin(clim_abs, U.bound) : U.bound;
+        bool can = (smax <= U.sloq) & (most >= U.min_x_lat) & (fixed + U.min_x_cost <= within);
+        if constexpr (!E01) can = can & (rl <= room1);
+        if (__builtin_amdgcn_ballot_w64(can) == 0) return;
+    }
     uint32_t best_rel = 0xFFFFFFFFu;        // cost modes: the run's minimum of position 1's key plus position 0's
     for (; d < re; d += 4) {
         // four digits at a time, two 16-byte scalar loads
