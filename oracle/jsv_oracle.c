@@ -41,9 +41,10 @@
  * Pins (tests/test_oracle_*.py): a hand-worked two-task chain, an independent
  * brute force on tiny inputs, closed forms (one task; separable minimum;
  * multiple-choice knapsack on chains), monotonicity invariants.  The cap-
- * thinning step of the prune is a heuristic of this build with no outside
- * definition: it is checked against a second, differently written
- * implementation and against its stated properties only.
+ * thinning step of the prune is a heuristic of this library with no outside
+ * definition: it is checked against hand-worked lists, a second, differently
+ * written implementation and its stated properties only ("parity unpinned"
+ * beyond that).
  */
 #include <stdint.h>
 #include <stdlib.h>
