@@ -2323,12 +2323,12 @@ template <int NIN, bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instance JSV_CONST* in,
                                          const Entry JSV_CONST* tab, const uint32_t JSV_CONST* k32,
                                          const Quad JSV_CONST* quads, const QuadC JSV_CONST* pairs, const Entry* s_tab, uint32_t k_max, bool mix,
-                                         uint64_t o, bool live, uint32_t chunk_id, uint32_t bound, double obj_seen, Best& best, uint64_t& visited)
+                                         uint64_t group, uint32_t chunk_id, uint32_t bound, double obj_seen, Best& best, uint64_t& visited)
 {
 #pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
-    // o: the lane's combination of the positions >= NIN as a mixed-radix number (position NIN the
-    // fastest digit); live: whether the lane holds one at all
     const uint32_t T = g->T;
+    uint64_t o = group * TILE_LANES + threadIdx.x;
+    const bool live = o < in->s_out;
     if (!live) o = 0;
 
     // digits of the outer positions, position NIN fastest
@@ -2461,34 +2461,6 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     }
 }
 
-// With bounds: does the combination o of the outer positions (n_in and up), together with the
-// cheapest entry of every in-lane position, stay within the cost bound?  Digits and keys only:
-// no latency, no accuracy (what run_tile's set-up gathers and recurses over).
-__device__ __forceinline__ bool outer_cost_within(const Graph JSV_CONST* g, const Instance JSV_CONST* in, const Entry* s_tab,
-                                                  uint32_t k_max, uint64_t o, uint32_t bound)
-{
-    const uint32_t T = g->T;
-    uint64_t key = 0;
-    if (in->s_out <= 0xFFFFFFFFull) {
-        uint32_t o32 = (uint32_t)o;
-        for (uint32_t p = in->n_in; p < T; ++p) {
-            const uint32_t t = g->task_at[p], K = in->K[t];
-            key += s_tab[t * k_max + o32 % K].key;
-            o32 /= K;
-        }
-    } else {
-        for (uint32_t p = in->n_in; p < T; ++p) {
-            const uint32_t t = g->task_at[p], K = in->K[t];
-            key += s_tab[t * k_max + (uint32_t)(o % K)].key;
-            o /= K;
-        }
-    }
-    return (key >> in->idx_bits) + in->min_in_cost <= bound;
-}
-
-// Combinations of outer positions that a wave has found within the cost bound and not yet searched.
-constexpr uint32_t QUEUE_SLOTS = 128;     // per wave: up to 63 left over plus the 64 of one more tile
-
 // A block's result for one instance: its lanes' best reduced over the block.
 template <bool OBJ>
 __device__ __forceinline__ void flush_block(const Plan& pl, uint32_t inst, const Best& best, uint64_t* s_key, double* s_obj)
@@ -2525,7 +2497,6 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     __shared__ uint64_t s_red[4];
     __shared__ double s_red_obj[4];
     __shared__ unsigned long long s_tile;
-    __shared__ uint64_t s_queue[BOUNDS ? 4 * QUEUE_SLOTS : 1];
 
     const Instance JSV_CONST* insts = as_uniform((const Instance*)pl.inst);
     const Graph JSV_CONST* graphs = as_uniform(pl.graphs);
@@ -2551,176 +2522,86 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     uint32_t round = 0;
     uint64_t tile = (uint64_t)blockIdx.x * own;
     uint64_t tile_end = rounds != 0 ? tile + own : tile;
-    // With bounds, a wave does not search a tile's 64 combinations of the outer positions as they
-    // come: most of them cost too much whatever the in-lane positions take, and the few that do
-    // not would keep the whole wave going through the loops.  It first tests the combinations
-    // for their cost alone and queues those within the bound (s_queue, per wave); whenever 64 are
-    // queued they are searched together, every lane with one of them, and what is left when the
-    // block moves to another instance, or runs out of tiles, is searched before it does.  Only
-    // where a tile covers the whole of the chunked loop (one chunk): a queued combination then
-    // stands for the same candidates whichever tile it came from.
-    constexpr uint32_t NOT_AN_INSTANCE = 0xFFFFFFFFu;
-    const uint32_t lane = threadIdx.x & 63u;
-    volatile uint64_t* queue = s_queue + (BOUNDS ? (threadIdx.x >> 6) * QUEUE_SLOTS : 0u);
-    uint32_t queued = 0;            // wave-uniform
-    bool first = true, again = false, done = false;
-    for (;;) {
-        // the next tile, unless the one at hand has not been dealt with yet (block-uniform)
-        if (!done && !again) {
-            if (!first) ++tile;
-            first = false;
-            if (tile >= tile_end) {
-                ++round;
-                if (round < rounds) {
-                    tile = ((uint64_t)round * gridDim.x + blockIdx.x) * own;
-                    tile_end = tile + own;
-                } else if (batch == 0) {
-                    done = true;                              // everything was shared out by index
-                } else {
-                    __syncthreads();                          // everyone has read the last ticket
-                    if (threadIdx.x == 0) s_tile = atomicAdd(&pl.summary->next_tile, (unsigned long long)batch);
-                    __syncthreads();
-                    const unsigned long long ticket = s_tile;
-                    tile = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ticket >> 32)) << 32) |
-                           (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ticket);
-                    tile_end = tile + batch;
-                }
-            }
-            if (!done && tile >= total) done = true;
-            if (!done && tile >= scan_end) {
-                // the instance that holds this tile: the last one that begins at or before it
-                uint32_t lo = 0, hi = pl.n_inst;
-                while (hi - lo > 1) {
-                    const uint32_t mid = (lo + hi) >> 1;
-                    if (as_uniform(begins)[mid] <= tile) lo = mid; else hi = mid;
-                }
-                scan = lo;
-                scan_end = insts[scan].tile_begin + insts[scan].tiles;
+    for (;; ++tile) {
+        if (tile >= tile_end) {
+            ++round;
+            if (round < rounds) {
+                tile = ((uint64_t)round * gridDim.x + blockIdx.x) * own;
+                tile_end = tile + own;
+            } else {
+                if (batch == 0) break;                    // everything was shared out by index
+                __syncthreads();                          // everyone has read the last ticket
+                if (threadIdx.x == 0) s_tile = atomicAdd(&pl.summary->next_tile, (unsigned long long)batch);
+                __syncthreads();
+                const unsigned long long ticket = s_tile;
+                tile = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ticket >> 32)) << 32) |
+                       (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ticket);
+                tile_end = tile + batch;
             }
         }
-        again = false;
-        if (done && cur == NOT_AN_INSTANCE) break;            // (a block that never had a tile)
-        const uint32_t want = done ? NOT_AN_INSTANCE : scan;
-        // what this wave searches in this pass, if anything
-        bool search = false, live = false;
-        uint64_t o = 0;
-        uint32_t chunk_id = 0;
-        if (want != cur) {
-            if (BOUNDS && queued != 0) {
-                // leaving the instance: first what this wave still has queued for it (the other waves
-                // wait at the barrier of the flush below)
-                live = lane < queued;
-                o = live ? queue[lane] : 0;
-                queued = 0;
-                search = true;
-                again = true;
-            } else {
-                if (cur != NOT_AN_INSTANCE) flush_block<OBJ>(pl, cur, best, s_red, s_red_obj);
-                if (done) { cur = NOT_AN_INSTANCE; break; }
-                __syncthreads();
-                const Entry* src = pl.entries + (size_t)scan * tk;
-                const uint4* s4 = (const uint4*)src;
-                uint4* d4 = (uint4*)s_tab;
-                for (uint32_t k = threadIdx.x; k < tk * 2; k += blockDim.x) d4[k] = s4[k];
-                __syncthreads();
-                cur = scan;
-                best.key = NO_KEY; best.obj = -__builtin_inf();
-                if constexpr (SHARE)
-                    bound_seen = (uint32_t)__builtin_amdgcn_readfirstlane(
-                        (int)__hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-                if constexpr (MODE == MODE_OBJ) {
-                    const unsigned long long ob = __hip_atomic_load(pl.best_obj + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    obj_seen = from_ordered_bits(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ob >> 32)) << 32) |
-                                                 (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ob));
-                }
-                again = true;                                 // now the tile itself
-                continue;
+        if (tile >= total) break;
+        if (tile >= scan_end) {
+            // the instance that holds this tile: the last one that begins at or before it
+            uint32_t lo = 0, hi = pl.n_inst;
+            while (hi - lo > 1) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (as_uniform(begins)[mid] <= tile) lo = mid; else hi = mid;
+            }
+            scan = lo;
+            scan_end = insts[scan].tile_begin + insts[scan].tiles;
+        }
+        if (scan != cur) {
+            if (cur != 0xFFFFFFFFu) {
+                flush_block<OBJ>(pl, cur, best, s_red, s_red_obj);
+            }
+            __syncthreads();
+            const Entry* src = pl.entries + (size_t)scan * tk;
+            const uint4* s4 = (const uint4*)src;
+            uint4* d4 = (uint4*)s_tab;
+            for (uint32_t k = threadIdx.x; k < tk * 2; k += blockDim.x) d4[k] = s4[k];
+            __syncthreads();
+            cur = scan;
+            best.key = NO_KEY; best.obj = -__builtin_inf();
+            if constexpr (SHARE)
+                bound_seen = (uint32_t)__builtin_amdgcn_readfirstlane(
+                    (int)__hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            if constexpr (MODE == MODE_OBJ) {
+                const unsigned long long ob = __hip_atomic_load(pl.best_obj + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                obj_seen = from_ordered_bits(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(ob >> 32)) << 32) |
+                                             (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)ob));
             }
         }
         const Instance JSV_CONST* in = insts + cur;
         const Graph JSV_CONST* g = graphs + in->problem;
-        // The wave works with the instance's cost bound as it knows it; a stale (higher) value only
-        // excludes less.  What other blocks have made of it meanwhile is fetched now and looked at
-        // after the pass, so that nobody waits for the load.
+        const Entry JSV_CONST* tab = as_uniform((const Entry*)pl.entries) + (size_t)cur * tk;
+        const uint32_t JSV_CONST* k32 = as_uniform((const uint32_t*)pl.k32) + (size_t)cur * tk;
+        const Quad JSV_CONST* quads = as_uniform((const Quad*)pl.quads) + (size_t)cur * quad_stride(pl.k_max);
+        const QuadC JSV_CONST* pairs = as_uniform((const QuadC*)pl.pairs) + (size_t)cur * (pl.pair_cap + 1);
+        const uint64_t local = tile - in->tile_begin;
+        const uint32_t n_chunks = in->n_chunks;
+        const uint32_t chunk_id = (uint32_t)(local % n_chunks);
+        const uint64_t group = local / n_chunks;
+        // The tile works with the instance's cost bound as this wave knows it; a stale (higher)
+        // value only excludes less.  What other blocks have made of it meanwhile is fetched now and
+        // looked at after the tile, so that nobody waits for the load.
+        const uint32_t bound = bound_seen;
         uint32_t fresh = 0xFFFFFFFFu;
         if constexpr (SHARE) fresh = __hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         unsigned long long fresh_obj = 0;
         if constexpr (MODE == MODE_OBJ) fresh_obj = __hip_atomic_load(pl.best_obj + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (!search) {
-            const uint64_t local = tile - in->tile_begin;
-            const uint32_t n_chunks = in->n_chunks;
-            chunk_id = (uint32_t)(local % n_chunks);
-            const uint64_t group = local / n_chunks;
-            o = group * TILE_LANES + threadIdx.x;
-            live = o < in->s_out;
-            search = true;
-            if (BOUNDS && n_chunks == 1) {
-                const bool within = live && outer_cost_within(g, in, s_tab, pl.k_max, live ? o : 0, bound_seen);
-                const uint64_t takers = __builtin_amdgcn_ballot_w64(within);
-                if (within) queue[queued + (uint32_t)__builtin_popcountll(takers & ((1ull << lane) - 1ull))] = o;
-                queued += (uint32_t)__builtin_popcountll(takers);         // at most 63 + 64
-                __builtin_amdgcn_wave_barrier();
-                search = queued >= 64u;
-                if (search) {
-                    queued -= 64u;
-                    o = queue[queued + lane];
-                    live = true;
-                    __builtin_amdgcn_wave_barrier();
-                }
+        const uint64_t key_before = best.key;
+        const double obj_before = best.obj;
+        if (in->use32) {
+            switch (in->n_in) {
+            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
+            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
+            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
             }
-        }
-        if (search) {
-            const Entry JSV_CONST* tab = as_uniform((const Entry*)pl.entries) + (size_t)cur * tk;
-            const uint32_t JSV_CONST* k32 = as_uniform((const uint32_t*)pl.k32) + (size_t)cur * tk;
-            const Quad JSV_CONST* quads = as_uniform((const Quad*)pl.quads) + (size_t)cur * quad_stride(pl.k_max);
-            const QuadC JSV_CONST* pairs = as_uniform((const QuadC*)pl.pairs) + (size_t)cur * (pl.pair_cap + 1);
-            const uint32_t bound = bound_seen;
-            const uint64_t key_before = best.key;
-            const double obj_before = best.obj;
-            if (in->use32) {
-                switch (in->n_in) {
-                case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, o, live, chunk_id, bound, obj_seen, best, visited); break;
-                case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, o, live, chunk_id, bound, obj_seen, best, visited); break;
-                default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, o, live, chunk_id, bound, obj_seen, best, visited); break;
-                }
-            } else {
-                switch (in->n_in) {
-                case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, o, live, chunk_id, bound, obj_seen, best, visited); break;
-                case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, o, live, chunk_id, bound, obj_seen, best, visited); break;
-                default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, o, live, chunk_id, bound, obj_seen, best, visited); break;
-                }
-            }
-            if constexpr (SHARE) {
-                // Did a lane of this wave find something better in this pass?  Then the bound may drop
-                // for every block working on the instance.
-                const bool improved = __builtin_amdgcn_ballot_w64((best.key != key_before) | (best.obj != obj_before)) != 0;
-                if (improved) {
-                    uint32_t wc = 0xFFFFFFFFu;
-                    if constexpr (!is_obj(MODE)) {
-                        // cost modes: nothing costlier than a candidate that meets both SLOs can be the answer
-                        const uint32_t c = best.key == NO_KEY ? 0xFFFFFFFFu : (uint32_t)(best.key >> in->idx_bits);
-                        wc = (uint32_t)wave_min((uint64_t)c);
-                    } else {
-                        // Eq. 14: A_obj <= 1, so a candidate of cost c scores at most alpha - beta*c.  With an
-                        // objective o already reached, nothing costlier than (alpha - o)/beta can match it;
-                        // one unit of slack keeps the test clear of rounding and of equal objectives.
-                        const Best wb = wave_best(best);
-                        if constexpr (MODE == MODE_OBJ) {
-                            if (wb.key != NO_KEY && wb.obj > obj_seen) {
-                                obj_seen = wb.obj;
-                                if ((threadIdx.x & 63u) == 0) atomicMax(pl.best_obj + cur, ordered_bits(wb.obj));
-                            }
-                        }
-                        if (wb.key != NO_KEY && in->beta > 1e-9 * (in->alpha + 1.0)) {     // else rounding could reach a unit of cost
-                            const double lim = (in->alpha - wb.obj) / in->beta;
-                            if (lim >= 0.0 && lim < 2147483000.0) wc = (uint32_t)lim + 1u;
-                        }
-                    }
-                    if (wc < bound_seen) {
-                        bound_seen = wc;
-                        if ((threadIdx.x & 63u) == 0) atomicMin(pl.bound + cur, wc);
-                    }
-                }
+        } else {
+            switch (in->n_in) {
+            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
+            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
+            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
             }
         }
         if constexpr (SHARE) {
@@ -2730,6 +2611,36 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
                 const double oo = from_ordered_bits(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(fresh_obj >> 32)) << 32) |
                                                     (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)fresh_obj));
                 obj_seen = oo > obj_seen ? oo : obj_seen;
+            }
+            // Did a lane of this wave find something better in this tile?  Then the bound may drop
+            // for every block working on the instance.
+            const bool improved = __builtin_amdgcn_ballot_w64((best.key != key_before) | (best.obj != obj_before)) != 0;
+            if (improved) {
+                uint32_t wc = 0xFFFFFFFFu;
+                if constexpr (!is_obj(MODE)) {
+                    // cost modes: nothing costlier than a candidate that meets both SLOs can be the answer
+                    const uint32_t c = best.key == NO_KEY ? 0xFFFFFFFFu : (uint32_t)(best.key >> in->idx_bits);
+                    wc = (uint32_t)wave_min((uint64_t)c);
+                } else {
+                    // Eq. 14: A_obj <= 1, so a candidate of cost c scores at most alpha - beta*c.  With an
+                    // objective o already reached, nothing costlier than (alpha - o)/beta can match it;
+                    // one unit of slack keeps the test clear of rounding and of equal objectives.
+                    const Best wb = wave_best(best);
+                    if constexpr (MODE == MODE_OBJ) {
+                        if (wb.key != NO_KEY && wb.obj > obj_seen) {
+                            obj_seen = wb.obj;
+                            if ((threadIdx.x & 63u) == 0) atomicMax(pl.best_obj + cur, ordered_bits(wb.obj));
+                        }
+                    }
+                    if (wb.key != NO_KEY && in->beta > 1e-9 * (in->alpha + 1.0)) {     // else rounding could reach a unit of cost
+                        const double lim = (in->alpha - wb.obj) / in->beta;
+                        if (lim >= 0.0 && lim < 2147483000.0) wc = (uint32_t)lim + 1u;
+                    }
+                }
+                if (wc < bound_seen) {
+                    bound_seen = wc;
+                    if ((threadIdx.x & 63u) == 0) atomicMin(pl.bound + cur, wc);
+                }
             }
         }
     }
