@@ -114,3 +114,25 @@ def test_chain4_exhaustive(ctx):
     w = W.chain4()
     res, summ = check_search(ctx, w.problems[0], w.searches[0])
     assert res[0].evaluated == 140 ** 4
+
+
+def test_records_as_the_library_wrote_them(ctx):
+    """raw=True hands back the C records without turning them into Python objects (what bench.py
+    times); results() of them is what the plain call returns, for one system and for a batch."""
+    w = W.diamond5(seed=0)
+    pb, se = w.problems[0], w.searches[0]
+    ctx.load(pb)
+    want, wsum = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap)
+    rec, rsum = ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, se.prune_cap, raw=True)
+    assert rec.shape == (len(se.demand_mrps),) and ctx.results(rec) == want
+    assert (rsum.best_level, rsum.max_demand_mrps) == (wsum.best_level, wsum.max_demand_mrps)
+    assert [int(c) for c in rec["cost_units"]] == [r.cost if r.feasible else 2**31 - 1 for r in want]
+    b = W.dagbatch(seed=0)
+    j = jsv.Jsv(device=0)
+    try:
+        j.load_batch(b.problems[:24], b.searches[:24])
+        got, _ = j.search_loaded_batch()
+        rec, _ = j.search_loaded_batch(raw=True)
+        assert j.results(rec, batch=True) == got
+    finally:
+        j.close()
