@@ -162,6 +162,24 @@ struct Graph {
 // Variants of the innermost position whose accuracy masks a wave keeps in scalar registers.
 constexpr int MAX_XVAR = 8;
 
+// x / k and x % k for 32-bit x by the reciprocal m = floor(2^32 / k) (k = 1: 2^32 - 1): the
+// product's high word is the quotient or one less (x * m / 2^32 lies in (x/k - 1, x/k]), so one
+// conditional step finishes it.  The remainder is always below k.
+#if defined(__HIPCC__) || defined(__HIP__)
+#define JSV_HD __host__ __device__
+#else
+#define JSV_HD
+#endif
+JSV_HD inline uint32_t div_by_magic(uint32_t x, uint32_t k, uint32_t m, uint32_t* rem)
+{
+    uint32_t q = (uint32_t)(((uint64_t)x * m) >> 32);
+    uint32_t r = x - q * k;
+    if (r >= k) { r -= k; ++q; }
+    *rem = r;
+    return q;
+}
+JSV_HD inline uint32_t magic_of(uint32_t k) { return k <= 1u ? 0xFFFFFFFFu : (uint32_t)((1ull << 32) / k); }
+
 struct Instance {
     // inputs (host)
     uint32_t problem;
@@ -214,6 +232,9 @@ struct Instance {
     uint32_t pair_nq;         // records per digit of position 1 in the pair stream; 0: no pair stream
     double   xacc[MAX_XVAR];
     uint32_t xqe[MAX_XVAR];   // byte offset in the QuadC copy at which each of them ends (past nvx: the stream's end)
+    // floor(2^32 / K[t]) per task id (K = 1: 2^32 - 1), so that the lanes split their combination
+    // into digits by a multiplication and one correction instead of a division (plan kernel)
+    uint32_t kmagic[MAXT];
 };
 
 // Result record as written by the finalize kernel; same layout as jsv_result.

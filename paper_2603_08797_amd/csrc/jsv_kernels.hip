@@ -785,6 +785,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     __shared__ uint32_t s_task_at[MAXT], s_capacity, s_PB;
     if (tid < MAXT) {
         s_maxcost[tid] = 0; s_mincost[tid] = 0xFFFFFFFFu; s_K[tid] = tid < T ? in->K[tid] : 0; s_lsT[tid] = 0xFFFFFFFFu;
+        in->kmagic[tid] = magic_of(s_K[tid]);
         s_task_at[tid] = g->task_at[tid];
     }
     if (tid == 32) s_capacity = g->capacity;
@@ -2337,7 +2338,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
         uint32_t o32 = (uint32_t)o;
 #pragma unroll
         for (int p = NIN; p < MAXT; ++p)
-            if (p < (int)T) { const uint32_t K = in->K[g->task_at[p]]; dig[p] = o32 % K; o32 /= K; }
+            if (p < (int)T) { const uint32_t t = g->task_at[p]; o32 = div_by_magic(o32, in->K[t], in->kmagic[t], &dig[p]); }
     } else {
 #pragma unroll
         for (int p = NIN; p < MAXT; ++p)
@@ -2448,9 +2449,8 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
         for (int a = 0; a < NIN; ++a) {
             const uint32_t p = in->ord[a];
             const uint32_t t = g->task_at[p];
-            const uint32_t K = in->K[t];
-            const uint32_t d = r % K;
-            r /= K;
+            uint32_t d;
+            r = div_by_magic(r, in->K[t], in->kmagic[t], &d);
             k += s_tab[t * k_max + d].key;
         }
         if constexpr (is_obj(MODE)) {
