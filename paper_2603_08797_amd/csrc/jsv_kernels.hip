@@ -2441,8 +2441,14 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     if (BOUNDS || U.mix) visited += tb.visits;
 
     if constexpr (W32) {
-        // the lane's 32-bit winner of this tile -> its full (cost, index) key
+        // the lane's 32-bit winner of this tile -> its full (cost, index) key; only where some lane's
+        // winner can replace what the lane holds (as cheap, or with as good an objective: the index
+        // decides between equals), which after the first tiles is rare
         const bool hit = tb.k32 != 0xFFFFFFFFu;
+        bool may;
+        if constexpr (is_obj(MODE)) may = hit && tb.obj >= best.obj;
+        else may = hit && (uint64_t)st.cost_out + (tb.k32 >> in->lb) <= (best.key >> in->idx_bits);
+        if (__builtin_amdgcn_ballot_w64(may) == 0) return;
         uint32_t r = hit ? (tb.k32 & ((1u << in->lb) - 1u)) : 0u;
         uint64_t k = st.key;
 #pragma unroll
