@@ -446,3 +446,53 @@ def test_pair_stream_with_capacity_and_thinned_lists(ctx):
     finally:
         ctx.set_geometry(0, 0)
         ctx.set_bounds(True)
+
+
+def test_pair_stream_with_full_records_in_both_objective_modes(ctx):
+    """Six tasks from the benchmark's table generator (5 variants of 48 choices, cap 20): every list
+    thins to four survivors per variant, so every record of the innermost stream is full and every
+    run of the other positions has four digits - the shape of the 8-task sweep, small enough for
+    the oracle to go through whole levels.  Cost mode and Eq. 14, with and without bounds, under
+    geometries that give three in-lane positions with tiles of four and more digits."""
+    sizes, batches = list(range(1, 9)), [1, 2, 4, 8, 16, 32]
+    lat, thr, acc = W._tables(W.SplitMix64(905, 1), W.SplitMix64(905, 2), 6, 5, sizes, 8, batches)
+    edges = [(0, 1), (0, 2), (0, 3), (1, 4), (2, 4), (3, 4), (4, 5)]
+    pb = W._problem(6, 5, sizes, 8, batches, lat, thr, acc, edges, [1000, 1000, 900, 1100, 1000, 1000], 64)
+    dem = [30000, 80000, 150000, 600000]
+    slo_l, slo_a, cap = 220000, 0.5, 20
+    o = oracle.Oracle.from_problem(pb)
+    assert o.accuracy_margin(slo_a) > 1e-9
+    for D in dem:
+        K, space, thinned = o.space(D, slo_l, cap)
+        assert list(K) == [20] * 6 and thinned, K        # four per variant everywhere
+    ref_cost, _, _ = o.search(dem, slo_l, slo_a, cap, threads=16)
+    o.set_objective(1, 1.0, 0.035)
+    ref_obj, _, _ = o.search(dem, slo_l, slo_a, cap, threads=16)
+    assert sum(r.feasible for r in ref_cost) >= 2 and not all(r.feasible for r in ref_cost)
+    try:
+        for blocks, lanes in ((0, 5), (1, 3), (0, 0)):
+            ctx.set_geometry(blocks, lanes)
+            for b in (False, True):
+                ctx.set_bounds(b)
+                ctx.set_objective(0)
+                ctx.load(pb)
+                got, _ = ctx.search(dem, slo_l, slo_a, cap)
+                for l, (x, y) in enumerate(zip(got, ref_cost)):
+                    same(x, y, f"cost mode, geometry {blocks},{lanes}, bounds {b}, level {l}")
+                ctx.set_objective(1, 1.0, 0.035)
+                got, _ = ctx.search(dem, slo_l, slo_a, cap)
+                for l, (x, y) in enumerate(zip(got, ref_obj)):
+                    where = f"objective mode, geometry {blocks},{lanes}, bounds {b}, level {l}"
+                    assert x.feasible == y.feasible, where
+                    if not y.feasible:
+                        continue
+                    assert abs(x.objective - y.objective) <= 1e-12 * max(1.0, abs(y.objective)), where
+                    if x.index == y.index:
+                        same(x, y, where)
+                    else:       # only candidates of different variants within rounding of each other may swap
+                        assert abs(x.objective - y.objective) <= 1e-9, where
+                        assert [c // 48 for c in x.choice] != [c // 48 for c in y.choice], where
+    finally:
+        ctx.set_objective(0)
+        ctx.set_geometry(0, 0)
+        ctx.set_bounds(True)
