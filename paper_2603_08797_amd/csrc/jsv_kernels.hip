@@ -343,6 +343,9 @@ __device__ __forceinline__ double mix_accuracy(uint64_t w1i, double a1, uint64_t
 }
 
 constexpr uint32_t MIX_MAX_REPLICAS = 65535u;
+// Threads per block of mix_kernel: a task's pairs of tuples and their splits are many (10^5 to
+// 10^6 options) and the blocks few (levels x tasks), so a block brings as many threads as it can.
+constexpr int MIX_THREADS = 1024;
 
 // Per-tuple facts of one task, in LDS.
 struct MixTuples {
@@ -402,7 +405,7 @@ __device__ __forceinline__ void mix_visit(const MixTuples& m, uint32_t C, uint64
 // the exact dominance test iff no other non-empty cell with cost <= and class <= has an
 // accuracy >=, read off a two-dimensional prefix maximum.  More than cap survivors are
 // thinned over a grid of latency bands and accuracy ranks (step (c) below).
-__global__ void __launch_bounds__(256) mix_kernel(Plan pl)
+__global__ void __launch_bounds__(MIX_THREADS) mix_kernel(Plan pl)
 {
     const uint32_t i = blockIdx.x / pl.t_max;
     const uint32_t t = blockIdx.x % pl.t_max;
@@ -2855,7 +2858,7 @@ size_t enumerate_lds_bytes(uint32_t t_max, uint32_t k_max) { return (size_t)t_ma
 hipError_t launch_prune_plan_scan(const Plan& pl, hipStream_t stream)
 {
     if (pl.mix)
-        hipLaunchKernelGGL(mix_kernel, dim3(pl.n_inst * pl.t_max), dim3(256), mix_lds_bytes(pl.c_max), stream, pl);
+        hipLaunchKernelGGL(mix_kernel, dim3(pl.n_inst * pl.t_max), dim3(MIX_THREADS), mix_lds_bytes(pl.c_max), stream, pl);
     else
         hipLaunchKernelGGL(prune_kernel, dim3(pl.n_inst * pl.t_max), dim3(256), prune_lds_bytes(pl.c_max), stream, pl);
     hipLaunchKernelGGL(plan_kernel, dim3(pl.n_inst), dim3(256), 0, stream, pl);
