@@ -37,6 +37,17 @@ def test_a_fresh_plan_has_every_mode_switch_off(tmp_path):
     assert out.returncode == 0 and "plan defaults ok" in out.stdout, out.stdout + out.stderr
 
 
+def test_reciprocal_division_of_the_tile_set_up(tmp_path):
+    """jsv::div_by_magic (how a lane splits its combination into digits) equals / and % for every
+    list length, on boundary and random dividends."""
+    import subprocess
+    exe = str(tmp_path / "div_by_magic")
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-Wall", os.path.join(ROOT, "tests", "c_abi", "div_by_magic.cpp"),
+                           "-o", exe])
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0 and "div by magic ok" in out.stdout, out.stdout + out.stderr
+
+
 @pytest.fixture()
 def ctx():
     j = jsv.Jsv(use_torch=False)
