@@ -2173,12 +2173,22 @@ __device__ __forceinline__ void z_batch_pairs(const LaneState& s, const Uniforms
             const uint32_t lat = U.ylat[dy];
             uint32_t thr[4] = {0, 0, 0, 0};
             uint64_t go[4] = {0, 0, 0, 0};
+            // as in y_batches: position 1 either feeds position 0's threshold or is a source
+            if constexpr (E01) {
+                if (U.m12 == 0) {
+                    // position 2 does not feed position 1: all slots leave position 1 the same room
+                    const uint32_t left = __builtin_elementwise_sub_sat(room1[0], lat);
+#pragma unroll
+                    for (int g = 0; g < G; ++g) thr[g] = umin(thr0[g], left);
+                } else {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) thr[g] = umin(thr0[g], __builtin_elementwise_sub_sat(room1[g], lat));
+                }
+            }
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                // as in y_batches: position 1 either feeds position 0's threshold or is a source
-                thr[g] = thr0[g]; go[g] = alive[g];
-                if constexpr (E01) thr[g] = umin(thr0[g], __builtin_elementwise_sub_sat(room1[g], lat));
-                else go[g] = alive[g] & __builtin_amdgcn_ballot_w64(lat <= room1[g]);
+                go[g] = alive[g];
+                if constexpr (!E01) { thr[g] = thr0[g]; go[g] = alive[g] & __builtin_amdgcn_ballot_w64(lat <= room1[g]); }
                 if constexpr (BOUNDS) {
                     const uint32_t fixed = s.cost_out + ((k32z[g] + U.yk32[dy]) >> U.lb);
                     const uint32_t within = MODE == MODE_OBJ ? umin(clim_abs, U.bound) : U.bound;
