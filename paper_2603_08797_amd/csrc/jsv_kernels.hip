@@ -2097,7 +2097,7 @@ __device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniform
 // One batch of G digits of position 2, starting at zb, against all digits of position 1 (the
 // slot count is a template parameter so that the minima keep their registers over the loops).
 // sacc2, hin1, hin0z: the accuracy state with position 2 fixed to the run's variant.
-template <int MODE, int G, bool BOUNDS, bool E01>
+template <int MODE, int G, bool BOUNDS, bool E01, bool SAME_ROOM = false>
 __device__ __forceinline__ void z_batch_pairs(const LaneState& s, const Uniforms& U, uint32_t zb, uint32_t nvx, uint32_t src2,
                                               double sacc2, double hin1, double hin0z, const uint32_t (&qe)[MAX_XVAR],
                                               uint32_t endb, uint32_t x_hi, uint64_t full, TileBest& tb)
@@ -2174,16 +2174,14 @@ __device__ __forceinline__ void z_batch_pairs(const LaneState& s, const Uniforms
             uint32_t thr[4] = {0, 0, 0, 0};
             uint64_t go[4] = {0, 0, 0, 0};
             // as in y_batches: position 1 either feeds position 0's threshold or is a source
-            if constexpr (E01) {
-                if (U.m12 == 0) {
-                    // position 2 does not feed position 1: all slots leave position 1 the same room
-                    const uint32_t left = __builtin_elementwise_sub_sat(room1[0], lat);
+            if constexpr (E01 && SAME_ROOM) {
+                // position 2 does not feed position 1: all slots leave position 1 the same room
+                const uint32_t left = __builtin_elementwise_sub_sat(room1[0], lat);
 #pragma unroll
-                    for (int g = 0; g < G; ++g) thr[g] = umin(thr0[g], left);
-                } else {
+                for (int g = 0; g < G; ++g) thr[g] = umin(thr0[g], left);
+            } else if constexpr (E01) {
 #pragma unroll
-                    for (int g = 0; g < G; ++g) thr[g] = umin(thr0[g], __builtin_elementwise_sub_sat(room1[g], lat));
-                }
+                for (int g = 0; g < G; ++g) thr[g] = umin(thr0[g], __builtin_elementwise_sub_sat(room1[g], lat));
             }
 #pragma unroll
             for (int g = 0; g < G; ++g) {
@@ -2262,7 +2260,11 @@ __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniform
         const double hin1 = __builtin_fma(U.w12, Hz, s.hin[1]);
         const double hin0z = __builtin_fma(U.w02, Hz, s.hin[0]);
         uint32_t zb = z;
-        for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
+        // full batches are compiled a second time for graphs in which position 2 does not feed position 1
+        if (E01 && U.m12 == 0)
+            for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01, true>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
+        else
+            for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
         switch (zre - zb) {
         case 3: z_batch_pairs<MODE, 3, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
         case 2: z_batch_pairs<MODE, 2, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
