@@ -1135,7 +1135,8 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     uint32_t min_x_lat; // lowest latency of position 0's entries: below it a lane has no candidate
     uint32_t min_x_cost; // cheapest entry of position 0
     uint32_t min_xy_cost; // cheapest entries of positions 0 and 1 together
-    uint32_t bound;     // total cost beyond which a candidate cannot be the answer (as read at the tile's start)
+    uint32_t bound;     // total cost beyond which a candidate cannot be the answer (as known when the tile's loops start)
+    uint32_t* bound_at; // where the instance's bound lives (with bounds: read and lowered while a tile runs)
     double   obj_seen;  // objective mode: an objective some wave has already reached for this instance (-inf: none known)
     double   slo_raw;   // SLO_a * A_max
     // objective mode (Eq. 14)
@@ -1411,6 +1412,7 @@ struct TileBest {
     uint32_t k32; double obj;
     uint32_t visits;    // wave-uniform: entries of position 0 this wave went through in the tile
     uint32_t klim;      // objective mode: local keys above it (fixed in-lane positions included) cannot matter
+    uint32_t bound;     // wave-uniform: the cost bound as the wave knows it when the tile ends
 };
 
 // Largest local key that can still matter for a lane whose positions outside the lane loops cost
@@ -2250,10 +2252,23 @@ __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniform
 #pragma unroll
     for (int v = 0; v < MAX_XVAR; ++v) qe[v] = U.xqe[v];
     const uint32_t endb = x_hi * (uint32_t)sizeof(QuadC);
+    // Cost mode with bounds: the bound moves while the tile runs.  Before each run of position 2 the
+    // wave takes in what the instance's bound has become (the load issued one run earlier, so nobody
+    // waits for it) and fetches it anew; after the run, a lane that has found a cheaper candidate than
+    // the wave knew of lowers the bound for its own next runs and for every block working on the instance.
+    // A stale value only excludes less; candidates as cheap as the bound stay in.
+    constexpr bool MOVING = BOUNDS && MODE == MODE_COST;
+    Uniforms V = U;
+    uint32_t fetched = V.bound;
     uint32_t z = lo;
     while (z < hi) {
         const uint32_t zrun_end = U.zrun[z];
         const uint32_t zre = zrun_end < hi ? zrun_end : hi;
+        if constexpr (MOVING) {
+            const uint32_t seen = (uint32_t)__builtin_amdgcn_readfirstlane((int)fetched);
+            V.bound = seen < V.bound ? seen : V.bound;
+            fetched = __hip_atomic_load(U.bound_at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         // accuracy state with position 2 fixed to this variant (fix_position<2>)
         const double Hz = tz[z].acc * s.hin[2];
         const double sacc2 = src2 != 0 ? s.sacc + Hz : s.sacc;
@@ -2262,17 +2277,27 @@ __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniform
         uint32_t zb = z;
         // full batches are compiled a second time for graphs in which position 2 does not feed position 1
         if (E01 && U.m12 == 0)
-            for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01, true>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
+            for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01, true>(s, V, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
         else
-            for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
+            for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01>(s, V, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
         switch (zre - zb) {
-        case 3: z_batch_pairs<MODE, 3, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
-        case 2: z_batch_pairs<MODE, 2, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
-        case 1: z_batch_pairs<MODE, 1, BOUNDS, E01>(s, U, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        case 3: z_batch_pairs<MODE, 3, BOUNDS, E01>(s, V, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        case 2: z_batch_pairs<MODE, 2, BOUNDS, E01>(s, V, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        case 1: z_batch_pairs<MODE, 1, BOUNDS, E01>(s, V, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
         default: break;
+        }
+        if constexpr (MOVING) {
+            // (the tile's best local key so far -> the total cost of that candidate)
+            const uint32_t c = tb.k32 != 0xFFFFFFFFu ? s.cost_out + (tb.k32 >> U.lb) : 0xFFFFFFFFu;
+            if (__builtin_amdgcn_ballot_w64(c < V.bound) != 0) {
+                const uint32_t wc = (uint32_t)wave_min((uint64_t)c);
+                V.bound = wc;
+                if ((threadIdx.x & 63u) == 0) atomicMin(U.bound_at, wc);
+            }
         }
         z = zre;
     }
+    if constexpr (MOVING) tb.bound = V.bound;
 }
 
 template <bool W32, int MODE, bool BOUNDS>
@@ -2339,7 +2364,8 @@ template <int NIN, bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instance JSV_CONST* in,
                                          const Entry JSV_CONST* tab, const uint32_t JSV_CONST* k32,
                                          const Quad JSV_CONST* quads, const QuadC JSV_CONST* pairs, const Entry* s_tab, uint32_t k_max, bool mix,
-                                         uint64_t group, uint32_t chunk_id, uint32_t bound, double obj_seen, Best& best, uint64_t& visited)
+                                         uint64_t group, uint32_t chunk_id, uint32_t& bound, uint32_t fresh, uint32_t* bound_at,
+                                         double obj_seen, Best& best, uint64_t& visited)
 {
 #pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
     const uint32_t T = g->T;
@@ -2412,7 +2438,14 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     U.min_x_lat = in->min_x_lat;
     U.min_x_cost = in->min_x_cost;
     U.min_xy_cost = in->min_xy_cost;
+    // (with bounds: what the instance's bound has become since the wave last looked - the load was
+    // issued before the tile's set-up, so it is there by now)
+    if constexpr (BOUNDS) {
+        const uint32_t f = (uint32_t)__builtin_amdgcn_readfirstlane((int)fresh);
+        bound = f < bound ? f : bound;
+    }
     U.bound = bound;
+    U.bound_at = bound_at;
     U.obj_seen = MODE == MODE_OBJ ? obj_seen : -__builtin_inf();
     U.slo_raw = in->slo_raw;
     U.idx_bits = in->idx_bits; U.lb = in->lb; U.capacity = g->capacity;
@@ -2447,13 +2480,14 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     // no key - a candidate must reach that objective to be noted, and ties are settled on the full
     // keys after the tile)
     tb.k32 = 0xFFFFFFFFu; tb.obj = (is_obj(MODE) && W32) ? best.obj : -__builtin_inf(); tb.visits = 0;
-    tb.klim = 0xFFFFFFFEu;
+    tb.klim = 0xFFFFFFFEu; tb.bound = U.bound;
     if constexpr (is_obj(MODE) && W32) tb.klim = key_limit(U, st.cost_out, best.obj, U.alpha);
     const uint64_t full = __builtin_amdgcn_read_exec();     // the loops below run convergent
     if constexpr (NIN == 3) loop_z<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
     else if constexpr (NIN == 2) loop_y<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
     else loop_x<W32, MODE, BOUNDS>(st, U, lo, hi, full, best, tb);
     if (BOUNDS || U.mix) visited += tb.visits;
+    bound = tb.bound;
 
     if constexpr (W32) {
         // the lane's 32-bit winner of this tile -> its full (cost, index) key; only where some lane's
@@ -2604,8 +2638,9 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const uint64_t group = local / n_chunks;
         // The tile works with the instance's cost bound as this wave knows it; a stale (higher)
         // value only excludes less.  What other blocks have made of it meanwhile is fetched now and
-        // looked at after the tile, so that nobody waits for the load.
-        const uint32_t bound = bound_seen;
+        // taken in after the tile's set-up (with bounds) and after the tile, so that nobody waits for
+        // the load.
+        uint32_t bound = bound_seen;
         uint32_t fresh = 0xFFFFFFFFu;
         if constexpr (SHARE) fresh = __hip_atomic_load(pl.bound + cur, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         unsigned long long fresh_obj = 0;
@@ -2614,20 +2649,21 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const double obj_before = best.obj;
         if (in->use32) {
             switch (in->n_in) {
-            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
-            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
-            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
+            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
+            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
+            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
             }
         } else {
             switch (in->n_in) {
-            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
-            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
-            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, obj_seen, best, visited); break;
+            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
+            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
+            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
             }
         }
         if constexpr (SHARE) {
             const uint32_t other = (uint32_t)__builtin_amdgcn_readfirstlane((int)fresh);
             bound_seen = other < bound_seen ? other : bound_seen;
+            bound_seen = bound < bound_seen ? bound : bound_seen;       // lowered while the tile ran
             if constexpr (MODE == MODE_OBJ) {
                 const double oo = from_ordered_bits(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(fresh_obj >> 32)) << 32) |
                                                     (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)fresh_obj));
