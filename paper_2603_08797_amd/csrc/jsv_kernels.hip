@@ -2632,10 +2632,10 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const uint32_t JSV_CONST* k32 = as_uniform((const uint32_t*)pl.k32) + (size_t)cur * tk;
         const Quad JSV_CONST* quads = as_uniform((const Quad*)pl.quads) + (size_t)cur * quad_stride(pl.k_max);
         const QuadC JSV_CONST* pairs = as_uniform((const QuadC*)pl.pairs) + (size_t)cur * (pl.pair_cap + 1);
-        const uint64_t local = tile - in->tile_begin;
+        const uint32_t local = (uint32_t)(tile - in->tile_begin);      // an instance has fewer than 2^31 tiles
         const uint32_t n_chunks = in->n_chunks;
-        const uint32_t chunk_id = (uint32_t)(local % n_chunks);
-        const uint64_t group = local / n_chunks;
+        uint32_t chunk_id = 0, group = local;
+        if (n_chunks != 1) { group = local / n_chunks; chunk_id = local - group * n_chunks; }
         // The tile works with the instance's cost bound as this wave knows it; a stale (higher)
         // value only excludes less.  What other blocks have made of it meanwhile is fetched now and
         // taken in after the tile's set-up (with bounds) and after the tile, so that nobody waits for
