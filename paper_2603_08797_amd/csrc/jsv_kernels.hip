@@ -1137,6 +1137,7 @@ struct Uniforms {       // wave-uniform facts about positions 0..2
     uint32_t min_xy_cost; // cheapest entries of positions 0 and 1 together
     uint32_t bound;     // total cost beyond which a candidate cannot be the answer (as known when the tile's loops start)
     uint32_t* bound_at; // where the instance's bound lives (with bounds: read and lowered while a tile runs)
+    unsigned long long* best_obj_at;    // objective mode: likewise the best objective reached (ordered bit pattern)
     double   obj_seen;  // objective mode: an objective some wave has already reached for this instance (-inf: none known)
     double   slo_raw;   // SLO_a * A_max
     // objective mode (Eq. 14)
@@ -1395,6 +1396,14 @@ __device__ __forceinline__ double words_f64(uint32_t lo, uint32_t hi)
     return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
 }
 
+// What the enumeration kernel is instantiated for.
+constexpr int MODE_COST = 0;      // cheapest feasible
+constexpr int MODE_OBJ  = 1;      // largest objective (Eq. 14)
+constexpr int MODE_MIX  = 2;      // cheapest feasible, options with their own accuracies (Eq. 9, 10)
+constexpr int MODE_MIXOBJ = 3;    // largest objective over such options
+constexpr bool is_obj(int mode) { return mode == MODE_OBJ || mode == MODE_MIXOBJ; }
+constexpr bool is_mix(int mode) { return mode == MODE_MIX || mode == MODE_MIXOBJ; }
+
 // Objective mode, 32-bit local keys.  All candidates of one variant of position 0
 // (other digits fixed) share their accuracy, so the one with the best objective is
 // the cheapest feasible one: per variant the same masked minimum as in cost mode,
@@ -1412,8 +1421,83 @@ struct TileBest {
     uint32_t k32; double obj;
     uint32_t visits;    // wave-uniform: entries of position 0 this wave went through in the tile
     uint32_t klim;      // objective mode: local keys above it (fixed in-lane positions included) cannot matter
-    uint32_t bound;     // wave-uniform: the cost bound as the wave knows it when the tile ends
+    uint32_t bound;     // wave-uniform: the cost bound as the wave knows it when the tile ends,
+    double obj_seen;    // and (objective mode) the best objective of the instance it knows of
 };
+
+// With bounds, the cost bound moves while a tile runs.  At the points where a loop calls
+// bound_take_in (before a digit or a run of the outermost in-lane position) the wave takes in what
+// the instance's bound has become - the load issued at the previous such point, so nobody waits
+// for it - and fetches it anew; where it calls bound_publish (after that digit or run), a wave one
+// of whose lanes has found something better than the wave knew of lowers the bound for its own
+// next steps and for every block working on the instance.  A stale value only excludes less;
+// candidates as cheap as the bound stay in.  Cost modes: the bound is the cost of the cheapest
+// candidate found that meets both SLOs.  Objective modes (Eq. 14): A_obj <= 1, so with an
+// objective o reached nothing costlier than (alpha - o)/beta can match it (one unit of slack
+// keeps the test clear of rounding and of equal objectives); single tuples also share o itself.
+struct Moving {
+    uint32_t fetched;                   // the bound, load in flight
+    unsigned long long fetched_obj;     // the best objective, load in flight (objective mode, single tuples)
+    double told;                        // per lane: the tile's best objective when the wave last published
+};
+
+template <int MODE>
+__device__ __forceinline__ Moving bound_start(const Uniforms& V, const TileBest& tb)
+{
+    Moving mv;
+    mv.fetched = V.bound;
+    mv.fetched_obj = ordered_bits(-__builtin_inf());
+    mv.told = tb.obj;
+    return mv;
+}
+
+template <int MODE>
+__device__ __forceinline__ void bound_take_in(Uniforms& V, Moving& mv)
+{
+    const uint32_t seen = (uint32_t)__builtin_amdgcn_readfirstlane((int)mv.fetched);
+    V.bound = seen < V.bound ? seen : V.bound;
+    mv.fetched = __hip_atomic_load(V.bound_at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if constexpr (MODE == MODE_OBJ) {
+        const double oo = from_ordered_bits(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(mv.fetched_obj >> 32)) << 32) |
+                                            (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)mv.fetched_obj));
+        V.obj_seen = oo > V.obj_seen ? oo : V.obj_seen;
+        mv.fetched_obj = __hip_atomic_load(V.best_obj_at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+template <int MODE>
+__device__ __forceinline__ void bound_publish(const LaneState& s, Uniforms& V, const TileBest& tb, Moving& mv)
+{
+    if constexpr (!is_obj(MODE)) {
+        // (the tile's best local key so far -> the total cost of that candidate)
+        const uint32_t c = tb.k32 != 0xFFFFFFFFu ? s.cost_out + (tb.k32 >> V.lb) : 0xFFFFFFFFu;
+        if (__builtin_amdgcn_ballot_w64(c < V.bound) == 0) return;
+        const uint32_t wc = (uint32_t)wave_min((uint64_t)c);
+        V.bound = wc;
+        if ((threadIdx.x & 63u) == 0) atomicMin(V.bound_at, wc);
+    } else {
+        if (__builtin_amdgcn_ballot_w64(tb.obj > mv.told) == 0) return;
+        mv.told = tb.obj;
+        const unsigned long long ob = ~wave_min(~ordered_bits(tb.obj));     // the largest of the lanes' objectives
+        const double o = from_ordered_bits(ob);
+        if constexpr (MODE == MODE_OBJ) {
+            if (o > V.obj_seen) {
+                V.obj_seen = o;
+                if ((threadIdx.x & 63u) == 0) atomicMax(V.best_obj_at, ob);
+            }
+        }
+        if (V.beta > 1e-9 * (V.alpha + 1.0)) {      // else rounding could reach a unit of cost
+            const double lim = (V.alpha - o) / V.beta;
+            if (lim >= 0.0 && lim < 2147483000.0) {
+                const uint32_t wc = (uint32_t)lim + 1u;
+                if (wc < V.bound) {
+                    V.bound = wc;
+                    if ((threadIdx.x & 63u) == 0) atomicMin(V.bound_at, wc);
+                }
+            }
+        }
+    }
+}
 
 // Largest local key that can still matter for a lane whose positions outside the lane loops cost
 // `cost_out` and that already holds a candidate of objective `have` (-inf: none).  0: none can
@@ -1556,14 +1640,6 @@ __device__ __forceinline__ void loop_x32_mixobj(const LaneState& s, const Unifor
     }
     if constexpr (BOUNDS) tb.visits += seen;
 }
-
-// What the enumeration kernel is instantiated for.
-constexpr int MODE_COST = 0;      // cheapest feasible
-constexpr int MODE_OBJ  = 1;      // largest objective (Eq. 14)
-constexpr int MODE_MIX  = 2;      // cheapest feasible, options with their own accuracies (Eq. 9, 10)
-constexpr int MODE_MIXOBJ = 3;    // largest objective over such options
-constexpr bool is_obj(int mode) { return mode == MODE_OBJ || mode == MODE_MIXOBJ; }
-constexpr bool is_mix(int mode) { return mode == MODE_MIX || mode == MODE_MIXOBJ; }
 
 template <bool W32, int MODE, bool BOUNDS>
 __device__ __forceinline__ void loop_x(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
@@ -2020,10 +2096,16 @@ __device__ __forceinline__ void loop_y_masked(const LaneState& s, const Uniforms
 // latency state (what fix_position<2> does to tails and keys) is formed again.  Same
 // operations on the same operands as digit by digit, in another order of the candidates.
 template <int MODE, bool BOUNDS, bool E01>
-__device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniforms& U, uint32_t lo, uint32_t hi,
+__device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniforms& U0, uint32_t lo, uint32_t hi,
                                                uint32_t x_hi, uint64_t full, TileBest& tb)
 {
 #pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
+    // objective mode with bounds: the bound moves while the tile runs, run by run of position 2 (see
+    // Moving; in the cost mode this loop only sees the small tiles that the pair stream leaves it,
+    // where taking the bound in run by run costs more than it excludes)
+    constexpr bool MOVING = BOUNDS && is_obj(MODE);
+    Uniforms V = U0;
+    const Uniforms& U = V;
     const Entry JSV_CONST* ty = U.tab[1];
     const Entry JSV_CONST* tz = U.tab[2];
     const uint32_t nvx = __builtin_amdgcn_readfirstlane(U.nvx);
@@ -2033,10 +2115,12 @@ __device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniform
     for (int v = 0; v < MAX_XVAR; ++v) qe[v] = U.xqe[v];
     const uint32_t endb = x_hi * (uint32_t)sizeof(QuadC);
     const uint32_t KY = U.K[1];
+    Moving mv = bound_start<MODE>(V, tb);
     uint32_t z = lo;
     while (z < hi) {
         const uint32_t zrun_end = U.zrun[z];
         const uint32_t zre = zrun_end < hi ? zrun_end : hi;
+        if constexpr (MOVING) bound_take_in<MODE>(V, mv);
         // accuracy state with position 2 fixed to this variant (fix_position<2>)
         const double Hz = tz[z].acc * s.hin[2];
         const double sacc2 = src2 != 0 ? s.sacc + Hz : s.sacc;
@@ -2083,8 +2167,10 @@ __device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniform
             }
             y = yre;
         }
+        if constexpr (MOVING) bound_publish<MODE>(s, V, tb, mv);
         z = zre;
     }
+    if constexpr (MOVING) { tb.bound = V.bound; tb.obj_seen = V.obj_seen; }
 }
 
 // Three in-lane positions with the pair stream (cost modes, single tuples).  The slots that go
@@ -2252,23 +2338,15 @@ __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniform
 #pragma unroll
     for (int v = 0; v < MAX_XVAR; ++v) qe[v] = U.xqe[v];
     const uint32_t endb = x_hi * (uint32_t)sizeof(QuadC);
-    // Cost mode with bounds: the bound moves while the tile runs.  Before each run of position 2 the
-    // wave takes in what the instance's bound has become (the load issued one run earlier, so nobody
-    // waits for it) and fetches it anew; after the run, a lane that has found a cheaper candidate than
-    // the wave knew of lowers the bound for its own next runs and for every block working on the instance.
-    // A stale value only excludes less; candidates as cheap as the bound stay in.
+    // cost mode with bounds: the bound moves while the tile runs, run by run of position 2 (see Moving)
     constexpr bool MOVING = BOUNDS && MODE == MODE_COST;
     Uniforms V = U;
-    uint32_t fetched = V.bound;
+    Moving mv = bound_start<MODE>(V, tb);
     uint32_t z = lo;
     while (z < hi) {
         const uint32_t zrun_end = U.zrun[z];
         const uint32_t zre = zrun_end < hi ? zrun_end : hi;
-        if constexpr (MOVING) {
-            const uint32_t seen = (uint32_t)__builtin_amdgcn_readfirstlane((int)fetched);
-            V.bound = seen < V.bound ? seen : V.bound;
-            fetched = __hip_atomic_load(U.bound_at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        if constexpr (MOVING) bound_take_in<MODE>(V, mv);
         // accuracy state with position 2 fixed to this variant (fix_position<2>)
         const double Hz = tz[z].acc * s.hin[2];
         const double sacc2 = src2 != 0 ? s.sacc + Hz : s.sacc;
@@ -2286,15 +2364,7 @@ __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniform
         case 1: z_batch_pairs<MODE, 1, BOUNDS, E01>(s, V, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
         default: break;
         }
-        if constexpr (MOVING) {
-            // (the tile's best local key so far -> the total cost of that candidate)
-            const uint32_t c = tb.k32 != 0xFFFFFFFFu ? s.cost_out + (tb.k32 >> U.lb) : 0xFFFFFFFFu;
-            if (__builtin_amdgcn_ballot_w64(c < V.bound) != 0) {
-                const uint32_t wc = (uint32_t)wave_min((uint64_t)c);
-                V.bound = wc;
-                if ((threadIdx.x & 63u) == 0) atomicMin(U.bound_at, wc);
-            }
-        }
+        if constexpr (MOVING) bound_publish<MODE>(s, V, tb, mv);
         z = zre;
     }
     if constexpr (MOVING) tb.bound = V.bound;
@@ -2344,17 +2414,24 @@ __device__ __forceinline__ void loop_z(const LaneState& s, const Uniforms& U, ui
         }
     }
     const Entry JSV_CONST* tz = U.tab[2];
+    // with bounds and 32-bit keys: the bound moves while the tile runs, digit by digit of position 2 (see Moving)
+    constexpr bool MOVING = BOUNDS && W32;
+    Uniforms V = U;
+    Moving mv = bound_start<MODE>(V, tb);
     for (uint32_t d = lo; d < hi; ++d) {
-        const LaneState s2 = fix_position<2>(s, U, tz[d].lat, tz[d].acc, W32 ? 0 : tz[d].key,
+        if constexpr (MOVING) bound_take_in<MODE>(V, mv);
+        const LaneState s2 = fix_position<2>(s, V, tz[d].lat, tz[d].acc, W32 ? 0 : tz[d].key,
                                              W32 ? U.k32[2][d] : 0u);
         if constexpr (BOUNDS) {
             // with this digit fixed, is any lane left that meets the latency SLO so far and stays
             // within the cost bound with the cheapest entries of the two positions below?
             const uint64_t fixed = W32 ? (uint64_t)(s2.cost_out + (s2.k32 >> U.lb)) : (s2.key >> U.idx_bits);
-            if (__builtin_amdgcn_ballot_w64((s2.smax <= U.sloq) & (fixed + U.min_xy_cost <= U.bound)) == 0) continue;
+            if (__builtin_amdgcn_ballot_w64((s2.smax <= U.sloq) & (fixed + U.min_xy_cost <= V.bound)) == 0) continue;
         }
-        loop_y<W32, MODE, BOUNDS>(s2, U, 0, U.K[1], x_hi, full, best, tb);
+        loop_y<W32, MODE, BOUNDS>(s2, V, 0, U.K[1], x_hi, full, best, tb);
+        if constexpr (MOVING) bound_publish<MODE>(s, V, tb, mv);
     }
+    if constexpr (MOVING) { tb.bound = V.bound; tb.obj_seen = V.obj_seen; }
 }
 
 // One tile: 256 lanes, each a different combination of the positions >= NIN
@@ -2365,7 +2442,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
                                          const Entry JSV_CONST* tab, const uint32_t JSV_CONST* k32,
                                          const Quad JSV_CONST* quads, const QuadC JSV_CONST* pairs, const Entry* s_tab, uint32_t k_max, bool mix,
                                          uint64_t group, uint32_t chunk_id, uint32_t& bound, uint32_t fresh, uint32_t* bound_at,
-                                         double obj_seen, Best& best, uint64_t& visited)
+                                         unsigned long long* best_obj_at, double& obj_seen, Best& best, uint64_t& visited)
 {
 #pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
     const uint32_t T = g->T;
@@ -2446,6 +2523,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     }
     U.bound = bound;
     U.bound_at = bound_at;
+    U.best_obj_at = best_obj_at;
     U.obj_seen = MODE == MODE_OBJ ? obj_seen : -__builtin_inf();
     U.slo_raw = in->slo_raw;
     U.idx_bits = in->idx_bits; U.lb = in->lb; U.capacity = g->capacity;
@@ -2480,7 +2558,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     // no key - a candidate must reach that objective to be noted, and ties are settled on the full
     // keys after the tile)
     tb.k32 = 0xFFFFFFFFu; tb.obj = (is_obj(MODE) && W32) ? best.obj : -__builtin_inf(); tb.visits = 0;
-    tb.klim = 0xFFFFFFFEu; tb.bound = U.bound;
+    tb.klim = 0xFFFFFFFEu; tb.bound = U.bound; tb.obj_seen = U.obj_seen;
     if constexpr (is_obj(MODE) && W32) tb.klim = key_limit(U, st.cost_out, best.obj, U.alpha);
     const uint64_t full = __builtin_amdgcn_read_exec();     // the loops below run convergent
     if constexpr (NIN == 3) loop_z<W32, MODE, BOUNDS>(st, U, lo, hi, x_all, full, best, tb);
@@ -2488,6 +2566,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     else loop_x<W32, MODE, BOUNDS>(st, U, lo, hi, full, best, tb);
     if (BOUNDS || U.mix) visited += tb.visits;
     bound = tb.bound;
+    if constexpr (MODE == MODE_OBJ) obj_seen = tb.obj_seen;
 
     if constexpr (W32) {
         // the lane's 32-bit winner of this tile -> its full (cost, index) key; only where some lane's
@@ -2649,15 +2728,15 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         const double obj_before = best.obj;
         if (in->use32) {
             switch (in->n_in) {
-            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
-            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
-            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
+            case 3: run_tile<3, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, pl.best_obj + cur, obj_seen, best, visited); break;
+            case 2: run_tile<2, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, pl.best_obj + cur, obj_seen, best, visited); break;
+            default: run_tile<1, true, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, pl.best_obj + cur, obj_seen, best, visited); break;
             }
         } else {
             switch (in->n_in) {
-            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
-            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
-            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, obj_seen, best, visited); break;
+            case 3: run_tile<3, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, pl.best_obj + cur, obj_seen, best, visited); break;
+            case 2: run_tile<2, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, pl.best_obj + cur, obj_seen, best, visited); break;
+            default: run_tile<1, false, MODE, BOUNDS>(g, in, tab, k32, quads, pairs, s_tab, pl.k_max, pl.mix != 0, group, chunk_id, bound, fresh, pl.bound + cur, pl.best_obj + cur, obj_seen, best, visited); break;
             }
         }
         if constexpr (SHARE) {
