@@ -2186,11 +2186,14 @@ __device__ __forceinline__ void loop_zy_masked(const LaneState& s, const Uniform
 // slot count is a template parameter so that the minima keep their registers over the loops).
 // sacc2, hin1, hin0z: the accuracy state with position 2 fixed to the run's variant.
 template <int MODE, int G, bool BOUNDS, bool E01, bool SAME_ROOM = false>
-__device__ __forceinline__ void z_batch_pairs(const LaneState& s, const Uniforms& U, uint32_t zb, uint32_t nvx, uint32_t src2,
+__device__ __forceinline__ void z_batch_pairs(const LaneState& s, Uniforms& U, Moving& mv, uint32_t zb, uint32_t nvx, uint32_t src2,
                                               double sacc2, double hin1, double hin0z, const uint32_t (&qe)[MAX_XVAR],
                                               uint32_t endb, uint32_t x_hi, uint64_t full, TileBest& tb)
 {
 #pragma clang fp contract(off)      // fp64 operations exactly as written (order: see jsv_device.h)
+    // cost mode with bounds: the bound moves while the tile runs, from one run of position 1 that is
+    // gone through to the next (see Moving)
+    constexpr bool MOVING = BOUNDS && MODE == MODE_COST;
     const Entry JSV_CONST* ty = U.tab[1];
     const Entry JSV_CONST* tz = U.tab[2];
     const uint32_t KY = U.K[1];
@@ -2240,6 +2243,7 @@ __device__ __forceinline__ void z_batch_pairs(const LaneState& s, const Uniforms
             }
             if (some == 0) { y = yre; continue; }
         }
+        if constexpr (MOVING) bound_take_in<MODE>(U, mv);
         // position 1 fixed to this run's accuracy (fix_position<1>), then Eq. 13 per variant of position 0
         const double H = ty[y].acc * hin1;
         const double sacc = E01 ? sacc2 : sacc2 + H;
@@ -2315,6 +2319,13 @@ __device__ __forceinline__ void z_batch_pairs(const LaneState& s, const Uniforms
                 }
             }
         }
+        if constexpr (MOVING) {
+            // the cheapest candidate this lane has met in the tile, the slots' minima so far included
+            TileBest now = tb;
+#pragma unroll
+            for (int g = 0; g < G; ++g) now.k32 = umin(now.k32, __builtin_elementwise_add_sat(m[g], k32z[g]));
+            bound_publish<MODE>(s, U, now, mv);
+        }
         y = yre;
     }
     if constexpr (MODE != MODE_OBJ) {
@@ -2338,7 +2349,7 @@ __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniform
 #pragma unroll
     for (int v = 0; v < MAX_XVAR; ++v) qe[v] = U.xqe[v];
     const uint32_t endb = x_hi * (uint32_t)sizeof(QuadC);
-    // cost mode with bounds: the bound moves while the tile runs, run by run of position 2 (see Moving)
+    // cost mode with bounds: the bound moves while the tile runs (see z_batch_pairs)
     constexpr bool MOVING = BOUNDS && MODE == MODE_COST;
     Uniforms V = U;
     Moving mv = bound_start<MODE>(V, tb);
@@ -2346,7 +2357,6 @@ __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniform
     while (z < hi) {
         const uint32_t zrun_end = U.zrun[z];
         const uint32_t zre = zrun_end < hi ? zrun_end : hi;
-        if constexpr (MOVING) bound_take_in<MODE>(V, mv);
         // accuracy state with position 2 fixed to this variant (fix_position<2>)
         const double Hz = tz[z].acc * s.hin[2];
         const double sacc2 = src2 != 0 ? s.sacc + Hz : s.sacc;
@@ -2355,16 +2365,15 @@ __device__ __forceinline__ void loop_zyx_pairs(const LaneState& s, const Uniform
         uint32_t zb = z;
         // full batches are compiled a second time for graphs in which position 2 does not feed position 1
         if (E01 && U.m12 == 0)
-            for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01, true>(s, V, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
+            for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01, true>(s, V, mv, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
         else
-            for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01>(s, V, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
+            for (; zb + 4 <= zre; zb += 4) z_batch_pairs<MODE, 4, BOUNDS, E01>(s, V, mv, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb);
         switch (zre - zb) {
-        case 3: z_batch_pairs<MODE, 3, BOUNDS, E01>(s, V, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
-        case 2: z_batch_pairs<MODE, 2, BOUNDS, E01>(s, V, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
-        case 1: z_batch_pairs<MODE, 1, BOUNDS, E01>(s, V, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        case 3: z_batch_pairs<MODE, 3, BOUNDS, E01>(s, V, mv, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        case 2: z_batch_pairs<MODE, 2, BOUNDS, E01>(s, V, mv, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
+        case 1: z_batch_pairs<MODE, 1, BOUNDS, E01>(s, V, mv, zb, nvx, src2, sacc2, hin1, hin0z, qe, endb, x_hi, full, tb); break;
         default: break;
         }
-        if constexpr (MOVING) bound_publish<MODE>(s, V, tb, mv);
         z = zre;
     }
     if constexpr (MOVING) tb.bound = V.bound;
