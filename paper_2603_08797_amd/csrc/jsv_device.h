@@ -235,6 +235,14 @@ struct Instance {
     // floor(2^32 / K[t]) per task id (K = 1: 2^32 - 1), so that the lanes split their combination
     // into digits by a multiplication and one correction instead of a division (plan kernel)
     uint32_t kmagic[MAXT];
+    // the same by position instead of task id, with the row of the position's task in the entry
+    // table (task id * k_max): the tile set-up reads them with a few wide scalar loads instead of a
+    // chain of dependent ones through the task ids (plan kernel)
+    uint32_t kpos[MAXT];
+    uint32_t mpos[MAXT];
+    uint32_t rowpos[MAXT];
+    uint32_t sloq;            // floor(slo_l / q): what Eq. 3 leaves for the critical path (plan kernel)
+    uint32_t pad_sloq;
 };
 
 // Result record as written by the finalize kernel; same layout as jsv_result.

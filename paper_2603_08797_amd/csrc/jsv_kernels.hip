@@ -796,6 +796,13 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
     if (tid == 0) s_minxlat = 0xFFFFFFFFu;
     __syncthreads();
     if (tid == 0) { uint32_t run = 0; for (uint32_t t = 0; t < T; ++t) { s_off[t] = run; run += s_K[t]; } s_off[T] = run; }
+    if (tid >= 64 && tid < 64 + MAXT) {
+        const uint32_t p = tid - 64, t = s_task_at[p];
+        in->kpos[p] = p < T ? s_K[t] : 0;
+        in->mpos[p] = magic_of(p < T ? s_K[t] : 0);
+        in->rowpos[p] = p < T ? t * pl.k_max : 0;
+    }
+    if (tid == 96) { in->sloq = in->slo_l / g->q; in->pad_sloq = 0; }
     __syncthreads();
     const uint32_t tx = s_task_at[0], PB = s_PB, KX = s_K[tx], n_all = s_off[T];
     const Entry* ent = pl.entries + (size_t)i * pl.t_max * pl.k_max;
@@ -2465,7 +2472,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
         uint32_t o32 = (uint32_t)o;
 #pragma unroll
         for (int p = NIN; p < MAXT; ++p)
-            if (p < (int)T) { const uint32_t t = g->task_at[p]; o32 = div_by_magic(o32, in->K[t], in->kmagic[t], &dig[p]); }
+            if (p < (int)T) o32 = div_by_magic(o32, in->kpos[p], in->mpos[p], &dig[p]);
     } else {
 #pragma unroll
         for (int p = NIN; p < MAXT; ++p)
@@ -2482,7 +2489,7 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
 #pragma unroll
     for (int p = MAXT - 1; p >= NIN; --p) {
         if (p < (int)T) {
-            const Entry* e = s_tab + (uint32_t)g->task_at[p] * k_max + dig[p];
+            const Entry* e = s_tab + in->rowpos[p] + dig[p];
             const uint32_t lat = e->lat;
             const double acc = e->acc;
             st.key += e->key;
@@ -2511,16 +2518,16 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
     Uniforms U;
 #pragma unroll
     for (int p = 0; p < 3; ++p) {
-        const uint32_t t = g->task_at[p < NIN ? p : 0];
-        U.tab[p] = tab + t * k_max;
-        U.k32[p] = k32 + t * k_max;
-        U.K[p] = in->K[t];
+        const uint32_t row = in->rowpos[p < NIN ? p : 0];
+        U.tab[p] = tab + row;
+        U.k32[p] = k32 + row;
+        U.K[p] = in->kpos[p < NIN ? p : 0];
         U.src[p] = (src_mask >> p) & 1u;
     }
     U.quads = quads;
     U.m01 = 0u - ((g->succ[0] >> 1) & 1u); U.m02 = 0u - ((g->succ[0] >> 2) & 1u); U.m12 = 0u - ((g->succ[1] >> 2) & 1u);
     U.w01 = g->w[0][1]; U.w02 = g->w[0][2]; U.w12 = g->w[1][2];
-    U.sloq = in->slo_l / g->q;
+    U.sloq = in->sloq;
     U.min_x_lat = in->min_x_lat;
     U.min_x_cost = in->min_x_cost;
     U.min_xy_cost = in->min_xy_cost;
@@ -2591,10 +2598,9 @@ __device__ __forceinline__ void run_tile(const Graph JSV_CONST* g, const Instanc
 #pragma unroll
         for (int a = 0; a < NIN; ++a) {
             const uint32_t p = in->ord[a];
-            const uint32_t t = g->task_at[p];
             uint32_t d;
-            r = div_by_magic(r, in->K[t], in->kmagic[t], &d);
-            k += s_tab[t * k_max + d].key;
+            r = div_by_magic(r, in->kpos[p], in->mpos[p], &d);
+            k += s_tab[in->rowpos[p] + d].key;
         }
         if constexpr (is_obj(MODE)) {
             if (hit && better(tb.obj, k, best.obj, best.key)) { best.obj = tb.obj; best.key = k; }
