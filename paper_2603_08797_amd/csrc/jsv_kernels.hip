@@ -619,6 +619,7 @@ __global__ void __launch_bounds__(MIX_THREADS) mix_kernel(Plan pl)
 //    block (9.1 ms against 16.6 ms for the sweep).
 // Giving every block one long contiguous run was tried too and is slower still: seven blocks of
 // a compute unit then stream seven instances' tables through one scalar cache.
+constexpr uint32_t SEED_MIN_TILES_PER_BLOCK = 8;      // the plan kernel seeds the cost bound of instances from here on
 constexpr uint32_t STATIC_ONLY_TILES_PER_BLOCK = 8;   // up to here: no counter at all
 constexpr uint32_t BOUNDED_COUNTER_TILES_PER_BLOCK = 64;   // with bounds: below this no counter either (one level of a
                                                       // large search: 0.51-0.72 ms by index, 0.59-0.85 ms with tickets)
@@ -762,6 +763,10 @@ __device__ void scan_tiles(const Plan& pl, uint64_t* s_sum)
 // of the innermost position, reset of the partials.  The last block to finish scans
 // the tile counts (plan_done is zeroed by the prune kernel, which runs before).
 //
+struct Score { uint32_t latency; uint32_t cost; double accuracy; uint8_t mask; };     // mask: bit 0 Eq. 3, 1 Eq. 13, 2 Eq. 8
+__device__ Score score_digits(const Graph* g, const Instance* in, const Entry* entries, uint32_t k_max,
+                              const uint32_t* dig);
+
 // Written for latency (one small instance is often all there is): every pass over the
 // entries covers all tasks at once (one round trip to memory instead of one per task), the
 // quads of the innermost stream are laid out by a parallel scan, and what only one thread
@@ -1103,6 +1108,71 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
             if (tid < 4) { XEnt pad; pad.lat = 0xFFFFFFFFu; pad.k32 = 0xFFFFFFFFu; pr[KY * per + tid] = pad; }
             if (tid == 0) in->pair_nq = nq;
         }
+    }
+    // A first cost bound for the search with bounds (cost modes): steepest descent over single-task
+    // swaps, from the most accurate choice of every task (fastest, then cheapest among equals).
+    // Every step takes the swap that saves most among those that keep Eq. 3, 8 and 13, each scored
+    // as the finalize kernel scores the winner; what it ends on is a candidate of the searched
+    // space that meets all three, so its cost is a bound the optimum cannot exceed (candidates as
+    // cheap as the bound stay in).  The enumeration otherwise starts every instance against
+    // S_avail and finds the cheap candidates only where its loops happen to reach them.  The
+    // descent takes some tens of microseconds (a few dozen rounds of scoring from global memory),
+    // so it runs for instances with enough tiles to win that back.
+    if (pl.bounds && !pl.objective && in->tiles >= SEED_MIN_TILES_PER_BLOCK * pl.grid) {
+        __shared__ uint32_t s_dig[MAXT], s_seed_cost, s_seed_ok;
+        __shared__ unsigned long long s_swap;
+        const Entry* ent = pl.entries + (size_t)i * pl.t_max * pl.k_max;
+        __syncthreads();
+        if (tid < T) {
+            const Entry* row = ent + (size_t)tid * pl.k_max;
+            uint32_t bd = 0;
+            for (uint32_t d = 1; d < s_K[tid]; ++d) {
+                const Entry& e = row[d];
+                const Entry& b = row[bd];
+                if (e.acc > b.acc || (e.acc == b.acc && (e.lat < b.lat || (e.lat == b.lat && e.cost < b.cost)))) bd = d;
+            }
+            s_dig[tid] = bd;
+        }
+        __syncthreads();
+        uint32_t dig[MAXT];
+        for (uint32_t t = 0; t < MAXT; ++t) dig[t] = t < T ? s_dig[t] : 0;
+        if (tid == 0) {
+            const Score sc = score_digits(g, in, ent, pl.k_max, dig);
+            s_seed_ok = sc.mask == 7 ? 1u : 0u;
+            s_seed_cost = sc.cost;
+        }
+        __syncthreads();
+        const bool seeded = s_seed_ok != 0;
+        for (uint32_t it = 0; seeded && it < 64; ++it) {
+            if (tid == 0) s_swap = 0;
+            __syncthreads();
+            unsigned long long mine = 0;
+            for (uint32_t f = tid; f < n_all; f += blockDim.x) {
+                uint32_t t = 0;
+                while (t + 1 < T && s_off[t + 1] <= f) ++t;
+                const uint32_t d = f - s_off[t], old = dig[t];
+                const uint32_t c_old = ent[(size_t)t * pl.k_max + old].cost, c_new = ent[(size_t)t * pl.k_max + d].cost;
+                if (c_new >= c_old) continue;
+                dig[t] = d;
+                const Score sc = score_digits(g, in, ent, pl.k_max, dig);
+                dig[t] = old;
+                if (sc.mask == 7) {
+                    const unsigned long long k = ((unsigned long long)(c_old - c_new) << 32) | (0xFFFFFFFFu - f);
+                    mine = k > mine ? k : mine;
+                }
+            }
+            if (mine != 0) atomicMax(&s_swap, mine);
+            __syncthreads();
+            const unsigned long long won = s_swap;
+            if (won == 0) break;
+            const uint32_t f = 0xFFFFFFFFu - (uint32_t)won;
+            uint32_t t = 0;
+            while (t + 1 < T && s_off[t + 1] <= f) ++t;
+            dig[t] = f - s_off[t];
+            if (tid == 0) s_seed_cost -= (uint32_t)(won >> 32);
+            __syncthreads();
+        }
+        if (tid == 0 && seeded) atomicMin(pl.bound + i, s_seed_cost);
     }
     for (uint32_t b = tid; b < pl.grid; b += blockDim.x) {
         pl.partial[(size_t)i * pl.grid + b] = NO_KEY;
@@ -2804,9 +2874,7 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         if ((threadIdx.x & 63u) == 0 && visited != 0) atomicAdd(&pl.summary->visited, (unsigned long long)visited);
 }
 
-// ---- scoring of one assignment (finalize and eval) -----------------------------------------
-struct Score { uint32_t latency; uint32_t cost; double accuracy; uint8_t mask; };
-
+// ---- scoring of one assignment (finalize, eval and the plan kernel's first bound) -----------
 // dig[t]: digit of task id t in its surviving list.
 __device__ Score score_digits(const Graph* g, const Instance* in, const Entry* entries, uint32_t k_max,
                               const uint32_t* dig)
