@@ -67,6 +67,26 @@ def test_xr8_at_the_benchmark_size(ctx):
     assert total == 7 * 20 ** 8 and on < off // 4
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_first_bound_from_the_plan_kernel(ctx, seed):
+    """An instance with at least eight tiles per block of the grid starts from the cost of a
+    candidate that the plan kernel reaches by descent, not from S_avail: the other seeds of xr8 at
+    the benchmark size, and thinner lists with one block per compute unit (whose tiles still
+    outnumber that grid eight to one), plain enumeration against the bounded search."""
+    w = workloads.xr8(seed=seed)
+    pb, se = w.problems[0], w.searches[0]
+    levels = se.demand_mrps[[0, 9, 18, 27, 36]]
+    ctx.load(pb)
+    on, off, total = both(ctx, lambda: ctx.search(levels, se.slo_latency_us, se.slo_accuracy, se.prune_cap))
+    assert total == 5 * 20 ** 8 and on < off // 4
+    ctx.set_geometry(1, 0)
+    try:
+        on, off, total = both(ctx, lambda: ctx.search(levels, se.slo_latency_us, se.slo_accuracy, 14))
+        assert on < off
+    finally:
+        ctx.set_geometry(0, 0)
+
+
 @pytest.mark.parametrize("seed", range(40))
 def test_tiny_random(ctx, seed):
     pb, se = workloads.tiny_random(9000 + seed)
