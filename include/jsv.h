@@ -177,7 +177,9 @@ JSV_API int jsv_set_search_space(jsv_ctx* ctx, int accuracy_scaling, int spatial
  * the innermost tasks exceeds S_avail (Eq. 8) or the cost of a candidate already found that
  * meets both SLOs (objective mode: the cost beyond which alpha - beta * cost falls below an
  * objective already reached); the kernel skips the tests of such candidates where a whole
- * 64-lane wave of groups is excluded.  The result is the same with bounds on or off (an
+ * 64-lane wave of groups is excluded.  In the cost modes a large level starts from the cost of
+ * a candidate that meets Eq. 3, 8 and 13, found by a descent over single-task swaps before
+ * the enumeration (the optimum cannot cost more; candidates as cheap stay in).  The result is the same with bounds on or off (an
  * excluded candidate fails a constraint or is worse than one that was found); off makes the kernel issue the tests
  * of every candidate, which is what throughput measurements of the plain enumeration use.
  * jsv_summary.candidates_visited tells how many candidates had their tests issued.  A search
