@@ -362,6 +362,25 @@ def main():
                 single_level[name] = (time.perf_counter() - t3) / 10 * 1e3
                 single_level["same_answer"] = single_level.get("same_answer", True) and \
                     (r1[0].feasible, r1[0].index, r1[0].cost) == (res[l1].feasible, res[l1].index, res[l1].cost)
+            # the same for the feasible level with the smallest demand, whose optimum lies far below
+            # S_avail (where the search with bounds starts from the plan kernel's first bound)
+            l0 = min(feas, key=lambda l: int(se.demand_mrps[l]))
+            if l0 != l1:
+                low = {"level": l0, "demand_mrps": int(se.demand_mrps[l0])}
+                one = se.demand_mrps[l0:l0 + 1]
+                for name, on in (("with_bounds_ms", True), ("plain_ms", False)):
+                    j.set_bounds(on)
+                    for _ in range(3):
+                        j.search(one, se.slo_latency_us, se.slo_accuracy, se.prune_cap)
+                    torch.cuda.synchronize()
+                    t3 = time.perf_counter()
+                    for _ in range(10):
+                        r1, _ = j.search(one, se.slo_latency_us, se.slo_accuracy, se.prune_cap)
+                    torch.cuda.synchronize()
+                    low[name] = (time.perf_counter() - t3) / 10 * 1e3
+                    low["same_answer"] = low.get("same_answer", True) and \
+                        (r1[0].feasible, r1[0].index, r1[0].cost) == (res[l0].feasible, res[l0].index, res[l0].cost)
+                single_level["lowest_level"] = low
             j.set_bounds(args.bounds)
 
     other_seeds = None

@@ -1138,7 +1138,7 @@ __global__ void __launch_bounds__(256) plan_kernel(Plan pl)
         for (uint32_t t = 0; t < MAXT; ++t) dig[t] = t < T ? s_dig[t] : 0;
         if (tid == 0) {
             const Score sc = score_digits(g, in, ent, pl.k_max, dig);
-            s_seed_ok = sc.mask == 7 ? 1u : 0u;
+            s_seed_ok = (sc.mask == 7 && sc.cost < 0x7FFFFFFFu) ? 1u : 0u;     // (the scorer clamps costs there)
             s_seed_cost = sc.cost;
         }
         __syncthreads();
