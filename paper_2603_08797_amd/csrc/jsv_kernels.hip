@@ -2736,7 +2736,7 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
     const uint32_t rounds = as_uniform((const SummaryRec*)pl.summary)->own_rounds;
     const uint32_t batch = as_uniform((const SummaryRec*)pl.summary)->batch_tiles;
     const uint64_t* begins = pl.tile_begin;
-    // rounds of own runs first (round r: the run that starts at (r * blocks + block) * own),
+    // rounds of own runs first (round r: the run that starts at (r * blocks + block) * own; see below),
     // then batches from the counter
     uint32_t round = 0;
     uint64_t tile = (uint64_t)blockIdx.x * own;
@@ -2745,7 +2745,11 @@ __global__ void __launch_bounds__(256) enumerate_kernel(Plan pl)
         if (tile >= tile_end) {
             ++round;
             if (round < rounds) {
-                tile = ((uint64_t)round * gridDim.x + blockIdx.x) * own;
+                // (where all tiles go out by index, shifted by one block per round: with an even grid and
+                // two chunks per group a block would otherwise meet the same chunk every round)
+                uint32_t slot = blockIdx.x + (batch == 0 ? round : 0u);
+                if (slot >= gridDim.x) slot %= gridDim.x;
+                tile = ((uint64_t)round * gridDim.x + slot) * own;
                 tile_end = tile + own;
             } else {
                 if (batch == 0) break;                    // everything was shared out by index
