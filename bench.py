@@ -43,15 +43,15 @@ UNSHARED_OPS_PER_CANDIDATE = 11
 # against a 1 GiB copy (profiles/enumerate_kernel_xr8_hbm_traffic.md); known only for the
 # default workload in cost mode.
 # key: workload, seed, objective mode, mixture mode, bounds
-MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (17931 + 10805) * 1024,
-                          ("xr8", 0, False, False, True): (6677 + 1610) * 1024}
+MEASURED_TRAFFIC_BYTES = {("xr8", 0, False, False, False): (18059 + 8614) * 1024,
+                          ("xr8", 0, False, False, True): (6631 + 1603) * 1024}
 # SQ counters of the same launch (profiles/enumerate_kernel_xr8_counters.md): vector instructions
 # issued per candidate (wave instructions x 64 lanes / candidates) and VALU issue utilisation
 # (wave instructions x 4 cycles / (SIMDs x elapsed cycles)); same key as above
 MEASURED_COUNTERS = {("xr8", 0, False, False, False): {"valu_lane_ops_per_candidate": 2.20, "issue_utilisation": 0.99,
                                                        "scalar_instructions_per_cu_cycle": 0.38,
                                                        "source": "profiles/enumerate_kernel_xr8_counters.md"},
-                     ("xr8", 0, False, False, True): {"valu_lane_ops_per_scored_candidate": 35.7, "issue_utilisation": 0.71,
+                     ("xr8", 0, False, False, True): {"valu_lane_ops_per_scored_candidate": 35.9, "issue_utilisation": 0.71,
                                                       "source": "profiles/enumerate_kernel_xr8_counters.md"},
                      ("xr8", 0, True, False, False): {"valu_lane_ops_per_candidate": 2.74, "issue_utilisation": 0.98,
                                                       "source": "profiles/enumerate_kernel_xr8_counters.md"}}
