@@ -116,3 +116,21 @@ def test_mixtures(ctx, seed):
         both(ctx, lambda: ctx.search(se.demand_mrps, se.slo_latency_us, se.slo_accuracy, 9), mixtures=True)
     finally:
         ctx.set_mixtures(False)
+
+
+def test_first_bound_over_mixtures(ctx):
+    """The plan kernel's first bound with two tuples per task: xr8 at cap 14 with one block per
+    compute unit (the instance's tiles outnumber that grid eight to one), a few levels, bounds on
+    and off."""
+    w = workloads.xr8()
+    pb, se = w.problems[0], w.searches[0]
+    levels = se.demand_mrps[[0, 12, 24, 31]]
+    ctx.load(pb)
+    ctx.set_mixtures(True)
+    ctx.set_geometry(1, 0)
+    try:
+        on, off, total = both(ctx, lambda: ctx.search(levels, se.slo_latency_us, se.slo_accuracy, 14), mixtures=True)
+        assert on < off
+    finally:
+        ctx.set_geometry(0, 0)
+        ctx.set_mixtures(False)
